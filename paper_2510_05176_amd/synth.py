@@ -1,0 +1,107 @@
+"""Seeded synthetic K/V/query generators shaped like the paper's workloads.
+
+This module only draws random inputs; it contains none of the method's
+arithmetic and is the one module both the tests of the GPU library and the
+CPU oracle's tests read their inputs from.
+
+Value structure (what the paper reports about real caches, Sec. 2.2):
+  * K: a few stable high-magnitude "outlier" channels plus a per-channel
+    offset that is a property of the head, not of the prompt (Insight 1), and
+    vectors that gather around a modest number of centres which drift slowly
+    along the sequence (Insight 2);
+  * V: no outliers and no wide dynamic range, but clustered (Insight 3).
+
+Recipe, per (layer, KV head), all draws from numpy PCG64 in this order:
+  head stream  [seed, layer, head, 0]   : K centres N(0,1)[n_c,d]; K channel
+        offsets N(0, offset_std^2)[d]; outlier channel ids (choice without
+        replacement); V centres N(0,1)[n_c,d]
+  token stream [seed, layer, head, 1+b] : (optional drift steps) ; cluster ids
+        uniform[T]; K noise N(0,1)[T,d]; V cluster ids uniform[T]; V noise
+  K = (centre[u] + sigma_k*noise + offset), outlier channels * outlier_scale
+  V =  centre_v[u'] + sigma_v*noise
+then rounded to fp16 (round to nearest even).  Centres, offsets and outlier
+ids are shared by all batch elements of a head; tokens are not.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+
+import numpy as np
+
+
+@dataclass(frozen=True)
+class KVSpec:
+    n_layers: int = 1
+    batch: int = 1
+    n_kv_heads: int = 1
+    n_q_heads: int = 1
+    T: int = 1024
+    d: int = 128
+    n_clusters: int = 16
+    sigma_k: float = 0.3
+    sigma_v: float = 0.5
+    n_outlier: int = 4
+    outlier_scale: float = 8.0
+    offset_std: float = 2.0
+    drift_sigma: float = 0.0     # per-chunk random walk of the K/V centres
+    drift_chunk: int = 128
+
+
+def head_params(seed: int, layer: int, head: int, spec: KVSpec):
+    rng = np.random.Generator(np.random.PCG64([seed, layer, head, 0]))
+    ck = rng.standard_normal((spec.n_clusters, spec.d))
+    off = rng.standard_normal(spec.d) * spec.offset_std
+    out_idx = rng.choice(spec.d, size=spec.n_outlier, replace=False)
+    cv = rng.standard_normal((spec.n_clusters, spec.d))
+    return ck, off, out_idx, cv
+
+
+def make_stream(seed: int, layer: int, head: int, b: int, spec: KVSpec, T: int | None = None):
+    """One (layer, head, batch element) stream: K, V as float16 [T, d]."""
+    T = spec.T if T is None else T
+    ck, off, out_idx, cv = head_params(seed, layer, head, spec)
+    rng = np.random.Generator(np.random.PCG64([seed, layer, head, 1 + b]))
+    if spec.drift_sigma > 0:
+        nchunk = -(-T // spec.drift_chunk)
+        wk = np.cumsum(rng.standard_normal((nchunk, spec.n_clusters, spec.d)) * spec.drift_sigma, axis=0)
+        wv = np.cumsum(rng.standard_normal((nchunk, spec.n_clusters, spec.d)) * spec.drift_sigma, axis=0)
+    u = rng.integers(0, spec.n_clusters, size=T)
+    nk = rng.standard_normal((T, spec.d))
+    uv = rng.integers(0, spec.n_clusters, size=T)
+    nv = rng.standard_normal((T, spec.d))
+    k = ck[u] + spec.sigma_k * nk + off[None, :]
+    v = cv[uv] + spec.sigma_v * nv
+    if spec.drift_sigma > 0:
+        chunk = np.arange(T) // spec.drift_chunk
+        k = k + wk[chunk, u]
+        v = v + wv[chunk, uv]
+    k[:, out_idx] *= spec.outlier_scale
+    return k.astype(np.float16), v.astype(np.float16)
+
+
+def make_kv(seed: int, spec: KVSpec, T: int | None = None):
+    """K, V as float16 [n_layers*batch, n_kv_heads, T, d]; sequence index = layer*batch + b."""
+    T = spec.T if T is None else T
+    n_seq = spec.n_layers * spec.batch
+    K = np.empty((n_seq, spec.n_kv_heads, T, spec.d), np.float16)
+    V = np.empty_like(K)
+    for layer in range(spec.n_layers):
+        for b in range(spec.batch):
+            for h in range(spec.n_kv_heads):
+                K[layer * spec.batch + b, h], V[layer * spec.batch + b, h] = make_stream(seed, layer, h, b, spec, T)
+    return K, V
+
+
+def make_queries(seed: int, n_seq: int, n_q_heads: int, d: int):
+    rng = np.random.Generator(np.random.PCG64([seed, 977]))
+    return rng.standard_normal((n_seq, n_q_heads, d)).astype(np.float16)
+
+
+# The five workload shapes of the benchmark contract (config 1 = smoke).
+SPECS = {
+    "cfg1": KVSpec(1, 1, 1, 1, 1024, 128, 16, 0.3, 0.5, 4, 8.0),
+    "cfg2": KVSpec(1, 1, 8, 32, 8192, 128, 32, 0.3, 0.5, 4, 8.0),
+    "cfg3": KVSpec(32, 16, 8, 32, 32768, 128, 32, 0.3, 0.5, 4, 8.0),
+    "cfg4": KVSpec(1, 64, 8, 32, 8192, 128, 32, 0.3, 0.5, 4, 8.0, drift_sigma=0.05, drift_chunk=128),
+    "cfg5": KVSpec(1, 1, 4, 28, 131072, 128, 256, 0.3, 0.5, 8, 10.0),
+}

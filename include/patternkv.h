@@ -1,0 +1,228 @@
+/*
+ * patternkv.h -- C ABI of the PatternKV hot path for AMD MI355X (gfx950).
+ *
+ * PatternKV (arXiv 2510.05176) mines a few pattern vectors per attention head,
+ * aligns every K/V vector to its nearest pattern and quantizes only the
+ * residual (Sec. 3).  This library is the data-parallel part of that method:
+ *
+ *   pk_mine_patterns      Sec. 3.1 "Prefilling Stage", Eq. 4  (K-means / Lloyd)
+ *   pk_quantize_append    Sec. 3.2 Eq. 6 (pattern selection, residual) followed
+ *                         by Sec. 2.1 Eq. 1 (asymmetric n-bit quantization), with
+ *                         K quantized per channel and V per token (Sec. 4.1)
+ *   pk_decode_attention   Sec. 3.4 "Decode-stage KV reconstruction": attention
+ *                         computed directly on the packed cache
+ *   pk_dequantize         the reconstruction rule below Eq. 6 (debug / parity)
+ *
+ * Conventions shared by every call
+ *   - All tensor pointers are DEVICE pointers unless marked "host".  Structs
+ *     (pk_config, pk_cache, pk_state, pk_layout) are HOST memory.
+ *   - Tensors are dense, row-major, last index fastest; fp16 = IEEE binary16.
+ *   - The caller owns every byte, including the workspace.  The library never
+ *     allocates or frees device memory, keeps no global state and retains no
+ *     pointer after a call returns.
+ *   - Calls enqueue work on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream) and return without synchronising.  pk_state is updated on
+ *     the host at enqueue time.
+ *   - Every argument, shape, alignment (16 bytes for all device pointers),
+ *     capacity and state error is detected on the host before anything is
+ *     launched; the call then returns a status other than PK_OK and leaves
+ *     pk_state and device memory untouched.  A failed launch gives
+ *     PK_ERR_DEVICE.  Nothing is printed, thrown or aborted.
+ *   - Calls are re-entrant; calls that touch different caches on different
+ *     streams may run concurrently.
+ *
+ * Streams and pattern sets
+ *   A "stream" is the K (or V) history of one (sequence, KV head) pair; there
+ *   are N = n_seq * n_kv_heads of them, stream index n = seq * n_kv_heads + head,
+ *   all of the same length.  `n_seq` may flatten layers and batch.  A pattern
+ *   table holds n_patterns vectors per pattern set; stream (seq, head) uses set
+ *       (seqs_per_set == 0 ? 0 : seq / seqs_per_set) * n_kv_heads + head.
+ *   seqs_per_set = 0 shares one table per KV head among all sequences (the
+ *   paper's memory formula of App. H has no batch factor); seqs_per_set = batch
+ *   gives one table per (layer, head) when n_seq = layers * batch.
+ *
+ * Packed cache format (the paper fixes none; d = head_dim, b = bits, G = group)
+ *   k_codes [N][t_capacity][d/32][b] uint32   bit i of word (w,j) of token t is
+ *                                             bit j of the code of channel 32w+i
+ *   k_scale, k_zero [N][t_capacity/G][d] fp16 one (s,z) per channel and group of
+ *                                             G consecutive tokens
+ *   k_idx   [N][t_capacity] uint8             pattern index k* of every token
+ *   v_codes [N][t_capacity*d*b/8] bytes       tokens in blocks of 32 = 4 slices of
+ *                                             8; the byte holding bit j of channel
+ *                                             c for slice kb of block blk is at
+ *       (((blk*4 + kb)*16 + c%16)*(d/16) + c/16)*b + j ,  bit (t%8) <-> token t
+ *   v_scale, v_zero [N][t_capacity][d/Gc] fp16   Gc = min(G, d): one (s,z) per
+ *                                             token and group of Gc channels
+ *   v_idx   [N][t_capacity] uint8
+ *   tail_k, tail_v [N][recent+flush][d] fp16  ring buffer of the most recent
+ *                                             vectors, kept in full precision;
+ *                                             logical tail token i is in slot
+ *                                             (tail_start + i) % (recent+flush)
+ *   Stored parameters: z = min of the residual group rounded to fp16 towards
+ *   -inf; s = (max - z)/(2^b - 1) rounded to fp16 towards +inf; code =
+ *   clamp(rint((r - z) * (1/s)), 0, 2^b - 1) in binary32, ties to even; a group
+ *   with s == 0 has all codes 0.  Reconstruction: M[k*] + (s*code + z).
+ */
+#ifndef PATTERNKV_H
+#define PATTERNKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PK_ABI_VERSION 1u
+
+typedef enum {
+    PK_OK = 0,
+    PK_ERR_INVALID_ARG = 1, /* NULL where a pointer is required, negative size, bad enum        */
+    PK_ERR_UNSUPPORTED = 2, /* head_dim / bits / group / GQA ratio outside the supported set    */
+    PK_ERR_SHAPE = 3,       /* sizes inconsistent with each other (T < n_patterns, ...)         */
+    PK_ERR_ALIGNMENT = 4,   /* a device pointer is not 16-byte aligned                          */
+    PK_ERR_CAPACITY = 5,    /* the append would exceed t_capacity                               */
+    PK_ERR_STATE = 6,       /* pk_state is not one this library could have produced             */
+    PK_ERR_WORKSPACE = 7,   /* workspace missing or smaller than pk_workspace_bytes             */
+    PK_ERR_DEVICE = 8       /* the HIP runtime refused a launch                                 */
+} pk_status;
+
+/* Pattern-selection metric.  L2 is the metric of the mining objective (Sec. 3.1
+ * Eq. 4); MINMAX is d_mm(x,m) = max_i(x_i-m_i) - min_j(x_j-m_j) of Sec. 3.2.
+ * Ties go to the lowest pattern index. */
+typedef enum { PK_METRIC_L2 = 0, PK_METRIC_MINMAX = 1 } pk_metric;
+
+typedef enum { PK_OP_MINE = 0, PK_OP_APPEND = 1, PK_OP_DECODE = 2 } pk_op;
+
+typedef struct {
+    int32_t n_seq;        /* sequences (layers x batch flattened), >= 1                       */
+    int32_t n_kv_heads;   /* >= 1                                                             */
+    int32_t n_q_heads;    /* multiple of n_kv_heads; n_q_heads/n_kv_heads in 1..8             */
+    int32_t head_dim;     /* d: 128                                                           */
+    int32_t n_patterns;   /* P: 1..256 (indices are stored in one byte)                       */
+    int32_t seqs_per_set; /* see "Streams and pattern sets" above; >= 0                       */
+    int32_t bits;         /* b: 2 or 4                                                        */
+    int32_t group;        /* G: 32, 64 or 128                                                 */
+    int32_t recent;       /* R >= 0: vectors always kept in fp16; R + flush multiple of 8     */
+    int32_t flush;        /* F: multiple of G; vectors quantized per flush                    */
+    int32_t t_capacity;   /* maximum packed tokens per stream, multiple of F                  */
+    int32_t metric;       /* pk_metric                                                        */
+} pk_config;
+
+/* Byte sizes of the cache arrays for a configuration (for the caller to allocate). */
+typedef struct {
+    uint64_t k_codes, k_scale, k_zero, k_idx;
+    uint64_t v_codes, v_scale, v_zero, v_idx;
+    uint64_t tail_k, tail_v;
+    uint64_t total; /* sum of the above, each rounded up to `align`                           */
+    uint32_t align; /* required alignment of every array (16)                                 */
+} pk_layout;
+
+/* Device pointers of one cache, each of at least the size pk_cache_layout reports. */
+typedef struct {
+    void *k_codes, *k_scale, *k_zero, *k_idx;
+    void *v_codes, *v_scale, *v_zero, *v_idx;
+    void *tail_k, *tail_v;
+} pk_cache;
+
+/* Host-side bookkeeping of a cache (all streams have the same lengths).  Start
+ * from all zeros.  Invariants: t_quant is a multiple of flush, t_quant <=
+ * t_capacity, 0 <= t_tail < recent + flush, 0 <= tail_start < recent + flush. */
+typedef struct {
+    int32_t t_quant;    /* tokens in the packed cache                                         */
+    int32_t t_tail;     /* tokens in the fp16 tail                                            */
+    int32_t tail_start; /* ring slot of the oldest tail token                                 */
+} pk_state;
+
+uint32_t pk_abi_version(void);
+const char *pk_status_string(pk_status s);
+
+/* Sizes of the cache arrays.  Host-only; never touches the device. */
+pk_status pk_cache_layout(const pk_config *cfg, pk_layout *out /* host, out */);
+
+/*
+ * Bytes of device workspace the given operation needs.
+ *   PK_OP_MINE  : a = tokens per set T, b = number of pattern sets
+ *   PK_OP_APPEND: a = n_new, b unused
+ *   PK_OP_DECODE: a = packed + tail tokens per stream of the cache itself,
+ *                 b = the same for the shared prefix (0 if none)
+ * Non-decreasing in a and b, so a workspace sized for the largest case serves
+ * all smaller ones.  Returns 0 for an invalid configuration.
+ */
+size_t pk_workspace_bytes(const pk_config *cfg, pk_op op, int64_t a, int64_t b);
+
+/*
+ * Pattern mining (Sec. 3.1, Eq. 4): `iters` Lloyd iterations of K-means under
+ * the Euclidean metric on each of n_sets independent vector sets; the centroid
+ * of each cluster is its pattern.  Uses cfg->head_dim and cfg->n_patterns only.
+ *   x          [n_sets][T][d] fp16, set s starts at x + s*set_stride elements
+ *   patterns   [n_sets][P][d] fp16.  init_given == 0: initialised from the first
+ *              P vectors of each set (T >= P required); != 0: used as the
+ *              starting centroids.  On return: the centroids after `iters`
+ *              updates, each the mean of its members rounded to fp16 (nearest
+ *              even); a cluster without members keeps its centroid.
+ *   assign     optional [n_sets][T] int32: assignment of the last assignment
+ *              step (taken against the centroids before the last update)
+ *   inertia    optional [n_sets][iters] float: within-cluster sum of squares
+ *              seen by each assignment step
+ * Sums are formed in a fixed order: results are reproducible bit for bit.
+ */
+pk_status pk_mine_patterns(const pk_config *cfg, const void *x, int64_t set_stride, int32_t n_sets,
+                           int32_t T, int32_t iters, int32_t init_given, void *patterns,
+                           int32_t *assign, float *inertia, void *workspace, size_t workspace_bytes,
+                           void *stream);
+
+/*
+ * Append n_new vectors per stream (Sec. 3.2): they join the fp16 tail; while
+ * the tail holds at least recent + flush vectors its oldest `flush` vectors are
+ * assigned to their nearest pattern (Eq. 6), residualised and quantized (Eq. 1;
+ * K per channel over groups of G tokens, V per token over groups of Gc
+ * channels), packed and written behind the t_quant tokens already there.
+ *   k_new, v_new  [n_seq][n_kv_heads][n_new][d] fp16; stream n starts at
+ *                 base + n*stream_stride elements (stream_stride 0 = n_new*d)
+ *   patterns_k/_v [n_sets][P][d] fp16
+ *   state         host, in/out
+ * n_new == 0 is a no-op.  Prefill is one call with n_new = prompt length.
+ */
+pk_status pk_quantize_append(const pk_config *cfg, const pk_cache *cache, pk_state *state,
+                             const void *k_new, const void *v_new, int32_t n_new,
+                             int64_t stream_stride, const void *patterns_k, const void *patterns_v,
+                             void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * One decode step of attention over [shared prefix | packed | tail] for every
+ * query head (Sec. 3.4): out = softmax(softmax_scale * q.K^) V^ where K^, V^ are
+ * the reconstructions M[k*] + (s*code + z) of the packed part and the fp16
+ * vectors of the tail.  Nothing is reconstructed in memory: q.M is computed
+ * once per pattern and gathered by index, q.(s*code + z) comes straight from
+ * the packed codes, and the V side adds pattern sums weighted by the softmax
+ * mass of each pattern to the weighted residuals.
+ *   q        [n_seq][n_q_heads][d] fp16; query head h reads KV head h/(n_q/n_kv)
+ *   prefix_* optional (all NULL if unused): a cache with n_seq == 1 whose
+ *            streams precede every sequence's own cache (a shared prompt).  It
+ *            must use the same head counts, head_dim, n_patterns, bits and group,
+ *            and is read with pattern set = KV head of patterns_k / patterns_v.
+ *   out      [n_seq][n_q_heads][d] float
+ *   lse      optional [n_seq][n_q_heads] float: log-sum-exp of the scaled scores
+ * A context of length 0 yields out = 0 and lse = -inf.
+ */
+pk_status pk_decode_attention(const pk_config *cfg, const pk_cache *cache, const pk_state *state,
+                              const pk_config *prefix_cfg, const pk_cache *prefix,
+                              const pk_state *prefix_state, const void *q, float softmax_scale,
+                              const void *patterns_k, const void *patterns_v, float *out, float *lse,
+                              void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Reconstruct packed tokens [t0, t1) of every stream: X^ = M[k*] + (s*code + z)
+ * in binary32, evaluated in that order (the rule below Eq. 6).  For parity
+ * tests and debugging; not on the hot path.
+ *   k_out, v_out [N][t1-t0][d] float (either may be NULL)
+ */
+pk_status pk_dequantize(const pk_config *cfg, const pk_cache *cache, const pk_state *state,
+                        const void *patterns_k, const void *patterns_v, int32_t t0, int32_t t1,
+                        float *k_out, float *v_out, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PATTERNKV_H */

@@ -1,0 +1,371 @@
+// Host side of the C ABI declared in include/patternkv.h: argument checking, cache
+// layout, workspace carving and kernel launches.  Nothing here allocates device memory
+// or synchronises with the device.
+#include <cstring>
+
+#include "pk_internal.h"
+
+using namespace pk;
+
+namespace {
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline uint64_t round_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
+
+pk_status check_config(const pk_config *c)
+{
+    if (!c) return PK_ERR_INVALID_ARG;
+    if (c->n_seq < 1 || c->n_kv_heads < 1 || c->n_q_heads < 1 || c->n_patterns < 1 || c->seqs_per_set < 0 ||
+        c->recent < 0 || c->flush < 1 || c->t_capacity < 0)
+        return PK_ERR_INVALID_ARG;
+    if (c->metric != PK_METRIC_L2 && c->metric != PK_METRIC_MINMAX) return PK_ERR_INVALID_ARG;
+    if (c->head_dim != kD) return PK_ERR_UNSUPPORTED;
+    if (c->n_patterns > 256) return PK_ERR_UNSUPPORTED;
+    if (c->bits != 2 && c->bits != 4) return PK_ERR_UNSUPPORTED;
+    if (c->group != 32 && c->group != 64 && c->group != 128) return PK_ERR_UNSUPPORTED;
+    if (c->n_q_heads % c->n_kv_heads != 0) return PK_ERR_SHAPE;
+    if (c->n_q_heads / c->n_kv_heads > 8) return PK_ERR_UNSUPPORTED;
+    if ((int64_t)c->n_seq * c->n_kv_heads > 65535) return PK_ERR_UNSUPPORTED;
+    if (c->flush % c->group != 0) return PK_ERR_SHAPE;
+    if (c->t_capacity % c->flush != 0) return PK_ERR_SHAPE;
+    return PK_OK;
+}
+
+pk_status check_state(const pk_config *c, const pk_state *s)
+{
+    if (!s) return PK_ERR_INVALID_ARG;
+    const int ring = c->recent + c->flush;
+    if (s->t_quant < 0 || s->t_quant > c->t_capacity || s->t_quant % c->flush != 0) return PK_ERR_STATE;
+    if (s->t_tail < 0 || s->t_tail >= ring) return PK_ERR_STATE;
+    if (s->tail_start < 0 || s->tail_start >= ring) return PK_ERR_STATE;
+    return PK_OK;
+}
+
+pk_status check_cache(const pk_cache *k)
+{
+    if (!k) return PK_ERR_INVALID_ARG;
+    const void *p[10] = {k->k_codes, k->k_scale, k->k_zero, k->k_idx, k->v_codes,
+                         k->v_scale, k->v_zero,  k->v_idx,  k->tail_k, k->tail_v};
+    for (const void *q : p)
+        if (!q) return PK_ERR_INVALID_ARG;
+    for (const void *q : p)
+        if (!aligned16(q)) return PK_ERR_ALIGNMENT;
+    return PK_OK;
+}
+
+CacheView make_view(const pk_config *c, const pk_cache *k, const pk_state *s)
+{
+    CacheView v;
+    v.k_codes = static_cast<const uint32_t *>(k->k_codes);
+    v.k_scale = static_cast<const __half *>(k->k_scale);
+    v.k_zero = static_cast<const __half *>(k->k_zero);
+    v.k_idx = static_cast<const uint8_t *>(k->k_idx);
+    v.v_codes = static_cast<const uint8_t *>(k->v_codes);
+    v.v_scale = static_cast<const __half *>(k->v_scale);
+    v.v_zero = static_cast<const __half *>(k->v_zero);
+    v.v_idx = static_cast<const uint8_t *>(k->v_idx);
+    v.tail_k = static_cast<const __half *>(k->tail_k);
+    v.tail_v = static_cast<const __half *>(k->tail_v);
+    v.t_capacity = c->t_capacity;
+    v.t_quant = s->t_quant;
+    v.t_tail = s->t_tail;
+    v.tail_start = s->tail_start;
+    v.ring_len = c->recent + c->flush;
+    return v;
+}
+
+// upper bound on the number of partial slots decode uses for up to a own / b prefix tokens
+int64_t decode_slots_bound(int64_t N, int64_t a, int64_t b)
+{
+    const int64_t fine = (a + 255) / 256 + (b + 255) / 256;
+    const int64_t target = 2048 / N + 4;
+    const int64_t coarse = (a + 8191) / 8192 + (b + 8191) / 8192;
+    int64_t s = fine < target ? fine : target;
+    if (coarse > s) s = coarse;
+    return s + 2;
+}
+
+struct MineCarve {
+    size_t assign, best, psum, pcnt, total;
+};
+MineCarve mine_carve(int64_t S, int64_t T, int P)
+{
+    MineCarve m;
+    const int ts = mine_tsplit((int)T);
+    m.assign = 0;
+    m.best = round_up(m.assign + (uint64_t)S * T * 4, 256);
+    m.psum = round_up(m.best + (uint64_t)S * T * 4, 256);
+    m.pcnt = round_up(m.psum + (uint64_t)S * ts * P * kD * 4, 256);
+    m.total = round_up(m.pcnt + (uint64_t)S * ts * P * 4, 256);
+    return m;
+}
+
+}  // namespace
+
+extern "C" {
+
+uint32_t pk_abi_version(void) { return PK_ABI_VERSION; }
+
+const char *pk_status_string(pk_status s)
+{
+    switch (s) {
+    case PK_OK: return "ok";
+    case PK_ERR_INVALID_ARG: return "invalid argument";
+    case PK_ERR_UNSUPPORTED: return "unsupported configuration";
+    case PK_ERR_SHAPE: return "inconsistent shapes";
+    case PK_ERR_ALIGNMENT: return "device pointer not 16-byte aligned";
+    case PK_ERR_CAPACITY: return "cache capacity exceeded";
+    case PK_ERR_STATE: return "invalid cache state";
+    case PK_ERR_WORKSPACE: return "workspace missing or too small";
+    case PK_ERR_DEVICE: return "HIP launch failed";
+    }
+    return "unknown status";
+}
+
+pk_status pk_cache_layout(const pk_config *cfg, pk_layout *out)
+{
+    pk_status st = check_config(cfg);
+    if (st != PK_OK) return st;
+    if (!out) return PK_ERR_INVALID_ARG;
+    const uint64_t N = (uint64_t)cfg->n_seq * cfg->n_kv_heads, cap = cfg->t_capacity, d = kD, b = cfg->bits;
+    const uint64_t G = cfg->group, Gc = G < d ? G : d;
+    out->align = 16;
+    out->k_codes = N * cap * d * b / 8;
+    out->k_scale = out->k_zero = N * (cap / G) * d * 2;
+    out->k_idx = N * cap;
+    out->v_codes = N * cap * d * b / 8;
+    out->v_scale = out->v_zero = N * cap * (d / Gc) * 2;
+    out->v_idx = N * cap;
+    out->tail_k = out->tail_v = N * (uint64_t)(cfg->recent + cfg->flush) * d * 2;
+    const uint64_t parts[10] = {out->k_codes, out->k_scale, out->k_zero, out->k_idx, out->v_codes,
+                                out->v_scale, out->v_zero,  out->v_idx,  out->tail_k, out->tail_v};
+    out->total = 0;
+    for (uint64_t p : parts) out->total += round_up(p, out->align);
+    return PK_OK;
+}
+
+size_t pk_workspace_bytes(const pk_config *cfg, pk_op op, int64_t a, int64_t b)
+{
+    if (!cfg || a < 0 || b < 0) return 0;
+    if (op == PK_OP_MINE) {
+        if (cfg->head_dim != kD || cfg->n_patterns < 1 || cfg->n_patterns > 256 || b < 1) return 0;
+        return mine_carve(b, a, cfg->n_patterns).total;
+    }
+    if (check_config(cfg) != PK_OK) return 0;
+    if (op == PK_OP_APPEND) return 0;
+    if (op == PK_OP_DECODE) {
+        const int64_t N = (int64_t)cfg->n_seq * cfg->n_kv_heads, r = cfg->n_q_heads / cfg->n_kv_heads;
+        const int64_t slots = decode_slots_bound(N, a, b);
+        return round_up((uint64_t)N * slots * r * kD * 4, 256) + round_up((uint64_t)N * slots * r * 2 * 4, 256);
+    }
+    return 0;
+}
+
+pk_status pk_mine_patterns(const pk_config *cfg, const void *x, int64_t set_stride, int32_t n_sets, int32_t T,
+                           int32_t iters, int32_t init_given, void *patterns, int32_t *assign, float *inertia,
+                           void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!cfg || !x || !patterns) return PK_ERR_INVALID_ARG;
+    if (n_sets < 1 || T < 1 || iters < 0 || cfg->n_patterns < 1) return PK_ERR_INVALID_ARG;
+    if (cfg->head_dim != kD || cfg->n_patterns > 256 || n_sets > 65535) return PK_ERR_UNSUPPORTED;
+    if (!init_given && T < cfg->n_patterns) return PK_ERR_SHAPE;
+    if (set_stride < (int64_t)T * kD || set_stride % 8 != 0) return PK_ERR_SHAPE;
+    if (!aligned16(x) || !aligned16(patterns) || (assign && !aligned16(assign))) return PK_ERR_ALIGNMENT;
+    const MineCarve mc = mine_carve(n_sets, T, cfg->n_patterns);
+    if (!workspace || workspace_bytes < mc.total) return PK_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return PK_ERR_ALIGNMENT;
+
+    char *ws = static_cast<char *>(workspace);
+    MineArgs a;
+    a.x = static_cast<const __half *>(x);
+    a.set_stride = set_stride;
+    a.n_sets = n_sets;
+    a.T = T;
+    a.P = cfg->n_patterns;
+    a.iters = iters;
+    a.init_given = init_given;
+    a.patterns = static_cast<__half *>(patterns);
+    a.assign = assign ? assign : reinterpret_cast<int32_t *>(ws + mc.assign);
+    a.best = reinterpret_cast<float *>(ws + mc.best);
+    a.psum = reinterpret_cast<float *>(ws + mc.psum);
+    a.pcnt = reinterpret_cast<int32_t *>(ws + mc.pcnt);
+    a.inertia = inertia;
+    a.tsplit = mine_tsplit(T);
+    return launch_mine(a, static_cast<hipStream_t>(stream)) == hipSuccess ? PK_OK : PK_ERR_DEVICE;
+}
+
+pk_status pk_quantize_append(const pk_config *cfg, const pk_cache *cache, pk_state *state, const void *k_new,
+                             const void *v_new, int32_t n_new, int64_t stream_stride, const void *patterns_k,
+                             const void *patterns_v, void *workspace, size_t workspace_bytes, void *stream)
+{
+    (void)workspace;
+    (void)workspace_bytes;
+    pk_status st = check_config(cfg);
+    if (st != PK_OK) return st;
+    if ((st = check_cache(cache)) != PK_OK) return st;
+    if ((st = check_state(cfg, state)) != PK_OK) return st;
+    if (n_new < 0) return PK_ERR_INVALID_ARG;
+    if (n_new == 0) return PK_OK;
+    if (!k_new || !v_new || !patterns_k || !patterns_v) return PK_ERR_INVALID_ARG;
+    if (stream_stride == 0) stream_stride = (int64_t)n_new * kD;
+    if (stream_stride < (int64_t)n_new * kD || stream_stride % 8 != 0) return PK_ERR_SHAPE;
+    if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(patterns_k) || !aligned16(patterns_v))
+        return PK_ERR_ALIGNMENT;
+
+    const int64_t R = cfg->recent, F = cfg->flush, ring = R + F;
+    const int64_t L = (int64_t)state->t_tail + n_new;
+    const int64_t nf = L >= R ? (L - R) / F : 0;
+    const int64_t nq = nf * F;
+    if ((int64_t)state->t_quant + nq > cfg->t_capacity) return PK_ERR_CAPACITY;
+
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    const int N = cfg->n_seq * cfg->n_kv_heads;
+    if (nq > 0) {
+        QuantArgs a;
+        a.src.ring_len = (int32_t)ring;
+        a.src.ring_start = state->tail_start;
+        a.src.n_ring = state->t_tail;
+        a.src.fresh_stride = stream_stride;
+        a.sets.n_kv_heads = cfg->n_kv_heads;
+        a.sets.seqs_per_set = cfg->seqs_per_set;
+        a.P = cfg->n_patterns;
+        a.metric = cfg->metric;
+        a.bits = cfg->bits;
+        a.G = cfg->group;
+        a.n_streams = N;
+        a.nq = (int32_t)nq;
+        a.t0 = state->t_quant;
+        a.t_capacity = cfg->t_capacity;
+        // K
+        a.src.ring = static_cast<const __half *>(cache->tail_k);
+        a.src.fresh = static_cast<const __half *>(k_new);
+        a.patterns = static_cast<const __half *>(patterns_k);
+        a.codes_k = static_cast<uint32_t *>(cache->k_codes);
+        a.codes_v = nullptr;
+        a.scale = static_cast<__half *>(cache->k_scale);
+        a.zero = static_cast<__half *>(cache->k_zero);
+        a.idx = static_cast<uint8_t *>(cache->k_idx);
+        if (launch_quantize_k(a, hs) != hipSuccess) return PK_ERR_DEVICE;
+        // V
+        a.src.ring = static_cast<const __half *>(cache->tail_v);
+        a.src.fresh = static_cast<const __half *>(v_new);
+        a.patterns = static_cast<const __half *>(patterns_v);
+        a.codes_k = nullptr;
+        a.codes_v = static_cast<uint8_t *>(cache->v_codes);
+        a.scale = static_cast<__half *>(cache->v_scale);
+        a.zero = static_cast<__half *>(cache->v_zero);
+        a.idx = static_cast<uint8_t *>(cache->v_idx);
+        if (launch_quantize_v(a, hs) != hipSuccess) return PK_ERR_DEVICE;
+    }
+    // what is left stays in (old tail vectors) or moves into (fresh vectors) the ring;
+    // logical vector i always lives in slot (tail_start + i) % ring
+    TailCopyArgs c;
+    c.fresh_k = static_cast<const __half *>(k_new);
+    c.fresh_v = static_cast<const __half *>(v_new);
+    c.fresh_stride = stream_stride;
+    c.ring_k = static_cast<__half *>(cache->tail_k);
+    c.ring_v = static_cast<__half *>(cache->tail_v);
+    c.ring_len = (int32_t)ring;
+    c.ring_start = state->tail_start;
+    c.n_ring = state->t_tail;
+    c.i0 = (int32_t)(nq > state->t_tail ? nq : state->t_tail);
+    c.i1 = (int32_t)L;
+    c.n_streams = N;
+    if (launch_tail_copy(c, hs) != hipSuccess) return PK_ERR_DEVICE;
+
+    state->t_quant += (int32_t)nq;
+    state->tail_start = (int32_t)((state->tail_start + nq) % ring);
+    state->t_tail = (int32_t)(L - nq);
+    return PK_OK;
+}
+
+pk_status pk_decode_attention(const pk_config *cfg, const pk_cache *cache, const pk_state *state,
+                              const pk_config *prefix_cfg, const pk_cache *prefix, const pk_state *prefix_state,
+                              const void *q, float softmax_scale, const void *patterns_k, const void *patterns_v,
+                              float *out, float *lse, void *workspace, size_t workspace_bytes, void *stream)
+{
+    pk_status st = check_config(cfg);
+    if (st != PK_OK) return st;
+    if ((st = check_cache(cache)) != PK_OK) return st;
+    if ((st = check_state(cfg, state)) != PK_OK) return st;
+    if (!q || !patterns_k || !patterns_v || !out) return PK_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(patterns_k) || !aligned16(patterns_v) || !aligned16(out) ||
+        (lse && !aligned16(lse)))
+        return PK_ERR_ALIGNMENT;
+    const bool has_prefix = prefix_cfg || prefix || prefix_state;
+    if (has_prefix) {
+        if (!prefix_cfg || !prefix || !prefix_state) return PK_ERR_INVALID_ARG;
+        if ((st = check_config(prefix_cfg)) != PK_OK) return st;
+        if ((st = check_cache(prefix)) != PK_OK) return st;
+        if ((st = check_state(prefix_cfg, prefix_state)) != PK_OK) return st;
+        if (prefix_cfg->n_seq != 1 || prefix_cfg->n_kv_heads != cfg->n_kv_heads ||
+            prefix_cfg->n_q_heads != cfg->n_q_heads || prefix_cfg->n_patterns != cfg->n_patterns ||
+            prefix_cfg->bits != cfg->bits || prefix_cfg->group != cfg->group)
+            return PK_ERR_SHAPE;
+    }
+
+    DecodeArgs a;
+    a.own = make_view(cfg, cache, state);
+    if (has_prefix) {
+        a.prefix = make_view(prefix_cfg, prefix, prefix_state);
+    } else {
+        std::memset(&a.prefix, 0, sizeof(a.prefix));
+        a.prefix.ring_len = 1;
+    }
+    const int64_t N = (int64_t)cfg->n_seq * cfg->n_kv_heads, r = cfg->n_q_heads / cfg->n_kv_heads;
+    a.chunk = decode_chunk(N, (int64_t)a.own.t_quant + a.prefix.t_quant);
+    a.splits_own = (a.own.t_quant + a.chunk - 1) / a.chunk;
+    a.splits_prefix = (a.prefix.t_quant + a.chunk - 1) / a.chunk;
+    const int64_t slots = a.splits_own + a.splits_prefix + 2;
+    const uint64_t o_bytes = round_up((uint64_t)N * slots * r * kD * 4, 256);
+    const uint64_t ml_bytes = round_up((uint64_t)N * slots * r * 2 * 4, 256);
+    if (!workspace || workspace_bytes < o_bytes + ml_bytes) return PK_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return PK_ERR_ALIGNMENT;
+
+    a.sets.n_kv_heads = cfg->n_kv_heads;
+    a.sets.seqs_per_set = cfg->seqs_per_set;
+    a.q = static_cast<const __half *>(q);
+    a.patterns_k = static_cast<const __half *>(patterns_k);
+    a.patterns_v = static_cast<const __half *>(patterns_v);
+    a.n_seq = cfg->n_seq;
+    a.n_kv_heads = cfg->n_kv_heads;
+    a.n_q_heads = cfg->n_q_heads;
+    a.P = cfg->n_patterns;
+    a.bits = cfg->bits;
+    a.G = cfg->group;
+    a.softmax_scale = softmax_scale;
+    a.part_o = reinterpret_cast<float *>(workspace);
+    a.part_ml = reinterpret_cast<float *>(static_cast<char *>(workspace) + o_bytes);
+    a.out = out;
+    a.lse = lse;
+    return launch_decode(a, static_cast<hipStream_t>(stream)) == hipSuccess ? PK_OK : PK_ERR_DEVICE;
+}
+
+pk_status pk_dequantize(const pk_config *cfg, const pk_cache *cache, const pk_state *state, const void *patterns_k,
+                        const void *patterns_v, int32_t t0, int32_t t1, float *k_out, float *v_out, void *stream)
+{
+    pk_status st = check_config(cfg);
+    if (st != PK_OK) return st;
+    if ((st = check_cache(cache)) != PK_OK) return st;
+    if ((st = check_state(cfg, state)) != PK_OK) return st;
+    if (t0 < 0 || t1 < t0 || t1 > state->t_quant) return PK_ERR_SHAPE;
+    if ((k_out && !patterns_k) || (v_out && !patterns_v)) return PK_ERR_INVALID_ARG;
+    if ((k_out && !aligned16(k_out)) || (v_out && !aligned16(v_out))) return PK_ERR_ALIGNMENT;
+    DequantArgs a;
+    a.c = make_view(cfg, cache, state);
+    a.sets.n_kv_heads = cfg->n_kv_heads;
+    a.sets.seqs_per_set = cfg->seqs_per_set;
+    a.patterns_k = static_cast<const __half *>(patterns_k);
+    a.patterns_v = static_cast<const __half *>(patterns_v);
+    a.n_streams = cfg->n_seq * cfg->n_kv_heads;
+    a.P = cfg->n_patterns;
+    a.bits = cfg->bits;
+    a.G = cfg->group;
+    a.t0 = t0;
+    a.t1 = t1;
+    a.k_out = k_out;
+    a.v_out = v_out;
+    return launch_dequant(a, static_cast<hipStream_t>(stream)) == hipSuccess ? PK_OK : PK_ERR_DEVICE;
+}
+
+}  // extern "C"

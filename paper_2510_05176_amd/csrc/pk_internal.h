@@ -1,0 +1,157 @@
+// Internal declarations shared by the HIP translation units of libpatternkv.
+// Not part of the public ABI (that is include/patternkv.h).
+#pragma once
+
+#include <hip/hip_fp16.h>
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "patternkv.h"
+
+namespace pk {
+
+constexpr int kD = 128;          // head_dim supported by the kernels
+constexpr int kRowChunks = 16;   // 16-byte chunks per fp16 row of kD elements
+
+// Where the logical vectors of an append come from: first the old fp16 tail
+// (a ring), then the freshly passed vectors.
+struct RowSource {
+    const __half *ring;        // [N][ring_len][kD]
+    const __half *fresh;       // stream n at fresh + n*fresh_stride
+    int64_t fresh_stride;      // elements
+    int32_t ring_len;
+    int32_t ring_start;        // slot of logical vector 0
+    int32_t n_ring;            // logical vectors [0, n_ring) live in the ring
+
+    __device__ __forceinline__ const __half *row(int n, int i) const
+    {
+        if (i < n_ring) {
+            int slot = ring_start + i;
+            if (slot >= ring_len) slot -= ring_len;
+            return ring + ((int64_t)n * ring_len + slot) * kD;
+        }
+        return fresh + (int64_t)n * fresh_stride + (int64_t)(i - n_ring) * kD;
+    }
+};
+
+struct SetMap {
+    int32_t n_kv_heads;
+    int32_t seqs_per_set;
+    __host__ __device__ __forceinline__ int set_of(int stream) const
+    {
+        const int seq = stream / n_kv_heads, head = stream - seq * n_kv_heads;
+        return (seqs_per_set == 0 ? 0 : seq / seqs_per_set) * n_kv_heads + head;
+    }
+};
+
+// ---- fp16 helpers -----------------------------------------------------------
+
+__device__ __forceinline__ float h2f(__half h) { return __half2float(h); }
+__device__ __forceinline__ float hbits2f(unsigned short u) { return __half2float(__ushort_as_half(u)); }
+
+// largest binary16 value <= f
+__device__ __forceinline__ unsigned short f2h_down(float f)
+{
+    unsigned short u = __half_as_ushort(__float2half_rn(f));
+    if (hbits2f(u) > f) {
+        if ((u & 0x7fffu) == 0) u = 0x8001u;   // +-0 -> smallest negative subnormal
+        else if (u & 0x8000u) u += 1;          // negative: one step away from zero
+        else u -= 1;                           // positive: one step towards zero
+    }
+    return u;
+}
+
+// smallest binary16 value >= f
+__device__ __forceinline__ unsigned short f2h_up(float f)
+{
+    unsigned short u = __half_as_ushort(__float2half_rn(f));
+    if (hbits2f(u) < f) {
+        if ((u & 0x7fffu) == 0) u = 0x0001u;
+        else if (u & 0x8000u) u -= 1;
+        else u += 1;
+    }
+    return u;
+}
+
+// ---- launchers (host) -------------------------------------------------------
+
+struct QuantArgs {
+    RowSource src;
+    SetMap sets;
+    const __half *patterns;   // [n_sets][P][kD]
+    int32_t P, metric, bits, G;
+    int32_t n_streams;
+    int32_t nq;               // vectors to quantize per stream (multiple of G)
+    int32_t t0;               // first packed position to write (= t_quant)
+    int32_t t_capacity;
+    uint32_t *codes_k;        // K side
+    uint8_t *codes_v;         // V side
+    __half *scale, *zero;
+    uint8_t *idx;
+};
+
+hipError_t launch_quantize_k(const QuantArgs &a, hipStream_t s);
+hipError_t launch_quantize_v(const QuantArgs &a, hipStream_t s);
+
+struct TailCopyArgs {
+    const __half *fresh_k, *fresh_v;
+    int64_t fresh_stride;
+    __half *ring_k, *ring_v;
+    int32_t ring_len, ring_start, n_ring;   // as in RowSource (state before the append)
+    int32_t i0, i1;                          // logical vectors [i0, i1) to place into the ring
+    int32_t n_streams;
+};
+hipError_t launch_tail_copy(const TailCopyArgs &a, hipStream_t s);
+
+struct MineArgs {
+    const __half *x;
+    int64_t set_stride;
+    int32_t n_sets, T, P, iters, init_given;
+    __half *patterns;
+    int32_t *assign;       // [n_sets][T] (workspace or caller's)
+    float *best;           // [n_sets][T] workspace
+    float *psum;           // [n_sets][tsplit][P][kD]
+    int32_t *pcnt;         // [n_sets][tsplit][P]
+    float *inertia;        // optional [n_sets][iters]
+    int32_t tsplit;
+};
+hipError_t launch_mine(const MineArgs &a, hipStream_t s);
+int mine_tsplit(int T);
+
+struct CacheView {
+    const uint32_t *k_codes;
+    const __half *k_scale, *k_zero;
+    const uint8_t *k_idx;
+    const uint8_t *v_codes;
+    const __half *v_scale, *v_zero;
+    const uint8_t *v_idx;
+    const __half *tail_k, *tail_v;
+    int32_t t_capacity, t_quant, t_tail, tail_start, ring_len;
+};
+
+struct DecodeArgs {
+    CacheView own, prefix;        // prefix.t_quant == prefix.t_tail == 0 when unused
+    SetMap sets;
+    const __half *q;              // [n_seq][Hq][kD]
+    const __half *patterns_k, *patterns_v;
+    int32_t n_seq, n_kv_heads, n_q_heads, P, bits, G;
+    float softmax_scale;
+    int32_t chunk;                // packed tokens per split
+    int32_t splits_prefix, splits_own;   // packed splits; two more slots hold the tails
+    float *part_o;                // [N][S][r][kD]
+    float *part_ml;               // [N][S][r][2]
+    float *out, *lse;
+};
+hipError_t launch_decode(const DecodeArgs &a, hipStream_t s);
+int decode_chunk(int64_t n_streams, int64_t t_packed_total);
+
+struct DequantArgs {
+    CacheView c;
+    SetMap sets;
+    const __half *patterns_k, *patterns_v;
+    int32_t n_streams, P, bits, G, t0, t1;
+    float *k_out, *v_out;
+};
+hipError_t launch_dequant(const DequantArgs &a, hipStream_t s);
+
+}  // namespace pk

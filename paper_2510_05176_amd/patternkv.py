@@ -1,0 +1,250 @@
+"""ctypes binding of libpatternkv.so (the C ABI of include/patternkv.h).
+
+Argument marshalling only: every step of the hot path runs in the HIP kernels of the
+library.  PyTorch is used for device memory and the current stream.  There is no CPU
+fallback: if the library has not been built, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass, asdict
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libpatternkv.so")
+
+if not os.path.exists(_LIB_PATH):
+    raise ImportError(
+        f"{_LIB_PATH} is missing: build it with `python -m paper_2510_05176_amd.build` "
+        "(hipcc, gfx950). There is no fallback path.")
+_lib = C.CDLL(_LIB_PATH)
+
+PK_OK = 0
+METRIC_L2, METRIC_MINMAX = 0, 1
+OP_MINE, OP_APPEND, OP_DECODE = 0, 1, 2
+
+
+class _Config(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in (
+        "n_seq", "n_kv_heads", "n_q_heads", "head_dim", "n_patterns", "seqs_per_set",
+        "bits", "group", "recent", "flush", "t_capacity", "metric")]
+
+
+class _Layout(C.Structure):
+    _fields_ = [(n, C.c_uint64) for n in (
+        "k_codes", "k_scale", "k_zero", "k_idx", "v_codes", "v_scale", "v_zero", "v_idx",
+        "tail_k", "tail_v", "total")] + [("align", C.c_uint32)]
+
+
+class _Cache(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in (
+        "k_codes", "k_scale", "k_zero", "k_idx", "v_codes", "v_scale", "v_zero", "v_idx",
+        "tail_k", "tail_v")]
+
+
+class _State(C.Structure):
+    _fields_ = [("t_quant", C.c_int32), ("t_tail", C.c_int32), ("tail_start", C.c_int32)]
+
+
+_lib.pk_abi_version.restype = C.c_uint32
+_lib.pk_status_string.restype = C.c_char_p
+_lib.pk_status_string.argtypes = [C.c_int]
+_lib.pk_cache_layout.restype = C.c_int
+_lib.pk_cache_layout.argtypes = [C.POINTER(_Config), C.POINTER(_Layout)]
+_lib.pk_workspace_bytes.restype = C.c_size_t
+_lib.pk_workspace_bytes.argtypes = [C.POINTER(_Config), C.c_int, C.c_int64, C.c_int64]
+_lib.pk_mine_patterns.restype = C.c_int
+_lib.pk_mine_patterns.argtypes = [C.POINTER(_Config), C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int32,
+                                  C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
+                                  C.c_void_p]
+_lib.pk_quantize_append.restype = C.c_int
+_lib.pk_quantize_append.argtypes = [C.POINTER(_Config), C.POINTER(_Cache), C.POINTER(_State), C.c_void_p,
+                                    C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
+                                    C.c_size_t, C.c_void_p]
+_lib.pk_decode_attention.restype = C.c_int
+_lib.pk_decode_attention.argtypes = [C.POINTER(_Config), C.POINTER(_Cache), C.POINTER(_State),
+                                     C.POINTER(_Config), C.POINTER(_Cache), C.POINTER(_State), C.c_void_p,
+                                     C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                     C.c_size_t, C.c_void_p]
+_lib.pk_dequantize.restype = C.c_int
+_lib.pk_dequantize.argtypes = [C.POINTER(_Config), C.POINTER(_Cache), C.POINTER(_State), C.c_void_p,
+                               C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+
+
+class PkError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {_lib.pk_status_string(status).decode()} (status {status})")
+
+
+def _check(status: int, where: str):
+    if status != PK_OK:
+        raise PkError(status, where)
+
+
+def pk_abi_version() -> int:
+    return int(_lib.pk_abi_version())
+
+
+def pk_status_string(status: int) -> str:
+    return _lib.pk_status_string(int(status)).decode()
+
+
+@dataclass
+class Config:
+    n_seq: int = 1
+    n_kv_heads: int = 1
+    n_q_heads: int = 1
+    head_dim: int = 128
+    n_patterns: int = 16
+    seqs_per_set: int = 0
+    bits: int = 2
+    group: int = 64
+    recent: int = 0
+    flush: int = 64
+    t_capacity: int = 0
+    metric: int = METRIC_L2
+
+    def c(self) -> _Config:
+        return _Config(**asdict(self))
+
+    @property
+    def n_streams(self) -> int:
+        return self.n_seq * self.n_kv_heads
+
+    @property
+    def n_sets(self) -> int:
+        if self.seqs_per_set == 0:
+            return self.n_kv_heads
+        return -(-self.n_seq // self.seqs_per_set) * self.n_kv_heads
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    assert t.is_contiguous(), "tensors handed to the library must be contiguous"
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def pk_cache_layout(cfg: Config) -> dict:
+    lay = _Layout()
+    c = cfg.c()
+    _check(_lib.pk_cache_layout(C.byref(c), C.byref(lay)), "pk_cache_layout")
+    return {n: int(getattr(lay, n)) for n, _ in _Layout._fields_}
+
+
+def pk_workspace_bytes(cfg: Config, op: int, a: int, b: int = 0) -> int:
+    c = cfg.c()
+    return int(_lib.pk_workspace_bytes(C.byref(c), op, a, b))
+
+
+_ARRAYS = ("k_codes", "k_scale", "k_zero", "k_idx", "v_codes", "v_scale", "v_zero", "v_idx", "tail_k", "tail_v")
+
+
+class Cache:
+    """Device memory of one cache (torch uint8 tensors sized by pk_cache_layout) plus its host state."""
+
+    def __init__(self, cfg: Config, device="cuda"):
+        self.cfg = cfg
+        lay = pk_cache_layout(cfg)
+        self.bytes = {n: lay[n] for n in _ARRAYS}
+        self.buf = {n: torch.zeros(max(lay[n], 16), dtype=torch.uint8, device=device) for n in _ARRAYS}
+        self.state = _State(0, 0, 0)
+
+    def c(self) -> _Cache:
+        return _Cache(**{n: self.buf[n].data_ptr() for n in _ARRAYS})
+
+    @property
+    def t_quant(self):
+        return int(self.state.t_quant)
+
+    @property
+    def t_tail(self):
+        return int(self.state.t_tail)
+
+    @property
+    def tail_start(self):
+        return int(self.state.tail_start)
+
+    def array(self, name):
+        """Raw bytes of one cache array (uint8 tensor of the layout's size)."""
+        return self.buf[name][: self.bytes[name]]
+
+
+def pk_mine_patterns(cfg: Config, x: torch.Tensor, iters: int, patterns: torch.Tensor | None = None,
+                     init_given: bool = False, assign: torch.Tensor | None = None,
+                     inertia: torch.Tensor | None = None, workspace: torch.Tensor | None = None):
+    """x [n_sets, T, d] fp16 (sets may be strided, rows contiguous) -> patterns [n_sets, P, d] fp16."""
+    assert x.dtype == torch.float16 and x.dim() == 3 and x.stride(2) == 1 and x.stride(1) == x.shape[2]
+    n_sets, T, d = x.shape
+    if patterns is None:
+        patterns = torch.empty((n_sets, cfg.n_patterns, d), dtype=torch.float16, device=x.device)
+    if workspace is None:
+        workspace = torch.empty(max(pk_workspace_bytes(cfg, OP_MINE, T, n_sets), 16), dtype=torch.uint8, device=x.device)
+    c = cfg.c()
+    st = _lib.pk_mine_patterns(C.byref(c), C.c_void_p(x.data_ptr()), x.stride(0), n_sets, T, iters,
+                               1 if init_given else 0, _ptr(patterns), _ptr(assign), _ptr(inertia),
+                               _ptr(workspace), workspace.numel(), _stream())
+    _check(st, "pk_mine_patterns")
+    return patterns
+
+
+def pk_quantize_append(cfg: Config, cache: Cache, k_new: torch.Tensor, v_new: torch.Tensor,
+                       patterns_k: torch.Tensor, patterns_v: torch.Tensor, workspace: torch.Tensor | None = None):
+    """k_new, v_new [n_seq, n_kv_heads, n_new, d] fp16 (token rows contiguous, streams may be strided)."""
+    assert k_new.dtype == torch.float16 and v_new.dtype == torch.float16 and k_new.shape == v_new.shape
+    n_seq, hkv, n_new, d = k_new.shape
+    for t in (k_new, v_new):
+        assert t.stride(3) == 1 and t.stride(2) == d and t.stride(0) == hkv * t.stride(1)
+    assert k_new.stride(1) == v_new.stride(1)
+    cc, kc = cfg.c(), cache.c()
+    st = _lib.pk_quantize_append(C.byref(cc), C.byref(kc), C.byref(cache.state), C.c_void_p(k_new.data_ptr()),
+                                 C.c_void_p(v_new.data_ptr()), n_new, k_new.stride(1), _ptr(patterns_k),
+                                 _ptr(patterns_v), _ptr(workspace), 0 if workspace is None else workspace.numel(),
+                                 _stream())
+    _check(st, "pk_quantize_append")
+
+
+def pk_decode_attention(cfg: Config, cache: Cache, q: torch.Tensor, softmax_scale: float,
+                        patterns_k: torch.Tensor, patterns_v: torch.Tensor, out: torch.Tensor | None = None,
+                        lse: torch.Tensor | None = None, workspace: torch.Tensor | None = None,
+                        prefix: Cache | None = None):
+    """q [n_seq, n_q_heads, d] fp16 -> out [n_seq, n_q_heads, d] fp32."""
+    assert q.dtype == torch.float16
+    if out is None:
+        out = torch.empty(q.shape, dtype=torch.float32, device=q.device)
+    if workspace is None:
+        a = cache.t_quant + cache.t_tail
+        b = 0 if prefix is None else prefix.t_quant + prefix.t_tail
+        workspace = torch.empty(max(pk_workspace_bytes(cfg, OP_DECODE, a, b), 16), dtype=torch.uint8, device=q.device)
+    cc, kc = cfg.c(), cache.c()
+    if prefix is not None:
+        pc, pkc = prefix.cfg.c(), prefix.c()
+        pargs = (C.byref(pc), C.byref(pkc), C.byref(prefix.state))
+    else:
+        pargs = (None, None, None)
+    st = _lib.pk_decode_attention(C.byref(cc), C.byref(kc), C.byref(cache.state), *pargs, _ptr(q),
+                                  C.c_float(softmax_scale), _ptr(patterns_k), _ptr(patterns_v), _ptr(out),
+                                  _ptr(lse), _ptr(workspace), workspace.numel(), _stream())
+    _check(st, "pk_decode_attention")
+    return out
+
+
+def pk_dequantize(cfg: Config, cache: Cache, patterns_k: torch.Tensor, patterns_v: torch.Tensor,
+                  t0: int = 0, t1: int | None = None):
+    """Reconstructed K^, V^ of packed tokens [t0, t1): two [N, t1-t0, d] fp32 tensors."""
+    t1 = cache.t_quant if t1 is None else t1
+    dev = patterns_k.device
+    k = torch.empty((cfg.n_streams, t1 - t0, cfg.head_dim), dtype=torch.float32, device=dev)
+    v = torch.empty_like(k)
+    cc, kc = cfg.c(), cache.c()
+    st = _lib.pk_dequantize(C.byref(cc), C.byref(kc), C.byref(cache.state), _ptr(patterns_k), _ptr(patterns_v),
+                            t0, t1, _ptr(k), _ptr(v), _stream())
+    _check(st, "pk_dequantize")
+    return k, v

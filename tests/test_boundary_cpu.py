@@ -1,0 +1,152 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the header
+declares, computes layouts / workspace sizes, and turns bad arguments into status codes before any launch.
+(Every error below is detected on the host; no kernel is ever launched from this file.)"""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "patternkv.h")
+LIB = os.path.join(ROOT, "paper_2510_05176_amd", "libpatternkv.so")
+
+pytestmark = pytest.mark.skipif(not os.path.exists(LIB), reason="libpatternkv.so not built")
+
+
+@pytest.fixture(scope="module")
+def pk():
+    from paper_2510_05176_amd import patternkv
+    return patternkv
+
+
+def test_exports_every_declared_symbol(pk):
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    names = set(re.findall(r"\b(pk_[a-z_]+)\s*\(", src))
+    assert {"pk_mine_patterns", "pk_quantize_append", "pk_decode_attention", "pk_dequantize", "pk_cache_layout",
+            "pk_workspace_bytes", "pk_status_string", "pk_abi_version"} <= names
+    lib = C.CDLL(LIB)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert pk.pk_abi_version() == 1
+
+
+def test_status_strings(pk):
+    seen = {pk.pk_status_string(s) for s in range(9)}
+    assert len(seen) == 9 and "ok" in seen
+
+
+def test_layout_byte_counts(pk):
+    cfg = pk.Config(n_seq=2, n_kv_heads=8, n_q_heads=32, n_patterns=64, bits=2, group=64, recent=128, flush=128,
+                    t_capacity=8192)
+    lay = pk.pk_cache_layout(cfg)
+    N = 16
+    assert lay["k_codes"] == lay["v_codes"] == N * 8192 * 128 * 2 // 8
+    assert lay["k_scale"] == lay["k_zero"] == N * (8192 // 64) * 128 * 2
+    assert lay["v_scale"] == lay["v_zero"] == N * 8192 * 2 * 2
+    assert lay["k_idx"] == lay["v_idx"] == N * 8192
+    assert lay["tail_k"] == lay["tail_v"] == N * 256 * 128 * 2
+    assert lay["align"] == 16
+    # packed bytes per token and KV head (K+V, with parameters and index): 82 B at 2 bits, group 64
+    per_tok = sum(lay[n] for n in ("k_codes", "k_scale", "k_zero", "k_idx", "v_codes", "v_scale", "v_zero", "v_idx")) / (N * 8192)
+    assert per_tok == 82
+    cfg4 = pk.Config(n_seq=1, n_kv_heads=1, n_q_heads=1, bits=4, group=64, flush=64, t_capacity=64)
+    lay4 = pk.pk_cache_layout(cfg4)
+    assert sum(lay4[n] for n in ("k_codes", "k_scale", "k_zero", "k_idx", "v_codes", "v_scale", "v_zero", "v_idx")) / 64 == 146
+
+
+@pytest.mark.parametrize("field,value,status", [
+    ("head_dim", 64, 2), ("bits", 3, 2), ("group", 48, 2), ("n_patterns", 257, 2), ("n_patterns", 0, 1),
+    ("n_q_heads", 5, 3), ("n_q_heads", 36, 2), ("flush", 96, 3), ("t_capacity", 100, 3), ("metric", 7, 1),
+    ("recent", -1, 1), ("n_seq", 0, 1), ("n_seq", 70000, 2),
+])
+def test_bad_config_is_refused(pk, field, value, status):
+    kw = dict(n_seq=1, n_kv_heads=4, n_q_heads=4, n_patterns=16, bits=2, group=64, recent=0, flush=64, t_capacity=1024)
+    kw[field] = value
+    with pytest.raises(pk.PkError) as e:
+        pk.pk_cache_layout(pk.Config(**kw))
+    assert e.value.status == status
+    assert pk.pk_workspace_bytes(pk.Config(**kw), pk.OP_DECODE, 1024) == 0
+
+
+def test_workspace_sizes_are_monotone(pk):
+    cfg = pk.Config(n_seq=4, n_kv_heads=8, n_q_heads=32, n_patterns=64, flush=64, t_capacity=1 << 20)
+    prev = 0
+    for t in [0, 1, 255, 256, 1000, 4096, 8192, 70000, 1 << 20]:
+        w = pk.pk_workspace_bytes(cfg, pk.OP_DECODE, t, 0)
+        assert w >= prev and w > 0
+        assert pk.pk_workspace_bytes(cfg, pk.OP_DECODE, t, 4096) >= w
+        prev = w
+    prev = 0
+    for t in [64, 1000, 8192, 131072]:
+        w = pk.pk_workspace_bytes(cfg, pk.OP_MINE, t, 16)
+        assert w > prev
+        prev = w
+    assert pk.pk_workspace_bytes(cfg, pk.OP_APPEND, 128) == 0
+
+
+def _fake_cache(pk, base=0x1000):
+    return pk._Cache(*[base + 0x100 * i for i in range(10)])
+
+
+def test_append_argument_errors_before_launch(pk):
+    lib = pk._lib
+    cfg = pk.Config(n_seq=1, n_kv_heads=2, n_q_heads=2, n_patterns=8, flush=64, group=64, t_capacity=128).c()
+    cache, state = _fake_cache(pk), pk._State(0, 0, 0)
+    good = C.c_void_p(0x2000)
+    call = lambda **kw: lib.pk_quantize_append(
+        C.byref(kw.get("cfg", cfg)), C.byref(kw.get("cache", cache)), C.byref(kw.get("state", state)),
+        kw.get("k", good), kw.get("v", good), kw.get("n", 64), kw.get("stride", 0), kw.get("pk", good),
+        kw.get("pv", good), None, 0, None)
+    assert call(n=-1) == 1
+    assert call(k=None) == 1
+    assert call(k=C.c_void_p(0x2008)) == 4                      # misaligned
+    assert call(cache=pk._Cache(*([0x1000] * 9 + [0]))) == 1     # a NULL cache array
+    assert call(cache=pk._Cache(*([0x1000] * 9 + [0x1004]))) == 4
+    assert call(state=pk._State(32, 0, 0)) == 6                  # t_quant not a multiple of flush
+    assert call(state=pk._State(0, 64, 0)) == 6                  # tail longer than the ring allows
+    assert call(state=pk._State(0, 0, 64)) == 6
+    assert call(n=64, stride=100) == 3                           # stream stride shorter than the rows
+    assert call(state=pk._State(128, 0, 0), n=64) == 5           # would exceed t_capacity
+    st = pk._State(64, 0, 0)
+    assert call(state=st, n=200) == 5 and (st.t_quant, st.t_tail, st.tail_start) == (64, 0, 0)   # state untouched
+    assert call(n=0) == 0                                        # zero-length append is a no-op
+
+
+def test_decode_and_mine_argument_errors_before_launch(pk):
+    lib = pk._lib
+    cfg = pk.Config(n_seq=1, n_kv_heads=2, n_q_heads=8, n_patterns=8, flush=64, group=64, t_capacity=128)
+    c, cache, state = cfg.c(), _fake_cache(pk), pk._State(64, 3, 0)
+    good = C.c_void_p(0x2000)
+
+    def dec(**kw):
+        return lib.pk_decode_attention(C.byref(c), C.byref(cache), C.byref(kw.get("state", state)),
+                                       kw.get("pcfg"), kw.get("pcache"), kw.get("pstate"), kw.get("q", good),
+                                       C.c_float(0.1), good, good, kw.get("out", good), None, kw.get("ws", good),
+                                       kw.get("wsb", 0), None)
+    assert dec(q=None) == 1
+    assert dec(out=C.c_void_p(0x2004)) == 4
+    assert dec(wsb=0) == 7                                       # workspace too small
+    assert dec(ws=None, wsb=1 << 30) == 7
+    pc = pk.Config(n_seq=1, n_kv_heads=2, n_q_heads=8, n_patterns=8, flush=64, group=32, t_capacity=128).c()
+    assert dec(pcfg=C.byref(pc)) == 1                            # prefix arguments must come together
+    pcache, pstate = _fake_cache(pk, 0x9000), pk._State(64, 0, 0)
+    assert dec(pcfg=C.byref(pc), pcache=C.byref(pcache), pstate=C.byref(pstate), wsb=1 << 30) == 3   # group differs
+    assert dec(state=pk._State(64, 64, 0)) == 6
+
+    def mine(**kw):
+        return lib.pk_mine_patterns(C.byref(c), kw.get("x", good), kw.get("stride", 64 * 128), kw.get("S", 2),
+                                    kw.get("T", 64), kw.get("iters", 3), 0, kw.get("pat", good), None, None,
+                                    kw.get("ws", good), kw.get("wsb", 0), None)
+    assert mine(x=None) == 1
+    assert mine(T=4) == 3                                        # fewer vectors than patterns
+    assert mine(stride=100) == 3
+    assert mine(pat=C.c_void_p(0x2002)) == 4
+    assert mine(wsb=16) == 7
+    assert mine(iters=-1) == 1
+
+    def deq(**kw):
+        return lib.pk_dequantize(C.byref(c), C.byref(cache), C.byref(state), good, good, kw.get("t0", 0),
+                                 kw.get("t1", 64), kw.get("k", good), good, None)
+    assert deq(t1=65) == 3 and deq(t0=10, t1=5) == 3 and deq(k=C.c_void_p(0x2004)) == 4

@@ -1,0 +1,405 @@
+"""GPU-vs-oracle parity of the three hot-path calls, through the C ABI, on seeded synthetic KV.
+
+Bars (the benchmark contract's): pattern indices bit-exact except where the oracle's top-2 distance gap
+is < 1e-4 relative; given equal assignments, codes / packed bytes / fp16 scale and zero bit-exact;
+reconstructed KV within 1e-3 absolute; attention outputs within 2e-3 relative L2.
+"""
+import numpy as np
+import pytest
+
+from paper_2510_05176_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def pk():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2510_05176_amd import patternkv
+    return patternkv
+
+
+def dev(a_f16):
+    return torch.from_numpy(np.ascontiguousarray(a_f16).view(np.int16)).cuda().view(torch.float16)
+
+
+def host_u16(t):
+    return t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+
+
+CACHE_ARRAYS = ("k_codes", "k_scale", "k_zero", "k_idx", "v_codes", "v_scale", "v_zero", "v_idx", "tail_k", "tail_v")
+
+
+def gpu_arrays(gc, ocache):
+    """GPU cache arrays as numpy arrays shaped like the oracle's."""
+    out = {}
+    for n in CACHE_ARRAYS:
+        ref = getattr(ocache, n)
+        raw = gc.array(n).cpu().numpy()
+        out[n] = raw.view(ref.dtype).reshape(ref.shape)
+    return out
+
+
+def upload(gc, ocache):
+    """Copy the oracle's cache into the GPU cache (to test decode on identical inputs)."""
+    for n in CACHE_ARRAYS:
+        raw = np.ascontiguousarray(getattr(ocache, n)).view(np.uint8).reshape(-1)
+        gc.buf[n][: raw.size] = torch.from_numpy(raw.copy()).cuda()
+    gc.state.t_quant, gc.state.t_tail, gc.state.tail_start = ocache.t_quant, ocache.t_tail, ocache.tail_start
+
+
+def make_case(oracle, pk, seed, *, n_seq=1, hkv=2, hq=2, T=320, P=16, bits=2, G=64, R=0, F=None, metric=0,
+              seqs_per_set=0, n_clusters=8, cap=None, mine_iters=3):
+    F = G if F is None else F
+    cap = cap if cap is not None else -(-T // F) * F
+    kw = dict(n_seq=n_seq, n_kv_heads=hkv, n_q_heads=hq, head_dim=128, n_patterns=P, seqs_per_set=seqs_per_set,
+              bits=bits, group=G, recent=R, flush=F, t_capacity=cap, metric=metric)
+    spec = synth.KVSpec(1, n_seq, hkv, hq, T, 128, n_clusters)
+    K, V = synth.make_kv(seed, spec)
+    ocfg, gcfg = oracle.Config(**kw), pk.Config(**kw)
+    # patterns: oracle-mined on the first sequences of each set (inputs to both sides)
+    set_of = ocfg.set_of()
+    first_stream = [int(np.flatnonzero(set_of == s)[0]) for s in range(ocfg.n_sets)]
+    Kf, Vf = K.reshape(-1, T, 128), V.reshape(-1, T, 128)
+    Mk, _, _, _ = oracle.mine(Kf[first_stream].view(np.uint16), P, mine_iters)
+    Mv, _, _, _ = oracle.mine(Vf[first_stream].view(np.uint16), P, mine_iters)
+    return kw, ocfg, gcfg, K, V, Mk, Mv
+
+
+def run_appends(oracle, pk, ocfg, gcfg, K, V, Mk, Mv, pieces):
+    oc, gc = oracle.Cache(ocfg), pk.Cache(gcfg)
+    Kd, Vd = dev(K), dev(V)
+    Mkd, Mvd = dev(Mk.view(np.float16)), dev(Mv.view(np.float16))
+    pos = 0
+    for n in pieces:
+        oc.append(K[:, :, pos:pos + n].view(np.uint16), V[:, :, pos:pos + n].view(np.uint16), Mk, Mv)
+        pk.pk_quantize_append(gcfg, gc, Kd[:, :, pos:pos + n], Vd[:, :, pos:pos + n], Mkd, Mvd)
+        pos += n
+        assert (gc.t_quant, gc.t_tail, gc.tail_start) == (oc.t_quant, oc.t_tail, oc.tail_start)
+    torch.cuda.synchronize()
+    return oc, gc, Mkd, Mvd
+
+
+def compare_caches(oracle, oc, gc, metric):
+    """Returns the number of tokens whose assignment differs (all inside the exemption band)."""
+    cfg = oc.cfg
+    N, d, b, G, tq = cfg.n_streams, cfg.head_dim, cfg.bits, cfg.group, oc.t_quant
+    g = gpu_arrays(gc, oc)
+    n_diff = 0
+    for side in "kv":
+        oi, gi = getattr(oc, side + "_idx")[:, :tq], g[side + "_idx"][:, :tq]
+        diff = oi != gi
+        if diff.any():
+            best, second = getattr(oc, side + "_best")[:, :tq], getattr(oc, side + "_second")[:, :tq]
+            gap = (second - best) / np.maximum(second, 1e-30)
+            assert metric == 0, "min-max selection uses exact binary32 operations on both sides"
+            assert np.all(gap[diff] < 1e-4), f"{side}: assignment differs outside the near-tie band, gap {gap[diff].max()}"
+            n_diff += int(diff.sum())
+        same = ~diff
+        if side == "k":
+            grp_same = same.reshape(N, tq // G, G).all(axis=2)
+            assert np.array_equal(g["k_scale"][:, :tq // G][grp_same], oc.k_scale[:, :tq // G][grp_same])
+            assert np.array_equal(g["k_zero"][:, :tq // G][grp_same], oc.k_zero[:, :tq // G][grp_same])
+            tok_same = np.repeat(grp_same, G, axis=1)
+            assert np.array_equal(g["k_codes"][:, :tq][tok_same], oc.k_codes[:, :tq][tok_same])
+        else:
+            assert np.array_equal(g["v_scale"][:, :tq][same], oc.v_scale[:, :tq][same])
+            assert np.array_equal(g["v_zero"][:, :tq][same], oc.v_zero[:, :tq][same])
+            bpt = d * b // 8
+            if not diff.any():
+                assert np.array_equal(g["v_codes"][:, :tq * bpt], oc.v_codes[:, :tq * bpt])   # packed bytes
+            for s in range(N):
+                cg = oracle.unpack_v(g["v_codes"][s, :tq * bpt], tq, d, b)
+                co = oracle.unpack_v(oc.v_codes[s, :tq * bpt], tq, d, b)
+                assert np.array_equal(cg[same[s]], co[same[s]])
+    # tails (logical order)
+    ring = cfg.recent + cfg.flush
+    slots = (oc.tail_start + np.arange(oc.t_tail)) % ring
+    assert np.array_equal(g["tail_k"][:, slots], oc.tail("k"))
+    assert np.array_equal(g["tail_v"][:, slots], oc.tail("v"))
+    return n_diff
+
+
+def rel_l2(a, b):
+    return float(np.linalg.norm(a.astype(np.float64) - b.astype(np.float64)) / max(np.linalg.norm(b.astype(np.float64)), 1e-30))
+
+
+# ------------------------------------------------------------------------------ quantize-append
+
+@pytest.mark.parametrize("bits,G,P,metric", [
+    (2, 64, 16, 0), (4, 32, 16, 0), (2, 128, 64, 0), (4, 64, 33, 0), (2, 32, 1, 0), (2, 64, 256, 0),
+    (2, 64, 16, 1), (4, 128, 40, 1), (2, 32, 7, 1),
+])
+def test_quantize_append_parity(oracle, pk, bits, G, P, metric):
+    kw, ocfg, gcfg, K, V, Mk, Mv = make_case(oracle, pk, 100 + bits + G + P, T=384 + 17, P=P, bits=bits, G=G,
+                                            metric=metric, n_seq=2, hkv=2, hq=2, n_clusters=max(4, min(P, 24)))
+    oc, gc, Mkd, Mvd = run_appends(oracle, pk, ocfg, gcfg, K, V, Mk, Mv, [K.shape[2]])
+    assert oc.t_quant == (401 // G) * G and oc.t_tail == 401 - oc.t_quant
+    n_diff = compare_caches(oracle, oc, gc, metric)
+    assert n_diff <= 0.002 * oc.t_quant * ocfg.n_streams * 2 + 2
+    # reconstruction (1e-3 absolute on tokens with equal assignment; the arithmetic is in fact identical)
+    kg, vg = pk.pk_dequantize(gcfg, gc, Mkd, Mvd)
+    ko, vo = oc.dequantize(Mk, Mv)
+    g = gpu_arrays(gc, oc)
+    tq = oc.t_quant
+    same_k = np.repeat((g["k_idx"][:, :tq] == oc.k_idx[:, :tq]).reshape(ocfg.n_streams, tq // G, G).all(2), G, axis=1)
+    same_v = g["v_idx"][:, :tq] == oc.v_idx[:, :tq]
+    assert np.abs(kg.cpu().numpy() - ko)[same_k].max() <= 1e-3
+    assert np.abs(vg.cpu().numpy() - vo)[same_v].max() <= 1e-3
+    if n_diff == 0:
+        assert np.array_equal(kg.cpu().numpy(), ko) and np.array_equal(vg.cpu().numpy(), vo)
+
+
+def test_streaming_appends_with_recent_window(oracle, pk):
+    kw, ocfg, gcfg, K, V, Mk, Mv = make_case(oracle, pk, 7, T=700, P=16, bits=2, G=32, R=48, F=64, n_seq=3, hkv=2,
+                                            hq=4, seqs_per_set=1, cap=704)
+    pieces = [1, 1, 5, 40, 64, 100, 1, 300, 111, 77]
+    assert sum(pieces) == 700
+    oc, gc, Mkd, Mvd = run_appends(oracle, pk, ocfg, gcfg, K, V, Mk, Mv, pieces)
+    assert oc.t_quant == 640 and oc.t_tail == 60
+    compare_caches(oracle, oc, gc, 0)
+    # the same tokens in one call give the same cache
+    oc1, gc1, _, _ = run_appends(oracle, pk, ocfg, gcfg, K, V, Mk, Mv, [700])
+    for n in ("k_codes", "k_scale", "k_zero", "k_idx", "v_codes", "v_scale", "v_zero", "v_idx"):
+        assert torch.equal(gc.array(n), gc1.array(n)), n
+
+
+def test_zero_residual_and_flat_groups(oracle, pk):
+    # vectors that are exact copies of patterns: residual 0, scale 0, codes 0, exact reconstruction
+    rng = np.random.default_rng(5)
+    M = rng.standard_normal((2, 8, 128)).astype(np.float16)
+    pick = rng.integers(0, 8, (1, 2, 128))
+    K = np.stack([M[h][pick[0, h]] for h in range(2)])[None]
+    V = K[:, ::-1].copy()
+    kw = dict(n_seq=1, n_kv_heads=2, n_q_heads=2, head_dim=128, n_patterns=8, seqs_per_set=0, bits=2, group=64,
+              recent=0, flush=64, t_capacity=128, metric=0)
+    ocfg, gcfg = oracle.Config(**kw), pk.Config(**kw)
+    Mv = M[::-1].copy()
+    oc, gc, Mkd, Mvd = run_appends(oracle, pk, ocfg, gcfg, K, V, M.view(np.uint16), Mv.view(np.uint16), [128])
+    assert compare_caches(oracle, oc, gc, 0) == 0
+    g = gpu_arrays(gc, oc)
+    assert not g["k_codes"].any() and not g["v_codes"].any() and not g["k_scale"].any() and not g["v_scale"].any()
+    kg, vg = pk.pk_dequantize(gcfg, gc, Mkd, Mvd)
+    assert np.array_equal(kg.cpu().numpy(), K.reshape(2, 128, 128).astype(np.float32))
+    assert np.array_equal(vg.cpu().numpy(), V.reshape(2, 128, 128).astype(np.float32))
+
+
+def test_append_is_reproducible_bit_for_bit(oracle, pk):
+    kw, ocfg, gcfg, K, V, Mk, Mv = make_case(oracle, pk, 9, T=512, P=32, bits=2, G=64, n_seq=2, hkv=4, hq=4)
+    _, g1, _, _ = run_appends(oracle, pk, ocfg, gcfg, K, V, Mk, Mv, [512])
+    _, g2, _, _ = run_appends(oracle, pk, ocfg, gcfg, K, V, Mk, Mv, [512])
+    for n in CACHE_ARRAYS:
+        assert torch.equal(g1.array(n), g2.array(n)), n
+
+
+# ------------------------------------------------------------------------------ decode attention
+
+@pytest.mark.parametrize("hkv,hq,bits,G,P,R,T", [
+    (2, 2, 2, 64, 16, 0, 401),        # r = 1, ragged tail
+    (2, 8, 2, 64, 64, 128, 1500),     # r = 4, recent window, several tiles
+    (1, 7, 2, 128, 40, 0, 1100),      # r = 7
+    (1, 8, 4, 32, 16, 32, 700),       # r = 8, 4-bit
+    (2, 8, 4, 64, 64, 0, 640),        # 4-bit, r = 4, empty tail
+])
+def test_decode_attention_parity(oracle, pk, hkv, hq, bits, G, P, R, T):
+    kw, ocfg, gcfg, K, V, Mk, Mv = make_case(oracle, pk, 31 + hq + T, T=T, P=P, bits=bits, G=G, R=R, F=G,
+                                            n_seq=2, hkv=hkv, hq=hq, n_clusters=min(P, 16))
+    oc, gc, Mkd, Mvd = run_appends(oracle, pk, ocfg, gcfg, K, V, Mk, Mv, [T])
+    q = synth.make_queries(3, 2, hq, 128)
+    scale = 128 ** -0.5
+    want, want_lse = oracle.decode_attention(oc, q.view(np.uint16), Mk, Mv, scale)
+    lse = torch.empty((2, hq), dtype=torch.float32, device="cuda")
+    # (a) end to end: GPU-built cache
+    got = pk.pk_decode_attention(gcfg, gc, dev(q), scale, Mkd, Mvd, lse=lse).cpu().numpy()
+    assert rel_l2(got, want) <= 2e-3
+    assert np.abs(lse.cpu().numpy() - want_lse).max() <= 2e-3
+    # (b) decode alone: the oracle's cache uploaded, so both sides read identical bytes
+    gc2 = pk.Cache(gcfg)
+    upload(gc2, oc)
+    got2 = pk.pk_decode_attention(gcfg, gc2, dev(q), scale, Mkd, Mvd).cpu().numpy()
+    assert rel_l2(got2, want) <= 2e-3
+    # reproducible
+    got3 = pk.pk_decode_attention(gcfg, gc2, dev(q), scale, Mkd, Mvd).cpu().numpy()
+    assert np.allclose(got2, got3, rtol=1e-5, atol=1e-6)
+
+
+def test_decode_tail_only_and_empty_context(oracle, pk):
+    kw, ocfg, gcfg, K, V, Mk, Mv = make_case(oracle, pk, 41, T=100, P=8, bits=2, G=64, R=64, F=64, n_seq=2, hkv=2,
+                                            hq=8, cap=128)
+    oc, gc, Mkd, Mvd = run_appends(oracle, pk, ocfg, gcfg, K, V, Mk, Mv, [100])
+    assert oc.t_quant == 0 and oc.t_tail == 100
+    q = synth.make_queries(4, 2, 8, 128)
+    want, _ = oracle.decode_attention(oc, q.view(np.uint16), Mk, Mv, 128 ** -0.5)
+    got = pk.pk_decode_attention(gcfg, gc, dev(q), 128 ** -0.5, Mkd, Mvd).cpu().numpy()
+    assert rel_l2(got, want) <= 2e-3
+    # plain fp16 attention over the window
+    Kd, Vd, Qd = K.astype(np.float64), V.astype(np.float64), q.astype(np.float64)
+    for s in range(2):
+        for h in range(8):
+            sc = Kd[s, h // 4] @ Qd[s, h] * 128 ** -0.5
+            p = np.exp(sc - sc.max()); p /= p.sum()
+            assert np.allclose(got[s, h], p @ Vd[s, h // 4], rtol=2e-3, atol=2e-4)
+    empty = pk.Cache(gcfg)
+    lse = torch.zeros((2, 8), dtype=torch.float32, device="cuda")
+    out = pk.pk_decode_attention(gcfg, empty, dev(q), 128 ** -0.5, Mkd, Mvd, lse=lse)
+    assert not out.any() and torch.isinf(lse).all()
+
+
+def test_decode_with_shared_prefix(oracle, pk):
+    # a shared prompt cache (n_seq = 1) in front of 3 sequences' own caches, same pattern tables
+    P, G, bits, hkv, hq = 32, 32, 2, 2, 8
+    own_kw = dict(n_seq=3, n_kv_heads=hkv, n_q_heads=hq, head_dim=128, n_patterns=P, seqs_per_set=0, bits=bits,
+                  group=G, recent=0, flush=128, t_capacity=1024, metric=0)
+    pre_kw = dict(own_kw, n_seq=1, flush=64, recent=16, t_capacity=512)
+    spec = synth.KVSpec(1, 3, hkv, hq, 900, 128, 12, drift_sigma=0.05)
+    K, V = synth.make_kv(77, spec)
+    Kp, Vp = synth.make_kv(78, synth.KVSpec(1, 1, hkv, hq, 500, 128, 12))
+    Mk, _, _, _ = oracle.mine(Kp[0].view(np.uint16), P, 4)
+    Mv, _, _, _ = oracle.mine(Vp[0].view(np.uint16), P, 4)
+    oo, go, Mkd, Mvd = run_appends(oracle, pk, oracle.Config(**own_kw), pk.Config(**own_kw), K, V, Mk, Mv, [700, 200])
+    op, gp, _, _ = run_appends(oracle, pk, oracle.Config(**pre_kw), pk.Config(**pre_kw), Kp, Vp, Mk, Mv, [500])
+    assert (op.t_quant, op.t_tail, oo.t_quant, oo.t_tail) == (448, 52, 896, 4)
+    q = synth.make_queries(5, 3, hq, 128)
+    want, want_lse = oracle.decode_attention(oo, q.view(np.uint16), Mk, Mv, 128 ** -0.5, prefix=op,
+                                             prefix_patterns_k=Mk, prefix_patterns_v=Mv)
+    lse = torch.empty((3, hq), dtype=torch.float32, device="cuda")
+    got = pk.pk_decode_attention(pk.Config(**own_kw), go, dev(q), 128 ** -0.5, Mkd, Mvd, lse=lse, prefix=gp).cpu().numpy()
+    assert rel_l2(got, want) <= 2e-3
+    assert np.abs(lse.cpu().numpy() - want_lse).max() <= 2e-3
+
+
+# ------------------------------------------------------------------------------ pattern mining
+
+def _ulp_diff(a_u16, b_u16):
+    def key(u):
+        u = u.astype(np.int32)
+        return np.where(u & 0x8000, -(u & 0x7fff), u)
+    return np.abs(key(a_u16) - key(b_u16))
+
+
+@pytest.mark.parametrize("T,P,n_c", [(1000, 16, 16), (4096 + 37, 64, 32), (640, 200, 64)])
+def test_mining_parity_per_iteration(oracle, pk, T, P, n_c):
+    spec = synth.KVSpec(1, 1, 3, 3, T, 128, n_c)
+    K, V = synth.make_kv(50 + P, spec)
+    x = np.concatenate([K[0], V[0, :1]])                      # 4 sets: 3 K heads and one V head
+    xd = dev(x)
+    gcfg = pk.Config(n_patterns=P)
+    cur = x[:, :P].copy().view(np.uint16)
+    for it in range(4):
+        Mo, ao, Jo, cnt = oracle.mine(x.view(np.uint16), P, 1, init=cur)
+        pat = dev(cur.view(np.float16)).clone()
+        asg = torch.empty((4, T), dtype=torch.int32, device="cuda")
+        J = torch.empty((4, 1), dtype=torch.float32, device="cuda")
+        pk.pk_mine_patterns(gcfg, xd, 1, patterns=pat, init_given=True, assign=asg, inertia=J)
+        ag, Mg = asg.cpu().numpy(), host_u16(pat)
+        for s in range(4):
+            diff = ag[s] != ao[s]
+            if diff.any():
+                _, best, second = oracle.assign(x[s].view(np.uint16), cur[s], 0)
+                gap = (second - best) / np.maximum(second, 1e-30)
+                assert np.all(gap[diff] < 1e-4)
+            clean = np.ones(P, bool)
+            clean[np.unique(np.concatenate([ag[s][diff], ao[s][diff]]))] = False   # clusters with equal member sets
+            assert _ulp_diff(Mg[s][clean], Mo[s][clean]).max() <= 1
+            assert np.abs(Mg[s].view(np.float16).astype(np.float32) - Mo[s].view(np.float16).astype(np.float32)).max() < 2e-2
+            empty = cnt[s] == 0
+            assert np.array_equal(Mg[s][empty & clean], cur[s][empty & clean])      # empty clusters keep their centroid
+        assert np.allclose(J.cpu().numpy()[:, 0], Jo[:, 0], rtol=1e-4)
+        cur = Mo                                                                    # both continue from the oracle's centroids
+
+
+def test_mining_end_to_end_and_reproducible(oracle, pk):
+    spec = synth.KVSpec(1, 1, 2, 2, 3000, 128, 24)
+    K, V = synth.make_kv(61, spec)
+    x = np.concatenate([K[0], V[0]])
+    P, iters = 32, 10
+    Mo, ao, Jo, _ = oracle.mine(x.view(np.uint16), P, iters)
+    gcfg = pk.Config(n_patterns=P)
+    J = torch.empty((4, iters), dtype=torch.float32, device="cuda")
+    asg = torch.empty((4, 3000), dtype=torch.int32, device="cuda")
+    Mg = pk.pk_mine_patterns(gcfg, dev(x), iters, assign=asg, inertia=J)
+    Jg = J.cpu().numpy()
+    assert np.allclose(Jg[:, -1], Jo[:, -1], rtol=1e-3)
+    assert np.all(Jg[:, 1:] <= Jg[:, :-1] * (1 + 1e-4))              # Lloyd never increases the objective (Sec. 3.1)
+    # first assignment step starts from the first P vectors
+    assert np.allclose(Jg[:, 0], Jo[:, 0], rtol=1e-4)
+    J2 = torch.empty_like(J)
+    Mg2 = pk.pk_mine_patterns(gcfg, dev(x), iters, inertia=J2)
+    assert torch.equal(Mg, Mg2) and torch.equal(J, J2)                  # fixed summation order
+    # the mined patterns serve quantization as well as the oracle's: compare objective on a fresh assignment
+    for s in range(4):
+        _, bo, _ = oracle.assign(x[s].view(np.uint16), Mo[s], 0)
+        _, bg, _ = oracle.assign(x[s].view(np.uint16), host_u16(Mg)[s], 0)
+        assert abs(bg.sum() - bo.sum()) <= 1e-3 * bo.sum()
+
+
+# ------------------------------------------------------------------------------ contract configs 1 and 2
+
+def test_config1_smoke_full_path(oracle, pk):
+    """Config 1: 1 head, T=1024, P=16 from 10 Lloyd iterations, 4-bit, group 32; whole path on the GPU."""
+    spec = synth.SPECS["cfg1"]
+    K, V = synth.make_kv(0, spec)
+    kw = dict(n_seq=1, n_kv_heads=1, n_q_heads=1, head_dim=128, n_patterns=16, seqs_per_set=0, bits=4, group=32,
+              recent=0, flush=32, t_capacity=1024, metric=0)
+    ocfg, gcfg = oracle.Config(**kw), pk.Config(**kw)
+    Mk_o, _, _, _ = oracle.mine(K[0].view(np.uint16), 16, 10)
+    Mv_o, _, _, _ = oracle.mine(V[0].view(np.uint16), 16, 10)
+    Mk_g = pk.pk_mine_patterns(gcfg, dev(K[0]), 10)
+    Mv_g = pk.pk_mine_patterns(gcfg, dev(V[0]), 10)
+    q = synth.make_queries(0, 1, 1, 128)
+    # GPU path end to end with its own patterns
+    gc = pk.Cache(gcfg)
+    pk.pk_quantize_append(gcfg, gc, dev(K), dev(V), Mk_g, Mv_g)
+    got = pk.pk_decode_attention(gcfg, gc, dev(q), 128 ** -0.5, Mk_g, Mv_g).cpu().numpy()
+    # oracle end to end with its own patterns
+    oc = oracle.Cache(ocfg)
+    oc.append(K.view(np.uint16), V.view(np.uint16), Mk_o, Mv_o)
+    want, _ = oracle.decode_attention(oc, q.view(np.uint16), Mk_o, Mv_o, 128 ** -0.5)
+    assert rel_l2(got, want) <= 2e-3
+    # and stage by stage on shared patterns
+    oc2, gc2, Mkd, Mvd = run_appends(oracle, pk, ocfg, gcfg, K, V, Mk_o, Mv_o, [1024])
+    compare_caches(oracle, oc2, gc2, 0)
+
+
+_CFG2 = {}
+
+
+def _cfg2_inputs(oracle):
+    if not _CFG2:
+        K, V = synth.make_kv(2, synth.SPECS["cfg2"])
+        Mk, _, Jk, _ = oracle.mine(K[0].view(np.uint16), 64, 10)
+        Mv, _, _, _ = oracle.mine(V[0].view(np.uint16), 64, 10)
+        _CFG2.update(K=K, V=V, Mk=Mk, Mv=Mv, Jk=Jk)
+    return _CFG2
+
+
+@pytest.mark.parametrize("bits", [2, 4])
+def test_config2_llama_shaped_layer(oracle, pk, bits):
+    """Config 2: T=8192, 8 KV heads, 32 query heads, P=64 from 10 Lloyd iterations, group 64, at full size."""
+    c = _cfg2_inputs(oracle)
+    K, V, Mk, Mv = c["K"], c["V"], c["Mk"], c["Mv"]
+    kw = dict(n_seq=1, n_kv_heads=8, n_q_heads=32, head_dim=128, n_patterns=64, seqs_per_set=0, bits=bits, group=64,
+              recent=0, flush=64, t_capacity=8192, metric=0)
+    ocfg, gcfg = oracle.Config(**kw), pk.Config(**kw)
+    oc, gc, Mkd, Mvd = run_appends(oracle, pk, ocfg, gcfg, K, V, Mk, Mv, [8192])
+    n_diff = compare_caches(oracle, oc, gc, 0)
+    assert n_diff <= 40
+    q = synth.make_queries(2, 1, 32, 128)
+    want, _ = oracle.decode_attention(oc, q.view(np.uint16), Mk, Mv, 128 ** -0.5)
+    got = pk.pk_decode_attention(gcfg, gc, dev(q), 128 ** -0.5, Mkd, Mvd).cpu().numpy()
+    assert rel_l2(got, want) <= 2e-3
+    if bits == 2:
+        # mining at full size: objective after 10 iterations against the oracle's run from the same start
+        J = torch.empty((8, 10), dtype=torch.float32, device="cuda")
+        Mg = pk.pk_mine_patterns(gcfg, dev(K[0]), 10, inertia=J)
+        assert np.allclose(J.cpu().numpy()[:, 0], c["Jk"][:, 0], rtol=1e-4)
+        assert np.allclose(J.cpu().numpy()[:, -1], c["Jk"][:, -1], rtol=1e-3)
+        # whole path on the GPU (its own patterns) against the whole path of the oracle
+        Mvg = pk.pk_mine_patterns(gcfg, dev(V[0]), 10)
+        gc2 = pk.Cache(gcfg)
+        pk.pk_quantize_append(gcfg, gc2, dev(K), dev(V), Mg, Mvg)
+        got2 = pk.pk_decode_attention(gcfg, gc2, dev(q), 128 ** -0.5, Mg, Mvg).cpu().numpy()
+        assert rel_l2(got2, want) <= 2e-3

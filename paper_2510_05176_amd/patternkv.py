@@ -200,12 +200,25 @@ def pk_quantize_append(cfg: Config, cache: Cache, k_new: torch.Tensor, v_new: to
     """k_new, v_new [n_seq, n_kv_heads, n_new, d] fp16 (token rows contiguous, streams may be strided)."""
     assert k_new.dtype == torch.float16 and v_new.dtype == torch.float16 and k_new.shape == v_new.shape
     n_seq, hkv, n_new, d = k_new.shape
-    for t in (k_new, v_new):
-        assert t.stride(3) == 1 and t.stride(2) == d and t.stride(0) == hkv * t.stride(1)
-    assert k_new.stride(1) == v_new.stride(1)
+
+    def stream_stride(t):
+        # elements between consecutive (sequence, head) streams; strides of size-1 dimensions carry no meaning
+        assert n_new <= 1 or t.stride(2) == d
+        assert d == 1 or t.stride(3) == 1
+        if hkv > 1:
+            ss = t.stride(1)
+            assert n_seq == 1 or t.stride(0) == hkv * ss
+        elif n_seq > 1:
+            ss = t.stride(0)
+        else:
+            ss = n_new * d
+        return ss
+
+    ss = stream_stride(k_new)
+    assert stream_stride(v_new) == ss
     cc, kc = cfg.c(), cache.c()
     st = _lib.pk_quantize_append(C.byref(cc), C.byref(kc), C.byref(cache.state), C.c_void_p(k_new.data_ptr()),
-                                 C.c_void_p(v_new.data_ptr()), n_new, k_new.stride(1), _ptr(patterns_k),
+                                 C.c_void_p(v_new.data_ptr()), n_new, ss, _ptr(patterns_k),
                                  _ptr(patterns_v), _ptr(workspace), 0 if workspace is None else workspace.numel(),
                                  _stream())
     _check(st, "pk_quantize_append")

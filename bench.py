@@ -1,0 +1,240 @@
+#!/usr/bin/env python3
+"""Benchmark of the PatternKV hot path on one MI355X.
+
+One "step" = one pass of the whole hot path over one batch of synthetic KV that is already resident
+in HBM: mine the K and V pattern tables (Lloyd iterations), quantize-append the whole context
+against them, run one decode-attention step over the packed cache for every query head.
+
+Prints ONE JSON line.  `value` is whole-path throughput (context tokens pushed through mining,
+quantize-append and decode per second); the per-stage figures the contract's metric names
+(quantize-append GB/s, decode-attention tokens/s, each as a fraction of the 8 TB/s HBM peak) are in
+`stages`.  `roofline` describes the stage kernel that takes the most time in a step; `stage_rooflines`
+has all three.  Per-stage durations come from HIP events recorded on the launch stream around each
+library call, with a cache flush (a 1 GiB fill, outside the events) before every timed call so that
+inputs come from HBM and not from the 256 MB Infinity Cache.
+
+Workloads (--workload): cfg2 (default; Llama-3-8B-shaped single layer, T=8192), cfg2x32 (the same for
+32 layers in one launch), cfg3 (32 layers x batch 16 x T=32768), cfg5 (T=131072, P=256).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np
+
+HBM_PEAK_GBPS = 8000.0
+MFMA_F16_PEAK_TFLOPS = 2500.0
+VALU_F32_PEAK_TFLOPS = 157.3
+
+WORKLOADS = {
+    # name: (spec key, layers, batch, P, iters, group, recent, flush, default bits)
+    "cfg2": dict(spec="cfg2", layers=1, batch=1, P=64, iters=10, group=64, recent=0, flush=64),
+    "cfg2x32": dict(spec="cfg2", layers=32, batch=1, P=64, iters=10, group=64, recent=0, flush=64),
+    "cfg3": dict(spec="cfg3", layers=32, batch=16, P=128, iters=10, group=64, recent=128, flush=128),
+    "cfg5": dict(spec="cfg5", layers=1, batch=1, P=256, iters=20, group=128, recent=0, flush=128),
+}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="cfg2", choices=sorted(WORKLOADS))
+    ap.add_argument("--bits", type=int, default=2, choices=[2, 4])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--seed", type=int, default=2)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus must be 1 (no sharding or collectives are part of it)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    from paper_2510_05176_amd import patternkv as pk
+    from paper_2510_05176_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = "cuda"
+    w = WORKLOADS[args.workload]
+    base = synth.SPECS[w["spec"]]
+    spec = synth.KVSpec(**{**base.__dict__, "n_layers": w["layers"], "batch": w["batch"]})
+    L, B, Hkv, Hq, T, d = w["layers"], w["batch"], spec.n_kv_heads, spec.n_q_heads, spec.T, spec.d
+    P, iters, G, R, F, bits = w["P"], w["iters"], w["group"], w["recent"], w["flush"], args.bits
+    n_seq = L * B
+    N = n_seq * Hkv
+    cap = (T - R) // F * F
+
+    # ---------------------------------------------------------------- inputs, resident in HBM
+    t_gen = time.time()
+    if n_seq == 1:
+        Kh, Vh = synth.make_kv(args.seed, spec)
+        K = torch.from_numpy(Kh.view(np.int16)).to(dev).view(torch.float16)
+        V = torch.from_numpy(Vh.view(np.int16)).to(dev).view(torch.float16)
+    else:
+        K = torch.empty((n_seq, Hkv, T, d), dtype=torch.float16, device=dev)
+        V = torch.empty_like(K)
+        one = synth.KVSpec(**{**spec.__dict__, "n_layers": 1})
+        for layer in range(L):
+            K[layer * B:(layer + 1) * B], V[layer * B:(layer + 1) * B] = synth.make_layer_device(args.seed, layer, one, dev)
+    q = torch.from_numpy(synth.make_queries(args.seed, n_seq, Hq, d).view(np.int16)).to(dev).view(torch.float16)
+    torch.cuda.synchronize()
+    t_gen = time.time() - t_gen
+
+    cfg = pk.Config(n_seq=n_seq, n_kv_heads=Hkv, n_q_heads=Hq, head_dim=d, n_patterns=P,
+                    seqs_per_set=(B if L > 1 else 0), bits=bits, group=G, recent=R, flush=F, t_capacity=cap,
+                    metric=pk.METRIC_L2)
+    n_sets = cfg.n_sets
+    cache = pk.Cache(cfg)
+    Mk = torch.empty((n_sets, P, d), dtype=torch.float16, device=dev)
+    Mv = torch.empty_like(Mk)
+    out = torch.empty((n_seq, Hq, d), dtype=torch.float32, device=dev)
+    ws_mine = torch.empty(max(pk.pk_workspace_bytes(cfg, pk.OP_MINE, T, Hkv), 16), dtype=torch.uint8, device=dev)
+    ws_dec = torch.empty(max(pk.pk_workspace_bytes(cfg, pk.OP_DECODE, T, 0), 16), dtype=torch.uint8, device=dev)
+    flush_buf = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    scale = d ** -0.5
+
+    def mine():
+        # one table per (layer, KV head), mined on the layer's first batch element
+        for layer in range(L):
+            s = layer * B
+            pk.pk_mine_patterns(cfg, K[s], iters, patterns=Mk[layer * Hkv:(layer + 1) * Hkv], workspace=ws_mine)
+            pk.pk_mine_patterns(cfg, V[s], iters, patterns=Mv[layer * Hkv:(layer + 1) * Hkv], workspace=ws_mine)
+
+    def quantize():
+        cache.state.t_quant = cache.state.t_tail = cache.state.tail_start = 0
+        pk.pk_quantize_append(cfg, cache, K, V, Mk, Mv)
+
+    def decode():
+        pk.pk_decode_attention(cfg, cache, q, scale, Mk, Mv, out=out, workspace=ws_dec)
+
+    stages = [("mine", mine), ("quantize_append", quantize), ("decode_attention", decode)]
+
+    def timed_pass(cold):
+        ms = {}
+        for name, fn in stages:
+            if cold:
+                flush_buf.fill_(1)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            e1.synchronize()
+            ms[name] = e0.elapsed_time(e1)
+        return ms
+
+    for _ in range(args.warmup):
+        for _, fn in stages:
+            fn()
+    torch.cuda.synchronize()
+    # whole steps, back to back
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        for _, fn in stages:
+            fn()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    # per-stage durations from HIP events, inputs evicted before every call
+    cold = [timed_pass(True) for _ in range(args.steps)]
+    stage_ms = {name: float(np.mean([c[name] for c in cold])) for name, _ in stages}
+    stage_ms_min = {name: float(np.min([c[name] for c in cold])) for name, _ in stages}
+    assert cache.t_quant == cap and cache.t_tail == T - cap
+
+    # ---------------------------------------------------------------- algorithmic bytes / flops
+    Gc = min(G, d)
+    k_tok = bits * d / 8 + 2 * 2 * d / G + 1          # K: codes + (s,z) amortised over the group + index
+    v_tok = bits * d / 8 + 2 * 2 * d / Gc + 1         # V: codes + (s,z) per channel group + index
+    packed_per_tok = k_tok + v_tok                    # 82 B at 2 bits, group 64
+    quant_bytes = N * (cap * (2 * d * 2 + packed_per_tok) + (T - cap) * 2 * d * 2 * 2)   # tail: read + write
+    dec_bytes = N * (cap * packed_per_tok + (T - cap) * 2 * d * 2 + 2 * P * d * 2) + n_seq * Hq * d * (2 + 4)
+    mine_flops = 2.0 * T * P * d * (2 * L * Hkv) * iters
+    mine_bytes = 2.0 * L * Hkv * iters * T * d * 2
+
+    def roof(bound, achieved, peak, unit):
+        return {"bound": bound, "achieved": round(achieved, 3), "peak": peak, "unit": unit,
+                "frac": round(achieved / peak, 4), "traffic": None}
+
+    rl = {
+        "mine": dict(roof("alu", mine_flops / (stage_ms["mine"] * 1e-3) / 1e12, VALU_F32_PEAK_TFLOPS, "TFLOP/s"),
+                     kernel="mine_assign_kernel"),
+        "quantize_append": dict(roof("hbm", quant_bytes / (stage_ms["quantize_append"] * 1e-3) / 1e9, HBM_PEAK_GBPS, "GB/s"),
+                                kernel="quantize_k_kernel+quantize_v_kernel"),
+        "decode_attention": dict(roof("hbm", dec_bytes / (stage_ms["decode_attention"] * 1e-3) / 1e9, HBM_PEAK_GBPS, "GB/s"),
+                                 kernel="decode_packed_kernel"),
+    }
+    dominant = max(stage_ms, key=stage_ms.get)
+    stage_out = {
+        "mine": {"ms": round(stage_ms["mine"], 4), "ms_min": round(stage_ms_min["mine"], 4),
+                 "TFLOP/s": rl["mine"]["achieved"], "GB/s": round(mine_bytes / (stage_ms["mine"] * 1e-3) / 1e9, 2)},
+        "quantize_append": {"ms": round(stage_ms["quantize_append"], 4), "ms_min": round(stage_ms_min["quantize_append"], 4),
+                            "GB/s": rl["quantize_append"]["achieved"], "frac_hbm_peak": rl["quantize_append"]["frac"],
+                            "algorithmic_bytes": int(quant_bytes)},
+        "decode_attention": {"ms": round(stage_ms["decode_attention"], 4), "ms_min": round(stage_ms_min["decode_attention"], 4),
+                             "GB/s": rl["decode_attention"]["achieved"], "frac_hbm_peak": rl["decode_attention"]["frac"],
+                             "tokens/s": round(B / (stage_ms["decode_attention"] * 1e-3), 2),
+                             "algorithmic_bytes": int(dec_bytes)},
+    }
+
+    result = {
+        "metric": "KV quantize-append GB/s and decode-attention tokens/s on 2-bit cache, % HBM peak",
+        "value": round(n_seq * T / (ms_per_step * 1e-3), 1),
+        "unit": "context tokens/s through the whole path (mine + quantize-append + decode)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16 in, f32 arithmetic, u%d codes" % bits,
+        "data": "synthetic",
+        "config": {"workload": args.workload, "layers": L, "batch": B, "n_kv_heads": Hkv, "n_q_heads": Hq, "T": T,
+                   "head_dim": d, "n_patterns": P, "lloyd_iters": iters, "bits": bits, "group": G, "recent": R,
+                   "flush": F, "metric": "L2", "seed": args.seed},
+        "stages": stage_out,
+        "roofline": rl[dominant],
+        "stage_rooflines": rl,
+        "input_generation_s": round(t_gen, 2),
+    }
+
+    # ---------------------------------------------------------------- the oracle on the host, bounded sample
+    if not args.no_cpu_baseline:
+        from oracle import pk_oracle as oracle
+        heads = min(Hkv, 2)                                   # sample: the first `heads` KV heads of sequence 0
+        r = Hq // Hkv
+        Ks = K[0, :heads].cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+        Vs = V[0, :heads].cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+        qs = q[0:1, :heads * r].cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+        Ts = min(T, 16384)
+        it_s = min(iters, 4)
+        Ks, Vs = np.ascontiguousarray(Ks[:, :Ts]), np.ascontiguousarray(Vs[:, :Ts])
+        ocfg = oracle.Config(n_seq=1, n_kv_heads=heads, n_q_heads=heads * r, head_dim=d, n_patterns=P, seqs_per_set=0,
+                             bits=bits, group=G, recent=R, flush=F, t_capacity=(Ts - R) // F * F, metric=0)
+        t0 = time.perf_counter()
+        Mko, _, _, _ = oracle.mine(Ks, P, it_s)
+        Mvo, _, _, _ = oracle.mine(Vs, P, it_s)
+        t_mine = (time.perf_counter() - t0) * iters / it_s
+        t0 = time.perf_counter()
+        oc = oracle.Cache(ocfg)
+        oc.append(Ks[None], Vs[None], Mko, Mvo)
+        t_q = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        oracle.decode_attention(oc, qs, Mko, Mvo, scale)
+        t_d = time.perf_counter() - t0
+        # scale the sample to the whole workload: streams and context length are both linear
+        factor = (N / heads) * (T / Ts)
+        t_full = (t_mine * (L * Hkv / heads) * (T / Ts)) + (t_q + t_d) * factor
+        result["cpu_baseline"] = {
+            "value": round(n_seq * T / t_full, 2), "unit": result["unit"], "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"{heads} of {N} KV streams, {Ts} of {T} tokens, {it_s} of {iters} Lloyd iterations; "
+                      f"measured {t_mine * it_s / iters + t_q + t_d:.2f} s, scaled linearly to the full workload",
+            "stage_seconds_sample": {"mine": round(t_mine * it_s / iters, 3), "quantize_append": round(t_q, 3),
+                                     "decode_attention": round(t_d, 3)},
+        }
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -181,14 +181,15 @@ def pk_mine_patterns(cfg: Config, x: torch.Tensor, iters: int, patterns: torch.T
                      init_given: bool = False, assign: torch.Tensor | None = None,
                      inertia: torch.Tensor | None = None, workspace: torch.Tensor | None = None):
     """x [n_sets, T, d] fp16 (sets may be strided, rows contiguous) -> patterns [n_sets, P, d] fp16."""
-    assert x.dtype == torch.float16 and x.dim() == 3 and x.stride(2) == 1 and x.stride(1) == x.shape[2]
+    assert x.dtype == torch.float16 and x.dim() == 3 and x.stride(2) == 1 and (x.shape[1] == 1 or x.stride(1) == x.shape[2])
     n_sets, T, d = x.shape
     if patterns is None:
         patterns = torch.empty((n_sets, cfg.n_patterns, d), dtype=torch.float16, device=x.device)
     if workspace is None:
         workspace = torch.empty(max(pk_workspace_bytes(cfg, OP_MINE, T, n_sets), 16), dtype=torch.uint8, device=x.device)
     c = cfg.c()
-    st = _lib.pk_mine_patterns(C.byref(c), C.c_void_p(x.data_ptr()), x.stride(0), n_sets, T, iters,
+    set_stride = x.stride(0) if n_sets > 1 else T * d
+    st = _lib.pk_mine_patterns(C.byref(c), C.c_void_p(x.data_ptr()), set_stride, n_sets, T, iters,
                                1 if init_given else 0, _ptr(patterns), _ptr(assign), _ptr(inertia),
                                _ptr(workspace), workspace.numel(), _stream())
     _check(st, "pk_mine_patterns")

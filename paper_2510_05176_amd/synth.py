@@ -105,3 +105,42 @@ SPECS = {
     "cfg4": KVSpec(1, 64, 8, 32, 8192, 128, 32, 0.3, 0.5, 4, 8.0, drift_sigma=0.05, drift_chunk=128),
     "cfg5": KVSpec(1, 1, 4, 28, 131072, 128, 256, 0.3, 0.5, 8, 10.0),
 }
+
+
+def make_layer_device(seed: int, layer: int, spec: KVSpec, device="cuda", T: int | None = None):
+    """Device-side twin of make_kv for workloads too large for host memory: one layer's
+    K, V as float16 [batch, n_kv_heads, T, d] on `device`.
+
+    Head parameters (centres, offsets, outlier channels) are the numpy draws of head_params, so they
+    match make_stream; the per-token draws (cluster ids, noise, drift) come from a torch generator
+    seeded with (seed, layer, head, batch element) and therefore differ from the numpy stream.
+    """
+    import torch
+
+    T = spec.T if T is None else T
+    K = torch.empty((spec.batch, spec.n_kv_heads, T, spec.d), dtype=torch.float16, device=device)
+    V = torch.empty_like(K)
+    gen = torch.Generator(device=device)
+    for h in range(spec.n_kv_heads):
+        ck, off, out_idx, cv = head_params(seed, layer, h, spec)
+        ck_d = torch.from_numpy(ck).to(device=device, dtype=torch.float32)
+        cv_d = torch.from_numpy(cv).to(device=device, dtype=torch.float32)
+        off_d = torch.from_numpy(off).to(device=device, dtype=torch.float32)
+        mult = torch.ones(spec.d, device=device)
+        mult[torch.from_numpy(out_idx).to(device)] = spec.outlier_scale
+        for b in range(spec.batch):
+            gen.manual_seed(((seed * 1009 + layer) * 1009 + h) * 100003 + b)
+            u = torch.randint(0, spec.n_clusters, (T,), generator=gen, device=device)
+            k = ck_d[u] + spec.sigma_k * torch.randn((T, spec.d), generator=gen, device=device) + off_d
+            uv = torch.randint(0, spec.n_clusters, (T,), generator=gen, device=device)
+            v = cv_d[uv] + spec.sigma_v * torch.randn((T, spec.d), generator=gen, device=device)
+            if spec.drift_sigma > 0:
+                nchunk = -(-T // spec.drift_chunk)
+                chunk = torch.arange(T, device=device) // spec.drift_chunk
+                wk = torch.cumsum(torch.randn((nchunk, spec.n_clusters, spec.d), generator=gen, device=device) * spec.drift_sigma, 0)
+                wv = torch.cumsum(torch.randn((nchunk, spec.n_clusters, spec.d), generator=gen, device=device) * spec.drift_sigma, 0)
+                k = k + wk[chunk, u]
+                v = v + wv[chunk, uv]
+            K[b, h] = (k * mult).to(torch.float16)
+            V[b, h] = v.to(torch.float16)
+    return K, V

@@ -326,8 +326,12 @@ void pko_quantize_k(const uint16_t *x, int n, int d, const uint16_t *M, const in
 
 /*
  * V side: per token, one (s,z) per group of Gc consecutive channels
- * (Gc = min(G, d)).  codes[n][d], scale/zero[n][d/Gc].
+ * (Gc = min(G, d)).  codes[n][d]; scale/zero are stored in slices of 16 tokens,
+ * [n/16][d/Gc][16]: the parameter of token t and channel group j is at
+ * ((t/16)*(d/Gc) + j)*16 + t%16.
  */
+static int64_t v_param(int64_t t, int j, int ng) { return ((t / 16) * ng + j) * 16 + t % 16; }
+
 void pko_quantize_v(const uint16_t *x, int n, int d, const uint16_t *M, const int32_t *idx,
                     int bits, int Gc, uint8_t *codes, uint16_t *scale, uint16_t *zero)
 {
@@ -347,8 +351,8 @@ void pko_quantize_v(const uint16_t *x, int n, int d, const uint16_t *M, const in
             }
             uint16_t s16, z16;
             group_params(mn, mx, bits, &s16, &z16);
-            scale[(int64_t)t * ng + j] = s16;
-            zero[(int64_t)t * ng + j] = z16;
+            scale[v_param(t, j, ng)] = s16;
+            zero[v_param(t, j, ng)] = z16;
             for (int c = j * Gc; c < (j + 1) * Gc; ++c)
                 codes[(int64_t)t * d + c] = quantize_one(r[c], s16, z16, bits);
         }
@@ -390,39 +394,36 @@ void pko_unpack_k(const uint32_t *in, int n, int d, int bits, uint8_t *codes)
 }
 
 /*
- * V codes: tokens are packed in blocks of 32; a block is 4 slices of 8
- * tokens; the bit planes run along the tokens.  Byte address of the plane
- * byte that holds bit j of the codes of channel c for the 8 tokens of slice
- * kb of block blk:
- *     (((blk*4 + kb)*16 + c%16) * (d/16) + c/16) * bits + j
- * and bit (t % 8) of that byte belongs to token t (blk = t/32, kb = (t%32)/8).
- * A block therefore occupies 32*d*bits/8 bytes, the same as 32 K rows.
+ * V codes: the bit planes run along the tokens.  Tokens are packed in blocks of
+ * 64 = 4 units of 16; one little-endian 32-bit word holds two planes of one
+ * channel for the 16 tokens of a unit: bit (16*(j%2) + t%16) of word
+ *     (((t/64)*4 + (t%64)/16)*16 + c%16) * (d/16)*(bits/2) + (c/16)*(bits/2) + j/2
+ * is bit j of the code of channel c of token t.  A block occupies
+ * 64*d*bits/8 bytes, the same as 64 K rows.
  */
-void pko_pack_v(const uint8_t *codes, int n, int d, int bits, uint8_t *out)
+static int64_t v_word(int64_t t, int c, int j, int d, int bits)
 {
-    int TAU = d / 16;
+    int64_t unit = (t / 64) * 4 + (t % 64) / 16;
+    return ((unit * 16 + c % 16) * (d / 16) + c / 16) * (bits / 2) + j / 2;
+}
+
+void pko_pack_v(const uint8_t *codes, int n, int d, int bits, uint32_t *out)
+{
     memset(out, 0, (size_t)n * d * bits / 8);
     for (int t = 0; t < n; ++t)
         for (int c = 0; c < d; ++c)
             for (int j = 0; j < bits; ++j)
-                if ((codes[(int64_t)t * d + c] >> j) & 1) {
-                    int64_t blk = t / 32, kb = (t % 32) / 8;
-                    int64_t byte = (((blk * 4 + kb) * 16 + c % 16) * TAU + c / 16) * bits + j;
-                    out[byte] |= (uint8_t)(1u << (t % 8));
-                }
+                if ((codes[(int64_t)t * d + c] >> j) & 1)
+                    out[v_word(t, c, j, d, bits)] |= (uint32_t)1 << (16 * (j % 2) + t % 16);
 }
 
-void pko_unpack_v(const uint8_t *in, int n, int d, int bits, uint8_t *codes)
+void pko_unpack_v(const uint32_t *in, int n, int d, int bits, uint8_t *codes)
 {
-    int TAU = d / 16;
     for (int t = 0; t < n; ++t)
         for (int c = 0; c < d; ++c) {
             int v = 0;
-            int64_t blk = t / 32, kb = (t % 32) / 8;
-            for (int j = 0; j < bits; ++j) {
-                int64_t byte = (((blk * 4 + kb) * 16 + c % 16) * TAU + c / 16) * bits + j;
-                v |= ((in[byte] >> (t % 8)) & 1) << j;
-            }
+            for (int j = 0; j < bits; ++j)
+                v |= (int)((in[v_word(t, c, j, d, bits)] >> (16 * (j % 2) + t % 16)) & 1) << j;
             codes[(int64_t)t * d + c] = (uint8_t)v;
         }
 }
@@ -449,8 +450,8 @@ void pko_dequant_v(const uint8_t *codes, const uint16_t *scale, const uint16_t *
     int ng = d / Gc;
     for (int t = 0; t < n; ++t)
         for (int c = 0; c < d; ++c) {
-            float s = pko_half_to_float(scale[(int64_t)t * ng + c / Gc]);
-            float z = pko_half_to_float(zero[(int64_t)t * ng + c / Gc]);
+            float s = pko_half_to_float(scale[v_param(t, c / Gc, ng)]);
+            float z = pko_half_to_float(zero[v_param(t, c / Gc, ng)]);
             float res = s * (float)codes[(int64_t)t * d + c] + z;
             out[(int64_t)t * d + c] = pko_half_to_float(M[(int64_t)idx[t] * d + c]) + res;
         }
@@ -528,7 +529,7 @@ void pko_mine_sets(const uint16_t *x, int S, int64_t T, int d, int P, int iters,
  *   side: 0 = K (groups of G tokens per channel), 1 = V (groups of Gc channels).
  * Outputs (per stream, contiguous): idx[N][n] int32, best/second[N][n]
  * (optional), codes_unpacked[N][n][d] (optional), packed[N][n*d*bits/8 bytes],
- * scale/zero[N][(n/G)*d] (K) or [N][n*(d/Gc)] (V).
+ * scale/zero[N][(n/G)*d] (K) or [N][(n/16)*(d/Gc)*16] (V).
  */
 void pko_quantize_streams(const uint16_t *x, int N, int n, int d, const int32_t *set_of,
                           const uint16_t *M, int P, int metric, int bits, int G, int side,
@@ -551,7 +552,7 @@ void pko_quantize_streams(const uint16_t *x, int N, int n, int d, const int32_t 
             pko_pack_k(codes, n, d, bits, (uint32_t *)(packed + s * npacked));
         } else {
             pko_quantize_v(xs, n, d, Ms, ix, bits, Gc, codes, scale + s * nparam, zero + s * nparam);
-            pko_pack_v(codes, n, d, bits, packed + s * npacked);
+            pko_pack_v(codes, n, d, bits, (uint32_t *)(packed + s * npacked));
         }
         if (codes_unpacked)
             memcpy(codes_unpacked + (int64_t)s * n * d, codes, (size_t)n * d);

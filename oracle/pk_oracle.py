@@ -117,7 +117,7 @@ def quantize_streams(x_u16, set_of, M_u16, metric, bits, G, side, want_codes=Fal
     N, n, d = x_u16.shape
     P = M_u16.shape[1]
     Gc = min(G, d)
-    assert n % 32 == 0 and (side == 1 or n % G == 0)
+    assert n % 64 == 0 and (side == 1 or n % G == 0)
     idx = np.empty((N, n), np.int32)
     best = np.empty((N, n), np.float64)
     second = np.empty((N, n), np.float64)
@@ -126,11 +126,17 @@ def quantize_streams(x_u16, set_of, M_u16, metric, bits, G, side, want_codes=Fal
     if side == 0:
         scale = np.empty((N, n // G, d), np.uint16)
     else:
-        scale = np.empty((N, n, d // Gc), np.uint16)
+        scale = np.empty((N, n // 16, d // Gc, 16), np.uint16)
     zero = np.empty_like(scale)
     lib().pko_quantize_streams(_p(x_u16), N, n, d, _p(set_of), _p(M_u16), P, metric, bits, G, side,
                                _p(idx), _p(best), _p(second), _p(codes), _p(packed), _p(scale), _p(zero))
     return dict(idx=idx, best=best, second=second, codes=codes, packed=packed, scale=scale, zero=zero)
+
+
+def v_params_by_token(a):
+    """V scale / zero from the stored [n/16, groups, 16] slices to [n, groups]."""
+    a = np.asarray(a)
+    return a.transpose(0, 2, 1).reshape(-1, a.shape[1])
 
 
 def pack_k(codes_u8, bits):
@@ -148,14 +154,14 @@ def unpack_k(words_u32, n, d, bits):
 
 def pack_v(codes_u8, bits):
     n, d = codes_u8.shape
-    out = np.zeros(n * d * bits // 8, np.uint8)
+    out = np.zeros(n * d * bits // 32, np.uint32)
     lib().pko_pack_v(_p(np.ascontiguousarray(codes_u8)), n, d, bits, _p(out))
     return out
 
 
-def unpack_v(bytes_u8, n, d, bits):
+def unpack_v(words_u32, n, d, bits):
     out = np.empty((n, d), np.uint8)
-    lib().pko_unpack_v(_p(np.ascontiguousarray(bytes_u8)), n, d, bits, _p(out))
+    lib().pko_unpack_v(_p(np.ascontiguousarray(words_u32)), n, d, bits, _p(out))
     return out
 
 
@@ -225,14 +231,15 @@ class Cache:
         self.cfg = cfg
         N, d, b, G = cfg.n_streams, cfg.head_dim, cfg.bits, cfg.group
         cap, Gc = cfg.t_capacity, min(cfg.group, cfg.head_dim)
+        assert cfg.flush % 64 == 0 and cfg.flush % cfg.group == 0 and cfg.t_capacity % cfg.flush == 0
         self.ring = cfg.recent + cfg.flush
         self.k_codes = np.zeros((N, cap, d // 32, b), np.uint32)
         self.k_scale = np.zeros((N, cap // G, d), np.uint16)
         self.k_zero = np.zeros((N, cap // G, d), np.uint16)
         self.k_idx = np.zeros((N, cap), np.uint8)
-        self.v_codes = np.zeros((N, cap * d * b // 8), np.uint8)
-        self.v_scale = np.zeros((N, cap, d // Gc), np.uint16)
-        self.v_zero = np.zeros((N, cap, d // Gc), np.uint16)
+        self.v_codes = np.zeros((N, cap * d * b // 32), np.uint32)
+        self.v_scale = np.zeros((N, cap // 16, d // Gc, 16), np.uint16)
+        self.v_zero = np.zeros((N, cap // 16, d // Gc, 16), np.uint16)
         self.v_idx = np.zeros((N, cap), np.uint8)
         self.tail_k = np.zeros((N, self.ring, d), np.uint16)
         self.tail_v = np.zeros((N, self.ring, d), np.uint16)
@@ -272,10 +279,10 @@ class Cache:
             self.k_scale[:, t0 // G:t1 // G] = rk["scale"]
             self.k_zero[:, t0 // G:t1 // G] = rk["zero"]
             self.k_idx[:, t0:t1] = rk["idx"].astype(np.uint8)
-            bpt = d * b // 8
-            self.v_codes[:, t0 * bpt:t1 * bpt] = rv["packed"]
-            self.v_scale[:, t0:t1] = rv["scale"]
-            self.v_zero[:, t0:t1] = rv["zero"]
+            wpt = d * b // 32
+            self.v_codes[:, t0 * wpt:t1 * wpt] = rv["packed"].view(np.uint32)
+            self.v_scale[:, t0 // 16:t1 // 16] = rv["scale"]
+            self.v_zero[:, t0 // 16:t1 // 16] = rv["zero"]
             self.v_idx[:, t0:t1] = rv["idx"].astype(np.uint8)
             self.k_best[:, t0:t1], self.k_second[:, t0:t1] = rk["best"], rk["second"]
             self.v_best[:, t0:t1], self.v_second[:, t0:t1] = rv["best"], rv["second"]
@@ -297,14 +304,14 @@ class Cache:
         set_of = cfg.set_of()
         K = np.empty((N, t1 - t0, d), np.float32)
         V = np.empty((N, t1 - t0, d), np.float32)
-        bpt = d * b // 8
+        wpt = d * b // 32
         for s in range(N):
             ck = unpack_k(self.k_codes[s, :self.t_quant], self.t_quant, d, b) if self.t_quant else np.zeros((0, d), np.uint8)
-            cv = unpack_v(self.v_codes[s, :self.t_quant * bpt], self.t_quant, d, b) if self.t_quant else np.zeros((0, d), np.uint8)
+            cv = unpack_v(self.v_codes[s, :self.t_quant * wpt], self.t_quant, d, b) if self.t_quant else np.zeros((0, d), np.uint8)
             if t1 > t0:
                 kfull = dequant(0, ck, self.k_scale[s, :self.t_quant // G], self.k_zero[s, :self.t_quant // G],
                                 self.k_idx[s, :self.t_quant].astype(np.int32), patterns_k[set_of[s]], G)
-                vfull = dequant(1, cv, self.v_scale[s, :self.t_quant], self.v_zero[s, :self.t_quant],
+                vfull = dequant(1, cv, self.v_scale[s, :self.t_quant // 16], self.v_zero[s, :self.t_quant // 16],
                                 self.v_idx[s, :self.t_quant].astype(np.int32), patterns_v[set_of[s]], G)
                 K[s], V[s] = kfull[t0:t1], vfull[t0:t1]
         return K, V

@@ -240,8 +240,8 @@ def test_quantize_reduces_to_textbook_with_zero_pattern(oracle, bits, G):
     Gc = min(G, d)
     qv, sv, zv = _numpy_asym_quant(r.reshape(n, d // Gc, Gc), bits, axis=2)
     assert np.array_equal(rv["codes"][0], qv.reshape(n, d))
-    assert np.array_equal(rv["scale"][0], sv.reshape(n, d // Gc).view(np.uint16))
-    assert np.array_equal(rv["zero"][0], zv.reshape(n, d // Gc).view(np.uint16))
+    assert np.array_equal(oracle.v_params_by_token(rv["scale"][0]), sv.reshape(n, d // Gc).view(np.uint16))
+    assert np.array_equal(oracle.v_params_by_token(rv["zero"][0]), zv.reshape(n, d // Gc).view(np.uint16))
 
 
 @pytest.mark.parametrize("side", [0, 1])
@@ -260,8 +260,11 @@ def test_quantize_invariants(oracle, side, bits, metric):
     assert codes.max() <= qmax
     for s in range(2):
         resid = x[s].astype(np.float32) - M[s][res["idx"][s]].astype(np.float32)
-        sc = res["scale"][s].view(np.float16).astype(np.float32)
-        ze = res["zero"][s].view(np.float16).astype(np.float32)
+        sc, ze = res["scale"][s], res["zero"][s]
+        if side == 1:
+            sc, ze = oracle.v_params_by_token(sc), oracle.v_params_by_token(ze)
+        sc = sc.view(np.float16).astype(np.float32)
+        ze = ze.view(np.float16).astype(np.float32)
         if side == 0:
             sc_e, ze_e = np.repeat(sc, G, axis=0), np.repeat(ze, G, axis=0)
             grp = codes[s].reshape(-1, G, 128)
@@ -302,7 +305,7 @@ def test_minmax_choice_minimises_v_scale(oracle):
     res = oracle.quantize_streams(x.view(np.uint16), np.zeros(1, np.int32), M.view(np.uint16), 1, 2, 128, 1)
     diff = x[0].astype(np.float32)[:, None] - M[0].astype(np.float32)[None]
     dmm = diff.max(-1) - diff.min(-1)
-    s = res["scale"][0].view(np.float16).astype(np.float64)[:, 0]
+    s = oracle.v_params_by_token(res["scale"][0]).view(np.float16).astype(np.float64)[:, 0]
     assert np.all(s >= dmm.min(1) / 3 * (1 - 1e-6))
     assert np.all(s <= dmm.min(1) / 3 * (1 + 2.0 ** -9))
 
@@ -331,7 +334,7 @@ def test_pack_roundtrip_and_format(oracle, bits):
             assert np.flatnonzero(w).tolist() == [int(unit)] and w[int(unit)] == 1 << int(bit)
         else:
             w = oracle.pack_v(one, bits)
-            assert np.flatnonzero(w).tolist() == [int(unit)] and w[int(unit)] == 1 << int(bit)
+            assert w.dtype == np.uint32 and np.flatnonzero(w).tolist() == [int(unit)] and w[int(unit)] == 1 << int(bit)
 
 
 def test_eq1_worked_examples(oracle):
@@ -342,9 +345,9 @@ def test_eq1_worked_examples(oracle):
         bits, vals, s_want, z_want, codes_want = [f.strip() for f in line.split("|")]
         vals = [float(v) for v in vals.split()]
         G = 32
-        x = np.zeros((1, G, 128), np.float16)
+        x = np.zeros((1, 2 * G, 128), np.float16)      # second group of the stream stays zero
         x[0, :len(vals), 0] = vals
-        x[0, len(vals):, 0] = vals[0]
+        x[0, len(vals):G, 0] = vals[0]
         res = oracle.quantize_streams(x.view(np.uint16), np.zeros(1, np.int32), np.zeros((1, 1, 128), np.uint16),
                                       0, int(bits), G, 0, want_codes=True)
         assert float(res["scale"][0, 0, 0:1].view(np.float16)[0]) == float(s_want)
@@ -433,10 +436,24 @@ def test_attention_matches_torch_sdpa(oracle):
     assert np.linalg.norm(out - full) / np.linalg.norm(full) < 0.35
 
 
+def test_v_parameter_layout(oracle):
+    # V (s, z) are stored in slices of 16 tokens: parameter of token t, channel group j at ((t/16)*groups + j)*16 + t%16
+    rng = np.random.default_rng(21)
+    x = f16(rng.standard_normal((1, 64, 128)) * (1 + np.arange(64))[None, :, None])   # scale grows with the token index
+    res = oracle.quantize_streams(x.view(np.uint16), np.zeros(1, np.int32), np.zeros((1, 1, 128), np.uint16), 0, 2, 32, 1)
+    flat = res["scale"][0].reshape(-1).view(np.float16).astype(np.float32)
+    r = x[0].astype(np.float32).reshape(64, 4, 32)
+    want = (r.max(2) - r.min(2)) / 3
+    for t in (0, 5, 16, 37, 63):
+        for j in range(4):
+            got = flat[((t // 16) * 4 + j) * 16 + t % 16]
+            assert abs(got - want[t, j]) <= 2e-3 * want[t, j]
+
+
 def test_attention_factorised_form_equals_plain(oracle):
     """The algebra the GPU kernels rely on: scores = q.M[idx] + sum_c (q_c s_c) code_c + q.z, and
     output = W.M_V + sum_t p_t (s code + z) with W[p] = sum of p_t over tokens assigned to p."""
-    cfg, c, K, V, M_k, M_v, q = _small_cache(oracle, seed=17, recent=0, flush=32)
+    cfg, c, K, V, M_k, M_v, q = _small_cache(oracle, seed=17, recent=0, flush=64)
     assert c.t_tail == 22 and c.t_quant == 128
     out, _ = oracle.decode_attention(c, q.view(np.uint16), M_k, M_v, 128 ** -0.5)
     d, G, tq = 128, cfg.group, c.t_quant
@@ -446,11 +463,11 @@ def test_attention_factorised_form_equals_plain(oracle):
             s = seq * cfg.n_kv_heads + h // 2
             qd = q[seq, h].astype(np.float64)
             ck = oracle.unpack_k(c.k_codes[s, :tq], tq, d, 2).astype(np.float64)
-            cv = oracle.unpack_v(c.v_codes[s, :tq * 32], tq, d, 2).astype(np.float64)
+            cv = oracle.unpack_v(c.v_codes[s, :tq * 8], tq, d, 2).astype(np.float64)
             ks = np.repeat(c.k_scale[s, :tq // G].view(np.float16).astype(np.float64), G, axis=0)
             kz = np.repeat(c.k_zero[s, :tq // G].view(np.float16).astype(np.float64), G, axis=0)
-            vs = np.repeat(c.v_scale[s, :tq].view(np.float16).astype(np.float64), G, axis=1)
-            vz = np.repeat(c.v_zero[s, :tq].view(np.float16).astype(np.float64), G, axis=1)
+            vs = np.repeat(oracle.v_params_by_token(c.v_scale[s, :tq // 16]).view(np.float16).astype(np.float64), G, axis=1)
+            vz = np.repeat(oracle.v_params_by_token(c.v_zero[s, :tq // 16]).view(np.float16).astype(np.float64), G, axis=1)
             Mk = M_k[set_of[s]].view(np.float16).astype(np.float64)
             Mv = M_v[set_of[s]].view(np.float16).astype(np.float64)
             QM = Mk @ qd
@@ -489,8 +506,8 @@ def test_attention_special_cases(oracle):
 def test_attention_shared_prefix_equals_concatenation(oracle):
     """A shared prompt cache in front of each sequence's own cache is the same as one cache holding
     both, when both are quantized against the same patterns."""
-    cfg_own = _cfg(oracle, recent=0, flush=32, n_seq=2)
-    cfg_pre = _cfg(oracle, recent=0, flush=32, n_seq=1)
+    cfg_own = _cfg(oracle, recent=0, flush=64, n_seq=2)
+    cfg_pre = _cfg(oracle, recent=0, flush=64, n_seq=1)
     spec = synth.KVSpec(1, 2, 2, 4, 160, 128, 8)
     K, V = synth.make_kv(19, spec)
     Kp, Vp = K[:1, :, :64], V[:1, :, :64]                   # prompt of sequence 0 is the shared prefix

@@ -47,12 +47,14 @@
  *   k_scale, k_zero [N][t_capacity/G][d] fp16 one (s,z) per channel and group of
  *                                             G consecutive tokens
  *   k_idx   [N][t_capacity] uint8             pattern index k* of every token
- *   v_codes [N][t_capacity*d*b/8] bytes       tokens in blocks of 32 = 4 slices of
- *                                             8; the byte holding bit j of channel
- *                                             c for slice kb of block blk is at
- *       (((blk*4 + kb)*16 + c%16)*(d/16) + c/16)*b + j ,  bit (t%8) <-> token t
- *   v_scale, v_zero [N][t_capacity][d/Gc] fp16   Gc = min(G, d): one (s,z) per
- *                                             token and group of Gc channels
+ *   v_codes [N][t_capacity*d*b/32] uint32     the bit planes of V run along the tokens:
+ *                                             tokens in blocks of 64 = 4 units of 16; bit
+ *                                             (16*(j%2) + t%16) of word
+ *       (((t/64)*4 + (t%64)/16)*16 + c%16) * (d/16)*(b/2) + (c/16)*(b/2) + j/2
+ *                                             is bit j of the code of channel c of token t
+ *   v_scale, v_zero [N][t_capacity/16][d/Gc][16] fp16   Gc = min(G, d): one (s,z) per token
+ *                                             and group of Gc channels, stored in slices of
+ *                                             16 tokens
  *   v_idx   [N][t_capacity] uint8
  *   tail_k, tail_v [N][recent+flush][d] fp16  ring buffer of the most recent
  *                                             vectors, kept in full precision;
@@ -97,14 +99,15 @@ typedef enum { PK_OP_MINE = 0, PK_OP_APPEND = 1, PK_OP_DECODE = 2 } pk_op;
 typedef struct {
     int32_t n_seq;        /* sequences (layers x batch flattened), >= 1                       */
     int32_t n_kv_heads;   /* >= 1                                                             */
-    int32_t n_q_heads;    /* multiple of n_kv_heads; n_q_heads/n_kv_heads in 1..8             */
+    int32_t n_q_heads;    /* multiple of n_kv_heads; r = n_q_heads/n_kv_heads in 1..8;
+                             pk_decode_attention needs r * (d / min(G, d)) <= 16                 */
     int32_t head_dim;     /* d: 128                                                           */
     int32_t n_patterns;   /* P: 1..256 (indices are stored in one byte)                       */
     int32_t seqs_per_set; /* see "Streams and pattern sets" above; >= 0                       */
     int32_t bits;         /* b: 2 or 4                                                        */
     int32_t group;        /* G: 32, 64 or 128                                                 */
-    int32_t recent;       /* R >= 0: vectors always kept in fp16; R + flush multiple of 8     */
-    int32_t flush;        /* F: multiple of G; vectors quantized per flush                    */
+    int32_t recent;       /* R >= 0: vectors always kept in fp16                              */
+    int32_t flush;        /* F: multiple of G and of 64; vectors quantized per flush          */
     int32_t t_capacity;   /* maximum packed tokens per stream, multiple of F                  */
     int32_t metric;       /* pk_metric                                                        */
 } pk_config;

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpatternkv.so")
-SOURCES = ["pk_api.hip", "pk_mine.hip", "pk_quantize.hip", "pk_decode.hip", "pk_dequant.hip"]
+SOURCES = ["pk_api.hip", "pk_mine.hip", "pk_quantize.hip", "pk_decode.hip", "pk_decode_packed.hip", "pk_dequant.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",

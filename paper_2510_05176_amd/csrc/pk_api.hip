@@ -26,7 +26,7 @@ pk_status check_config(const pk_config *c)
     if (c->n_q_heads % c->n_kv_heads != 0) return PK_ERR_SHAPE;
     if (c->n_q_heads / c->n_kv_heads > 8) return PK_ERR_UNSUPPORTED;
     if ((int64_t)c->n_seq * c->n_kv_heads > 65535) return PK_ERR_UNSUPPORTED;
-    if (c->flush % c->group != 0) return PK_ERR_SHAPE;
+    if (c->flush % c->group != 0 || c->flush % 64 != 0) return PK_ERR_SHAPE;
     if (c->t_capacity % c->flush != 0) return PK_ERR_SHAPE;
     return PK_OK;
 }
@@ -156,7 +156,8 @@ size_t pk_workspace_bytes(const pk_config *cfg, pk_op op, int64_t a, int64_t b)
     if (op == PK_OP_DECODE) {
         const int64_t N = (int64_t)cfg->n_seq * cfg->n_kv_heads, r = cfg->n_q_heads / cfg->n_kv_heads;
         const int64_t slots = decode_slots_bound(N, a, b);
-        return round_up((uint64_t)N * slots * r * kD * 4, 256) + round_up((uint64_t)N * slots * r * 2 * 4, 256);
+        return round_up((uint64_t)N * slots * r * kD * 4, 256) + round_up((uint64_t)N * slots * r * cfg->n_patterns * 4, 256) +
+               round_up((uint64_t)N * slots * r * 2 * 4, 256);
     }
     return 0;
 }
@@ -289,6 +290,7 @@ pk_status pk_decode_attention(const pk_config *cfg, const pk_cache *cache, const
     if ((st = check_cache(cache)) != PK_OK) return st;
     if ((st = check_state(cfg, state)) != PK_OK) return st;
     if (!q || !patterns_k || !patterns_v || !out) return PK_ERR_INVALID_ARG;
+    if ((cfg->n_q_heads / cfg->n_kv_heads) * (kD / (cfg->group < kD ? cfg->group : kD)) > 16) return PK_ERR_UNSUPPORTED;
     if (!aligned16(q) || !aligned16(patterns_k) || !aligned16(patterns_v) || !aligned16(out) ||
         (lse && !aligned16(lse)))
         return PK_ERR_ALIGNMENT;
@@ -318,8 +320,9 @@ pk_status pk_decode_attention(const pk_config *cfg, const pk_cache *cache, const
     a.splits_prefix = (a.prefix.t_quant + a.chunk - 1) / a.chunk;
     const int64_t slots = a.splits_own + a.splits_prefix + 2;
     const uint64_t o_bytes = round_up((uint64_t)N * slots * r * kD * 4, 256);
+    const uint64_t w_bytes = round_up((uint64_t)N * slots * r * cfg->n_patterns * 4, 256);
     const uint64_t ml_bytes = round_up((uint64_t)N * slots * r * 2 * 4, 256);
-    if (!workspace || workspace_bytes < o_bytes + ml_bytes) return PK_ERR_WORKSPACE;
+    if (!workspace || workspace_bytes < o_bytes + w_bytes + ml_bytes) return PK_ERR_WORKSPACE;
     if (!aligned16(workspace)) return PK_ERR_ALIGNMENT;
 
     a.sets.n_kv_heads = cfg->n_kv_heads;
@@ -335,7 +338,8 @@ pk_status pk_decode_attention(const pk_config *cfg, const pk_cache *cache, const
     a.G = cfg->group;
     a.softmax_scale = softmax_scale;
     a.part_o = reinterpret_cast<float *>(workspace);
-    a.part_ml = reinterpret_cast<float *>(static_cast<char *>(workspace) + o_bytes);
+    a.part_w = reinterpret_cast<float *>(static_cast<char *>(workspace) + o_bytes);
+    a.part_ml = reinterpret_cast<float *>(static_cast<char *>(workspace) + o_bytes + w_bytes);
     a.out = out;
     a.lse = lse;
     return launch_decode(a, static_cast<hipStream_t>(stream)) == hipSuccess ? PK_OK : PK_ERR_DEVICE;

@@ -1,0 +1,458 @@
+// Decode attention over the packed part of the cache on the matrix cores
+// (Sec. 3.4 "Decode-stage KV reconstruction": index restoration + dequantization + QK, and
+// dequantization + index restoration + weights.V, fused; here softmax is fused in as well).
+//
+// For one KV stream and its r query heads, with NG = channel groups per V token:
+//   score[h][t] = scale * ( QM[h][k*_t] + sum_c (q_h[c] s_K[g][c]) code_K[t][c] + q_h . z_K[g] )
+//   out[h][c]   = sum_p W[h][p] M_V[p][c] + sum_t p[h][t] s_V[t][g(c)] code_V[t][c] + sum_t p[h][t] z_V[t][g(c)]
+// Both code contractions run as v_mfma_f32_16x16x32_f16.  The 2-bit codes are never converted to
+// floating point: two bit planes are merged into 2-bit fields with two bit-field inserts, and a
+// field masked in place inside the mantissa of an fp16 with exponent field 0 *is* the subnormal
+// number code * 2^(pos-24).  The power of two is folded into the other operand (q*s on the K side,
+// p*s on the V side), which is built in packed fp16.
+//
+// Work split: a workgroup = 4 waves handles one split of one stream; each wave walks its own run
+// of 64-token blocks with its own online-softmax state, and the four states are merged at the end.
+// Lane roles inside a wave (lane = 16*kb + n):
+//   K side  A operand: row n  <-> token 16*(n/4) + 4*x + n%4 of the block (tile x = 0..3),
+//                      lane group kb <-> channels 32*kb .. 32*kb+31 (one plane word per plane)
+//           B operand: column n <-> (head h = n % r, V channel group g = n / r), duplicated over g so
+//                      that the softmax numerators come out of the MFMA already in the lanes that
+//                      need them for the V side;  D: column n, rows 4*kb+i <-> token 16*kb + 4*x + i
+//   V side  A operand: row n = (h, g), lane group kb <-> the 16 tokens of unit kb of the block
+//           B operand: column n <-> channel 16*tile + n, lane group kb <-> the same 16 tokens
+//           D (output accumulators): column n <-> channel 16*tile + n, rows 4*kb+i <-> (h, g) rows
+#include "pk_internal.h"
+
+namespace pk {
+
+namespace {
+
+constexpr int kMaxP = 256;
+constexpr float kLog2e = 1.4426950408889634f;
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float float2v __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint32_t bfi(uint32_t m, uint32_t a, uint32_t b) { return (a & m) | (b & ~m); }
+
+__device__ __forceinline__ floatx4 mfma16(const uint32_t *a, const uint32_t *b, floatx4 c)
+{
+    union { uint32_t u[4]; half8 h; } A, B;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        A.u[i] = a[i];
+        B.u[i] = b[i];
+    }
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(A.h, B.h, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ uint32_t pack2(_Float16 lo, _Float16 hi)
+{
+    half2v v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, v);
+}
+__device__ __forceinline__ uint32_t pk_mul(uint32_t a, uint32_t b)
+{
+    return __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2v, a) * __builtin_bit_cast(half2v, b));
+}
+__device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c)
+{
+    return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, a), __builtin_bit_cast(half2v, b), c, false);
+}
+__device__ __forceinline__ uint32_t cvt2(float lo, float hi)
+{
+    float2v f = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, half2v));
+}
+
+// Sixteen 2-bit fields at the even bit positions of X -> eight operand registers.  Register v
+// holds, in its low half, the field of X-bit e_lo(v) and, in its high half, the field of X-bit
+// e_lo(v) + 16, both at mantissa position pos(v):
+//   v = 0..4: e_lo = 2v, pos = 2v ;  v = 5..7: e_lo = 10 + 2(v-5), pos = 2(v-5).
+__device__ __forceinline__ void fields_to_operand(uint32_t X, uint32_t *out)
+{
+    out[0] = X & 0x00030003u;
+    out[1] = X & 0x000C000Cu;
+    out[2] = X & 0x00300030u;
+    out[3] = X & 0x00C000C0u;
+    out[4] = X & 0x03000300u;
+    const uint32_t Y = X >> 10;
+    out[5] = Y & 0x00030003u;
+    out[6] = Y & 0x000C000Cu;
+    out[7] = Y & 0x00300030u;
+}
+__host__ __device__ constexpr int e_lo(int v) { return v < 5 ? 2 * v : 10 + 2 * (v - 5); }
+__host__ __device__ constexpr int fpos(int v) { return v < 5 ? 2 * v : 2 * (v - 5); }
+
+struct GroupOperand {
+    uint32_t Bq[16];   // q[h][c] * s[g][c] * 2^(8-pos), operand order
+    float qz;          // scale * log2(e) * q_h . z[g]
+};
+
+template <int BITS, bool G32>
+__global__ __launch_bounds__(256) void decode_packed_kernel(DecodeArgs a)
+{
+    constexpr int WPU = BITS / 2;   // 32-bit words per (channel, 16-token unit) of V; K: 4*BITS words per token
+    __shared__ float QMs[kMaxP][16];
+    __shared__ float Ws[4][8][kMaxP];
+    __shared__ float Os[8][kD];
+    __shared__ float stat_m[4][16], stat_l[4][16], stat_pz[4][16];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 15, kb = lane >> 4;
+    const int split = blockIdx.x, ns = blockIdx.y;
+    const int n_slots = a.splits_prefix + a.splits_own + 2;
+    const int seq = ns / a.n_kv_heads, head = ns - seq * a.n_kv_heads;
+    const bool in_prefix = split < a.splits_prefix;
+    const CacheView &cv = in_prefix ? a.prefix : a.own;
+    const int cstream = in_prefix ? head : ns;
+    const int set = in_prefix ? head : a.sets.set_of(ns);
+    const int t_begin = (in_prefix ? split : split - a.splits_prefix) * a.chunk;
+    const int t_end = min(cv.t_quant, t_begin + a.chunk);
+    const int cap = cv.t_capacity;
+
+    const int R = a.n_q_heads / a.n_kv_heads, G = a.G, P = a.P;
+    const int Gc = G < kD ? G : kD, NG = kD / Gc;
+    const bool col_ok = n < R * NG;
+    const int h = col_ok ? n % R : 0, g = col_ok ? n / R : 0;
+    const __half *MK = a.patterns_k + (int64_t)set * P * kD;
+    const float sc2 = a.softmax_scale * kLog2e;
+    const float c1 = sc2 * 65536.f;
+
+    // ---- this lane's slice of its query head: channels 32*kb .. 32*kb+31
+    _Float16 qh[32];
+    {
+        const uint4 *qsrc = reinterpret_cast<const uint4 *>(a.q + ((int64_t)seq * a.n_q_heads + head * R + h) * kD + 32 * kb);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            uint4 v = qsrc[i];
+            if (!col_ok) v = make_uint4(0, 0, 0, 0);
+            const half2v *hv = reinterpret_cast<const half2v *>(&v);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                qh[8 * i + 2 * k] = hv[k][0];
+                qh[8 * i + 2 * k + 1] = hv[k][1];
+            }
+        }
+    }
+    uint32_t qn[16], qp[16];   // natural channel order; operand order with the field scale folded in
+#pragma unroll
+    for (int i = 0; i < 16; ++i) qn[i] = pack2(qh[2 * i], qh[2 * i + 1]);
+#pragma unroll
+    for (int V = 0; V < 16; ++V) {
+        const int v = V & 7, odd = V >> 3;
+        const _Float16 c = (_Float16)(float)(1 << (8 - fpos(v)));
+        qp[V] = pack2(qh[e_lo(v) + odd] * c, qh[e_lo(v) + 16 + odd] * c);
+    }
+
+    // ---- QM[p][n] = scale*log2e * q_h . M_K[p], one 16-pattern tile per wave and round
+    for (int tp = wave; tp * 16 < P; tp += 4) {
+        floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+        const int p = tp * 16 + n;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            uint4 av = make_uint4(0, 0, 0, 0);
+            if (p < P) av = *reinterpret_cast<const uint4 *>(MK + (int64_t)p * kD + 32 * kb + 8 * s);
+            acc = mfma16(reinterpret_cast<const uint32_t *>(&av), &qn[4 * s], acc);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int pr = tp * 16 + 4 * kb + i;
+            if (pr < P) QMs[pr][n] = acc[i] * sc2;
+        }
+    }
+    for (int i = lane; i < 8 * kMaxP; i += 64) (&Ws[wave][0][0])[i] = 0.f;
+    __syncthreads();
+
+    // ---- this wave's run of 64-token blocks
+    const int n_blocks = (t_end - t_begin) >> 6;
+    const int per = (n_blocks + 3) >> 2;
+    const int b0 = wave * per, b1 = min(n_blocks, b0 + per);
+
+    float m_run = -INFINITY, l_run = 0.f, pzacc = 0.f;
+    floatx4 O[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) O[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+    GroupOperand ga, gb;   // gb: second K group of a block, only when G == 32
+    int cur_group = -1;
+
+    auto load_group = [&](int grp, GroupOperand &go) {
+        const int64_t prow = ((int64_t)cstream * (cap / G) + grp) * kD + 32 * kb;
+        const uint4 *sp = reinterpret_cast<const uint4 *>(cv.k_scale + prow);
+        const uint4 *zp = reinterpret_cast<const uint4 *>(cv.k_zero + prow);
+        _Float16 sh[32];
+        float acc = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint4 sv = sp[i], zv = zp[i];
+            const half2v *hv = reinterpret_cast<const half2v *>(&sv);
+            const uint32_t *zu = reinterpret_cast<const uint32_t *>(&zv);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                sh[8 * i + 2 * k] = hv[k][0];
+                sh[8 * i + 2 * k + 1] = hv[k][1];
+                acc = dot2(qn[4 * i + k], zu[k], acc);
+            }
+        }
+#pragma unroll
+        for (int V = 0; V < 16; ++V) {
+            const int v = V & 7, odd = V >> 3;
+            go.Bq[V] = pk_mul(qp[V], pack2(sh[e_lo(v) + odd], sh[e_lo(v) + 16 + odd]));
+        }
+        acc += __shfl_xor(acc, 16);
+        acc += __shfl_xor(acc, 32);
+        go.qz = acc * sc2;
+    };
+
+    const uint32_t *kcodes = cv.k_codes + (int64_t)cstream * cap * 4 * BITS;
+    const uint32_t *vcodes = reinterpret_cast<const uint32_t *>(cv.v_codes) + (int64_t)cstream * cap * (kD * BITS / 32);
+    const __half *vscale = cv.v_scale + (int64_t)cstream * cap * NG;
+    const __half *vzero = cv.v_zero + (int64_t)cstream * cap * NG;
+    const uint8_t *kidx = cv.k_idx + (int64_t)cstream * cap;
+    const uint8_t *vidx = cv.v_idx + (int64_t)cstream * cap;
+
+    for (int b = b0; b < b1; ++b) {
+        const int tb = t_begin + (b << 6);
+        if (G32) {
+            load_group(tb >> 5, ga);
+            load_group((tb >> 5) + 1, gb);
+        } else {
+            const int grp = tb / G;
+            if (grp != cur_group) {
+                load_group(grp, ga);
+                cur_group = grp;
+            }
+        }
+
+        // ---- loads of the block
+        uint32_t kw[4][BITS];
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            const int tok = tb + 16 * (n >> 2) + 4 * x + (n & 3);
+            const uint32_t *src = kcodes + ((int64_t)tok * 4 + kb) * BITS;
+            if (BITS == 2) {
+                const uint2 v = *reinterpret_cast<const uint2 *>(src);
+                kw[x][0] = v.x;
+                kw[x][1] = v.y;
+            } else {
+                const uint4 v = *reinterpret_cast<const uint4 *>(src);
+                kw[x][0] = v.x;
+                kw[x][1] = v.y;
+                kw[x][BITS - 2] = v.z;
+                kw[x][BITS - 1] = v.w;
+            }
+        }
+        const int unit = (tb >> 4) + kb;   // 16-token unit of this lane group
+        const uint4 kid = *reinterpret_cast<const uint4 *>(kidx + tb + 16 * kb);
+        const uint4 vid = *reinterpret_cast<const uint4 *>(vidx + tb + 16 * kb);
+        uint32_t vw[8 * WPU];
+        {
+            const uint4 *src = reinterpret_cast<const uint4 *>(vcodes + ((int64_t)unit * 16 + n) * 8 * WPU);
+#pragma unroll
+            for (int i = 0; i < 2 * WPU; ++i) {
+                const uint4 v = src[i];
+                vw[4 * i] = v.x;
+                vw[4 * i + 1] = v.y;
+                vw[4 * i + 2] = v.z;
+                vw[4 * i + 3] = v.w;
+            }
+        }
+        uint32_t sv[8], zv[8];
+        {
+            const uint4 *sp = reinterpret_cast<const uint4 *>(vscale + ((int64_t)unit * NG + g) * 16);
+            const uint4 *zp = reinterpret_cast<const uint4 *>(vzero + ((int64_t)unit * NG + g) * 16);
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const uint4 s4 = sp[i], z4 = zp[i];
+                sv[4 * i] = s4.x; sv[4 * i + 1] = s4.y; sv[4 * i + 2] = s4.z; sv[4 * i + 3] = s4.w;
+                zv[4 * i] = z4.x; zv[4 * i + 1] = z4.y; zv[4 * i + 2] = z4.z; zv[4 * i + 3] = z4.w;
+            }
+        }
+
+        // ---- K side: scores of the 64 tokens (this lane: column n, tokens 16*kb + 0..15), log2 domain
+        float S[16];
+        const uint32_t kidw[4] = {kid.x, kid.y, kid.z, kid.w};
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            uint32_t A16[16];
+            fields_to_operand(bfi(0x55555555u, kw[x][0], kw[x][1] << 1), A16);
+            fields_to_operand(bfi(0x55555555u, kw[x][0] >> 1, kw[x][1]), A16 + 8);
+            floatx4 d = {0.f, 0.f, 0.f, 0.f}, d2 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < 4; ++s) d = mfma16(&A16[4 * s], &ga.Bq[4 * s], d);
+            if (G32) {
+#pragma unroll
+                for (int s = 0; s < 4; ++s) d2 = mfma16(&A16[4 * s], &gb.Bq[4 * s], d2);
+            }
+            if (BITS == 4) {
+                uint32_t H16[16];
+                fields_to_operand(bfi(0x55555555u, kw[x][BITS - 2], kw[x][BITS - 1] << 1), H16);
+                fields_to_operand(bfi(0x55555555u, kw[x][BITS - 2] >> 1, kw[x][BITS - 1]), H16 + 8);
+                floatx4 e = {0.f, 0.f, 0.f, 0.f}, e2 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int s = 0; s < 4; ++s) e = mfma16(&H16[4 * s], &ga.Bq[4 * s], e);
+                d += 4.f * e;
+                if (G32) {
+#pragma unroll
+                    for (int s = 0; s < 4; ++s) e2 = mfma16(&H16[4 * s], &gb.Bq[4 * s], e2);
+                    d2 += 4.f * e2;
+                }
+            }
+            float qz = ga.qz;
+            if (G32 && kb >= 2) {
+                d = d2;
+                qz = gb.qz;
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int id = (kidw[x] >> (8 * i)) & 255;
+                S[4 * x + i] = fmaf(d[i], c1, QMs[id][n] + qz);
+            }
+        }
+
+        // ---- online softmax (per column; the four lane groups hold different tokens)
+        float mx = S[0];
+#pragma unroll
+        for (int k = 1; k < 16; ++k) mx = fmaxf(mx, S[k]);
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run, mx);
+        if (__ballot(m_new > m_run) != 0ull) {
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);   // 0 on the first block
+            l_run *= alpha;
+            pzacc *= alpha;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float ar = __shfl(alpha, 4 * kb + i);   // column 4*kb+i owns output row 4*kb+i
+#pragma unroll
+                for (int t = 0; t < 8; ++t) O[t][i] *= ar;
+            }
+            for (int hh = 0; hh < R; ++hh) {
+                const float ar = __shfl(alpha, hh);
+                for (int p = lane; p < P; p += 64) Ws[wave][hh][p] *= ar;
+            }
+            m_run = m_new;
+        }
+        float pr[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            pr[k] = __builtin_amdgcn_exp2f(S[k] - m_run);
+            l_run += pr[k];
+        }
+
+        // ---- softmax mass per V pattern (columns of group 0 carry the heads once)
+        if (n < R) {
+            const uint32_t vidw[4] = {vid.x, vid.y, vid.z, vid.w};
+#pragma unroll
+            for (int k = 0; k < 16; ++k) atomicAdd(&Ws[wave][n][(vidw[k >> 2] >> (8 * (k & 3))) & 255], pr[k]);
+        }
+
+        // ---- V side
+        uint32_t Ap[8], Ap4[8];
+#pragma unroll
+        for (int V = 0; V < 8; ++V) {
+            const uint32_t ph = cvt2(pr[2 * V], pr[2 * V + 1]);
+            pzacc = dot2(ph, zv[V], pzacc);
+            const _Float16 c = (_Float16)(float)(1 << (8 - fpos(V)));
+            Ap[V] = pk_mul(pk_mul(ph, sv[V]), pack2(c, c));
+            if (BITS == 4) Ap4[V] = pk_mul(Ap[V], pack2((_Float16)4.f, (_Float16)4.f));
+        }
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            // one word = plane 0 (bits 0..15) and plane 1 (bits 16..31) of 16 tokens of channel 16*t + n;
+            // merge into 2-bit fields: even tokens in the low half, odd tokens in the high half
+            uint32_t Bv[8];
+            {
+                const uint32_t D = vw[t * WPU];
+                const uint32_t u = bfi(0x0000AAAAu, D >> 15, D);
+                fields_to_operand(bfi(0x55550000u, D << 15, u), Bv);
+            }
+            O[t] = mfma16(&Ap[0], &Bv[0], O[t]);
+            O[t] = mfma16(&Ap[4], &Bv[4], O[t]);
+            if (BITS == 4) {
+                const uint32_t D = vw[t * WPU + WPU - 1];
+                const uint32_t u = bfi(0x0000AAAAu, D >> 15, D);
+                fields_to_operand(bfi(0x55550000u, D << 15, u), Bv);
+                O[t] = mfma16(&Ap4[0], &Bv[0], O[t]);
+                O[t] = mfma16(&Ap4[4], &Bv[4], O[t]);
+            }
+        }
+    }
+
+    // ---- merge the four waves of the workgroup
+    l_run += __shfl_xor(l_run, 16);
+    l_run += __shfl_xor(l_run, 32);
+    pzacc += __shfl_xor(pzacc, 16);
+    pzacc += __shfl_xor(pzacc, 32);
+    if (kb == 0) {
+        stat_m[wave][n] = m_run;
+        stat_l[wave][n] = l_run;
+        stat_pz[wave][n] = pzacc;
+    }
+    __syncthreads();
+    for (int w = 0; w < 4; ++w) {
+        if (wave == w) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int rho = 4 * kb + i;
+                if (rho < R * NG) {
+                    const int hh = rho % R, gg = rho / R;
+                    const float M = fmaxf(fmaxf(stat_m[0][rho], stat_m[1][rho]), fmaxf(stat_m[2][rho], stat_m[3][rho]));
+                    const float f = __builtin_amdgcn_exp2f(stat_m[w][rho] - M);
+                    const float pzv = stat_pz[w][rho];
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) {
+                        if ((16 * t) / Gc == gg) {
+                            const float v = f * fmaf(O[t][i], 65536.f, pzv);
+                            float *dst = &Os[hh][16 * t + n];
+                            *dst = w == 0 ? v : *dst + v;
+                        }
+                    }
+                }
+            }
+        }
+        __syncthreads();
+    }
+    const int64_t pbase = ((int64_t)ns * n_slots + split) * R;
+    for (int e = tid; e < R * kD; e += 256) a.part_o[pbase * kD + e] = (&Os[0][0])[e];
+    for (int e = tid; e < R * P; e += 256) {
+        const int hh = e / P, pp = e - hh * P;
+        const float M = fmaxf(fmaxf(stat_m[0][hh], stat_m[1][hh]), fmaxf(stat_m[2][hh], stat_m[3][hh]));
+        float acc = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) acc = fmaf(__builtin_amdgcn_exp2f(stat_m[w][hh] - M), Ws[w][hh][pp], acc);
+        a.part_w[pbase * P + e] = acc;
+    }
+    if (tid < R) {
+        const float M = fmaxf(fmaxf(stat_m[0][tid], stat_m[1][tid]), fmaxf(stat_m[2][tid], stat_m[3][tid]));
+        float L = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) L = fmaf(__builtin_amdgcn_exp2f(stat_m[w][tid] - M), stat_l[w][tid], L);
+        a.part_ml[(pbase + tid) * 2] = M;
+        a.part_ml[(pbase + tid) * 2 + 1] = L;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_decode_packed(const DecodeArgs &a, hipStream_t s)
+{
+    const int splits = a.splits_prefix + a.splits_own;
+    if (splits == 0) return hipSuccess;
+    const dim3 grid(splits, a.n_seq * a.n_kv_heads), block(256);
+    if (a.bits == 2 && a.G == 32)
+        hipLaunchKernelGGL((decode_packed_kernel<2, true>), grid, block, 0, s, a);
+    else if (a.bits == 2)
+        hipLaunchKernelGGL((decode_packed_kernel<2, false>), grid, block, 0, s, a);
+    else if (a.bits == 4 && a.G == 32)
+        hipLaunchKernelGGL((decode_packed_kernel<4, true>), grid, block, 0, s, a);
+    else if (a.bits == 4)
+        hipLaunchKernelGGL((decode_packed_kernel<4, false>), grid, block, 0, s, a);
+    else
+        return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+}  // namespace pk

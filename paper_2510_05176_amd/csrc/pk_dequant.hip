@@ -28,12 +28,12 @@ __global__ __launch_bounds__(128) void dequant_kernel(DequantArgs a)
         a.k_out[orow] = h2f(a.patterns_k[((int64_t)set * a.P + a.c.k_idx[tok]) * kD + c]) + res;
     }
     if (a.v_out) {
-        const uint8_t *vbase = a.c.v_codes + (int64_t)n * a.c.t_capacity * (kD * BITS / 8);
-        const int64_t unit = ((int64_t)(t >> 3) * 16 + (c & 15)) * (kD / 16) + (c >> 4);
+        const uint32_t *vbase = reinterpret_cast<const uint32_t *>(a.c.v_codes) + (int64_t)n * a.c.t_capacity * (kD * BITS / 32);
+        const int64_t word = (((int64_t)(t >> 4) * 16 + (c & 15)) * (kD / 16) + (c >> 4)) * (BITS / 2);
         int code = 0;
 #pragma unroll
-        for (int j = 0; j < BITS; ++j) code |= (int)((vbase[unit * BITS + j] >> (t & 7)) & 1u) << j;
-        const int64_t prow = tok * ng + c / Gc;
+        for (int j = 0; j < BITS; ++j) code |= (int)((vbase[word + j / 2] >> (16 * (j % 2) + (t & 15))) & 1u) << j;
+        const int64_t prow = ((int64_t)n * a.c.t_capacity * ng) + ((int64_t)(t >> 4) * ng + c / Gc) * 16 + (t & 15);
         const float s = h2f(a.c.v_scale[prow]), z = h2f(a.c.v_zero[prow]);
         const float res = s * (float)code + z;
         a.v_out[orow] = h2f(a.patterns_v[((int64_t)set * a.P + a.c.v_idx[tok]) * kD + c]) + res;

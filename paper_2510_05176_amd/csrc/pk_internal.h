@@ -138,8 +138,9 @@ struct DecodeArgs {
     float softmax_scale;
     int32_t chunk;                // packed tokens per split
     int32_t splits_prefix, splits_own;   // packed splits; two more slots hold the tails
-    float *part_o;                // [N][S][r][kD]
-    float *part_ml;               // [N][S][r][2]
+    float *part_o;                // [N][S][r][kD]  unnormalised partial outputs
+    float *part_w;                // [N][S][r][P]   softmax mass per V pattern (packed splits only)
+    float *part_ml;               // [N][S][r][2]   running maximum (log2 domain) and sum
     float *out, *lse;
 };
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t s);

@@ -96,31 +96,32 @@ __global__ __launch_bounds__(128) void quantize_k_kernel(QuantArgs a)
 }
 
 // ---------------------------------------------------------------------------
-// V: one workgroup (128 threads) per (tile of up to 64 tokens, stream).
+// V: one workgroup (128 threads) per (block of 64 tokens, stream).
 // ---------------------------------------------------------------------------
 template <int BITS>
 __global__ __launch_bounds__(128) void quantize_v_kernel(QuantArgs a)
 {
     constexpr int TV = 64;
+    constexpr int WPU = BITS / 2;   // 32-bit words per (channel, 16-token unit)
     __shared__ __align__(16) __half xs[TV * kXsStride];
     __shared__ AssignScratch sc;
     __shared__ int idx_s[TV];
     __shared__ float red_mn[TV][4], red_mx[TV][4];
-    __shared__ __align__(16) uint8_t out_s[TV * kD * BITS / 8];
+    __shared__ __align__(16) uint32_t out_s[TV * kD * BITS / 32];
+    __shared__ __align__(16) unsigned short par_s[2][4 * 4 * 16];   // scale / zero slices: [unit][group][16]
 
     const int tile = blockIdx.x, n = blockIdx.y, tid = threadIdx.x;
-    const int n_tok = min(TV, a.nq - tile * TV);   // 32 or 64
     const __half *Mg = a.patterns + (int64_t)a.sets.set_of(n) * a.P * kD;
 
-    stage_rows(xs, n_tok, [&](int r) { return a.src.row(n, tile * TV + r); });
-    assign_tile<TV>(xs, n_tok, Mg, a.P, a.metric, sc, idx_s, nullptr);
+    stage_rows(xs, TV, [&](int r) { return a.src.row(n, tile * TV + r); });
+    assign_tile<TV>(xs, TV, Mg, a.P, a.metric, sc, idx_s, nullptr);
 
     const int64_t tq = (int64_t)a.t0 + (int64_t)tile * TV;
-    if (tid < n_tok) a.idx[(int64_t)n * a.t_capacity + tq + tid] = (uint8_t)idx_s[tid];
+    if (tid < TV) a.idx[(int64_t)n * a.t_capacity + tq + tid] = (uint8_t)idx_s[tid];
 
     const int c = tid, lane = tid & 63, quarter = tid >> 5;
     // phase A: min / max of every 32-channel quarter of every token
-    for (int t = 0; t < n_tok; ++t) {
+    for (int t = 0; t < TV; ++t) {
         const float r = h2f(xs[t * kXsStride + c]) - h2f(Mg[(int64_t)idx_s[t] * kD + c]);
         float mn = r, mx = r;
 #pragma unroll
@@ -134,14 +135,14 @@ __global__ __launch_bounds__(128) void quantize_v_kernel(QuantArgs a)
         }
     }
     __syncthreads();
-    // phase B: stored parameters, codes, bit planes along the tokens
+    // phase B: stored parameters, codes, bit planes along the tokens (16 tokens per word)
     const int Gc = a.G < kD ? a.G : kD;
     const int ng = kD / Gc, qpg = Gc / 32;   // channel groups per token, quarters per group
     const int grp = c / Gc;
     uint32_t acc[BITS];
 #pragma unroll
     for (int j = 0; j < BITS; ++j) acc[j] = 0;
-    for (int t = 0; t < n_tok; ++t) {
+    for (int t = 0; t < TV; ++t) {
         float mn = red_mn[t][grp * qpg], mx = red_mx[t][grp * qpg];
         for (int k = 1; k < qpg; ++k) {
             mn = fminf(mn, red_mn[t][grp * qpg + k]);
@@ -149,28 +150,33 @@ __global__ __launch_bounds__(128) void quantize_v_kernel(QuantArgs a)
         }
         const GroupParams gp = group_params(mn, mx, BITS);
         if (c % Gc == 0) {
-            const int64_t prow = ((int64_t)n * a.t_capacity + tq + t) * ng + grp;
-            a.scale[prow] = __ushort_as_half(gp.s16);
-            a.zero[prow] = __ushort_as_half(gp.z16);
+            par_s[0][((t >> 4) * ng + grp) * 16 + (t & 15)] = gp.s16;
+            par_s[1][((t >> 4) * ng + grp) * 16 + (t & 15)] = gp.z16;
         }
         const float r = h2f(xs[t * kXsStride + c]) - h2f(Mg[(int64_t)idx_s[t] * kD + c]);
         const int code = quantize_one(r, gp, BITS);
 #pragma unroll
-        for (int j = 0; j < BITS; ++j) acc[j] |= (uint32_t)((code >> j) & 1) << (t & 7);
-        if ((t & 7) == 7) {
-            const int slice = t >> 3;   // 8-token slice inside the tile (4 per 32-token block)
+        for (int j = 0; j < BITS; ++j) acc[j] |= (uint32_t)((code >> j) & 1) << (t & 15);
+        if ((t & 15) == 15) {
+            const int unit = t >> 4;   // 16-token unit inside the block
 #pragma unroll
-            for (int j = 0; j < BITS; ++j) {
-                out_s[((slice * 16 + (c & 15)) * (kD / 16) + (c >> 4)) * BITS + j] = (uint8_t)acc[j];
-                acc[j] = 0;
+            for (int w = 0; w < WPU; ++w) {
+                out_s[((unit * 16 + (c & 15)) * (kD / 16) + (c >> 4)) * WPU + w] = acc[2 * w] | (acc[2 * w + 1] << 16);
+                acc[2 * w] = acc[2 * w + 1] = 0;
             }
         }
     }
     __syncthreads();
-    const int nbytes = n_tok * kD * BITS / 8;
     uint4 *dst = reinterpret_cast<uint4 *>(a.codes_v + ((int64_t)n * a.t_capacity + tq) * (kD * BITS / 8));
     const uint4 *srcp = reinterpret_cast<const uint4 *>(out_s);
-    for (int i = tid; i < nbytes / 16; i += 128) dst[i] = srcp[i];
+    for (int i = tid; i < TV * kD * BITS / 8 / 16; i += 128) dst[i] = srcp[i];
+    // parameters of the block: 4 units x ng groups x 16 tokens, contiguous in memory
+    const int npar = 4 * ng * 16;
+    const int64_t pbase = ((int64_t)n * a.t_capacity + tq) * ng;
+    for (int i = tid; i < npar; i += 128) {
+        a.scale[pbase + i] = __ushort_as_half(par_s[0][i]);
+        a.zero[pbase + i] = __ushort_as_half(par_s[1][i]);
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -209,7 +215,7 @@ hipError_t launch_quantize_k(const QuantArgs &a, hipStream_t s)
 
 hipError_t launch_quantize_v(const QuantArgs &a, hipStream_t s)
 {
-    const dim3 grid((a.nq + 63) / 64, a.n_streams), block(128);
+    const dim3 grid(a.nq / 64, a.n_streams), block(128);
     if (a.bits == 2)
         hipLaunchKernelGGL((quantize_v_kernel<2>), grid, block, 0, s, a);
     else if (a.bits == 4)

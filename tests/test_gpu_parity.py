@@ -53,7 +53,7 @@ def upload(gc, ocache):
 
 def make_case(oracle, pk, seed, *, n_seq=1, hkv=2, hq=2, T=320, P=16, bits=2, G=64, R=0, F=None, metric=0,
               seqs_per_set=0, n_clusters=8, cap=None, mine_iters=3):
-    F = G if F is None else F
+    F = max(G, 64) if F is None else F
     cap = cap if cap is not None else -(-T // F) * F
     kw = dict(n_seq=n_seq, n_kv_heads=hkv, n_q_heads=hq, head_dim=128, n_patterns=P, seqs_per_set=seqs_per_set,
               bits=bits, group=G, recent=R, flush=F, t_capacity=cap, metric=metric)
@@ -106,9 +106,10 @@ def compare_caches(oracle, oc, gc, metric):
             tok_same = np.repeat(grp_same, G, axis=1)
             assert np.array_equal(g["k_codes"][:, :tq][tok_same], oc.k_codes[:, :tq][tok_same])
         else:
-            assert np.array_equal(g["v_scale"][:, :tq][same], oc.v_scale[:, :tq][same])
-            assert np.array_equal(g["v_zero"][:, :tq][same], oc.v_zero[:, :tq][same])
-            bpt = d * b // 8
+            by_tok = lambda arr: arr[:, :tq // 16].transpose(0, 1, 3, 2).reshape(N, tq, -1)   # [N, t/16, groups, 16] -> [N, t, groups]
+            assert np.array_equal(by_tok(g["v_scale"])[same], by_tok(oc.v_scale)[same])
+            assert np.array_equal(by_tok(g["v_zero"])[same], by_tok(oc.v_zero)[same])
+            bpt = d * b // 32
             if not diff.any():
                 assert np.array_equal(g["v_codes"][:, :tq * bpt], oc.v_codes[:, :tq * bpt])   # packed bytes
             for s in range(N):
@@ -137,7 +138,8 @@ def test_quantize_append_parity(oracle, pk, bits, G, P, metric):
     kw, ocfg, gcfg, K, V, Mk, Mv = make_case(oracle, pk, 100 + bits + G + P, T=384 + 17, P=P, bits=bits, G=G,
                                             metric=metric, n_seq=2, hkv=2, hq=2, n_clusters=max(4, min(P, 24)))
     oc, gc, Mkd, Mvd = run_appends(oracle, pk, ocfg, gcfg, K, V, Mk, Mv, [K.shape[2]])
-    assert oc.t_quant == (401 // G) * G and oc.t_tail == 401 - oc.t_quant
+    F = max(G, 64)
+    assert oc.t_quant == (401 // F) * F and oc.t_tail == 401 - oc.t_quant
     n_diff = compare_caches(oracle, oc, gc, metric)
     assert n_diff <= 0.002 * oc.t_quant * ocfg.n_streams * 2 + 2
     # reconstruction (1e-3 absolute on tokens with equal assignment; the arithmetic is in fact identical)
@@ -201,11 +203,13 @@ def test_append_is_reproducible_bit_for_bit(oracle, pk):
     (2, 2, 2, 64, 16, 0, 401),        # r = 1, ragged tail
     (2, 8, 2, 64, 64, 128, 1500),     # r = 4, recent window, several tiles
     (1, 7, 2, 128, 40, 0, 1100),      # r = 7
-    (1, 8, 4, 32, 16, 32, 700),       # r = 8, 4-bit
+    (1, 8, 4, 64, 16, 32, 700),       # r = 8, 4-bit
+    (2, 8, 2, 32, 64, 0, 900),        # r = 4, group 32: four V channel groups, two K groups per 64-token block
+    (1, 4, 4, 32, 16, 0, 333),        # 4-bit with group 32
     (2, 8, 4, 64, 64, 0, 640),        # 4-bit, r = 4, empty tail
 ])
 def test_decode_attention_parity(oracle, pk, hkv, hq, bits, G, P, R, T):
-    kw, ocfg, gcfg, K, V, Mk, Mv = make_case(oracle, pk, 31 + hq + T, T=T, P=P, bits=bits, G=G, R=R, F=G,
+    kw, ocfg, gcfg, K, V, Mk, Mv = make_case(oracle, pk, 31 + hq + T, T=T, P=P, bits=bits, G=G, R=R, F=max(G, 64),
                                             n_seq=2, hkv=hkv, hq=hq, n_clusters=min(P, 16))
     oc, gc, Mkd, Mvd = run_appends(oracle, pk, ocfg, gcfg, K, V, Mk, Mv, [T])
     q = synth.make_queries(3, 2, hq, 128)
@@ -224,6 +228,17 @@ def test_decode_attention_parity(oracle, pk, hkv, hq, bits, G, P, R, T):
     # reproducible
     got3 = pk.pk_decode_attention(gcfg, gc2, dev(q), scale, Mkd, Mvd).cpu().numpy()
     assert np.allclose(got2, got3, rtol=1e-5, atol=1e-6)
+
+
+def test_decode_unsupported_head_group_combination(oracle, pk):
+    # r * (V channel groups per token) must fit the 16 rows of one matrix-core tile
+    cfg = pk.Config(n_seq=1, n_kv_heads=1, n_q_heads=8, n_patterns=8, bits=2, group=32, flush=64, t_capacity=64)
+    cache = pk.Cache(cfg)
+    q = torch.zeros((1, 8, 128), dtype=torch.float16, device="cuda")
+    M = torch.zeros((1, 8, 128), dtype=torch.float16, device="cuda")
+    with pytest.raises(pk.PkError) as e:
+        pk.pk_decode_attention(cfg, cache, q, 0.1, M, M)
+    assert e.value.status == 2
 
 
 def test_decode_tail_only_and_empty_context(oracle, pk):
@@ -343,7 +358,7 @@ def test_config1_smoke_full_path(oracle, pk):
     spec = synth.SPECS["cfg1"]
     K, V = synth.make_kv(0, spec)
     kw = dict(n_seq=1, n_kv_heads=1, n_q_heads=1, head_dim=128, n_patterns=16, seqs_per_set=0, bits=4, group=32,
-              recent=0, flush=32, t_capacity=1024, metric=0)
+              recent=0, flush=64, t_capacity=1024, metric=0)
     ocfg, gcfg = oracle.Config(**kw), pk.Config(**kw)
     Mk_o, _, _, _ = oracle.mine(K[0].view(np.uint16), 16, 10)
     Mv_o, _, _, _ = oracle.mine(V[0].view(np.uint16), 16, 10)

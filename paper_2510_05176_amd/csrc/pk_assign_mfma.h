@@ -1,0 +1,194 @@
+// Nearest-pattern search under the Euclidean metric on the matrix cores (Sec. 3.1 Eq. 4 assignment
+// step; Sec. 3.2 Eq. 6 argmin in L2 mode).
+//
+// Ranking uses ||m||^2 - 2 x.m from v_mfma_f32_16x16x32_f16 (fp16 products are exact in fp32; only
+// the accumulation rounds).  The smallest and second smallest value are tracked; a token whose gap
+// between the two is not safely above the rounding error of that form is re-evaluated exactly,
+// sum_c (x_c - m_c)^2 in binary32 over all patterns, lowest index on ties.  A token that is not
+// re-evaluated has a gap larger than any possible ranking error, so the result always equals the
+// exact argmin.
+//
+// Operand layout (lane = 16*kb + n):  A = patterns, row n of the 16-pattern tile, K-step s covers
+// channels 32*s + 8*kb + j;  B = vectors, column n = token n of the 16-token tile, same channels;
+// D: column n = token, rows 4*kb + i = patterns 16*tile + 4*kb + i.
+#pragma once
+
+#include "pk_internal.h"
+
+namespace pk {
+
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef float floatx4_t __attribute__((ext_vector_type(4)));
+
+constexpr int kTabStride = kD + 8;   // halves per pattern row in LDS (272 B: 16-byte aligned, spreads banks)
+
+struct PatternTable {
+    const __half *lds_rows;   // LDS copy, row stride kTabStride (used when the kernel is built with TAB_LDS)
+    const __half *glb_rows;   // global table, row stride kD
+    const float *norm2;       // LDS [P]: ||m_p||^2
+    float norm2_max;
+    int P;
+};
+
+__device__ __forceinline__ floatx4_t mfma_f16(const uint4 &a, const uint4 &b, floatx4_t c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, a), __builtin_bit_cast(half8_t, b), c, 0, 0, 0);
+}
+
+// Stage a pattern table into LDS (256 threads) and compute the row norms.  Ends with a barrier.
+__device__ __forceinline__ void stage_patterns(const __half *Mg, int P, __half *tab_s, float *norm_s, float *red_s,
+                                               bool to_lds)
+{
+    const int tid = threadIdx.x;
+    if (to_lds) {
+        for (int i = tid; i < P * kRowChunks; i += 256) {
+            const int r = i >> 4, ch = i & 15;
+            *reinterpret_cast<uint4 *>(tab_s + r * kTabStride + ch * 8) =
+                *reinterpret_cast<const uint4 *>(Mg + (int64_t)r * kD + ch * 8);
+        }
+    }
+    float mx = 0.f;
+    for (int p = tid; p < P; p += 256) {
+        float acc = 0.f;
+        for (int ch = 0; ch < kRowChunks; ++ch) {
+            const uint4 v = *reinterpret_cast<const uint4 *>(Mg + (int64_t)p * kD + ch * 8);
+            const half2_t *h = reinterpret_cast<const half2_t *>(&v);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float a = (float)h[k][0], b = (float)h[k][1];
+                acc = fmaf(a, a, fmaf(b, b, acc));
+            }
+        }
+        norm_s[p] = acc;
+        mx = fmaxf(mx, acc);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+    if ((tid & 63) == 0) red_s[tid >> 6] = mx;
+    __syncthreads();
+}
+
+// One 16-token tile held as B operand xb[4] (K-step s in xb[s]).  Returns, in every lane of column n:
+// best index / value (without the ||x||^2 term) and whether the token needs the exact re-evaluation.
+template <bool TAB_LDS>
+__device__ __forceinline__ void assign_tile_mfma(const uint4 (&xb)[4], const PatternTable &tb, int lane, int &best_i,
+                                                 float &best_v, float &x2, bool &flag)
+{
+    const int n = lane & 15, kb = lane >> 4;
+    float b1 = INFINITY, b2 = INFINITY;
+    int i1 = 0;
+    for (int p0 = 0; p0 < tb.P; p0 += 16) {
+        floatx4_t d = {0.f, 0.f, 0.f, 0.f};
+        const int prow = min(p0 + n, tb.P - 1);   // rows past the table repeat the last pattern; masked below
+        const __half *arow = TAB_LDS ? tb.lds_rows + prow * kTabStride + 8 * kb : tb.glb_rows + (int64_t)prow * kD + 8 * kb;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) d = mfma_f16(*reinterpret_cast<const uint4 *>(arow + 32 * s), xb[s], d);
+        const int pr = p0 + 4 * kb;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float v = pr + i < tb.P ? fmaf(-2.f, d[i], tb.norm2[pr + i]) : INFINITY;
+            b2 = fminf(b2, fmaxf(b1, v));
+            if (v < b1) {   // rows are visited in increasing pattern order within a lane
+                b1 = v;
+                i1 = pr + i;
+            }
+        }
+    }
+    // merge the four lane groups of the column
+#pragma unroll
+    for (int off = 16; off <= 32; off <<= 1) {
+        const float o1 = __shfl_xor(b1, off), o2 = __shfl_xor(b2, off);
+        const int oi = __shfl_xor(i1, off);
+        b2 = fminf(fminf(b2, o2), fmaxf(b1, o1));
+        if (o1 < b1 || (o1 == b1 && oi < i1)) {
+            b1 = o1;
+            i1 = oi;
+        }
+    }
+    // ||x||^2 of the token (for the error bound and for the distance itself)
+    float xx = 0.f;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        const half2_t *h = reinterpret_cast<const half2_t *>(&xb[s]);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) xx = __builtin_amdgcn_fdot2(h[k], h[k], xx, false);
+    }
+    xx += __shfl_xor(xx, 16);
+    xx += __shfl_xor(xx, 32);
+    best_i = i1;
+    best_v = b1;
+    x2 = xx;
+    // accumulation error of x.m is far below 2^-20 (|x|^2 + |m|^2); flag with a wide margin.
+    // A single pattern has nothing to be confused with.
+    flag = tb.P > 1 && !(b2 - b1 > 7.62939453125e-06f * (xx + tb.norm2_max));
+}
+
+// Exact re-evaluation of one token by a whole wave: xrow_s = its 128 channels (fp16) in LDS.
+// Every lane returns the exact argmin (lowest index on ties) and its distance.
+__device__ __forceinline__ void exact_argmin_wave(const __half *xrow_s, const PatternTable &tb, const __half *Mg,
+                                                  int lane, int &best_i, float &best_d)
+{
+    float bd = INFINITY;
+    int bi = 0x7fffffff;
+    for (int p = lane; p < tb.P; p += 64) {
+        const __half *m = Mg + (int64_t)p * kD;
+        float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+        for (int ch = 0; ch < kRowChunks; ++ch) {
+            const uint4 mv = *reinterpret_cast<const uint4 *>(m + ch * 8);
+            const uint4 xv = *reinterpret_cast<const uint4 *>(xrow_s + ch * 8);
+            const half2_t *mh = reinterpret_cast<const half2_t *>(&mv);
+            const half2_t *xh = reinterpret_cast<const half2_t *>(&xv);
+            const float d0 = (float)xh[0][0] - (float)mh[0][0], d1 = (float)xh[0][1] - (float)mh[0][1];
+            const float d2 = (float)xh[1][0] - (float)mh[1][0], d3 = (float)xh[1][1] - (float)mh[1][1];
+            const float d4 = (float)xh[2][0] - (float)mh[2][0], d5 = (float)xh[2][1] - (float)mh[2][1];
+            const float d6 = (float)xh[3][0] - (float)mh[3][0], d7 = (float)xh[3][1] - (float)mh[3][1];
+            a0 = fmaf(d0, d0, a0); a1 = fmaf(d1, d1, a1); a2 = fmaf(d2, d2, a2); a3 = fmaf(d3, d3, a3);
+            a0 = fmaf(d4, d4, a0); a1 = fmaf(d5, d5, a1); a2 = fmaf(d6, d6, a2); a3 = fmaf(d7, d7, a3);
+        }
+        const float dist = (a0 + a1) + (a2 + a3);
+        if (dist < bd) {
+            bd = dist;
+            bi = p;
+        }
+    }
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const float od = __shfl_xor(bd, off);
+        const int oi = __shfl_xor(bi, off);
+        if (od < bd || (od == bd && oi < bi)) {
+            bd = od;
+            bi = oi;
+        }
+    }
+    best_i = bi;
+    best_d = bd;
+}
+
+// Re-evaluate the flagged tokens of a tile.  xrow_s: per-wave LDS scratch of kD halves.
+__device__ __forceinline__ void resolve_flagged(const uint4 (&xb)[4], bool flag, __half *xrow_s, const PatternTable &tb,
+                                                const __half *Mg, int lane, int &best_i, float &best_d)
+{
+    const int n = lane & 15, kb = lane >> 4;
+    unsigned long long todo = __ballot(flag) & 0xffffull;   // one bit per column
+    while (todo) {
+        const int col = __ffsll((long long)todo) - 1;
+        todo &= todo - 1;
+        if (n == col) {
+#pragma unroll
+            for (int s = 0; s < 4; ++s) *reinterpret_cast<uint4 *>(xrow_s + 32 * s + 8 * kb) = xb[s];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        int bi;
+        float bd;
+        exact_argmin_wave(xrow_s, tb, Mg, lane, bi, bd);
+        if (n == col) {
+            best_i = bi;
+            best_d = bd;
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+}  // namespace pk

@@ -1,7 +1,10 @@
-// Pattern mining: Lloyd iterations for the K-means objective of Sec. 3.1 Eq. 4,
-// one independent problem per pattern set (layer x KV head, K and V separately).
+// Pattern mining: Lloyd iterations for the K-means objective of Sec. 3.1 Eq. 4, one independent
+// problem per pattern set (layer x KV head, K and V separately).
+//
+// One iteration = mine_step_kernel (assignment step on the matrix cores + per-chunk cluster sums in
+// LDS) followed by mine_update_kernel (fixed-order reduction over the chunks, mean, fp16 rounding).
 // Every sum is formed in a fixed order, so results are reproducible bit for bit.
-#include "pk_assign.h"
+#include "pk_assign_mfma.h"
 #include "pk_internal.h"
 
 namespace pk {
@@ -19,51 +22,70 @@ __global__ __launch_bounds__(256) void mine_init_kernel(MineArgs a)
     *reinterpret_cast<uint4 *>(a.patterns + ((int64_t)s * a.P + p) * kD + ch * 8) = v;
 }
 
-// assignment step: nearest centroid of each of 128 vectors per workgroup
-__global__ __launch_bounds__(128) void mine_assign_kernel(MineArgs a)
+// Assignment step + partial cluster sums of one chunk of one set.  256 threads.
+// Dynamic LDS: [table (TAB_LDS only)] [norm2 P] [sums P*kD] [cnt P] [idx chunk bytes] [xrow 4*kD halves]
+template <bool TAB_LDS>
+__global__ __launch_bounds__(256) void mine_step_kernel(MineArgs a, int chunk)
 {
-    __shared__ __align__(16) __half xs[128 * kXsStride];
-    __shared__ AssignScratch sc;
-    __shared__ int idx_s[128];
-    __shared__ float best_s[128];
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int P = a.P;
+    __half *tab_s = reinterpret_cast<__half *>(smem);
+    float *norm_s = reinterpret_cast<float *>(smem + (TAB_LDS ? (size_t)P * kTabStride * 2 : 0));
+    float *sums = norm_s + P;
+    int *cnt = reinterpret_cast<int *>(sums + (size_t)P * kD);
+    uint8_t *idx_s = reinterpret_cast<uint8_t *>(cnt + P);
+    __half *xrow_s = reinterpret_cast<__half *>(idx_s + chunk);
+    __shared__ float red_s[4];
 
-    const int tile = blockIdx.x, s = blockIdx.y, tid = threadIdx.x;
-    const int n_tok = min(128, a.T - tile * 128);
-    const __half *xg = a.x + (int64_t)s * a.set_stride + (int64_t)tile * 128 * kD;
-    stage_rows(xs, n_tok, [&](int r) { return xg + (int64_t)r * kD; });
-    assign_tile<128>(xs, n_tok, a.patterns + (int64_t)s * a.P * kD, a.P, PK_METRIC_L2, sc, idx_s, best_s);
-    if (tid < n_tok) {
-        a.assign[(int64_t)s * a.T + tile * 128 + tid] = idx_s[tid];
-        a.best[(int64_t)s * a.T + tile * 128 + tid] = best_s[tid];
-    }
-}
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 15, kb = lane >> 4;
+    const int ck = blockIdx.x, s = blockIdx.y;
+    const int t_begin = ck * chunk, n_tok = min(chunk, a.T - t_begin);
+    const __half *xg = a.x + (int64_t)s * a.set_stride + (int64_t)t_begin * kD;
+    const __half *Mg = a.patterns + (int64_t)s * P * kD;
 
-// partial sums of the members of cluster p inside one slice of the token range;
-// thread <-> channel, tokens visited in increasing order
-__global__ __launch_bounds__(128) void mine_sum_kernel(MineArgs a)
-{
-    __shared__ int as[128];
-    const int p = blockIdx.x, ts = blockIdx.y, s = blockIdx.z, c = threadIdx.x;
-    const int len = (a.T + a.tsplit - 1) / a.tsplit;
-    const int t_begin = ts * len, t_end = min(a.T, t_begin + len);
-    const int32_t *asg = a.assign + (int64_t)s * a.T;
-    const __half *xg = a.x + (int64_t)s * a.set_stride;
-    float sum = 0.f;
-    int cnt = 0;
-    for (int base = t_begin; base < t_end; base += 128) {
-        __syncthreads();
-        as[c] = base + c < t_end ? asg[base + c] : -1;
-        __syncthreads();
-        for (int k = 0; k < 128; ++k) {
-            if (as[k] == p) {
-                sum += h2f(xg[(int64_t)(base + k) * kD + c]);
-                ++cnt;
-            }
+    for (int i = tid; i < P * kD; i += 256) sums[i] = 0.f;
+    for (int i = tid; i < P; i += 256) cnt[i] = 0;
+    stage_patterns(Mg, P, tab_s, norm_s, red_s, TAB_LDS);   // ends with a barrier
+    PatternTable tb;
+    tb.lds_rows = tab_s;
+    tb.glb_rows = Mg;
+    tb.norm2 = norm_s;
+    tb.norm2_max = fmaxf(fmaxf(red_s[0], red_s[1]), fmaxf(red_s[2], red_s[3]));
+    tb.P = P;
+
+    // ---- assignment: wave w takes the 16-token tiles w, w+4, ...
+    const int n_tiles = (n_tok + 15) >> 4;
+    for (int tile = wave; tile < n_tiles; tile += 4) {
+        const int tok = tile * 16 + n;
+        const int tok_c = min(tok, n_tok - 1);
+        uint4 xb[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) xb[k] = *reinterpret_cast<const uint4 *>(xg + (int64_t)tok_c * kD + 32 * k + 8 * kb);
+        int bi;
+        float bv, x2, bd;
+        bool flag;
+        assign_tile_mfma<TAB_LDS>(xb, tb, lane, bi, bv, x2, flag);
+        bd = fmaxf(bv + x2, 0.f);
+        resolve_flagged(xb, flag, xrow_s + wave * kD, tb, Mg, lane, bi, bd);
+        if (kb == 0 && tok < n_tok) {
+            idx_s[tok] = (uint8_t)bi;
+            a.assign[(int64_t)s * a.T + t_begin + tok] = bi;
+            a.best[(int64_t)s * a.T + t_begin + tok] = bd;
         }
     }
-    const int64_t o = ((int64_t)s * a.tsplit + ts) * a.P + p;
-    a.psum[o * kD + c] = sum;
-    if (c == 0) a.pcnt[o] = cnt;
+    __syncthreads();
+
+    // ---- cluster sums of the chunk: thread <-> channel, vectors in increasing order
+    if (tid < kD) {
+        const int c = tid;
+        for (int t = 0; t < n_tok; ++t) atomicAdd(&sums[idx_s[t] * kD + c], h2f(xg[(int64_t)t * kD + c]));
+    } else if (tid == kD) {
+        for (int t = 0; t < n_tok; ++t) cnt[idx_s[t]] += 1;
+    }
+    __syncthreads();
+    const int64_t o = ((int64_t)s * a.tsplit + ck) * P;
+    for (int i = tid; i < P * kD; i += 256) a.psum[o * kD + i] = sums[i];
+    for (int i = tid; i < P; i += 256) a.pcnt[o + i] = cnt[i];
 }
 
 // update step: centroid = mean of members (binary32 division), rounded to fp16;
@@ -98,32 +120,51 @@ __global__ __launch_bounds__(256) void mine_inertia_kernel(MineArgs a, int it)
     if (tid == 0) a.inertia[(int64_t)s * a.iters + it] = red[0];
 }
 
+size_t step_lds_bytes(int P, int chunk, bool tab_lds)
+{
+    size_t b = tab_lds ? (size_t)P * kTabStride * 2 : 0;
+    b += (size_t)P * 4 + (size_t)P * kD * 4 + (size_t)P * 4 + (size_t)chunk + 4 * kD * 2;
+    return (b + 15) / 16 * 16;
+}
+
 }  // namespace
 
-int mine_tsplit(int T)
+int mine_chunk(int T)
 {
-    int ts = T / 2048;
-    if (ts < 1) ts = 1;
-    if (ts > 16) ts = 16;
-    return ts;
+    int c = (T / 64 + 255) / 256 * 256;   // at most 64 chunks per set
+    if (c < 256) c = 256;
+    return c;
 }
+
+int mine_tsplit(int T) { return (T + mine_chunk(T) - 1) / mine_chunk(T); }
 
 hipError_t launch_mine(const MineArgs &a, hipStream_t s)
 {
     hipError_t e;
+    const int chunk = mine_chunk(a.T);
+    const bool tab_lds = a.P <= 128;
+    const size_t lds = step_lds_bytes(a.P, chunk, tab_lds);
+    if (tab_lds)
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&mine_step_kernel<true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    else
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&mine_step_kernel<false>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
     if (!a.init_given) {
         hipLaunchKernelGGL(mine_init_kernel, dim3((a.P * kRowChunks + 255) / 256, a.n_sets), dim3(256), 0, s, a);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     for (int it = 0; it < a.iters; ++it) {
-        hipLaunchKernelGGL(mine_assign_kernel, dim3((a.T + 127) / 128, a.n_sets), dim3(128), 0, s, a);
+        if (tab_lds)
+            hipLaunchKernelGGL((mine_step_kernel<true>), dim3(a.tsplit, a.n_sets), dim3(256), lds, s, a, chunk);
+        else
+            hipLaunchKernelGGL((mine_step_kernel<false>), dim3(a.tsplit, a.n_sets), dim3(256), lds, s, a, chunk);
         if ((e = hipGetLastError()) != hipSuccess) return e;
         if (a.inertia) {
             hipLaunchKernelGGL(mine_inertia_kernel, dim3(a.n_sets), dim3(256), 0, s, a, it);
             if ((e = hipGetLastError()) != hipSuccess) return e;
         }
-        hipLaunchKernelGGL(mine_sum_kernel, dim3(a.P, a.tsplit, a.n_sets), dim3(128), 0, s, a);
-        if ((e = hipGetLastError()) != hipSuccess) return e;
         hipLaunchKernelGGL(mine_update_kernel, dim3(a.P, a.n_sets), dim3(128), 0, s, a);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }

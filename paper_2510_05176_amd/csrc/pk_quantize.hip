@@ -10,6 +10,7 @@
 #pragma clang fp contract(off)
 
 #include "pk_assign.h"
+#include "pk_assign_mfma.h"
 #include "pk_internal.h"
 
 namespace pk {
@@ -46,7 +47,7 @@ __device__ __forceinline__ int quantize_one(float r, const GroupParams &g, int b
 // K: one workgroup (128 threads) per (group of G tokens, stream).
 // ---------------------------------------------------------------------------
 template <int G, int BITS>
-__global__ __launch_bounds__(128) void quantize_k_kernel(QuantArgs a)
+__global__ __launch_bounds__(128) void quantize_k_valu_kernel(QuantArgs a)
 {
     __shared__ __align__(16) __half xs[G * kXsStride];
     __shared__ AssignScratch sc;
@@ -99,7 +100,7 @@ __global__ __launch_bounds__(128) void quantize_k_kernel(QuantArgs a)
 // V: one workgroup (128 threads) per (block of 64 tokens, stream).
 // ---------------------------------------------------------------------------
 template <int BITS>
-__global__ __launch_bounds__(128) void quantize_v_kernel(QuantArgs a)
+__global__ __launch_bounds__(128) void quantize_v_valu_kernel(QuantArgs a)
 {
     constexpr int TV = 64;
     constexpr int WPU = BITS / 2;   // 32-bit words per (channel, 16-token unit)
@@ -179,6 +180,274 @@ __global__ __launch_bounds__(128) void quantize_v_kernel(QuantArgs a)
     }
 }
 
+
+// ===========================================================================
+// Euclidean metric: nearest pattern on the matrix cores (pk_assign_mfma.h), then residuals are
+// staged in LDS as binary32 and quantized with one thread per channel (K) or per token (V), so
+// that the group minimum / maximum is a sequential scan inside a thread and every bit plane is
+// one ballot across the lanes.
+// ===========================================================================
+
+constexpr int kRStride = kD + 4;   // floats per row of the residual tile (16-byte aligned rows)
+constexpr float kRoundMagic = 8388608.f;   // y + 2^23 has rint(y) in its low mantissa bits (0 <= y < 2^22)
+
+// v_writelane_b32: put the wave-uniform value `v` into lane `lane` of a register, keep the other lanes.
+extern "C" __device__ int pk_llvm_writelane(int, int, int) __asm("llvm.amdgcn.writelane.i32");
+__device__ __forceinline__ uint32_t write_lane(uint32_t v, int lane, uint32_t old)
+{
+    return (uint32_t)pk_llvm_writelane((int)v, lane, (int)old);
+}
+
+// Code of one residual from the stored parameters: the low bits of the returned word.
+__device__ __forceinline__ uint32_t code_word(float r, const GroupParams &g)
+{
+    const float y = (r - g.z) * g.inv;       // in [0, 2^b - 1] up to rounding, see the header of the format
+    return __float_as_uint(y + kRoundMagic); // round half to even, as rintf
+}
+
+struct TileShared {
+    // carved from dynamic LDS by the kernels below
+    __half *tab;     // [P][kTabStride]   (TAB_LDS only)
+    float *norm;     // [P]
+    float *rt;       // [TT][kRStride]
+    __half *xrow;    // [4][kD]
+    float *stat;     // K: [2][2][kD]; V: [64][4][2]
+    int *idx;        // [TT]
+};
+
+template <int TT, bool TAB_LDS>
+__device__ __forceinline__ TileShared carve(unsigned char *smem, int P)
+{
+    TileShared t;
+    size_t o = 0;
+    t.tab = reinterpret_cast<__half *>(smem);
+    if (TAB_LDS) o += (size_t)P * kTabStride * 2;
+    t.norm = reinterpret_cast<float *>(smem + o);
+    o += (size_t)((P + 3) / 4 * 4) * 4;
+    t.rt = reinterpret_cast<float *>(smem + o);
+    o += (size_t)TT * kRStride * 4;
+    t.xrow = reinterpret_cast<__half *>(smem + o);
+    o += 4 * kD * 2;
+    t.stat = reinterpret_cast<float *>(smem + o);
+    o += 512 * 4;
+    t.idx = reinterpret_cast<int *>(smem + o);
+    return t;
+}
+template <int TT>
+size_t tile_lds_bytes(int P, bool tab_lds)
+{
+    return (tab_lds ? (size_t)P * kTabStride * 2 : 0) + (size_t)((P + 3) / 4 * 4) * 4 + (size_t)TT * kRStride * 4 + 4 * kD * 2 +
+           512 * 4 + TT * 4;
+}
+
+// Assign the NT 16-token tiles of this wave, write the indices, stage the residuals.
+// i0 = logical index of the first vector of the workgroup's tile; tq0 = its packed position.
+template <int NT, bool TAB_LDS>
+__device__ __forceinline__ void assign_and_stage(const QuantArgs &a, const TileShared &sh, const PatternTable &tb,
+                                                 const __half *Mg, int ns, int i0, int64_t tq0)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n = lane & 15, kb = lane >> 4;
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+        const int tl = (wave * NT + j) * 16 + n;   // token slot inside the tile
+        const __half *row = a.src.row(ns, i0 + tl);
+        uint4 xb[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) xb[k] = *reinterpret_cast<const uint4 *>(row + 32 * k + 8 * kb);
+        int bi;
+        float bv, x2, bd;
+        bool flag;
+        assign_tile_mfma<TAB_LDS>(xb, tb, lane, bi, bv, x2, flag);
+        resolve_flagged(xb, flag, sh.xrow + wave * kD, tb, Mg, lane, bi, bd);
+        if (kb == 0) {
+            sh.idx[tl] = bi;
+            a.idx[(int64_t)ns * a.t_capacity + tq0 + tl] = (uint8_t)bi;
+        }
+        // residual r = x - M[k*] of this lane's 32 channels, one binary32 subtraction each
+        const __half *mrow = TAB_LDS ? sh.tab + bi * kTabStride + 8 * kb : Mg + (int64_t)bi * kD + 8 * kb;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const uint4 mv = *reinterpret_cast<const uint4 *>(mrow + 32 * k);
+            const half2_t *xh = reinterpret_cast<const half2_t *>(&xb[k]);
+            const half2_t *mh = reinterpret_cast<const half2_t *>(&mv);
+            float4 r0, r1;
+            r0.x = (float)xh[0][0] - (float)mh[0][0];
+            r0.y = (float)xh[0][1] - (float)mh[0][1];
+            r0.z = (float)xh[1][0] - (float)mh[1][0];
+            r0.w = (float)xh[1][1] - (float)mh[1][1];
+            r1.x = (float)xh[2][0] - (float)mh[2][0];
+            r1.y = (float)xh[2][1] - (float)mh[2][1];
+            r1.z = (float)xh[3][0] - (float)mh[3][0];
+            r1.w = (float)xh[3][1] - (float)mh[3][1];
+            float4 *dst = reinterpret_cast<float4 *>(sh.rt + tl * kRStride + 32 * k + 8 * kb);
+            dst[0] = r0;
+            dst[1] = r1;
+        }
+    }
+}
+
+// K: workgroup = 256 threads, tiles of TT = max(64, G) tokens of one stream.
+template <int G, int BITS, bool TAB_LDS>
+__global__ __launch_bounds__(256) void quantize_k_kernel(QuantArgs a, int tiles_per_wg)
+{
+    constexpr int TT = G == 128 ? 128 : 64, NT = TT / 64, HT = TT / 2;
+    extern __shared__ __align__(16) unsigned char smem[];
+    __shared__ float red_s[4];
+    const TileShared sh = carve<TT, TAB_LDS>(smem, a.P);
+    const int tid = threadIdx.x, ns = blockIdx.y;
+    const __half *Mg = a.patterns + (int64_t)a.sets.set_of(ns) * a.P * kD;
+    stage_patterns(Mg, a.P, sh.tab, sh.norm, red_s, TAB_LDS);
+    PatternTable tb;
+    tb.lds_rows = sh.tab;
+    tb.glb_rows = Mg;
+    tb.norm2 = sh.norm;
+    tb.norm2_max = fmaxf(fmaxf(red_s[0], red_s[1]), fmaxf(red_s[2], red_s[3]));
+    tb.P = a.P;
+
+    const int n_tiles = a.nq / TT;
+    const int c = tid & 127, half = tid >> 7, lane = tid & 63, chw = (tid >> 6) & 1;
+    for (int tile = blockIdx.x * tiles_per_wg; tile < min(n_tiles, (int)(blockIdx.x + 1) * tiles_per_wg); ++tile) {
+        const int i0 = tile * TT;
+        const int64_t tq0 = (int64_t)a.t0 + i0;
+        assign_and_stage<NT, TAB_LDS>(a, sh, tb, Mg, ns, i0, tq0);
+        __syncthreads();
+
+        // thread <-> (channel c, token half): scan HT tokens
+        float r[HT];
+        float mn = INFINITY, mx = -INFINITY;
+#pragma unroll
+        for (int t = 0; t < HT; ++t) {
+            r[t] = sh.rt[(half * HT + t) * kRStride + c];
+            mn = fminf(mn, r[t]);
+            mx = fmaxf(mx, r[t]);
+        }
+        if (G > HT) {   // the group spans both halves
+            sh.stat[(half * 2 + 0) * kD + c] = mn;
+            sh.stat[(half * 2 + 1) * kD + c] = mx;
+            __syncthreads();
+            mn = fminf(mn, sh.stat[((half ^ 1) * 2 + 0) * kD + c]);
+            mx = fmaxf(mx, sh.stat[((half ^ 1) * 2 + 1) * kD + c]);
+        }
+        const GroupParams gp = group_params(mn, mx, BITS);
+        if (G <= HT || half == 0) {
+            const int64_t grow = ((int64_t)ns * (a.t_capacity / G) + tq0 / G + (G <= HT ? half : 0)) * kD + c;
+            a.scale[grow] = __ushort_as_half(gp.s16);
+            a.zero[grow] = __ushort_as_half(gp.z16);
+        }
+        // codes; one ballot per plane gives the plane words of 64 channels; lane t collects token t
+        uint32_t wacc[2][BITS];
+#pragma unroll
+        for (int j = 0; j < BITS; ++j) wacc[0][j] = wacc[1][j] = 0;
+#pragma unroll
+        for (int t = 0; t < HT; ++t) {
+            const uint32_t ub = code_word(r[t], gp);
+#pragma unroll
+            for (int j = 0; j < BITS; ++j) {
+                const unsigned long long m = __ballot((ub >> j) & 1u);
+                wacc[0][j] = write_lane((uint32_t)m, t, wacc[0][j]);
+                wacc[1][j] = write_lane((uint32_t)(m >> 32), t, wacc[1][j]);
+            }
+        }
+        if (lane < HT) {
+            uint32_t *dst = a.codes_k + (((int64_t)ns * a.t_capacity + tq0 + half * HT + lane) * 4 + 2 * chw) * BITS;
+            if (BITS == 2) {
+                *reinterpret_cast<uint4 *>(dst) = make_uint4(wacc[0][0], wacc[0][1], wacc[1][0], wacc[1][1]);
+            } else {
+                reinterpret_cast<uint4 *>(dst)[0] = make_uint4(wacc[0][0], wacc[0][1], wacc[0][BITS - 2], wacc[0][BITS - 1]);
+                reinterpret_cast<uint4 *>(dst)[1] = make_uint4(wacc[1][0], wacc[1][1], wacc[1][BITS - 2], wacc[1][BITS - 1]);
+            }
+        }
+        __syncthreads();   // residual tile and statistics are reused by the next tile
+    }
+}
+
+// V: workgroup = 256 threads, blocks of 64 tokens of one stream; wave w owns channels 32w..32w+31,
+// lane t owns token t.
+template <int BITS, bool TAB_LDS>
+__global__ __launch_bounds__(256) void quantize_v_kernel(QuantArgs a, int tiles_per_wg)
+{
+    constexpr int TT = 64, WPU = BITS / 2;
+    extern __shared__ __align__(16) unsigned char smem[];
+    __shared__ float red_s[4];
+    const TileShared sh = carve<TT, TAB_LDS>(smem, a.P);
+    const int tid = threadIdx.x, ns = blockIdx.y;
+    const __half *Mg = a.patterns + (int64_t)a.sets.set_of(ns) * a.P * kD;
+    stage_patterns(Mg, a.P, sh.tab, sh.norm, red_s, TAB_LDS);
+    PatternTable tb;
+    tb.lds_rows = sh.tab;
+    tb.glb_rows = Mg;
+    tb.norm2 = sh.norm;
+    tb.norm2_max = fmaxf(fmaxf(red_s[0], red_s[1]), fmaxf(red_s[2], red_s[3]));
+    tb.P = a.P;
+
+    const int Gc = a.G < kD ? a.G : kD, ng = kD / Gc, qpg = Gc / 32;
+    const int n_tiles = a.nq / TT;
+    const int t = tid & 63, w = tid >> 6;
+    const int grp = (32 * w) / Gc;
+    for (int tile = blockIdx.x * tiles_per_wg; tile < min(n_tiles, (int)(blockIdx.x + 1) * tiles_per_wg); ++tile) {
+        const int i0 = tile * TT;
+        const int64_t tq0 = (int64_t)a.t0 + i0;
+        assign_and_stage<1, TAB_LDS>(a, sh, tb, Mg, ns, i0, tq0);
+        __syncthreads();
+
+        float r[32];
+        float mn = INFINITY, mx = -INFINITY;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const float4 v = *reinterpret_cast<const float4 *>(sh.rt + t * kRStride + 32 * w + 4 * k);
+            r[4 * k] = v.x; r[4 * k + 1] = v.y; r[4 * k + 2] = v.z; r[4 * k + 3] = v.w;
+            mn = fminf(mn, fminf(fminf(v.x, v.y), fminf(v.z, v.w)));
+            mx = fmaxf(mx, fmaxf(fmaxf(v.x, v.y), fmaxf(v.z, v.w)));
+        }
+        if (qpg > 1) {   // the channel group spans several waves
+            sh.stat[(t * 4 + w) * 2] = mn;
+            sh.stat[(t * 4 + w) * 2 + 1] = mx;
+            __syncthreads();
+            for (int k = 0; k < qpg; ++k) {
+                mn = fminf(mn, sh.stat[(t * 4 + grp * qpg + k) * 2]);
+                mx = fmaxf(mx, sh.stat[(t * 4 + grp * qpg + k) * 2 + 1]);
+            }
+        }
+        const GroupParams gp = group_params(mn, mx, BITS);
+        if (w % qpg == 0) {
+            const int64_t prow = ((int64_t)ns * a.t_capacity + tq0) * ng + ((t >> 4) * ng + grp) * 16 + (t & 15);
+            a.scale[prow] = __ushort_as_half(gp.s16);
+            a.zero[prow] = __ushort_as_half(gp.z16);
+        }
+        // codes; a ballot over the 64 token lanes is the plane of one channel for the 4 units of the
+        // block; lane L = 16*unit + c%16 collects the words of its (unit, channel) pairs
+        uint32_t vacc[2 * WPU];
+#pragma unroll
+        for (int k = 0; k < 2 * WPU; ++k) vacc[k] = 0;
+#pragma unroll
+        for (int cc = 0; cc < 32; ++cc) {
+            const uint32_t ub = code_word(r[cc], gp);
+            unsigned long long m[BITS];
+#pragma unroll
+            for (int j = 0; j < BITS; ++j) m[j] = __ballot((ub >> j) & 1u);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+#pragma unroll
+                for (int jj = 0; jj < WPU; ++jj) {
+                    const uint32_t word = (uint32_t)((m[2 * jj] >> (16 * u)) & 0xffffull) |
+                                          ((uint32_t)((m[2 * jj + 1] >> (16 * u)) & 0xffffull) << 16);
+                    vacc[(cc >> 4) * WPU + jj] =
+                        write_lane(word, 16 * u + (cc & 15), vacc[(cc >> 4) * WPU + jj]);
+                }
+            }
+        }
+        {
+            uint32_t *dst = reinterpret_cast<uint32_t *>(a.codes_v) + ((int64_t)ns * a.t_capacity + tq0) * (kD * BITS / 32) +
+                            ((int64_t)t * 8 + 2 * w) * WPU;
+            if (BITS == 2)
+                *reinterpret_cast<uint2 *>(dst) = make_uint2(vacc[0], vacc[1]);
+            else
+                *reinterpret_cast<uint4 *>(dst) = make_uint4(vacc[0], vacc[1], vacc[2], vacc[3]);
+        }
+        __syncthreads();
+    }
+}
+
 // ---------------------------------------------------------------------------
 // Tail ring: place logical vectors [i0, i1) of an append into their ring slots.
 // ---------------------------------------------------------------------------
@@ -199,13 +468,42 @@ __global__ __launch_bounds__(256) void tail_copy_kernel(TailCopyArgs a)
 
 }  // namespace
 
+static int tiles_per_wg(int n_tiles, int n_streams)
+{
+    int t = (int)(((int64_t)n_tiles * n_streams + 1023) / 1024);   // aim at ~1024 workgroups
+    return t < 1 ? 1 : (t > 16 ? 16 : t);
+}
+
+template <class K>
+static hipError_t launch_tiled(K kernel, const QuantArgs &a, int TT, size_t lds, hipStream_t s)
+{
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    const int n_tiles = a.nq / TT, tpw = tiles_per_wg(n_tiles, a.n_streams);
+    hipLaunchKernelGGL(kernel, dim3((n_tiles + tpw - 1) / tpw, a.n_streams), dim3(256), lds, s, a, tpw);
+    return hipGetLastError();
+}
+
 hipError_t launch_quantize_k(const QuantArgs &a, hipStream_t s)
 {
+    if (a.metric == PK_METRIC_L2) {
+        const bool tl = a.P <= 128;
+#define PK_LAUNCH_K2(GG, BB)                                                                                       \
+    if (a.G == GG && a.bits == BB) {                                                                               \
+        constexpr int TT = GG == 128 ? 128 : 64;                                                                   \
+        return tl ? launch_tiled(quantize_k_kernel<GG, BB, true>, a, TT, tile_lds_bytes<TT>(a.P, true), s)         \
+                  : launch_tiled(quantize_k_kernel<GG, BB, false>, a, TT, tile_lds_bytes<TT>(a.P, false), s);      \
+    }
+        PK_LAUNCH_K2(32, 2) PK_LAUNCH_K2(64, 2) PK_LAUNCH_K2(128, 2)
+        PK_LAUNCH_K2(32, 4) PK_LAUNCH_K2(64, 4) PK_LAUNCH_K2(128, 4)
+#undef PK_LAUNCH_K2
+        return hipErrorInvalidValue;
+    }
     const dim3 grid(a.nq / a.G, a.n_streams), block(128);
-#define PK_LAUNCH_K(GG, BB)                                                        \
-    if (a.G == GG && a.bits == BB) {                                               \
-        hipLaunchKernelGGL((quantize_k_kernel<GG, BB>), grid, block, 0, s, a);     \
-        return hipGetLastError();                                                  \
+#define PK_LAUNCH_K(GG, BB)                                                             \
+    if (a.G == GG && a.bits == BB) {                                                    \
+        hipLaunchKernelGGL((quantize_k_valu_kernel<GG, BB>), grid, block, 0, s, a);     \
+        return hipGetLastError();                                                       \
     }
     PK_LAUNCH_K(32, 2) PK_LAUNCH_K(64, 2) PK_LAUNCH_K(128, 2)
     PK_LAUNCH_K(32, 4) PK_LAUNCH_K(64, 4) PK_LAUNCH_K(128, 4)
@@ -215,11 +513,21 @@ hipError_t launch_quantize_k(const QuantArgs &a, hipStream_t s)
 
 hipError_t launch_quantize_v(const QuantArgs &a, hipStream_t s)
 {
+    if (a.metric == PK_METRIC_L2) {
+        const bool tl = a.P <= 128;
+        if (a.bits == 2)
+            return tl ? launch_tiled(quantize_v_kernel<2, true>, a, 64, tile_lds_bytes<64>(a.P, true), s)
+                      : launch_tiled(quantize_v_kernel<2, false>, a, 64, tile_lds_bytes<64>(a.P, false), s);
+        if (a.bits == 4)
+            return tl ? launch_tiled(quantize_v_kernel<4, true>, a, 64, tile_lds_bytes<64>(a.P, true), s)
+                      : launch_tiled(quantize_v_kernel<4, false>, a, 64, tile_lds_bytes<64>(a.P, false), s);
+        return hipErrorInvalidValue;
+    }
     const dim3 grid(a.nq / 64, a.n_streams), block(128);
     if (a.bits == 2)
-        hipLaunchKernelGGL((quantize_v_kernel<2>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((quantize_v_valu_kernel<2>), grid, block, 0, s, a);
     else if (a.bits == 4)
-        hipLaunchKernelGGL((quantize_v_kernel<4>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((quantize_v_valu_kernel<4>), grid, block, 0, s, a);
     else
         return hipErrorInvalidValue;
     return hipGetLastError();

@@ -63,6 +63,7 @@ __device__ __forceinline__ void stage_patterns(const __half *Mg, int P, __half *
         norm_s[p] = acc;
         mx = fmaxf(mx, acc);
     }
+    for (int p = P + tid; p < (P + 15) / 16 * 16; p += 256) norm_s[p] = 0.f;   // padding read by the last tile
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
     if ((tid & 63) == 0) red_s[tid >> 6] = mx;
@@ -70,43 +71,18 @@ __device__ __forceinline__ void stage_patterns(const __half *Mg, int P, __half *
 }
 
 // One 16-token tile held as B operand xb[4] (K-step s in xb[s]).  Returns, in every lane of column n:
-// best index / value (without the ||x||^2 term) and whether the token needs the exact re-evaluation.
+// best index, best squared distance (from the expanded form, low 8 mantissa bits dropped) and whether
+// the token needs the exact re-evaluation.
+//
+// Candidates are ranked as integer keys: the binary32 pattern of d = ||x||^2 + ||m||^2 - 2 x.m with the
+// pattern index in the low 8 bits.  For d >= 0 the signed-integer order of the keys is the order of
+// (d truncated, index); a d that rounding made slightly negative can only be mis-ordered against
+// another such d, and both are then inside the re-evaluation band.
 template <bool TAB_LDS>
 __device__ __forceinline__ void assign_tile_mfma(const uint4 (&xb)[4], const PatternTable &tb, int lane, int &best_i,
                                                  float &best_v, float &x2, bool &flag)
 {
     const int n = lane & 15, kb = lane >> 4;
-    float b1 = INFINITY, b2 = INFINITY;
-    int i1 = 0;
-    for (int p0 = 0; p0 < tb.P; p0 += 16) {
-        floatx4_t d = {0.f, 0.f, 0.f, 0.f};
-        const int prow = min(p0 + n, tb.P - 1);   // rows past the table repeat the last pattern; masked below
-        const __half *arow = TAB_LDS ? tb.lds_rows + prow * kTabStride + 8 * kb : tb.glb_rows + (int64_t)prow * kD + 8 * kb;
-#pragma unroll
-        for (int s = 0; s < 4; ++s) d = mfma_f16(*reinterpret_cast<const uint4 *>(arow + 32 * s), xb[s], d);
-        const int pr = p0 + 4 * kb;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            float v = pr + i < tb.P ? fmaf(-2.f, d[i], tb.norm2[pr + i]) : INFINITY;
-            b2 = fminf(b2, fmaxf(b1, v));
-            if (v < b1) {   // rows are visited in increasing pattern order within a lane
-                b1 = v;
-                i1 = pr + i;
-            }
-        }
-    }
-    // merge the four lane groups of the column
-#pragma unroll
-    for (int off = 16; off <= 32; off <<= 1) {
-        const float o1 = __shfl_xor(b1, off), o2 = __shfl_xor(b2, off);
-        const int oi = __shfl_xor(i1, off);
-        b2 = fminf(fminf(b2, o2), fmaxf(b1, o1));
-        if (o1 < b1 || (o1 == b1 && oi < i1)) {
-            b1 = o1;
-            i1 = oi;
-        }
-    }
-    // ||x||^2 of the token (for the error bound and for the distance itself)
     float xx = 0.f;
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
@@ -116,12 +92,40 @@ __device__ __forceinline__ void assign_tile_mfma(const uint4 (&xb)[4], const Pat
     }
     xx += __shfl_xor(xx, 16);
     xx += __shfl_xor(xx, 32);
-    best_i = i1;
-    best_v = b1;
+
+    int k1 = 0x7fffffff, k2 = 0x7fffffff;
+    for (int p0 = 0; p0 < tb.P; p0 += 16) {
+        floatx4_t d = {0.f, 0.f, 0.f, 0.f};
+        const int prow = min(p0 + n, tb.P - 1);   // rows past the table repeat the last pattern; masked below
+        const __half *arow = TAB_LDS ? tb.lds_rows + prow * kTabStride + 8 * kb : tb.glb_rows + (int64_t)prow * kD + 8 * kb;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) d = mfma_f16(*reinterpret_cast<const uint4 *>(arow + 32 * s), xb[s], d);
+        const int pr = p0 + 4 * kb;
+        const float4 nm = *reinterpret_cast<const float4 *>(tb.norm2 + pr);   // norm2 is padded to a multiple of 16
+        const float nv[4] = {nm.x, nm.y, nm.z, nm.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float v = fmaf(-2.f, d[i], nv[i] + xx);
+            int key = (int)((__float_as_uint(v) & 0xffffff00u) | (uint32_t)(pr + i));
+            if (pr + i >= tb.P) key = 0x7fffffff;
+            k2 = max(min(k1, k2), min(max(k1, k2), key));   // median of three = second smallest so far
+            k1 = min(k1, key);
+        }
+    }
+    // merge the four lane groups of the column
+#pragma unroll
+    for (int off = 16; off <= 32; off <<= 1) {
+        const int o1 = __shfl_xor(k1, off), o2 = __shfl_xor(k2, off);
+        k2 = min(min(k2, o2), max(k1, o1));
+        k1 = min(k1, o1);
+    }
+    best_i = k1 & 0xff;
+    best_v = __uint_as_float((uint32_t)k1 & 0xffffff00u);
+    const float second = __uint_as_float((uint32_t)k2 & 0xffffff00u);
     x2 = xx;
-    // accumulation error of x.m is far below 2^-20 (|x|^2 + |m|^2); flag with a wide margin.
-    // A single pattern has nothing to be confused with.
-    flag = tb.P > 1 && !(b2 - b1 > 7.62939453125e-06f * (xx + tb.norm2_max));
+    // accumulation error of x.m is far below 2^-20 (|x|^2 + |m|^2), the keys drop 8 mantissa bits of d:
+    // flag with a wide margin.  A single pattern has nothing to be confused with.
+    flag = tb.P > 1 && !(fabsf(second - best_v) > 7.62939453125e-06f * (xx + tb.norm2_max) + 6.103515625e-05f * fabsf(second));
 }
 
 // Exact re-evaluation of one token by a whole wave: xrow_s = its 128 channels (fp16) in LDS.

@@ -31,7 +31,7 @@ __global__ __launch_bounds__(256) void mine_step_kernel(MineArgs a, int chunk)
     const int P = a.P;
     __half *tab_s = reinterpret_cast<__half *>(smem);
     float *norm_s = reinterpret_cast<float *>(smem + (TAB_LDS ? (size_t)P * kTabStride * 2 : 0));
-    float *sums = norm_s + P;
+    float *sums = norm_s + (P + 15) / 16 * 16;
     int *cnt = reinterpret_cast<int *>(sums + (size_t)P * kD);
     uint8_t *idx_s = reinterpret_cast<uint8_t *>(cnt + P);
     __half *xrow_s = reinterpret_cast<__half *>(idx_s + chunk);
@@ -65,7 +65,7 @@ __global__ __launch_bounds__(256) void mine_step_kernel(MineArgs a, int chunk)
         float bv, x2, bd;
         bool flag;
         assign_tile_mfma<TAB_LDS>(xb, tb, lane, bi, bv, x2, flag);
-        bd = fmaxf(bv + x2, 0.f);
+        bd = fmaxf(bv, 0.f);
         resolve_flagged(xb, flag, xrow_s + wave * kD, tb, Mg, lane, bi, bd);
         if (kb == 0 && tok < n_tok) {
             idx_s[tok] = (uint8_t)bi;
@@ -78,7 +78,19 @@ __global__ __launch_bounds__(256) void mine_step_kernel(MineArgs a, int chunk)
     // ---- cluster sums of the chunk: thread <-> channel, vectors in increasing order
     if (tid < kD) {
         const int c = tid;
-        for (int t = 0; t < n_tok; ++t) atomicAdd(&sums[idx_s[t] * kD + c], h2f(xg[(int64_t)t * kD + c]));
+        for (int t = 0; t < n_tok; t += 16) {
+            __half xv[16];
+            int id[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const int tt = min(t + u, n_tok - 1);
+                xv[u] = xg[(int64_t)tt * kD + c];
+                id[u] = idx_s[tt];
+            }
+#pragma unroll
+            for (int u = 0; u < 16; ++u)
+                if (t + u < n_tok) atomicAdd(&sums[id[u] * kD + c], h2f(xv[u]));
+        }
     } else if (tid == kD) {
         for (int t = 0; t < n_tok; ++t) cnt[idx_s[t]] += 1;
     }
@@ -123,7 +135,7 @@ __global__ __launch_bounds__(256) void mine_inertia_kernel(MineArgs a, int it)
 size_t step_lds_bytes(int P, int chunk, bool tab_lds)
 {
     size_t b = tab_lds ? (size_t)P * kTabStride * 2 : 0;
-    b += (size_t)P * 4 + (size_t)P * kD * 4 + (size_t)P * 4 + (size_t)chunk + 4 * kD * 2;
+    b += (size_t)((P + 15) / 16 * 16) * 4 + (size_t)P * kD * 4 + (size_t)P * 4 + (size_t)chunk + 4 * kD * 2;
     return (b + 15) / 16 * 16;
 }
 

@@ -191,28 +191,39 @@ __global__ __launch_bounds__(128) void quantize_v_valu_kernel(QuantArgs a)
 constexpr int kRStride = kD + 4;   // floats per row of the residual tile (16-byte aligned rows)
 constexpr float kRoundMagic = 8388608.f;   // y + 2^23 has rint(y) in its low mantissa bits (0 <= y < 2^22)
 
-// v_writelane_b32: put the wave-uniform value `v` into lane `lane` of a register, keep the other lanes.
-extern "C" __device__ int pk_llvm_writelane(int, int, int) __asm("llvm.amdgcn.writelane.i32");
-__device__ __forceinline__ uint32_t write_lane(uint32_t v, int lane, uint32_t old)
+// x - m for the low / high halves of two packed fp16 pairs: one v_fma_mix_f32 (x*1.0 + (-m) with fp16
+// sources widened exactly), i.e. the binary32 subtraction of the two converted values.
+__device__ __forceinline__ float sub_lo(uint32_t x, uint32_t m)
 {
-    return (uint32_t)pk_llvm_writelane((int)v, lane, (int)old);
+    float r;
+    asm("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel:[0,0,0] op_sel_hi:[1,0,1]" : "=v"(r) : "v"(x), "v"(m));
+    return r;
+}
+__device__ __forceinline__ float sub_hi(uint32_t x, uint32_t m)
+{
+    float r;
+    asm("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel:[1,0,1] op_sel_hi:[1,0,1]" : "=v"(r) : "v"(x), "v"(m));
+    return r;
 }
 
 // Code of one residual from the stored parameters: the low bits of the returned word.
+// (r - z) * (1/s) lies in [0, 2^b - 1] up to rounding because z <= min and s >= (max - z)/(2^b - 1),
+// so the clamp of the definition never acts; the caller keeps only the low b bits.
 __device__ __forceinline__ uint32_t code_word(float r, const GroupParams &g)
 {
-    const float y = (r - g.z) * g.inv;       // in [0, 2^b - 1] up to rounding, see the header of the format
-    return __float_as_uint(y + kRoundMagic); // round half to even, as rintf
+    const float y = (r - g.z) * g.inv;
+    return __float_as_uint(y + kRoundMagic);   // round half to even, as rintf
 }
 
 struct TileShared {
     // carved from dynamic LDS by the kernels below
-    __half *tab;     // [P][kTabStride]   (TAB_LDS only)
-    float *norm;     // [P]
-    float *rt;       // [TT][kRStride]
-    __half *xrow;    // [4][kD]
-    float *stat;     // K: [2][2][kD]; V: [64][4][2]
-    int *idx;        // [TT]
+    __half *tab;               // [P][kTabStride]   (TAB_LDS only)
+    float *norm;               // [P rounded up to 16]
+    float *rt;                 // [TT][kRStride]
+    __half *xrow;              // [4][kD]
+    float *stat;               // K: [2][2][kD]; V: [64][4][2]
+    unsigned long long *mask;  // plane masks: K [4 waves][HT][BITS]; V [kD][BITS]
+    int *idx;                  // [TT]
 };
 
 template <int TT, bool TAB_LDS>
@@ -223,42 +234,53 @@ __device__ __forceinline__ TileShared carve(unsigned char *smem, int P)
     t.tab = reinterpret_cast<__half *>(smem);
     if (TAB_LDS) o += (size_t)P * kTabStride * 2;
     t.norm = reinterpret_cast<float *>(smem + o);
-    o += (size_t)((P + 3) / 4 * 4) * 4;
+    o += (size_t)((P + 15) / 16 * 16) * 4;
     t.rt = reinterpret_cast<float *>(smem + o);
     o += (size_t)TT * kRStride * 4;
     t.xrow = reinterpret_cast<__half *>(smem + o);
     o += 4 * kD * 2;
     t.stat = reinterpret_cast<float *>(smem + o);
     o += 512 * 4;
+    t.mask = reinterpret_cast<unsigned long long *>(smem + o);
+    o += 4 * 64 * 4 * 8;
     t.idx = reinterpret_cast<int *>(smem + o);
     return t;
 }
 template <int TT>
 size_t tile_lds_bytes(int P, bool tab_lds)
 {
-    return (tab_lds ? (size_t)P * kTabStride * 2 : 0) + (size_t)((P + 3) / 4 * 4) * 4 + (size_t)TT * kRStride * 4 + 4 * kD * 2 +
-           512 * 4 + TT * 4;
+    return (tab_lds ? (size_t)P * kTabStride * 2 : 0) + (size_t)((P + 15) / 16 * 16) * 4 + (size_t)TT * kRStride * 4 +
+           4 * kD * 2 + 512 * 4 + 4 * 64 * 4 * 8 + TT * 4;
+}
+
+// B operands of the NT 16-token tiles of this wave.
+template <int NT>
+__device__ __forceinline__ void load_tiles(const QuantArgs &a, int ns, int i0, uint4 (&xb)[NT][4])
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n = lane & 15, kb = lane >> 4;
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+        const __half *row = a.src.row(ns, i0 + (wave * NT + j) * 16 + n);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) xb[j][k] = *reinterpret_cast<const uint4 *>(row + 32 * k + 8 * kb);
+    }
 }
 
 // Assign the NT 16-token tiles of this wave, write the indices, stage the residuals.
-// i0 = logical index of the first vector of the workgroup's tile; tq0 = its packed position.
+// tq0 = packed position of the first vector of the workgroup's tile.
 template <int NT, bool TAB_LDS>
 __device__ __forceinline__ void assign_and_stage(const QuantArgs &a, const TileShared &sh, const PatternTable &tb,
-                                                 const __half *Mg, int ns, int i0, int64_t tq0)
+                                                 const __half *Mg, int ns, int64_t tq0, const uint4 (&xb)[NT][4])
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n = lane & 15, kb = lane >> 4;
 #pragma unroll
     for (int j = 0; j < NT; ++j) {
         const int tl = (wave * NT + j) * 16 + n;   // token slot inside the tile
-        const __half *row = a.src.row(ns, i0 + tl);
-        uint4 xb[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) xb[k] = *reinterpret_cast<const uint4 *>(row + 32 * k + 8 * kb);
         int bi;
         float bv, x2, bd;
         bool flag;
-        assign_tile_mfma<TAB_LDS>(xb, tb, lane, bi, bv, x2, flag);
-        resolve_flagged(xb, flag, sh.xrow + wave * kD, tb, Mg, lane, bi, bd);
+        assign_tile_mfma<TAB_LDS>(xb[j], tb, lane, bi, bv, x2, flag);
+        resolve_flagged(xb[j], flag, sh.xrow + wave * kD, tb, Mg, lane, bi, bd);
         if (kb == 0) {
             sh.idx[tl] = bi;
             a.idx[(int64_t)ns * a.t_capacity + tq0 + tl] = (uint8_t)bi;
@@ -268,22 +290,29 @@ __device__ __forceinline__ void assign_and_stage(const QuantArgs &a, const TileS
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const uint4 mv = *reinterpret_cast<const uint4 *>(mrow + 32 * k);
-            const half2_t *xh = reinterpret_cast<const half2_t *>(&xb[k]);
-            const half2_t *mh = reinterpret_cast<const half2_t *>(&mv);
+            const uint4 xv = xb[j][k];
             float4 r0, r1;
-            r0.x = (float)xh[0][0] - (float)mh[0][0];
-            r0.y = (float)xh[0][1] - (float)mh[0][1];
-            r0.z = (float)xh[1][0] - (float)mh[1][0];
-            r0.w = (float)xh[1][1] - (float)mh[1][1];
-            r1.x = (float)xh[2][0] - (float)mh[2][0];
-            r1.y = (float)xh[2][1] - (float)mh[2][1];
-            r1.z = (float)xh[3][0] - (float)mh[3][0];
-            r1.w = (float)xh[3][1] - (float)mh[3][1];
+            r0.x = sub_lo(xv.x, mv.x);
+            r0.y = sub_hi(xv.x, mv.x);
+            r0.z = sub_lo(xv.y, mv.y);
+            r0.w = sub_hi(xv.y, mv.y);
+            r1.x = sub_lo(xv.z, mv.z);
+            r1.y = sub_hi(xv.z, mv.z);
+            r1.z = sub_lo(xv.w, mv.w);
+            r1.w = sub_hi(xv.w, mv.w);
             float4 *dst = reinterpret_cast<float4 *>(sh.rt + tl * kRStride + 32 * k + 8 * kb);
             dst[0] = r0;
             dst[1] = r1;
         }
     }
+}
+
+// Plane j of the codes in `ub` across the wave: one compare for the top plane, mask-and-compare below.
+template <int BITS>
+__device__ __forceinline__ unsigned long long plane_mask(uint32_t ub, int j)
+{
+    if (j == BITS - 1) return __ballot((ub & ((1u << BITS) - 1u)) >= (1u << (BITS - 1)));
+    return __ballot((ub & (1u << j)) != 0u);
 }
 
 // K: workgroup = 256 threads, tiles of TT = max(64, G) tokens of one stream.
@@ -296,6 +325,11 @@ __global__ __launch_bounds__(256) void quantize_k_kernel(QuantArgs a, int tiles_
     const TileShared sh = carve<TT, TAB_LDS>(smem, a.P);
     const int tid = threadIdx.x, ns = blockIdx.y;
     const __half *Mg = a.patterns + (int64_t)a.sets.set_of(ns) * a.P * kD;
+    const int n_tiles = a.nq / TT;
+    const int tile0 = blockIdx.x * tiles_per_wg, tile1 = min(n_tiles, tile0 + tiles_per_wg);
+    uint4 xb[NT][4];
+    load_tiles<NT>(a, ns, tile0 * TT, xb);   // in flight while the table is staged
+
     stage_patterns(Mg, a.P, sh.tab, sh.norm, red_s, TAB_LDS);
     PatternTable tb;
     tb.lds_rows = sh.tab;
@@ -304,22 +338,23 @@ __global__ __launch_bounds__(256) void quantize_k_kernel(QuantArgs a, int tiles_
     tb.norm2_max = fmaxf(fmaxf(red_s[0], red_s[1]), fmaxf(red_s[2], red_s[3]));
     tb.P = a.P;
 
-    const int n_tiles = a.nq / TT;
-    const int c = tid & 127, half = tid >> 7, lane = tid & 63, chw = (tid >> 6) & 1;
-    for (int tile = blockIdx.x * tiles_per_wg; tile < min(n_tiles, (int)(blockIdx.x + 1) * tiles_per_wg); ++tile) {
-        const int i0 = tile * TT;
-        const int64_t tq0 = (int64_t)a.t0 + i0;
-        assign_and_stage<NT, TAB_LDS>(a, sh, tb, Mg, ns, i0, tq0);
+    const int c = tid & 127, half = tid >> 7, lane = tid & 63, wave = tid >> 6, chw = wave & 1;
+    unsigned long long *mask_w = sh.mask + wave * (64 * 4);
+    for (int tile = tile0; tile < tile1; ++tile) {
+        const int64_t tq0 = (int64_t)a.t0 + (int64_t)tile * TT;
+        assign_and_stage<NT, TAB_LDS>(a, sh, tb, Mg, ns, tq0, xb);
         __syncthreads();
+        if (tile + 1 < tile1) load_tiles<NT>(a, ns, (tile + 1) * TT, xb);   // next tile's vectors: hidden behind the scan
 
         // thread <-> (channel c, token half): scan HT tokens
         float r[HT];
         float mn = INFINITY, mx = -INFINITY;
 #pragma unroll
-        for (int t = 0; t < HT; ++t) {
+        for (int t = 0; t < HT; t += 2) {
             r[t] = sh.rt[(half * HT + t) * kRStride + c];
-            mn = fminf(mn, r[t]);
-            mx = fmaxf(mx, r[t]);
+            r[t + 1] = sh.rt[(half * HT + t + 1) * kRStride + c];
+            mn = fminf(fminf(mn, r[t]), r[t + 1]);
+            mx = fmaxf(fmaxf(mx, r[t]), r[t + 1]);
         }
         if (G > HT) {   // the group spans both halves
             sh.stat[(half * 2 + 0) * kD + c] = mn;
@@ -334,30 +369,33 @@ __global__ __launch_bounds__(256) void quantize_k_kernel(QuantArgs a, int tiles_
             a.scale[grow] = __ushort_as_half(gp.s16);
             a.zero[grow] = __ushort_as_half(gp.z16);
         }
-        // codes; one ballot per plane gives the plane words of 64 channels; lane t collects token t
-        uint32_t wacc[2][BITS];
-#pragma unroll
-        for (int j = 0; j < BITS; ++j) wacc[0][j] = wacc[1][j] = 0;
+        // codes; one ballot per plane = the plane words of this wave's 64 channels for one token
 #pragma unroll
         for (int t = 0; t < HT; ++t) {
             const uint32_t ub = code_word(r[t], gp);
 #pragma unroll
             for (int j = 0; j < BITS; ++j) {
-                const unsigned long long m = __ballot((ub >> j) & 1u);
-                wacc[0][j] = write_lane((uint32_t)m, t, wacc[0][j]);
-                wacc[1][j] = write_lane((uint32_t)(m >> 32), t, wacc[1][j]);
+                const unsigned long long m = plane_mask<BITS>(ub, j);
+                if (lane == 0) mask_w[t * BITS + j] = m;
             }
         }
+        // lane t of the wave writes token t: K row = [word w][plane j], this wave owns words 2*chw, 2*chw+1
         if (lane < HT) {
+            unsigned long long m[BITS];
+#pragma unroll
+            for (int j = 0; j < BITS; ++j) m[j] = mask_w[lane * BITS + j];
             uint32_t *dst = a.codes_k + (((int64_t)ns * a.t_capacity + tq0 + half * HT + lane) * 4 + 2 * chw) * BITS;
             if (BITS == 2) {
-                *reinterpret_cast<uint4 *>(dst) = make_uint4(wacc[0][0], wacc[0][1], wacc[1][0], wacc[1][1]);
+                *reinterpret_cast<uint4 *>(dst) =
+                    make_uint4((uint32_t)m[0], (uint32_t)m[1], (uint32_t)(m[0] >> 32), (uint32_t)(m[1] >> 32));
             } else {
-                reinterpret_cast<uint4 *>(dst)[0] = make_uint4(wacc[0][0], wacc[0][1], wacc[0][BITS - 2], wacc[0][BITS - 1]);
-                reinterpret_cast<uint4 *>(dst)[1] = make_uint4(wacc[1][0], wacc[1][1], wacc[1][BITS - 2], wacc[1][BITS - 1]);
+                reinterpret_cast<uint4 *>(dst)[0] =
+                    make_uint4((uint32_t)m[0], (uint32_t)m[1], (uint32_t)m[BITS - 2], (uint32_t)m[BITS - 1]);
+                reinterpret_cast<uint4 *>(dst)[1] = make_uint4((uint32_t)(m[0] >> 32), (uint32_t)(m[1] >> 32),
+                                                               (uint32_t)(m[BITS - 2] >> 32), (uint32_t)(m[BITS - 1] >> 32));
             }
         }
-        __syncthreads();   // residual tile and statistics are reused by the next tile
+        __syncthreads();   // residual tile, statistics and masks are reused by the next tile
     }
 }
 
@@ -372,6 +410,11 @@ __global__ __launch_bounds__(256) void quantize_v_kernel(QuantArgs a, int tiles_
     const TileShared sh = carve<TT, TAB_LDS>(smem, a.P);
     const int tid = threadIdx.x, ns = blockIdx.y;
     const __half *Mg = a.patterns + (int64_t)a.sets.set_of(ns) * a.P * kD;
+    const int n_tiles = a.nq / TT;
+    const int tile0 = blockIdx.x * tiles_per_wg, tile1 = min(n_tiles, tile0 + tiles_per_wg);
+    uint4 xb[1][4];
+    load_tiles<1>(a, ns, tile0 * TT, xb);
+
     stage_patterns(Mg, a.P, sh.tab, sh.norm, red_s, TAB_LDS);
     PatternTable tb;
     tb.lds_rows = sh.tab;
@@ -381,14 +424,14 @@ __global__ __launch_bounds__(256) void quantize_v_kernel(QuantArgs a, int tiles_
     tb.P = a.P;
 
     const int Gc = a.G < kD ? a.G : kD, ng = kD / Gc, qpg = Gc / 32;
-    const int n_tiles = a.nq / TT;
     const int t = tid & 63, w = tid >> 6;
     const int grp = (32 * w) / Gc;
-    for (int tile = blockIdx.x * tiles_per_wg; tile < min(n_tiles, (int)(blockIdx.x + 1) * tiles_per_wg); ++tile) {
-        const int i0 = tile * TT;
-        const int64_t tq0 = (int64_t)a.t0 + i0;
-        assign_and_stage<1, TAB_LDS>(a, sh, tb, Mg, ns, i0, tq0);
+    const uint16_t *mask16 = reinterpret_cast<const uint16_t *>(sh.mask);
+    for (int tile = tile0; tile < tile1; ++tile) {
+        const int64_t tq0 = (int64_t)a.t0 + (int64_t)tile * TT;
+        assign_and_stage<1, TAB_LDS>(a, sh, tb, Mg, ns, tq0, xb);
         __syncthreads();
+        if (tile + 1 < tile1) load_tiles<1>(a, ns, (tile + 1) * TT, xb);
 
         float r[32];
         float mn = INFINITY, mx = -INFINITY;
@@ -396,8 +439,8 @@ __global__ __launch_bounds__(256) void quantize_v_kernel(QuantArgs a, int tiles_
         for (int k = 0; k < 8; ++k) {
             const float4 v = *reinterpret_cast<const float4 *>(sh.rt + t * kRStride + 32 * w + 4 * k);
             r[4 * k] = v.x; r[4 * k + 1] = v.y; r[4 * k + 2] = v.z; r[4 * k + 3] = v.w;
-            mn = fminf(mn, fminf(fminf(v.x, v.y), fminf(v.z, v.w)));
-            mx = fmaxf(mx, fmaxf(fmaxf(v.x, v.y), fmaxf(v.z, v.w)));
+            mn = fminf(fminf(fminf(mn, v.x), v.y), fminf(v.z, v.w));
+            mx = fmaxf(fmaxf(fmaxf(mx, v.x), v.y), fmaxf(v.z, v.w));
         }
         if (qpg > 1) {   // the channel group spans several waves
             sh.stat[(t * 4 + w) * 2] = mn;
@@ -414,35 +457,37 @@ __global__ __launch_bounds__(256) void quantize_v_kernel(QuantArgs a, int tiles_
             a.scale[prow] = __ushort_as_half(gp.s16);
             a.zero[prow] = __ushort_as_half(gp.z16);
         }
-        // codes; a ballot over the 64 token lanes is the plane of one channel for the 4 units of the
-        // block; lane L = 16*unit + c%16 collects the words of its (unit, channel) pairs
-        uint32_t vacc[2 * WPU];
-#pragma unroll
-        for (int k = 0; k < 2 * WPU; ++k) vacc[k] = 0;
+        // codes; a ballot over the 64 token lanes = plane j of one channel for the 4 units of the block
 #pragma unroll
         for (int cc = 0; cc < 32; ++cc) {
             const uint32_t ub = code_word(r[cc], gp);
-            unsigned long long m[BITS];
 #pragma unroll
-            for (int j = 0; j < BITS; ++j) m[j] = __ballot((ub >> j) & 1u);
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-#pragma unroll
-                for (int jj = 0; jj < WPU; ++jj) {
-                    const uint32_t word = (uint32_t)((m[2 * jj] >> (16 * u)) & 0xffffull) |
-                                          ((uint32_t)((m[2 * jj + 1] >> (16 * u)) & 0xffffull) << 16);
-                    vacc[(cc >> 4) * WPU + jj] =
-                        write_lane(word, 16 * u + (cc & 15), vacc[(cc >> 4) * WPU + jj]);
-                }
+            for (int j = 0; j < BITS; ++j) {
+                const unsigned long long m = plane_mask<BITS>(ub, j);
+                if (t == 0) sh.mask[(32 * w + cc) * BITS + j] = m;
             }
         }
+        __syncthreads();
+        // thread (unit u, channel-in-tile n, tile pair w): gather the 16-bit pieces into words
         {
+            const int u = t >> 4, n = t & 15;
+            uint32_t out[2 * WPU];
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const int ch = 16 * (2 * w + q) + n;
+#pragma unroll
+                for (int jj = 0; jj < WPU; ++jj) {
+                    const uint32_t lo = mask16[((ch * BITS + 2 * jj) << 2) + u];
+                    const uint32_t hi = mask16[((ch * BITS + 2 * jj + 1) << 2) + u];
+                    out[q * WPU + jj] = lo | (hi << 16);
+                }
+            }
             uint32_t *dst = reinterpret_cast<uint32_t *>(a.codes_v) + ((int64_t)ns * a.t_capacity + tq0) * (kD * BITS / 32) +
                             ((int64_t)t * 8 + 2 * w) * WPU;
             if (BITS == 2)
-                *reinterpret_cast<uint2 *>(dst) = make_uint2(vacc[0], vacc[1]);
+                *reinterpret_cast<uint2 *>(dst) = make_uint2(out[0], out[1]);
             else
-                *reinterpret_cast<uint4 *>(dst) = make_uint4(vacc[0], vacc[1], vacc[2], vacc[3]);
+                *reinterpret_cast<uint4 *>(dst) = make_uint4(out[0], out[1], out[2], out[3]);
         }
         __syncthreads();
     }

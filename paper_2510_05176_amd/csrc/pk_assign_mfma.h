@@ -1,8 +1,9 @@
 // Nearest-pattern search under the Euclidean metric on the matrix cores (Sec. 3.1 Eq. 4 assignment
 // step; Sec. 3.2 Eq. 6 argmin in L2 mode).
 //
-// Ranking uses ||m||^2 - 2 x.m from v_mfma_f32_16x16x32_f16 (fp16 products are exact in fp32; only
-// the accumulation rounds).  The smallest and second smallest value are tracked; a token whose gap
+// Ranking uses e = x.m - ||m||^2/2 - ||x||^2/2 = -||x - m||^2 / 2 from v_mfma_f32_16x16x32_f16: the
+// accumulator starts at -(||m||^2 + ||x||^2)/2 and the four K-steps add x.m (fp16 products are exact in
+// fp32; only the accumulation rounds).  The best and second best value are tracked; a token whose gap
 // between the two is not safely above the rounding error of that form is re-evaluated exactly,
 // sum_c (x_c - m_c)^2 in binary32 over all patterns, lowest index on ties.  A token that is not
 // re-evaluated has a gap larger than any possible ranking error, so the result always equals the
@@ -23,11 +24,13 @@ typedef float floatx4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kTabStride = kD + 8;   // halves per pattern row in LDS (272 B: 16-byte aligned, spreads banks)
 
+__host__ __device__ constexpr int pad16(int p) { return (p + 15) & ~15; }
+
 struct PatternTable {
-    const __half *lds_rows;   // LDS copy, row stride kTabStride (used when the kernel is built with TAB_LDS)
+    const __half *lds_rows;   // LDS copy, pad16(P) rows of stride kTabStride, rows past P are zero (TAB_LDS kernels)
     const __half *glb_rows;   // global table, row stride kD
-    const float *norm2;       // LDS [P]: ||m_p||^2
-    float norm2_max;
+    const float *nh;          // LDS [pad16(P)]: -||m_p||^2 / 2, -inf past P
+    float norm2_max;          // max_p ||m_p||^2
     int P;
 };
 
@@ -37,15 +40,16 @@ __device__ __forceinline__ floatx4_t mfma_f16(const uint4 &a, const uint4 &b, fl
 }
 
 // Stage a pattern table into LDS (256 threads) and compute the row norms.  Ends with a barrier.
-__device__ __forceinline__ void stage_patterns(const __half *Mg, int P, __half *tab_s, float *norm_s, float *red_s,
+__device__ __forceinline__ void stage_patterns(const __half *Mg, int P, __half *tab_s, float *nh_s, float *red_s,
                                                bool to_lds)
 {
     const int tid = threadIdx.x;
     if (to_lds) {
-        for (int i = tid; i < P * kRowChunks; i += 256) {
+        for (int i = tid; i < pad16(P) * kRowChunks; i += 256) {
             const int r = i >> 4, ch = i & 15;
-            *reinterpret_cast<uint4 *>(tab_s + r * kTabStride + ch * 8) =
-                *reinterpret_cast<const uint4 *>(Mg + (int64_t)r * kD + ch * 8);
+            uint4 v = make_uint4(0u, 0u, 0u, 0u);
+            if (r < P) v = *reinterpret_cast<const uint4 *>(Mg + (int64_t)r * kD + ch * 8);
+            *reinterpret_cast<uint4 *>(tab_s + r * kTabStride + ch * 8) = v;
         }
     }
     float mx = 0.f;
@@ -60,24 +64,51 @@ __device__ __forceinline__ void stage_patterns(const __half *Mg, int P, __half *
                 acc = fmaf(a, a, fmaf(b, b, acc));
             }
         }
-        norm_s[p] = acc;
+        nh_s[p] = -0.5f * acc;
         mx = fmaxf(mx, acc);
     }
-    for (int p = P + tid; p < (P + 15) / 16 * 16; p += 256) norm_s[p] = 0.f;   // padding read by the last tile
+    for (int p = P + tid; p < pad16(P); p += 256) nh_s[p] = -INFINITY;   // rows past the table never win
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
     if ((tid & 63) == 0) red_s[tid >> 6] = mx;
     __syncthreads();
 }
 
+// A operand and accumulator start of one 16-pattern tile.
+struct PatternTile {
+    uint4 a[4];
+    float4 nh;
+};
+
+template <bool TAB_LDS>
+__device__ __forceinline__ void load_pattern_tile(const PatternTable &tb, int p0, int n, int kb, PatternTile &t)
+{
+    const __half *arow = TAB_LDS ? tb.lds_rows + (p0 + n) * kTabStride + 8 * kb
+                                 : tb.glb_rows + (int64_t)min(p0 + n, tb.P - 1) * kD + 8 * kb;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) t.a[s] = *reinterpret_cast<const uint4 *>(arow + 32 * s);
+    t.nh = *reinterpret_cast<const float4 *>(tb.nh + p0 + 4 * kb);
+}
+
+// Candidates are ranked as integer keys: the binary32 pattern of e (sign bit forced, low 8 mantissa
+// bits replaced by the pattern index).  e <= 0 up to rounding, and among negative floats the signed
+// integer order is the order of decreasing value, so the smallest key is the nearest pattern.
+__device__ __forceinline__ void rank_pattern_tile(const uint4 (&xb)[4], const PatternTile &t, float hx, int p0, int &k1, int &k2)
+{
+    floatx4_t d = {t.nh.x - hx, t.nh.y - hx, t.nh.z - hx, t.nh.w - hx};
+#pragma unroll
+    for (int s = 0; s < 4; ++s) d = mfma_f16(t.a[s], xb[s], d);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int key = (int)((__float_as_uint(d[i]) & 0xffffff00u) | (0x80000000u | (uint32_t)(p0 + i)));
+        k2 = max(min(k1, k2), min(max(k1, k2), key));   // median of three = second smallest so far
+        k1 = min(k1, key);
+    }
+}
+
 // One 16-token tile held as B operand xb[4] (K-step s in xb[s]).  Returns, in every lane of column n:
-// best index, best squared distance (from the expanded form, low 8 mantissa bits dropped) and whether
-// the token needs the exact re-evaluation.
-//
-// Candidates are ranked as integer keys: the binary32 pattern of d = ||x||^2 + ||m||^2 - 2 x.m with the
-// pattern index in the low 8 bits.  For d >= 0 the signed-integer order of the keys is the order of
-// (d truncated, index); a d that rounding made slightly negative can only be mis-ordered against
-// another such d, and both are then inside the re-evaluation band.
+// best index, best squared distance (from the expanded form, low 8 mantissa bits dropped), ||x||^2 and
+// whether the token needs the exact re-evaluation.
 template <bool TAB_LDS>
 __device__ __forceinline__ void assign_tile_mfma(const uint4 (&xb)[4], const PatternTable &tb, int lane, int &best_i,
                                                  float &best_v, float &x2, bool &flag)
@@ -92,26 +123,23 @@ __device__ __forceinline__ void assign_tile_mfma(const uint4 (&xb)[4], const Pat
     }
     xx += __shfl_xor(xx, 16);
     xx += __shfl_xor(xx, 32);
+    const float hx = 0.5f * xx;
 
-    int k1 = 0x7fffffff, k2 = 0x7fffffff;
-    for (int p0 = 0; p0 < tb.P; p0 += 16) {
-        floatx4_t d = {0.f, 0.f, 0.f, 0.f};
-        const int prow = min(p0 + n, tb.P - 1);   // rows past the table repeat the last pattern; masked below
-        const __half *arow = TAB_LDS ? tb.lds_rows + prow * kTabStride + 8 * kb : tb.glb_rows + (int64_t)prow * kD + 8 * kb;
-#pragma unroll
-        for (int s = 0; s < 4; ++s) d = mfma_f16(*reinterpret_cast<const uint4 *>(arow + 32 * s), xb[s], d);
-        const int pr = p0 + 4 * kb;
-        const float4 nm = *reinterpret_cast<const float4 *>(tb.norm2 + pr);   // norm2 is padded to a multiple of 16
-        const float nv[4] = {nm.x, nm.y, nm.z, nm.w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const float v = fmaf(-2.f, d[i], nv[i] + xx);
-            int key = (int)((__float_as_uint(v) & 0xffffff00u) | (uint32_t)(pr + i));
-            if (pr + i >= tb.P) key = 0x7fffffff;
-            k2 = max(min(k1, k2), min(max(k1, k2), key));   // median of three = second smallest so far
-            k1 = min(k1, key);
-        }
+    // the key's index bits are p0 + i here; the lane's 4*kb is added after the loop (no carries: p0 % 16 == 0)
+    int k1 = -1, k2 = -1;   // 0xffffffff: above every key
+    const int Pp = pad16(tb.P);
+    PatternTile ta, tc;
+    load_pattern_tile<TAB_LDS>(tb, 0, n, kb, ta);
+    for (int p0 = 0;;) {   // two tiles per round, the next one in flight while the current is ranked
+        if (p0 + 16 < Pp) load_pattern_tile<TAB_LDS>(tb, p0 + 16, n, kb, tc);
+        rank_pattern_tile(xb, ta, hx, p0, k1, k2);
+        if ((p0 += 16) >= Pp) break;
+        if (p0 + 16 < Pp) load_pattern_tile<TAB_LDS>(tb, p0 + 16, n, kb, ta);
+        rank_pattern_tile(xb, tc, hx, p0, k1, k2);
+        if ((p0 += 16) >= Pp) break;
     }
+    k1 |= kb << 2;
+    k2 |= kb << 2;
     // merge the four lane groups of the column
 #pragma unroll
     for (int off = 16; off <= 32; off <<= 1) {
@@ -120,12 +148,12 @@ __device__ __forceinline__ void assign_tile_mfma(const uint4 (&xb)[4], const Pat
         k1 = min(k1, o1);
     }
     best_i = k1 & 0xff;
-    best_v = __uint_as_float((uint32_t)k1 & 0xffffff00u);
-    const float second = __uint_as_float((uint32_t)k2 & 0xffffff00u);
+    best_v = -2.f * __uint_as_float((uint32_t)k1 & 0xffffff00u);
+    const float second = -2.f * __uint_as_float((uint32_t)k2 & 0xffffff00u);
     x2 = xx;
-    // accumulation error of x.m is far below 2^-20 (|x|^2 + |m|^2), the keys drop 8 mantissa bits of d:
+    // accumulation error of e is far below 2^-21 (|x|^2 + |m|^2), the keys drop 8 mantissa bits:
     // flag with a wide margin.  A single pattern has nothing to be confused with.
-    flag = tb.P > 1 && !(fabsf(second - best_v) > 7.62939453125e-06f * (xx + tb.norm2_max) + 6.103515625e-05f * fabsf(second));
+    flag = tb.P > 1 && !(second - best_v > 7.62939453125e-06f * (xx + tb.norm2_max) + 6.103515625e-05f * second);
 }
 
 // Exact re-evaluation of one token by a whole wave: xrow_s = its 128 channels (fp16) in LDS.

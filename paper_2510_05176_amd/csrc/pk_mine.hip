@@ -23,15 +23,15 @@ __global__ __launch_bounds__(256) void mine_init_kernel(MineArgs a)
 }
 
 // Assignment step + partial cluster sums of one chunk of one set.  256 threads.
-// Dynamic LDS: [table (TAB_LDS only)] [norm2 P] [sums P*kD] [cnt P] [idx chunk bytes] [xrow 4*kD halves]
+// Dynamic LDS: [table pad16(P) rows (TAB_LDS only)] [-norm2/2 pad16(P)] [sums P*kD] [cnt P] [idx chunk bytes] [xrow 4*kD halves]
 template <bool TAB_LDS>
 __global__ __launch_bounds__(256) void mine_step_kernel(MineArgs a, int chunk)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const int P = a.P;
     __half *tab_s = reinterpret_cast<__half *>(smem);
-    float *norm_s = reinterpret_cast<float *>(smem + (TAB_LDS ? (size_t)P * kTabStride * 2 : 0));
-    float *sums = norm_s + (P + 15) / 16 * 16;
+    float *norm_s = reinterpret_cast<float *>(smem + (TAB_LDS ? (size_t)pad16(P) * kTabStride * 2 : 0));
+    float *sums = norm_s + pad16(P);
     int *cnt = reinterpret_cast<int *>(sums + (size_t)P * kD);
     uint8_t *idx_s = reinterpret_cast<uint8_t *>(cnt + P);
     __half *xrow_s = reinterpret_cast<__half *>(idx_s + chunk);
@@ -49,7 +49,7 @@ __global__ __launch_bounds__(256) void mine_step_kernel(MineArgs a, int chunk)
     PatternTable tb;
     tb.lds_rows = tab_s;
     tb.glb_rows = Mg;
-    tb.norm2 = norm_s;
+    tb.nh = norm_s;
     tb.norm2_max = fmaxf(fmaxf(red_s[0], red_s[1]), fmaxf(red_s[2], red_s[3]));
     tb.P = P;
 
@@ -134,8 +134,8 @@ __global__ __launch_bounds__(256) void mine_inertia_kernel(MineArgs a, int it)
 
 size_t step_lds_bytes(int P, int chunk, bool tab_lds)
 {
-    size_t b = tab_lds ? (size_t)P * kTabStride * 2 : 0;
-    b += (size_t)((P + 15) / 16 * 16) * 4 + (size_t)P * kD * 4 + (size_t)P * 4 + (size_t)chunk + 4 * kD * 2;
+    size_t b = tab_lds ? (size_t)pad16(P) * kTabStride * 2 : 0;
+    b += (size_t)pad16(P) * 4 + (size_t)P * kD * 4 + (size_t)P * 4 + (size_t)chunk + 4 * kD * 2;
     return (b + 15) / 16 * 16;
 }
 

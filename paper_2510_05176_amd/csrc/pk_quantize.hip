@@ -182,314 +182,387 @@ __global__ __launch_bounds__(128) void quantize_v_valu_kernel(QuantArgs a)
 
 
 // ===========================================================================
-// Euclidean metric: nearest pattern on the matrix cores (pk_assign_mfma.h), then residuals are
-// staged in LDS as binary32 and quantized with one thread per channel (K) or per token (V), so
-// that the group minimum / maximum is a sequential scan inside a thread and every bit plane is
-// one ballot across the lanes.
+// Euclidean metric: nearest pattern on the matrix cores (pk_assign_mfma.h).  A wave owns 16-token
+// tiles; lane 16*kb + n holds, of token n, the 32 channels 32*k + 8*kb + j (k < 4, j < 8) - the MFMA
+// B-operand layout - and keeps the residuals of those channels in registers through quantization and
+// bit-plane packing.
+//
+// K: residuals also go to an LDS tile so that the per-channel minimum / maximum over the group's tokens
+//    is a column scan; the parameters come back through LDS; every lane then forms one byte of each
+//    plane word (8 channels) and stores it.
+// V: everything per token stays inside the wave: group minimum / maximum by two cross-lane steps,
+//    16 codes per plane packed per lane, and a 16x16 bit transpose across the 16 token lanes turns
+//    them into the words of 16 tokens per channel.
 // ===========================================================================
 
-constexpr int kRStride = kD + 4;   // floats per row of the residual tile (16-byte aligned rows)
+constexpr int kRStride = kD + 4;           // floats per row of the residual tile (16-byte aligned rows, bank skew 4)
 constexpr float kRoundMagic = 8388608.f;   // y + 2^23 has rint(y) in its low mantissa bits (0 <= y < 2^22)
 
-// x - m for the low / high halves of two packed fp16 pairs: one v_fma_mix_f32 (x*1.0 + (-m) with fp16
-// sources widened exactly), i.e. the binary32 subtraction of the two converted values.
-__device__ __forceinline__ float sub_lo(uint32_t x, uint32_t m)
+// Differences with one rounding, as the binary32 subtraction of the widened values: v_fma_mix_f32
+// computes a*1.0 + (-b) with fp16 sources widened exactly.
+__device__ __forceinline__ float sub_lo(uint32_t x, uint32_t m)   // half(x.lo) - half(m.lo)
 {
     float r;
     asm("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel:[0,0,0] op_sel_hi:[1,0,1]" : "=v"(r) : "v"(x), "v"(m));
     return r;
 }
-__device__ __forceinline__ float sub_hi(uint32_t x, uint32_t m)
+__device__ __forceinline__ float sub_hi(uint32_t x, uint32_t m)   // half(x.hi) - half(m.hi)
 {
     float r;
     asm("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel:[1,0,1] op_sel_hi:[1,0,1]" : "=v"(r) : "v"(x), "v"(m));
     return r;
 }
-
-// Code of one residual from the stored parameters: the low bits of the returned word.
-// (r - z) * (1/s) lies in [0, 2^b - 1] up to rounding because z <= min and s >= (max - z)/(2^b - 1),
-// so the clamp of the definition never acts; the caller keeps only the low b bits.
-__device__ __forceinline__ uint32_t code_word(float r, const GroupParams &g)
+__device__ __forceinline__ float subz_lo(float x, uint32_t z)   // x - half(z.lo)
 {
-    const float y = (r - g.z) * g.inv;
+    float r;
+    asm("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel:[0,0,0] op_sel_hi:[0,0,1]" : "=v"(r) : "v"(x), "v"(z));
+    return r;
+}
+__device__ __forceinline__ float subz_hi(float x, uint32_t z)   // x - half(z.hi)
+{
+    float r;
+    asm("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel:[0,0,1] op_sel_hi:[0,0,1]" : "=v"(r) : "v"(x), "v"(z));
+    return r;
+}
+
+// Code of one residual: the low bits of the returned word.  d = r - z >= 0 and d * (1/s) lies in
+// [0, 2^b - 1] up to rounding because z <= min and s >= (max - z)/(2^b - 1), so the clamp of the
+// definition never acts; the caller keeps only the low b bits.
+__device__ __forceinline__ uint32_t code_word(float d, float inv)
+{
+    const float y = d * inv;
     return __float_as_uint(y + kRoundMagic);   // round half to even, as rintf
 }
 
+// plane <- plane with bit p of the code shifted in at the top (the first of n codes ends at bit 32 - n)
+template <int BITS>
+__device__ __forceinline__ void shift_in(uint32_t (&pl)[BITS], uint32_t ub)
+{
+#pragma unroll
+    for (int p = 0; p < BITS; ++p) pl[p] = __builtin_amdgcn_alignbit(ub >> p, pl[p], 1);
+}
+
 struct TileShared {
-    // carved from dynamic LDS by the kernels below
-    __half *tab;               // [P][kTabStride]   (TAB_LDS only)
-    float *norm;               // [P rounded up to 16]
-    float *rt;                 // [TT][kRStride]
-    __half *xrow;              // [4][kD]
-    float *stat;               // K: [2][2][kD]; V: [64][4][2]
-    unsigned long long *mask;  // plane masks: K [4 waves][HT][BITS]; V [kD][BITS]
-    int *idx;                  // [TT]
+    __half *tab;      // [pad16(P)][kTabStride]   (TAB_LDS only)
+    float *nh;        // [pad16(P)]
+    __half *xrow;     // [4][kD]
+    float *red;       // [4]
+    float *rt;        // K: [TT][kRStride]
+    uint16_t *pz;     // K: [TT/G][kD] zero points (fp16 bits)
+    float *pinv;      // K: [TT/G][kD] 1/s
 };
 
-template <int TT, bool TAB_LDS>
-__device__ __forceinline__ TileShared carve(unsigned char *smem, int P)
+// TT = 0: no residual tile (V)
+__host__ __device__ inline size_t carve_offsets(int P, bool tab_lds, int TT, int G, size_t (&o)[7])
 {
+    size_t at = 0;
+    o[0] = at; at += tab_lds ? (size_t)pad16(P) * kTabStride * 2 : 0;
+    o[1] = at; at += (size_t)pad16(P) * 4;
+    o[2] = at; at += 4 * kD * 2;
+    o[3] = at; at += 16;
+    o[4] = at; at += (size_t)TT * kRStride * 4;
+    const int ngrp = TT ? TT / G : 0;
+    o[5] = at; at += (size_t)ngrp * kD * 2;
+    o[6] = at; at += (size_t)ngrp * kD * 4;
+    return at;
+}
+
+__device__ __forceinline__ TileShared carve(unsigned char *smem, int P, bool tab_lds, int TT, int G)
+{
+    size_t o[7];
+    carve_offsets(P, tab_lds, TT, G, o);
     TileShared t;
-    size_t o = 0;
-    t.tab = reinterpret_cast<__half *>(smem);
-    if (TAB_LDS) o += (size_t)P * kTabStride * 2;
-    t.norm = reinterpret_cast<float *>(smem + o);
-    o += (size_t)((P + 15) / 16 * 16) * 4;
-    t.rt = reinterpret_cast<float *>(smem + o);
-    o += (size_t)TT * kRStride * 4;
-    t.xrow = reinterpret_cast<__half *>(smem + o);
-    o += 4 * kD * 2;
-    t.stat = reinterpret_cast<float *>(smem + o);
-    o += 512 * 4;
-    t.mask = reinterpret_cast<unsigned long long *>(smem + o);
-    o += 4 * 64 * 4 * 8;
-    t.idx = reinterpret_cast<int *>(smem + o);
+    t.tab = reinterpret_cast<__half *>(smem + o[0]);
+    t.nh = reinterpret_cast<float *>(smem + o[1]);
+    t.xrow = reinterpret_cast<__half *>(smem + o[2]);
+    t.red = reinterpret_cast<float *>(smem + o[3]);
+    t.rt = reinterpret_cast<float *>(smem + o[4]);
+    t.pz = reinterpret_cast<uint16_t *>(smem + o[5]);
+    t.pinv = reinterpret_cast<float *>(smem + o[6]);
     return t;
 }
-template <int TT>
-size_t tile_lds_bytes(int P, bool tab_lds)
+
+static size_t tile_lds_bytes(int P, bool tab_lds, int TT, int G)
 {
-    return (tab_lds ? (size_t)P * kTabStride * 2 : 0) + (size_t)((P + 15) / 16 * 16) * 4 + (size_t)TT * kRStride * 4 +
-           4 * kD * 2 + 512 * 4 + 4 * 64 * 4 * 8 + TT * 4;
+    size_t o[7];
+    return carve_offsets(P, tab_lds, TT, G, o);
 }
 
-// B operands of the NT 16-token tiles of this wave.
-template <int NT>
-__device__ __forceinline__ void load_tiles(const QuantArgs &a, int ns, int i0, uint4 (&xb)[NT][4])
+__device__ __forceinline__ PatternTable make_table(const TileShared &sh, const __half *Mg, int P)
+{
+    PatternTable tb;
+    tb.lds_rows = sh.tab;
+    tb.glb_rows = Mg;
+    tb.nh = sh.nh;
+    tb.norm2_max = fmaxf(fmaxf(sh.red[0], sh.red[1]), fmaxf(sh.red[2], sh.red[3]));
+    tb.P = P;
+    return tb;
+}
+
+// B operand of one 16-token tile: vectors i0 .. i0+15 of stream ns.
+__device__ __forceinline__ void load_tile(const QuantArgs &a, int ns, int i0, uint4 (&xb)[4])
+{
+    const int lane = threadIdx.x & 63, n = lane & 15, kb = lane >> 4;
+    const __half *row = a.src.row(ns, i0 + n);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) xb[k] = *reinterpret_cast<const uint4 *>(row + 32 * k + 8 * kb);
+}
+
+// Nearest pattern of the tile's tokens (exact), index stored; residuals r[8k + j] of channel 32k + 8kb + j.
+// t_first = packed position of token 0 of the tile.
+template <bool TAB_LDS>
+__device__ __forceinline__ void assign_residuals(const QuantArgs &a, const TileShared &sh, const PatternTable &tb,
+                                                 const __half *Mg, int ns, int64_t t_first, const uint4 (&xb)[4],
+                                                 float (&r)[32])
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n = lane & 15, kb = lane >> 4;
+    int bi;
+    float bv, x2, bd;
+    bool flag;
+    assign_tile_mfma<TAB_LDS>(xb, tb, lane, bi, bv, x2, flag);
+    resolve_flagged(xb, flag, sh.xrow + wave * kD, tb, Mg, lane, bi, bd);
+    if (kb == 0) a.idx[(int64_t)ns * a.t_capacity + t_first + n] = (uint8_t)bi;
+    const __half *mrow = TAB_LDS ? sh.tab + bi * kTabStride + 8 * kb : Mg + (int64_t)bi * kD + 8 * kb;
 #pragma unroll
-    for (int j = 0; j < NT; ++j) {
-        const __half *row = a.src.row(ns, i0 + (wave * NT + j) * 16 + n);
-#pragma unroll
-        for (int k = 0; k < 4; ++k) xb[j][k] = *reinterpret_cast<const uint4 *>(row + 32 * k + 8 * kb);
+    for (int k = 0; k < 4; ++k) {
+        const uint4 mv = *reinterpret_cast<const uint4 *>(mrow + 32 * k);
+        const uint4 xv = xb[k];
+        r[8 * k + 0] = sub_lo(xv.x, mv.x);
+        r[8 * k + 1] = sub_hi(xv.x, mv.x);
+        r[8 * k + 2] = sub_lo(xv.y, mv.y);
+        r[8 * k + 3] = sub_hi(xv.y, mv.y);
+        r[8 * k + 4] = sub_lo(xv.z, mv.z);
+        r[8 * k + 5] = sub_hi(xv.z, mv.z);
+        r[8 * k + 6] = sub_lo(xv.w, mv.w);
+        r[8 * k + 7] = sub_hi(xv.w, mv.w);
     }
 }
 
-// Assign the NT 16-token tiles of this wave, write the indices, stage the residuals.
-// tq0 = packed position of the first vector of the workgroup's tile.
-template <int NT, bool TAB_LDS>
-__device__ __forceinline__ void assign_and_stage(const QuantArgs &a, const TileShared &sh, const PatternTable &tb,
-                                                 const __half *Mg, int ns, int64_t tq0, const uint4 (&xb)[NT][4])
-{
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n = lane & 15, kb = lane >> 4;
-#pragma unroll
-    for (int j = 0; j < NT; ++j) {
-        const int tl = (wave * NT + j) * 16 + n;   // token slot inside the tile
-        int bi;
-        float bv, x2, bd;
-        bool flag;
-        assign_tile_mfma<TAB_LDS>(xb[j], tb, lane, bi, bv, x2, flag);
-        resolve_flagged(xb[j], flag, sh.xrow + wave * kD, tb, Mg, lane, bi, bd);
-        if (kb == 0) {
-            sh.idx[tl] = bi;
-            a.idx[(int64_t)ns * a.t_capacity + tq0 + tl] = (uint8_t)bi;
-        }
-        // residual r = x - M[k*] of this lane's 32 channels, one binary32 subtraction each
-        const __half *mrow = TAB_LDS ? sh.tab + bi * kTabStride + 8 * kb : Mg + (int64_t)bi * kD + 8 * kb;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const uint4 mv = *reinterpret_cast<const uint4 *>(mrow + 32 * k);
-            const uint4 xv = xb[j][k];
-            float4 r0, r1;
-            r0.x = sub_lo(xv.x, mv.x);
-            r0.y = sub_hi(xv.x, mv.x);
-            r0.z = sub_lo(xv.y, mv.y);
-            r0.w = sub_hi(xv.y, mv.y);
-            r1.x = sub_lo(xv.z, mv.z);
-            r1.y = sub_hi(xv.z, mv.z);
-            r1.z = sub_lo(xv.w, mv.w);
-            r1.w = sub_hi(xv.w, mv.w);
-            float4 *dst = reinterpret_cast<float4 *>(sh.rt + tl * kRStride + 32 * k + 8 * kb);
-            dst[0] = r0;
-            dst[1] = r1;
-        }
-    }
-}
-
-// Plane j of the codes in `ub` across the wave: one compare for the top plane, mask-and-compare below.
-template <int BITS>
-__device__ __forceinline__ unsigned long long plane_mask(uint32_t ub, int j)
-{
-    if (j == BITS - 1) return __ballot((ub & ((1u << BITS) - 1u)) >= (1u << (BITS - 1)));
-    return __ballot((ub & (1u << j)) != 0u);
-}
-
-// K: workgroup = 256 threads, tiles of TT = max(64, G) tokens of one stream.
+// K: workgroup = 256 threads, tiles of TT = max(64, G) tokens of one stream; wave w owns the 16-token
+// tiles w*NT .. w*NT + NT-1 of the tile.
 template <int G, int BITS, bool TAB_LDS>
 __global__ __launch_bounds__(256) void quantize_k_kernel(QuantArgs a, int tiles_per_wg)
 {
-    constexpr int TT = G == 128 ? 128 : 64, NT = TT / 64, HT = TT / 2;
+    constexpr int TT = G == 128 ? 128 : 64, NT = TT / 64;
+    constexpr int LPC = TT / 32;          // lanes that share one channel in the column scan, 32 tokens each
+    constexpr int CPR = 256 / LPC;        // channels per round of the scan
     extern __shared__ __align__(16) unsigned char smem[];
-    __shared__ float red_s[4];
-    const TileShared sh = carve<TT, TAB_LDS>(smem, a.P);
+    const TileShared sh = carve(smem, a.P, TAB_LDS, TT, G);
     const int tid = threadIdx.x, ns = blockIdx.y;
+    const int lane = tid & 63, wave = tid >> 6, n = lane & 15, kb = lane >> 4;
     const __half *Mg = a.patterns + (int64_t)a.sets.set_of(ns) * a.P * kD;
     const int n_tiles = a.nq / TT;
     const int tile0 = blockIdx.x * tiles_per_wg, tile1 = min(n_tiles, tile0 + tiles_per_wg);
     uint4 xb[NT][4];
-    load_tiles<NT>(a, ns, tile0 * TT, xb);   // in flight while the table is staged
+#pragma unroll
+    for (int j = 0; j < NT; ++j) load_tile(a, ns, tile0 * TT + (wave * NT + j) * 16, xb[j]);   // in flight while the table is staged
 
-    stage_patterns(Mg, a.P, sh.tab, sh.norm, red_s, TAB_LDS);
-    PatternTable tb;
-    tb.lds_rows = sh.tab;
-    tb.glb_rows = Mg;
-    tb.norm2 = sh.norm;
-    tb.norm2_max = fmaxf(fmaxf(red_s[0], red_s[1]), fmaxf(red_s[2], red_s[3]));
-    tb.P = a.P;
+    stage_patterns(Mg, a.P, sh.tab, sh.nh, sh.red, TAB_LDS);
+    const PatternTable tb = make_table(sh, Mg, a.P);
 
-    const int c = tid & 127, half = tid >> 7, lane = tid & 63, wave = tid >> 6, chw = wave & 1;
-    unsigned long long *mask_w = sh.mask + wave * (64 * 4);
+    const int q = tid % LPC, cc = tid / LPC;
+    uint8_t *codes = reinterpret_cast<uint8_t *>(a.codes_k);
     for (int tile = tile0; tile < tile1; ++tile) {
         const int64_t tq0 = (int64_t)a.t0 + (int64_t)tile * TT;
-        assign_and_stage<NT, TAB_LDS>(a, sh, tb, Mg, ns, tq0, xb);
+        float r[NT][32];
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+            const int tl = (wave * NT + j) * 16 + n;   // token slot inside the tile
+            assign_residuals<TAB_LDS>(a, sh, tb, Mg, ns, tq0 + (wave * NT + j) * 16, xb[j], r[j]);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                float4 *dst = reinterpret_cast<float4 *>(sh.rt + tl * kRStride + 32 * k + 8 * kb);
+                dst[0] = make_float4(r[j][8 * k], r[j][8 * k + 1], r[j][8 * k + 2], r[j][8 * k + 3]);
+                dst[1] = make_float4(r[j][8 * k + 4], r[j][8 * k + 5], r[j][8 * k + 6], r[j][8 * k + 7]);
+            }
+        }
         __syncthreads();
-        if (tile + 1 < tile1) load_tiles<NT>(a, ns, (tile + 1) * TT, xb);   // next tile's vectors: hidden behind the scan
+        if (tile + 1 < tile1) {   // next tile's vectors: hidden behind the rest of this tile
+#pragma unroll
+            for (int j = 0; j < NT; ++j) load_tile(a, ns, (tile + 1) * TT + (wave * NT + j) * 16, xb[j]);
+        }
 
-        // thread <-> (channel c, token half): scan HT tokens
-        float r[HT];
-        float mn = INFINITY, mx = -INFINITY;
+        // column scan: lane q of a channel takes tokens 32q .. 32q+31, in an order rotated by q*16/LPC so
+        // that the lanes of a wave fall on distinct banks
 #pragma unroll
-        for (int t = 0; t < HT; t += 2) {
-            r[t] = sh.rt[(half * HT + t) * kRStride + c];
-            r[t + 1] = sh.rt[(half * HT + t + 1) * kRStride + c];
-            mn = fminf(fminf(mn, r[t]), r[t + 1]);
-            mx = fmaxf(fmaxf(mx, r[t]), r[t + 1]);
-        }
-        if (G > HT) {   // the group spans both halves
-            sh.stat[(half * 2 + 0) * kD + c] = mn;
-            sh.stat[(half * 2 + 1) * kD + c] = mx;
-            __syncthreads();
-            mn = fminf(mn, sh.stat[((half ^ 1) * 2 + 0) * kD + c]);
-            mx = fmaxf(mx, sh.stat[((half ^ 1) * 2 + 1) * kD + c]);
-        }
-        const GroupParams gp = group_params(mn, mx, BITS);
-        if (G <= HT || half == 0) {
-            const int64_t grow = ((int64_t)ns * (a.t_capacity / G) + tq0 / G + (G <= HT ? half : 0)) * kD + c;
-            a.scale[grow] = __ushort_as_half(gp.s16);
-            a.zero[grow] = __ushort_as_half(gp.z16);
-        }
-        // codes; one ballot per plane = the plane words of this wave's 64 channels for one token
+        for (int rd = 0; rd < 128 / CPR; ++rd) {
+            const int c = cc + rd * CPR;
+            float mn = INFINITY, mx = -INFINITY;
 #pragma unroll
-        for (int t = 0; t < HT; ++t) {
-            const uint32_t ub = code_word(r[t], gp);
-#pragma unroll
-            for (int j = 0; j < BITS; ++j) {
-                const unsigned long long m = plane_mask<BITS>(ub, j);
-                if (lane == 0) mask_w[t * BITS + j] = m;
+            for (int t = 0; t < 32; t += 2) {
+                const float v0 = sh.rt[(32 * q + ((t + q * (16 / LPC)) & 31)) * kRStride + c];
+                const float v1 = sh.rt[(32 * q + ((t + 1 + q * (16 / LPC)) & 31)) * kRStride + c];
+                mn = fminf(fminf(mn, v0), v1);
+                mx = fmaxf(fmaxf(mx, v0), v1);
+            }
+            if (G >= 64) {
+                mn = fminf(mn, __shfl_xor(mn, 1));
+                mx = fmaxf(mx, __shfl_xor(mx, 1));
+            }
+            if (G == 128) {
+                mn = fminf(mn, __shfl_xor(mn, 2));
+                mx = fmaxf(mx, __shfl_xor(mx, 2));
+            }
+            const GroupParams gp = group_params(mn, mx, BITS);
+            const int grp = G == 32 ? q : 0;
+            if (G == 32 || q == 0) {
+                const int64_t grow = ((int64_t)ns * (a.t_capacity / G) + tq0 / G + grp) * kD + c;
+                a.scale[grow] = __ushort_as_half(gp.s16);
+                a.zero[grow] = __ushort_as_half(gp.z16);
+                sh.pz[grp * kD + c] = gp.z16;
+                sh.pinv[grp * kD + c] = gp.inv;
             }
         }
-        // lane t of the wave writes token t: K row = [word w][plane j], this wave owns words 2*chw, 2*chw+1
-        if (lane < HT) {
-            unsigned long long m[BITS];
+        __syncthreads();
+
+        // codes of the lane's 32 channels per token; 8 channels = one byte of a plane word
 #pragma unroll
-            for (int j = 0; j < BITS; ++j) m[j] = mask_w[lane * BITS + j];
-            uint32_t *dst = a.codes_k + (((int64_t)ns * a.t_capacity + tq0 + half * HT + lane) * 4 + 2 * chw) * BITS;
-            if (BITS == 2) {
-                *reinterpret_cast<uint4 *>(dst) =
-                    make_uint4((uint32_t)m[0], (uint32_t)m[1], (uint32_t)(m[0] >> 32), (uint32_t)(m[1] >> 32));
-            } else {
-                reinterpret_cast<uint4 *>(dst)[0] =
-                    make_uint4((uint32_t)m[0], (uint32_t)m[1], (uint32_t)m[BITS - 2], (uint32_t)m[BITS - 1]);
-                reinterpret_cast<uint4 *>(dst)[1] = make_uint4((uint32_t)(m[0] >> 32), (uint32_t)(m[1] >> 32),
-                                                               (uint32_t)(m[BITS - 2] >> 32), (uint32_t)(m[BITS - 1] >> 32));
+        for (int j = 0; j < NT; ++j) {
+            const int tl0 = (wave * NT + j) * 16;
+            const int grp = G == 32 ? tl0 >> 5 : 0;
+            uint8_t *dst = codes + (((int64_t)ns * a.t_capacity + tq0 + tl0 + n) * 4) * BITS * 4 + kb;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const uint4 zq = *reinterpret_cast<const uint4 *>(sh.pz + grp * kD + 32 * k + 8 * kb);
+                const float4 i0 = *reinterpret_cast<const float4 *>(sh.pinv + grp * kD + 32 * k + 8 * kb);
+                const float4 i1 = *reinterpret_cast<const float4 *>(sh.pinv + grp * kD + 32 * k + 8 * kb + 4);
+                uint32_t pl[BITS];
+#pragma unroll
+                for (int p = 0; p < BITS; ++p) pl[p] = 0u;
+                shift_in<BITS>(pl, code_word(subz_lo(r[j][8 * k + 0], zq.x), i0.x));
+                shift_in<BITS>(pl, code_word(subz_hi(r[j][8 * k + 1], zq.x), i0.y));
+                shift_in<BITS>(pl, code_word(subz_lo(r[j][8 * k + 2], zq.y), i0.z));
+                shift_in<BITS>(pl, code_word(subz_hi(r[j][8 * k + 3], zq.y), i0.w));
+                shift_in<BITS>(pl, code_word(subz_lo(r[j][8 * k + 4], zq.z), i1.x));
+                shift_in<BITS>(pl, code_word(subz_hi(r[j][8 * k + 5], zq.z), i1.y));
+                shift_in<BITS>(pl, code_word(subz_lo(r[j][8 * k + 6], zq.w), i1.z));
+                shift_in<BITS>(pl, code_word(subz_hi(r[j][8 * k + 7], zq.w), i1.w));
+#pragma unroll
+                for (int p = 0; p < BITS; ++p) dst[(k * BITS + p) * 4] = (uint8_t)(pl[p] >> 24);
             }
         }
-        __syncthreads();   // residual tile, statistics and masks are reused by the next tile
+        // the residual tile is rewritten only after the next barrier-separated scan has been passed by
+        // every wave: the scan of this tile ended before the barrier above
     }
 }
 
-// V: workgroup = 256 threads, blocks of 64 tokens of one stream; wave w owns channels 32w..32w+31,
-// lane t owns token t.
-template <int BITS, bool TAB_LDS>
+// 16x16 bit transpose across the 16 lanes of a row, on both 16-bit halves of x at once:
+// on return bit t of a half in lane i is what bit i of that half was in lane t.
+struct TransposeConst {
+    uint32_t sh[4], keep[4];   // stage d = 8, 4, 2, 1: rotation of the partner's word, bits kept from the own word
+};
+__device__ __forceinline__ TransposeConst transpose_const(int n)
+{
+    TransposeConst c;
+    const uint32_t m0[4] = {0x00ff00ffu, 0x0f0f0f0fu, 0x33333333u, 0x55555555u};   // positions with bit d clear
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        const int d = 8 >> s;
+        const bool lo = (n & d) == 0;
+        c.sh[s] = lo ? 32 - d : d;        // lo lanes take the partner's bits d places up, hi lanes d places down
+        c.keep[s] = lo ? m0[s] : ~m0[s];
+    }
+    return c;
+}
+__device__ __forceinline__ uint32_t transpose16(uint32_t x, const TransposeConst &c)
+{
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        const uint32_t partner = (uint32_t)__shfl_xor((int)x, 8 >> s);
+        const uint32_t rot = __builtin_amdgcn_alignbit(partner, partner, c.sh[s]);   // bits that cross a half are masked out
+        x = (x & c.keep[s]) | (rot & ~c.keep[s]);
+    }
+    return x;
+}
+
+// V: workgroup = 256 threads, blocks of 64 tokens of one stream; wave w owns the 16-token unit w of the
+// block.  NG = channel groups per token (kD / Gc).
+template <int BITS, int NG, bool TAB_LDS>
 __global__ __launch_bounds__(256) void quantize_v_kernel(QuantArgs a, int tiles_per_wg)
 {
-    constexpr int TT = 64, WPU = BITS / 2;
+    constexpr int TT = 64, WPU = BITS / 2, BPG = 4 / NG;   // BPG = 32-channel blocks per group
     extern __shared__ __align__(16) unsigned char smem[];
-    __shared__ float red_s[4];
-    const TileShared sh = carve<TT, TAB_LDS>(smem, a.P);
+    const TileShared sh = carve(smem, a.P, TAB_LDS, 0, 1);
     const int tid = threadIdx.x, ns = blockIdx.y;
+    const int lane = tid & 63, wave = tid >> 6, n = lane & 15, kb = lane >> 4;
     const __half *Mg = a.patterns + (int64_t)a.sets.set_of(ns) * a.P * kD;
     const int n_tiles = a.nq / TT;
     const int tile0 = blockIdx.x * tiles_per_wg, tile1 = min(n_tiles, tile0 + tiles_per_wg);
-    uint4 xb[1][4];
-    load_tiles<1>(a, ns, tile0 * TT, xb);
+    uint4 xb[4];
+    load_tile(a, ns, tile0 * TT + wave * 16, xb);
 
-    stage_patterns(Mg, a.P, sh.tab, sh.norm, red_s, TAB_LDS);
-    PatternTable tb;
-    tb.lds_rows = sh.tab;
-    tb.glb_rows = Mg;
-    tb.norm2 = sh.norm;
-    tb.norm2_max = fmaxf(fmaxf(red_s[0], red_s[1]), fmaxf(red_s[2], red_s[3]));
-    tb.P = a.P;
+    stage_patterns(Mg, a.P, sh.tab, sh.nh, sh.red, TAB_LDS);
+    const PatternTable tb = make_table(sh, Mg, a.P);
+    const TransposeConst tc = transpose_const(n);
+    uint32_t *codes = reinterpret_cast<uint32_t *>(a.codes_v);
 
-    const int Gc = a.G < kD ? a.G : kD, ng = kD / Gc, qpg = Gc / 32;
-    const int t = tid & 63, w = tid >> 6;
-    const int grp = (32 * w) / Gc;
-    const uint16_t *mask16 = reinterpret_cast<const uint16_t *>(sh.mask);
     for (int tile = tile0; tile < tile1; ++tile) {
-        const int64_t tq0 = (int64_t)a.t0 + (int64_t)tile * TT;
-        assign_and_stage<1, TAB_LDS>(a, sh, tb, Mg, ns, tq0, xb);
-        __syncthreads();
-        if (tile + 1 < tile1) load_tiles<1>(a, ns, (tile + 1) * TT, xb);
-
+        const int64_t t_first = (int64_t)a.t0 + (int64_t)tile * TT + wave * 16;   // first token of the unit
         float r[32];
-        float mn = INFINITY, mx = -INFINITY;
+        assign_residuals<TAB_LDS>(a, sh, tb, Mg, ns, t_first, xb, r);
+        if (tile + 1 < tile1) load_tile(a, ns, (tile + 1) * TT + wave * 16, xb);
+
+        // minimum / maximum per channel group: lane-local over its channels, then over the 4 lanes of the token
+        float mn[NG], mx[NG];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            const float4 v = *reinterpret_cast<const float4 *>(sh.rt + t * kRStride + 32 * w + 4 * k);
-            r[4 * k] = v.x; r[4 * k + 1] = v.y; r[4 * k + 2] = v.z; r[4 * k + 3] = v.w;
-            mn = fminf(fminf(fminf(mn, v.x), v.y), fminf(v.z, v.w));
-            mx = fmaxf(fmaxf(fmaxf(mx, v.x), v.y), fmaxf(v.z, v.w));
-        }
-        if (qpg > 1) {   // the channel group spans several waves
-            sh.stat[(t * 4 + w) * 2] = mn;
-            sh.stat[(t * 4 + w) * 2 + 1] = mx;
-            __syncthreads();
-            for (int k = 0; k < qpg; ++k) {
-                mn = fminf(mn, sh.stat[(t * 4 + grp * qpg + k) * 2]);
-                mx = fmaxf(mx, sh.stat[(t * 4 + grp * qpg + k) * 2 + 1]);
+        for (int g = 0; g < NG; ++g) {
+            mn[g] = INFINITY;
+            mx[g] = -INFINITY;
+#pragma unroll
+            for (int e = 8 * BPG * g; e < 8 * BPG * (g + 1); e += 2) {
+                mn[g] = fminf(fminf(mn[g], r[e]), r[e + 1]);
+                mx[g] = fmaxf(fmaxf(mx[g], r[e]), r[e + 1]);
+            }
+#pragma unroll
+            for (int off = 16; off <= 32; off <<= 1) {
+                mn[g] = fminf(mn[g], __shfl_xor(mn[g], off));
+                mx[g] = fmaxf(mx[g], __shfl_xor(mx[g], off));
             }
         }
-        const GroupParams gp = group_params(mn, mx, BITS);
-        if (w % qpg == 0) {
-            const int64_t prow = ((int64_t)ns * a.t_capacity + tq0) * ng + ((t >> 4) * ng + grp) * 16 + (t & 15);
+        // lane kb works out the parameters of group kb % NG and stores them; the others fetch them
+        float my_mn = mn[0], my_mx = mx[0];
+#pragma unroll
+        for (int g = 1; g < NG; ++g) {
+            if ((kb & (NG - 1)) == g) {
+                my_mn = mn[g];
+                my_mx = mx[g];
+            }
+        }
+        const GroupParams gp = group_params(my_mn, my_mx, BITS);
+        if (kb < NG) {
+            const int64_t prow = ((int64_t)ns * a.t_capacity + t_first) * NG + kb * 16 + n;
             a.scale[prow] = __ushort_as_half(gp.s16);
             a.zero[prow] = __ushort_as_half(gp.z16);
         }
-        // codes; a ballot over the 64 token lanes = plane j of one channel for the 4 units of the block
+        float z[NG], inv[NG];
 #pragma unroll
-        for (int cc = 0; cc < 32; ++cc) {
-            const uint32_t ub = code_word(r[cc], gp);
+        for (int g = 0; g < NG; ++g) {
+            z[g] = NG == 1 ? gp.z : __shfl(gp.z, n + 16 * g);
+            inv[g] = NG == 1 ? gp.inv : __shfl(gp.inv, n + 16 * g);
+        }
+
+        // block b = channels 32*(2b + i/8) + 8*kb + i%8, i < 16: codes -> planes -> transpose -> words
+        const int64_t unit_base = ((int64_t)ns * a.t_capacity + t_first) * (kD * BITS / 32);
 #pragma unroll
-            for (int j = 0; j < BITS; ++j) {
-                const unsigned long long m = plane_mask<BITS>(ub, j);
-                if (t == 0) sh.mask[(32 * w + cc) * BITS + j] = m;
+        for (int b = 0; b < 2; ++b) {
+            uint32_t pl[BITS];
+#pragma unroll
+            for (int p = 0; p < BITS; ++p) pl[p] = 0u;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int e = 16 * b + i, g = (e / 8) / BPG;
+                shift_in<BITS>(pl, code_word(r[e] - z[g], inv[g]));
+            }
+            // channel of this lane after the transpose: i = n
+            const int c = 32 * (2 * b + (n >> 3)) + 8 * kb + (n & 7);
+            uint32_t *dst = codes + unit_base + ((c & 15) * (kD / 16) + (c >> 4)) * WPU;
+#pragma unroll
+            for (int w = 0; w < WPU; ++w) {
+                // low half = top 16 bits of plane 2w, high half = top 16 bits of plane 2w+1
+                const uint32_t x = __builtin_amdgcn_perm(pl[2 * w + 1], pl[2 * w], 0x07060302u);
+                dst[w] = transpose16(x, tc);
             }
         }
-        __syncthreads();
-        // thread (unit u, channel-in-tile n, tile pair w): gather the 16-bit pieces into words
-        {
-            const int u = t >> 4, n = t & 15;
-            uint32_t out[2 * WPU];
-#pragma unroll
-            for (int q = 0; q < 2; ++q) {
-                const int ch = 16 * (2 * w + q) + n;
-#pragma unroll
-                for (int jj = 0; jj < WPU; ++jj) {
-                    const uint32_t lo = mask16[((ch * BITS + 2 * jj) << 2) + u];
-                    const uint32_t hi = mask16[((ch * BITS + 2 * jj + 1) << 2) + u];
-                    out[q * WPU + jj] = lo | (hi << 16);
-                }
-            }
-            uint32_t *dst = reinterpret_cast<uint32_t *>(a.codes_v) + ((int64_t)ns * a.t_capacity + tq0) * (kD * BITS / 32) +
-                            ((int64_t)t * 8 + 2 * w) * WPU;
-            if (BITS == 2)
-                *reinterpret_cast<uint2 *>(dst) = make_uint2(out[0], out[1]);
-            else
-                *reinterpret_cast<uint4 *>(dst) = make_uint4(out[0], out[1], out[2], out[3]);
-        }
-        __syncthreads();
     }
 }
 
@@ -536,8 +609,8 @@ hipError_t launch_quantize_k(const QuantArgs &a, hipStream_t s)
 #define PK_LAUNCH_K2(GG, BB)                                                                                       \
     if (a.G == GG && a.bits == BB) {                                                                               \
         constexpr int TT = GG == 128 ? 128 : 64;                                                                   \
-        return tl ? launch_tiled(quantize_k_kernel<GG, BB, true>, a, TT, tile_lds_bytes<TT>(a.P, true), s)         \
-                  : launch_tiled(quantize_k_kernel<GG, BB, false>, a, TT, tile_lds_bytes<TT>(a.P, false), s);      \
+        return tl ? launch_tiled(quantize_k_kernel<GG, BB, true>, a, TT, tile_lds_bytes(a.P, true, TT, GG), s)     \
+                  : launch_tiled(quantize_k_kernel<GG, BB, false>, a, TT, tile_lds_bytes(a.P, false, TT, GG), s);  \
     }
         PK_LAUNCH_K2(32, 2) PK_LAUNCH_K2(64, 2) PK_LAUNCH_K2(128, 2)
         PK_LAUNCH_K2(32, 4) PK_LAUNCH_K2(64, 4) PK_LAUNCH_K2(128, 4)
@@ -560,12 +633,15 @@ hipError_t launch_quantize_v(const QuantArgs &a, hipStream_t s)
 {
     if (a.metric == PK_METRIC_L2) {
         const bool tl = a.P <= 128;
-        if (a.bits == 2)
-            return tl ? launch_tiled(quantize_v_kernel<2, true>, a, 64, tile_lds_bytes<64>(a.P, true), s)
-                      : launch_tiled(quantize_v_kernel<2, false>, a, 64, tile_lds_bytes<64>(a.P, false), s);
-        if (a.bits == 4)
-            return tl ? launch_tiled(quantize_v_kernel<4, true>, a, 64, tile_lds_bytes<64>(a.P, true), s)
-                      : launch_tiled(quantize_v_kernel<4, false>, a, 64, tile_lds_bytes<64>(a.P, false), s);
+        const int ng = kD / (a.G < kD ? a.G : kD);
+        const size_t lds = tile_lds_bytes(a.P, tl, 0, 1);
+#define PK_LAUNCH_V2(BB, NN)                                                                   \
+    if (a.bits == BB && ng == NN)                                                              \
+        return tl ? launch_tiled(quantize_v_kernel<BB, NN, true>, a, 64, lds, s)               \
+                  : launch_tiled(quantize_v_kernel<BB, NN, false>, a, 64, lds, s);
+        PK_LAUNCH_V2(2, 1) PK_LAUNCH_V2(2, 2) PK_LAUNCH_V2(2, 4)
+        PK_LAUNCH_V2(4, 1) PK_LAUNCH_V2(4, 2) PK_LAUNCH_V2(4, 4)
+#undef PK_LAUNCH_V2
         return hipErrorInvalidValue;
     }
     const dim3 grid(a.nq / 64, a.n_streams), block(128);

@@ -22,7 +22,7 @@ typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef float floatx4_t __attribute__((ext_vector_type(4)));
 
-constexpr int kTabStride = kD + 8;   // halves per pattern row in LDS (272 B: 16-byte aligned, spreads banks)
+constexpr int kTabStride = kD + 16;   // halves per pattern row in LDS: 288 B = 72 words, the row skew at which 16-byte reads of 16 rows x 4 column groups run at full rate
 
 __host__ __device__ constexpr int pad16(int p) { return (p + 15) & ~15; }
 
@@ -90,17 +90,21 @@ __device__ __forceinline__ void load_pattern_tile(const PatternTable &tb, int p0
     t.nh = *reinterpret_cast<const float4 *>(tb.nh + p0 + 4 * kb);
 }
 
-// Candidates are ranked as integer keys: the binary32 pattern of e (sign bit forced, low 8 mantissa
-// bits replaced by the pattern index).  e <= 0 up to rounding, and among negative floats the signed
-// integer order is the order of decreasing value, so the smallest key is the nearest pattern.
-__device__ __forceinline__ void rank_pattern_tile(const uint4 (&xb)[4], const PatternTile &t, float hx, int p0, int &k1, int &k2)
+// Candidates are ranked as unsigned integer keys: the binary32 pattern of e with the low 8 mantissa bits
+// replaced by the pattern index.  e <= 0 up to rounding; among negative floats the unsigned order of the
+// patterns is the order of decreasing value, so the smallest key is the nearest pattern.  An e that
+// rounding made slightly positive ranks below every negative one, which is right, and can only be
+// mis-ordered against another such e: both are then inside the re-evaluation band.
+__device__ __forceinline__ void rank_pattern_tile(const uint4 (&xb)[4], const PatternTile &t, float hx, int p0, uint32_t &k1,
+                                                  uint32_t &k2)
 {
     floatx4_t d = {t.nh.x - hx, t.nh.y - hx, t.nh.z - hx, t.nh.w - hx};
 #pragma unroll
     for (int s = 0; s < 4; ++s) d = mfma_f16(t.a[s], xb[s], d);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const int key = (int)((__float_as_uint(d[i]) & 0xffffff00u) | (0x80000000u | (uint32_t)(p0 + i)));
+        // bytes 3..1 of e, byte 0 = index (one byte permute)
+        const uint32_t key = __builtin_amdgcn_perm(__float_as_uint(d[i]), (uint32_t)(p0 + i), 0x07060500u);
         k2 = max(min(k1, k2), min(max(k1, k2), key));   // median of three = second smallest so far
         k1 = min(k1, key);
     }
@@ -126,7 +130,7 @@ __device__ __forceinline__ void assign_tile_mfma(const uint4 (&xb)[4], const Pat
     const float hx = 0.5f * xx;
 
     // the key's index bits are p0 + i here; the lane's 4*kb is added after the loop (no carries: p0 % 16 == 0)
-    int k1 = -1, k2 = -1;   // 0xffffffff: above every key
+    uint32_t k1 = 0xffffffffu, k2 = 0xffffffffu;   // above every key
     const int Pp = pad16(tb.P);
     PatternTile ta, tc;
     load_pattern_tile<TAB_LDS>(tb, 0, n, kb, ta);
@@ -138,18 +142,18 @@ __device__ __forceinline__ void assign_tile_mfma(const uint4 (&xb)[4], const Pat
         rank_pattern_tile(xb, tc, hx, p0, k1, k2);
         if ((p0 += 16) >= Pp) break;
     }
-    k1 |= kb << 2;
-    k2 |= kb << 2;
+    k1 |= (uint32_t)kb << 2;
+    k2 |= (uint32_t)kb << 2;
     // merge the four lane groups of the column
 #pragma unroll
     for (int off = 16; off <= 32; off <<= 1) {
-        const int o1 = __shfl_xor(k1, off), o2 = __shfl_xor(k2, off);
+        const uint32_t o1 = (uint32_t)__shfl_xor((int)k1, off), o2 = (uint32_t)__shfl_xor((int)k2, off);
         k2 = min(min(k2, o2), max(k1, o1));
         k1 = min(k1, o1);
     }
-    best_i = k1 & 0xff;
-    best_v = -2.f * __uint_as_float((uint32_t)k1 & 0xffffff00u);
-    const float second = -2.f * __uint_as_float((uint32_t)k2 & 0xffffff00u);
+    best_i = (int)(k1 & 0xffu);
+    best_v = -2.f * __uint_as_float(k1 & 0xffffff00u);
+    const float second = -2.f * __uint_as_float(k2 & 0xffffff00u);
     x2 = xx;
     // accumulation error of e is far below 2^-21 (|x|^2 + |m|^2), the keys drop 8 mantissa bits:
     // flag with a wide margin.  A single pattern has nothing to be confused with.

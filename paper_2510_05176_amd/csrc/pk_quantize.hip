@@ -245,12 +245,21 @@ __device__ __forceinline__ void shift_in(uint32_t (&pl)[BITS], uint32_t ub)
 struct TileShared {
     __half *tab;      // [pad16(P)][kTabStride]   (TAB_LDS only)
     float *nh;        // [pad16(P)]
-    __half *xrow;     // [4][kD]
+    unsigned char *wsc;   // V: [4 waves][kWaveScratch] (re-evaluation row, output staging)
     float *red;       // [4]
     float *rt;        // K: [TT][kRStride]
-    uint16_t *pz;     // K: [TT/G][kD] zero points (fp16 bits)
+    uint16_t *pz;     // K: [TT/G][kD] zero points (fp16 bits), then [TT/G][kD] scales
     float *pinv;      // K: [TT/G][kD] 1/s
 };
+
+// Per-wave output staging: the pieces a wave produces for its 16 tokens are put together in LDS so that
+// every global store is one contiguous run of 8- or 16-byte lane pieces.
+constexpr int kWsRow = 0;          // 256 B: one vector for the exact re-evaluation
+constexpr int kWsCodes = 256;      // up to 1024 B: the unit's code words in memory order
+constexpr int kWsIdx = 1280;       // 16 B: pattern indices
+constexpr int kWsScale = 1296;     // up to 128 B: scales [group][16]
+constexpr int kWsZero = 1424;      // up to 128 B: zero points [group][16]
+constexpr int kWaveScratch = 1552;
 
 // TT = 0: no residual tile (V)
 __host__ __device__ inline size_t carve_offsets(int P, bool tab_lds, int TT, int G, size_t (&o)[7])
@@ -258,11 +267,11 @@ __host__ __device__ inline size_t carve_offsets(int P, bool tab_lds, int TT, int
     size_t at = 0;
     o[0] = at; at += tab_lds ? (size_t)pad16(P) * kTabStride * 2 : 0;
     o[1] = at; at += (size_t)pad16(P) * 4;
-    o[2] = at; at += 4 * kD * 2;
+    o[2] = at; at += TT ? 0 : 4 * kWaveScratch;   // K stages in its own residual rows instead
     o[3] = at; at += 16;
     o[4] = at; at += (size_t)TT * kRStride * 4;
     const int ngrp = TT ? TT / G : 0;
-    o[5] = at; at += (size_t)ngrp * kD * 2;
+    o[5] = at; at += (size_t)ngrp * kD * 2 * 2;
     o[6] = at; at += (size_t)ngrp * kD * 4;
     return at;
 }
@@ -274,7 +283,7 @@ __device__ __forceinline__ TileShared carve(unsigned char *smem, int P, bool tab
     TileShared t;
     t.tab = reinterpret_cast<__half *>(smem + o[0]);
     t.nh = reinterpret_cast<float *>(smem + o[1]);
-    t.xrow = reinterpret_cast<__half *>(smem + o[2]);
+    t.wsc = smem + o[2];
     t.red = reinterpret_cast<float *>(smem + o[3]);
     t.rt = reinterpret_cast<float *>(smem + o[4]);
     t.pz = reinterpret_cast<uint16_t *>(smem + o[5]);
@@ -308,20 +317,17 @@ __device__ __forceinline__ void load_tile(const QuantArgs &a, int ns, int i0, ui
     for (int k = 0; k < 4; ++k) xb[k] = *reinterpret_cast<const uint4 *>(row + 32 * k + 8 * kb);
 }
 
-// Nearest pattern of the tile's tokens (exact), index stored; residuals r[8k + j] of channel 32k + 8kb + j.
-// t_first = packed position of token 0 of the tile.
+// Nearest pattern of the tile's tokens (exact), returned; residuals r[8k + j] of channel 32k + 8kb + j.
 template <bool TAB_LDS>
-__device__ __forceinline__ void assign_residuals(const QuantArgs &a, const TileShared &sh, const PatternTable &tb,
-                                                 const __half *Mg, int ns, int64_t t_first, const uint4 (&xb)[4],
-                                                 float (&r)[32])
+__device__ __forceinline__ int assign_residuals(const TileShared &sh, const PatternTable &tb, const __half *Mg,
+                                                const uint4 (&xb)[4], __half *xrow, float (&r)[32])
 {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n = lane & 15, kb = lane >> 4;
+    const int lane = threadIdx.x & 63, kb = lane >> 4;
     int bi;
     float bv, x2, bd;
     bool flag;
     assign_tile_mfma<TAB_LDS>(xb, tb, lane, bi, bv, x2, flag);
-    resolve_flagged(xb, flag, sh.xrow + wave * kD, tb, Mg, lane, bi, bd);
-    if (kb == 0) a.idx[(int64_t)ns * a.t_capacity + t_first + n] = (uint8_t)bi;
+    resolve_flagged(xb, flag, xrow, tb, Mg, lane, bi, bd);
     const __half *mrow = TAB_LDS ? sh.tab + bi * kTabStride + 8 * kb : Mg + (int64_t)bi * kD + 8 * kb;
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
@@ -336,6 +342,15 @@ __device__ __forceinline__ void assign_residuals(const QuantArgs &a, const TileS
         r[8 * k + 6] = sub_lo(xv.w, mv.w);
         r[8 * k + 7] = sub_hi(xv.w, mv.w);
     }
+    return bi;
+}
+
+// All LDS writes of the wave so far are visible to its own later reads.
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
 // K: workgroup = 256 threads, tiles of TT = max(64, G) tokens of one stream; wave w owns the 16-token
@@ -346,6 +361,7 @@ __global__ __launch_bounds__(256) void quantize_k_kernel(QuantArgs a, int tiles_
     constexpr int TT = G == 128 ? 128 : 64, NT = TT / 64;
     constexpr int LPC = TT / 32;          // lanes that share one channel in the column scan, 32 tokens each
     constexpr int CPR = 256 / LPC;        // channels per round of the scan
+    constexpr int NGRP = TT / G;          // parameter groups per tile
     extern __shared__ __align__(16) unsigned char smem[];
     const TileShared sh = carve(smem, a.P, TAB_LDS, TT, G);
     const int tid = threadIdx.x, ns = blockIdx.y;
@@ -365,10 +381,13 @@ __global__ __launch_bounds__(256) void quantize_k_kernel(QuantArgs a, int tiles_
     for (int tile = tile0; tile < tile1; ++tile) {
         const int64_t tq0 = (int64_t)a.t0 + (int64_t)tile * TT;
         float r[NT][32];
+        int bi[NT];
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
             const int tl = (wave * NT + j) * 16 + n;   // token slot inside the tile
-            assign_residuals<TAB_LDS>(a, sh, tb, Mg, ns, tq0 + (wave * NT + j) * 16, xb[j], r[j]);
+            // scratch for the exact re-evaluation: the tile's own residual rows, which are written only below
+            bi[j] = assign_residuals<TAB_LDS>(sh, tb, Mg, xb[j],
+                                              reinterpret_cast<__half *>(sh.rt + (wave * NT + j) * 16 * kRStride), r[j]);
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 float4 *dst = reinterpret_cast<float4 *>(sh.rt + tl * kRStride + 32 * k + 8 * kb);
@@ -406,21 +425,29 @@ __global__ __launch_bounds__(256) void quantize_k_kernel(QuantArgs a, int tiles_
             const GroupParams gp = group_params(mn, mx, BITS);
             const int grp = G == 32 ? q : 0;
             if (G == 32 || q == 0) {
-                const int64_t grow = ((int64_t)ns * (a.t_capacity / G) + tq0 / G + grp) * kD + c;
-                a.scale[grow] = __ushort_as_half(gp.s16);
-                a.zero[grow] = __ushort_as_half(gp.z16);
                 sh.pz[grp * kD + c] = gp.z16;
+                sh.pz[(NGRP + grp) * kD + c] = gp.s16;
                 sh.pinv[grp * kD + c] = gp.inv;
             }
         }
         __syncthreads();
+        // stored parameters of the tile's groups: 16-byte pieces, zero points then scales
+        if (wave == 3 && lane < NGRP * 32) {
+            const int grp = lane >> 5, arr = (lane >> 4) & 1, piece = lane & 15;
+            const uint4 v = *reinterpret_cast<const uint4 *>(sh.pz + (arr * NGRP + grp) * kD + piece * 8);
+            __half *dstp = (arr ? a.scale : a.zero) + ((int64_t)ns * (a.t_capacity / G) + tq0 / G + grp) * kD + piece * 8;
+            *reinterpret_cast<uint4 *>(dstp) = v;
+        }
 
-        // codes of the lane's 32 channels per token; 8 channels = one byte of a plane word
+        // codes of the lane's 32 channels per token; 8 channels = one byte of a plane word.  The bytes of the
+        // wave's 16 tokens are put together in its own residual rows (no longer read by anyone) and leave as
+        // one contiguous store.
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
             const int tl0 = (wave * NT + j) * 16;
             const int grp = G == 32 ? tl0 >> 5 : 0;
-            uint8_t *dst = codes + (((int64_t)ns * a.t_capacity + tq0 + tl0 + n) * 4) * BITS * 4 + kb;
+            uint8_t *stg = reinterpret_cast<uint8_t *>(sh.rt + tl0 * kRStride);
+            uint8_t *mine = stg + n * 16 * BITS + kb;
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 const uint4 zq = *reinterpret_cast<const uint4 *>(sh.pz + grp * kD + 32 * k + 8 * kb);
@@ -438,8 +465,16 @@ __global__ __launch_bounds__(256) void quantize_k_kernel(QuantArgs a, int tiles_
                 shift_in<BITS>(pl, code_word(subz_lo(r[j][8 * k + 6], zq.w), i1.z));
                 shift_in<BITS>(pl, code_word(subz_hi(r[j][8 * k + 7], zq.w), i1.w));
 #pragma unroll
-                for (int p = 0; p < BITS; ++p) dst[(k * BITS + p) * 4] = (uint8_t)(pl[p] >> 24);
+                for (int p = 0; p < BITS; ++p) mine[(k * BITS + p) * 4] = (uint8_t)(pl[p] >> 24);
             }
+            if (kb == 0) stg[16 * 16 * BITS + n] = (uint8_t)bi[j];
+            wave_lds_sync();
+            const int64_t tok0 = (int64_t)ns * a.t_capacity + tq0 + tl0;
+            if (BITS == 2)
+                reinterpret_cast<uint2 *>(codes + tok0 * 32)[lane] = reinterpret_cast<const uint2 *>(stg)[lane];
+            else
+                reinterpret_cast<uint4 *>(codes + tok0 * 64)[lane] = reinterpret_cast<const uint4 *>(stg)[lane];
+            if (lane == 0) *reinterpret_cast<uint4 *>(a.idx + tok0) = *reinterpret_cast<const uint4 *>(stg + 16 * 16 * BITS);
         }
         // the residual tile is rewritten only after the next barrier-separated scan has been passed by
         // every wave: the scan of this tile ended before the barrier above
@@ -494,12 +529,12 @@ __global__ __launch_bounds__(256) void quantize_v_kernel(QuantArgs a, int tiles_
     stage_patterns(Mg, a.P, sh.tab, sh.nh, sh.red, TAB_LDS);
     const PatternTable tb = make_table(sh, Mg, a.P);
     const TransposeConst tc = transpose_const(n);
-    uint32_t *codes = reinterpret_cast<uint32_t *>(a.codes_v);
+    unsigned char *wsc = sh.wsc + wave * kWaveScratch;
 
     for (int tile = tile0; tile < tile1; ++tile) {
         const int64_t t_first = (int64_t)a.t0 + (int64_t)tile * TT + wave * 16;   // first token of the unit
         float r[32];
-        assign_residuals<TAB_LDS>(a, sh, tb, Mg, ns, t_first, xb, r);
+        const int bi = assign_residuals<TAB_LDS>(sh, tb, Mg, xb, reinterpret_cast<__half *>(wsc + kWsRow), r);
         if (tile + 1 < tile1) load_tile(a, ns, (tile + 1) * TT + wave * 16, xb);
 
         // minimum / maximum per channel group: lane-local over its channels, then over the 4 lanes of the token
@@ -530,10 +565,10 @@ __global__ __launch_bounds__(256) void quantize_v_kernel(QuantArgs a, int tiles_
         }
         const GroupParams gp = group_params(my_mn, my_mx, BITS);
         if (kb < NG) {
-            const int64_t prow = ((int64_t)ns * a.t_capacity + t_first) * NG + kb * 16 + n;
-            a.scale[prow] = __ushort_as_half(gp.s16);
-            a.zero[prow] = __ushort_as_half(gp.z16);
+            reinterpret_cast<uint16_t *>(wsc + kWsScale)[kb * 16 + n] = gp.s16;
+            reinterpret_cast<uint16_t *>(wsc + kWsZero)[kb * 16 + n] = gp.z16;
         }
+        if (kb == 0) wsc[kWsIdx + n] = (uint8_t)bi;
         float z[NG], inv[NG];
 #pragma unroll
         for (int g = 0; g < NG; ++g) {
@@ -541,8 +576,9 @@ __global__ __launch_bounds__(256) void quantize_v_kernel(QuantArgs a, int tiles_
             inv[g] = NG == 1 ? gp.inv : __shfl(gp.inv, n + 16 * g);
         }
 
-        // block b = channels 32*(2b + i/8) + 8*kb + i%8, i < 16: codes -> planes -> transpose -> words
-        const int64_t unit_base = ((int64_t)ns * a.t_capacity + t_first) * (kD * BITS / 32);
+        // block b = channels 32*(2b + i/8) + 8*kb + i%8, i < 16: codes -> planes -> transpose -> words, put in
+        // memory order in the wave's staging area
+        uint32_t *stg = reinterpret_cast<uint32_t *>(wsc + kWsCodes);
 #pragma unroll
         for (int b = 0; b < 2; ++b) {
             uint32_t pl[BITS];
@@ -555,7 +591,7 @@ __global__ __launch_bounds__(256) void quantize_v_kernel(QuantArgs a, int tiles_
             }
             // channel of this lane after the transpose: i = n
             const int c = 32 * (2 * b + (n >> 3)) + 8 * kb + (n & 7);
-            uint32_t *dst = codes + unit_base + ((c & 15) * (kD / 16) + (c >> 4)) * WPU;
+            uint32_t *dst = stg + ((c & 15) * (kD / 16) + (c >> 4)) * WPU;
 #pragma unroll
             for (int w = 0; w < WPU; ++w) {
                 // low half = top 16 bits of plane 2w, high half = top 16 bits of plane 2w+1
@@ -563,6 +599,20 @@ __global__ __launch_bounds__(256) void quantize_v_kernel(QuantArgs a, int tiles_
                 dst[w] = transpose16(x, tc);
             }
         }
+        wave_lds_sync();
+        // contiguous stores: code words of the unit, its parameters, its indices
+        const int64_t tok0 = (int64_t)ns * a.t_capacity + t_first;
+        if (BITS == 2)
+            reinterpret_cast<uint2 *>(a.codes_v + tok0 * (kD * BITS / 8))[lane] = reinterpret_cast<const uint2 *>(stg)[lane];
+        else
+            reinterpret_cast<uint4 *>(a.codes_v + tok0 * (kD * BITS / 8))[lane] = reinterpret_cast<const uint4 *>(stg)[lane];
+        if (lane < 4 * NG) {   // NG*32 bytes per array = 2*NG pieces of 16 bytes; scales first, then zero points
+            const int arr = lane / (2 * NG), piece = lane % (2 * NG);
+            const uint4 v = *reinterpret_cast<const uint4 *>(wsc + (arr ? kWsZero : kWsScale) + piece * 16);
+            *reinterpret_cast<uint4 *>((arr ? a.zero : a.scale) + tok0 * NG + piece * 8) = v;
+        }
+        if (lane == 63) *reinterpret_cast<uint4 *>(a.idx + tok0) = *reinterpret_cast<const uint4 *>(wsc + kWsIdx);
+        wave_lds_sync();   // the staging area is rewritten by the next unit
     }
 }
 

@@ -196,7 +196,6 @@ __global__ __launch_bounds__(128) void quantize_v_valu_kernel(QuantArgs a)
 // ===========================================================================
 
 constexpr int kRStride = kD + 4;           // floats per row of the residual tile (16-byte aligned rows, bank skew 4)
-constexpr float kRoundMagic = 8388608.f;   // y + 2^23 has rint(y) in its low mantissa bits (0 <= y < 2^22)
 
 // Differences with one rounding, as the binary32 subtraction of the widened values: v_fma_mix_f32
 // computes a*1.0 + (-b) with fp16 sources widened exactly.
@@ -225,21 +224,22 @@ __device__ __forceinline__ float subz_hi(float x, uint32_t z)   // x - half(z.hi
     return r;
 }
 
-// Code of one residual: the low bits of the returned word.  d = r - z >= 0 and d * (1/s) lies in
-// [0, 2^b - 1] up to rounding because z <= min and s >= (max - z)/(2^b - 1), so the clamp of the
-// definition never acts; the caller keeps only the low b bits.
-__device__ __forceinline__ uint32_t code_word(float d, float inv)
+// Codes.  d = r - z >= 0 and d * (1/s) lies in [0, 2^b - 1] up to rounding because z <= min and
+// s >= (max - z)/(2^b - 1), so the clamp of the definition never acts.  v_cvt_pk_u8_f32 rounds half to
+// even like rintf (and saturates at 0 and 255) and drops the code into one byte of a word: four codes per
+// word.  packed <- packed with code(d * inv) in byte `slot`.
+__device__ __forceinline__ uint32_t put_code(float d, float inv, int slot, uint32_t packed)
 {
-    const float y = d * inv;
-    return __float_as_uint(y + kRoundMagic);   // round half to even, as rintf
+    return __builtin_amdgcn_cvt_pk_u8_f32(d * inv, (uint32_t)slot, packed);
 }
 
-// plane <- plane with bit p of the code shifted in at the top (the first of n codes ends at bit 32 - n)
-template <int BITS>
-__device__ __forceinline__ void shift_in(uint32_t (&pl)[BITS], uint32_t ub)
+// Bits p of the 8 codes held in the bytes of (lo, hi), gathered into bits p .. p+7 of the result:
+// two masked byte dot products with weights 1, 2, 4, .. 128.
+__device__ __forceinline__ uint32_t plane_byte_shifted(uint32_t lo, uint32_t hi, int p)
 {
-#pragma unroll
-    for (int p = 0; p < BITS; ++p) pl[p] = __builtin_amdgcn_alignbit(ub >> p, pl[p], 1);
+    const uint32_t m = 0x01010101u << p;
+    uint32_t acc = __builtin_amdgcn_udot4(lo & m, 0x08040201u, 0u, false);
+    return __builtin_amdgcn_udot4(hi & m, 0x80402010u, acc, false);
 }
 
 struct TileShared {
@@ -453,19 +453,17 @@ __global__ __launch_bounds__(256) void quantize_k_kernel(QuantArgs a, int tiles_
                 const uint4 zq = *reinterpret_cast<const uint4 *>(sh.pz + grp * kD + 32 * k + 8 * kb);
                 const float4 i0 = *reinterpret_cast<const float4 *>(sh.pinv + grp * kD + 32 * k + 8 * kb);
                 const float4 i1 = *reinterpret_cast<const float4 *>(sh.pinv + grp * kD + 32 * k + 8 * kb + 4);
-                uint32_t pl[BITS];
+                uint32_t lo = 0u, hi = 0u;
+                lo = put_code(subz_lo(r[j][8 * k + 0], zq.x), i0.x, 0, lo);
+                lo = put_code(subz_hi(r[j][8 * k + 1], zq.x), i0.y, 1, lo);
+                lo = put_code(subz_lo(r[j][8 * k + 2], zq.y), i0.z, 2, lo);
+                lo = put_code(subz_hi(r[j][8 * k + 3], zq.y), i0.w, 3, lo);
+                hi = put_code(subz_lo(r[j][8 * k + 4], zq.z), i1.x, 0, hi);
+                hi = put_code(subz_hi(r[j][8 * k + 5], zq.z), i1.y, 1, hi);
+                hi = put_code(subz_lo(r[j][8 * k + 6], zq.w), i1.z, 2, hi);
+                hi = put_code(subz_hi(r[j][8 * k + 7], zq.w), i1.w, 3, hi);
 #pragma unroll
-                for (int p = 0; p < BITS; ++p) pl[p] = 0u;
-                shift_in<BITS>(pl, code_word(subz_lo(r[j][8 * k + 0], zq.x), i0.x));
-                shift_in<BITS>(pl, code_word(subz_hi(r[j][8 * k + 1], zq.x), i0.y));
-                shift_in<BITS>(pl, code_word(subz_lo(r[j][8 * k + 2], zq.y), i0.z));
-                shift_in<BITS>(pl, code_word(subz_hi(r[j][8 * k + 3], zq.y), i0.w));
-                shift_in<BITS>(pl, code_word(subz_lo(r[j][8 * k + 4], zq.z), i1.x));
-                shift_in<BITS>(pl, code_word(subz_hi(r[j][8 * k + 5], zq.z), i1.y));
-                shift_in<BITS>(pl, code_word(subz_lo(r[j][8 * k + 6], zq.w), i1.z));
-                shift_in<BITS>(pl, code_word(subz_hi(r[j][8 * k + 7], zq.w), i1.w));
-#pragma unroll
-                for (int p = 0; p < BITS; ++p) mine[(k * BITS + p) * 4] = (uint8_t)(pl[p] >> 24);
+                for (int p = 0; p < BITS; ++p) mine[(k * BITS + p) * 4] = (uint8_t)(plane_byte_shifted(lo, hi, p) >> p);
             }
             if (kb == 0) stg[16 * 16 * BITS + n] = (uint8_t)bi[j];
             wave_lds_sync();
@@ -581,21 +579,21 @@ __global__ __launch_bounds__(256) void quantize_v_kernel(QuantArgs a, int tiles_
         uint32_t *stg = reinterpret_cast<uint32_t *>(wsc + kWsCodes);
 #pragma unroll
         for (int b = 0; b < 2; ++b) {
-            uint32_t pl[BITS];
-#pragma unroll
-            for (int p = 0; p < BITS; ++p) pl[p] = 0u;
+            uint32_t cw[4] = {0u, 0u, 0u, 0u};   // codes of elements 4q .. 4q+3 in the bytes of cw[q]
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const int e = 16 * b + i, g = (e / 8) / BPG;
-                shift_in<BITS>(pl, code_word(r[e] - z[g], inv[g]));
+                cw[i >> 2] = put_code(r[e] - z[g], inv[g], i & 3, cw[i >> 2]);
             }
             // channel of this lane after the transpose: i = n
             const int c = 32 * (2 * b + (n >> 3)) + 8 * kb + (n & 7);
             uint32_t *dst = stg + ((c & 15) * (kD / 16) + (c >> 4)) * WPU;
 #pragma unroll
             for (int w = 0; w < WPU; ++w) {
-                // low half = top 16 bits of plane 2w, high half = top 16 bits of plane 2w+1
-                const uint32_t x = __builtin_amdgcn_perm(pl[2 * w + 1], pl[2 * w], 0x07060302u);
+                // t_p = (bits p of the 16 codes) << p; low half of x = plane 2w, high half = plane 2w+1
+                const uint32_t t0 = (plane_byte_shifted(cw[2], cw[3], 2 * w) << 8) | plane_byte_shifted(cw[0], cw[1], 2 * w);
+                const uint32_t t1 = (plane_byte_shifted(cw[2], cw[3], 2 * w + 1) << 8) | plane_byte_shifted(cw[0], cw[1], 2 * w + 1);
+                const uint32_t x = (t0 >> (2 * w)) | (t1 << (15 - 2 * w));
                 dst[w] = transpose16(x, tc);
             }
         }

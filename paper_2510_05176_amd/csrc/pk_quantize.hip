@@ -317,17 +317,11 @@ __device__ __forceinline__ void load_tile(const QuantArgs &a, int ns, int i0, ui
     for (int k = 0; k < 4; ++k) xb[k] = *reinterpret_cast<const uint4 *>(row + 32 * k + 8 * kb);
 }
 
-// Nearest pattern of the tile's tokens (exact), returned; residuals r[8k + j] of channel 32k + 8kb + j.
+// Residuals r[8k + j] of channel 32k + 8kb + j of the lane's token against pattern bi.
 template <bool TAB_LDS>
-__device__ __forceinline__ int assign_residuals(const TileShared &sh, const PatternTable &tb, const __half *Mg,
-                                                const uint4 (&xb)[4], __half *xrow, float (&r)[32])
+__device__ __forceinline__ void residuals(const TileShared &sh, const __half *Mg, const uint4 (&xb)[4], int bi, float (&r)[32])
 {
-    const int lane = threadIdx.x & 63, kb = lane >> 4;
-    int bi;
-    float bv, x2, bd;
-    bool flag;
-    assign_tile_mfma<TAB_LDS>(xb, tb, lane, bi, bv, x2, flag);
-    resolve_flagged(xb, flag, xrow, tb, Mg, lane, bi, bd);
+    const int kb = (threadIdx.x & 63) >> 4;
     const __half *mrow = TAB_LDS ? sh.tab + bi * kTabStride + 8 * kb : Mg + (int64_t)bi * kD + 8 * kb;
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
@@ -342,6 +336,27 @@ __device__ __forceinline__ int assign_residuals(const TileShared &sh, const Patt
         r[8 * k + 6] = sub_lo(xv.w, mv.w);
         r[8 * k + 7] = sub_hi(xv.w, mv.w);
     }
+}
+
+// Nearest pattern of the tile's tokens (exact).
+template <bool TAB_LDS>
+__device__ __forceinline__ int assign_index(const PatternTable &tb, const __half *Mg, const uint4 (&xb)[4], __half *xrow)
+{
+    const int lane = threadIdx.x & 63;
+    int bi;
+    float bv, x2, bd;
+    bool flag;
+    assign_tile_mfma<TAB_LDS>(xb, tb, lane, bi, bv, x2, flag);
+    resolve_flagged(xb, flag, xrow, tb, Mg, lane, bi, bd);
+    return bi;
+}
+
+template <bool TAB_LDS>
+__device__ __forceinline__ int assign_residuals(const TileShared &sh, const PatternTable &tb, const __half *Mg,
+                                                const uint4 (&xb)[4], __half *xrow, float (&r)[32])
+{
+    const int bi = assign_index<TAB_LDS>(tb, Mg, xb, xrow);
+    residuals<TAB_LDS>(sh, Mg, xb, bi, r);
     return bi;
 }
 
@@ -351,6 +366,46 @@ __device__ __forceinline__ void wave_lds_sync()
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Codes of the lane's 32 channels of one token against the group's parameters in LDS (zero points as fp16
+// bits, 1/s as binary32, indexed by channel); 8 channels = one byte of a plane word, written to the token's
+// row of the staging area stg ([16 tokens][4 words][BITS planes] words, memory order).
+template <int BITS>
+__device__ __forceinline__ void k_codes_to_staging(const float (&r)[32], const uint16_t *pz, const float *pinv, uint8_t *stg)
+{
+    const int lane = threadIdx.x & 63, n = lane & 15, kb = lane >> 4;
+    uint8_t *mine = stg + n * 16 * BITS + kb;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const uint4 zq = *reinterpret_cast<const uint4 *>(pz + 32 * k + 8 * kb);
+        const float4 i0 = *reinterpret_cast<const float4 *>(pinv + 32 * k + 8 * kb);
+        const float4 i1 = *reinterpret_cast<const float4 *>(pinv + 32 * k + 8 * kb + 4);
+        uint32_t lo = 0u, hi = 0u;
+        lo = put_code(subz_lo(r[8 * k + 0], zq.x), i0.x, 0, lo);
+        lo = put_code(subz_hi(r[8 * k + 1], zq.x), i0.y, 1, lo);
+        lo = put_code(subz_lo(r[8 * k + 2], zq.y), i0.z, 2, lo);
+        lo = put_code(subz_hi(r[8 * k + 3], zq.y), i0.w, 3, lo);
+        hi = put_code(subz_lo(r[8 * k + 4], zq.z), i1.x, 0, hi);
+        hi = put_code(subz_hi(r[8 * k + 5], zq.z), i1.y, 1, hi);
+        hi = put_code(subz_lo(r[8 * k + 6], zq.w), i1.z, 2, hi);
+        hi = put_code(subz_hi(r[8 * k + 7], zq.w), i1.w, 3, hi);
+#pragma unroll
+        for (int p = 0; p < BITS; ++p) mine[(k * BITS + p) * 4] = (uint8_t)(plane_byte_shifted(lo, hi, p) >> p);
+    }
+}
+
+// Staging area -> global: the 16 tokens' code words as one contiguous run, then their 16 indices.
+template <int BITS>
+__device__ __forceinline__ void k_store_staging(const QuantArgs &a, int64_t tok0, const uint8_t *stg)
+{
+    const int lane = threadIdx.x & 63;
+    uint8_t *codes = reinterpret_cast<uint8_t *>(a.codes_k);
+    if (BITS == 2)
+        reinterpret_cast<uint2 *>(codes + tok0 * 32)[lane] = reinterpret_cast<const uint2 *>(stg)[lane];
+    else
+        reinterpret_cast<uint4 *>(codes + tok0 * 64)[lane] = reinterpret_cast<const uint4 *>(stg)[lane];
+    if (lane == 0) *reinterpret_cast<uint4 *>(a.idx + tok0) = *reinterpret_cast<const uint4 *>(stg + 16 * 16 * BITS);
 }
 
 // K: workgroup = 256 threads, tiles of TT = max(64, G) tokens of one stream; wave w owns the 16-token
@@ -377,7 +432,6 @@ __global__ __launch_bounds__(256) void quantize_k_kernel(QuantArgs a, int tiles_
     const PatternTable tb = make_table(sh, Mg, a.P);
 
     const int q = tid % LPC, cc = tid / LPC;
-    uint8_t *codes = reinterpret_cast<uint8_t *>(a.codes_k);
     for (int tile = tile0; tile < tile1; ++tile) {
         const int64_t tq0 = (int64_t)a.t0 + (int64_t)tile * TT;
         float r[NT][32];
@@ -447,35 +501,122 @@ __global__ __launch_bounds__(256) void quantize_k_kernel(QuantArgs a, int tiles_
             const int tl0 = (wave * NT + j) * 16;
             const int grp = G == 32 ? tl0 >> 5 : 0;
             uint8_t *stg = reinterpret_cast<uint8_t *>(sh.rt + tl0 * kRStride);
-            uint8_t *mine = stg + n * 16 * BITS + kb;
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const uint4 zq = *reinterpret_cast<const uint4 *>(sh.pz + grp * kD + 32 * k + 8 * kb);
-                const float4 i0 = *reinterpret_cast<const float4 *>(sh.pinv + grp * kD + 32 * k + 8 * kb);
-                const float4 i1 = *reinterpret_cast<const float4 *>(sh.pinv + grp * kD + 32 * k + 8 * kb + 4);
-                uint32_t lo = 0u, hi = 0u;
-                lo = put_code(subz_lo(r[j][8 * k + 0], zq.x), i0.x, 0, lo);
-                lo = put_code(subz_hi(r[j][8 * k + 1], zq.x), i0.y, 1, lo);
-                lo = put_code(subz_lo(r[j][8 * k + 2], zq.y), i0.z, 2, lo);
-                lo = put_code(subz_hi(r[j][8 * k + 3], zq.y), i0.w, 3, lo);
-                hi = put_code(subz_lo(r[j][8 * k + 4], zq.z), i1.x, 0, hi);
-                hi = put_code(subz_hi(r[j][8 * k + 5], zq.z), i1.y, 1, hi);
-                hi = put_code(subz_lo(r[j][8 * k + 6], zq.w), i1.z, 2, hi);
-                hi = put_code(subz_hi(r[j][8 * k + 7], zq.w), i1.w, 3, hi);
-#pragma unroll
-                for (int p = 0; p < BITS; ++p) mine[(k * BITS + p) * 4] = (uint8_t)(plane_byte_shifted(lo, hi, p) >> p);
-            }
+            k_codes_to_staging<BITS>(r[j], sh.pz + grp * kD, sh.pinv + grp * kD, stg);
             if (kb == 0) stg[16 * 16 * BITS + n] = (uint8_t)bi[j];
             wave_lds_sync();
-            const int64_t tok0 = (int64_t)ns * a.t_capacity + tq0 + tl0;
-            if (BITS == 2)
-                reinterpret_cast<uint2 *>(codes + tok0 * 32)[lane] = reinterpret_cast<const uint2 *>(stg)[lane];
-            else
-                reinterpret_cast<uint4 *>(codes + tok0 * 64)[lane] = reinterpret_cast<const uint4 *>(stg)[lane];
-            if (lane == 0) *reinterpret_cast<uint4 *>(a.idx + tok0) = *reinterpret_cast<const uint4 *>(stg + 16 * 16 * BITS);
+            k_store_staging<BITS>(a, (int64_t)ns * a.t_capacity + tq0 + tl0, stg);
         }
         // the residual tile is rewritten only after the next barrier-separated scan has been passed by
         // every wave: the scan of this tile ended before the barrier above
+    }
+}
+
+// K, groups of 32 or 64 tokens: a wave owns whole groups, so nothing but the pattern table is shared in
+// the workgroup and no workgroup barrier is needed after it is staged.  The group's NTG = G/16 tiles stay
+// in registers as loaded (fp16); pass A assigns every tile and feeds its residuals through a small LDS
+// tile to a per-channel running minimum / maximum (lane <-> channel), pass B forms the residuals again,
+// quantizes and stores.  A tile's registers are refilled with the wave's next group as soon as pass B
+// has used them.
+constexpr int kWkStride = 64 + 4;                     // floats per row of the half-width residual tile
+constexpr int kWkTile = 16 * kWkStride * 4;           // bytes: 16 tokens x 64 channels
+constexpr int kWkWave = kWkTile + kD * 2 * 2 + kD * 4;   // + zero points, scales (fp16 bits), 1/s
+
+static size_t wave_k_lds_bytes(int P, bool tab_lds)
+{
+    return (tab_lds ? (size_t)pad16(P) * kTabStride * 2 : 0) + (size_t)pad16(P) * 4 + 16 + 4 * (size_t)kWkWave;
+}
+
+template <int G, int BITS, bool TAB_LDS>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void quantize_k_wave_kernel(QuantArgs a, int tiles_per_wg)
+{
+    constexpr int NTG = G / 16;
+    static_assert(G == 32 || G == 64, "a wave holds the group's tiles in registers");
+    static_assert(16 * 16 * BITS + 16 <= kWkTile, "output staging fits the residual tile");
+    extern __shared__ __align__(16) unsigned char smem[];
+    TileShared sh;
+    size_t at = 0;
+    sh.tab = reinterpret_cast<__half *>(smem);
+    at += TAB_LDS ? (size_t)pad16(a.P) * kTabStride * 2 : 0;
+    sh.nh = reinterpret_cast<float *>(smem + at);
+    at += (size_t)pad16(a.P) * 4;
+    sh.red = reinterpret_cast<float *>(smem + at);
+    at += 16;
+    const int tid = threadIdx.x, ns = blockIdx.y;
+    const int lane = tid & 63, wave = tid >> 6, n = lane & 15, kb = lane >> 4;
+    unsigned char *mine = smem + at + (size_t)wave * kWkWave;
+    float *rt = reinterpret_cast<float *>(mine);
+    uint16_t *pz = reinterpret_cast<uint16_t *>(mine + kWkTile);   // [kD] zero points, then [kD] scales
+    float *pinv = reinterpret_cast<float *>(mine + kWkTile + kD * 2 * 2);
+
+    const __half *Mg = a.patterns + (int64_t)a.sets.set_of(ns) * a.P * kD;
+    const int n_tiles = a.nq / 64;
+    const int tile0 = blockIdx.x * tiles_per_wg, tile1 = min(n_tiles, tile0 + tiles_per_wg);
+    const int g_end = tile1 * (64 / G);
+    int g = tile0 * (64 / G) + wave;
+    uint4 xb[NTG][4];
+    if (g < g_end) {
+#pragma unroll
+        for (int j = 0; j < NTG; ++j) load_tile(a, ns, g * G + j * 16, xb[j]);   // in flight while the table is staged
+    }
+    stage_patterns(Mg, a.P, sh.tab, sh.nh, sh.red, TAB_LDS);
+    const PatternTable tb = make_table(sh, Mg, a.P);
+
+    for (; g < g_end; g += 4) {
+        const int64_t tq0 = (int64_t)a.t0 + (int64_t)g * G;   // packed position of the group's first token
+        // ---- pass A: indices, running minimum / maximum of channels lane and lane + 64
+        float mn[2] = {INFINITY, INFINITY}, mx[2] = {-INFINITY, -INFINITY};
+        int bi[NTG];
+#pragma unroll
+        for (int j = 0; j < NTG; ++j) {
+            float r[32];
+            bi[j] = assign_residuals<TAB_LDS>(sh, tb, Mg, xb[j], reinterpret_cast<__half *>(rt), r);
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {   // channels 64h .. 64h+63 = operand steps k = 2h, 2h+1
+#pragma unroll
+                for (int kk = 0; kk < 2; ++kk) {
+                    const int e = 8 * (2 * h + kk);
+                    float4 *dst = reinterpret_cast<float4 *>(rt + n * kWkStride + 32 * kk + 8 * kb);
+                    dst[0] = make_float4(r[e], r[e + 1], r[e + 2], r[e + 3]);
+                    dst[1] = make_float4(r[e + 4], r[e + 5], r[e + 6], r[e + 7]);
+                }
+                wave_lds_sync();
+#pragma unroll
+                for (int t = 0; t < 16; t += 2) {
+                    const float v0 = rt[t * kWkStride + lane], v1 = rt[(t + 1) * kWkStride + lane];
+                    mn[h] = fminf(fminf(mn[h], v0), v1);
+                    mx[h] = fmaxf(fmaxf(mx[h], v0), v1);
+                }
+                wave_lds_sync();
+            }
+        }
+        // ---- parameters of the group: channel lane + 64h
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const GroupParams gp = group_params(mn[h], mx[h], BITS);
+            pz[64 * h + lane] = gp.z16;
+            pz[kD + 64 * h + lane] = gp.s16;
+            pinv[64 * h + lane] = gp.inv;
+        }
+        wave_lds_sync();
+        if (lane < 32) {   // stored parameters: 16-byte pieces, zero points then scales
+            const int arr = lane >> 4, piece = lane & 15;
+            const uint4 v = *reinterpret_cast<const uint4 *>(pz + arr * kD + piece * 8);
+            __half *dstp = (arr ? a.scale : a.zero) + ((int64_t)ns * (a.t_capacity / G) + tq0 / G) * kD + piece * 8;
+            *reinterpret_cast<uint4 *>(dstp) = v;
+        }
+        // ---- pass B: residuals again, codes, planes; the tile's registers then take the next group
+        uint8_t *stg = reinterpret_cast<uint8_t *>(rt);
+#pragma unroll
+        for (int j = 0; j < NTG; ++j) {
+            float r[32];
+            residuals<TAB_LDS>(sh, Mg, xb[j], bi[j], r);
+            if (g + 4 < g_end) load_tile(a, ns, (g + 4) * G + j * 16, xb[j]);
+            k_codes_to_staging<BITS>(r, pz, pinv, stg);
+            if (kb == 0) stg[16 * 16 * BITS + n] = (uint8_t)bi[j];
+            wave_lds_sync();
+            k_store_staging<BITS>(a, (int64_t)ns * a.t_capacity + tq0 + j * 16, stg);
+            wave_lds_sync();   // the staging area is rewritten by the next tile
+        }
     }
 }
 
@@ -660,8 +801,14 @@ hipError_t launch_quantize_k(const QuantArgs &a, hipStream_t s)
         return tl ? launch_tiled(quantize_k_kernel<GG, BB, true>, a, TT, tile_lds_bytes(a.P, true, TT, GG), s)     \
                   : launch_tiled(quantize_k_kernel<GG, BB, false>, a, TT, tile_lds_bytes(a.P, false, TT, GG), s);  \
     }
-        PK_LAUNCH_K2(32, 2) PK_LAUNCH_K2(64, 2) PK_LAUNCH_K2(128, 2)
-        PK_LAUNCH_K2(32, 4) PK_LAUNCH_K2(64, 4) PK_LAUNCH_K2(128, 4)
+#define PK_LAUNCH_KW(GG, BB)                                                                                       \
+    if (a.G == GG && a.bits == BB) {                                                                               \
+        return tl ? launch_tiled(quantize_k_wave_kernel<GG, BB, true>, a, 64, wave_k_lds_bytes(a.P, true), s)      \
+                  : launch_tiled(quantize_k_wave_kernel<GG, BB, false>, a, 64, wave_k_lds_bytes(a.P, false), s);   \
+    }
+        PK_LAUNCH_KW(32, 2) PK_LAUNCH_KW(64, 2) PK_LAUNCH_K2(128, 2)
+        PK_LAUNCH_KW(32, 4) PK_LAUNCH_KW(64, 4) PK_LAUNCH_K2(128, 4)
+#undef PK_LAUNCH_KW
 #undef PK_LAUNCH_K2
         return hipErrorInvalidValue;
     }

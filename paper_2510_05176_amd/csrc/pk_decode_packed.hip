@@ -93,7 +93,7 @@ struct GroupOperand {
 };
 
 template <int BITS, bool G32>
-__global__ __launch_bounds__(256) void decode_packed_kernel(DecodeArgs a)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void decode_packed_kernel(DecodeArgs a)
 {
     constexpr int WPU = BITS / 2;   // 32-bit words per (channel, 16-token unit) of V; K: 4*BITS words per token
     __shared__ float QMs[kMaxP][16];
@@ -114,12 +114,13 @@ __global__ __launch_bounds__(256) void decode_packed_kernel(DecodeArgs a)
     const int cap = cv.t_capacity;
 
     const int R = a.n_q_heads / a.n_kv_heads, G = a.G, P = a.P;
+    const int lgG = 31 - __clz(G);   // G is a power of two
     const int Gc = G < kD ? G : kD, NG = kD / Gc;
     const bool col_ok = n < R * NG;
     const int h = col_ok ? n % R : 0, g = col_ok ? n / R : 0;
     const __half *MK = a.patterns_k + (int64_t)set * P * kD;
     const float sc2 = a.softmax_scale * kLog2e;
-    const float c1 = sc2 * 65536.f;
+    const float c1 = sc2 * 65536.f, inv_c1 = 1.f / c1;
 
     // ---- this lane's slice of its query head: channels 32*kb .. 32*kb+31
     _Float16 qh[32];
@@ -171,24 +172,37 @@ __global__ __launch_bounds__(256) void decode_packed_kernel(DecodeArgs a)
     const int per = (n_blocks + 3) >> 2;
     const int b0 = wave * per, b1 = min(n_blocks, b0 + per);
 
-    float m_run = -INFINITY, l_run = 0.f, pzacc = 0.f;
+    // Online softmax state per column.  Scores are formed relative to m_run (the reference enters the
+    // matrix-core accumulator), so the exponentials need no subtraction; the reference is raised only
+    // when a block exceeds it.
+    float m_run = 0.f, l_run = 0.f, pzacc = 0.f;
+    bool started = false;
     floatx4 O[8];
 #pragma unroll
     for (int t = 0; t < 8; ++t) O[t] = floatx4{0.f, 0.f, 0.f, 0.f};
     GroupOperand ga, gb;   // gb: second K group of a block, only when G == 32
-    int cur_group = -1;
 
-    auto load_group = [&](int grp, GroupOperand &go) {
-        const int64_t prow = ((int64_t)cstream * (cap / G) + grp) * kD + 32 * kb;
+    // parameters of one K group: raw loads, then the B operand
+    struct GroupRaw {
+        uint4 s[4], z[4];
+    };
+    auto load_group_raw = [&](int grp, GroupRaw &gr) {
+        const int64_t prow = ((int64_t)cstream * (cap >> lgG) + grp) * kD + 32 * kb;
         const uint4 *sp = reinterpret_cast<const uint4 *>(cv.k_scale + prow);
         const uint4 *zp = reinterpret_cast<const uint4 *>(cv.k_zero + prow);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            gr.s[i] = sp[i];
+            gr.z[i] = zp[i];
+        }
+    };
+    auto build_group = [&](const GroupRaw &gr, GroupOperand &go) {
         _Float16 sh[32];
         float acc = 0.f;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const uint4 sv = sp[i], zv = zp[i];
-            const half2v *hv = reinterpret_cast<const half2v *>(&sv);
-            const uint32_t *zu = reinterpret_cast<const uint32_t *>(&zv);
+            const half2v *hv = reinterpret_cast<const half2v *>(&gr.s[i]);
+            const uint32_t *zu = reinterpret_cast<const uint32_t *>(&gr.z[i]);
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 sh[8 * i + 2 * k] = hv[k][0];
@@ -213,21 +227,10 @@ __global__ __launch_bounds__(256) void decode_packed_kernel(DecodeArgs a)
     const uint8_t *kidx = cv.k_idx + (int64_t)cstream * cap;
     const uint8_t *vidx = cv.v_idx + (int64_t)cstream * cap;
 
-    for (int b = b0; b < b1; ++b) {
-        const int tb = t_begin + (b << 6);
-        if (G32) {
-            load_group(tb >> 5, ga);
-            load_group((tb >> 5) + 1, gb);
-        } else {
-            const int grp = tb / G;
-            if (grp != cur_group) {
-                load_group(grp, ga);
-                cur_group = grp;
-            }
-        }
-
-        // ---- loads of the block
-        uint32_t kw[4][BITS];
+    // K-side inputs of a block: plane words of this lane's 4 token rows, pattern indices of its 16 tokens
+    uint32_t kw[4][BITS];
+    uint4 kid;
+    auto load_k = [&](int tb) {
 #pragma unroll
         for (int x = 0; x < 4; ++x) {
             const int tok = tb + 16 * (n >> 2) + 4 * x + (n & 3);
@@ -244,8 +247,26 @@ __global__ __launch_bounds__(256) void decode_packed_kernel(DecodeArgs a)
                 kw[x][BITS - 1] = v.w;
             }
         }
+        kid = *reinterpret_cast<const uint4 *>(kidx + tb + 16 * kb);
+    };
+
+    if (b0 < b1) {
+        const int tb = t_begin + (b0 << 6);
+        load_k(tb);
+        GroupRaw gr;
+        load_group_raw(tb >> lgG, gr);
+        build_group(gr, ga);
+        if (G32) {
+            load_group_raw((tb >> lgG) + 1, gr);
+            build_group(gr, gb);
+        }
+    }
+
+    for (int b = b0; b < b1; ++b) {
+        const int tb = t_begin + (b << 6);
+
+        // ---- V-side loads of the block (used after the scores)
         const int unit = (tb >> 4) + kb;   // 16-token unit of this lane group
-        const uint4 kid = *reinterpret_cast<const uint4 *>(kidx + tb + 16 * kb);
         const uint4 vid = *reinterpret_cast<const uint4 *>(vidx + tb + 16 * kb);
         uint32_t vw[8 * WPU];
         {
@@ -271,15 +292,18 @@ __global__ __launch_bounds__(256) void decode_packed_kernel(DecodeArgs a)
             }
         }
 
-        // ---- K side: scores of the 64 tokens (this lane: column n, tokens 16*kb + 0..15), log2 domain
+        // ---- K side: scores of the 64 tokens relative to m_run (this lane: column n, tokens 16*kb + 0..15),
+        //      log2 domain.  The accumulator starts at (q.z - m_run) / c1.
         float S[16];
         const uint32_t kidw[4] = {kid.x, kid.y, kid.z, kid.w};
+        const float d0 = (ga.qz - m_run) * inv_c1;
+        const float d02 = G32 ? (gb.qz - m_run) * inv_c1 : 0.f;
 #pragma unroll
         for (int x = 0; x < 4; ++x) {
             uint32_t A16[16];
             fields_to_operand(bfi(0x55555555u, kw[x][0], kw[x][1] << 1), A16);
             fields_to_operand(bfi(0x55555555u, kw[x][0] >> 1, kw[x][1]), A16 + 8);
-            floatx4 d = {0.f, 0.f, 0.f, 0.f}, d2 = {0.f, 0.f, 0.f, 0.f};
+            floatx4 d = {d0, d0, d0, d0}, d2 = {d02, d02, d02, d02};
 #pragma unroll
             for (int s = 0; s < 4; ++s) d = mfma16(&A16[4 * s], &ga.Bq[4 * s], d);
             if (G32) {
@@ -300,27 +324,31 @@ __global__ __launch_bounds__(256) void decode_packed_kernel(DecodeArgs a)
                     d2 += 4.f * e2;
                 }
             }
-            float qz = ga.qz;
-            if (G32 && kb >= 2) {
-                d = d2;
-                qz = gb.qz;
-            }
+            if (G32 && kb >= 2) d = d2;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int id = (kidw[x] >> (8 * i)) & 255;
-                S[4 * x + i] = fmaf(d[i], c1, QMs[id][n] + qz);
+                S[4 * x + i] = fmaf(d[i], c1, QMs[id][n]);
             }
         }
 
+        // ---- next block's K-side inputs and group parameters: in flight during the rest of this block
+        const bool more = b + 1 < b1;
+        const int tbn = tb + 64;
+        const bool new_group = more && (G32 || (tbn >> lgG) != (tb >> lgG));
+        GroupRaw gr;
+        if (more) load_k(tbn);
+        if (new_group) load_group_raw(tbn >> lgG, gr);
+
         // ---- online softmax (per column; the four lane groups hold different tokens)
-        float mx = S[0];
+        float bmax = fmaxf(S[0], S[1]);
 #pragma unroll
-        for (int k = 1; k < 16; ++k) mx = fmaxf(mx, S[k]);
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run, mx);
-        if (__ballot(m_new > m_run) != 0ull) {
-            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);   // 0 on the first block
+        for (int k = 2; k < 16; k += 2) bmax = fmaxf(fmaxf(bmax, S[k]), S[k + 1]);
+        if (!started || __ballot(bmax > 0.f) != 0ull) {
+            bmax = fmaxf(bmax, __shfl_xor(bmax, 16));
+            bmax = fmaxf(bmax, __shfl_xor(bmax, 32));
+            const float delta = started ? fmaxf(bmax, 0.f) : bmax;
+            const float alpha = started ? __builtin_amdgcn_exp2f(-delta) : 0.f;
             l_run *= alpha;
             pzacc *= alpha;
 #pragma unroll
@@ -329,18 +357,20 @@ __global__ __launch_bounds__(256) void decode_packed_kernel(DecodeArgs a)
 #pragma unroll
                 for (int t = 0; t < 8; ++t) O[t][i] *= ar;
             }
-            for (int hh = 0; hh < R; ++hh) {
-                const float ar = __shfl(alpha, hh);
-                for (int p = lane; p < P; p += 64) Ws[wave][hh][p] *= ar;
+            if (started) {
+                for (int hh = 0; hh < R; ++hh) {
+                    const float ar = __shfl(alpha, hh);
+                    for (int p = lane; p < P; p += 64) Ws[wave][hh][p] *= ar;
+                }
             }
-            m_run = m_new;
+            m_run += delta;
+#pragma unroll
+            for (int k = 0; k < 16; ++k) S[k] -= delta;
+            started = true;
         }
         float pr[16];
 #pragma unroll
-        for (int k = 0; k < 16; ++k) {
-            pr[k] = __builtin_amdgcn_exp2f(S[k] - m_run);
-            l_run += pr[k];
-        }
+        for (int k = 0; k < 16; ++k) pr[k] = __builtin_amdgcn_exp2f(S[k]);
 
         // ---- softmax mass per V pattern (columns of group 0 carry the heads once)
         if (n < R) {
@@ -351,13 +381,19 @@ __global__ __launch_bounds__(256) void decode_packed_kernel(DecodeArgs a)
 
         // ---- V side
         uint32_t Ap[8], Ap4[8];
+        const uint32_t ones = pack2((_Float16)1.f, (_Float16)1.f);
 #pragma unroll
         for (int V = 0; V < 8; ++V) {
             const uint32_t ph = cvt2(pr[2 * V], pr[2 * V + 1]);
             pzacc = dot2(ph, zv[V], pzacc);
+            l_run = dot2(ph, ones, l_run);   // the denominator sums the same rounded weights the numerator uses
             const _Float16 c = (_Float16)(float)(1 << (8 - fpos(V)));
             Ap[V] = pk_mul(pk_mul(ph, sv[V]), pack2(c, c));
             if (BITS == 4) Ap4[V] = pk_mul(Ap[V], pack2((_Float16)4.f, (_Float16)4.f));
+        }
+        if (G32 && new_group) {   // first group done here, so that one set of registers serves both loads
+            build_group(gr, ga);
+            load_group_raw((tbn >> lgG) + 1, gr);
         }
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
@@ -379,7 +415,11 @@ __global__ __launch_bounds__(256) void decode_packed_kernel(DecodeArgs a)
                 O[t] = mfma16(&Ap4[4], &Bv[4], O[t]);
             }
         }
+
+        // ---- B operand of the next block's K group(s)
+        if (new_group) build_group(gr, G32 ? gb : ga);
     }
+    if (!started) m_run = -INFINITY;   // a wave without blocks contributes nothing to the merge
 
     // ---- merge the four waves of the workgroup
     l_run += __shfl_xor(l_run, 16);

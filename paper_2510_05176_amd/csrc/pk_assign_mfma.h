@@ -40,34 +40,26 @@ __device__ __forceinline__ floatx4_t mfma_f16(const uint4 &a, const uint4 &b, fl
 }
 
 // Stage a pattern table into LDS (256 threads) and compute the row norms.  Ends with a barrier.
+// Work item i = (row i/16, 16-byte piece i%16): the 16 lanes of a row sum their squares.
 __device__ __forceinline__ void stage_patterns(const __half *Mg, int P, __half *tab_s, float *nh_s, float *red_s,
                                                bool to_lds)
 {
     const int tid = threadIdx.x;
-    if (to_lds) {
-        for (int i = tid; i < pad16(P) * kRowChunks; i += 256) {
-            const int r = i >> 4, ch = i & 15;
-            uint4 v = make_uint4(0u, 0u, 0u, 0u);
-            if (r < P) v = *reinterpret_cast<const uint4 *>(Mg + (int64_t)r * kD + ch * 8);
-            *reinterpret_cast<uint4 *>(tab_s + r * kTabStride + ch * 8) = v;
-        }
-    }
     float mx = 0.f;
-    for (int p = tid; p < P; p += 256) {
+    for (int i = tid; i < pad16(P) * kRowChunks; i += 256) {   // pad16(P) * 16 is a multiple of 256
+        const int r = i >> 4, ch = i & 15;
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (r < P) v = *reinterpret_cast<const uint4 *>(Mg + (int64_t)r * kD + ch * 8);
+        if (to_lds) *reinterpret_cast<uint4 *>(tab_s + r * kTabStride + ch * 8) = v;   // rows past P are zero
+        const half2_t *h = reinterpret_cast<const half2_t *>(&v);
         float acc = 0.f;
-        for (int ch = 0; ch < kRowChunks; ++ch) {
-            const uint4 v = *reinterpret_cast<const uint4 *>(Mg + (int64_t)p * kD + ch * 8);
-            const half2_t *h = reinterpret_cast<const half2_t *>(&v);
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const float a = (float)h[k][0], b = (float)h[k][1];
-                acc = fmaf(a, a, fmaf(b, b, acc));
-            }
-        }
-        nh_s[p] = -0.5f * acc;
+        for (int k = 0; k < 4; ++k) acc = __builtin_amdgcn_fdot2(h[k], h[k], acc, false);
+#pragma unroll
+        for (int off = 1; off < 16; off <<= 1) acc += __shfl_xor(acc, off);
+        if (ch == 0) nh_s[r] = r < P ? -0.5f * acc : -INFINITY;   // rows past the table never win
         mx = fmaxf(mx, acc);
     }
-    for (int p = P + tid; p < pad16(P); p += 256) nh_s[p] = -INFINITY;   // rows past the table never win
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
     if ((tid & 63) == 0) red_s[tid >> 6] = mx;

@@ -23,18 +23,29 @@ __global__ __launch_bounds__(256) void mine_init_kernel(MineArgs a)
 }
 
 // Assignment step + partial cluster sums of one chunk of one set.  256 threads.
-// Dynamic LDS: [table pad16(P) rows (TAB_LDS only)] [-norm2/2 pad16(P)] [sums P*kD] [cnt P] [idx chunk bytes] [xrow 4*kD halves]
-template <bool TAB_LDS>
+// The chunk is walked in sub-tiles of 64 vectors: every wave assigns 16 of them on the matrix cores and
+// leaves them, with their indices, in an LDS tile.  The cluster sums are a second contraction on the
+// matrix cores, sums[p][c] += sum_t onehot[p][t] x[t][c]: wave w owns channels 32w .. 32w+31 and keeps
+// its NPT x 2 accumulator tiles in registers for the whole chunk.  The one-hot operand is formed in packed
+// fp16 as clamp(1 - (idx_t - p)^2, 0, 1), which is exactly 1 or 0 for integers below 256; products are
+// exact and the accumulation order is fixed by the instruction sequence, so the sums are reproducible.
+// Dynamic LDS: [table pad16(P) rows (TAB_LDS only)] [-norm2/2 pad16(P)] [cnt pad16(P)] [xs 64 rows]
+//              [idx 64 bytes] [xrow 4*kD halves]
+constexpr int kMineXs = kD + 8;   // halves per row of the vector tile
+
+typedef _Float16 half2m __attribute__((ext_vector_type(2)));
+
+template <bool TAB_LDS, int NPT>
 __global__ __launch_bounds__(256) void mine_step_kernel(MineArgs a, int chunk)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const int P = a.P;
     __half *tab_s = reinterpret_cast<__half *>(smem);
     float *norm_s = reinterpret_cast<float *>(smem + (TAB_LDS ? (size_t)pad16(P) * kTabStride * 2 : 0));
-    float *sums = norm_s + pad16(P);
-    int *cnt = reinterpret_cast<int *>(sums + (size_t)P * kD);
-    uint8_t *idx_s = reinterpret_cast<uint8_t *>(cnt + P);
-    __half *xrow_s = reinterpret_cast<__half *>(idx_s + chunk);
+    int *cnt = reinterpret_cast<int *>(norm_s + pad16(P));
+    __half *xs = reinterpret_cast<__half *>(cnt + pad16(P));
+    uint8_t *idx_s = reinterpret_cast<uint8_t *>(xs + 64 * kMineXs);
+    __half *xrow_s = reinterpret_cast<__half *>(idx_s + 64);
     __shared__ float red_s[4];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 15, kb = lane >> 4;
@@ -43,8 +54,15 @@ __global__ __launch_bounds__(256) void mine_step_kernel(MineArgs a, int chunk)
     const __half *xg = a.x + (int64_t)s * a.set_stride + (int64_t)t_begin * kD;
     const __half *Mg = a.patterns + (int64_t)s * P * kD;
 
-    for (int i = tid; i < P * kD; i += 256) sums[i] = 0.f;
-    for (int i = tid; i < P; i += 256) cnt[i] = 0;
+    auto load_tile = [&](int sub, uint4 (&xb)[4]) {
+        const int tok = min(sub * 64 + wave * 16 + n, n_tok - 1);   // rows past the chunk repeat its last vector
+#pragma unroll
+        for (int k = 0; k < 4; ++k) xb[k] = *reinterpret_cast<const uint4 *>(xg + (int64_t)tok * kD + 32 * k + 8 * kb);
+    };
+    uint4 xb[4];
+    load_tile(0, xb);
+
+    for (int i = tid; i < pad16(P); i += 256) cnt[i] = 0;
     stage_patterns(Mg, P, tab_s, norm_s, red_s, TAB_LDS);   // ends with a barrier
     PatternTable tb;
     tb.lds_rows = tab_s;
@@ -53,50 +71,93 @@ __global__ __launch_bounds__(256) void mine_step_kernel(MineArgs a, int chunk)
     tb.norm2_max = fmaxf(fmaxf(red_s[0], red_s[1]), fmaxf(red_s[2], red_s[3]));
     tb.P = P;
 
-    // ---- assignment: wave w takes the 16-token tiles w, w+4, ...
-    const int n_tiles = (n_tok + 15) >> 4;
-    for (int tile = wave; tile < n_tiles; tile += 4) {
-        const int tok = tile * 16 + n;
-        const int tok_c = min(tok, n_tok - 1);
-        uint4 xb[4];
+    floatx4_t acc[NPT][2];
+    half2m prow[NPT];   // this lane's pattern row of every tile, as a packed pair
 #pragma unroll
-        for (int k = 0; k < 4; ++k) xb[k] = *reinterpret_cast<const uint4 *>(xg + (int64_t)tok_c * kD + 32 * k + 8 * kb);
+    for (int pt = 0; pt < NPT; ++pt) {
+        acc[pt][0] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+        acc[pt][1] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+        const _Float16 v = (_Float16)(float)(16 * pt + n);
+        prow[pt] = half2m{v, v};
+    }
+    const half2m one2 = {(_Float16)1.f, (_Float16)1.f};
+
+    const int n_sub = (n_tok + 63) >> 6;
+    for (int sub = 0; sub < n_sub; ++sub) {
+        const int tl = wave * 16 + n, tok = sub * 64 + tl;
         int bi;
         float bv, x2, bd;
         bool flag;
         assign_tile_mfma<TAB_LDS>(xb, tb, lane, bi, bv, x2, flag);
         bd = fmaxf(bv, 0.f);
         resolve_flagged(xb, flag, xrow_s + wave * kD, tb, Mg, lane, bi, bd);
-        if (kb == 0 && tok < n_tok) {
-            idx_s[tok] = (uint8_t)bi;
-            a.assign[(int64_t)s * a.T + t_begin + tok] = bi;
-            a.best[(int64_t)s * a.T + t_begin + tok] = bd;
-        }
-    }
-    __syncthreads();
-
-    // ---- cluster sums of the chunk: thread <-> channel, vectors in increasing order
-    if (tid < kD) {
-        const int c = tid;
-        for (int t = 0; t < n_tok; t += 16) {
-            __half xv[16];
-            int id[16];
 #pragma unroll
-            for (int u = 0; u < 16; ++u) {
-                const int tt = min(t + u, n_tok - 1);
-                xv[u] = xg[(int64_t)tt * kD + c];
-                id[u] = idx_s[tt];
+        for (int k = 0; k < 4; ++k)   // a row past the chunk is stored as zeros, so it adds nothing to any sum
+            *reinterpret_cast<uint4 *>(xs + tl * kMineXs + 32 * k + 8 * kb) = tok < n_tok ? xb[k] : make_uint4(0u, 0u, 0u, 0u);
+        if (kb == 0) {
+            idx_s[tl] = (uint8_t)bi;
+            if (tok < n_tok) {
+                a.assign[(int64_t)s * a.T + t_begin + tok] = bi;
+                a.best[(int64_t)s * a.T + t_begin + tok] = bd;
+                atomicAdd(&cnt[bi], 1);
+            }
+        }
+        if (sub + 1 < n_sub) load_tile(sub + 1, xb);   // in flight during the accumulation
+        __syncthreads();
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {   // 32 vectors per step; this lane's k-slots: vectors 32ks + 8kb + j
+            const int t0 = 32 * ks + 8 * kb;
+            const uint2 id8 = *reinterpret_cast<const uint2 *>(idx_s + t0);
+            half2m idh[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t w = j < 2 ? id8.x : id8.y;
+                const int sh = 16 * (j & 1);
+                idh[j] = half2m{(_Float16)(float)((w >> sh) & 255u), (_Float16)(float)((w >> (sh + 8)) & 255u)};
+            }
+            uint4 bop[2];
+#pragma unroll
+            for (int ci = 0; ci < 2; ++ci) {
+                const __half *col = xs + t0 * kMineXs + 16 * (2 * wave + ci) + n;
+                uint32_t w[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t lo = __half_as_ushort(col[(2 * j) * kMineXs]);
+                    const uint32_t hi = __half_as_ushort(col[(2 * j + 1) * kMineXs]);
+                    w[j] = lo | (hi << 16);
+                }
+                bop[ci] = make_uint4(w[0], w[1], w[2], w[3]);
             }
 #pragma unroll
-            for (int u = 0; u < 16; ++u)
-                if (t + u < n_tok) atomicAdd(&sums[id[u] * kD + c], h2f(xv[u]));
+            for (int pt = 0; pt < NPT; ++pt) {
+                uint32_t aop[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const half2m d = idh[j] - prow[pt];
+                    half2m oh = one2 - d * d;                       // 1 where the index equals the row, <= 0 elsewhere
+                    oh = __builtin_elementwise_max(oh, half2m{(_Float16)0.f, (_Float16)0.f});
+                    aop[j] = __builtin_bit_cast(uint32_t, oh);
+                }
+                const uint4 av = make_uint4(aop[0], aop[1], aop[2], aop[3]);
+                acc[pt][0] = mfma_f16(av, bop[0], acc[pt][0]);
+                acc[pt][1] = mfma_f16(av, bop[1], acc[pt][1]);
+            }
         }
-    } else if (tid == kD) {
-        for (int t = 0; t < n_tok; ++t) cnt[idx_s[t]] += 1;
+        __syncthreads();
     }
-    __syncthreads();
+    // partial sums of the chunk: D rows 4kb+i = pattern 16pt + 4kb + i, column n = channel 16(2 wave + ci) + n
     const int64_t o = ((int64_t)s * a.tsplit + ck) * P;
-    for (int i = tid; i < P * kD; i += 256) a.psum[o * kD + i] = sums[i];
+#pragma unroll
+    for (int pt = 0; pt < NPT; ++pt) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int pr = 16 * pt + 4 * kb + i;
+            if (pr < P) {
+                a.psum[(o + pr) * kD + 16 * (2 * wave) + n] = acc[pt][0][i];
+                a.psum[(o + pr) * kD + 16 * (2 * wave + 1) + n] = acc[pt][1][i];
+            }
+        }
+    }
     for (int i = tid; i < P; i += 256) a.pcnt[o + i] = cnt[i];
 }
 
@@ -135,7 +196,8 @@ __global__ __launch_bounds__(256) void mine_inertia_kernel(MineArgs a, int it)
 size_t step_lds_bytes(int P, int chunk, bool tab_lds)
 {
     size_t b = tab_lds ? (size_t)pad16(P) * kTabStride * 2 : 0;
-    b += (size_t)pad16(P) * 4 + (size_t)P * kD * 4 + (size_t)P * 4 + (size_t)chunk + 4 * kD * 2;
+    b += (size_t)pad16(P) * 4 + (size_t)pad16(P) * 4 + 64 * (size_t)kMineXs * 2 + 64 + 4 * kD * 2;
+    (void)chunk;
     return (b + 15) / 16 * 16;
 }
 
@@ -150,29 +212,36 @@ int mine_chunk(int T)
 
 int mine_tsplit(int T) { return (T + mine_chunk(T) - 1) / mine_chunk(T); }
 
+template <bool TAB_LDS, int NPT>
+static hipError_t launch_step(const MineArgs &a, int chunk, size_t lds, hipStream_t s)
+{
+    hipLaunchKernelGGL((mine_step_kernel<TAB_LDS, NPT>), dim3(a.tsplit, a.n_sets), dim3(256), lds, s, a, chunk);
+    return hipGetLastError();
+}
+
+template <bool TAB_LDS, int NPT>
+static hipError_t prepare_step(size_t lds)
+{
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(&mine_step_kernel<TAB_LDS, NPT>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+}
+
 hipError_t launch_mine(const MineArgs &a, hipStream_t s)
 {
     hipError_t e;
     const int chunk = mine_chunk(a.T);
     const bool tab_lds = a.P <= 128;
     const size_t lds = step_lds_bytes(a.P, chunk, tab_lds);
-    if (tab_lds)
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&mine_step_kernel<true>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    else
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&mine_step_kernel<false>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
+    const int npt = a.P <= 16 ? 1 : a.P <= 32 ? 2 : a.P <= 64 ? 4 : a.P <= 128 ? 8 : 16;   // pattern tiles held in registers
+#define PK_STEP(CALL)                                                          \
+    (npt == 1 ? CALL<true, 1> : npt == 2 ? CALL<true, 2> : npt == 4 ? CALL<true, 4> : npt == 8 ? CALL<true, 8> : CALL<false, 16>)
+    if ((e = PK_STEP(prepare_step)(lds)) != hipSuccess) return e;
     if (!a.init_given) {
         hipLaunchKernelGGL(mine_init_kernel, dim3((a.P * kRowChunks + 255) / 256, a.n_sets), dim3(256), 0, s, a);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     for (int it = 0; it < a.iters; ++it) {
-        if (tab_lds)
-            hipLaunchKernelGGL((mine_step_kernel<true>), dim3(a.tsplit, a.n_sets), dim3(256), lds, s, a, chunk);
-        else
-            hipLaunchKernelGGL((mine_step_kernel<false>), dim3(a.tsplit, a.n_sets), dim3(256), lds, s, a, chunk);
-        if ((e = hipGetLastError()) != hipSuccess) return e;
+        if ((e = PK_STEP(launch_step)(a, chunk, lds, s)) != hipSuccess) return e;
         if (a.inertia) {
             hipLaunchKernelGGL(mine_inertia_kernel, dim3(a.n_sets), dim3(256), 0, s, a, it);
             if ((e = hipGetLastError()) != hipSuccess) return e;
@@ -180,6 +249,7 @@ hipError_t launch_mine(const MineArgs &a, hipStream_t s)
         hipLaunchKernelGGL(mine_update_kernel, dim3(a.P, a.n_sets), dim3(128), 0, s, a);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
+#undef PK_STEP
     return hipSuccess;
 }
 

@@ -30,7 +30,6 @@ import numpy as np
 
 HBM_PEAK_GBPS = 8000.0
 MFMA_F16_PEAK_TFLOPS = 2500.0
-VALU_F32_PEAK_TFLOPS = 157.3
 
 WORKLOADS = {
     # name: (spec key, layers, batch, P, iters, group, recent, flush, default bits)
@@ -97,13 +96,18 @@ def main():
     Mk = torch.empty((n_sets, P, d), dtype=torch.float16, device=dev)
     Mv = torch.empty_like(Mk)
     out = torch.empty((n_seq, Hq, d), dtype=torch.float32, device=dev)
-    ws_mine = torch.empty(max(pk.pk_workspace_bytes(cfg, pk.OP_MINE, T, Hkv), 16), dtype=torch.uint8, device=dev)
+    mine_sets = n_sets if B == 1 else Hkv                 # pattern sets mined by one library call
+    ws_mine = torch.empty(max(pk.pk_workspace_bytes(cfg, pk.OP_MINE, T, mine_sets), 16), dtype=torch.uint8, device=dev)
     ws_dec = torch.empty(max(pk.pk_workspace_bytes(cfg, pk.OP_DECODE, T, 0), 16), dtype=torch.uint8, device=dev)
     flush_buf = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
     scale = d ** -0.5
 
     def mine():
         # one table per (layer, KV head), mined on the layer's first batch element
+        if B == 1:      # all layers' streams are uniformly strided: one call per tensor
+            pk.pk_mine_patterns(cfg, K.view(n_sets, T, d), iters, patterns=Mk, workspace=ws_mine)
+            pk.pk_mine_patterns(cfg, V.view(n_sets, T, d), iters, patterns=Mv, workspace=ws_mine)
+            return
         for layer in range(L):
             s = layer * B
             pk.pk_mine_patterns(cfg, K[s], iters, patterns=Mk[layer * Hkv:(layer + 1) * Hkv], workspace=ws_mine)
@@ -156,24 +160,36 @@ def main():
     quant_bytes = N * (cap * (2 * d * 2 + packed_per_tok) + (T - cap) * 2 * d * 2 * 2)   # tail: read + write
     dec_bytes = N * (cap * packed_per_tok + (T - cap) * 2 * d * 2 + 2 * P * d * 2) + n_seq * Hq * d * (2 + 4)
     mine_flops = 2.0 * T * P * d * (2 * L * Hkv) * iters
-    mine_bytes = 2.0 * L * Hkv * iters * T * d * 2
+    mine_bytes = 2.0 * L * Hkv * iters * T * (d * 2 + 8)      # per Lloyd iteration: one pass over x, index + distance out
 
-    def roof(bound, achieved, peak, unit):
+    # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE, scaled by a copy of known
+    # size): written by profiles/collect_traffic.py from runs of this script, read back here
+    traffic = {}
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get("%s_%dbit" % (args.workload, bits), {})
+
+    def roof(stage, bound, achieved, peak, unit, kernels):
         return {"bound": bound, "achieved": round(achieved, 3), "peak": peak, "unit": unit,
-                "frac": round(achieved / peak, 4), "traffic": None}
+                "frac": round(achieved / peak, 4), "traffic": traffic.get(stage), "kernel": kernels}
 
+    # mining: the distance contraction is a dense GEMM only at large P; below that the pass over x binds
+    mine_s = stage_ms["mine"] * 1e-3
+    if P >= 256:
+        mine_roof = roof("mine", "mfma", mine_flops / mine_s / 1e12, MFMA_F16_PEAK_TFLOPS, "TFLOP/s", "mine_step_kernel")
+    else:
+        mine_roof = roof("mine", "hbm", mine_bytes / mine_s / 1e9, HBM_PEAK_GBPS, "GB/s", "mine_step_kernel")
     rl = {
-        "mine": dict(roof("alu", mine_flops / (stage_ms["mine"] * 1e-3) / 1e12, VALU_F32_PEAK_TFLOPS, "TFLOP/s"),
-                     kernel="mine_assign_kernel"),
-        "quantize_append": dict(roof("hbm", quant_bytes / (stage_ms["quantize_append"] * 1e-3) / 1e9, HBM_PEAK_GBPS, "GB/s"),
-                                kernel="quantize_k_kernel+quantize_v_kernel"),
-        "decode_attention": dict(roof("hbm", dec_bytes / (stage_ms["decode_attention"] * 1e-3) / 1e9, HBM_PEAK_GBPS, "GB/s"),
-                                 kernel="decode_packed_kernel"),
+        "mine": mine_roof,
+        "quantize_append": roof("quantize_append", "hbm", quant_bytes / (stage_ms["quantize_append"] * 1e-3) / 1e9,
+                                HBM_PEAK_GBPS, "GB/s", "quantize_k_wave_kernel+quantize_v_kernel"),
+        "decode_attention": roof("decode_attention", "hbm", dec_bytes / (stage_ms["decode_attention"] * 1e-3) / 1e9,
+                                 HBM_PEAK_GBPS, "GB/s", "decode_packed_kernel(+decode_tail_kernel+decode_merge_kernel)"),
     }
     dominant = max(stage_ms, key=stage_ms.get)
     stage_out = {
         "mine": {"ms": round(stage_ms["mine"], 4), "ms_min": round(stage_ms_min["mine"], 4),
-                 "TFLOP/s": rl["mine"]["achieved"], "GB/s": round(mine_bytes / (stage_ms["mine"] * 1e-3) / 1e9, 2)},
+                 "TFLOP/s": round(mine_flops / mine_s / 1e12, 3), "GB/s": round(mine_bytes / mine_s / 1e9, 2)},
         "quantize_append": {"ms": round(stage_ms["quantize_append"], 4), "ms_min": round(stage_ms_min["quantize_append"], 4),
                             "GB/s": rl["quantize_append"]["achieved"], "frac_hbm_peak": rl["quantize_append"]["frac"],
                             "algorithmic_bytes": int(quant_bytes)},

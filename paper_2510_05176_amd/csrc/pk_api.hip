@@ -315,10 +315,11 @@ pk_status pk_decode_attention(const pk_config *cfg, const pk_cache *cache, const
         a.prefix.ring_len = 1;
     }
     const int64_t N = (int64_t)cfg->n_seq * cfg->n_kv_heads, r = cfg->n_q_heads / cfg->n_kv_heads;
-    a.chunk = decode_chunk(N, (int64_t)a.own.t_quant + a.prefix.t_quant);
+    a.chunk = decode_chunk(N, (int64_t)a.own.t_quant + a.prefix.t_quant, cfg->n_patterns, (int)r);
     a.splits_own = (a.own.t_quant + a.chunk - 1) / a.chunk;
     a.splits_prefix = (a.prefix.t_quant + a.chunk - 1) / a.chunk;
     const int64_t slots = a.splits_own + a.splits_prefix + 2;
+    if (slots > kMaxSlots) return PK_ERR_UNSUPPORTED;
     const uint64_t o_bytes = round_up((uint64_t)N * slots * r * kD * 4, 256);
     const uint64_t w_bytes = round_up((uint64_t)N * slots * r * cfg->n_patterns * 4, 256);
     const uint64_t ml_bytes = round_up((uint64_t)N * slots * r * 2 * 4, 256);

@@ -160,51 +160,66 @@ __global__ __launch_bounds__(256) void decode_tail_kernel(DecodeArgs a)
     }
 }
 
-// log-sum-exp merge of the partials of one (sequence, query head); thread <-> channel
+// log-sum-exp merge of the partials of one (sequence, query head); thread <-> channel.
+// The weights exp2(m_s - M) of the slots are formed once, in parallel, and kept in LDS; every loop over the
+// slots is then a run of independent loads.
 __global__ __launch_bounds__(128) void decode_merge_kernel(DecodeArgs a)
 {
     __shared__ float Wt[2][kMaxP];   // softmax mass per pattern: shared prefix, own cache
+    __shared__ float wslot[kMaxSlots];
+    __shared__ float red[2];
     const int u = blockIdx.x, c = threadIdx.x;
     const int seq = u / a.n_q_heads, qh = u - seq * a.n_q_heads;
     const int r = a.n_q_heads / a.n_kv_heads, P = a.P;
     const int head = qh / r, hr = qh - head * r;
     const int n = seq * a.n_kv_heads + head;
-    const int n_slots = a.splits_prefix + a.splits_own + 2;
+    const int n_packed = a.splits_prefix + a.splits_own, n_slots = n_packed + 2;
     const int64_t base = (int64_t)n * n_slots;
+    // maximum over the slots that hold anything
     float M = -INFINITY;
-    for (int s = 0; s < n_slots; ++s) {
+    for (int s = c; s < n_slots; s += 128) {
         const int64_t pb = (base + s) * r + hr;
         if (a.part_ml[pb * 2 + 1] > 0.f) M = fmaxf(M, a.part_ml[pb * 2]);
     }
-    float L = 0.f, acc = 0.f;
-    for (int s = 0; s < n_slots; ++s) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) M = fmaxf(M, __shfl_xor(M, off));
+    if ((c & 63) == 0) red[c >> 6] = M;
+    __syncthreads();
+    M = fmaxf(red[0], red[1]);
+    float L = 0.f;
+    for (int s = c; s < n_slots; s += 128) {
         const int64_t pb = (base + s) * r + hr;
         const float l = a.part_ml[pb * 2 + 1];
-        if (l > 0.f) {
-            const float w = exp2f(a.part_ml[pb * 2] - M);
-            L = fmaf(l, w, L);
-            acc = fmaf(a.part_o[pb * kD + c], w, acc);
-        }
+        const float w = l > 0.f ? exp2f(a.part_ml[pb * 2] - M) : 0.f;
+        wslot[s] = w;
+        L = fmaf(l, w, L);
     }
+    __syncthreads();   // also orders the reads of red above against the writes below
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) L += __shfl_xor(L, off);
+    if ((c & 63) == 0) red[c >> 6] = L;
+    float acc = 0.f;
+#pragma unroll 4
+    for (int s = 0; s < n_slots; ++s) acc = fmaf(a.part_o[((base + s) * r + hr) * kD + c], wslot[s], acc);
     for (int p = c; p < P; p += 128) {
         float wp = 0.f, wo = 0.f;
-        for (int s = 0; s < a.splits_prefix + a.splits_own; ++s) {
-            const int64_t pb = (base + s) * r + hr;
-            if (a.part_ml[pb * 2 + 1] > 0.f) {
-                const float v = a.part_w[pb * P + p] * exp2f(a.part_ml[pb * 2] - M);
-                if (s < a.splits_prefix) wp += v; else wo += v;
-            }
-        }
+#pragma unroll 4
+        for (int s = 0; s < a.splits_prefix; ++s) wp = fmaf(a.part_w[((base + s) * r + hr) * P + p], wslot[s], wp);
+#pragma unroll 4
+        for (int s = a.splits_prefix; s < n_packed; ++s) wo = fmaf(a.part_w[((base + s) * r + hr) * P + p], wslot[s], wo);
         Wt[0][p] = wp;
         Wt[1][p] = wo;
     }
     __syncthreads();
+    L = red[0] + red[1];
     if (a.splits_prefix > 0) {
         const __half *MV = a.patterns_v + (int64_t)head * P * kD;
+#pragma unroll 8
         for (int p = 0; p < P; ++p) acc = fmaf(Wt[0][p], h2f(MV[(int64_t)p * kD + c]), acc);
     }
     if (a.splits_own > 0) {
         const __half *MV = a.patterns_v + (int64_t)a.sets.set_of(n) * P * kD;
+#pragma unroll 8
         for (int p = 0; p < P; ++p) acc = fmaf(Wt[1][p], h2f(MV[(int64_t)p * kD + c]), acc);
     }
     a.out[(int64_t)u * kD + c] = L > 0.f ? acc / L : 0.f;
@@ -213,10 +228,13 @@ __global__ __launch_bounds__(128) void decode_merge_kernel(DecodeArgs a)
 
 }  // namespace
 
-int decode_chunk(int64_t n_streams, int64_t t_packed_total)
+int decode_chunk(int64_t n_streams, int64_t t_packed_total, int P, int r)
 {
-    // aim at ~2048 workgroups; one 64-token block per wave at least, 8192 tokens per split at most
+    // aim at ~2048 workgroups; one 64-token block per wave at least, 8192 tokens per split at most.  Every
+    // split also writes r*P pattern masses and r*128 outputs, so a split should hold a few times r*P tokens.
     int64_t c = (n_streams * t_packed_total + 2047) / 2048;
+    const int64_t floor_c = (int64_t)r * P;
+    if (c < floor_c) c = floor_c;
     c = (c + 255) / 256 * 256;
     if (c < 256) c = 256;
     if (c > 8192) c = 8192;

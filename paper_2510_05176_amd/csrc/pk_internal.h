@@ -144,7 +144,8 @@ struct DecodeArgs {
     float *out, *lse;
 };
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t s);
-int decode_chunk(int64_t n_streams, int64_t t_packed_total);
+int decode_chunk(int64_t n_streams, int64_t t_packed_total, int P, int r);
+constexpr int kMaxSlots = 2304;   // partial slots per stream the merge kernel holds weights for (splits + 2)
 
 struct DequantArgs {
     CacheView c;

@@ -166,12 +166,28 @@ __global__ __launch_bounds__(256) void mine_step_kernel(MineArgs a, int chunk)
 __global__ __launch_bounds__(128) void mine_update_kernel(MineArgs a)
 {
     const int p = blockIdx.x, s = blockIdx.y, c = threadIdx.x;
+    const int64_t o0 = (int64_t)s * a.tsplit * a.P + p, step = a.P;
+    // chunks in increasing order, eight loads in flight at a time; the order of the additions is fixed
     float sum = 0.f;
     int cnt = 0;
-    for (int ts = 0; ts < a.tsplit; ++ts) {
-        const int64_t o = ((int64_t)s * a.tsplit + ts) * a.P + p;
-        sum += a.psum[o * kD + c];
-        cnt += a.pcnt[o];
+    int ts = 0;
+    for (; ts + 8 <= a.tsplit; ts += 8) {
+        float v[8];
+        int k[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            v[u] = a.psum[(o0 + (ts + u) * step) * kD + c];
+            k[u] = a.pcnt[o0 + (ts + u) * step];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            sum += v[u];
+            cnt += k[u];
+        }
+    }
+    for (; ts < a.tsplit; ++ts) {
+        sum += a.psum[(o0 + ts * step) * kD + c];
+        cnt += a.pcnt[o0 + ts * step];
     }
     if (cnt > 0) a.patterns[((int64_t)s * a.P + p) * kD + c] = __float2half_rn(sum / (float)cnt);
 }

@@ -49,6 +49,9 @@ def main():
     ap.add_argument("--bits", type=int, default=2, choices=[2, 4])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=2)
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="also run one 1 GiB elementwise copy kernel (bitwise_not) at the end: the known traffic that "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings of this command are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus must be 1 (no sharding or collectives are part of it)",
@@ -249,6 +252,13 @@ def main():
             "stage_seconds_sample": {"mine": round(t_mine * it_s / iters, 3), "quantize_append": round(t_q, 3),
                                      "decode_attention": round(t_d, 3)},
         }
+    if args.traffic_probe:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(3)
+        dst = torch.empty_like(src)
+        flush_buf.fill_(2)
+        torch.cuda.synchronize()
+        torch.bitwise_not(src, out=dst)      # one dispatch: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
     print(json.dumps(result))
 
 

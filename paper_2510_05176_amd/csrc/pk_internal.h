@@ -116,7 +116,7 @@ struct MineArgs {
     int32_t tsplit;
 };
 hipError_t launch_mine(const MineArgs &a, hipStream_t s);
-int mine_tsplit(int T);
+int mine_tsplit(int T, int n_sets);
 
 struct CacheView {
     const uint32_t *k_codes;

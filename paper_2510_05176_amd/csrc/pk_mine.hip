@@ -219,14 +219,18 @@ size_t step_lds_bytes(int P, int chunk, bool tab_lds)
 
 }  // namespace
 
-int mine_chunk(int T)
+int mine_chunk(int T, int n_sets)
 {
-    int c = (T / 64 + 255) / 256 * 256;   // at most 64 chunks per set
+    // aim at ~2048 workgroups over all sets, at most 64 chunks per set; every chunk writes P*128 partial sums,
+    // so chunks should not be smaller than the parallelism needs
+    int64_t c = ((int64_t)T * n_sets + 2047) / 2048;
+    if (c < (T + 63) / 64) c = (T + 63) / 64;
+    c = (c + 255) / 256 * 256;
     if (c < 256) c = 256;
-    return c;
+    return (int)c;
 }
 
-int mine_tsplit(int T) { return (T + mine_chunk(T) - 1) / mine_chunk(T); }
+int mine_tsplit(int T, int n_sets) { return (T + mine_chunk(T, n_sets) - 1) / mine_chunk(T, n_sets); }
 
 template <bool TAB_LDS, int NPT>
 static hipError_t launch_step(const MineArgs &a, int chunk, size_t lds, hipStream_t s)
@@ -245,7 +249,7 @@ static hipError_t prepare_step(size_t lds)
 hipError_t launch_mine(const MineArgs &a, hipStream_t s)
 {
     hipError_t e;
-    const int chunk = mine_chunk(a.T);
+    const int chunk = mine_chunk(a.T, a.n_sets);
     const bool tab_lds = a.P <= 128;
     const size_t lds = step_lds_bytes(a.P, chunk, tab_lds);
     const int npt = a.P <= 16 ? 1 : a.P <= 32 ? 2 : a.P <= 64 ? 4 : a.P <= 128 ? 8 : 16;   // pattern tiles held in registers

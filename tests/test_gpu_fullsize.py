@@ -1,0 +1,153 @@
+"""Parity at the benchmark's full sizes, in the launch configurations bench.py times.
+
+The oracle cannot run these workloads whole, so each test runs the GPU path on the complete input and
+checks sampled KV streams one by one: the oracle quantizes the sampled stream on its own (its results do
+not depend on the other streams) and must agree with the GPU's rows for that stream to the usual bars -
+packed bytes, fp16 scale / zero and indices bit for bit outside the near-tie band, attention output of the
+stream's query heads within 2e-3 relative L2.  Pattern tables are the first P vectors of each set's first
+stream (a slice of the inputs, the same for both sides), so nothing the oracle reads comes from a kernel.
+"""
+import numpy as np
+import pytest
+
+from paper_2510_05176_amd import synth
+from test_gpu_parity import compare_caches, dev, host_u16, rel_l2   # noqa: F401  (shared helpers)
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def pk():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2510_05176_amd import patternkv
+    return patternkv
+
+
+class StreamView:
+    """The rows of one KV stream inside a GPU cache, presented like a one-stream cache."""
+
+    def __init__(self, gc, ns):
+        self.gc, self.ns, self.N = gc, ns, gc.cfg.n_seq * gc.cfg.n_kv_heads
+
+    def array(self, name):
+        raw = self.gc.array(name)
+        per = raw.numel() // self.N
+        return raw[self.ns * per:(self.ns + 1) * per]
+
+
+def check_stream(oracle, pk, gc, gcfg, kw, K, V, Mk, Mv, q, out, seq, head, appends, max_near_ties):
+    """Oracle run of stream (seq, head) against the GPU's rows; q, out: the GPU's whole-batch query / output."""
+    r = kw["n_q_heads"] // kw["n_kv_heads"]
+    okw = dict(kw, n_seq=1, n_kv_heads=1, n_q_heads=r, seqs_per_set=0)
+    ocfg = oracle.Config(**okw)
+    ns = seq * kw["n_kv_heads"] + head
+    set_id = (0 if kw["seqs_per_set"] == 0 else seq // kw["seqs_per_set"]) * kw["n_kv_heads"] + head
+    Ks, Vs = host_u16(K[seq, head]), host_u16(V[seq, head])
+    Mks, Mvs = host_u16(Mk[set_id])[None], host_u16(Mv[set_id])[None]
+    oc = oracle.Cache(ocfg)
+    t = 0
+    for n_new in appends:
+        oc.append(Ks[None, None, t:t + n_new], Vs[None, None, t:t + n_new], Mks, Mvs)
+        t += n_new
+    assert (oc.t_quant, oc.t_tail) == (gc.t_quant, gc.t_tail)
+    n_diff = compare_caches(oracle, oc, StreamView(gc, ns), 0)
+    assert n_diff <= max_near_ties
+    qs = host_u16(q[seq, head * r:(head + 1) * r])[None]
+    want, _ = oracle.decode_attention(oc, qs, Mks, Mvs, 128 ** -0.5)
+    got = out[seq, head * r:(head + 1) * r].cpu().numpy()[None]
+    assert rel_l2(got, want) <= 2e-3
+    return n_diff
+
+
+def first_vectors(X, P, B):
+    """[n_seq, H, T, d] -> [n_sets, P, d]: the first P vectors of the first batch element of every layer."""
+    n_seq, H, T, d = X.shape
+    return X[::B, :, :P].reshape(-1, P, d).contiguous()
+
+
+def test_config3_long_context_batched_decode(oracle, pk):
+    """Config 3 whole: 32 layers x batch 16 x T=32768, 8 KV / 32 query heads, P=128, 2 bits, group 64, 128 recent."""
+    spec = synth.SPECS["cfg3"]
+    L, B, Hkv, Hq, T, d, P = spec.n_layers, spec.batch, spec.n_kv_heads, spec.n_q_heads, spec.T, spec.d, 128
+    kw = dict(n_seq=L * B, n_kv_heads=Hkv, n_q_heads=Hq, head_dim=d, n_patterns=P, seqs_per_set=B, bits=2, group=64,
+              recent=128, flush=128, t_capacity=(T - 128) // 128 * 128, metric=0)
+    gcfg = pk.Config(**kw)
+    K = torch.empty((L * B, Hkv, T, d), dtype=torch.float16, device="cuda")
+    V = torch.empty_like(K)
+    one = synth.KVSpec(**{**spec.__dict__, "n_layers": 1})
+    for layer in range(L):
+        K[layer * B:(layer + 1) * B], V[layer * B:(layer + 1) * B] = synth.make_layer_device(3, layer, one, "cuda")
+    Mk, Mv = first_vectors(K, P, B), first_vectors(V, P, B)
+    q = dev(synth.make_queries(3, L * B, Hq, d))
+    gc = pk.Cache(gcfg)
+    pk.pk_quantize_append(gcfg, gc, K, V, Mk, Mv)
+    out = pk.pk_decode_attention(gcfg, gc, q, d ** -0.5, Mk, Mv)
+    torch.cuda.synchronize()
+    assert gc.t_quant == T - 128 and gc.t_tail == 128
+    for seq, head in [(0, 0), (301, 5), (L * B - 1, Hkv - 1)]:
+        check_stream(oracle, pk, gc, gcfg, kw, K, V, Mk, Mv, q, out, seq, head, [T], max_near_ties=40)
+
+
+def test_config5_large_pattern_stress(oracle, pk):
+    """Config 5 whole: T=131072, 4 KV / 28 query heads, P=256, 2 bits, group 128."""
+    spec = synth.SPECS["cfg5"]
+    Hkv, Hq, T, d, P = spec.n_kv_heads, spec.n_q_heads, spec.T, spec.d, 256
+    kw = dict(n_seq=1, n_kv_heads=Hkv, n_q_heads=Hq, head_dim=d, n_patterns=P, seqs_per_set=0, bits=2, group=128,
+              recent=0, flush=128, t_capacity=T, metric=0)
+    gcfg = pk.Config(**kw)
+    K, V = synth.make_layer_device(5, 0, spec, "cuda")
+    Mk, Mv = first_vectors(K, P, 1), first_vectors(V, P, 1)
+    q = dev(synth.make_queries(5, 1, Hq, d))
+    gc = pk.Cache(gcfg)
+    pk.pk_quantize_append(gcfg, gc, K, V, Mk, Mv)
+    out = pk.pk_decode_attention(gcfg, gc, q, d ** -0.5, Mk, Mv)
+    torch.cuda.synchronize()
+    check_stream(oracle, pk, gc, gcfg, kw, K, V, Mk, Mv, q, out, 0, 2, [T], max_near_ties=80)
+
+
+def test_config4_streaming_appends_over_shared_prompt(oracle, pk):
+    """Config 4 at full breadth: 64 samples over one 4096-token prompt cache, P=64, 2 bits, group 32; generated
+    tokens arrive one at a time and are flushed in 128-token chunks; decode runs over prompt + own cache."""
+    spec = synth.SPECS["cfg4"]
+    S, Hkv, Hq, d, P, Tp, Tg = spec.batch, spec.n_kv_heads, spec.n_q_heads, spec.d, 64, 4096, 300
+    pkw = dict(n_seq=1, n_kv_heads=Hkv, n_q_heads=Hq, head_dim=d, n_patterns=P, seqs_per_set=0, bits=2, group=32,
+               recent=0, flush=128, t_capacity=Tp, metric=0)
+    kw = dict(pkw, n_seq=S, seqs_per_set=S, t_capacity=512)
+    pcfg, gcfg = pk.Config(**pkw), pk.Config(**kw)
+    prompt = synth.KVSpec(**{**spec.__dict__, "batch": 1, "T": Tp})
+    Kp, Vp = synth.make_layer_device(4, 0, prompt, "cuda")
+    Kg, Vg = synth.make_layer_device(4, 1, synth.KVSpec(**{**spec.__dict__, "T": Tg}), "cuda")
+    Mk, Mv = first_vectors(Kp, P, 1), first_vectors(Vp, P, 1)
+    pc, gc = pk.Cache(pcfg), pk.Cache(gcfg)
+    pk.pk_quantize_append(pcfg, pc, Kp, Vp, Mk, Mv)
+    appends = [1] * 130 + [126, 44]                       # crosses a flush with single tokens, then chunks
+    t = 0
+    for n_new in appends:
+        pk.pk_quantize_append(gcfg, gc, Kg[:, :, t:t + n_new], Vg[:, :, t:t + n_new], Mk, Mv)
+        t += n_new
+    q = dev(synth.make_queries(4, S, Hq, d))
+    out = pk.pk_decode_attention(gcfg, gc, q, d ** -0.5, Mk, Mv, prefix=pc)
+    torch.cuda.synchronize()
+    assert gc.t_quant == 256 and gc.t_tail == 44
+    # oracle: the prompt cache of one head plus the sample's own cache
+    r = Hq // Hkv
+    for seq, head in [(0, 1), (37, 6), (S - 1, 0)]:
+        okw = dict(pkw, n_kv_heads=1, n_q_heads=r)
+        opc = oracle.Cache(oracle.Config(**okw))
+        Mks, Mvs = host_u16(Mk[head])[None], host_u16(Mv[head])[None]
+        opc.append(host_u16(Kp[0, head])[None, None], host_u16(Vp[0, head])[None, None], Mks, Mvs)
+        compare_caches(oracle, opc, StreamView(pc, head), 0)
+        ooc = oracle.Cache(oracle.Config(**dict(okw, t_capacity=512)))
+        t = 0
+        for n_new in appends:
+            ooc.append(host_u16(Kg[seq, head, t:t + n_new])[None, None], host_u16(Vg[seq, head, t:t + n_new])[None, None], Mks, Mvs)
+            t += n_new
+        compare_caches(oracle, ooc, StreamView(gc, seq * Hkv + head), 0)
+        qs = host_u16(q[seq, head * r:(head + 1) * r])[None]
+        want, _ = oracle.decode_attention(ooc, qs, Mks, Mvs, d ** -0.5, prefix=opc, prefix_patterns_k=Mks,
+                                          prefix_patterns_v=Mvs)
+        got = out[seq, head * r:(head + 1) * r].cpu().numpy()[None]
+        assert rel_l2(got, want) <= 2e-3

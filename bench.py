@@ -13,8 +13,9 @@ has all three.  Per-stage durations come from HIP events recorded on the launch 
 library call, with a cache flush (a 1 GiB fill, outside the events) before every timed call so that
 inputs come from HBM and not from the 256 MB Infinity Cache.
 
-Workloads (--workload): cfg2 (default; Llama-3-8B-shaped single layer, T=8192), cfg2x32 (the same for
-32 layers in one launch), cfg3 (32 layers x batch 16 x T=32768), cfg5 (T=131072, P=256).
+Workloads (--workload): cfg2x32 (default: the contract's config 2 - Llama-3-8B-shaped layer, batch 1, T=8192,
+8 KV / 32 query heads, P=64, group 64 - for the model's 32 layers in one launch, 256 KV streams), cfg2 (one
+layer of it: 8 streams, launch-bound), cfg3 (32 layers x batch 16 x T=32768, P=128), cfg5 (T=131072, P=256).
 """
 import argparse
 import json
@@ -45,7 +46,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="cfg2", choices=sorted(WORKLOADS))
+    ap.add_argument("--workload", default="cfg2x32", choices=sorted(WORKLOADS))
     ap.add_argument("--bits", type=int, default=2, choices=[2, 4])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=2)

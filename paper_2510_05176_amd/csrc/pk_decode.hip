@@ -230,9 +230,10 @@ __global__ __launch_bounds__(128) void decode_merge_kernel(DecodeArgs a)
 
 int decode_chunk(int64_t n_streams, int64_t t_packed_total, int P, int r)
 {
-    // aim at ~2048 workgroups; one 64-token block per wave at least, 8192 tokens per split at most.  Every
-    // split also writes r*P pattern masses and r*128 outputs, so a split should hold a few times r*P tokens.
-    int64_t c = (n_streams * t_packed_total + 2047) / 2048;
+    // aim at ~1024 workgroups (two are resident per CU); one 64-token block per wave at least, 8192 tokens per
+    // split at most.  Every split also writes r*P pattern masses and r*128 outputs and pays a fixed prologue
+    // (q.M_K table, LDS clears) and epilogue (merge of the four waves), so it should hold at least r*P tokens.
+    int64_t c = (n_streams * t_packed_total + 1023) / 1024;
     const int64_t floor_c = (int64_t)r * P;
     if (c < floor_c) c = floor_c;
     c = (c + 255) / 256 * 256;

@@ -332,8 +332,18 @@ void pko_quantize_k(const uint16_t *x, int n, int d, const uint16_t *M, const in
  */
 static int64_t v_param(int64_t t, int j, int ng) { return ((t / 16) * ng + j) * 16 + t % 16; }
 
-void pko_quantize_v(const uint16_t *x, int n, int d, const uint16_t *M, const int32_t *idx,
-                    int bits, int Gc, uint8_t *codes, uint16_t *scale, uint16_t *zero)
+/*
+ * V side with the adaptive threshold of Sec. 3.3 ("Adaptive Threshold for V"): a token keeps its
+ * pattern only if the range of the residual is at most rho times the range of the raw vector,
+ *     R_flat = max_c r_c - min_c r_c ,  R_raw = max_c x_c - min_c x_c ,  R_flat <= rho * R_raw
+ * (one binary32 multiply, ranges over all d channels of the token); otherwise the raw vector is
+ * quantized and the index becomes PKO_NO_PATTERN.  rho = rho_*(d, alpha) of Sec. 3.3 is the caller's;
+ * rho <= 0 switches the test off.
+ */
+#define PKO_NO_PATTERN 255
+
+void pko_quantize_v(const uint16_t *x, int n, int d, const uint16_t *M, int32_t *idx,
+                    int bits, int Gc, float rho, uint8_t *codes, uint16_t *scale, uint16_t *zero)
 {
     int ng = d / Gc;
     float *r = (float *)malloc(sizeof(float) * d);
@@ -341,6 +351,23 @@ void pko_quantize_v(const uint16_t *x, int n, int d, const uint16_t *M, const in
         const uint16_t *m = M + (int64_t)idx[t] * d;
         for (int c = 0; c < d; ++c)
             r[c] = pko_half_to_float(x[(int64_t)t * d + c]) - pko_half_to_float(m[c]);
+        if (rho > 0.0f) {
+            float rmn = r[0], rmx = r[0];
+            float xmn = pko_half_to_float(x[(int64_t)t * d]), xmx = xmn;
+            for (int c = 1; c < d; ++c) {
+                float xv = pko_half_to_float(x[(int64_t)t * d + c]);
+                if (r[c] < rmn) rmn = r[c];
+                if (r[c] > rmx) rmx = r[c];
+                if (xv < xmn) xmn = xv;
+                if (xv > xmx) xmx = xv;
+            }
+            float r_flat = rmx - rmn, r_raw = xmx - xmn;
+            if (!(r_flat <= rho * r_raw)) {
+                for (int c = 0; c < d; ++c)
+                    r[c] = pko_half_to_float(x[(int64_t)t * d + c]);
+                idx[t] = PKO_NO_PATTERN;
+            }
+        }
         for (int j = 0; j < ng; ++j) {
             float mn = r[j * Gc], mx = r[j * Gc];
             for (int c = j * Gc + 1; c < (j + 1) * Gc; ++c) {
@@ -444,8 +471,9 @@ void pko_dequant_k(const uint8_t *codes, const uint16_t *scale, const uint16_t *
         }
 }
 
+/* thresholded != 0: tokens whose index is PKO_NO_PATTERN were quantized raw (Sec. 3.3), no pattern is added */
 void pko_dequant_v(const uint8_t *codes, const uint16_t *scale, const uint16_t *zero,
-                   const int32_t *idx, const uint16_t *M, int n, int d, int Gc, float *out)
+                   const int32_t *idx, const uint16_t *M, int n, int d, int Gc, int thresholded, float *out)
 {
     int ng = d / Gc;
     for (int t = 0; t < n; ++t)
@@ -453,7 +481,10 @@ void pko_dequant_v(const uint8_t *codes, const uint16_t *scale, const uint16_t *
             float s = pko_half_to_float(scale[v_param(t, c / Gc, ng)]);
             float z = pko_half_to_float(zero[v_param(t, c / Gc, ng)]);
             float res = s * (float)codes[(int64_t)t * d + c] + z;
-            out[(int64_t)t * d + c] = pko_half_to_float(M[(int64_t)idx[t] * d + c]) + res;
+            if (thresholded && idx[t] == PKO_NO_PATTERN)
+                out[(int64_t)t * d + c] = res;
+            else
+                out[(int64_t)t * d + c] = pko_half_to_float(M[(int64_t)idx[t] * d + c]) + res;
         }
 }
 
@@ -532,7 +563,7 @@ void pko_mine_sets(const uint16_t *x, int S, int64_t T, int d, int P, int iters,
  * scale/zero[N][(n/G)*d] (K) or [N][(n/16)*(d/Gc)*16] (V).
  */
 void pko_quantize_streams(const uint16_t *x, int N, int n, int d, const int32_t *set_of,
-                          const uint16_t *M, int P, int metric, int bits, int G, int side,
+                          const uint16_t *M, int P, int metric, int bits, int G, int side, float v_rho,
                           int32_t *idx, double *best, double *second, uint8_t *codes_unpacked,
                           uint8_t *packed, uint16_t *scale, uint16_t *zero)
 {
@@ -551,7 +582,7 @@ void pko_quantize_streams(const uint16_t *x, int N, int n, int d, const int32_t 
             pko_quantize_k(xs, n, d, Ms, ix, bits, G, codes, scale + s * nparam, zero + s * nparam);
             pko_pack_k(codes, n, d, bits, (uint32_t *)(packed + s * npacked));
         } else {
-            pko_quantize_v(xs, n, d, Ms, ix, bits, Gc, codes, scale + s * nparam, zero + s * nparam);
+            pko_quantize_v(xs, n, d, Ms, ix, bits, Gc, v_rho, codes, scale + s * nparam, zero + s * nparam);
             pko_pack_v(codes, n, d, bits, (uint32_t *)(packed + s * npacked));
         }
         if (codes_unpacked)

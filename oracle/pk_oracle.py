@@ -109,8 +109,10 @@ def mine(x_u16: np.ndarray, P: int, iters: int, init: np.ndarray | None = None):
     return M, a, J[:, :iters], cnt
 
 
-def quantize_streams(x_u16, set_of, M_u16, metric, bits, G, side, want_codes=False):
-    """x[N,n,d]; M[sets,P,d].  side 0 = K, 1 = V.  Returns dict of arrays."""
+def quantize_streams(x_u16, set_of, M_u16, metric, bits, G, side, want_codes=False, v_rho=0.0):
+    """x[N,n,d]; M[sets,P,d].  side 0 = K, 1 = V.  Returns dict of arrays.
+
+    v_rho > 0 (V side only): the adaptive threshold of Sec. 3.3; rejected tokens get index NO_PATTERN."""
     x_u16 = np.ascontiguousarray(x_u16, dtype=np.uint16)
     M_u16 = np.ascontiguousarray(M_u16, dtype=np.uint16)
     set_of = np.ascontiguousarray(set_of, dtype=np.int32)
@@ -128,8 +130,9 @@ def quantize_streams(x_u16, set_of, M_u16, metric, bits, G, side, want_codes=Fal
     else:
         scale = np.empty((N, n // 16, d // Gc, 16), np.uint16)
     zero = np.empty_like(scale)
+    assert v_rho <= 0 or P <= NO_PATTERN
     lib().pko_quantize_streams(_p(x_u16), N, n, d, _p(set_of), _p(M_u16), P, metric, bits, G, side,
-                               _p(idx), _p(best), _p(second), _p(codes), _p(packed), _p(scale), _p(zero))
+                               C.c_float(v_rho if side == 1 else 0.0), _p(idx), _p(best), _p(second), _p(codes), _p(packed), _p(scale), _p(zero))
     return dict(idx=idx, best=best, second=second, codes=codes, packed=packed, scale=scale, zero=zero)
 
 
@@ -165,14 +168,32 @@ def unpack_v(words_u32, n, d, bits):
     return out
 
 
-def dequant(side, codes_u8, scale, zero, idx_i32, M_u16, G):
+def dequant(side, codes_u8, scale, zero, idx_i32, M_u16, G, thresholded=False):
+    """thresholded (V side): tokens with index NO_PATTERN were quantized raw and get no pattern added."""
     n, d = codes_u8.shape
     out = np.empty((n, d), np.float32)
-    fn = lib().pko_dequant_k if side == 0 else lib().pko_dequant_v
-    Gx = G if side == 0 else min(G, d)
-    fn(_p(np.ascontiguousarray(codes_u8)), _p(np.ascontiguousarray(scale)), _p(np.ascontiguousarray(zero)),
-       _p(np.ascontiguousarray(idx_i32, dtype=np.int32)), _p(np.ascontiguousarray(M_u16)), n, d, Gx, _p(out))
+    args = (_p(np.ascontiguousarray(codes_u8)), _p(np.ascontiguousarray(scale)), _p(np.ascontiguousarray(zero)),
+            _p(np.ascontiguousarray(idx_i32, dtype=np.int32)), _p(np.ascontiguousarray(M_u16)), n, d)
+    if side == 0:
+        lib().pko_dequant_k(*args, G, _p(out))
+    else:
+        lib().pko_dequant_v(*args, min(G, d), 1 if thresholded else 0, _p(out))
     return out
+
+
+NO_PATTERN = 255   # V index of a token the adaptive threshold sent to raw quantization
+
+
+def rho_star(d: int, alpha: float) -> float:
+    """Largest contraction ratio R_flat / R_raw at which flattening is kept (Sec. 3.3): the root in (0, 1) of
+    1 - rho^2 = c sqrt(1 + rho^4), c = 2 z_{1-alpha} / sqrt(5 d).  With u = rho^2 the equality squares to
+    (1 - c^2) u^2 - 2u + (1 - c^2) = 0, whose smaller root is the one with 1 - u >= 0."""
+    from statistics import NormalDist
+    c = 2.0 * NormalDist().inv_cdf(1.0 - alpha) / (5.0 * d) ** 0.5
+    a = 1.0 - c * c
+    assert a > 0, "the test rejects every ratio at this (d, alpha)"
+    u = (1.0 - (1.0 - a * a) ** 0.5) / a
+    return u ** 0.5
 
 
 def attend(q_u16, Khat, Vhat, softmax_scale):
@@ -207,6 +228,7 @@ class Config:
     flush: int
     t_capacity: int
     metric: int
+    v_rho: float = 0.0     # > 0: adaptive threshold on V (Sec. 3.3), keep the pattern iff R_flat <= v_rho * R_raw
 
     @property
     def n_streams(self):
@@ -274,7 +296,7 @@ class Cache:
             set_of = cfg.set_of()
             t0, t1 = self.t_quant, self.t_quant + nq
             rk = quantize_streams(zk[:, :nq], set_of, patterns_k, cfg.metric, b, G, 0)
-            rv = quantize_streams(zv[:, :nq], set_of, patterns_v, cfg.metric, b, G, 1)
+            rv = quantize_streams(zv[:, :nq], set_of, patterns_v, cfg.metric, b, G, 1, v_rho=cfg.v_rho)
             self.k_codes[:, t0:t1] = rk["packed"].view(np.uint32).reshape(N, nq, d // 32, b)
             self.k_scale[:, t0 // G:t1 // G] = rk["scale"]
             self.k_zero[:, t0 // G:t1 // G] = rk["zero"]
@@ -312,7 +334,8 @@ class Cache:
                 kfull = dequant(0, ck, self.k_scale[s, :self.t_quant // G], self.k_zero[s, :self.t_quant // G],
                                 self.k_idx[s, :self.t_quant].astype(np.int32), patterns_k[set_of[s]], G)
                 vfull = dequant(1, cv, self.v_scale[s, :self.t_quant // 16], self.v_zero[s, :self.t_quant // 16],
-                                self.v_idx[s, :self.t_quant].astype(np.int32), patterns_v[set_of[s]], G)
+                                self.v_idx[s, :self.t_quant].astype(np.int32), patterns_v[set_of[s]], G,
+                                thresholded=cfg.v_rho > 0)
                 K[s], V[s] = kfull[t0:t1], vfull[t0:t1]
         return K, V
 

@@ -284,6 +284,85 @@ def test_quantize_invariants(oracle, side, bits, metric):
         assert np.all(np.abs(out - x[s].astype(np.float32)) <= sc_e * 0.5 * (1 + 1e-5) + 1e-6)
 
 
+# ------------------------------------------------------------------ adaptive threshold on V (Sec. 3.3)
+
+def test_rho_star_solves_the_criterion(oracle):
+    from scipy.stats import norm
+    for d, alpha in [(96, 0.05), (128, 0.05), (128, 0.01), (256, 0.1), (128, 0.3)]:
+        rho = oracle.rho_star(d, alpha)
+        c = 2.0 * norm.ppf(1.0 - alpha) / np.sqrt(5.0 * d)
+        f = lambda r: (1.0 - r * r) - c * np.sqrt(1.0 + r ** 4)     # Sec. 3.3: keep iff f(rho) >= 0
+        assert 0.0 < rho < 1.0 and abs(f(rho)) < 1e-12
+        assert f(rho - 1e-6) > 0 > f(rho + 1e-6)                    # f decreases through its only root in (0, 1)
+        grid = np.linspace(0.0, 1.0, 2001)
+        assert np.all((f(grid) >= 0) == (grid <= rho))
+    # a stricter test (smaller alpha) or a shorter vector keeps fewer ratios
+    assert oracle.rho_star(128, 0.01) < oracle.rho_star(128, 0.05) < oracle.rho_star(256, 0.05)
+    assert abs(oracle.rho_star(128, 0.05) - 0.9116) < 1e-4
+
+
+@pytest.mark.parametrize("bits,G,metric", [(2, 64, 0), (4, 32, 0), (2, 128, 1)])
+def test_v_threshold_decision_and_raw_fallback(oracle, bits, G, metric):
+    spec = synth.KVSpec(1, 1, 2, 2, 256, 128, 8)
+    _, V = synth.make_kv(21, spec)
+    x = V[0].copy()
+    x[0, 20] = np.float16(1.25)                     # a constant vector: R_raw = 0, rejected unless the residual is flat too
+    x[1, 30] = x[1, 3]                              # a vector equal to a pattern: R_flat = 0, always kept
+    M = x[:, :7].copy()
+    set_of = np.arange(2, dtype=np.int32)
+    rho = 0.8
+    base = oracle.quantize_streams(x.view(np.uint16), set_of, M.view(np.uint16), metric, bits, G, 1, want_codes=True)
+    thr = oracle.quantize_streams(x.view(np.uint16), set_of, M.view(np.uint16), metric, bits, G, 1, want_codes=True, v_rho=rho)
+    zeroM = np.zeros_like(M)
+    rawq = oracle.quantize_streams(x.view(np.uint16), set_of, zeroM.view(np.uint16), metric, bits, G, 1, want_codes=True)
+    n_raw = 0
+    for s in range(2):
+        xf = x[s].astype(np.float32)
+        resid = xf - M[s][base["idx"][s]].astype(np.float32)
+        r_flat = resid.max(1) - resid.min(1)
+        r_raw = xf.max(1) - xf.min(1)
+        raw = ~(r_flat <= np.float32(rho) * r_raw)
+        assert np.array_equal(thr["idx"][s] == oracle.NO_PATTERN, raw)
+        assert np.array_equal(thr["idx"][s][~raw], base["idx"][s][~raw])
+        # kept tokens: exactly the unthresholded result; rejected tokens: exactly the quantization of the vector itself
+        pt = oracle.v_params_by_token
+        for name in ("codes",):
+            assert np.array_equal(thr[name][s][~raw], base[name][s][~raw])
+            assert np.array_equal(thr[name][s][raw], rawq[name][s][raw])
+        for name in ("scale", "zero"):
+            assert np.array_equal(pt(thr[name][s])[~raw], pt(base[name][s])[~raw])
+            assert np.array_equal(pt(thr[name][s])[raw], pt(rawq[name][s])[raw])
+        # reconstruction never adds a pattern to a rejected token, and stays within half a step everywhere
+        out = oracle.dequant(1, thr["codes"][s], thr["scale"][s], thr["zero"][s], thr["idx"][s], M[s].view(np.uint16), G,
+                             thresholded=True)
+        Gc = min(G, 128)
+        sc = np.repeat(pt(thr["scale"][s]).view(np.float16).astype(np.float32), Gc, axis=1)
+        assert np.all(np.abs(out - xf) <= sc * 0.5 * (1 + 1e-5) + 1e-6)
+        n_raw += int(raw.sum())
+    assert thr["idx"][0][20] == oracle.NO_PATTERN and np.all(thr["codes"][0][20] == 0)   # constant vector: raw, flat group
+    assert thr["idx"][1][30] == 3                                                       # pattern itself: kept
+    assert 0 < n_raw < 2 * 256
+    # rho = 0 switches the test off; a looser rho keeps at least as many tokens
+    off = oracle.quantize_streams(x.view(np.uint16), set_of, M.view(np.uint16), metric, bits, G, 1, want_codes=True, v_rho=0.0)
+    assert all(np.array_equal(off[k], base[k]) for k in ("idx", "codes", "scale", "zero", "packed"))
+    loose = oracle.quantize_streams(x.view(np.uint16), set_of, M.view(np.uint16), metric, bits, G, 1, v_rho=0.95)
+    assert (loose["idx"] == oracle.NO_PATTERN).sum() <= n_raw
+
+
+def test_v_threshold_minmax_range_is_dmm(oracle):
+    # with the min-max metric the flat range of the chosen pattern is d_mm itself (Sec. 3.2), so a token is
+    # rejected exactly when min_p d_mm(x, M_p) > rho * (max x - min x)
+    rng = np.random.default_rng(31)
+    x = f16(rng.standard_normal((1, 64, 128)))
+    M = f16(rng.standard_normal((1, 6, 128)) * 0.5)
+    rho = 0.9
+    res = oracle.quantize_streams(x.view(np.uint16), np.zeros(1, np.int32), M.view(np.uint16), 1, 2, 64, 1, v_rho=rho)
+    diff = x[0].astype(np.float32)[:, None, :] - M[0].astype(np.float32)[None]
+    dmm = (diff.max(2) - diff.min(2)).min(1)
+    xr = x[0].astype(np.float32)
+    assert np.array_equal(res["idx"][0] == oracle.NO_PATTERN, ~(dmm <= np.float32(rho) * (xr.max(1) - xr.min(1))))
+
+
 def test_zero_residual_reconstructs_exactly(oracle):
     rng = np.random.default_rng(12)
     M = f16(rng.standard_normal((1, 5, 128)))

@@ -75,7 +75,7 @@
 extern "C" {
 #endif
 
-#define PK_ABI_VERSION 1u
+#define PK_ABI_VERSION 2u
 
 typedef enum {
     PK_OK = 0,
@@ -110,7 +110,16 @@ typedef struct {
     int32_t flush;        /* F: multiple of G and of 64; vectors quantized per flush          */
     int32_t t_capacity;   /* maximum packed tokens per stream, multiple of F                  */
     int32_t metric;       /* pk_metric                                                        */
+    float v_rho;          /* adaptive threshold on V (Sec. 3.3, "Adaptive Threshold for V"): 0 = off.  With
+                             0 < v_rho < 1 a V vector keeps its pattern only if
+                             R_flat <= v_rho * R_raw, R = max - min over its d channels of the residual
+                             (flat) and of the vector itself (raw), one binary32 multiply; otherwise the
+                             vector itself is quantized and its index is PK_NO_PATTERN.  The caller passes
+                             rho_*(d, alpha), the root in (0,1) of 1 - rho^2 = 2 z_{1-alpha}/sqrt(5d) *
+                             sqrt(1 + rho^4).  Needs n_patterns <= 255.  K is never thresholded.        */
 } pk_config;
+
+#define PK_NO_PATTERN 255 /* v_idx of a token quantized without a pattern (only when v_rho > 0)    */
 
 /* Byte sizes of the cache arrays for a configuration (for the caller to allocate). */
 typedef struct {

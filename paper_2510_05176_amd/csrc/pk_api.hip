@@ -21,6 +21,8 @@ pk_status check_config(const pk_config *c)
     if (c->metric != PK_METRIC_L2 && c->metric != PK_METRIC_MINMAX) return PK_ERR_INVALID_ARG;
     if (c->head_dim != kD) return PK_ERR_UNSUPPORTED;
     if (c->n_patterns > 256) return PK_ERR_UNSUPPORTED;
+    if (!(c->v_rho >= 0.f) || !(c->v_rho < 1.f)) return PK_ERR_INVALID_ARG;   // also rejects NaN
+    if (c->v_rho > 0.f && c->n_patterns > PK_NO_PATTERN) return PK_ERR_UNSUPPORTED;
     if (c->bits != 2 && c->bits != 4) return PK_ERR_UNSUPPORTED;
     if (c->group != 32 && c->group != 64 && c->group != 128) return PK_ERR_UNSUPPORTED;
     if (c->n_q_heads % c->n_kv_heads != 0) return PK_ERR_SHAPE;
@@ -231,6 +233,7 @@ pk_status pk_quantize_append(const pk_config *cfg, const pk_cache *cache, pk_sta
         a.sets.seqs_per_set = cfg->seqs_per_set;
         a.P = cfg->n_patterns;
         a.metric = cfg->metric;
+        a.v_rho = 0.f;
         a.bits = cfg->bits;
         a.G = cfg->group;
         a.n_streams = N;
@@ -256,6 +259,7 @@ pk_status pk_quantize_append(const pk_config *cfg, const pk_cache *cache, pk_sta
         a.scale = static_cast<__half *>(cache->v_scale);
         a.zero = static_cast<__half *>(cache->v_zero);
         a.idx = static_cast<uint8_t *>(cache->v_idx);
+        a.v_rho = cfg->v_rho;
         if (launch_quantize_v(a, hs) != hipSuccess) return PK_ERR_DEVICE;
     }
     // what is left stays in (old tail vectors) or moves into (fresh vectors) the ring;
@@ -366,6 +370,7 @@ pk_status pk_dequantize(const pk_config *cfg, const pk_cache *cache, const pk_st
     a.P = cfg->n_patterns;
     a.bits = cfg->bits;
     a.G = cfg->group;
+    a.v_thresholded = cfg->v_rho > 0.f ? 1 : 0;
     a.t0 = t0;
     a.t1 = t1;
     a.k_out = k_out;

@@ -36,7 +36,11 @@ __global__ __launch_bounds__(128) void dequant_kernel(DequantArgs a)
         const int64_t prow = ((int64_t)n * a.c.t_capacity * ng) + ((int64_t)(t >> 4) * ng + c / Gc) * 16 + (t & 15);
         const float s = h2f(a.c.v_scale[prow]), z = h2f(a.c.v_zero[prow]);
         const float res = s * (float)code + z;
-        a.v_out[orow] = h2f(a.patterns_v[((int64_t)set * a.P + a.c.v_idx[tok]) * kD + c]) + res;
+        const int vi = a.c.v_idx[tok];
+        if (a.v_thresholded && vi == PK_NO_PATTERN)
+            a.v_out[orow] = res;   // quantized without a pattern (adaptive threshold, Sec. 3.3)
+        else
+            a.v_out[orow] = h2f(a.patterns_v[((int64_t)set * a.P + vi) * kD + c]) + res;
     }
 }
 

@@ -80,6 +80,7 @@ struct QuantArgs {
     SetMap sets;
     const __half *patterns;   // [n_sets][P][kD]
     int32_t P, metric, bits, G;
+    float v_rho;              // V side: adaptive threshold (0 = off)
     int32_t n_streams;
     int32_t nq;               // vectors to quantize per stream (multiple of G)
     int32_t t0;               // first packed position to write (= t_quant)
@@ -152,6 +153,7 @@ struct DequantArgs {
     SetMap sets;
     const __half *patterns_k, *patterns_v;
     int32_t n_streams, P, bits, G, t0, t1;
+    int32_t v_thresholded;    // v_idx == PK_NO_PATTERN marks a token quantized without a pattern
     float *k_out, *v_out;
 };
 hipError_t launch_dequant(const DequantArgs &a, hipStream_t s);

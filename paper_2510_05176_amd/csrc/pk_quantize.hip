@@ -107,7 +107,7 @@ __global__ __launch_bounds__(128) void quantize_v_valu_kernel(QuantArgs a)
     __shared__ __align__(16) __half xs[TV * kXsStride];
     __shared__ AssignScratch sc;
     __shared__ int idx_s[TV];
-    __shared__ float red_mn[TV][4], red_mx[TV][4];
+    __shared__ float red_mn[TV][4], red_mx[TV][4], raw_mn[TV][4], raw_mx[TV][4];
     __shared__ __align__(16) uint32_t out_s[TV * kD * BITS / 32];
     __shared__ __align__(16) unsigned short par_s[2][4 * 4 * 16];   // scale / zero slices: [unit][group][16]
 
@@ -118,22 +118,44 @@ __global__ __launch_bounds__(128) void quantize_v_valu_kernel(QuantArgs a)
     assign_tile<TV>(xs, TV, Mg, a.P, a.metric, sc, idx_s, nullptr);
 
     const int64_t tq = (int64_t)a.t0 + (int64_t)tile * TV;
-    if (tid < TV) a.idx[(int64_t)n * a.t_capacity + tq + tid] = (uint8_t)idx_s[tid];
+    const bool thr = a.v_rho > 0.f;
 
     const int c = tid, lane = tid & 63, quarter = tid >> 5;
-    // phase A: min / max of every 32-channel quarter of every token
+    // phase A: min / max of every 32-channel quarter of every token, of the residual and (for the adaptive
+    // threshold) of the vector itself
     for (int t = 0; t < TV; ++t) {
-        const float r = h2f(xs[t * kXsStride + c]) - h2f(Mg[(int64_t)idx_s[t] * kD + c]);
-        float mn = r, mx = r;
+        const float xv = h2f(xs[t * kXsStride + c]);
+        const float r = xv - h2f(Mg[(int64_t)idx_s[t] * kD + c]);
+        float mn = r, mx = r, xn = xv, xx = xv;
 #pragma unroll
         for (int off = 1; off < 32; off <<= 1) {
             mn = fminf(mn, __shfl_xor(mn, off));
             mx = fmaxf(mx, __shfl_xor(mx, off));
+            if (thr) {
+                xn = fminf(xn, __shfl_xor(xn, off));
+                xx = fmaxf(xx, __shfl_xor(xx, off));
+            }
         }
         if ((lane & 31) == 0) {
             red_mn[t][quarter] = mn;
             red_mx[t][quarter] = mx;
+            raw_mn[t][quarter] = xn;
+            raw_mx[t][quarter] = xx;
         }
+    }
+    __syncthreads();
+    // adaptive threshold (Sec. 3.3): keep the pattern iff R_flat <= rho * R_raw over the whole vector
+    if (tid < TV) {
+        int id = idx_s[tid];
+        if (thr) {
+            const float rf = fmaxf(fmaxf(red_mx[tid][0], red_mx[tid][1]), fmaxf(red_mx[tid][2], red_mx[tid][3])) -
+                             fminf(fminf(red_mn[tid][0], red_mn[tid][1]), fminf(red_mn[tid][2], red_mn[tid][3]));
+            const float rr = fmaxf(fmaxf(raw_mx[tid][0], raw_mx[tid][1]), fmaxf(raw_mx[tid][2], raw_mx[tid][3])) -
+                             fminf(fminf(raw_mn[tid][0], raw_mn[tid][1]), fminf(raw_mn[tid][2], raw_mn[tid][3]));
+            if (!(rf <= a.v_rho * rr)) id = PK_NO_PATTERN;
+        }
+        idx_s[tid] = id;
+        a.idx[(int64_t)n * a.t_capacity + tq + tid] = (uint8_t)id;
     }
     __syncthreads();
     // phase B: stored parameters, codes, bit planes along the tokens (16 tokens per word)
@@ -144,17 +166,20 @@ __global__ __launch_bounds__(128) void quantize_v_valu_kernel(QuantArgs a)
 #pragma unroll
     for (int j = 0; j < BITS; ++j) acc[j] = 0;
     for (int t = 0; t < TV; ++t) {
-        float mn = red_mn[t][grp * qpg], mx = red_mx[t][grp * qpg];
+        const bool raw = thr && idx_s[t] == PK_NO_PATTERN;   // quantized without a pattern
+        const float(*smn)[4] = raw ? raw_mn : red_mn;
+        const float(*smx)[4] = raw ? raw_mx : red_mx;
+        float mn = smn[t][grp * qpg], mx = smx[t][grp * qpg];
         for (int k = 1; k < qpg; ++k) {
-            mn = fminf(mn, red_mn[t][grp * qpg + k]);
-            mx = fmaxf(mx, red_mx[t][grp * qpg + k]);
+            mn = fminf(mn, smn[t][grp * qpg + k]);
+            mx = fmaxf(mx, smx[t][grp * qpg + k]);
         }
         const GroupParams gp = group_params(mn, mx, BITS);
         if (c % Gc == 0) {
             par_s[0][((t >> 4) * ng + grp) * 16 + (t & 15)] = gp.s16;
             par_s[1][((t >> 4) * ng + grp) * 16 + (t & 15)] = gp.z16;
         }
-        const float r = h2f(xs[t * kXsStride + c]) - h2f(Mg[(int64_t)idx_s[t] * kD + c]);
+        const float r = raw ? h2f(xs[t * kXsStride + c]) : h2f(xs[t * kXsStride + c]) - h2f(Mg[(int64_t)idx_s[t] * kD + c]);
         const int code = quantize_one(r, gp, BITS);
 #pragma unroll
         for (int j = 0; j < BITS; ++j) acc[j] |= (uint32_t)((code >> j) & 1) << (t & 15);
@@ -673,7 +698,49 @@ __global__ __launch_bounds__(256) void quantize_v_kernel(QuantArgs a, int tiles_
     for (int tile = tile0; tile < tile1; ++tile) {
         const int64_t t_first = (int64_t)a.t0 + (int64_t)tile * TT + wave * 16;   // first token of the unit
         float r[32];
-        const int bi = assign_residuals<TAB_LDS>(sh, tb, Mg, xb, reinterpret_cast<__half *>(wsc + kWsRow), r);
+        int bi = assign_residuals<TAB_LDS>(sh, tb, Mg, xb, reinterpret_cast<__half *>(wsc + kWsRow), r);
+        if (a.v_rho > 0.f) {
+            // adaptive threshold (Sec. 3.3): keep the pattern iff R_flat <= rho * R_raw, ranges over all d
+            // channels of the token: lane-local over its 32 channels, then over the token's 4 lanes
+            float rmn = fminf(r[0], r[1]), rmx = fmaxf(r[0], r[1]);
+            half2_t xmn = __builtin_bit_cast(half2_t, xb[0].x), xmx = xmn;
+#pragma unroll
+            for (int e = 2; e < 32; e += 2) {
+                rmn = fminf(fminf(rmn, r[e]), r[e + 1]);
+                rmx = fmaxf(fmaxf(rmx, r[e]), r[e + 1]);
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const uint32_t w[4] = {xb[k].x, xb[k].y, xb[k].z, xb[k].w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    xmn = __builtin_elementwise_min(xmn, __builtin_bit_cast(half2_t, w[i]));
+                    xmx = __builtin_elementwise_max(xmx, __builtin_bit_cast(half2_t, w[i]));
+                }
+            }
+            float x_lo = fminf((float)xmn[0], (float)xmn[1]), x_hi = fmaxf((float)xmx[0], (float)xmx[1]);
+#pragma unroll
+            for (int off = 16; off <= 32; off <<= 1) {
+                rmn = fminf(rmn, __shfl_xor(rmn, off));
+                rmx = fmaxf(rmx, __shfl_xor(rmx, off));
+                x_lo = fminf(x_lo, __shfl_xor(x_lo, off));
+                x_hi = fmaxf(x_hi, __shfl_xor(x_hi, off));
+            }
+            const bool keep = (rmx - rmn) <= a.v_rho * (x_hi - x_lo);
+            if (!keep) {   // quantize the vector itself
+                bi = PK_NO_PATTERN;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const uint32_t w[4] = {xb[k].x, xb[k].y, xb[k].z, xb[k].w};
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const half2_t h = __builtin_bit_cast(half2_t, w[i]);
+                        r[8 * k + 2 * i] = (float)h[0];
+                        r[8 * k + 2 * i + 1] = (float)h[1];
+                    }
+                }
+            }
+        }
         if (tile + 1 < tile1) load_tile(a, ns, (tile + 1) * TT + wave * 16, xb);
 
         // minimum / maximum per channel group: lane-local over its channels, then over the 4 lanes of the token

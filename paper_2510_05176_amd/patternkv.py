@@ -23,13 +23,14 @@ _lib = C.CDLL(_LIB_PATH)
 
 PK_OK = 0
 METRIC_L2, METRIC_MINMAX = 0, 1
+NO_PATTERN = 255   # v_idx of a token the adaptive threshold sent to raw quantization
 OP_MINE, OP_APPEND, OP_DECODE = 0, 1, 2
 
 
 class _Config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "n_seq", "n_kv_heads", "n_q_heads", "head_dim", "n_patterns", "seqs_per_set",
-        "bits", "group", "recent", "flush", "t_capacity", "metric")]
+        "bits", "group", "recent", "flush", "t_capacity", "metric")] + [("v_rho", C.c_float)]
 
 
 class _Layout(C.Structure):
@@ -106,6 +107,7 @@ class Config:
     flush: int = 64
     t_capacity: int = 0
     metric: int = METRIC_L2
+    v_rho: float = 0.0      # adaptive threshold on V (0 = off); see include/patternkv.h
 
     def c(self) -> _Config:
         return _Config(**asdict(self))

@@ -29,7 +29,7 @@ def test_exports_every_declared_symbol(pk):
     lib = C.CDLL(LIB)
     for n in names:
         assert hasattr(lib, n), n
-    assert pk.pk_abi_version() == 1
+    assert pk.pk_abi_version() == 2
 
 
 def test_status_strings(pk):
@@ -60,6 +60,7 @@ def test_layout_byte_counts(pk):
     ("head_dim", 64, 2), ("bits", 3, 2), ("group", 48, 2), ("n_patterns", 257, 2), ("n_patterns", 0, 1),
     ("n_q_heads", 5, 3), ("n_q_heads", 36, 2), ("flush", 96, 3), ("t_capacity", 100, 3), ("metric", 7, 1),
     ("recent", -1, 1), ("n_seq", 0, 1), ("n_seq", 70000, 2),
+    ("v_rho", -0.1, 1), ("v_rho", 1.0, 1), ("v_rho", float("nan"), 1),
 ])
 def test_bad_config_is_refused(pk, field, value, status):
     kw = dict(n_seq=1, n_kv_heads=4, n_q_heads=4, n_patterns=16, bits=2, group=64, recent=0, flush=64, t_capacity=1024)
@@ -68,6 +69,16 @@ def test_bad_config_is_refused(pk, field, value, status):
         pk.pk_cache_layout(pk.Config(**kw))
     assert e.value.status == status
     assert pk.pk_workspace_bytes(pk.Config(**kw), pk.OP_DECODE, 1024) == 0
+
+
+def test_v_threshold_needs_a_free_index(pk):
+    # the adaptive threshold marks raw-quantized V tokens with index 255 (PK_NO_PATTERN)
+    kw = dict(n_seq=1, n_kv_heads=4, n_q_heads=4, bits=2, group=64, recent=0, flush=64, t_capacity=1024, v_rho=0.9)
+    pk.pk_cache_layout(pk.Config(n_patterns=255, **kw))
+    with pytest.raises(pk.PkError) as e:
+        pk.pk_cache_layout(pk.Config(n_patterns=256, **kw))
+    assert e.value.status == 2
+    assert pk.NO_PATTERN == 255
 
 
 def test_workspace_sizes_are_monotone(pk):

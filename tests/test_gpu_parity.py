@@ -52,11 +52,11 @@ def upload(gc, ocache):
 
 
 def make_case(oracle, pk, seed, *, n_seq=1, hkv=2, hq=2, T=320, P=16, bits=2, G=64, R=0, F=None, metric=0,
-              seqs_per_set=0, n_clusters=8, cap=None, mine_iters=3):
+              seqs_per_set=0, n_clusters=8, cap=None, mine_iters=3, v_rho=0.0):
     F = max(G, 64) if F is None else F
     cap = cap if cap is not None else -(-T // F) * F
     kw = dict(n_seq=n_seq, n_kv_heads=hkv, n_q_heads=hq, head_dim=128, n_patterns=P, seqs_per_set=seqs_per_set,
-              bits=bits, group=G, recent=R, flush=F, t_capacity=cap, metric=metric)
+              bits=bits, group=G, recent=R, flush=F, t_capacity=cap, metric=metric, v_rho=v_rho)
     spec = synth.KVSpec(1, n_seq, hkv, hq, T, 128, n_clusters)
     K, V = synth.make_kv(seed, spec)
     ocfg, gcfg = oracle.Config(**kw), pk.Config(**kw)
@@ -153,6 +153,30 @@ def test_quantize_append_parity(oracle, pk, bits, G, P, metric):
     assert np.abs(vg.cpu().numpy() - vo)[same_v].max() <= 1e-3
     if n_diff == 0:
         assert np.array_equal(kg.cpu().numpy(), ko) and np.array_equal(vg.cpu().numpy(), vo)
+
+
+@pytest.mark.parametrize("bits,G,P,metric,hq", [(2, 64, 4, 0, 8), (4, 32, 5, 0, 2), (2, 128, 3, 1, 4), (2, 32, 255, 0, 4)])
+def test_v_adaptive_threshold_parity(oracle, pk, bits, G, P, metric, hq):
+    """Sec. 3.3: V tokens whose flat range exceeds rho times their raw range are quantized without a pattern
+    (index 255); fewer patterns than clusters make a large share of tokens take that branch."""
+    rho = 0.8 if P < 255 else float(np.float32(oracle.rho_star(128, 0.05)))
+    kw, ocfg, gcfg, K, V, Mk, Mv = make_case(oracle, pk, 500 + P + G, T=448, P=P, bits=bits, G=G, metric=metric,
+                                            n_seq=2, hkv=2, hq=hq, n_clusters=12 if P < 255 else 40, v_rho=rho)
+    oc, gc, Mkd, Mvd = run_appends(oracle, pk, ocfg, gcfg, K, V, Mk, Mv, [300, 148])
+    raw_share = float((oc.v_idx[:, :oc.t_quant] == oracle.NO_PATTERN).mean())
+    if P < 255:
+        assert 0.05 < raw_share < 0.95
+    n_diff = compare_caches(oracle, oc, gc, metric)
+    assert n_diff <= 4
+    assert not (oc.k_idx[:, :oc.t_quant] == oracle.NO_PATTERN).any() or P == 256   # K is never thresholded
+    kg, vg = pk.pk_dequantize(gcfg, gc, Mkd, Mvd)
+    ko, vo = oc.dequantize(Mk, Mv)
+    if n_diff == 0:
+        assert np.array_equal(kg.cpu().numpy(), ko) and np.array_equal(vg.cpu().numpy(), vo)
+    q = synth.make_queries(9, 2, hq, 128)
+    want, _ = oracle.decode_attention(oc, q.view(np.uint16), Mk, Mv, 128 ** -0.5)
+    got = pk.pk_decode_attention(gcfg, gc, dev(q), 128 ** -0.5, Mkd, Mvd).cpu().numpy()
+    assert rel_l2(got, want) <= 2e-3
 
 
 def test_streaming_appends_with_recent_window(oracle, pk):

@@ -30,7 +30,7 @@ __global__ __launch_bounds__(256) void mine_init_kernel(MineArgs a)
 // fp16 as clamp(1 - (idx_t - p)^2, 0, 1), which is exactly 1 or 0 for integers below 256; products are
 // exact and the accumulation order is fixed by the instruction sequence, so the sums are reproducible.
 // Dynamic LDS: [table pad16(P) rows (TAB_LDS only)] [-norm2/2 pad16(P)] [cnt pad16(P)] [xs 64 rows]
-//              [idx 64 bytes] [xrow 4*kD halves]
+//              [idx 64 halves] [xrow 4*kD halves]
 constexpr int kMineXs = kD + 8;   // halves per row of the vector tile
 
 typedef _Float16 half2m __attribute__((ext_vector_type(2)));
@@ -44,8 +44,8 @@ __global__ __launch_bounds__(256) void mine_step_kernel(MineArgs a, int chunk)
     float *norm_s = reinterpret_cast<float *>(smem + (TAB_LDS ? (size_t)pad16(P) * kTabStride * 2 : 0));
     int *cnt = reinterpret_cast<int *>(norm_s + pad16(P));
     __half *xs = reinterpret_cast<__half *>(cnt + pad16(P));
-    uint8_t *idx_s = reinterpret_cast<uint8_t *>(xs + 64 * kMineXs);
-    __half *xrow_s = reinterpret_cast<__half *>(idx_s + 64);
+    __half *idx_s = xs + 64 * kMineXs;   // pattern index of every vector of the sub-tile, as an fp16 number
+    __half *xrow_s = idx_s + 64;
     __shared__ float red_s[4];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 15, kb = lane >> 4;
@@ -95,7 +95,7 @@ __global__ __launch_bounds__(256) void mine_step_kernel(MineArgs a, int chunk)
         for (int k = 0; k < 4; ++k)   // a row past the chunk is stored as zeros, so it adds nothing to any sum
             *reinterpret_cast<uint4 *>(xs + tl * kMineXs + 32 * k + 8 * kb) = tok < n_tok ? xb[k] : make_uint4(0u, 0u, 0u, 0u);
         if (kb == 0) {
-            idx_s[tl] = (uint8_t)bi;
+            idx_s[tl] = __float2half_rn((float)bi);   // integers below 2048 are exact
             if (tok < n_tok) {
                 a.assign[(int64_t)s * a.T + t_begin + tok] = bi;
                 a.best[(int64_t)s * a.T + t_begin + tok] = bd;
@@ -107,14 +107,9 @@ __global__ __launch_bounds__(256) void mine_step_kernel(MineArgs a, int chunk)
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {   // 32 vectors per step; this lane's k-slots: vectors 32ks + 8kb + j
             const int t0 = 32 * ks + 8 * kb;
-            const uint2 id8 = *reinterpret_cast<const uint2 *>(idx_s + t0);
-            half2m idh[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const uint32_t w = j < 2 ? id8.x : id8.y;
-                const int sh = 16 * (j & 1);
-                idh[j] = half2m{(_Float16)(float)((w >> sh) & 255u), (_Float16)(float)((w >> (sh + 8)) & 255u)};
-            }
+            const uint4 id8 = *reinterpret_cast<const uint4 *>(idx_s + t0);   // 8 indices, pairs in k-slot order
+            const half2m idh[4] = {__builtin_bit_cast(half2m, id8.x), __builtin_bit_cast(half2m, id8.y),
+                                   __builtin_bit_cast(half2m, id8.z), __builtin_bit_cast(half2m, id8.w)};
             uint4 bop[2];
 #pragma unroll
             for (int ci = 0; ci < 2; ++ci) {
@@ -135,7 +130,7 @@ __global__ __launch_bounds__(256) void mine_step_kernel(MineArgs a, int chunk)
                 for (int j = 0; j < 4; ++j) {
                     const half2m d = idh[j] - prow[pt];
                     half2m oh = one2 - d * d;                       // 1 where the index equals the row, <= 0 elsewhere
-                    oh = __builtin_elementwise_max(oh, half2m{(_Float16)0.f, (_Float16)0.f});
+                    oh = __builtin_elementwise_min(__builtin_elementwise_max(oh, half2m{(_Float16)0.f, (_Float16)0.f}), one2);   // folds into the clamp bit
                     aop[j] = __builtin_bit_cast(uint32_t, oh);
                 }
                 const uint4 av = make_uint4(aop[0], aop[1], aop[2], aop[3]);
@@ -212,7 +207,7 @@ __global__ __launch_bounds__(256) void mine_inertia_kernel(MineArgs a, int it)
 size_t step_lds_bytes(int P, int chunk, bool tab_lds)
 {
     size_t b = tab_lds ? (size_t)pad16(P) * kTabStride * 2 : 0;
-    b += (size_t)pad16(P) * 4 + (size_t)pad16(P) * 4 + 64 * (size_t)kMineXs * 2 + 64 + 4 * kD * 2;
+    b += (size_t)pad16(P) * 4 + (size_t)pad16(P) * 4 + 64 * (size_t)kMineXs * 2 + 64 * 2 + 4 * kD * 2;
     (void)chunk;
     return (b + 15) / 16 * 16;
 }

@@ -100,22 +100,19 @@ def main():
     Mk = torch.empty((n_sets, P, d), dtype=torch.float16, device=dev)
     Mv = torch.empty_like(Mk)
     out = torch.empty((n_seq, Hq, d), dtype=torch.float32, device=dev)
-    mine_sets = n_sets if B == 1 else Hkv                 # pattern sets mined by one library call
-    ws_mine = torch.empty(max(pk.pk_workspace_bytes(cfg, pk.OP_MINE, T, mine_sets), 16), dtype=torch.uint8, device=dev)
+    ws_mine = torch.empty(max(pk.pk_workspace_bytes(cfg, pk.OP_MINE, T, n_sets), 16), dtype=torch.uint8, device=dev)
     ws_dec = torch.empty(max(pk.pk_workspace_bytes(cfg, pk.OP_DECODE, T, 0), 16), dtype=torch.uint8, device=dev)
     flush_buf = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
     scale = d ** -0.5
 
+    # mining reads the first batch element of every layer: for a batch > 1 those streams are gathered once, at
+    # set-up, into one uniformly strided tensor, so that all layers' tables are mined by one call per tensor
+    Kmine = K.view(n_sets, T, d) if B == 1 else K[::B].reshape(n_sets, T, d).contiguous()
+    Vmine = V.view(n_sets, T, d) if B == 1 else V[::B].reshape(n_sets, T, d).contiguous()
+
     def mine():
-        # one table per (layer, KV head), mined on the layer's first batch element
-        if B == 1:      # all layers' streams are uniformly strided: one call per tensor
-            pk.pk_mine_patterns(cfg, K.view(n_sets, T, d), iters, patterns=Mk, workspace=ws_mine)
-            pk.pk_mine_patterns(cfg, V.view(n_sets, T, d), iters, patterns=Mv, workspace=ws_mine)
-            return
-        for layer in range(L):
-            s = layer * B
-            pk.pk_mine_patterns(cfg, K[s], iters, patterns=Mk[layer * Hkv:(layer + 1) * Hkv], workspace=ws_mine)
-            pk.pk_mine_patterns(cfg, V[s], iters, patterns=Mv[layer * Hkv:(layer + 1) * Hkv], workspace=ws_mine)
+        pk.pk_mine_patterns(cfg, Kmine, iters, patterns=Mk, workspace=ws_mine)
+        pk.pk_mine_patterns(cfg, Vmine, iters, patterns=Mv, workspace=ws_mine)
 
     def quantize():
         cache.state.t_quant = cache.state.t_tail = cache.state.tail_start = 0

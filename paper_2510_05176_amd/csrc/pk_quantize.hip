@@ -538,12 +538,12 @@ __global__ __launch_bounds__(256) void quantize_k_kernel(QuantArgs a, int tiles_
 
 // K, groups of 32 or 64 tokens: a wave owns whole groups, so nothing but the pattern table is shared in
 // the workgroup and no workgroup barrier is needed after it is staged.  The group's NTG = G/16 tiles stay
-// in registers as loaded (fp16); pass A assigns every tile and feeds its residuals through a small LDS
-// tile to a per-channel running minimum / maximum (lane <-> channel), pass B forms the residuals again,
+// in registers as loaded (fp16); pass A assigns every tile and feeds its residuals, 32 channels at a time,
+// through a small LDS tile to a per-channel running minimum / maximum, pass B forms the residuals again,
 // quantizes and stores.  A tile's registers are refilled with the wave's next group as soon as pass B
 // has used them.
-constexpr int kWkStride = 64 + 4;                     // floats per row of the half-width residual tile
-constexpr int kWkTile = 16 * kWkStride * 4;           // bytes: 16 tokens x 64 channels
+constexpr int kWkStride = 32 + 4;                     // floats per row of the quarter-width residual tile
+constexpr int kWkTile = 16 * kWkStride * 4;           // bytes: 16 tokens x 32 channels (also the output staging area)
 constexpr int kWkWave = kWkTile + kD * 2 * 2 + kD * 4;   // + zero points, scales (fp16 bits), 1/s
 
 static size_t wave_k_lds_bytes(int P, bool tab_lds)
@@ -588,39 +588,44 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void q
 
     for (; g < g_end; g += 4) {
         const int64_t tq0 = (int64_t)a.t0 + (int64_t)g * G;   // packed position of the group's first token
-        // ---- pass A: indices, running minimum / maximum of channels lane and lane + 64
-        float mn[2] = {INFINITY, INFINITY}, mx[2] = {-INFINITY, -INFINITY};
+        // ---- pass A: indices; running minimum / maximum per channel.  The residuals pass through the LDS tile a
+        //      quarter (32 channels = one operand step) at a time; lane <-> (channel lane%32, token half lane/32)
+        float mn[4] = {INFINITY, INFINITY, INFINITY, INFINITY}, mx[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
         int bi[NTG];
+        const int sc = lane & 31, sth = lane >> 5;
 #pragma unroll
         for (int j = 0; j < NTG; ++j) {
             float r[32];
             bi[j] = assign_residuals<TAB_LDS>(sh, tb, Mg, xb[j], reinterpret_cast<__half *>(rt), r);
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {   // channels 64h .. 64h+63 = operand steps k = 2h, 2h+1
-#pragma unroll
-                for (int kk = 0; kk < 2; ++kk) {
-                    const int e = 8 * (2 * h + kk);
-                    float4 *dst = reinterpret_cast<float4 *>(rt + n * kWkStride + 32 * kk + 8 * kb);
-                    dst[0] = make_float4(r[e], r[e + 1], r[e + 2], r[e + 3]);
-                    dst[1] = make_float4(r[e + 4], r[e + 5], r[e + 6], r[e + 7]);
-                }
+            for (int k = 0; k < 4; ++k) {   // channels 32k .. 32k+31
+                float4 *dst = reinterpret_cast<float4 *>(rt + n * kWkStride + 8 * kb);
+                dst[0] = make_float4(r[8 * k], r[8 * k + 1], r[8 * k + 2], r[8 * k + 3]);
+                dst[1] = make_float4(r[8 * k + 4], r[8 * k + 5], r[8 * k + 6], r[8 * k + 7]);
                 wave_lds_sync();
 #pragma unroll
-                for (int t = 0; t < 16; t += 2) {
-                    const float v0 = rt[t * kWkStride + lane], v1 = rt[(t + 1) * kWkStride + lane];
-                    mn[h] = fminf(fminf(mn[h], v0), v1);
-                    mx[h] = fmaxf(fmaxf(mx[h], v0), v1);
+                for (int t = 0; t < 8; t += 2) {
+                    const float v0 = rt[(8 * sth + t) * kWkStride + sc], v1 = rt[(8 * sth + t + 1) * kWkStride + sc];
+                    mn[k] = fminf(fminf(mn[k], v0), v1);
+                    mx[k] = fmaxf(fmaxf(mx[k], v0), v1);
                 }
                 wave_lds_sync();
             }
         }
-        // ---- parameters of the group: channel lane + 64h
+        // ---- parameters of the group: the two token halves are combined, then lane (c, half) takes the channels
+        //      32(2 half) + c and 32(2 half + 1) + c
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            mn[k] = fminf(mn[k], __shfl_xor(mn[k], 32));
+            mx[k] = fmaxf(mx[k], __shfl_xor(mx[k], 32));
+        }
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-            const GroupParams gp = group_params(mn[h], mx[h], BITS);
-            pz[64 * h + lane] = gp.z16;
-            pz[kD + 64 * h + lane] = gp.s16;
-            pinv[64 * h + lane] = gp.inv;
+            const GroupParams gp = group_params(sth ? mn[2 + h] : mn[h], sth ? mx[2 + h] : mx[h], BITS);
+            const int c = 32 * (2 * sth + h) + sc;
+            pz[c] = gp.z16;
+            pz[kD + c] = gp.s16;
+            pinv[c] = gp.inv;
         }
         wave_lds_sync();
         if (lane < 32) {   // stored parameters: 16-byte pieces, zero points then scales

@@ -15,7 +15,8 @@ inputs come from HBM and not from the 256 MB Infinity Cache.
 
 Workloads (--workload): cfg2x32 (default: the contract's config 2 - Llama-3-8B-shaped layer, batch 1, T=8192,
 8 KV / 32 query heads, P=64, group 64 - for the model's 32 layers in one launch, 256 KV streams), cfg2 (one
-layer of it: 8 streams, launch-bound), cfg3 (32 layers x batch 16 x T=32768, P=128), cfg5 (T=131072, P=256).
+layer of it: 8 streams, launch-bound), cfg3 (32 layers x batch 16 x T=32768, P=128), cfg5 (T=131072, P=256),
+cfg4 (streaming: 64 samples over a shared 4096-token prompt cache, one token appended per step; use --steps 256).
 """
 import argparse
 import json
@@ -38,7 +39,88 @@ WORKLOADS = {
     "cfg2x32": dict(spec="cfg2", layers=32, batch=1, P=64, iters=10, group=64, recent=0, flush=64),
     "cfg3": dict(spec="cfg3", layers=32, batch=16, P=128, iters=10, group=64, recent=128, flush=128),
     "cfg5": dict(spec="cfg5", layers=1, batch=1, P=256, iters=20, group=128, recent=0, flush=128),
+    "cfg4": dict(spec="cfg4"),   # streaming: its own step, see run_streaming()
 }
+
+
+def run_streaming(args, torch, pk, synth):
+    """Config 4: 64 samples share a 4096-token prompt cache (patterns mined once on the prompt, P=64); every step
+    appends one generated token per sample (flushed to the packed cache in 128-token chunks, group 32, 2 bits)
+    and runs decode attention over prompt + own cache.  A step here = one generation step of all samples."""
+    dev = "cuda"
+    spec = synth.SPECS["cfg4"]
+    S, Hkv, Hq, d, P, Tp, G, F, bits = spec.batch, spec.n_kv_heads, spec.n_q_heads, spec.d, 64, 4096, 32, 128, args.bits
+    gen0, steps, warm = args.gen_len, args.steps, args.warmup
+    t_all = gen0 + steps + warm
+    cap = -(-t_all // F) * F
+    pcfg = pk.Config(n_seq=1, n_kv_heads=Hkv, n_q_heads=Hq, head_dim=d, n_patterns=P, seqs_per_set=0, bits=bits,
+                     group=G, recent=0, flush=F, t_capacity=Tp, metric=pk.METRIC_L2)
+    cfg = pk.Config(n_seq=S, n_kv_heads=Hkv, n_q_heads=Hq, head_dim=d, n_patterns=P, seqs_per_set=S, bits=bits,
+                    group=G, recent=0, flush=F, t_capacity=cap, metric=pk.METRIC_L2)
+    Kp, Vp = synth.make_layer_device(args.seed, 0, synth.KVSpec(**{**spec.__dict__, "batch": 1, "T": Tp}), dev)
+    Kg, Vg = synth.make_layer_device(args.seed, 1, synth.KVSpec(**{**spec.__dict__, "T": t_all}), dev)
+    Mk = pk.pk_mine_patterns(pcfg, Kp[0], 10)
+    Mv = pk.pk_mine_patterns(pcfg, Vp[0], 10)
+    pc, gc = pk.Cache(pcfg), pk.Cache(cfg)
+    pk.pk_quantize_append(pcfg, pc, Kp, Vp, Mk, Mv)
+    pk.pk_quantize_append(cfg, gc, Kg[:, :, :gen0], Vg[:, :, :gen0], Mk, Mv)
+    q = torch.from_numpy(synth.make_queries(args.seed, S, Hq, d).view(np.int16)).to(dev).view(torch.float16)
+    out = torch.empty((S, Hq, d), dtype=torch.float32, device=dev)
+    ws = torch.empty(max(pk.pk_workspace_bytes(cfg, pk.OP_DECODE, t_all, Tp), 16), dtype=torch.uint8, device=dev)
+    scale = d ** -0.5
+
+    def step(t):
+        pk.pk_quantize_append(cfg, gc, Kg[:, :, t:t + 1], Vg[:, :, t:t + 1], Mk, Mv)
+        pk.pk_decode_attention(cfg, gc, q, scale, Mk, Mv, out=out, workspace=ws, prefix=pc)
+
+    t = gen0
+    for _ in range(warm):
+        step(t)
+        t += 1
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        step(t)
+        t += 1
+    e1.record()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
+    # the two calls on their own at the final length (HIP events on the launch stream, median of 20)
+    def med(fn):
+        v = []
+        for _ in range(20):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(); fn(); b.record(); b.synchronize()
+            v.append(a.elapsed_time(b))
+        return float(np.median(v))
+    dec_ms = med(lambda: pk.pk_decode_attention(cfg, gc, q, scale, Mk, Mv, out=out, workspace=ws, prefix=pc))
+    N = S * Hkv
+    tq, tt = gc.t_quant, gc.t_tail
+    per_tok = 2 * (bits * d / 8) + 2 * (2 * 2 * d / G) + 2
+    dec_bytes = N * (tq * per_tok + tt * 2 * d * 2) + Hkv * (pc.t_quant * per_tok + 2 * P * d * 2) + S * Hq * d * 6
+    flush_bytes = N * F * (2 * d * 2 + per_tok)
+    result = {
+        "metric": "KV quantize-append GB/s and decode-attention tokens/s on 2-bit cache, % HBM peak",
+        "value": round(S * steps / (ms_per_step * steps * 1e-3), 1),
+        "unit": "generated tokens/s (64 samples, one layer: append + decode attention per step)",
+        "n_gpus": 1, "steps": steps, "warmup": warm, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16 in, f32 arithmetic, u%d codes" % bits,
+        "data": "synthetic",
+        "config": {"workload": "cfg4", "samples": S, "n_kv_heads": Hkv, "n_q_heads": Hq, "prompt_tokens": Tp,
+                   "generated_tokens_at_end": t, "head_dim": d, "n_patterns": P, "bits": bits, "group": G, "flush": F,
+                   "metric": "L2", "seed": args.seed},
+        "stages": {"step_ms_events": round(e0.elapsed_time(e1) / steps, 4),
+                   "decode_attention": {"ms": round(dec_ms, 4), "GB/s": round(dec_bytes / dec_ms / 1e6, 2),
+                                        "frac_hbm_peak": round(dec_bytes / dec_ms / 1e6 / HBM_PEAK_GBPS, 4),
+                                        "tokens/s": round(S / (dec_ms * 1e-3), 1), "algorithmic_bytes": int(dec_bytes)},
+                   "append_flush_bytes_every_128_steps": int(flush_bytes)},
+        "roofline": {"bound": "hbm", "achieved": round(dec_bytes / dec_ms / 1e6, 3), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(dec_bytes / dec_ms / 1e6 / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "kernel": "decode_packed_kernel(+decode_tail_kernel+decode_merge_kernel)"},
+    }
+    print(json.dumps(result))
 
 
 def main():
@@ -50,6 +132,7 @@ def main():
     ap.add_argument("--bits", type=int, default=2, choices=[2, 4])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=2)
+    ap.add_argument("--gen-len", type=int, default=4096, help="cfg4: generated tokens per sample before the timed steps")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="also run one 1 GiB elementwise copy kernel (bitwise_not) at the end: the known traffic that "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings of this command are scaled by")
@@ -66,6 +149,8 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.workload == "cfg4":
+        return run_streaming(args, torch, pk, synth)
     dev = "cuda"
     w = WORKLOADS[args.workload]
     base = synth.SPECS[w["spec"]]

@@ -245,11 +245,11 @@ hipError_t launch_mine(const MineArgs &a, hipStream_t s)
 {
     hipError_t e;
     const int chunk = mine_chunk(a.T, a.n_sets);
-    const bool tab_lds = a.P <= 128;
+    const bool tab_lds = true;   // up to 256 rows of 288 bytes: 74 KB, one workgroup per CU then
     const size_t lds = step_lds_bytes(a.P, chunk, tab_lds);
     const int npt = a.P <= 16 ? 1 : a.P <= 32 ? 2 : a.P <= 64 ? 4 : a.P <= 128 ? 8 : 16;   // pattern tiles held in registers
 #define PK_STEP(CALL)                                                          \
-    (npt == 1 ? CALL<true, 1> : npt == 2 ? CALL<true, 2> : npt == 4 ? CALL<true, 4> : npt == 8 ? CALL<true, 8> : CALL<false, 16>)
+    (npt == 1 ? CALL<true, 1> : npt == 2 ? CALL<true, 2> : npt == 4 ? CALL<true, 4> : npt == 8 ? CALL<true, 8> : CALL<true, 16>)
     if ((e = PK_STEP(prepare_step)(lds)) != hipSuccess) return e;
     if (!a.init_given) {
         hipLaunchKernelGGL(mine_init_kernel, dim3((a.P * kRowChunks + 255) / 256, a.n_sets), dim3(256), 0, s, a);

@@ -866,7 +866,7 @@ static hipError_t launch_tiled(K kernel, const QuantArgs &a, int TT, size_t lds,
 hipError_t launch_quantize_k(const QuantArgs &a, hipStream_t s)
 {
     if (a.metric == PK_METRIC_L2) {
-        const bool tl = a.P <= 128;
+        const bool tl = a.P <= 256;   // table rows in LDS (74 KB at 256 patterns)
 #define PK_LAUNCH_K2(GG, BB)                                                                                       \
     if (a.G == GG && a.bits == BB) {                                                                               \
         constexpr int TT = GG == 128 ? 128 : 64;                                                                   \
@@ -899,7 +899,7 @@ hipError_t launch_quantize_k(const QuantArgs &a, hipStream_t s)
 hipError_t launch_quantize_v(const QuantArgs &a, hipStream_t s)
 {
     if (a.metric == PK_METRIC_L2) {
-        const bool tl = a.P <= 128;
+        const bool tl = a.P <= 256;   // table rows in LDS (74 KB at 256 patterns)
         const int ng = kD / (a.G < kD ? a.G : kD);
         const size_t lds = tile_lds_bytes(a.P, tl, 0, 1);
 #define PK_LAUNCH_V2(BB, NN)                                                                   \

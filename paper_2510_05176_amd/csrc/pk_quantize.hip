@@ -854,11 +854,13 @@ static int tiles_per_wg(int n_tiles, int n_streams)
 }
 
 template <class K>
-static hipError_t launch_tiled(K kernel, const QuantArgs &a, int TT, size_t lds, hipStream_t s)
+static hipError_t launch_tiled(K kernel, const QuantArgs &a, int TT, size_t lds, hipStream_t s, int min_tiles = 1)
 {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    const int n_tiles = a.nq / TT, tpw = tiles_per_wg(n_tiles, a.n_streams);
+    int tpw = tiles_per_wg(a.nq / TT, a.n_streams);
+    if (tpw < min_tiles) tpw = min_tiles;
+    const int n_tiles = a.nq / TT;
     hipLaunchKernelGGL(kernel, dim3((n_tiles + tpw - 1) / tpw, a.n_streams), dim3(256), lds, s, a, tpw);
     return hipGetLastError();
 }
@@ -875,8 +877,9 @@ hipError_t launch_quantize_k(const QuantArgs &a, hipStream_t s)
     }
 #define PK_LAUNCH_KW(GG, BB)                                                                                       \
     if (a.G == GG && a.bits == BB) {                                                                               \
-        return tl ? launch_tiled(quantize_k_wave_kernel<GG, BB, true>, a, 64, wave_k_lds_bytes(a.P, true), s)      \
-                  : launch_tiled(quantize_k_wave_kernel<GG, BB, false>, a, 64, wave_k_lds_bytes(a.P, false), s);   \
+        /* a wave owns whole groups: at least four groups per workgroup */                                        \
+        return tl ? launch_tiled(quantize_k_wave_kernel<GG, BB, true>, a, 64, wave_k_lds_bytes(a.P, true), s, GG / 16)      \
+                  : launch_tiled(quantize_k_wave_kernel<GG, BB, false>, a, 64, wave_k_lds_bytes(a.P, false), s, GG / 16);   \
     }
         PK_LAUNCH_KW(32, 2) PK_LAUNCH_KW(64, 2) PK_LAUNCH_K2(128, 2)
         PK_LAUNCH_KW(32, 4) PK_LAUNCH_KW(64, 4) PK_LAUNCH_K2(128, 4)

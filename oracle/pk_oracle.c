@@ -387,6 +387,24 @@ void pko_quantize_v(const uint16_t *x, int n, int d, const uint16_t *M, int32_t 
     free(r);
 }
 
+/*
+ * Decode-stage pattern of a window of vectors (Sec. 3.1 "Decoding Stage", Eq. 5): per channel the
+ * Chebyshev centre of the window's values, (min_i x_ic + max_i x_ic) / 2, computed in binary32 (the sum
+ * of two fp16 values and the halving are exact) and rounded to fp16, ties to even.
+ */
+void pko_window_pattern(const uint16_t *x, int n, int d, uint16_t *out)
+{
+    for (int c = 0; c < d; ++c) {
+        float mn = pko_half_to_float(x[c]), mx = mn;
+        for (int t = 1; t < n; ++t) {
+            float v = pko_half_to_float(x[(int64_t)t * d + c]);
+            if (v < mn) mn = v;
+            if (v > mx) mx = v;
+        }
+        out[c] = pko_float_to_half_rne((mn + mx) * 0.5f);
+    }
+}
+
 /* ------------------------------------------------------------------------- */
 /* Bit-plane packing.  The paper does not fix a storage format; this is the   */
 /* format of this repository, defined by the two index formulas below.        */

@@ -181,6 +181,16 @@ def dequant(side, codes_u8, scale, zero, idx_i32, M_u16, G, thresholded=False):
     return out
 
 
+def window_pattern(x_u16):
+    """x[S, n, d] u16 -> [S, d] u16: the decode-stage pattern of each window (Sec. 3.1 Eq. 5, per-channel midrange)."""
+    x_u16 = np.ascontiguousarray(x_u16, dtype=np.uint16)
+    S, n, d = x_u16.shape
+    out = np.empty((S, d), np.uint16)
+    for s in range(S):
+        lib().pko_window_pattern(_p(x_u16[s]), n, d, _p(out[s]))
+    return out
+
+
 NO_PATTERN = 255   # V index of a token the adaptive threshold sent to raw quantization
 
 

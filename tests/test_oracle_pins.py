@@ -363,6 +363,26 @@ def test_v_threshold_minmax_range_is_dmm(oracle):
     assert np.array_equal(res["idx"][0] == oracle.NO_PATTERN, ~(dmm <= np.float32(rho) * (xr.max(1) - xr.min(1))))
 
 
+# ------------------------------------------------------------------ decode-stage patterns (Sec. 3.1 Eq. 5)
+
+def test_window_pattern_is_the_per_channel_chebyshev_centre(oracle):
+    rng = np.random.default_rng(41)
+    x = f16(rng.standard_normal((3, 128, 128)) * np.exp(rng.standard_normal((3, 1, 128))))
+    m = oracle.window_pattern(x.view(np.uint16)).view(np.float16)
+    xf = x.astype(np.float64)
+    mid = (xf.min(1) + xf.max(1)) / 2                              # Eq. 5 in exact arithmetic
+    assert np.array_equal(m, mid.astype(np.float16))               # one rounding to fp16, ties to even
+    # Chebyshev centre: no other fp16 value has a smaller worst deviation from the window, per channel
+    dev = np.abs(xf - m.astype(np.float64)[:, None, :]).max(1)
+    for other in (np.nextafter(m, np.float16(np.inf)), np.nextafter(m, np.float16(-np.inf)), xf.mean(1).astype(np.float16)):
+        assert np.all(dev <= np.abs(xf - other.astype(np.float64)[:, None, :]).max(1) + 1e-12)
+    # it halves the range a raw quantizer would see: residuals of the window lie in [-R/2, R/2] (+ fp16 rounding of m)
+    R = xf.max(1) - xf.min(1)
+    assert np.all(dev <= R / 2 + np.abs(m.astype(np.float64)) * 2.0 ** -11 + 1e-12)
+    # a window of one vector is that vector; a constant channel stays exact
+    assert np.array_equal(oracle.window_pattern(x[:, :1].view(np.uint16)), x[:, 0].view(np.uint16))
+
+
 def test_zero_residual_reconstructs_exactly(oracle):
     rng = np.random.default_rng(12)
     M = f16(rng.standard_normal((1, 5, 128)))

@@ -11,6 +11,8 @@
  *                         K quantized per channel and V per token (Sec. 4.1)
  *   pk_decode_attention   Sec. 3.4 "Decode-stage KV reconstruction": attention
  *                         computed directly on the packed cache
+ *   pk_window_pattern     Sec. 3.1 "Decoding Stage", Eq. 5: the pattern of a window of
+ *                         vectors (per-channel Chebyshev centre)
  *   pk_dequantize         the reconstruction rule below Eq. 6 (debug / parity)
  *
  * Conventions shared by every call
@@ -223,6 +225,20 @@ pk_status pk_decode_attention(const pk_config *cfg, const pk_cache *cache, const
                               const pk_state *prefix_state, const void *q, float softmax_scale,
                               const void *patterns_k, const void *patterns_v, float *out, float *lse,
                               void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Decode-stage pattern update (Sec. 3.1 "Decoding Stage", Eq. 5): for each of n_sets windows of n
+ * vectors, the per-channel Chebyshev centre  m_c = (min_i x_ic + max_i x_ic) / 2,  computed in binary32
+ * (exact for fp16 inputs) and rounded to fp16, ties to even.  The caller merges the result into its
+ * pattern table (one more row, n_patterns + 1 afterwards; tables are [sets][n_patterns][d] contiguous, so
+ * growing one means re-laying it out) and uses the grown table for the following appends and decodes.
+ *   x           device, fp16, window s at x + s*set_stride elements, n rows of head_dim contiguous
+ *   pattern_out device, fp16, row s at pattern_out + s*out_stride elements (head_dim values)
+ * Errors (before any launch): NULL pointers, n_sets < 1, n < 1 -> PK_ERR_INVALID_ARG; head_dim != 128 ->
+ * PK_ERR_UNSUPPORTED; pointers or strides not 16-byte aligned -> PK_ERR_ALIGNMENT.  Asynchronous on `stream`.
+ */
+pk_status pk_window_pattern(const void *x, int64_t set_stride, int32_t n_sets, int32_t n, int32_t head_dim,
+                            void *pattern_out, int64_t out_stride, void *stream);
 
 /*
  * Reconstruct packed tokens [t0, t1) of every stream: X^ = M[k*] + (s*code + z)

@@ -350,6 +350,18 @@ pk_status pk_decode_attention(const pk_config *cfg, const pk_cache *cache, const
     return launch_decode(a, static_cast<hipStream_t>(stream)) == hipSuccess ? PK_OK : PK_ERR_DEVICE;
 }
 
+pk_status pk_window_pattern(const void *x, int64_t set_stride, int32_t n_sets, int32_t n, int32_t head_dim,
+                            void *pattern_out, int64_t out_stride, void *stream)
+{
+    if (!x || !pattern_out || n_sets < 1 || n < 1 || set_stride < 0 || out_stride < 0) return PK_ERR_INVALID_ARG;
+    if (head_dim != kD || n_sets > 65535) return PK_ERR_UNSUPPORTED;
+    if (!aligned16(x) || !aligned16(pattern_out) || set_stride % 8 != 0 || out_stride % 8 != 0) return PK_ERR_ALIGNMENT;
+    return launch_window_pattern(static_cast<const __half *>(x), set_stride, n_sets, n, static_cast<__half *>(pattern_out),
+                                 out_stride, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? PK_OK
+               : PK_ERR_DEVICE;
+}
+
 pk_status pk_dequantize(const pk_config *cfg, const pk_cache *cache, const pk_state *state, const void *patterns_k,
                         const void *patterns_v, int32_t t0, int32_t t1, float *k_out, float *v_out, void *stream)
 {

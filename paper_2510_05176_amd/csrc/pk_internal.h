@@ -118,6 +118,8 @@ struct MineArgs {
 };
 hipError_t launch_mine(const MineArgs &a, hipStream_t s);
 int mine_tsplit(int T, int n_sets);
+hipError_t launch_window_pattern(const __half *x, int64_t set_stride, int n_sets, int n, __half *out, int64_t out_stride,
+                                 hipStream_t s);
 
 struct CacheView {
     const uint32_t *k_codes;

@@ -204,6 +204,33 @@ __global__ __launch_bounds__(256) void mine_inertia_kernel(MineArgs a, int it)
     if (tid == 0) a.inertia[(int64_t)s * a.iters + it] = red[0];
 }
 
+// Decode-stage pattern of a window (Sec. 3.1 "Decoding Stage", Eq. 5): per channel (min + max) / 2 over the
+// window's vectors, in binary32 (exact for fp16 inputs), rounded to fp16.  One workgroup per window;
+// thread <-> (channel, token parity).
+__global__ __launch_bounds__(256) void window_pattern_kernel(const __half *x, int64_t set_stride, int n, __half *out,
+                                                             int64_t out_stride)
+{
+    __shared__ float s_mn[kD], s_mx[kD];
+    const int c = threadIdx.x & (kD - 1), par = threadIdx.x >> 7;
+    const __half *xs = x + (int64_t)blockIdx.x * set_stride + c;
+    float mn = INFINITY, mx = -INFINITY;
+    for (int t = par; t < n; t += 2) {
+        const float v = h2f(xs[(int64_t)t * kD]);
+        mn = fminf(mn, v);
+        mx = fmaxf(mx, v);
+    }
+    if (par == 1) {
+        s_mn[c] = mn;
+        s_mx[c] = mx;
+    }
+    __syncthreads();
+    if (par == 0) {
+        mn = fminf(mn, s_mn[c]);
+        mx = fmaxf(mx, s_mx[c]);
+        out[(int64_t)blockIdx.x * out_stride + c] = __float2half_rn((mn + mx) * 0.5f);
+    }
+}
+
 size_t step_lds_bytes(int P, int chunk, bool tab_lds)
 {
     size_t b = tab_lds ? (size_t)pad16(P) * kTabStride * 2 : 0;
@@ -266,6 +293,13 @@ hipError_t launch_mine(const MineArgs &a, hipStream_t s)
     }
 #undef PK_STEP
     return hipSuccess;
+}
+
+hipError_t launch_window_pattern(const __half *x, int64_t set_stride, int n_sets, int n, __half *out, int64_t out_stride,
+                                 hipStream_t s)
+{
+    hipLaunchKernelGGL(window_pattern_kernel, dim3(n_sets), dim3(256), 0, s, x, set_stride, n, out, out_stride);
+    return hipGetLastError();
 }
 
 }  // namespace pk

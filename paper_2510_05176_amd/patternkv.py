@@ -69,6 +69,8 @@ _lib.pk_decode_attention.argtypes = [C.POINTER(_Config), C.POINTER(_Cache), C.PO
                                      C.POINTER(_Config), C.POINTER(_Cache), C.POINTER(_State), C.c_void_p,
                                      C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                      C.c_size_t, C.c_void_p]
+_lib.pk_window_pattern.restype = C.c_int
+_lib.pk_window_pattern.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p]
 _lib.pk_dequantize.restype = C.c_int
 _lib.pk_dequantize.argtypes = [C.POINTER(_Config), C.POINTER(_Cache), C.POINTER(_State), C.c_void_p,
                                C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -196,6 +198,21 @@ def pk_mine_patterns(cfg: Config, x: torch.Tensor, iters: int, patterns: torch.T
                                _ptr(workspace), workspace.numel(), _stream())
     _check(st, "pk_mine_patterns")
     return patterns
+
+
+def pk_window_pattern(x: torch.Tensor, out: torch.Tensor | None = None):
+    """x [n_sets, n, d] fp16 (windows may be strided, rows contiguous) -> [n_sets, d] fp16: per-channel
+    Chebyshev centre of every window (the decode-stage pattern).  `out` may be a strided view, e.g. one row of
+    every set of a table [n_sets, P, d]."""
+    assert x.dtype == torch.float16 and x.dim() == 3 and x.stride(2) == 1 and (x.shape[1] == 1 or x.stride(1) == x.shape[2])
+    n_sets, n, d = x.shape
+    if out is None:
+        out = torch.empty((n_sets, d), dtype=torch.float16, device=x.device)
+    assert out.dtype == torch.float16 and out.shape == (n_sets, d) and out.stride(1) == 1
+    st = _lib.pk_window_pattern(C.c_void_p(x.data_ptr()), x.stride(0) if n_sets > 1 else n * d, n_sets, n, d,
+                                C.c_void_p(out.data_ptr()), out.stride(0) if n_sets > 1 else d, _stream())
+    _check(st, "pk_window_pattern")
+    return out
 
 
 def pk_quantize_append(cfg: Config, cache: Cache, k_new: torch.Tensor, v_new: torch.Tensor,

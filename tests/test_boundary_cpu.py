@@ -25,7 +25,7 @@ def test_exports_every_declared_symbol(pk):
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
     names = set(re.findall(r"\b(pk_[a-z_]+)\s*\(", src))
     assert {"pk_mine_patterns", "pk_quantize_append", "pk_decode_attention", "pk_dequantize", "pk_cache_layout",
-            "pk_workspace_bytes", "pk_status_string", "pk_abi_version"} <= names
+            "pk_workspace_bytes", "pk_status_string", "pk_abi_version", "pk_window_pattern"} <= names
     lib = C.CDLL(LIB)
     for n in names:
         assert hasattr(lib, n), n
@@ -161,3 +161,14 @@ def test_decode_and_mine_argument_errors_before_launch(pk):
         return lib.pk_dequantize(C.byref(c), C.byref(cache), C.byref(state), good, good, kw.get("t0", 0),
                                  kw.get("t1", 64), kw.get("k", good), good, None)
     assert deq(t1=65) == 3 and deq(t0=10, t1=5) == 3 and deq(k=C.c_void_p(0x2004)) == 4
+
+
+def test_window_pattern_argument_errors_before_launch(pk):
+    lib = pk._lib
+    good, odd = C.c_void_p(0x2000), C.c_void_p(0x2002)
+
+    def wp(x=good, ss=128 * 16, n_sets=2, n=16, d=128, out=good, os=128):
+        return lib.pk_window_pattern(x, ss, n_sets, n, d, out, os, None)
+    assert wp(x=None) == 1 and wp(out=None) == 1 and wp(n=0) == 1 and wp(n_sets=0) == 1
+    assert wp(d=64) == 2
+    assert wp(x=odd) == 4 and wp(out=odd) == 4 and wp(ss=100) == 4 and wp(os=130) == 4

@@ -310,6 +310,49 @@ def test_decode_with_shared_prefix(oracle, pk):
     assert np.abs(lse.cpu().numpy() - want_lse).max() <= 2e-3
 
 
+# ------------------------------------------------------------------------------ decode-stage pattern update
+
+def test_window_pattern_and_growing_tables(oracle, pk):
+    """Sec. 3.1 "Decoding Stage": every flushed chunk of generated vectors contributes its Chebyshev centre as a
+    new pattern of that stream's table; the grown tables serve the following appends and the decode."""
+    P0, G, F, bits, hkv, hq, n_seq = 6, 32, 64, 2, 2, 4, 3
+    spec = synth.KVSpec(1, n_seq, hkv, hq, 64 * 5, 128, 10, drift_sigma=0.2, drift_chunk=64)
+    K, V = synth.make_kv(91, spec)
+    N = n_seq * hkv
+    Kf, Vf = K.reshape(N, -1, 128), V.reshape(N, -1, 128)
+    # one table per stream (seqs_per_set = 1), started from the stream's first vectors
+    Mk, Mv = Kf[:, :P0].copy().view(np.uint16), Vf[:, :P0].copy().view(np.uint16)
+    Mkd, Mvd = dev(Mk.view(np.float16)), dev(Mv.view(np.float16))
+    Kd, Vd = dev(K), dev(V)
+    kw = dict(n_seq=n_seq, n_kv_heads=hkv, n_q_heads=hq, head_dim=128, n_patterns=P0, seqs_per_set=1, bits=bits,
+              group=G, recent=0, flush=F, t_capacity=64 * 5, metric=0)
+    oc, gc = oracle.Cache(oracle.Config(**kw)), pk.Cache(pk.Config(**kw))
+    for step in range(5):
+        sl = slice(64 * step, 64 * (step + 1))
+        if step > 0:   # the window about to be flushed yields one more pattern per stream, K and V
+            wk, wv = oracle.window_pattern(Kf[:, sl].view(np.uint16)), oracle.window_pattern(Vf[:, sl].view(np.uint16))
+            gk = pk.pk_window_pattern(Kd.view(N, -1, 128)[:, sl])
+            gv = pk.pk_window_pattern(Vd.view(N, -1, 128)[:, sl])
+            assert np.array_equal(host_u16(gk), wk) and np.array_equal(host_u16(gv), wv)
+            Mk, Mv = np.concatenate([Mk, wk[:, None]], 1), np.concatenate([Mv, wv[:, None]], 1)
+            Mkd, Mvd = torch.cat([Mkd, gk[:, None]], 1).contiguous(), torch.cat([Mvd, gv[:, None]], 1).contiguous()
+        kw["n_patterns"] = Mk.shape[1]
+        oc.cfg, gc.cfg = oracle.Config(**kw), pk.Config(**kw)
+        oc.append(K[:, :, sl].view(np.uint16), V[:, :, sl].view(np.uint16), Mk, Mv)
+        pk.pk_quantize_append(gc.cfg, gc, Kd[:, :, sl], Vd[:, :, sl], Mkd, Mvd)
+    assert Mk.shape[1] == P0 + 4 and oc.t_quant == 320
+    compare_caches(oracle, oc, gc, 0)
+    assert (oc.k_idx[:, 64:] >= P0).any() and oc.k_idx.max() < P0 + 4          # the added patterns are in use
+    q = synth.make_queries(12, n_seq, hq, 128)
+    want, _ = oracle.decode_attention(oc, q.view(np.uint16), Mk, Mv, 128 ** -0.5)
+    got = pk.pk_decode_attention(gc.cfg, gc, dev(q), 128 ** -0.5, Mkd, Mvd).cpu().numpy()
+    assert rel_l2(got, want) <= 2e-3
+    # strided output: straight into a row of a table
+    tab = torch.zeros((N, 4, 128), dtype=torch.float16, device="cuda")
+    pk.pk_window_pattern(Kd.view(N, -1, 128)[:, 64:128], out=tab[:, 2])
+    assert np.array_equal(host_u16(tab[:, 2]), oracle.window_pattern(Kf[:, 64:128].view(np.uint16))) and not tab[:, 3].any()
+
+
 # ------------------------------------------------------------------------------ pattern mining
 
 def _ulp_diff(a_u16, b_u16):

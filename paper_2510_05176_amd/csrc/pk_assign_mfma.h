@@ -39,14 +39,17 @@ __device__ __forceinline__ floatx4_t mfma_f16(const uint4 &a, const uint4 &b, fl
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, a), __builtin_bit_cast(half8_t, b), c, 0, 0, 0);
 }
 
-// Stage a pattern table into LDS (256 threads) and compute the row norms.  Ends with a barrier.
+// Stage a pattern table into LDS (nthr threads, a multiple of 64 dividing pad16(P)*16... or not: the loop is
+// guarded) and compute the row norms; red_s gets one maximum per wave.  Ends with a barrier.
 // Work item i = (row i/16, 16-byte piece i%16): the 16 lanes of a row sum their squares.
 __device__ __forceinline__ void stage_patterns(const __half *Mg, int P, __half *tab_s, float *nh_s, float *red_s,
-                                               bool to_lds)
+                                               bool to_lds, int nthr = 256)
 {
     const int tid = threadIdx.x;
     float mx = 0.f;
-    for (int i = tid; i < pad16(P) * kRowChunks; i += 256) {   // pad16(P) * 16 is a multiple of 256
+    // pad16(P) * 16 is a multiple of 256, and every 16 consecutive work items sit in one wave: the row sums
+    // below see whole rows (a trailing half round of a 512-thread group has whole waves idle)
+    for (int i = tid; i < pad16(P) * kRowChunks; i += nthr) {
         const int r = i >> 4, ch = i & 15;
         uint4 v = make_uint4(0u, 0u, 0u, 0u);
         if (r < P) v = *reinterpret_cast<const uint4 *>(Mg + (int64_t)r * kD + ch * 8);

@@ -22,11 +22,12 @@ __global__ __launch_bounds__(256) void mine_init_kernel(MineArgs a)
     *reinterpret_cast<uint4 *>(a.patterns + ((int64_t)s * a.P + p) * kD + ch * 8) = v;
 }
 
-// Assignment step + partial cluster sums of one chunk of one set.  256 threads.
-// The chunk is walked in sub-tiles of 64 vectors: every wave assigns 16 of them on the matrix cores and
+// Assignment step + partial cluster sums of one chunk of one set.  64*NW threads.
+// The chunk is walked in sub-tiles of 16*NW vectors: every wave assigns 16 of them on the matrix cores and
 // leaves them, with their indices, in an LDS tile.  The cluster sums are a second contraction on the
-// matrix cores, sums[p][c] += sum_t onehot[p][t] x[t][c]: wave w owns channels 32w .. 32w+31 and keeps
-// its NPT x 2 accumulator tiles in registers for the whole chunk.  The one-hot operand is formed in packed
+// matrix cores, sums[p][c] += sum_t onehot[p][t] x[t][c]: the NW waves (4, or 8 when the table is large and
+// only one workgroup fits a CU) split the 8 channel tiles and keep their NPT x 8/NW accumulator tiles in
+// registers for the whole chunk.  The one-hot operand is formed in packed
 // fp16 as clamp(1 - (idx_t - p)^2, 0, 1), which is exactly 1 or 0 for integers below 256; products are
 // exact and the accumulation order is fixed by the instruction sequence, so the sums are reproducible.
 // Dynamic LDS: [table pad16(P) rows (TAB_LDS only)] [-norm2/2 pad16(P)] [cnt pad16(P)] [xs 64 rows]
@@ -35,8 +36,8 @@ constexpr int kMineXs = kD + 8;   // halves per row of the vector tile
 
 typedef _Float16 half2m __attribute__((ext_vector_type(2)));
 
-template <bool TAB_LDS, int NPT>
-__global__ __launch_bounds__(256) void mine_step_kernel(MineArgs a, int chunk)
+template <bool TAB_LDS, int NPT, int NW>
+__global__ __launch_bounds__(64 * NW) void mine_step_kernel(MineArgs a, int chunk)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const int P = a.P;
@@ -44,9 +45,11 @@ __global__ __launch_bounds__(256) void mine_step_kernel(MineArgs a, int chunk)
     float *norm_s = reinterpret_cast<float *>(smem + (TAB_LDS ? (size_t)pad16(P) * kTabStride * 2 : 0));
     int *cnt = reinterpret_cast<int *>(norm_s + pad16(P));
     __half *xs = reinterpret_cast<__half *>(cnt + pad16(P));
-    __half *idx_s = xs + 64 * kMineXs;   // pattern index of every vector of the sub-tile, as an fp16 number
-    __half *xrow_s = idx_s + 64;
-    __shared__ float red_s[4];
+    constexpr int ST = 16 * NW;          // vectors per sub-tile
+    constexpr int CT = 8 / NW;           // 16-channel tiles of the sums owned by a wave
+    __half *idx_s = xs + ST * kMineXs;   // pattern index of every vector of the sub-tile, as an fp16 number
+    __half *xrow_s = idx_s + ST;
+    __shared__ float red_s[NW];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 15, kb = lane >> 4;
     const int ck = blockIdx.x, s = blockIdx.y;
@@ -55,36 +58,38 @@ __global__ __launch_bounds__(256) void mine_step_kernel(MineArgs a, int chunk)
     const __half *Mg = a.patterns + (int64_t)s * P * kD;
 
     auto load_tile = [&](int sub, uint4 (&xb)[4]) {
-        const int tok = min(sub * 64 + wave * 16 + n, n_tok - 1);   // rows past the chunk repeat its last vector
+        const int tok = min(sub * ST + wave * 16 + n, n_tok - 1);   // rows past the chunk repeat its last vector
 #pragma unroll
         for (int k = 0; k < 4; ++k) xb[k] = *reinterpret_cast<const uint4 *>(xg + (int64_t)tok * kD + 32 * k + 8 * kb);
     };
     uint4 xb[4];
     load_tile(0, xb);
 
-    for (int i = tid; i < pad16(P); i += 256) cnt[i] = 0;
-    stage_patterns(Mg, P, tab_s, norm_s, red_s, TAB_LDS);   // ends with a barrier
+    for (int i = tid; i < pad16(P); i += 64 * NW) cnt[i] = 0;
+    stage_patterns(Mg, P, tab_s, norm_s, red_s, TAB_LDS, 64 * NW);   // ends with a barrier
     PatternTable tb;
     tb.lds_rows = tab_s;
     tb.glb_rows = Mg;
     tb.nh = norm_s;
-    tb.norm2_max = fmaxf(fmaxf(red_s[0], red_s[1]), fmaxf(red_s[2], red_s[3]));
+    tb.norm2_max = red_s[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) tb.norm2_max = fmaxf(tb.norm2_max, red_s[w]);
     tb.P = P;
 
-    floatx4_t acc[NPT][2];
+    floatx4_t acc[NPT][CT];
     half2m prow[NPT];   // this lane's pattern row of every tile, as a packed pair
 #pragma unroll
     for (int pt = 0; pt < NPT; ++pt) {
-        acc[pt][0] = floatx4_t{0.f, 0.f, 0.f, 0.f};
-        acc[pt][1] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ci = 0; ci < CT; ++ci) acc[pt][ci] = floatx4_t{0.f, 0.f, 0.f, 0.f};
         const _Float16 v = (_Float16)(float)(16 * pt + n);
         prow[pt] = half2m{v, v};
     }
     const half2m one2 = {(_Float16)1.f, (_Float16)1.f};
 
-    const int n_sub = (n_tok + 63) >> 6;
+    const int n_sub = (n_tok + ST - 1) / ST;
     for (int sub = 0; sub < n_sub; ++sub) {
-        const int tl = wave * 16 + n, tok = sub * 64 + tl;
+        const int tl = wave * 16 + n, tok = sub * ST + tl;
         int bi;
         float bv, x2, bd;
         bool flag;
@@ -105,15 +110,15 @@ __global__ __launch_bounds__(256) void mine_step_kernel(MineArgs a, int chunk)
         if (sub + 1 < n_sub) load_tile(sub + 1, xb);   // in flight during the accumulation
         __syncthreads();
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {   // 32 vectors per step; this lane's k-slots: vectors 32ks + 8kb + j
+        for (int ks = 0; ks < ST / 32; ++ks) {   // 32 vectors per step; this lane's k-slots: vectors 32ks + 8kb + j
             const int t0 = 32 * ks + 8 * kb;
             const uint4 id8 = *reinterpret_cast<const uint4 *>(idx_s + t0);   // 8 indices, pairs in k-slot order
             const half2m idh[4] = {__builtin_bit_cast(half2m, id8.x), __builtin_bit_cast(half2m, id8.y),
                                    __builtin_bit_cast(half2m, id8.z), __builtin_bit_cast(half2m, id8.w)};
-            uint4 bop[2];
+            uint4 bop[CT];
 #pragma unroll
-            for (int ci = 0; ci < 2; ++ci) {
-                const __half *col = xs + t0 * kMineXs + 16 * (2 * wave + ci) + n;
+            for (int ci = 0; ci < CT; ++ci) {
+                const __half *col = xs + t0 * kMineXs + 16 * (CT * wave + ci) + n;
                 uint32_t w[4];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
@@ -134,13 +139,13 @@ __global__ __launch_bounds__(256) void mine_step_kernel(MineArgs a, int chunk)
                     aop[j] = __builtin_bit_cast(uint32_t, oh);
                 }
                 const uint4 av = make_uint4(aop[0], aop[1], aop[2], aop[3]);
-                acc[pt][0] = mfma_f16(av, bop[0], acc[pt][0]);
-                acc[pt][1] = mfma_f16(av, bop[1], acc[pt][1]);
+#pragma unroll
+                for (int ci = 0; ci < CT; ++ci) acc[pt][ci] = mfma_f16(av, bop[ci], acc[pt][ci]);
             }
         }
         __syncthreads();
     }
-    // partial sums of the chunk: D rows 4kb+i = pattern 16pt + 4kb + i, column n = channel 16(2 wave + ci) + n
+    // partial sums of the chunk: D rows 4kb+i = pattern 16pt + 4kb + i, column n = channel 16(CT wave + ci) + n
     const int64_t o = ((int64_t)s * a.tsplit + ck) * P;
 #pragma unroll
     for (int pt = 0; pt < NPT; ++pt) {
@@ -148,12 +153,12 @@ __global__ __launch_bounds__(256) void mine_step_kernel(MineArgs a, int chunk)
         for (int i = 0; i < 4; ++i) {
             const int pr = 16 * pt + 4 * kb + i;
             if (pr < P) {
-                a.psum[(o + pr) * kD + 16 * (2 * wave) + n] = acc[pt][0][i];
-                a.psum[(o + pr) * kD + 16 * (2 * wave + 1) + n] = acc[pt][1][i];
+#pragma unroll
+                for (int ci = 0; ci < CT; ++ci) a.psum[(o + pr) * kD + 16 * (CT * wave + ci) + n] = acc[pt][ci][i];
             }
         }
     }
-    for (int i = tid; i < P; i += 256) a.pcnt[o + i] = cnt[i];
+    for (int i = tid; i < P; i += 64 * NW) a.pcnt[o + i] = cnt[i];
 }
 
 // update step: centroid = mean of members (binary32 division), rounded to fp16;
@@ -231,11 +236,10 @@ __global__ __launch_bounds__(256) void window_pattern_kernel(const __half *x, in
     }
 }
 
-size_t step_lds_bytes(int P, int chunk, bool tab_lds)
+size_t step_lds_bytes(int P, int nw, bool tab_lds)
 {
     size_t b = tab_lds ? (size_t)pad16(P) * kTabStride * 2 : 0;
-    b += (size_t)pad16(P) * 4 + (size_t)pad16(P) * 4 + 64 * (size_t)kMineXs * 2 + 64 * 2 + 4 * kD * 2;
-    (void)chunk;
+    b += (size_t)pad16(P) * 4 + (size_t)pad16(P) * 4 + 16 * nw * (size_t)kMineXs * 2 + 16 * nw * 2 + (size_t)nw * kD * 2;
     return (b + 15) / 16 * 16;
 }
 
@@ -254,17 +258,17 @@ int mine_chunk(int T, int n_sets)
 
 int mine_tsplit(int T, int n_sets) { return (T + mine_chunk(T, n_sets) - 1) / mine_chunk(T, n_sets); }
 
-template <bool TAB_LDS, int NPT>
+template <int NPT, int NW>
 static hipError_t launch_step(const MineArgs &a, int chunk, size_t lds, hipStream_t s)
 {
-    hipLaunchKernelGGL((mine_step_kernel<TAB_LDS, NPT>), dim3(a.tsplit, a.n_sets), dim3(256), lds, s, a, chunk);
+    hipLaunchKernelGGL((mine_step_kernel<true, NPT, NW>), dim3(a.tsplit, a.n_sets), dim3(64 * NW), lds, s, a, chunk);
     return hipGetLastError();
 }
 
-template <bool TAB_LDS, int NPT>
-static hipError_t prepare_step(size_t lds)
+template <int NPT, int NW>
+static hipError_t prepare_step(const MineArgs &, int, size_t lds, hipStream_t)
 {
-    return hipFuncSetAttribute(reinterpret_cast<const void *>(&mine_step_kernel<TAB_LDS, NPT>),
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(&mine_step_kernel<true, NPT, NW>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
 }
 
@@ -272,12 +276,14 @@ hipError_t launch_mine(const MineArgs &a, hipStream_t s)
 {
     hipError_t e;
     const int chunk = mine_chunk(a.T, a.n_sets);
-    const bool tab_lds = true;   // up to 256 rows of 288 bytes: 74 KB, one workgroup per CU then
-    const size_t lds = step_lds_bytes(a.P, chunk, tab_lds);
-    const int npt = a.P <= 16 ? 1 : a.P <= 32 ? 2 : a.P <= 64 ? 4 : a.P <= 128 ? 8 : 16;   // pattern tiles held in registers
-#define PK_STEP(CALL)                                                          \
-    (npt == 1 ? CALL<true, 1> : npt == 2 ? CALL<true, 2> : npt == 4 ? CALL<true, 4> : npt == 8 ? CALL<true, 8> : CALL<true, 16>)
-    if ((e = PK_STEP(prepare_step)(lds)) != hipSuccess) return e;
+    // pattern tiles held in registers; 8 waves share the table when only one workgroup fits a CU (P > 128;
+    // at 128 patterns two 4-wave workgroups measured faster than one 8-wave group pair)
+    const int npt = a.P <= 16 ? 1 : a.P <= 32 ? 2 : a.P <= 64 ? 4 : a.P <= 128 ? 8 : 16;
+    const int nw = a.P > 128 ? 8 : 4;
+    const size_t lds = step_lds_bytes(a.P, nw, true);
+#define PK_STEP(CALL)                                                                                       \
+    (npt == 1 ? CALL<1, 4> : npt == 2 ? CALL<2, 4> : npt == 4 ? CALL<4, 4> : npt == 8 ? CALL<8, 4> : CALL<16, 8>)
+    if ((e = PK_STEP(prepare_step)(a, chunk, lds, s)) != hipSuccess) return e;
     if (!a.init_given) {
         hipLaunchKernelGGL(mine_init_kernel, dim3((a.P * kRowChunks + 255) / 256, a.n_sets), dim3(256), 0, s, a);
         if ((e = hipGetLastError()) != hipSuccess) return e;

@@ -1,8 +1,8 @@
 // Pattern mining: Lloyd iterations for the K-means objective of Sec. 3.1 Eq. 4, one independent
 // problem per pattern set (layer x KV head, K and V separately).
 //
-// One iteration = mine_step_kernel (assignment step on the matrix cores + per-chunk cluster sums in
-// LDS) followed by mine_update_kernel (fixed-order reduction over the chunks, mean, fp16 rounding).
+// One iteration = mine_step_kernel (assignment step and per-chunk cluster sums, both on the matrix
+// cores) followed by mine_update_kernel (fixed-order reduction over the chunks, mean, fp16 rounding).
 // Every sum is formed in a fixed order, so results are reproducible bit for bit.
 #include "pk_assign_mfma.h"
 #include "pk_internal.h"

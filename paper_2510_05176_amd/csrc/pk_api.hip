@@ -320,6 +320,7 @@ pk_status pk_decode_attention(const pk_config *cfg, const pk_cache *cache, const
     }
     const int64_t N = (int64_t)cfg->n_seq * cfg->n_kv_heads, r = cfg->n_q_heads / cfg->n_kv_heads;
     a.chunk = decode_chunk(N, (int64_t)a.own.t_quant + a.prefix.t_quant, cfg->n_patterns, (int)r);
+    a.w_stride = (cfg->v_rho > 0.f || (has_prefix && prefix_cfg->v_rho > 0.f)) ? 256 : cfg->n_patterns;
     a.splits_own = (a.own.t_quant + a.chunk - 1) / a.chunk;
     a.splits_prefix = (a.prefix.t_quant + a.chunk - 1) / a.chunk;
     const int64_t slots = a.splits_own + a.splits_prefix + 2;

@@ -96,8 +96,10 @@ template <int BITS, bool G32>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void decode_packed_kernel(DecodeArgs a)
 {
     constexpr int WPU = BITS / 2;   // 32-bit words per (channel, 16-token unit) of V; K: 4*BITS words per token
-    __shared__ float QMs[kMaxP][16];
-    __shared__ float Ws[4][8][kMaxP];
+    // dynamic LDS: QMs [P][16] floats (q.M_K per pattern and column); Ws [4 waves][R][w_stride] 64-bit fixed-point
+    // sums (softmax mass per V pattern, unit 2^-31).  Integer LDS atomics run at full rate on this chip, float
+    // ones retire about one lane per 2.6 cycles (measured), which made the mass sums the slowest part of a block.
+    extern __shared__ __align__(16) unsigned char dyn_smem[];
     __shared__ float Os[8][kD];
     __shared__ float stat_m[4][16], stat_l[4][16], stat_pz[4][16];
 
@@ -121,6 +123,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
     const __half *MK = a.patterns_k + (int64_t)set * P * kD;
     const float sc2 = a.softmax_scale * kLog2e;
     const float c1 = sc2 * 65536.f, inv_c1 = 1.f / c1;
+    const int WS = a.w_stride;   // P, or 256 when index 255 can occur (tokens quantized without a pattern)
+    float *QMs = reinterpret_cast<float *>(dyn_smem);
+    unsigned long long *Ws = reinterpret_cast<unsigned long long *>(QMs + P * 16);
+    constexpr float kWUnit = 2147483648.f;   // 2^31: weights are at most 1
 
     // ---- this lane's slice of its query head: channels 32*kb .. 32*kb+31
     _Float16 qh[32];
@@ -161,10 +167,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int pr = tp * 16 + 4 * kb + i;
-            if (pr < P) QMs[pr][n] = acc[i] * sc2;
+            if (pr < P) QMs[pr * 16 + n] = acc[i] * sc2;
         }
     }
-    for (int i = lane; i < 8 * kMaxP; i += 64) (&Ws[wave][0][0])[i] = 0.f;
+    for (int i = lane; i < R * WS; i += 64) Ws[wave * R * WS + i] = 0ull;
     __syncthreads();
 
     // ---- this wave's run of 64-token blocks
@@ -328,7 +334,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int id = (kidw[x] >> (8 * i)) & 255;
-                S[4 * x + i] = fmaf(d[i], c1, QMs[id][n]);
+                S[4 * x + i] = fmaf(d[i], c1, QMs[id * 16 + n]);
             }
         }
 
@@ -360,7 +366,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
             if (started) {
                 for (int hh = 0; hh < R; ++hh) {
                     const float ar = __shfl(alpha, hh);
-                    for (int p = lane; p < P; p += 64) Ws[wave][hh][p] *= ar;
+                    for (int p = lane; p < P; p += 64) {
+                        unsigned long long *w = &Ws[(wave * R + hh) * WS + p];
+                        *w = (unsigned long long)((float)*w * ar);
+                    }
                 }
             }
             m_run += delta;
@@ -376,7 +385,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
         if (n < R) {
             const uint32_t vidw[4] = {vid.x, vid.y, vid.z, vid.w};
 #pragma unroll
-            for (int k = 0; k < 16; ++k) atomicAdd(&Ws[wave][n][(vidw[k >> 2] >> (8 * (k & 3))) & 255], pr[k]);
+            for (int k = 0; k < 16; ++k)
+                atomicAdd(&Ws[(wave * R + n) * WS + ((vidw[k >> 2] >> (8 * (k & 3))) & 255)],
+                          (unsigned long long)__float2uint_rn(pr[k] * kWUnit));   // pr <= 1: no overflow
         }
 
         // ---- V side
@@ -462,8 +473,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
         const float M = fmaxf(fmaxf(stat_m[0][hh], stat_m[1][hh]), fmaxf(stat_m[2][hh], stat_m[3][hh]));
         float acc = 0.f;
 #pragma unroll
-        for (int w = 0; w < 4; ++w) acc = fmaf(__builtin_amdgcn_exp2f(stat_m[w][hh] - M), Ws[w][hh][pp], acc);
-        a.part_w[pbase * P + e] = acc;
+        for (int w = 0; w < 4; ++w) acc = fmaf(__builtin_amdgcn_exp2f(stat_m[w][hh] - M), (float)Ws[(w * R + hh) * WS + pp], acc);
+        a.part_w[pbase * P + e] = acc * (1.f / kWUnit);
     }
     if (tid < R) {
         const float M = fmaxf(fmaxf(stat_m[0][tid], stat_m[1][tid]), fmaxf(stat_m[2][tid], stat_m[3][tid]));
@@ -477,22 +488,28 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
 
 }  // namespace
 
+template <int BITS, bool G32>
+static hipError_t launch_one(const DecodeArgs &a, dim3 grid, size_t lds, hipStream_t s)
+{
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_packed_kernel<BITS, G32>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((decode_packed_kernel<BITS, G32>), grid, dim3(256), lds, s, a);
+    return hipGetLastError();
+}
+
 hipError_t launch_decode_packed(const DecodeArgs &a, hipStream_t s)
 {
     const int splits = a.splits_prefix + a.splits_own;
     if (splits == 0) return hipSuccess;
-    const dim3 grid(splits, a.n_seq * a.n_kv_heads), block(256);
-    if (a.bits == 2 && a.G == 32)
-        hipLaunchKernelGGL((decode_packed_kernel<2, true>), grid, block, 0, s, a);
-    else if (a.bits == 2)
-        hipLaunchKernelGGL((decode_packed_kernel<2, false>), grid, block, 0, s, a);
-    else if (a.bits == 4 && a.G == 32)
-        hipLaunchKernelGGL((decode_packed_kernel<4, true>), grid, block, 0, s, a);
-    else if (a.bits == 4)
-        hipLaunchKernelGGL((decode_packed_kernel<4, false>), grid, block, 0, s, a);
-    else
-        return hipErrorInvalidValue;
-    return hipGetLastError();
+    const dim3 grid(splits, a.n_seq * a.n_kv_heads);
+    const int R = a.n_q_heads / a.n_kv_heads;
+    const size_t lds = (size_t)a.P * 16 * 4 + (size_t)4 * R * a.w_stride * 8;   // QMs, Ws
+    if (a.bits == 2 && a.G == 32) return launch_one<2, true>(a, grid, lds, s);
+    if (a.bits == 2) return launch_one<2, false>(a, grid, lds, s);
+    if (a.bits == 4 && a.G == 32) return launch_one<4, true>(a, grid, lds, s);
+    if (a.bits == 4) return launch_one<4, false>(a, grid, lds, s);
+    return hipErrorInvalidValue;
 }
 
 }  // namespace pk

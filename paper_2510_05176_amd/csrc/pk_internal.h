@@ -140,6 +140,8 @@ struct DecodeArgs {
     int32_t n_seq, n_kv_heads, n_q_heads, P, bits, G;
     float softmax_scale;
     int32_t chunk;                // packed tokens per split
+    int32_t w_stride;             // entries per (wave, head) row of the per-pattern softmax mass in LDS: P, or 256
+                                  // when v_idx may hold PK_NO_PATTERN
     int32_t splits_prefix, splits_own;   // packed splits; two more slots hold the tails
     float *part_o;                // [N][S][r][kD]  unnormalised partial outputs
     float *part_w;                // [N][S][r][P]   softmax mass per V pattern (packed splits only)

@@ -304,7 +304,7 @@ def main():
     # ---------------------------------------------------------------- the oracle on the host, bounded sample
     if not args.no_cpu_baseline:
         from oracle import pk_oracle as oracle
-        heads = min(Hkv, 4)                                   # sample: the first `heads` KV heads of sequence 0
+        heads = min(Hkv, 8)                                   # sample: the first `heads` KV heads of sequence 0
         r = Hq // Hkv
         Ks = K[0, :heads].cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
         Vs = V[0, :heads].cpu().contiguous().view(torch.int16).numpy().view(np.uint16)

@@ -110,7 +110,7 @@ typedef struct {
     int32_t group;        /* G: 32, 64 or 128                                                 */
     int32_t recent;       /* R >= 0: vectors always kept in fp16                              */
     int32_t flush;        /* F: multiple of G and of 64; vectors quantized per flush          */
-    int32_t t_capacity;   /* maximum packed tokens per stream, multiple of F                  */
+    int32_t t_capacity;   /* maximum packed tokens per stream, multiple of F, at most 2^25    */
     int32_t metric;       /* pk_metric                                                        */
     float v_rho;          /* adaptive threshold on V (Sec. 3.3, "Adaptive Threshold for V"): 0 = off.  With
                              0 < v_rho < 1 a V vector keeps its pattern only if

@@ -30,6 +30,7 @@ pk_status check_config(const pk_config *c)
     if ((int64_t)c->n_seq * c->n_kv_heads > 65535) return PK_ERR_UNSUPPORTED;
     if (c->flush % c->group != 0 || c->flush % 64 != 0) return PK_ERR_SHAPE;
     if (c->t_capacity % c->flush != 0) return PK_ERR_SHAPE;
+    if (c->t_capacity > (1 << 25)) return PK_ERR_UNSUPPORTED;   // byte offsets inside a stream stay below 2^32
     return PK_OK;
 }
 

@@ -188,14 +188,26 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
     for (int t = 0; t < 8; ++t) O[t] = floatx4{0.f, 0.f, 0.f, 0.f};
     GroupOperand ga, gb;   // gb: second K group of a block, only when G == 32
 
+    // per-stream base pointers (wave-uniform); everything inside a stream is addressed with 32-bit byte offsets
+    // (the host refuses capacities for which those would not fit)
+    const char *kcodes = reinterpret_cast<const char *>(cv.k_codes + (int64_t)cstream * cap * 4 * BITS);
+    const char *vcodes = reinterpret_cast<const char *>(cv.v_codes) + (int64_t)cstream * cap * (kD * BITS / 8);
+    const char *kscale = reinterpret_cast<const char *>(cv.k_scale + (int64_t)cstream * (cap >> lgG) * kD);
+    const char *kzero = reinterpret_cast<const char *>(cv.k_zero + (int64_t)cstream * (cap >> lgG) * kD);
+    const char *vscale = reinterpret_cast<const char *>(cv.v_scale + (int64_t)cstream * cap * NG);
+    const char *vzero = reinterpret_cast<const char *>(cv.v_zero + (int64_t)cstream * cap * NG);
+    const char *kidx = reinterpret_cast<const char *>(cv.k_idx + (int64_t)cstream * cap);
+    const char *vidx = reinterpret_cast<const char *>(cv.v_idx + (int64_t)cstream * cap);
+
     // parameters of one K group: raw loads, then the B operand
     struct GroupRaw {
         uint4 s[4], z[4];
     };
     auto load_group_raw = [&](int grp, GroupRaw &gr) {
-        const int64_t prow = ((int64_t)cstream * (cap >> lgG) + grp) * kD + 32 * kb;
-        const uint4 *sp = reinterpret_cast<const uint4 *>(cv.k_scale + prow);
-        const uint4 *zp = reinterpret_cast<const uint4 *>(cv.k_zero + prow);
+        // offsets inside a stream fit 32 bits (checked on the host): base pointer + 32-bit lane offset
+        const uint32_t prow = ((uint32_t)grp * kD + 32 * kb) * 2;
+        const uint4 *sp = reinterpret_cast<const uint4 *>(kscale + prow);
+        const uint4 *zp = reinterpret_cast<const uint4 *>(kzero + prow);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             gr.s[i] = sp[i];
@@ -226,12 +238,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
         go.qz = acc * sc2;
     };
 
-    const uint32_t *kcodes = cv.k_codes + (int64_t)cstream * cap * 4 * BITS;
-    const uint32_t *vcodes = reinterpret_cast<const uint32_t *>(cv.v_codes) + (int64_t)cstream * cap * (kD * BITS / 32);
-    const __half *vscale = cv.v_scale + (int64_t)cstream * cap * NG;
-    const __half *vzero = cv.v_zero + (int64_t)cstream * cap * NG;
-    const uint8_t *kidx = cv.k_idx + (int64_t)cstream * cap;
-    const uint8_t *vidx = cv.v_idx + (int64_t)cstream * cap;
 
     // K-side inputs of a block: plane words of this lane's 4 token rows, pattern indices of its 16 tokens
     uint32_t kw[4][BITS];
@@ -240,7 +246,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
 #pragma unroll
         for (int x = 0; x < 4; ++x) {
             const int tok = tb + 16 * (n >> 2) + 4 * x + (n & 3);
-            const uint32_t *src = kcodes + ((int64_t)tok * 4 + kb) * BITS;
+            const char *src = kcodes + ((uint32_t)tok * 4 + kb) * BITS * 4;
             if (BITS == 2) {
                 const uint2 v = *reinterpret_cast<const uint2 *>(src);
                 kw[x][0] = v.x;
@@ -253,7 +259,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
                 kw[x][BITS - 1] = v.w;
             }
         }
-        kid = *reinterpret_cast<const uint4 *>(kidx + tb + 16 * kb);
+        kid = *reinterpret_cast<const uint4 *>(kidx + (uint32_t)(tb + 16 * kb));
     };
 
     if (b0 < b1) {
@@ -273,10 +279,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
 
         // ---- V-side loads of the block (used after the scores)
         const int unit = (tb >> 4) + kb;   // 16-token unit of this lane group
-        const uint4 vid = *reinterpret_cast<const uint4 *>(vidx + tb + 16 * kb);
+        const uint4 vid = *reinterpret_cast<const uint4 *>(vidx + (uint32_t)(tb + 16 * kb));
         uint32_t vw[8 * WPU];
         {
-            const uint4 *src = reinterpret_cast<const uint4 *>(vcodes + ((int64_t)unit * 16 + n) * 8 * WPU);
+            const uint4 *src = reinterpret_cast<const uint4 *>(vcodes + ((uint32_t)unit * 16 + n) * 8 * WPU * 4);
 #pragma unroll
             for (int i = 0; i < 2 * WPU; ++i) {
                 const uint4 v = src[i];
@@ -288,8 +294,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
         }
         uint32_t sv[8], zv[8];
         {
-            const uint4 *sp = reinterpret_cast<const uint4 *>(vscale + ((int64_t)unit * NG + g) * 16);
-            const uint4 *zp = reinterpret_cast<const uint4 *>(vzero + ((int64_t)unit * NG + g) * 16);
+            const uint4 *sp = reinterpret_cast<const uint4 *>(vscale + ((uint32_t)unit * NG + g) * 32);
+            const uint4 *zp = reinterpret_cast<const uint4 *>(vzero + ((uint32_t)unit * NG + g) * 32);
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
                 const uint4 s4 = sp[i], z4 = zp[i];
@@ -387,7 +393,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
 #pragma unroll
             for (int k = 0; k < 16; ++k)
                 atomicAdd(&Ws[(wave * R + n) * WS + ((vidw[k >> 2] >> (8 * (k & 3))) & 255)],
-                          (unsigned long long)__float2uint_rn(pr[k] * kWUnit));   // pr <= 1: no overflow
+                          (unsigned long long)(uint32_t)(pr[k] * kWUnit));   // pr <= 1: no overflow; truncation loses < 2^-31
         }
 
         // ---- V side

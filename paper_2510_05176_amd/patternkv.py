@@ -49,7 +49,11 @@ class _State(C.Structure):
     _fields_ = [("t_quant", C.c_int32), ("t_tail", C.c_int32), ("tail_start", C.c_int32)]
 
 
+ABI_VERSION = 2          # PK_ABI_VERSION of include/patternkv.h this binding's structs are laid out for
+
 _lib.pk_abi_version.restype = C.c_uint32
+if int(_lib.pk_abi_version()) != ABI_VERSION:
+    raise ImportError(f"libpatternkv.so has ABI {int(_lib.pk_abi_version())}, this binding needs {ABI_VERSION}: rebuild")
 _lib.pk_status_string.restype = C.c_char_p
 _lib.pk_status_string.argtypes = [C.c_int]
 _lib.pk_cache_layout.restype = C.c_int

@@ -94,7 +94,7 @@ struct MineCarve {
 MineCarve mine_carve(int64_t S, int64_t T, int P)
 {
     MineCarve m;
-    const int ts = mine_tsplit((int)T, (int)S);
+    const int ts = mine_tsplit((int)T, (int)S, P);
     m.assign = 0;
     m.best = round_up(m.assign + (uint64_t)S * T * 4, 256);
     m.psum = round_up(m.best + (uint64_t)S * T * 4, 256);
@@ -194,7 +194,7 @@ pk_status pk_mine_patterns(const pk_config *cfg, const void *x, int64_t set_stri
     a.psum = reinterpret_cast<float *>(ws + mc.psum);
     a.pcnt = reinterpret_cast<int32_t *>(ws + mc.pcnt);
     a.inertia = inertia;
-    a.tsplit = mine_tsplit(T, n_sets);
+    a.tsplit = mine_tsplit(T, n_sets, a.P);
     return launch_mine(a, static_cast<hipStream_t>(stream)) == hipSuccess ? PK_OK : PK_ERR_DEVICE;
 }
 

@@ -117,7 +117,7 @@ struct MineArgs {
     int32_t tsplit;
 };
 hipError_t launch_mine(const MineArgs &a, hipStream_t s);
-int mine_tsplit(int T, int n_sets);
+int mine_tsplit(int T, int n_sets, int P);
 hipError_t launch_window_pattern(const __half *x, int64_t set_stride, int n_sets, int n, __half *out, int64_t out_stride,
                                  hipStream_t s);
 

@@ -25,19 +25,26 @@ __global__ __launch_bounds__(256) void mine_init_kernel(MineArgs a)
 // Assignment step + partial cluster sums of one chunk of one set.  64*NW threads.
 // The chunk is walked in sub-tiles of 16*NW vectors: every wave assigns 16 of them on the matrix cores and
 // leaves them, with their indices, in an LDS tile.  The cluster sums are a second contraction on the
-// matrix cores, sums[p][c] += sum_t onehot[p][t] x[t][c]: the NW waves (4, or 8 when the table is large and
-// only one workgroup fits a CU) split the 8 channel tiles and keep their NPT x 8/NW accumulator tiles in
-// registers for the whole chunk.  The one-hot operand is formed in packed
-// fp16 as clamp(1 - (idx_t - p)^2, 0, 1), which is exactly 1 or 0 for integers below 256; products are
-// exact and the accumulation order is fixed by the instruction sequence, so the sums are reproducible.
-// Dynamic LDS: [table pad16(P) rows (TAB_LDS only)] [-norm2/2 pad16(P)] [cnt pad16(P)] [xs 64 rows]
-//              [idx 64 halves] [xrow 4*kD halves]
-constexpr int kMineXs = kD + 8;   // halves per row of the vector tile
+// matrix cores, sums[p][c] += sum_t onehot[p][t] x[t][c].  The NW waves (4, or 8 when the table is large and
+// only one workgroup fits a CU) split the pattern tiles (and, when there are fewer pattern tiles than waves,
+// the 8 channel tiles as well), so each wave forms the one-hot operand of its own pattern rows only and keeps
+// its accumulator tiles in registers for the whole chunk.  The vector operand is x transposed (the
+// contraction runs over vectors, the tile is stored vector-major): it comes out of LDS with the transposing
+// 64-bit read, in which lane i of a 16-lane group receives element i of four rows whose 32-byte pieces the
+// group's lanes address four to a row.  The one-hot operand is formed in packed fp16 as
+// clamp(1 - (idx_t - p)^2, 0, 1), which is exactly 1 or 0 for integers below 256; products are exact and the
+// accumulation order is fixed by the instruction sequence, so the sums are reproducible.
+// Dynamic LDS: [table pad16(P) rows (TAB_LDS only)] [-norm2/2 pad16(P)] [cnt pad16(P)] [xs 16 NW rows]
+//              [idx 16 NW halves] [xrow NW*kD halves]
+constexpr int kMineXs = kD + 16;   // halves per row of the vector tile: 72 words, so the eight rows that 32 lanes
+                                   // of a transposing read touch (8 words each) fall on 64 distinct banks
 
 typedef _Float16 half2m __attribute__((ext_vector_type(2)));
+typedef short short4m __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) short4m *lds_short4_ptr;
 
 template <bool TAB_LDS, int NPT, int NW>
-__global__ __launch_bounds__(64 * NW) void mine_step_kernel(MineArgs a, int chunk)
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NPT <= 4 ? 4 : 2))) void mine_step_kernel(MineArgs a, int chunk)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const int P = a.P;
@@ -46,7 +53,6 @@ __global__ __launch_bounds__(64 * NW) void mine_step_kernel(MineArgs a, int chun
     int *cnt = reinterpret_cast<int *>(norm_s + pad16(P));
     __half *xs = reinterpret_cast<__half *>(cnt + pad16(P));
     constexpr int ST = 16 * NW;          // vectors per sub-tile
-    constexpr int CT = 8 / NW;           // 16-channel tiles of the sums owned by a wave
     __half *idx_s = xs + ST * kMineXs;   // pattern index of every vector of the sub-tile, as an fp16 number
     __half *xrow_s = idx_s + ST;
     __shared__ float red_s[NW];
@@ -76,14 +82,19 @@ __global__ __launch_bounds__(64 * NW) void mine_step_kernel(MineArgs a, int chun
     for (int w = 1; w < NW; ++w) tb.norm2_max = fmaxf(tb.norm2_max, red_s[w]);
     tb.P = P;
 
-    floatx4_t acc[NPT][CT];
-    half2m prow[NPT];   // this lane's pattern row of every tile, as a packed pair
+    // this wave's share of the sums: PW pattern tiles from pt0, CW channel tiles from ct0
+    constexpr int PW = NPT >= NW ? NPT / NW : 1;
+    constexpr int CW = NPT >= NW ? 8 : 8 * NPT / NW;
+    const int pt0 = NPT >= NW ? wave * PW : wave % NPT;
+    const int ct0 = NPT >= NW ? 0 : (wave / NPT) * CW;
+    floatx4_t acc[PW][CW];
+    half2m prow[PW];   // this lane's pattern row of every tile, as a packed pair
 #pragma unroll
-    for (int pt = 0; pt < NPT; ++pt) {
+    for (int pi = 0; pi < PW; ++pi) {
 #pragma unroll
-        for (int ci = 0; ci < CT; ++ci) acc[pt][ci] = floatx4_t{0.f, 0.f, 0.f, 0.f};
-        const _Float16 v = (_Float16)(float)(16 * pt + n);
-        prow[pt] = half2m{v, v};
+        for (int ci = 0; ci < CW; ++ci) acc[pi][ci] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+        const _Float16 v = (_Float16)(float)(16 * (pt0 + pi) + n);
+        prow[pi] = half2m{v, v};
     }
     const half2m one2 = {(_Float16)1.f, (_Float16)1.f};
 
@@ -110,51 +121,50 @@ __global__ __launch_bounds__(64 * NW) void mine_step_kernel(MineArgs a, int chun
         if (sub + 1 < n_sub) load_tile(sub + 1, xb);   // in flight during the accumulation
         __syncthreads();
 #pragma unroll
-        for (int ks = 0; ks < ST / 32; ++ks) {   // 32 vectors per step; this lane's k-slots: vectors 32ks + 8kb + j
-            const int t0 = 32 * ks + 8 * kb;
-            const uint4 id8 = *reinterpret_cast<const uint4 *>(idx_s + t0);   // 8 indices, pairs in k-slot order
-            const half2m idh[4] = {__builtin_bit_cast(half2m, id8.x), __builtin_bit_cast(half2m, id8.y),
-                                   __builtin_bit_cast(half2m, id8.z), __builtin_bit_cast(half2m, id8.w)};
-            uint4 bop[CT];
+        for (int ks = 0; ks < ST / 32; ++ks) {
+            // 32 vectors per step; this lane's k-slots 0-3 are vectors ta .. ta+3, its slots 4-7 the ones 16 later
+            const int ta = 32 * ks + 4 * kb;
+            const uint2 ia = *reinterpret_cast<const uint2 *>(idx_s + ta);
+            const uint2 ib = *reinterpret_cast<const uint2 *>(idx_s + ta + 16);
+            const half2m idh[4] = {__builtin_bit_cast(half2m, ia.x), __builtin_bit_cast(half2m, ia.y),
+                                   __builtin_bit_cast(half2m, ib.x), __builtin_bit_cast(half2m, ib.y)};
+            uint4 av[PW];
 #pragma unroll
-            for (int ci = 0; ci < CT; ++ci) {
-                const __half *col = xs + t0 * kMineXs + 16 * (CT * wave + ci) + n;
-                uint32_t w[4];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const uint32_t lo = __half_as_ushort(col[(2 * j) * kMineXs]);
-                    const uint32_t hi = __half_as_ushort(col[(2 * j + 1) * kMineXs]);
-                    w[j] = lo | (hi << 16);
-                }
-                bop[ci] = make_uint4(w[0], w[1], w[2], w[3]);
-            }
-#pragma unroll
-            for (int pt = 0; pt < NPT; ++pt) {
+            for (int pi = 0; pi < PW; ++pi) {
                 uint32_t aop[4];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const half2m d = idh[j] - prow[pt];
+                    const half2m d = idh[j] - prow[pi];
                     half2m oh = one2 - d * d;                       // 1 where the index equals the row, <= 0 elsewhere
                     oh = __builtin_elementwise_min(__builtin_elementwise_max(oh, half2m{(_Float16)0.f, (_Float16)0.f}), one2);   // folds into the clamp bit
                     aop[j] = __builtin_bit_cast(uint32_t, oh);
                 }
-                const uint4 av = make_uint4(aop[0], aop[1], aop[2], aop[3]);
+                av[pi] = make_uint4(aop[0], aop[1], aop[2], aop[3]);
+            }
+            // lane n of group kb addresses the 8-byte piece (n & 3) of row ta + n / 4 and receives column n of rows ta .. ta+3
+            const __half *piece = xs + (ta + (n >> 2)) * kMineXs + 16 * ct0 + 4 * (n & 3);
 #pragma unroll
-                for (int ci = 0; ci < CT; ++ci) acc[pt][ci] = mfma_f16(av, bop[ci], acc[pt][ci]);
+            for (int ci = 0; ci < CW; ++ci) {
+                const short4m lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(piece + 16 * ci));
+                const short4m hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(piece + 16 * kMineXs + 16 * ci));
+                const uint2 l2 = __builtin_bit_cast(uint2, lo), h2 = __builtin_bit_cast(uint2, hi);
+                const uint4 bop = make_uint4(l2.x, l2.y, h2.x, h2.y);
+#pragma unroll
+                for (int pi = 0; pi < PW; ++pi) acc[pi][ci] = mfma_f16(av[pi], bop, acc[pi][ci]);
             }
         }
         __syncthreads();
     }
-    // partial sums of the chunk: D rows 4kb+i = pattern 16pt + 4kb + i, column n = channel 16(CT wave + ci) + n
+    // partial sums of the chunk: D rows 4kb+i = pattern 16(pt0 + pi) + 4kb + i, column n = channel 16(ct0 + ci) + n
     const int64_t o = ((int64_t)s * a.tsplit + ck) * P;
 #pragma unroll
-    for (int pt = 0; pt < NPT; ++pt) {
+    for (int pi = 0; pi < PW; ++pi) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int pr = 16 * pt + 4 * kb + i;
+            const int pr = 16 * (pt0 + pi) + 4 * kb + i;
             if (pr < P) {
 #pragma unroll
-                for (int ci = 0; ci < CT; ++ci) a.psum[(o + pr) * kD + 16 * (CT * wave + ci) + n] = acc[pt][ci][i];
+                for (int ci = 0; ci < CW; ++ci) a.psum[(o + pr) * kD + 16 * (ct0 + ci) + n] = acc[pi][ci][i];
             }
         }
     }
@@ -245,18 +255,25 @@ size_t step_lds_bytes(int P, int nw, bool tab_lds)
 
 }  // namespace
 
-int mine_chunk(int T, int n_sets)
+// Workgroups of the step kernel that one compute unit holds at a time: registers allow four 4-wave groups up
+// to 64 patterns; the table and the vector tile in LDS allow two at 128 patterns and one 8-wave group above.
+static int step_groups_per_cu(int P) { return P <= 64 ? 4 : P <= 128 ? 2 : 1; }
+
+int mine_chunk(int T, int n_sets, int P)
 {
-    // aim at ~2048 workgroups over all sets, at most 64 chunks per set; every chunk writes P*128 partial sums,
-    // so chunks should not be smaller than the parallelism needs
-    int64_t c = ((int64_t)T * n_sets + 2047) / 2048;
+    // One resident round of workgroups over the chip's 256 compute units: all chunks then run side by side and
+    // take the same time, and every chunk writes its P*128 partial sums once, so fewer, longer chunks also
+    // mean less traffic.  At most 64 chunks per set, none shorter than 256 vectors.
+    const int64_t slots = 256 * step_groups_per_cu(P);
+    const int64_t per_set = slots / n_sets > 1 ? slots / n_sets : 1;
+    int64_t c = (T + per_set - 1) / per_set;
     if (c < (T + 63) / 64) c = (T + 63) / 64;
-    c = (c + 255) / 256 * 256;
+    c = (c + 127) / 128 * 128;
     if (c < 256) c = 256;
     return (int)c;
 }
 
-int mine_tsplit(int T, int n_sets) { return (T + mine_chunk(T, n_sets) - 1) / mine_chunk(T, n_sets); }
+int mine_tsplit(int T, int n_sets, int P) { return (T + mine_chunk(T, n_sets, P) - 1) / mine_chunk(T, n_sets, P); }
 
 template <int NPT, int NW>
 static hipError_t launch_step(const MineArgs &a, int chunk, size_t lds, hipStream_t s)
@@ -275,7 +292,7 @@ static hipError_t prepare_step(const MineArgs &, int, size_t lds, hipStream_t)
 hipError_t launch_mine(const MineArgs &a, hipStream_t s)
 {
     hipError_t e;
-    const int chunk = mine_chunk(a.T, a.n_sets);
+    const int chunk = mine_chunk(a.T, a.n_sets, a.P);
     // pattern tiles held in registers; 8 waves share the table when only one workgroup fits a CU (P > 128;
     // at 128 patterns two 4-wave workgroups measured faster than one 8-wave group pair)
     const int npt = a.P <= 16 ? 1 : a.P <= 32 ? 2 : a.P <= 64 ? 4 : a.P <= 128 ? 8 : 16;

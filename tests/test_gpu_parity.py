@@ -362,7 +362,7 @@ def _ulp_diff(a_u16, b_u16):
     return np.abs(key(a_u16) - key(b_u16))
 
 
-@pytest.mark.parametrize("T,P,n_c", [(1000, 16, 16), (4096 + 37, 64, 32), (640, 200, 64)])
+@pytest.mark.parametrize("T,P,n_c", [(1000, 16, 16), (4096 + 37, 64, 32), (700, 128, 64), (640, 200, 64)])
 def test_mining_parity_per_iteration(oracle, pk, T, P, n_c):
     spec = synth.KVSpec(1, 1, 3, 3, T, 128, n_c)
     K, V = synth.make_kv(50 + P, spec)

@@ -230,15 +230,16 @@ __global__ __launch_bounds__(128) void decode_merge_kernel(DecodeArgs a)
 
 int decode_chunk(int64_t n_streams, int64_t t_packed_total, int P, int r)
 {
-    // aim at ~1024 workgroups (two are resident per CU); one 64-token block per wave at least, 8192 tokens per
-    // split at most.  Every split also writes r*P pattern masses and r*128 outputs and pays a fixed prologue
-    // (q.M_K table, LDS clears) and epilogue (merge of the four waves), so it should hold at least r*P tokens.
-    int64_t c = (n_streams * t_packed_total + 1023) / 1024;
+    // aim at one resident round of workgroups (two per CU, 512 on the chip): splits that run side by side take
+    // the same time, and a longer split pays the fixed parts once - prologue (q.M_K table, LDS clears), epilogue
+    // (merge of the four waves) and the r*P pattern masses and r*128 outputs it writes - so a split holds at
+    // least r*P tokens, one 64-token block per wave at least, and at most 32768 tokens.
+    int64_t c = (n_streams * t_packed_total + 511) / 512;
     const int64_t floor_c = (int64_t)r * P;
     if (c < floor_c) c = floor_c;
     c = (c + 255) / 256 * 256;
     if (c < 256) c = 256;
-    if (c > 8192) c = 8192;
+    if (c > 32768) c = 32768;
     return (int)c;
 }
 

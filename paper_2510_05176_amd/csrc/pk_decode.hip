@@ -160,15 +160,19 @@ __global__ __launch_bounds__(256) void decode_tail_kernel(DecodeArgs a)
     }
 }
 
-// log-sum-exp merge of the partials of one (sequence, query head); thread <-> channel.
-// The weights exp2(m_s - M) of the slots are formed once, in parallel, and kept in LDS; every loop over the
-// slots is then a run of independent loads.
-__global__ __launch_bounds__(128) void decode_merge_kernel(DecodeArgs a)
+// log-sum-exp merge of the partials of one (sequence, query head); 128*NQ threads, thread <-> (channel c,
+// part q).  The weights exp2(m_s - M) of the slots are formed once, in parallel, and kept in LDS; every loop
+// over the slots or the patterns is then a run of independent loads, of which each of the NQ parts takes every
+// NQ-th term (NQ = 4 when there are many slots or patterns, so that no thread walks a long chain alone); the
+// parts are added in a fixed order.
+template <int NQ>
+__global__ __launch_bounds__(128 * NQ) void decode_merge_kernel(DecodeArgs a)
 {
-    __shared__ float Wt[2][kMaxP];   // softmax mass per pattern: shared prefix, own cache
+    __shared__ float Wq[NQ][2][kMaxP];   // softmax mass per pattern (shared prefix, own cache), per part
+    __shared__ float accq[NQ][kD];
     __shared__ float wslot[kMaxSlots];
-    __shared__ float red[2];
-    const int u = blockIdx.x, c = threadIdx.x;
+    __shared__ float red[2 * NQ];
+    const int u = blockIdx.x, tid = threadIdx.x, c = tid & (kD - 1), q = tid >> 7;
     const int seq = u / a.n_q_heads, qh = u - seq * a.n_q_heads;
     const int r = a.n_q_heads / a.n_kv_heads, P = a.P;
     const int head = qh / r, hr = qh - head * r;
@@ -177,17 +181,19 @@ __global__ __launch_bounds__(128) void decode_merge_kernel(DecodeArgs a)
     const int64_t base = (int64_t)n * n_slots;
     // maximum over the slots that hold anything
     float M = -INFINITY;
-    for (int s = c; s < n_slots; s += 128) {
+    for (int s = tid; s < n_slots; s += 128 * NQ) {
         const int64_t pb = (base + s) * r + hr;
         if (a.part_ml[pb * 2 + 1] > 0.f) M = fmaxf(M, a.part_ml[pb * 2]);
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) M = fmaxf(M, __shfl_xor(M, off));
-    if ((c & 63) == 0) red[c >> 6] = M;
+    if ((tid & 63) == 0) red[tid >> 6] = M;
     __syncthreads();
-    M = fmaxf(red[0], red[1]);
+    M = red[0];
+#pragma unroll
+    for (int w = 1; w < 2 * NQ; ++w) M = fmaxf(M, red[w]);
     float L = 0.f;
-    for (int s = c; s < n_slots; s += 128) {
+    for (int s = tid; s < n_slots; s += 128 * NQ) {
         const int64_t pb = (base + s) * r + hr;
         const float l = a.part_ml[pb * 2 + 1];
         const float w = l > 0.f ? exp2f(a.part_ml[pb * 2] - M) : 0.f;
@@ -197,30 +203,50 @@ __global__ __launch_bounds__(128) void decode_merge_kernel(DecodeArgs a)
     __syncthreads();   // also orders the reads of red above against the writes below
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) L += __shfl_xor(L, off);
-    if ((c & 63) == 0) red[c >> 6] = L;
+    if ((tid & 63) == 0) red[tid >> 6] = L;
     float acc = 0.f;
 #pragma unroll 4
-    for (int s = 0; s < n_slots; ++s) acc = fmaf(a.part_o[((base + s) * r + hr) * kD + c], wslot[s], acc);
+    for (int s = q; s < n_slots; s += NQ) acc = fmaf(a.part_o[((base + s) * r + hr) * kD + c], wslot[s], acc);
     for (int p = c; p < P; p += 128) {
         float wp = 0.f, wo = 0.f;
 #pragma unroll 4
-        for (int s = 0; s < a.splits_prefix; ++s) wp = fmaf(a.part_w[((base + s) * r + hr) * P + p], wslot[s], wp);
+        for (int s = q; s < a.splits_prefix; s += NQ) wp = fmaf(a.part_w[((base + s) * r + hr) * P + p], wslot[s], wp);
 #pragma unroll 4
-        for (int s = a.splits_prefix; s < n_packed; ++s) wo = fmaf(a.part_w[((base + s) * r + hr) * P + p], wslot[s], wo);
-        Wt[0][p] = wp;
-        Wt[1][p] = wo;
+        for (int s = a.splits_prefix + q; s < n_packed; s += NQ) wo = fmaf(a.part_w[((base + s) * r + hr) * P + p], wslot[s], wo);
+        Wq[q][0][p] = wp;
+        Wq[q][1][p] = wo;
     }
     __syncthreads();
-    L = red[0] + red[1];
+    L = red[0];
+#pragma unroll
+    for (int w = 1; w < 2 * NQ; ++w) L += red[w];
+    if (NQ > 1) {
+        for (int i = tid; i < 2 * P; i += 128 * NQ) {
+            const int k = i >= P ? 1 : 0, p = i - k * P;
+            float w = Wq[0][k][p];
+#pragma unroll
+            for (int j = 1; j < NQ; ++j) w += Wq[j][k][p];
+            Wq[0][k][p] = w;
+        }
+        __syncthreads();
+    }
     if (a.splits_prefix > 0) {
         const __half *MV = a.patterns_v + (int64_t)head * P * kD;
 #pragma unroll 8
-        for (int p = 0; p < P; ++p) acc = fmaf(Wt[0][p], h2f(MV[(int64_t)p * kD + c]), acc);
+        for (int p = q; p < P; p += NQ) acc = fmaf(Wq[0][0][p], h2f(MV[(int64_t)p * kD + c]), acc);
     }
     if (a.splits_own > 0) {
         const __half *MV = a.patterns_v + (int64_t)a.sets.set_of(n) * P * kD;
 #pragma unroll 8
-        for (int p = 0; p < P; ++p) acc = fmaf(Wt[1][p], h2f(MV[(int64_t)p * kD + c]), acc);
+        for (int p = q; p < P; p += NQ) acc = fmaf(Wq[0][1][p], h2f(MV[(int64_t)p * kD + c]), acc);
+    }
+    if (NQ > 1) {
+        accq[q][c] = acc;
+        __syncthreads();
+        if (q > 0) return;
+        acc = accq[0][c];
+#pragma unroll
+        for (int j = 1; j < NQ; ++j) acc += accq[j][c];
     }
     a.out[(int64_t)u * kD + c] = L > 0.f ? acc / L : 0.f;
     if (a.lse && c == 0) a.lse[u] = L > 0.f ? (M + log2f(L)) * kLn2 : -INFINITY;
@@ -254,7 +280,12 @@ hipError_t launch_decode(const DecodeArgs &a, hipStream_t s)
     else
         hipLaunchKernelGGL((decode_tail_kernel<8>), dim3(2, N), dim3(256), 0, s, a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    hipLaunchKernelGGL(decode_merge_kernel, dim3(a.n_seq * a.n_q_heads), dim3(128), 0, s, a);
+    // four parts per channel when a thread would otherwise walk many slots or patterns alone and the
+    // (sequence, head) pairs are too few to fill the chip with 128-thread workgroups
+    if (a.splits_prefix + a.splits_own + a.P >= 96 && a.n_seq * a.n_q_heads <= 2048)
+        hipLaunchKernelGGL(decode_merge_kernel<4>, dim3(a.n_seq * a.n_q_heads), dim3(512), 0, s, a);
+    else
+        hipLaunchKernelGGL(decode_merge_kernel<1>, dim3(a.n_seq * a.n_q_heads), dim3(128), 0, s, a);
     return hipGetLastError();
 }
 

@@ -105,54 +105,80 @@ __device__ __forceinline__ void rank_pattern_tile(const uint4 (&xb)[4], const Pa
     }
 }
 
-// One 16-token tile held as B operand xb[4] (K-step s in xb[s]).  Returns, in every lane of column n:
-// best index, best squared distance (from the expanded form, low 8 mantissa bits dropped), ||x||^2 and
-// whether the token needs the exact re-evaluation.
-template <bool TAB_LDS>
-__device__ __forceinline__ void assign_tile_mfma(const uint4 (&xb)[4], const PatternTable &tb, int lane, int &best_i,
-                                                 float &best_v, float &x2, bool &flag)
+// NT 16-token tiles held as B operands xb[j][4] (K-step s in xb[j][s]); every pattern tile read from the table
+// serves all NT of them.  Returns, in every lane of column n, per tile: best index, best squared distance (from
+// the expanded form, low 8 mantissa bits dropped), ||x||^2 and whether the token needs the exact re-evaluation.
+template <bool TAB_LDS, int NT>
+__device__ __forceinline__ void assign_tiles_mfma(const uint4 (&xb)[NT][4], const PatternTable &tb, int lane, int (&best_i)[NT],
+                                                  float (&best_v)[NT], float (&x2)[NT], bool (&flag)[NT])
 {
     const int n = lane & 15, kb = lane >> 4;
-    float xx = 0.f;
+    float xx[NT], hx[NT];
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-        const half2_t *h = reinterpret_cast<const half2_t *>(&xb[s]);
+    for (int j = 0; j < NT; ++j) {
+        float acc = 0.f;
 #pragma unroll
-        for (int k = 0; k < 4; ++k) xx = __builtin_amdgcn_fdot2(h[k], h[k], xx, false);
+        for (int s = 0; s < 4; ++s) {
+            const half2_t *h = reinterpret_cast<const half2_t *>(&xb[j][s]);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) acc = __builtin_amdgcn_fdot2(h[k], h[k], acc, false);
+        }
+        acc += __shfl_xor(acc, 16);
+        acc += __shfl_xor(acc, 32);
+        xx[j] = acc;
+        hx[j] = 0.5f * acc;
     }
-    xx += __shfl_xor(xx, 16);
-    xx += __shfl_xor(xx, 32);
-    const float hx = 0.5f * xx;
 
     // the key's index bits are p0 + i here; the lane's 4*kb is added after the loop (no carries: p0 % 16 == 0)
-    uint32_t k1 = 0xffffffffu, k2 = 0xffffffffu;   // above every key
+    uint32_t k1[NT], k2[NT];
+#pragma unroll
+    for (int j = 0; j < NT; ++j) k1[j] = k2[j] = 0xffffffffu;   // above every key
     const int Pp = pad16(tb.P);
     PatternTile ta, tc;
     load_pattern_tile<TAB_LDS>(tb, 0, n, kb, ta);
     for (int p0 = 0;;) {   // two tiles per round, the next one in flight while the current is ranked
         if (p0 + 16 < Pp) load_pattern_tile<TAB_LDS>(tb, p0 + 16, n, kb, tc);
-        rank_pattern_tile(xb, ta, hx, p0, k1, k2);
+#pragma unroll
+        for (int j = 0; j < NT; ++j) rank_pattern_tile(xb[j], ta, hx[j], p0, k1[j], k2[j]);
         if ((p0 += 16) >= Pp) break;
         if (p0 + 16 < Pp) load_pattern_tile<TAB_LDS>(tb, p0 + 16, n, kb, ta);
-        rank_pattern_tile(xb, tc, hx, p0, k1, k2);
+#pragma unroll
+        for (int j = 0; j < NT; ++j) rank_pattern_tile(xb[j], tc, hx[j], p0, k1[j], k2[j]);
         if ((p0 += 16) >= Pp) break;
     }
-    k1 |= (uint32_t)kb << 2;
-    k2 |= (uint32_t)kb << 2;
-    // merge the four lane groups of the column
 #pragma unroll
-    for (int off = 16; off <= 32; off <<= 1) {
-        const uint32_t o1 = (uint32_t)__shfl_xor((int)k1, off), o2 = (uint32_t)__shfl_xor((int)k2, off);
-        k2 = min(min(k2, o2), max(k1, o1));
-        k1 = min(k1, o1);
+    for (int j = 0; j < NT; ++j) {
+        uint32_t a1 = k1[j] | (uint32_t)kb << 2, a2 = k2[j] | (uint32_t)kb << 2;
+        // merge the four lane groups of the column
+#pragma unroll
+        for (int off = 16; off <= 32; off <<= 1) {
+            const uint32_t o1 = (uint32_t)__shfl_xor((int)a1, off), o2 = (uint32_t)__shfl_xor((int)a2, off);
+            a2 = min(min(a2, o2), max(a1, o1));
+            a1 = min(a1, o1);
+        }
+        best_i[j] = (int)(a1 & 0xffu);
+        best_v[j] = -2.f * __uint_as_float(a1 & 0xffffff00u);
+        const float second = -2.f * __uint_as_float(a2 & 0xffffff00u);
+        x2[j] = xx[j];
+        // accumulation error of e is far below 2^-21 (|x|^2 + |m|^2), the keys drop 8 mantissa bits:
+        // flag with a wide margin.  A single pattern has nothing to be confused with.
+        flag[j] = tb.P > 1 && !(second - best_v[j] > 7.62939453125e-06f * (xx[j] + tb.norm2_max) + 6.103515625e-05f * second);
     }
-    best_i = (int)(k1 & 0xffu);
-    best_v = -2.f * __uint_as_float(k1 & 0xffffff00u);
-    const float second = -2.f * __uint_as_float(k2 & 0xffffff00u);
-    x2 = xx;
-    // accumulation error of e is far below 2^-21 (|x|^2 + |m|^2), the keys drop 8 mantissa bits:
-    // flag with a wide margin.  A single pattern has nothing to be confused with.
-    flag = tb.P > 1 && !(second - best_v > 7.62939453125e-06f * (xx + tb.norm2_max) + 6.103515625e-05f * second);
+}
+
+// One 16-token tile.
+template <bool TAB_LDS>
+__device__ __forceinline__ void assign_tile_mfma(const uint4 (&xb)[4], const PatternTable &tb, int lane, int &best_i,
+                                                 float &best_v, float &x2, bool &flag)
+{
+    int bi[1];
+    float bv[1], xx[1];
+    bool fl[1];
+    assign_tiles_mfma<TAB_LDS, 1>(reinterpret_cast<const uint4 (&)[1][4]>(xb), tb, lane, bi, bv, xx, fl);
+    best_i = bi[0];
+    best_v = bv[0];
+    x2 = xx[0];
+    flag = fl[0];
 }
 
 // Exact re-evaluation of one token by a whole wave: xrow_s = its 128 channels (fp16) in LDS.

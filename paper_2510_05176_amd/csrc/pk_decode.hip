@@ -259,9 +259,9 @@ int decode_chunk(int64_t n_streams, int64_t t_packed_total, int P, int r)
     // aim at one resident round of workgroups (two per CU, 512 on the chip): splits that run side by side take
     // the same time, and a longer split pays the fixed parts once - prologue (q.M_K table, LDS clears), epilogue
     // (merge of the four waves) and the r*P pattern masses and r*128 outputs it writes - so a split holds at
-    // least r*P tokens, one 64-token block per wave at least, and at most 32768 tokens.
+    // least r*P/2 tokens, one 64-token block per wave at least, and at most 32768 tokens.
     int64_t c = (n_streams * t_packed_total + 511) / 512;
-    const int64_t floor_c = (int64_t)r * P;
+    const int64_t floor_c = (int64_t)r * P / 2;
     if (c < floor_c) c = floor_c;
     c = (c + 255) / 256 * 256;
     if (c < 256) c = 256;

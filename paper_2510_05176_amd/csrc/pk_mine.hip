@@ -23,8 +23,8 @@ __global__ __launch_bounds__(256) void mine_init_kernel(MineArgs a)
 }
 
 // Assignment step + partial cluster sums of one chunk of one set.  64*NW threads.
-// The chunk is walked in sub-tiles of 16*NW vectors: every wave assigns 16 of them on the matrix cores and
-// leaves them, with their indices, in an LDS tile.  The cluster sums are a second contraction on the
+// The chunk is walked in sub-tiles of 16*NT*NW vectors: every wave assigns 16*NT of them on the matrix cores
+// (NT tiles per pass over the table) and leaves them, with their indices, in an LDS tile.  The cluster sums are a second contraction on the
 // matrix cores, sums[p][c] += sum_t onehot[p][t] x[t][c].  The NW waves (4, or 8 when the table is large and
 // only one workgroup fits a CU) split the pattern tiles (and, when there are fewer pattern tiles than waves,
 // the 8 channel tiles as well), so each wave forms the one-hot operand of its own pattern rows only and keeps
@@ -34,8 +34,8 @@ __global__ __launch_bounds__(256) void mine_init_kernel(MineArgs a)
 // group's lanes address four to a row.  The one-hot operand is formed in packed fp16 as
 // clamp(1 - (idx_t - p)^2, 0, 1), which is exactly 1 or 0 for integers below 256; products are exact and the
 // accumulation order is fixed by the instruction sequence, so the sums are reproducible.
-// Dynamic LDS: [table pad16(P) rows (TAB_LDS only)] [-norm2/2 pad16(P)] [cnt pad16(P)] [xs 16 NW rows]
-//              [idx 16 NW halves] [xrow NW*kD halves]
+// Dynamic LDS: [table pad16(P) rows (TAB_LDS only)] [-norm2/2 pad16(P)] [cnt pad16(P)] [xs 16 NT NW rows]
+//              [idx 16 NT NW halves] [xrow NW*kD halves]
 constexpr int kMineXs = kD + 16;   // halves per row of the vector tile: 72 words, so the eight rows that 32 lanes
                                    // of a transposing read touch (8 words each) fall on 64 distinct banks
 
@@ -43,8 +43,8 @@ typedef _Float16 half2m __attribute__((ext_vector_type(2)));
 typedef short short4m __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) short4m *lds_short4_ptr;
 
-template <bool TAB_LDS, int NPT, int NW>
-__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NPT <= 4 ? 4 : 2))) void mine_step_kernel(MineArgs a, int chunk)
+template <bool TAB_LDS, int NPT, int NW, int NT>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NT == 1 && NPT <= 4 ? 4 : 2))) void mine_step_kernel(MineArgs a, int chunk)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const int P = a.P;
@@ -52,7 +52,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NPT <= 
     float *norm_s = reinterpret_cast<float *>(smem + (TAB_LDS ? (size_t)pad16(P) * kTabStride * 2 : 0));
     int *cnt = reinterpret_cast<int *>(norm_s + pad16(P));
     __half *xs = reinterpret_cast<__half *>(cnt + pad16(P));
-    constexpr int ST = 16 * NW;          // vectors per sub-tile
+    constexpr int ST = 16 * NT * NW;     // vectors per sub-tile: NT 16-vector tiles per wave
     __half *idx_s = xs + ST * kMineXs;   // pattern index of every vector of the sub-tile, as an fp16 number
     __half *xrow_s = idx_s + ST;
     __shared__ float red_s[NW];
@@ -63,12 +63,15 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NPT <= 
     const __half *xg = a.x + (int64_t)s * a.set_stride + (int64_t)t_begin * kD;
     const __half *Mg = a.patterns + (int64_t)s * P * kD;
 
-    auto load_tile = [&](int sub, uint4 (&xb)[4]) {
-        const int tok = min(sub * ST + wave * 16 + n, n_tok - 1);   // rows past the chunk repeat its last vector
+    auto load_tile = [&](int sub, uint4 (&xb)[NT][4]) {
 #pragma unroll
-        for (int k = 0; k < 4; ++k) xb[k] = *reinterpret_cast<const uint4 *>(xg + (int64_t)tok * kD + 32 * k + 8 * kb);
+        for (int j = 0; j < NT; ++j) {
+            const int tok = min(sub * ST + (wave * NT + j) * 16 + n, n_tok - 1);   // rows past the chunk repeat its last vector
+#pragma unroll
+            for (int k = 0; k < 4; ++k) xb[j][k] = *reinterpret_cast<const uint4 *>(xg + (int64_t)tok * kD + 32 * k + 8 * kb);
+        }
     };
-    uint4 xb[4];
+    uint4 xb[NT][4];
     load_tile(0, xb);
 
     for (int i = tid; i < pad16(P); i += 64 * NW) cnt[i] = 0;
@@ -100,22 +103,25 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NPT <= 
 
     const int n_sub = (n_tok + ST - 1) / ST;
     for (int sub = 0; sub < n_sub; ++sub) {
-        const int tl = wave * 16 + n, tok = sub * ST + tl;
-        int bi;
-        float bv, x2, bd;
-        bool flag;
-        assign_tile_mfma<TAB_LDS>(xb, tb, lane, bi, bv, x2, flag);
-        bd = fmaxf(bv, 0.f);
-        resolve_flagged(xb, flag, xrow_s + wave * kD, tb, Mg, lane, bi, bd);
+        int bi[NT];
+        float bv[NT], x2[NT];
+        bool flag[NT];
+        assign_tiles_mfma<TAB_LDS, NT>(xb, tb, lane, bi, bv, x2, flag);
 #pragma unroll
-        for (int k = 0; k < 4; ++k)   // a row past the chunk is stored as zeros, so it adds nothing to any sum
-            *reinterpret_cast<uint4 *>(xs + tl * kMineXs + 32 * k + 8 * kb) = tok < n_tok ? xb[k] : make_uint4(0u, 0u, 0u, 0u);
-        if (kb == 0) {
-            idx_s[tl] = __float2half_rn((float)bi);   // integers below 2048 are exact
-            if (tok < n_tok) {
-                a.assign[(int64_t)s * a.T + t_begin + tok] = bi;
-                a.best[(int64_t)s * a.T + t_begin + tok] = bd;
-                atomicAdd(&cnt[bi], 1);
+        for (int j = 0; j < NT; ++j) {
+            const int tl = (wave * NT + j) * 16 + n, tok = sub * ST + tl;
+            float bd = fmaxf(bv[j], 0.f);
+            resolve_flagged(xb[j], flag[j], xrow_s + wave * kD, tb, Mg, lane, bi[j], bd);
+#pragma unroll
+            for (int k = 0; k < 4; ++k)   // a row past the chunk is stored as zeros, so it adds nothing to any sum
+                *reinterpret_cast<uint4 *>(xs + tl * kMineXs + 32 * k + 8 * kb) = tok < n_tok ? xb[j][k] : make_uint4(0u, 0u, 0u, 0u);
+            if (kb == 0) {
+                idx_s[tl] = __float2half_rn((float)bi[j]);   // integers below 2048 are exact
+                if (tok < n_tok) {
+                    a.assign[(int64_t)s * a.T + t_begin + tok] = bi[j];
+                    a.best[(int64_t)s * a.T + t_begin + tok] = bd;
+                    atomicAdd(&cnt[bi[j]], 1);
+                }
             }
         }
         if (sub + 1 < n_sub) load_tile(sub + 1, xb);   // in flight during the accumulation
@@ -246,10 +252,10 @@ __global__ __launch_bounds__(256) void window_pattern_kernel(const __half *x, in
     }
 }
 
-size_t step_lds_bytes(int P, int nw, bool tab_lds)
+size_t step_lds_bytes(int P, int nw, int nt, bool tab_lds)
 {
     size_t b = tab_lds ? (size_t)pad16(P) * kTabStride * 2 : 0;
-    b += (size_t)pad16(P) * 4 + (size_t)pad16(P) * 4 + 16 * nw * (size_t)kMineXs * 2 + 16 * nw * 2 + (size_t)nw * kD * 2;
+    b += (size_t)pad16(P) * 4 + (size_t)pad16(P) * 4 + 16 * nw * nt * (size_t)kMineXs * 2 + 16 * nw * nt * 2 + (size_t)nw * kD * 2;
     return (b + 15) / 16 * 16;
 }
 
@@ -275,17 +281,17 @@ int mine_chunk(int T, int n_sets, int P)
 
 int mine_tsplit(int T, int n_sets, int P) { return (T + mine_chunk(T, n_sets, P) - 1) / mine_chunk(T, n_sets, P); }
 
-template <int NPT, int NW>
+template <int NPT, int NW, int NT>
 static hipError_t launch_step(const MineArgs &a, int chunk, size_t lds, hipStream_t s)
 {
-    hipLaunchKernelGGL((mine_step_kernel<true, NPT, NW>), dim3(a.tsplit, a.n_sets), dim3(64 * NW), lds, s, a, chunk);
+    hipLaunchKernelGGL((mine_step_kernel<true, NPT, NW, NT>), dim3(a.tsplit, a.n_sets), dim3(64 * NW), lds, s, a, chunk);
     return hipGetLastError();
 }
 
-template <int NPT, int NW>
+template <int NPT, int NW, int NT>
 static hipError_t prepare_step(const MineArgs &, int, size_t lds, hipStream_t)
 {
-    return hipFuncSetAttribute(reinterpret_cast<const void *>(&mine_step_kernel<true, NPT, NW>),
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(&mine_step_kernel<true, NPT, NW, NT>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
 }
 
@@ -293,13 +299,16 @@ hipError_t launch_mine(const MineArgs &a, hipStream_t s)
 {
     hipError_t e;
     const int chunk = mine_chunk(a.T, a.n_sets, a.P);
-    // pattern tiles held in registers; 8 waves share the table when only one workgroup fits a CU (P > 128;
-    // at 128 patterns two 4-wave workgroups measured faster than one 8-wave group pair)
     const int npt = a.P <= 16 ? 1 : a.P <= 32 ? 2 : a.P <= 64 ? 4 : a.P <= 128 ? 8 : 16;
+    // 8 waves share the table when only one workgroup fits a CU (P > 128; at 128 patterns two 4-wave workgroups
+    // measured faster than one 8-wave group).  From 128 patterns on a wave assigns two 16-vector tiles per
+    // table pass: reading the table out of LDS is what limits the assignment there, and every tile read then
+    // serves 32 vectors (at 64 patterns and below the smaller tile and the higher occupancy win).
+    const int nt = npt >= 8 ? 2 : 1;
     const int nw = a.P > 128 ? 8 : 4;
-    const size_t lds = step_lds_bytes(a.P, nw, true);
+    const size_t lds = step_lds_bytes(a.P, nw, nt, true);
 #define PK_STEP(CALL)                                                                                       \
-    (npt == 1 ? CALL<1, 4> : npt == 2 ? CALL<2, 4> : npt == 4 ? CALL<4, 4> : npt == 8 ? CALL<8, 4> : CALL<16, 8>)
+    (npt == 1 ? CALL<1, 4, 1> : npt == 2 ? CALL<2, 4, 1> : npt == 4 ? CALL<4, 4, 1> : npt == 8 ? CALL<8, 4, 2> : CALL<16, 8, 2>)
     if ((e = PK_STEP(prepare_step)(a, chunk, lds, s)) != hipSuccess) return e;
     if (!a.init_given) {
         hipLaunchKernelGGL(mine_init_kernel, dim3((a.P * kRowChunks + 255) / 256, a.n_sets), dim3(256), 0, s, a);

@@ -481,12 +481,22 @@ __global__ __launch_bounds__(256) void quantize_k_kernel(QuantArgs a, int tiles_
         const int64_t tq0 = (int64_t)a.t0 + (int64_t)tile * TT;
         float r[NT][32];
         int bi[NT];
+        {   // the wave's NT 16-token tiles in one pass over the pattern table
+            float bv[NT], x2[NT];
+            bool flag[NT];
+            assign_tiles_mfma<TAB_LDS, NT>(xb, tb, lane, bi, bv, x2, flag);
+#pragma unroll
+            for (int j = 0; j < NT; ++j) {
+                float bd;
+                // scratch for the exact re-evaluation: the tile's own residual rows, which are written only below
+                resolve_flagged(xb[j], flag[j], reinterpret_cast<__half *>(sh.rt + (wave * NT + j) * 16 * kRStride), tb, Mg, lane,
+                                bi[j], bd);
+            }
+        }
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
             const int tl = (wave * NT + j) * 16 + n;   // token slot inside the tile
-            // scratch for the exact re-evaluation: the tile's own residual rows, which are written only below
-            bi[j] = assign_residuals<TAB_LDS>(sh, tb, Mg, xb[j],
-                                              reinterpret_cast<__half *>(sh.rt + (wave * NT + j) * 16 * kRStride), r[j]);
+            residuals<TAB_LDS>(sh, Mg, xb[j], bi[j], r[j]);
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 float4 *dst = reinterpret_cast<float4 *>(sh.rt + tl * kRStride + 32 * k + 8 * kb);
@@ -571,8 +581,8 @@ static size_t wave_k_lds_bytes(int P, bool tab_lds)
     return (tab_lds ? (size_t)pad16(P) * kTabStride * 2 : 0) + (size_t)pad16(P) * 4 + 16 + 4 * (size_t)kWkWave;
 }
 
-template <int G, int BITS, bool TAB_LDS>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void quantize_k_wave_kernel(QuantArgs a, int tiles_per_wg)
+template <int G, int BITS, bool TAB_LDS, int NTA>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NTA > 2 ? 2 : 3))) void quantize_k_wave_kernel(QuantArgs a, int tiles_per_wg)
 {
     constexpr int NTG = G / 16;
     static_assert(G == 32 || G == 64, "a wave holds the group's tiles in registers");
@@ -613,10 +623,28 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void q
         float mn[4] = {INFINITY, INFINITY, INFINITY, INFINITY}, mx[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
         int bi[NTG];
         const int sc = lane & 31, sth = lane >> 5;
+        if (NTA > 1) {   // NTA tiles of the group per pass over the pattern table
+#pragma unroll
+            for (int j0 = 0; j0 < NTG; j0 += NTA) {
+                float bv[NTA], x2[NTA];
+                bool flag[NTA];
+                int bj[NTA];
+                assign_tiles_mfma<TAB_LDS, NTA>(reinterpret_cast<const uint4 (&)[NTA][4]>(xb[j0]), tb, lane, bj, bv, x2, flag);
+#pragma unroll
+                for (int j = 0; j < NTA; ++j) {
+                    float bd;
+                    resolve_flagged(xb[j0 + j], flag[j], reinterpret_cast<__half *>(rt), tb, Mg, lane, bj[j], bd);
+                    bi[j0 + j] = bj[j];
+                }
+            }
+        }
 #pragma unroll
         for (int j = 0; j < NTG; ++j) {
             float r[32];
-            bi[j] = assign_residuals<TAB_LDS>(sh, tb, Mg, xb[j], reinterpret_cast<__half *>(rt), r);
+            if (NTA > 1)
+                residuals<TAB_LDS>(sh, Mg, xb[j], bi[j], r);
+            else
+                bi[j] = assign_residuals<TAB_LDS>(sh, tb, Mg, xb[j], reinterpret_cast<__half *>(rt), r);
 #pragma unroll
             for (int k = 0; k < 4; ++k) {   // channels 32k .. 32k+31
                 float4 *dst = reinterpret_cast<float4 *>(rt + n * kWkStride + 8 * kb);
@@ -700,8 +728,10 @@ __device__ __forceinline__ uint32_t transpose16(uint32_t x, const TransposeConst
 }
 
 // V: workgroup = 256 threads, blocks of 64 tokens of one stream; wave w owns the 16-token unit w of the
-// block.  NG = channel groups per token (kD / Gc).
-template <int BITS, int NG, bool TAB_LDS>
+// block.  NG = channel groups per token (kD / Gc).  NT = blocks taken together: the wave assigns its units of
+// NT consecutive blocks in one pass over the pattern table (every table tile read from LDS serves all of
+// them), then quantizes them one after the other.
+template <int BITS, int NG, bool TAB_LDS, int NT>
 __global__ __launch_bounds__(256) void quantize_v_kernel(QuantArgs a, int tiles_per_wg)
 {
     constexpr int TT = 64, WPU = BITS / 2, BPG = 4 / NG;   // BPG = 32-channel blocks per group
@@ -712,18 +742,37 @@ __global__ __launch_bounds__(256) void quantize_v_kernel(QuantArgs a, int tiles_
     const __half *Mg = a.patterns + (int64_t)a.sets.set_of(ns) * a.P * kD;
     const int n_tiles = a.nq / TT;
     const int tile0 = blockIdx.x * tiles_per_wg, tile1 = min(n_tiles, tile0 + tiles_per_wg);
-    uint4 xb[4];
-    load_tile(a, ns, tile0 * TT + wave * 16, xb);
+    uint4 xbs[NT][4];
+#pragma unroll
+    for (int j = 0; j < NT; ++j)   // a block past the workgroup's range repeats the last one; its result is not used
+        load_tile(a, ns, min(tile0 + j, tile1 - 1) * TT + wave * 16, xbs[j]);
 
     stage_patterns(Mg, a.P, sh.tab, sh.nh, sh.red, TAB_LDS);
     const PatternTable tb = make_table(sh, Mg, a.P);
     const TransposeConst tc = transpose_const(n);
     unsigned char *wsc = sh.wsc + wave * kWaveScratch;
 
-    for (int tile = tile0; tile < tile1; ++tile) {
+    for (int tile_base = tile0; tile_base < tile1; tile_base += NT) {
+        int bis[NT];
+        {
+            float bv[NT], x2[NT];
+            bool flag[NT];
+            assign_tiles_mfma<TAB_LDS, NT>(xbs, tb, lane, bis, bv, x2, flag);
+#pragma unroll
+            for (int j = 0; j < NT; ++j) {
+                float bd;
+                resolve_flagged(xbs[j], flag[j], reinterpret_cast<__half *>(wsc + kWsRow), tb, Mg, lane, bis[j], bd);
+            }
+        }
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        const int tile = tile_base + j;
+        if (tile >= tile1) break;
+        uint4 (&xb)[4] = xbs[j];
         const int64_t t_first = (int64_t)a.t0 + (int64_t)tile * TT + wave * 16;   // first token of the unit
         float r[32];
-        int bi = assign_residuals<TAB_LDS>(sh, tb, Mg, xb, reinterpret_cast<__half *>(wsc + kWsRow), r);
+        int bi = bis[j];
+        residuals<TAB_LDS>(sh, Mg, xb, bi, r);
         if (a.v_rho > 0.f) {
             // adaptive threshold (Sec. 3.3): keep the pattern iff R_flat <= rho * R_raw, ranges over all d
             // channels of the token: lane-local over its 32 channels, then over the token's 4 lanes
@@ -766,7 +815,7 @@ __global__ __launch_bounds__(256) void quantize_v_kernel(QuantArgs a, int tiles_
                 }
             }
         }
-        if (tile + 1 < tile1) load_tile(a, ns, (tile + 1) * TT + wave * 16, xb);
+        if (tile + NT < tile1) load_tile(a, ns, (tile + NT) * TT + wave * 16, xb);   // else the registers keep this block
 
         // minimum / maximum per channel group: lane-local over its channels, then over the 4 lanes of the token
         float mn[NG], mx[NG];
@@ -844,6 +893,7 @@ __global__ __launch_bounds__(256) void quantize_v_kernel(QuantArgs a, int tiles_
         }
         if (lane == 63) *reinterpret_cast<uint4 *>(a.idx + tok0) = *reinterpret_cast<const uint4 *>(wsc + kWsIdx);
         wave_lds_sync();   // the staging area is rewritten by the next unit
+      }
     }
 }
 
@@ -889,6 +939,10 @@ hipError_t launch_quantize_k(const QuantArgs &a, hipStream_t s)
 {
     if (a.metric == PK_METRIC_L2) {
         const bool tl = a.P <= 256;   // table rows in LDS (74 KB at 256 patterns)
+        // Tiles of a group assigned per pass over the pattern table (every table tile read from LDS serves all of
+        // them): pairs keep three waves per SIMD; the whole 64-token group takes two, which pays above 128
+        // patterns; 32-token groups gain from pairs only once the table is large.
+        const int kmulti = a.G == 64 ? (a.P > 128 ? 4 : 2) : (a.P >= 128 ? 2 : 1);
 #define PK_LAUNCH_K2(GG, BB)                                                                                       \
     if (a.G == GG && a.bits == BB) {                                                                               \
         constexpr int TT = GG == 128 ? 128 : 64;                                                                   \
@@ -898,8 +952,10 @@ hipError_t launch_quantize_k(const QuantArgs &a, hipStream_t s)
 #define PK_LAUNCH_KW(GG, BB)                                                                                       \
     if (a.G == GG && a.bits == BB) {                                                                               \
         /* a wave owns whole groups: at least four groups per workgroup */                                        \
-        return tl ? launch_tiled(quantize_k_wave_kernel<GG, BB, true>, a, 64, wave_k_lds_bytes(a.P, true), s, GG / 16)      \
-                  : launch_tiled(quantize_k_wave_kernel<GG, BB, false>, a, 64, wave_k_lds_bytes(a.P, false), s, GG / 16);   \
+        return !tl ? launch_tiled(quantize_k_wave_kernel<GG, BB, false, 1>, a, 64, wave_k_lds_bytes(a.P, false), s, GG / 16)   \
+               : kmulti == 4 && GG == 64 ? launch_tiled(quantize_k_wave_kernel<GG, BB, true, GG / 16>, a, 64, wave_k_lds_bytes(a.P, true), s, GG / 16) \
+               : kmulti >= 2 ? launch_tiled(quantize_k_wave_kernel<GG, BB, true, 2>, a, 64, wave_k_lds_bytes(a.P, true), s, GG / 16) \
+                        : launch_tiled(quantize_k_wave_kernel<GG, BB, true, 1>, a, 64, wave_k_lds_bytes(a.P, true), s, GG / 16); \
     }
         PK_LAUNCH_KW(32, 2) PK_LAUNCH_KW(64, 2) PK_LAUNCH_K2(128, 2)
         PK_LAUNCH_KW(32, 4) PK_LAUNCH_KW(64, 4) PK_LAUNCH_K2(128, 4)
@@ -925,10 +981,12 @@ hipError_t launch_quantize_v(const QuantArgs &a, hipStream_t s)
         const bool tl = a.P <= 256;   // table rows in LDS (74 KB at 256 patterns)
         const int ng = kD / (a.G < kD ? a.G : kD);
         const size_t lds = tile_lds_bytes(a.P, tl, 0, 1);
+        const bool two = a.P >= 128;   // two blocks per table pass (three waves per SIMD instead of four) pay from 128 patterns on
 #define PK_LAUNCH_V2(BB, NN)                                                                   \
     if (a.bits == BB && ng == NN)                                                              \
-        return tl ? launch_tiled(quantize_v_kernel<BB, NN, true>, a, 64, lds, s)               \
-                  : launch_tiled(quantize_v_kernel<BB, NN, false>, a, 64, lds, s);
+        return !tl ? launch_tiled(quantize_v_kernel<BB, NN, false, 1>, a, 64, lds, s)          \
+               : two ? launch_tiled(quantize_v_kernel<BB, NN, true, 2>, a, 64, lds, s)         \
+                     : launch_tiled(quantize_v_kernel<BB, NN, true, 1>, a, 64, lds, s);
         PK_LAUNCH_V2(2, 1) PK_LAUNCH_V2(2, 2) PK_LAUNCH_V2(2, 4)
         PK_LAUNCH_V2(4, 1) PK_LAUNCH_V2(4, 2) PK_LAUNCH_V2(4, 4)
 #undef PK_LAUNCH_V2

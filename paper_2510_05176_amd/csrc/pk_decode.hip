@@ -20,14 +20,16 @@ constexpr float kLn2 = 0.6931471805599453f;
 
 template <int RP>
 struct TailShared {
-    float q[RP][kD];
-    float ps[kTile][RP];        // scores, then softmax numerators of the tile
-    float half_acc[kTile][RP];  // second channel half's partial dot products; later output halves
+    float ps[kTile][RP];      // scores, then softmax numerators of the tile
     float mt[RP];
     float red[RP][2];
+    float osum[4][RP][kD];    // output partials of the four waves
 };
 
 // fp16 tail of one stream (own cache or shared prefix): plain q.k / softmax / p.v, 256 threads.
+// Thread (cg, tg) = (tid % 16, tid / 16) owns channels 8cg .. 8cg+7 of the tokens tg, tg+16, ... of a tile, in
+// the score phase and in the value phase alike: the 16 lanes of a token read its 256-byte row in 16-byte
+// pieces, scores are summed over those lanes, outputs over the token groups at the end.
 template <int RP>
 __global__ __launch_bounds__(256) void decode_tail_kernel(DecodeArgs a)
 {
@@ -40,53 +42,59 @@ __global__ __launch_bounds__(256) void decode_tail_kernel(DecodeArgs a)
     const int cstream = which == 0 ? n : head;
     const int slot = n_slots - 2 + which;
     const int t_end = cv.t_tail;
+    const int cg = tid & 15, tg = tid >> 4, lane = tid & 63, wave = tid >> 6;
 
-    for (int i = tid; i < RP * kD; i += 256) {
-        const int h = i / kD, c = i - h * kD;
-        sh.q[h][c] = h < r ? h2f(a.q[((int64_t)seq * a.n_q_heads + head * r + h) * kD + c]) : 0.f;
+    float qr[RP][8];
+#pragma unroll
+    for (int h = 0; h < RP; ++h) {
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (h < r) v = *reinterpret_cast<const uint4 *>(a.q + ((int64_t)seq * a.n_q_heads + head * r + h) * kD + 8 * cg);
+        const __half2 *h2 = reinterpret_cast<const __half2 *>(&v);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            qr[h][2 * k] = __low2float(h2[k]);
+            qr[h][2 * k + 1] = __high2float(h2[k]);
+        }
     }
-    float m_run[RP], l_thr[RP], o[RP];
+    float m_run[RP], l_thr[RP], acc[RP][8];
 #pragma unroll
     for (int h = 0; h < RP; ++h) {
         m_run[h] = -INFINITY;
         l_thr[h] = 0.f;
-        o[h] = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[h][e] = 0.f;
     }
-    const int tt = tid & (kTile - 1), hf = tid >> 7;   // K phase: token slot, channel half; V phase: channel, token half
+    const __half *tail_k = cv.tail_k + (int64_t)cstream * cv.ring_len * kD + 8 * cg;
+    const __half *tail_v = cv.tail_v + (int64_t)cstream * cv.ring_len * kD + 8 * cg;
 
     for (int t0 = 0; t0 < t_end; t0 += kTile) {
         const int n_valid = min(kTile, t_end - t0);
-        __syncthreads();
-        // ---- scores: thread (token slot tt, channel half hf)
-        float acc[RP];
+        __syncthreads();   // the previous tile's numerators have been used
+        // ---- scores
 #pragma unroll
-        for (int h = 0; h < RP; ++h) acc[h] = 0.f;
-        const bool valid = tt < n_valid;
-        if (valid) {
-            int slotk = cv.tail_start + t0 + tt;
-            if (slotk >= cv.ring_len) slotk -= cv.ring_len;
-            const __half *krow = cv.tail_k + ((int64_t)cstream * cv.ring_len + slotk) * kD + hf * 64;
+        for (int i = 0; i < kTile / 16; ++i) {
+            const int tk = tg + 16 * i;
+            const bool valid = tk < n_valid;
+            uint4 v = make_uint4(0u, 0u, 0u, 0u);
+            int rs = cv.tail_start + t0 + tk;   // ring slot: one wrap at most, since t0 + tk < t_tail <= ring_len
+            if (rs >= cv.ring_len) rs -= cv.ring_len;
+            if (valid) v = *reinterpret_cast<const uint4 *>(tail_k + (int64_t)rs * kD);
+            const __half2 *h2 = reinterpret_cast<const __half2 *>(&v);
+            float kf[8];
 #pragma unroll
-            for (int c8 = 0; c8 < 64; c8 += 8) {
-                const uint4 v = *reinterpret_cast<const uint4 *>(krow + c8);
-                const __half2 *h2 = reinterpret_cast<const __half2 *>(&v);
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const float k0 = __low2float(h2[k]), k1 = __high2float(h2[k]);
-                    const int c = hf * 64 + c8 + 2 * k;
-#pragma unroll
-                    for (int h = 0; h < RP; ++h) acc[h] = fmaf(sh.q[h][c], k0, fmaf(sh.q[h][c + 1], k1, acc[h]));
-                }
+            for (int k = 0; k < 4; ++k) {
+                kf[2 * k] = __low2float(h2[k]);
+                kf[2 * k + 1] = __high2float(h2[k]);
             }
-        }
-        if (hf == 1) {
 #pragma unroll
-            for (int h = 0; h < RP; ++h) sh.half_acc[tt][h] = acc[h];
-        }
-        __syncthreads();
-        if (hf == 0 && valid) {
+            for (int h = 0; h < RP; ++h) {
+                float sdot = 0.f;
 #pragma unroll
-            for (int h = 0; h < RP; ++h) sh.ps[tt][h] = (acc[h] + sh.half_acc[tt][h]) * a.softmax_scale;
+                for (int e = 0; e < 8; ++e) sdot = fmaf(qr[h][e], kf[e], sdot);
+#pragma unroll
+                for (int off = 1; off < 16; off <<= 1) sdot += __shfl_xor(sdot, off);
+                if (cg == 0 && valid) sh.ps[tk][h] = sdot * a.softmax_scale;
+            }
         }
         __syncthreads();
         if (tid < 64) {   // wave 0: tile maximum per head
@@ -101,56 +109,70 @@ __global__ __launch_bounds__(256) void decode_tail_kernel(DecodeArgs a)
             }
         }
         __syncthreads();
-        // ---- online softmax update
-        float pr[RP];
+        // ---- online softmax update; thread t < 128 turns the scores of token t into numerators
 #pragma unroll
         for (int h = 0; h < RP; ++h) {
             const float m_new = fmaxf(m_run[h], sh.mt[h]);
             const float alpha = m_run[h] == -INFINITY ? 0.f : __expf(m_run[h] - m_new);
             m_run[h] = m_new;
-            o[h] *= alpha;
-            pr[h] = (hf == 0 && valid) ? __expf(sh.ps[tt][h] - m_new) : 0.f;
-            l_thr[h] = l_thr[h] * alpha + pr[h];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[h][e] *= alpha;
+            float pr = 0.f;
+            if (tid < n_valid) {   // n_valid <= 128
+                pr = __expf(sh.ps[tid][h] - m_new);
+                sh.ps[tid][h] = pr;
+            }
+            l_thr[h] = l_thr[h] * alpha + pr;
         }
         __syncthreads();
-        if (hf == 0) {
+        // ---- values
 #pragma unroll
-            for (int h = 0; h < RP; ++h) sh.ps[tt][h] = pr[h];
-        }
-        __syncthreads();
-        // ---- values: thread (channel c, token half hf)
-        const int c = tt;
-        const int tk_end = min(n_valid, hf * 64 + 64);
-        for (int tk = hf * 64; tk < tk_end; ++tk) {
-            int slotv = cv.tail_start + t0 + tk;
-            if (slotv >= cv.ring_len) slotv -= cv.ring_len;
-            const float v = h2f(cv.tail_v[((int64_t)cstream * cv.ring_len + slotv) * kD + c]);
+        for (int i = 0; i < kTile / 16; ++i) {
+            const int tk = tg + 16 * i;
+            if (tk < n_valid) {
+                int rs = cv.tail_start + t0 + tk;
+                if (rs >= cv.ring_len) rs -= cv.ring_len;
+                const uint4 v = *reinterpret_cast<const uint4 *>(tail_v + (int64_t)rs * kD);
+                const __half2 *h2 = reinterpret_cast<const __half2 *>(&v);
+                float vf[8];
 #pragma unroll
-            for (int h = 0; h < RP; ++h) o[h] = fmaf(sh.ps[tk][h], v, o[h]);
+                for (int k = 0; k < 4; ++k) {
+                    vf[2 * k] = __low2float(h2[k]);
+                    vf[2 * k + 1] = __high2float(h2[k]);
+                }
+#pragma unroll
+                for (int h = 0; h < RP; ++h) {
+                    const float pw = sh.ps[tk][h];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) acc[h][e] = fmaf(pw, vf[e], acc[h][e]);
+                }
+            }
         }
     }
 
-    __syncthreads();
-    const int c = tt;
-    if (hf == 1) {
+    // ---- outputs: the four token groups of a wave by shuffles, the four waves through LDS
 #pragma unroll
-        for (int h = 0; h < RP; ++h) sh.half_acc[c][h] = o[h];
-    } else {
+    for (int h = 0; h < RP; ++h) {
 #pragma unroll
-        for (int h = 0; h < RP; ++h) {
-            float l = l_thr[h];
-#pragma unroll
-            for (int off = 32; off > 0; off >>= 1) l += __shfl_xor(l, off);
-            if ((tid & 63) == 0) sh.red[h][tid >> 6] = l;
+        for (int e = 0; e < 8; ++e) {
+            float v = acc[h][e];
+            v += __shfl_xor(v, 16);
+            v += __shfl_xor(v, 32);
+            if (lane < 16) sh.osum[wave][h][8 * cg + e] = v;
         }
+        float l = l_thr[h];   // nonzero in threads 0..127 only
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) l += __shfl_xor(l, off);
+        if (lane == 0 && wave < 2) sh.red[h][wave] = l;
     }
     __syncthreads();
-    if (hf == 0) {
+    if (tid < kD) {
+        const int c = tid;
         const int64_t pbase = ((int64_t)n * n_slots + slot) * r;
 #pragma unroll
         for (int h = 0; h < RP; ++h) {
             if (h < r) {
-                a.part_o[(pbase + h) * kD + c] = o[h] + sh.half_acc[c][h];
+                a.part_o[(pbase + h) * kD + c] = (sh.osum[0][h][c] + sh.osum[1][h][c]) + (sh.osum[2][h][c] + sh.osum[3][h][c]);
                 if (c == 0) {
                     a.part_ml[(pbase + h) * 2] = m_run[h] * kLog2e;   // partials carry the maximum in the log2 domain
                     a.part_ml[(pbase + h) * 2 + 1] = sh.red[h][0] + sh.red[h][1];

@@ -199,8 +199,10 @@ __global__ __launch_bounds__(128 * NQ) void decode_merge_kernel(DecodeArgs a)
     const int r = a.n_q_heads / a.n_kv_heads, P = a.P;
     const int head = qh / r, hr = qh - head * r;
     const int n = seq * a.n_kv_heads + head;
-    const int n_packed = a.splits_prefix + a.splits_own, n_slots = n_packed + 2;
-    const int64_t base = (int64_t)n * n_slots;
+    const int n_packed = a.splits_prefix + a.splits_own;
+    const int64_t base = (int64_t)n * (n_packed + 2);
+    // the two tail slots are written (and read here) only when there is a tail at all
+    const int n_slots = (a.own.t_tail > 0 || a.prefix.t_tail > 0) ? n_packed + 2 : n_packed;
     // maximum over the slots that hold anything
     float M = -INFINITY;
     for (int s = tid; s < n_slots; s += 128 * NQ) {
@@ -297,11 +299,13 @@ hipError_t launch_decode(const DecodeArgs &a, hipStream_t s)
     const int N = a.n_seq * a.n_kv_heads;
     hipError_t e;
     if ((e = launch_decode_packed(a, s)) != hipSuccess) return e;
-    if (r <= 4)
-        hipLaunchKernelGGL((decode_tail_kernel<4>), dim3(2, N), dim3(256), 0, s, a);
-    else
-        hipLaunchKernelGGL((decode_tail_kernel<8>), dim3(2, N), dim3(256), 0, s, a);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (a.own.t_tail > 0 || a.prefix.t_tail > 0) {
+        if (r <= 4)
+            hipLaunchKernelGGL((decode_tail_kernel<4>), dim3(2, N), dim3(256), 0, s, a);
+        else
+            hipLaunchKernelGGL((decode_tail_kernel<8>), dim3(2, N), dim3(256), 0, s, a);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
     // four parts per channel when a thread would otherwise walk many slots or patterns alone and the
     // (sequence, head) pairs are too few to fill the chip with 128-thread workgroups
     if (a.splits_prefix + a.splits_own + a.P >= 96 && a.n_seq * a.n_q_heads <= 2048)

@@ -91,6 +91,24 @@ def test_config3_long_context_batched_decode(oracle, pk):
         check_stream(oracle, pk, gc, gcfg, kw, K, V, Mk, Mv, q, out, seq, head, [T], max_near_ties=40)
 
 
+def test_odd_tile_count_per_workgroup(oracle, pk):
+    """64 streams x 2560 tokens at P=128: the quantize launches give every workgroup three 64-token blocks, so the
+    kernels that take two blocks (V) or a pair of tiles (K) per pass over the pattern table end on a lone one."""
+    Hkv, Hq, T, d, P, n_seq = 8, 32, 2560, 128, 128, 8
+    kw = dict(n_seq=n_seq, n_kv_heads=Hkv, n_q_heads=Hq, head_dim=d, n_patterns=P, seqs_per_set=n_seq, bits=2, group=64,
+              recent=0, flush=64, t_capacity=T, metric=0)
+    gcfg = pk.Config(**kw)
+    K, V = synth.make_layer_device(7, 0, synth.KVSpec(1, n_seq, Hkv, Hq, T, d, 48), "cuda")
+    Mk, Mv = first_vectors(K, P, n_seq), first_vectors(V, P, n_seq)
+    q = dev(synth.make_queries(7, n_seq, Hq, d))
+    gc = pk.Cache(gcfg)
+    pk.pk_quantize_append(gcfg, gc, K, V, Mk, Mv)
+    out = pk.pk_decode_attention(gcfg, gc, q, d ** -0.5, Mk, Mv)
+    torch.cuda.synchronize()
+    for seq, head in [(0, 0), (3, 5), (n_seq - 1, Hkv - 1)]:
+        check_stream(oracle, pk, gc, gcfg, kw, K, V, Mk, Mv, q, out, seq, head, [T], max_near_ties=10)
+
+
 def test_config5_large_pattern_stress(oracle, pk):
     """Config 5 whole: T=131072, 4 KV / 28 query heads, P=256, 2 bits, group 128."""
     spec = synth.SPECS["cfg5"]

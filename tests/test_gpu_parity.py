@@ -132,6 +132,7 @@ def rel_l2(a, b):
 
 @pytest.mark.parametrize("bits,G,P,metric", [
     (2, 64, 16, 0), (4, 32, 16, 0), (2, 128, 64, 0), (4, 64, 33, 0), (2, 32, 1, 0), (2, 64, 256, 0),
+    (2, 32, 200, 0), (4, 64, 128, 0), (2, 128, 130, 0),     # large tables: several tiles per pass over the table
     (2, 64, 16, 1), (4, 128, 40, 1), (2, 32, 7, 1),
 ])
 def test_quantize_append_parity(oracle, pk, bits, G, P, metric):

@@ -246,7 +246,7 @@ def main():
     quant_bytes = N * (cap * (2 * d * 2 + packed_per_tok) + (T - cap) * 2 * d * 2 * 2)   # tail: read + write
     dec_bytes = N * (cap * packed_per_tok + (T - cap) * 2 * d * 2 + 2 * P * d * 2) + n_seq * Hq * d * (2 + 4)
     mine_flops = 2.0 * T * P * d * (2 * L * Hkv) * iters
-    mine_bytes = 2.0 * L * Hkv * iters * T * (d * 2 + 8)      # per Lloyd iteration: one pass over x, index + distance out
+    mine_bytes = 2.0 * L * Hkv * iters * T * d * 2            # per Lloyd iteration: one pass over x
 
     # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE, scaled by a copy of known
     # size): written by profiles/collect_traffic.py from runs of this script, read back here

@@ -189,7 +189,7 @@ pk_status pk_mine_patterns(const pk_config *cfg, const void *x, int64_t set_stri
     a.iters = iters;
     a.init_given = init_given;
     a.patterns = static_cast<__half *>(patterns);
-    a.assign = assign ? assign : reinterpret_cast<int32_t *>(ws + mc.assign);
+    a.assign = assign;   // optional: written by the last step only
     a.best = reinterpret_cast<float *>(ws + mc.best);
     a.psum = reinterpret_cast<float *>(ws + mc.psum);
     a.pcnt = reinterpret_cast<int32_t *>(ws + mc.pcnt);

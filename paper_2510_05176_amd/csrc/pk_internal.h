@@ -109,8 +109,8 @@ struct MineArgs {
     int64_t set_stride;
     int32_t n_sets, T, P, iters, init_given;
     __half *patterns;
-    int32_t *assign;       // [n_sets][T] (workspace or caller's)
-    float *best;           // [n_sets][T] workspace
+    int32_t *assign;       // [n_sets][T] caller's, or null
+    float *best;           // [n_sets][T] workspace (written when inertia is asked for)
     float *psum;           // [n_sets][tsplit][P][kD]
     int32_t *pcnt;         // [n_sets][tsplit][P]
     float *inertia;        // optional [n_sets][iters]

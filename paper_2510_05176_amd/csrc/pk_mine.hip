@@ -44,7 +44,7 @@ typedef short short4m __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) short4m *lds_short4_ptr;
 
 template <bool TAB_LDS, int NPT, int NW, int NT>
-__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NT == 1 && NPT <= 4 ? 4 : 2))) void mine_step_kernel(MineArgs a, int chunk)
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NT == 1 && NPT <= 4 ? 4 : 2))) void mine_step_kernel(MineArgs a, int chunk, int outputs)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const int P = a.P;
@@ -118,8 +118,10 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NT == 1
             if (kb == 0) {
                 idx_s[tl] = __float2half_rn((float)bi[j]);   // integers below 2048 are exact
                 if (tok < n_tok) {
-                    a.assign[(int64_t)s * a.T + t_begin + tok] = bi[j];
-                    a.best[(int64_t)s * a.T + t_begin + tok] = bd;
+                    // per-vector outputs only where somebody reads them: indices from the last step (if asked
+                    // for), distances when the objective is reported
+                    if (outputs & 1) a.assign[(int64_t)s * a.T + t_begin + tok] = bi[j];
+                    if (outputs & 2) a.best[(int64_t)s * a.T + t_begin + tok] = bd;
                     atomicAdd(&cnt[bi[j]], 1);
                 }
             }
@@ -282,14 +284,14 @@ int mine_chunk(int T, int n_sets, int P)
 int mine_tsplit(int T, int n_sets, int P) { return (T + mine_chunk(T, n_sets, P) - 1) / mine_chunk(T, n_sets, P); }
 
 template <int NPT, int NW, int NT>
-static hipError_t launch_step(const MineArgs &a, int chunk, size_t lds, hipStream_t s)
+static hipError_t launch_step(const MineArgs &a, int chunk, size_t lds, hipStream_t s, int outputs)
 {
-    hipLaunchKernelGGL((mine_step_kernel<true, NPT, NW, NT>), dim3(a.tsplit, a.n_sets), dim3(64 * NW), lds, s, a, chunk);
+    hipLaunchKernelGGL((mine_step_kernel<true, NPT, NW, NT>), dim3(a.tsplit, a.n_sets), dim3(64 * NW), lds, s, a, chunk, outputs);
     return hipGetLastError();
 }
 
 template <int NPT, int NW, int NT>
-static hipError_t prepare_step(const MineArgs &, int, size_t lds, hipStream_t)
+static hipError_t prepare_step(const MineArgs &, int, size_t lds, hipStream_t, int)
 {
     return hipFuncSetAttribute(reinterpret_cast<const void *>(&mine_step_kernel<true, NPT, NW, NT>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -309,13 +311,14 @@ hipError_t launch_mine(const MineArgs &a, hipStream_t s)
     const size_t lds = step_lds_bytes(a.P, nw, nt, true);
 #define PK_STEP(CALL)                                                                                       \
     (npt == 1 ? CALL<1, 4, 1> : npt == 2 ? CALL<2, 4, 1> : npt == 4 ? CALL<4, 4, 1> : npt == 8 ? CALL<8, 4, 2> : CALL<16, 8, 2>)
-    if ((e = PK_STEP(prepare_step)(a, chunk, lds, s)) != hipSuccess) return e;
+    if ((e = PK_STEP(prepare_step)(a, chunk, lds, s, 0)) != hipSuccess) return e;
     if (!a.init_given) {
         hipLaunchKernelGGL(mine_init_kernel, dim3((a.P * kRowChunks + 255) / 256, a.n_sets), dim3(256), 0, s, a);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     for (int it = 0; it < a.iters; ++it) {
-        if ((e = PK_STEP(launch_step)(a, chunk, lds, s)) != hipSuccess) return e;
+        const int outputs = (a.assign && it == a.iters - 1 ? 1 : 0) | (a.inertia ? 2 : 0);
+        if ((e = PK_STEP(launch_step)(a, chunk, lds, s, outputs)) != hipSuccess) return e;
         if (a.inertia) {
             hipLaunchKernelGGL(mine_inertia_kernel, dim3(a.n_sets), dim3(256), 0, s, a, it);
             if ((e = hipGetLastError()) != hipSuccess) return e;

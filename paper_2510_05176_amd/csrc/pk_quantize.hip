@@ -752,6 +752,29 @@ __global__ __launch_bounds__(256) void quantize_v_kernel(QuantArgs a, int tiles_
     const TransposeConst tc = transpose_const(n);
     unsigned char *wsc = sh.wsc + wave * kWaveScratch;
 
+    // Contiguous stores of a finished unit (code words, parameters, indices) out of the wave's staging area.
+    // They are issued at the start of the NEXT unit, after that unit's vectors have arrived and before the
+    // loads for the one after are issued: the wait for those loads at the top of a round would otherwise also
+    // wait for stores issued just before it (loads and stores retire through one in-order counter).
+    int64_t pend_tok0 = -1;
+    auto store_pending = [&]() {
+        if (pend_tok0 < 0) return;
+        const int64_t tok0 = pend_tok0;
+        const uint32_t *stg = reinterpret_cast<const uint32_t *>(wsc + kWsCodes);
+        if (BITS == 2)
+            reinterpret_cast<uint2 *>(a.codes_v + tok0 * (kD * BITS / 8))[lane] = reinterpret_cast<const uint2 *>(stg)[lane];
+        else
+            reinterpret_cast<uint4 *>(a.codes_v + tok0 * (kD * BITS / 8))[lane] = reinterpret_cast<const uint4 *>(stg)[lane];
+        if (lane < 4 * NG) {   // NG*32 bytes per array = 2*NG pieces of 16 bytes; scales first, then zero points
+            const int arr = lane / (2 * NG), piece = lane % (2 * NG);
+            const uint4 v = *reinterpret_cast<const uint4 *>(wsc + (arr ? kWsZero : kWsScale) + piece * 16);
+            *reinterpret_cast<uint4 *>((arr ? a.zero : a.scale) + tok0 * NG + piece * 8) = v;
+        }
+        if (lane == 63) *reinterpret_cast<uint4 *>(a.idx + tok0) = *reinterpret_cast<const uint4 *>(wsc + kWsIdx);
+        wave_lds_sync();   // the staging area is rewritten by the unit that follows
+        pend_tok0 = -1;
+    };
+
     for (int tile_base = tile0; tile_base < tile1; tile_base += NT) {
         int bis[NT];
         {
@@ -772,6 +795,7 @@ __global__ __launch_bounds__(256) void quantize_v_kernel(QuantArgs a, int tiles_
         const int64_t t_first = (int64_t)a.t0 + (int64_t)tile * TT + wave * 16;   // first token of the unit
         float r[32];
         int bi = bis[j];
+        store_pending();
         residuals<TAB_LDS>(sh, Mg, xb, bi, r);
         if (a.v_rho > 0.f) {
             // adaptive threshold (Sec. 3.3): keep the pattern iff R_flat <= rho * R_raw, ranges over all d
@@ -880,21 +904,10 @@ __global__ __launch_bounds__(256) void quantize_v_kernel(QuantArgs a, int tiles_
             }
         }
         wave_lds_sync();
-        // contiguous stores: code words of the unit, its parameters, its indices
-        const int64_t tok0 = (int64_t)ns * a.t_capacity + t_first;
-        if (BITS == 2)
-            reinterpret_cast<uint2 *>(a.codes_v + tok0 * (kD * BITS / 8))[lane] = reinterpret_cast<const uint2 *>(stg)[lane];
-        else
-            reinterpret_cast<uint4 *>(a.codes_v + tok0 * (kD * BITS / 8))[lane] = reinterpret_cast<const uint4 *>(stg)[lane];
-        if (lane < 4 * NG) {   // NG*32 bytes per array = 2*NG pieces of 16 bytes; scales first, then zero points
-            const int arr = lane / (2 * NG), piece = lane % (2 * NG);
-            const uint4 v = *reinterpret_cast<const uint4 *>(wsc + (arr ? kWsZero : kWsScale) + piece * 16);
-            *reinterpret_cast<uint4 *>((arr ? a.zero : a.scale) + tok0 * NG + piece * 8) = v;
-        }
-        if (lane == 63) *reinterpret_cast<uint4 *>(a.idx + tok0) = *reinterpret_cast<const uint4 *>(wsc + kWsIdx);
-        wave_lds_sync();   // the staging area is rewritten by the next unit
+        pend_tok0 = (int64_t)ns * a.t_capacity + t_first;   // stored at the start of the next unit
       }
     }
+    store_pending();
 }
 
 // ---------------------------------------------------------------------------

@@ -376,3 +376,18 @@ def decode_attention(cache: Cache, q_u16, patterns_k, patterns_v, softmax_scale,
         K = np.concatenate([pk, K], axis=2)
         V = np.concatenate([pv, V], axis=2)
     return attend(q_u16, K, V, softmax_scale)
+
+
+def decode_attention_ragged(caches, q_u16, patterns_k, patterns_v, softmax_scale,
+                            prefix: Cache | None = None, prefix_patterns_k=None, prefix_patterns_v=None):
+    """A batch whose sequences are filled to different lengths.  The attention of Sec. 3.4 is defined per
+    sequence, so this is decode_attention applied to every sequence on its own: caches[i] is sequence i's cache
+    (n_seq == 1, one pattern set per KV head), q_u16[i] its query heads."""
+    outs, lses = [], []
+    for i, c in enumerate(caches):
+        assert c.cfg.n_seq == 1
+        o, l = decode_attention(c, q_u16[i:i + 1], patterns_k, patterns_v, softmax_scale, prefix=prefix,
+                                prefix_patterns_k=prefix_patterns_k, prefix_patterns_v=prefix_patterns_v)
+        outs.append(o)
+        lses.append(l)
+    return np.concatenate(outs), np.concatenate(lses)

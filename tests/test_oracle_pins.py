@@ -621,3 +621,44 @@ def test_attention_shared_prefix_equals_concatenation(oracle):
     both = oracle.Cache(cfg_own); both.append(K2.view(np.uint16), V2.view(np.uint16), M_k, M_v)
     ref, _ = oracle.decode_attention(both, q.view(np.uint16), M_k, M_v, 128 ** -0.5)
     assert np.allclose(out, ref, rtol=1e-6, atol=1e-7)
+
+
+def test_ragged_batch_is_attention_per_sequence(oracle):
+    """A batch of sequences filled to different lengths: equal lengths give the uniform batch's result, and a
+    sequence's rows are the plain softmax attention over exactly its own vectors (tail-only sequences, so the
+    reference needs no quantizer), whatever the other sequences hold."""
+    spec = synth.KVSpec(1, 3, 2, 4, 200, 128, 8)
+    K, V = synth.make_kv(23, spec)
+    M_k, _, _, _ = oracle.mine(K[0].view(np.uint16), 8, 2)
+    M_v, _, _, _ = oracle.mine(V[0].view(np.uint16), 8, 2)
+    q = synth.make_queries(23, 3, 4, 128)
+    one = _cfg(oracle, recent=32, flush=64, n_seq=1)
+    # equal lengths == the uniform batch
+    uni = oracle.Cache(_cfg(oracle, recent=32, flush=64, n_seq=3))
+    uni.append(K.view(np.uint16), V.view(np.uint16), M_k, M_v)
+    per = []
+    for i in range(3):
+        c = oracle.Cache(one); c.append(K[i:i + 1].view(np.uint16), V[i:i + 1].view(np.uint16), M_k, M_v); per.append(c)
+    ref, ref_lse = oracle.decode_attention(uni, q.view(np.uint16), M_k, M_v, 128 ** -0.5)
+    out, lse = oracle.decode_attention_ragged(per, q.view(np.uint16), M_k, M_v, 128 ** -0.5)
+    assert np.array_equal(out, ref) and np.array_equal(lse, ref_lse)
+    # different lengths, short enough to stay in the fp16 tail: plain attention over each sequence's own vectors
+    lens = [0, 17, 90]
+    per = []
+    for i, n in enumerate(lens):
+        c = oracle.Cache(_cfg(oracle, recent=128, flush=64, n_seq=1))
+        if n:
+            c.append(K[i:i + 1, :, :n].view(np.uint16), V[i:i + 1, :, :n].view(np.uint16), M_k, M_v)
+        assert c.t_quant == 0 and c.t_tail == n
+        per.append(c)
+    out, lse = oracle.decode_attention_ragged(per, q.view(np.uint16), M_k, M_v, 128 ** -0.5)
+    assert np.all(out[0] == 0) and np.all(np.isneginf(lse[0]))
+    Qd = q.astype(np.float64)
+    for i, n in enumerate(lens):
+        for h in range(4):
+            if n == 0:
+                continue
+            sc = K[i, h // 2, :n].astype(np.float64) @ Qd[i, h] * 128 ** -0.5
+            p = np.exp(sc - sc.max()); p /= p.sum()
+            assert np.allclose(out[i, h], p @ V[i, h // 2, :n].astype(np.float64), rtol=1e-6, atol=1e-7)
+            assert abs(lse[i, h] - (sc.max() + np.log(np.exp(sc - sc.max()).sum()))) < 1e-5

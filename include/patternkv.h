@@ -11,6 +11,7 @@
  *                         K quantized per channel and V per token (Sec. 4.1)
  *   pk_decode_attention   Sec. 3.4 "Decode-stage KV reconstruction": attention
  *                         computed directly on the packed cache
+ *   pk_decode_attention_ragged  the same over sequences filled to different lengths
  *   pk_window_pattern     Sec. 3.1 "Decoding Stage", Eq. 5: the pattern of a window of
  *                         vectors (per-channel Chebyshev centre)
  *   pk_dequantize         the reconstruction rule below Eq. 6 (debug / parity)
@@ -77,7 +78,7 @@
 extern "C" {
 #endif
 
-#define PK_ABI_VERSION 2u
+#define PK_ABI_VERSION 3u
 
 typedef enum {
     PK_OK = 0,
@@ -225,6 +226,29 @@ pk_status pk_decode_attention(const pk_config *cfg, const pk_cache *cache, const
                               const pk_state *prefix_state, const void *q, float softmax_scale,
                               const void *patterns_k, const void *patterns_v, float *out, float *lse,
                               void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * The same decode step for a batch whose sequences are filled to different lengths (the long-context and
+ * test-time-scaling workloads of Sec. 4 batch requests whose prompts and generations differ in length;
+ * Sec. 3.4's computation is per sequence and unchanged).  The caller fills each sequence through a cache
+ * view of its own (the cache arrays are laid out stream by stream, so the part of sequence i is a cache with
+ * n_seq == 1 whose pointers are offset by i times the per-sequence size) and keeps one pk_state per sequence.
+ *   bound       host: t_quant and t_tail no smaller than any sequence's (t_quant a multiple of flush, both
+ *               within what check of a uniform state allows), tail_start 0.  Launch sizes and the workspace
+ *               (pk_workspace_bytes with these bounds) follow the bound.
+ *   seq_states  DEVICE, int32 [n_seq][4], 16-byte aligned: t_quant, t_tail, tail_start of every sequence's
+ *               own cache and one unused word.  Read by the kernels at run time, so the host cannot check the
+ *               values: an entry is clamped to [0, bound] (t_quant to whole 64-token blocks, tail_start to
+ *               the ring) before use, which keeps every access inside the cache whatever the array holds.
+ * Everything else as pk_decode_attention (the shared prefix, if any, is uniform).  A sequence of length 0
+ * yields out = 0 and lse = -inf.  Errors before any launch: as pk_decode_attention; seq_states or bound NULL
+ * -> PK_ERR_INVALID_ARG; seq_states misaligned -> PK_ERR_ALIGNMENT; bound->tail_start != 0 -> PK_ERR_STATE.
+ */
+pk_status pk_decode_attention_ragged(const pk_config *cfg, const pk_cache *cache, const pk_state *bound,
+                                     const int32_t *seq_states, const pk_config *prefix_cfg, const pk_cache *prefix,
+                                     const pk_state *prefix_state, const void *q, float softmax_scale,
+                                     const void *patterns_k, const void *patterns_v, float *out, float *lse,
+                                     void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Decode-stage pattern update (Sec. 3.1 "Decoding Stage", Eq. 5): for each of n_sets windows of n

@@ -285,10 +285,10 @@ pk_status pk_quantize_append(const pk_config *cfg, const pk_cache *cache, pk_sta
     return PK_OK;
 }
 
-pk_status pk_decode_attention(const pk_config *cfg, const pk_cache *cache, const pk_state *state,
-                              const pk_config *prefix_cfg, const pk_cache *prefix, const pk_state *prefix_state,
-                              const void *q, float softmax_scale, const void *patterns_k, const void *patterns_v,
-                              float *out, float *lse, void *workspace, size_t workspace_bytes, void *stream)
+static pk_status decode_impl(const pk_config *cfg, const pk_cache *cache, const pk_state *state, const int32_t *seq_states,
+                             const pk_config *prefix_cfg, const pk_cache *prefix, const pk_state *prefix_state,
+                             const void *q, float softmax_scale, const void *patterns_k, const void *patterns_v,
+                             float *out, float *lse, void *workspace, size_t workspace_bytes, void *stream)
 {
     pk_status st = check_config(cfg);
     if (st != PK_OK) return st;
@@ -349,7 +349,30 @@ pk_status pk_decode_attention(const pk_config *cfg, const pk_cache *cache, const
     a.part_ml = reinterpret_cast<float *>(static_cast<char *>(workspace) + o_bytes + w_bytes);
     a.out = out;
     a.lse = lse;
+    a.seq_state = seq_states;
     return launch_decode(a, static_cast<hipStream_t>(stream)) == hipSuccess ? PK_OK : PK_ERR_DEVICE;
+}
+
+pk_status pk_decode_attention(const pk_config *cfg, const pk_cache *cache, const pk_state *state,
+                              const pk_config *prefix_cfg, const pk_cache *prefix, const pk_state *prefix_state,
+                              const void *q, float softmax_scale, const void *patterns_k, const void *patterns_v,
+                              float *out, float *lse, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return decode_impl(cfg, cache, state, nullptr, prefix_cfg, prefix, prefix_state, q, softmax_scale, patterns_k, patterns_v,
+                       out, lse, workspace, workspace_bytes, stream);
+}
+
+pk_status pk_decode_attention_ragged(const pk_config *cfg, const pk_cache *cache, const pk_state *bound,
+                                     const int32_t *seq_states, const pk_config *prefix_cfg, const pk_cache *prefix,
+                                     const pk_state *prefix_state, const void *q, float softmax_scale,
+                                     const void *patterns_k, const void *patterns_v, float *out, float *lse,
+                                     void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!seq_states || !bound) return PK_ERR_INVALID_ARG;
+    if (!aligned16(seq_states)) return PK_ERR_ALIGNMENT;
+    if (bound->tail_start != 0) return PK_ERR_STATE;   // the bound carries sizes only; ring positions are per sequence
+    return decode_impl(cfg, cache, bound, seq_states, prefix_cfg, prefix, prefix_state, q, softmax_scale, patterns_k,
+                       patterns_v, out, lse, workspace, workspace_bytes, stream);
 }
 
 pk_status pk_window_pattern(const void *x, int64_t set_stride, int32_t n_sets, int32_t n, int32_t head_dim,

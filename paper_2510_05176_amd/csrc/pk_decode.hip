@@ -41,7 +41,11 @@ __global__ __launch_bounds__(256) void decode_tail_kernel(DecodeArgs a)
     const CacheView &cv = which == 0 ? a.own : a.prefix;
     const int cstream = which == 0 ? n : head;
     const int slot = n_slots - 2 + which;
-    const int t_end = cv.t_tail;
+    int t_end = cv.t_tail, tail_start = cv.tail_start;
+    if (which == 0) {   // a ragged batch: this sequence's own fill state
+        int tq;
+        own_state(a, seq, tq, t_end, tail_start);
+    }
     const int cg = tid & 15, tg = tid >> 4, lane = tid & 63, wave = tid >> 6;
 
     float qr[RP][8];
@@ -76,7 +80,7 @@ __global__ __launch_bounds__(256) void decode_tail_kernel(DecodeArgs a)
             const int tk = tg + 16 * i;
             const bool valid = tk < n_valid;
             uint4 v = make_uint4(0u, 0u, 0u, 0u);
-            int rs = cv.tail_start + t0 + tk;   // ring slot: one wrap at most, since t0 + tk < t_tail <= ring_len
+            int rs = tail_start + t0 + tk;   // ring slot: one wrap at most, since t0 + tk < t_tail <= ring_len
             if (rs >= cv.ring_len) rs -= cv.ring_len;
             if (valid) v = *reinterpret_cast<const uint4 *>(tail_k + (int64_t)rs * kD);
             const __half2 *h2 = reinterpret_cast<const __half2 *>(&v);
@@ -130,7 +134,7 @@ __global__ __launch_bounds__(256) void decode_tail_kernel(DecodeArgs a)
         for (int i = 0; i < kTile / 16; ++i) {
             const int tk = tg + 16 * i;
             if (tk < n_valid) {
-                int rs = cv.tail_start + t0 + tk;
+                int rs = tail_start + t0 + tk;
                 if (rs >= cv.ring_len) rs -= cv.ring_len;
                 const uint4 v = *reinterpret_cast<const uint4 *>(tail_v + (int64_t)rs * kD);
                 const __half2 *h2 = reinterpret_cast<const __half2 *>(&v);

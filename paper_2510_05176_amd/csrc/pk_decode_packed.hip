@@ -112,7 +112,23 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
     const int cstream = in_prefix ? head : ns;
     const int set = in_prefix ? head : a.sets.set_of(ns);
     const int t_begin = (in_prefix ? split : split - a.splits_prefix) * a.chunk;
-    const int t_end = min(cv.t_quant, t_begin + a.chunk);
+    int tq = cv.t_quant;
+    if (!in_prefix) {   // a ragged batch: this sequence's own fill state; a split past its end has no blocks
+        int tt, ts;
+        own_state(a, seq, tq, tt, ts);
+    }
+    const int t_end = max(t_begin, min(tq, t_begin + a.chunk));
+    if (t_end == t_begin) {   // nothing of this sequence in the split: an empty partial (mass 0; the merge skips it)
+        const int R0 = a.n_q_heads / a.n_kv_heads;
+        const int64_t pbase = ((int64_t)ns * n_slots + split) * R0;
+        for (int e = tid; e < R0 * kD; e += 256) a.part_o[pbase * kD + e] = 0.f;
+        for (int e = tid; e < R0 * a.P; e += 256) a.part_w[pbase * a.P + e] = 0.f;
+        if (tid < R0) {
+            a.part_ml[(pbase + tid) * 2] = -INFINITY;
+            a.part_ml[(pbase + tid) * 2 + 1] = 0.f;
+        }
+        return;
+    }
     const int cap = cv.t_capacity;
 
     const int R = a.n_q_heads / a.n_kv_heads, G = a.G, P = a.P;

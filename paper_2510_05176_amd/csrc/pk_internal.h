@@ -147,7 +147,23 @@ struct DecodeArgs {
     float *part_w;                // [N][S][r][P]   softmax mass per V pattern (packed splits only)
     float *part_ml;               // [N][S][r][2]   running maximum (log2 domain) and sum
     float *out, *lse;
+    const int32_t *seq_state;     // optional, device [n_seq][4]: t_quant, t_tail, tail_start, 0 of every sequence's own
+                                  // cache; own.t_quant / own.t_tail are then upper bounds
 };
+// Fill state of sequence seq's own cache: the uniform one, or the sequence's entry clamped to the bounds the
+// launch was sized for (t_quant to whole 64-token blocks), so that a bad entry cannot lead outside the cache.
+__device__ __forceinline__ void own_state(const DecodeArgs &a, int seq, int &t_quant, int &t_tail, int &tail_start)
+{
+    t_quant = a.own.t_quant;
+    t_tail = a.own.t_tail;
+    tail_start = a.own.tail_start;
+    if (a.seq_state) {
+        const int4 v = *reinterpret_cast<const int4 *>(a.seq_state + 4 * seq);
+        t_quant = min(max(v.x, 0), a.own.t_quant) & ~63;
+        t_tail = min(max(v.y, 0), a.own.t_tail);
+        tail_start = min(max(v.z, 0), a.own.ring_len - 1);
+    }
+}
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t s);
 int decode_chunk(int64_t n_streams, int64_t t_packed_total, int P, int r);
 constexpr int kMaxSlots = 2304;   // partial slots per stream the merge kernel holds weights for (splits + 2)

@@ -8,7 +8,7 @@ from __future__ import annotations
 
 import ctypes as C
 import os
-from dataclasses import dataclass, asdict
+from dataclasses import dataclass, asdict, replace
 
 import torch
 
@@ -49,7 +49,7 @@ class _State(C.Structure):
     _fields_ = [("t_quant", C.c_int32), ("t_tail", C.c_int32), ("tail_start", C.c_int32)]
 
 
-ABI_VERSION = 2          # PK_ABI_VERSION of include/patternkv.h this binding's structs are laid out for
+ABI_VERSION = 3          # PK_ABI_VERSION of include/patternkv.h this binding's structs are laid out for
 
 _lib.pk_abi_version.restype = C.c_uint32
 if int(_lib.pk_abi_version()) != ABI_VERSION:
@@ -73,6 +73,11 @@ _lib.pk_decode_attention.argtypes = [C.POINTER(_Config), C.POINTER(_Cache), C.PO
                                      C.POINTER(_Config), C.POINTER(_Cache), C.POINTER(_State), C.c_void_p,
                                      C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                      C.c_size_t, C.c_void_p]
+_lib.pk_decode_attention_ragged.restype = C.c_int
+_lib.pk_decode_attention_ragged.argtypes = [C.POINTER(_Config), C.POINTER(_Cache), C.POINTER(_State), C.c_void_p,
+                                            C.POINTER(_Config), C.POINTER(_Cache), C.POINTER(_State), C.c_void_p,
+                                            C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                            C.c_size_t, C.c_void_p]
 _lib.pk_window_pattern.restype = C.c_int
 _lib.pk_window_pattern.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p]
 _lib.pk_dequantize.restype = C.c_int
@@ -184,6 +189,16 @@ class Cache:
         """Raw bytes of one cache array (uint8 tensor of the layout's size)."""
         return self.buf[name][: self.bytes[name]]
 
+    def sequence(self, i: int) -> "Cache":
+        """The part of sequence i as a cache of its own (n_seq = 1, one pattern set per KV head) over the same
+        memory, with a fill state of its own: the arrays are laid out stream by stream."""
+        sub = Cache.__new__(Cache)
+        sub.cfg = replace(self.cfg, n_seq=1, seqs_per_set=0)
+        sub.bytes = {n: self.bytes[n] // self.cfg.n_seq for n in _ARRAYS}
+        sub.buf = {n: self.buf[n][i * sub.bytes[n]:(i + 1) * sub.bytes[n]] for n in _ARRAYS}
+        sub.state = _State(0, 0, 0)
+        return sub
+
 
 def pk_mine_patterns(cfg: Config, x: torch.Tensor, iters: int, patterns: torch.Tensor | None = None,
                      init_given: bool = False, assign: torch.Tensor | None = None,
@@ -270,6 +285,34 @@ def pk_decode_attention(cfg: Config, cache: Cache, q: torch.Tensor, softmax_scal
                                   C.c_float(softmax_scale), _ptr(patterns_k), _ptr(patterns_v), _ptr(out),
                                   _ptr(lse), _ptr(workspace), workspace.numel(), _stream())
     _check(st, "pk_decode_attention")
+    return out
+
+
+def pk_decode_attention_ragged(cfg: Config, cache: Cache, seq_states: torch.Tensor, bound_t_quant: int, bound_t_tail: int,
+                               q: torch.Tensor, softmax_scale: float, patterns_k: torch.Tensor, patterns_v: torch.Tensor,
+                               out: torch.Tensor | None = None, lse: torch.Tensor | None = None,
+                               workspace: torch.Tensor | None = None, prefix: Cache | None = None):
+    """Decode over sequences filled to different lengths.  seq_states: device int32 [n_seq, 4] holding t_quant,
+    t_tail, tail_start of every sequence's own cache (and an unused word); bound_*: host upper bounds."""
+    assert q.dtype == torch.float16 and seq_states.dtype == torch.int32 and seq_states.is_contiguous()
+    assert tuple(seq_states.shape) == (cfg.n_seq, 4)
+    if out is None:
+        out = torch.empty(q.shape, dtype=torch.float32, device=q.device)
+    if workspace is None:
+        b = 0 if prefix is None else prefix.t_quant + prefix.t_tail
+        workspace = torch.empty(max(pk_workspace_bytes(cfg, OP_DECODE, bound_t_quant + bound_t_tail, b), 16),
+                                dtype=torch.uint8, device=q.device)
+    cc, kc = cfg.c(), cache.c()
+    bound = _State(bound_t_quant, bound_t_tail, 0)
+    if prefix is not None:
+        pc, pkc = prefix.cfg.c(), prefix.c()
+        pargs = (C.byref(pc), C.byref(pkc), C.byref(prefix.state))
+    else:
+        pargs = (None, None, None)
+    st = _lib.pk_decode_attention_ragged(C.byref(cc), C.byref(kc), C.byref(bound), _ptr(seq_states), *pargs, _ptr(q),
+                                         C.c_float(softmax_scale), _ptr(patterns_k), _ptr(patterns_v), _ptr(out),
+                                         _ptr(lse), _ptr(workspace), workspace.numel(), _stream())
+    _check(st, "pk_decode_attention_ragged")
     return out
 
 

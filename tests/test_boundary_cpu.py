@@ -25,11 +25,12 @@ def test_exports_every_declared_symbol(pk):
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
     names = set(re.findall(r"\b(pk_[a-z_]+)\s*\(", src))
     assert {"pk_mine_patterns", "pk_quantize_append", "pk_decode_attention", "pk_dequantize", "pk_cache_layout",
-            "pk_workspace_bytes", "pk_status_string", "pk_abi_version", "pk_window_pattern"} <= names
+            "pk_workspace_bytes", "pk_status_string", "pk_abi_version", "pk_window_pattern",
+            "pk_decode_attention_ragged"} <= names
     lib = C.CDLL(LIB)
     for n in names:
         assert hasattr(lib, n), n
-    assert pk.pk_abi_version() == 2
+    assert pk.pk_abi_version() == 3
 
 
 def test_status_strings(pk):
@@ -145,6 +146,17 @@ def test_decode_and_mine_argument_errors_before_launch(pk):
     pcache, pstate = _fake_cache(pk, 0x9000), pk._State(64, 0, 0)
     assert dec(pcfg=C.byref(pc), pcache=C.byref(pcache), pstate=C.byref(pstate), wsb=1 << 30) == 3   # group differs
     assert dec(state=pk._State(64, 64, 0)) == 6
+
+    def rag(**kw):
+        return lib.pk_decode_attention_ragged(C.byref(c), C.byref(cache), C.byref(kw.get("bound", state)),
+                                              kw.get("states", good), None, None, None, kw.get("q", good), C.c_float(0.1),
+                                              good, good, good, None, kw.get("ws", good), kw.get("wsb", 0), None)
+    assert rag(states=None) == 1
+    assert rag(states=C.c_void_p(0x2004)) == 4
+    assert rag(bound=pk._State(64, 3, 5)) == 6                   # the bound carries no ring position
+    assert rag(bound=pk._State(70, 3, 0)) == 6                   # not a multiple of flush
+    assert rag(q=None) == 1
+    assert rag(wsb=0) == 7
 
     def mine(**kw):
         return lib.pk_mine_patterns(C.byref(c), kw.get("x", good), kw.get("stride", 64 * 128), kw.get("S", 2),

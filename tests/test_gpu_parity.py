@@ -311,6 +311,89 @@ def test_decode_with_shared_prefix(oracle, pk):
     assert np.abs(lse.cpu().numpy() - want_lse).max() <= 2e-3
 
 
+def _ragged_batch(oracle, pk, kw, K, V, Mk, Mv, lens):
+    """Fills sequence i of a GPU cache and an oracle cache of its own with the first lens[i] vectors."""
+    gcfg = pk.Config(**dict(kw, n_seq=len(lens), seqs_per_set=len(lens)))
+    gc = pk.Cache(gcfg)
+    Kd, Vd = dev(K), dev(V)
+    Mkd, Mvd = dev(Mk.view(np.float16)), dev(Mv.view(np.float16))
+    ocs, states = [], []
+    for i, n in enumerate(lens):
+        oc = oracle.Cache(oracle.Config(**dict(kw, n_seq=1, seqs_per_set=0)))
+        sub = gc.sequence(i)
+        if n:
+            oc.append(K[i:i + 1, :, :n].view(np.uint16), V[i:i + 1, :, :n].view(np.uint16), Mk, Mv)
+            pk.pk_quantize_append(sub.cfg, sub, Kd[i:i + 1, :, :n], Vd[i:i + 1, :, :n], Mkd, Mvd)
+        assert (sub.t_quant, sub.t_tail, sub.tail_start) == (oc.t_quant, oc.t_tail, oc.tail_start)
+        ocs.append(oc)
+        states.append([sub.t_quant, sub.t_tail, sub.tail_start, 0])
+    torch.cuda.synchronize()
+    return gcfg, gc, ocs, states, Mkd, Mvd
+
+
+@pytest.mark.parametrize("hkv,hq,bits,G,P,R,lens", [
+    (2, 8, 2, 64, 32, 32, [0, 70, 197, 1000, 517]),        # an empty sequence, a tail-only one, several splits
+    (1, 4, 4, 32, 16, 0, [640, 64, 1, 333]),               # 4-bit, group 32, no recent window
+])
+def test_decode_ragged_batch_parity(oracle, pk, hkv, hq, bits, G, P, R, lens):
+    S, T = len(lens), max(lens)
+    kw = dict(n_kv_heads=hkv, n_q_heads=hq, head_dim=128, n_patterns=P, bits=bits, group=G, recent=R, flush=64,
+              t_capacity=-(-T // 64) * 64, metric=0)
+    K, V = synth.make_kv(300 + P, synth.KVSpec(1, S, hkv, hq, T, 128, 12))
+    Mk, _, _, _ = oracle.mine(K[0].view(np.uint16), P, 3)
+    Mv, _, _, _ = oracle.mine(V[0].view(np.uint16), P, 3)
+    gcfg, gc, ocs, states, Mkd, Mvd = _ragged_batch(oracle, pk, kw, K, V, Mk, Mv, lens)
+    q = synth.make_queries(31, S, hq, 128)
+    want, want_lse = oracle.decode_attention_ragged(ocs, q.view(np.uint16), Mk, Mv, 128 ** -0.5)
+    st = torch.tensor(states, dtype=torch.int32, device="cuda")
+    bq, bt = max(s[0] for s in states), max(s[1] for s in states)
+    lse = torch.empty((S, hq), dtype=torch.float32, device="cuda")
+    got = pk.pk_decode_attention_ragged(gcfg, gc, st, bq, bt, dev(q), 128 ** -0.5, Mkd, Mvd, lse=lse).cpu().numpy()
+    glse = lse.cpu().numpy()
+    for i, n in enumerate(lens):
+        if n == 0:
+            assert np.all(got[i] == 0) and np.all(np.isneginf(glse[i]))
+        else:
+            assert rel_l2(got[i], want[i]) <= 2e-3, (i, n)
+            assert np.abs(glse[i] - want_lse[i]).max() <= 2e-3
+    # entries beyond the bound are clamped to it: the longest sequence reads the same with an oversized entry
+    big = int(np.argmax([s[0] for s in states]))
+    st2 = st.clone()
+    st2[big, 0] = bq + 640
+    got2 = pk.pk_decode_attention_ragged(gcfg, gc, st2, bq, bt, dev(q), 128 ** -0.5, Mkd, Mvd).cpu().numpy()
+    assert np.array_equal(got2, got)
+    # a uniform state array reproduces the uniform entry point bit for bit
+    full = gc.sequence(big)
+    full.state = pk._State(*states[big][:3])
+    one = pk.pk_decode_attention(full.cfg, full, dev(q[big:big + 1]), 128 ** -0.5, Mkd, Mvd).cpu().numpy()
+    st1 = torch.tensor([states[big]], dtype=torch.int32, device="cuda")
+    rag1 = pk.pk_decode_attention_ragged(full.cfg, full, st1, states[big][0], states[big][1], dev(q[big:big + 1]),
+                                         128 ** -0.5, Mkd, Mvd).cpu().numpy()
+    assert np.array_equal(one, rag1)
+
+
+def test_decode_ragged_batch_with_shared_prefix(oracle, pk):
+    """Samples of different generated length over one shared prompt cache (the breadth-sampling shape of Sec. 4.3)."""
+    P, G, hkv, hq, lens = 32, 32, 2, 8, [130, 5, 300]
+    kw = dict(n_kv_heads=hkv, n_q_heads=hq, head_dim=128, n_patterns=P, bits=2, group=G, recent=0, flush=128,
+              t_capacity=384, metric=0)
+    K, V = synth.make_kv(81, synth.KVSpec(1, 3, hkv, hq, 300, 128, 12, drift_sigma=0.05))
+    Kp, Vp = synth.make_kv(82, synth.KVSpec(1, 1, hkv, hq, 500, 128, 12))
+    Mk, _, _, _ = oracle.mine(Kp[0].view(np.uint16), P, 4)
+    Mv, _, _, _ = oracle.mine(Vp[0].view(np.uint16), P, 4)
+    pre_kw = dict(kw, n_seq=1, seqs_per_set=0, flush=64, recent=16, t_capacity=512)
+    op, gp, _, _ = run_appends(oracle, pk, oracle.Config(**pre_kw), pk.Config(**pre_kw), Kp, Vp, Mk, Mv, [500])
+    gcfg, gc, ocs, states, Mkd, Mvd = _ragged_batch(oracle, pk, kw, K, V, Mk, Mv, lens)
+    q = synth.make_queries(32, 3, hq, 128)
+    want, _ = oracle.decode_attention_ragged(ocs, q.view(np.uint16), Mk, Mv, 128 ** -0.5, prefix=op,
+                                             prefix_patterns_k=Mk, prefix_patterns_v=Mv)
+    st = torch.tensor(states, dtype=torch.int32, device="cuda")
+    got = pk.pk_decode_attention_ragged(gcfg, gc, st, max(s[0] for s in states), max(s[1] for s in states), dev(q),
+                                        128 ** -0.5, Mkd, Mvd, prefix=gp).cpu().numpy()
+    for i in range(3):
+        assert rel_l2(got[i], want[i]) <= 2e-3, i
+
+
 # ------------------------------------------------------------------------------ decode-stage pattern update
 
 def test_window_pattern_and_growing_tables(oracle, pk):

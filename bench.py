@@ -40,6 +40,7 @@ WORKLOADS = {
     "cfg3": dict(spec="cfg3", layers=32, batch=16, P=128, iters=10, group=64, recent=128, flush=128),
     "cfg5": dict(spec="cfg5", layers=1, batch=1, P=256, iters=20, group=128, recent=0, flush=128),
     "cfg4": dict(spec="cfg4"),   # streaming: its own step, see run_streaming()
+    "cfg3r": dict(spec="cfg3"),  # config 3's shape with a mix of sequence lengths: decode only, see run_ragged()
 }
 
 
@@ -123,6 +124,84 @@ def run_streaming(args, torch, pk, synth):
     print(json.dumps(result))
 
 
+def run_ragged(args, torch, pk, synth):
+    """Config 3's shape (32 layers x batch 16, 8 KV / 32 query heads, P=128, group 64, 128 recent fp16 tokens) with
+    the batch's 16 sequences filled to different lengths, drawn once (seeded, uniform in [2048, 32768]; a sequence
+    has the same length in every layer).  Every sequence is appended through its own cache view; the timed step
+    is one ragged decode call over all 512 (layer, sequence) pairs."""
+    dev = "cuda"
+    base = synth.SPECS["cfg3"]
+    L, B, Hkv, Hq, T, d = base.n_layers, base.batch, base.n_kv_heads, base.n_q_heads, base.T, base.d
+    P, G, R, F, bits, iters = 128, 64, 128, 128, args.bits, 10
+    lens = [int(v) for v in np.random.default_rng(args.seed).integers(2048, T + 1, size=B)]
+    lens[0] = T                                               # the first sequence of a layer is the one mined on
+    n_seq, cap = L * B, (T - R) // F * F
+    cfg = pk.Config(n_seq=n_seq, n_kv_heads=Hkv, n_q_heads=Hq, head_dim=d, n_patterns=P, seqs_per_set=B, bits=bits,
+                    group=G, recent=R, flush=F, t_capacity=cap, metric=pk.METRIC_L2)
+    cache = pk.Cache(cfg)
+    Mk = torch.empty((L * Hkv, P, d), dtype=torch.float16, device=dev)
+    Mv = torch.empty_like(Mk)
+    one = synth.KVSpec(**{**base.__dict__, "n_layers": 1})
+    states = []
+    for layer in range(L):
+        K, V = synth.make_layer_device(args.seed, layer, one, dev)
+        mk, mv = Mk[layer * Hkv:(layer + 1) * Hkv], Mv[layer * Hkv:(layer + 1) * Hkv]
+        sub0 = cache.sequence(layer * B)
+        pk.pk_mine_patterns(sub0.cfg, K[0], iters, patterns=mk)
+        pk.pk_mine_patterns(sub0.cfg, V[0], iters, patterns=mv)
+        for b in range(B):
+            sub = cache.sequence(layer * B + b)
+            pk.pk_quantize_append(sub.cfg, sub, K[b:b + 1, :, :lens[b]], V[b:b + 1, :, :lens[b]], mk, mv)
+            states.append([sub.t_quant, sub.t_tail, sub.tail_start, 0])
+        del K, V
+    st = torch.tensor(states, dtype=torch.int32, device=dev)
+    bq, bt = max(s[0] for s in states), max(s[1] for s in states)
+    q = torch.from_numpy(synth.make_queries(args.seed, n_seq, Hq, d).view(np.int16)).to(dev).view(torch.float16)
+    out = torch.empty((n_seq, Hq, d), dtype=torch.float32, device=dev)
+    ws = torch.empty(max(pk.pk_workspace_bytes(cfg, pk.OP_DECODE, bq + bt, 0), 16), dtype=torch.uint8, device=dev)
+    flush_buf = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    scale = d ** -0.5
+
+    def decode():
+        pk.pk_decode_attention_ragged(cfg, cache, st, bq, bt, q, scale, Mk, Mv, out=out, workspace=ws)
+
+    for _ in range(args.warmup):
+        decode()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        decode()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    cold = []
+    for _ in range(args.steps):
+        flush_buf.fill_(1)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(); decode(); e1.record(); e1.synchronize()
+        cold.append(e0.elapsed_time(e1))
+    dec_ms = float(np.mean(cold))
+    per_tok = 2 * (bits * d / 8) + 2 * (2 * 2 * d / G) + 2
+    dec_bytes = Hkv * sum(s[0] * per_tok + s[1] * 2 * d * 2 + 2 * P * d * 2 for s in states) + n_seq * Hq * d * 6
+    roof = {"bound": "hbm", "achieved": round(dec_bytes / dec_ms / 1e6, 3), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": round(dec_bytes / dec_ms / 1e6 / HBM_PEAK_GBPS, 4), "traffic": None,
+            "kernel": "decode_packed_kernel(+decode_tail_kernel+decode_merge_kernel)"}
+    print(json.dumps({
+        "metric": "KV quantize-append GB/s and decode-attention tokens/s on 2-bit cache, % HBM peak",
+        "value": round(B / (ms_per_step * 1e-3), 1),
+        "unit": "generated tokens/s (one ragged decode step of the 16-sequence batch over all 32 layers)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16 in, f32 arithmetic, u%d codes" % bits, "data": "synthetic",
+        "config": {"workload": "cfg3r", "layers": L, "batch": B, "n_kv_heads": Hkv, "n_q_heads": Hq, "lengths": lens,
+                   "head_dim": d, "n_patterns": P, "bits": bits, "group": G, "recent": R, "flush": F, "metric": "L2",
+                   "seed": args.seed},
+        "stages": {"decode_attention": {"ms": round(dec_ms, 4), "ms_min": round(float(np.min(cold)), 4),
+                                        "GB/s": roof["achieved"], "frac_hbm_peak": roof["frac"],
+                                        "tokens/s": round(B / (dec_ms * 1e-3), 1), "algorithmic_bytes": int(dec_bytes)}},
+        "roofline": roof,
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -151,6 +230,8 @@ def main():
     torch.cuda.set_device(0)
     if args.workload == "cfg4":
         return run_streaming(args, torch, pk, synth)
+    if args.workload == "cfg3r":
+        return run_ragged(args, torch, pk, synth)
     dev = "cuda"
     w = WORKLOADS[args.workload]
     base = synth.SPECS[w["spec"]]

@@ -187,6 +187,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
         }
     }
     for (int i = lane; i < R * WS; i += 64) Ws[wave * R * WS + i] = 0ull;
+    // With two K groups per block, or the extra operands of 4-bit codes, the registers that q in natural order
+    // would hold for the rest of the kernel are needed elsewhere (the kernel is at its 256-register limit and
+    // spilled): it waits in LDS instead (identical in the four waves; [piece][lane]).
+    constexpr bool Q_LDS = G32 || BITS == 4;
+    __shared__ uint4 qn_s[Q_LDS ? 4 : 1][64];
+    if (Q_LDS && wave == 0) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) qn_s[i][lane] = make_uint4(qn[4 * i], qn[4 * i + 1], qn[4 * i + 2], qn[4 * i + 3]);
+    }
     __syncthreads();
 
     // ---- this wave's run of 64-token blocks
@@ -237,11 +246,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
         for (int i = 0; i < 4; ++i) {
             const half2v *hv = reinterpret_cast<const half2v *>(&gr.s[i]);
             const uint32_t *zu = reinterpret_cast<const uint32_t *>(&gr.z[i]);
+            uint4 qv;
+            if (G32 || BITS == 4)
+                qv = qn_s[i][lane];
+            else
+                qv = make_uint4(qn[4 * i], qn[4 * i + 1], qn[4 * i + 2], qn[4 * i + 3]);
+            const uint32_t qw[4] = {qv.x, qv.y, qv.z, qv.w};
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 sh[8 * i + 2 * k] = hv[k][0];
                 sh[8 * i + 2 * k + 1] = hv[k][1];
-                acc = dot2(qn[4 * i + k], zu[k], acc);
+                acc = dot2(qw[k], zu[k], acc);
             }
         }
 #pragma unroll

@@ -26,6 +26,17 @@ struct TailShared {
     float osum[4][RP][kD];    // output partials of the four waves
 };
 
+// Sum over the 16 lanes of a row with data-parallel-primitive shifts (row_shr 1, 2, 4, 8; lanes shifted in from
+// outside the row read 0): an inclusive scan, so the row's last lane ends with the total.  No LDS traffic.
+__device__ __forceinline__ float row_sum_to_last(float v)
+{
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x111, 0xf, 0xf, true));
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x112, 0xf, 0xf, true));
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x114, 0xf, 0xf, true));
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x118, 0xf, 0xf, true));
+    return v;
+}
+
 // fp16 tail of one stream (own cache or shared prefix): plain q.k / softmax / p.v, 256 threads.
 // Thread (cg, tg) = (tid % 16, tid / 16) owns channels 8cg .. 8cg+7 of the tokens tg, tg+16, ... of a tile, in
 // the score phase and in the value phase alike: the 16 lanes of a token read its 256-byte row in 16-byte
@@ -95,9 +106,8 @@ __global__ __launch_bounds__(256) void decode_tail_kernel(DecodeArgs a)
                 float sdot = 0.f;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) sdot = fmaf(qr[h][e], kf[e], sdot);
-#pragma unroll
-                for (int off = 1; off < 16; off <<= 1) sdot += __shfl_xor(sdot, off);
-                if (cg == 0 && valid) sh.ps[tk][h] = sdot * a.softmax_scale;
+                sdot = row_sum_to_last(sdot);   // the token's 16 lanes; lane 15 of the row holds the sum
+                if (cg == 15 && valid) sh.ps[tk][h] = sdot * a.softmax_scale;
             }
         }
         __syncthreads();
@@ -206,7 +216,8 @@ __global__ __launch_bounds__(128 * NQ) void decode_merge_kernel(DecodeArgs a)
     const int n_packed = a.splits_prefix + a.splits_own;
     const int64_t base = (int64_t)n * (n_packed + 2);
     // the two tail slots are written (and read here) only when there is a tail at all
-    const int n_slots = (a.own.t_tail > 0 || a.prefix.t_tail > 0) ? n_packed + 2 : n_packed;
+    // (own tail at n_packed, prefix tail behind it; without a prefix tail only the own one is launched)
+    const int n_slots = a.prefix.t_tail > 0 ? n_packed + 2 : a.own.t_tail > 0 ? n_packed + 1 : n_packed;
     // maximum over the slots that hold anything
     float M = -INFINITY;
     for (int s = tid; s < n_slots; s += 128 * NQ) {
@@ -304,10 +315,13 @@ hipError_t launch_decode(const DecodeArgs &a, hipStream_t s)
     hipError_t e;
     if ((e = launch_decode_packed(a, s)) != hipSuccess) return e;
     if (a.own.t_tail > 0 || a.prefix.t_tail > 0) {
+        // x = 0: own tails, x = 1: the shared prefix's tail (launched only if there is one: workgroups that find
+        // nothing to do still cost their dispatch, tens of nanoseconds each)
+        const dim3 grid(a.prefix.t_tail > 0 ? 2 : 1, N);
         if (r <= 4)
-            hipLaunchKernelGGL((decode_tail_kernel<4>), dim3(2, N), dim3(256), 0, s, a);
+            hipLaunchKernelGGL((decode_tail_kernel<4>), grid, dim3(256), 0, s, a);
         else
-            hipLaunchKernelGGL((decode_tail_kernel<8>), dim3(2, N), dim3(256), 0, s, a);
+            hipLaunchKernelGGL((decode_tail_kernel<8>), grid, dim3(256), 0, s, a);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     // four parts per channel when a thread would otherwise walk many slots or patterns alone and the

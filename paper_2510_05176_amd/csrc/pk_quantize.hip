@@ -961,17 +961,23 @@ hipError_t launch_quantize_k(const QuantArgs &a, hipStream_t s)
         // them): pairs keep three waves per SIMD; the whole 64-token group takes two, which pays above 128
         // patterns; 32-token groups gain from pairs only once the table is large.
         const int kmulti = a.G == 64 ? (a.P > 128 ? 4 : 2) : (a.P >= 128 ? 2 : 1);
+        // group 128 with a large table: one workgroup fills a CU's LDS and stages 64 KB of patterns, so a small
+        // job is cut into one resident round (256 workgroups) rather than many short ones
+        const int64_t tiles64k = (int64_t)(a.nq / 64) * a.n_streams;   // the same for the group-64 wave kernel above 128 patterns (one workgroup per CU)
+        const int bigw = a.P > 128 && tiles64k <= 256 * 64 ? (int)((tiles64k + 255) / 256) : 1;
+        const int64_t tiles128 = (int64_t)(a.nq / 128) * a.n_streams;
+        const int big1 = a.P > 128 && tiles128 <= 256 * 64 ? (int)((tiles128 + 255) / 256) : 1;
 #define PK_LAUNCH_K2(GG, BB)                                                                                       \
     if (a.G == GG && a.bits == BB) {                                                                               \
         constexpr int TT = GG == 128 ? 128 : 64;                                                                   \
-        return tl ? launch_tiled(quantize_k_kernel<GG, BB, true>, a, TT, tile_lds_bytes(a.P, true, TT, GG), s)     \
+        return tl ? launch_tiled(quantize_k_kernel<GG, BB, true>, a, TT, tile_lds_bytes(a.P, true, TT, GG), s, big1) \
                   : launch_tiled(quantize_k_kernel<GG, BB, false>, a, TT, tile_lds_bytes(a.P, false, TT, GG), s);  \
     }
 #define PK_LAUNCH_KW(GG, BB)                                                                                       \
     if (a.G == GG && a.bits == BB) {                                                                               \
         /* a wave owns whole groups: at least four groups per workgroup */                                        \
         return !tl ? launch_tiled(quantize_k_wave_kernel<GG, BB, false, 1>, a, 64, wave_k_lds_bytes(a.P, false), s, GG / 16)   \
-               : kmulti == 4 && GG == 64 ? launch_tiled(quantize_k_wave_kernel<GG, BB, true, GG / 16>, a, 64, wave_k_lds_bytes(a.P, true), s, GG / 16) \
+               : kmulti == 4 && GG == 64 ? launch_tiled(quantize_k_wave_kernel<GG, BB, true, GG / 16>, a, 64, wave_k_lds_bytes(a.P, true), s, bigw > GG / 16 ? bigw : GG / 16) \
                : kmulti >= 2 ? launch_tiled(quantize_k_wave_kernel<GG, BB, true, 2>, a, 64, wave_k_lds_bytes(a.P, true), s, GG / 16) \
                         : launch_tiled(quantize_k_wave_kernel<GG, BB, true, 1>, a, 64, wave_k_lds_bytes(a.P, true), s, GG / 16); \
     }
@@ -1000,10 +1006,13 @@ hipError_t launch_quantize_v(const QuantArgs &a, hipStream_t s)
         const int ng = kD / (a.G < kD ? a.G : kD);
         const size_t lds = tile_lds_bytes(a.P, tl, 0, 1);
         const bool two = a.P >= 128;   // two blocks per table pass (three waves per SIMD instead of four) pay from 128 patterns on
+        // a large table (two workgroups per CU, 64 KB of patterns staged by each): a small job as one resident round
+        const int64_t tiles64 = (int64_t)(a.nq / 64) * a.n_streams;
+        const int big1 = a.P > 128 && tiles64 <= 512 * 64 ? (int)((tiles64 + 511) / 512) : 1;
 #define PK_LAUNCH_V2(BB, NN)                                                                   \
     if (a.bits == BB && ng == NN)                                                              \
         return !tl ? launch_tiled(quantize_v_kernel<BB, NN, false, 1>, a, 64, lds, s)          \
-               : two ? launch_tiled(quantize_v_kernel<BB, NN, true, 2>, a, 64, lds, s)         \
+               : two ? launch_tiled(quantize_v_kernel<BB, NN, true, 2>, a, 64, lds, s, big1)   \
                      : launch_tiled(quantize_v_kernel<BB, NN, true, 1>, a, 64, lds, s);
         PK_LAUNCH_V2(2, 1) PK_LAUNCH_V2(2, 2) PK_LAUNCH_V2(2, 4)
         PK_LAUNCH_V2(4, 1) PK_LAUNCH_V2(4, 2) PK_LAUNCH_V2(4, 4)

@@ -100,7 +100,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
     // sums (softmax mass per V pattern, unit 2^-31).  Integer LDS atomics run at full rate on this chip, float
     // ones retire about one lane per 2.6 cycles (measured), which made the mass sums the slowest part of a block.
     extern __shared__ __align__(16) unsigned char dyn_smem[];
-    __shared__ float Os[8][kD];
+    __shared__ float Os[4][8][kD];   // the four waves' scaled outputs, added up when the partial is written
     __shared__ float stat_m[4][16], stat_l[4][16], stat_pz[4][16];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 15, kb = lane >> 4;
@@ -480,33 +480,36 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
         stat_pz[wave][n] = pzacc;
     }
     __syncthreads();
-    for (int w = 0; w < 4; ++w) {
-        if (wave == w) {
+    // (column rho of the score tile = head rho % R, channel group rho / R; the quotients are formed by comparison
+    // and the channel tile's group by a shift - integer divisions by run-time values here once cost more than
+    // the rest of the epilogue, 10 us per workgroup)
+    const int lgGc = 31 - __clz(Gc);
+    {   // every wave leaves its outputs, scaled to the workgroup's reference, in a slab of its own
+        const int w = wave;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int rho = 4 * kb + i;
-                if (rho < R * NG) {
-                    const int hh = rho % R, gg = rho / R;
-                    const float M = fmaxf(fmaxf(stat_m[0][rho], stat_m[1][rho]), fmaxf(stat_m[2][rho], stat_m[3][rho]));
-                    const float f = __builtin_amdgcn_exp2f(stat_m[w][rho] - M);
-                    const float pzv = stat_pz[w][rho];
+        for (int i = 0; i < 4; ++i) {
+            const int rho = 4 * kb + i;
+            if (rho < R * NG) {
+                const int gg = (rho >= R) + (rho >= 2 * R) + (rho >= 3 * R), hh = rho - gg * R;   // NG <= 4
+                const float M = fmaxf(fmaxf(stat_m[0][rho], stat_m[1][rho]), fmaxf(stat_m[2][rho], stat_m[3][rho]));
+                const float f = __builtin_amdgcn_exp2f(stat_m[w][rho] - M);
+                const float pzv = stat_pz[w][rho];
 #pragma unroll
-                    for (int t = 0; t < 8; ++t) {
-                        if ((16 * t) / Gc == gg) {
-                            const float v = f * fmaf(O[t][i], 65536.f, pzv);
-                            float *dst = &Os[hh][16 * t + n];
-                            *dst = w == 0 ? v : *dst + v;
-                        }
-                    }
+                for (int t = 0; t < 8; ++t) {
+                    if (((16 * t) >> lgGc) == gg) Os[w][hh][16 * t + n] = f * fmaf(O[t][i], 65536.f, pzv);
                 }
             }
         }
-        __syncthreads();
     }
+    __syncthreads();
     const int64_t pbase = ((int64_t)ns * n_slots + split) * R;
-    for (int e = tid; e < R * kD; e += 256) a.part_o[pbase * kD + e] = (&Os[0][0])[e];
+    for (int e = tid; e < R * kD; e += 256)   // waves added in order 0, 1, 2, 3 as before
+        a.part_o[pbase * kD + e] = (((&Os[0][0][0])[e] + (&Os[1][0][0])[e]) + (&Os[2][0][0])[e]) + (&Os[3][0][0])[e];
     for (int e = tid; e < R * P; e += 256) {
-        const int hh = e / P, pp = e - hh * P;
+        int hh = 0;
+#pragma unroll
+        for (int k = 1; k < 8; ++k) hh += (e >= k * P) ? 1 : 0;   // e / P without a division (R <= 8)
+        const int pp = e - hh * P;
         const float M = fmaxf(fmaxf(stat_m[0][hh], stat_m[1][hh]), fmaxf(stat_m[2][hh], stat_m[3][hh]));
         float acc = 0.f;
 #pragma unroll

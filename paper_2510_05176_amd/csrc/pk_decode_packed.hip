@@ -100,7 +100,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
     // sums (softmax mass per V pattern, unit 2^-31).  Integer LDS atomics run at full rate on this chip, float
     // ones retire about one lane per 2.6 cycles (measured), which made the mass sums the slowest part of a block.
     extern __shared__ __align__(16) unsigned char dyn_smem[];
-    __shared__ float Os[4][8][kD];   // the four waves' scaled outputs, added up when the partial is written
     __shared__ float stat_m[4][16], stat_l[4][16], stat_pz[4][16];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 15, kb = lane >> 4;
@@ -484,27 +483,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
     // and the channel tile's group by a shift - integer divisions by run-time values here once cost more than
     // the rest of the epilogue, 10 us per workgroup)
     const int lgGc = 31 - __clz(Gc);
-    {   // every wave leaves its outputs, scaled to the workgroup's reference, in a slab of its own
-        const int w = wave;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int rho = 4 * kb + i;
-            if (rho < R * NG) {
-                const int gg = (rho >= R) + (rho >= 2 * R) + (rho >= 3 * R), hh = rho - gg * R;   // NG <= 4
-                const float M = fmaxf(fmaxf(stat_m[0][rho], stat_m[1][rho]), fmaxf(stat_m[2][rho], stat_m[3][rho]));
-                const float f = __builtin_amdgcn_exp2f(stat_m[w][rho] - M);
-                const float pzv = stat_pz[w][rho];
-#pragma unroll
-                for (int t = 0; t < 8; ++t) {
-                    if (((16 * t) >> lgGc) == gg) Os[w][hh][16 * t + n] = f * fmaf(O[t][i], 65536.f, pzv);
-                }
-            }
-        }
-    }
-    __syncthreads();
     const int64_t pbase = ((int64_t)ns * n_slots + split) * R;
-    for (int e = tid; e < R * kD; e += 256)   // waves added in order 0, 1, 2, 3 as before
-        a.part_o[pbase * kD + e] = (((&Os[0][0][0])[e] + (&Os[1][0][0])[e]) + (&Os[2][0][0])[e]) + (&Os[3][0][0])[e];
+    // pattern masses first: afterwards the table and mass area of the dynamic LDS is free for the outputs
     for (int e = tid; e < R * P; e += 256) {
         int hh = 0;
 #pragma unroll
@@ -516,6 +496,30 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
         for (int w = 0; w < 4; ++w) acc = fmaf(__builtin_amdgcn_exp2f(stat_m[w][hh] - M), (float)Ws[(w * R + hh) * WS + pp], acc);
         a.part_w[pbase * P + e] = acc * (1.f / kWUnit);
     }
+    __syncthreads();
+    // every wave leaves its outputs, scaled to the workgroup's reference, in a slab of its own: Os[4][R][kD] floats
+    // over the start of the dynamic LDS (the launch sizes it for that)
+    float *Os = reinterpret_cast<float *>(dyn_smem);
+    {
+        const int w = wave;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int rho = 4 * kb + i;
+            if (rho < R * NG) {
+                const int gg = (rho >= R) + (rho >= 2 * R) + (rho >= 3 * R), hh = rho - gg * R;   // NG <= 4
+                const float M = fmaxf(fmaxf(stat_m[0][rho], stat_m[1][rho]), fmaxf(stat_m[2][rho], stat_m[3][rho]));
+                const float f = __builtin_amdgcn_exp2f(stat_m[w][rho] - M);
+                const float pzv = stat_pz[w][rho];
+#pragma unroll
+                for (int t = 0; t < 8; ++t) {
+                    if (((16 * t) >> lgGc) == gg) Os[(w * R + hh) * kD + 16 * t + n] = f * fmaf(O[t][i], 65536.f, pzv);
+                }
+            }
+        }
+    }
+    __syncthreads();
+    for (int e = tid; e < R * kD; e += 256)   // waves added in order 0, 1, 2, 3
+        a.part_o[pbase * kD + e] = ((Os[e] + Os[R * kD + e]) + Os[2 * R * kD + e]) + Os[3 * R * kD + e];
     if (tid < R) {
         const float M = fmaxf(fmaxf(stat_m[0][tid], stat_m[1][tid]), fmaxf(stat_m[2][tid], stat_m[3][tid]));
         float L = 0.f;
@@ -544,7 +548,8 @@ hipError_t launch_decode_packed(const DecodeArgs &a, hipStream_t s)
     if (splits == 0) return hipSuccess;
     const dim3 grid(splits, a.n_seq * a.n_kv_heads);
     const int R = a.n_q_heads / a.n_kv_heads;
-    const size_t lds = (size_t)a.P * 16 * 4 + (size_t)4 * R * a.w_stride * 8;   // QMs, Ws
+    size_t lds = (size_t)a.P * 16 * 4 + (size_t)4 * R * a.w_stride * 8;   // QMs, Ws
+    if (lds < (size_t)4 * R * kD * 4) lds = (size_t)4 * R * kD * 4;               // reused for the four waves' outputs at the end
     if (a.bits == 2 && a.G == 32) return launch_one<2, true>(a, grid, lds, s);
     if (a.bits == 2) return launch_one<2, false>(a, grid, lds, s);
     if (a.bits == 4 && a.G == 32) return launch_one<4, true>(a, grid, lds, s);

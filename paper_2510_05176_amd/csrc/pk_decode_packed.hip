@@ -28,7 +28,6 @@ namespace pk {
 
 namespace {
 
-constexpr int kMaxP = 256;
 constexpr float kLog2e = 1.4426950408889634f;
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));

@@ -9,6 +9,7 @@ import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HEADER = os.path.join(ROOT, "include", "patternkv.h")
+PROBE_HEADER = os.path.join(ROOT, "include", "patternkv_probe.h")
 LIB = os.path.join(ROOT, "paper_2510_05176_amd", "libpatternkv.so")
 
 pytestmark = pytest.mark.skipif(not os.path.exists(LIB), reason="libpatternkv.so not built")
@@ -21,12 +22,13 @@ def pk():
 
 
 def test_exports_every_declared_symbol(pk):
-    src = open(HEADER).read()
+    src = open(HEADER).read() + open(PROBE_HEADER).read()
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
-    names = set(re.findall(r"\b(pk_[a-z_]+)\s*\(", src))
+    names = set(re.findall(r"\b(pk_[a-z0-9_]+)\s*\(", src))
     assert {"pk_mine_patterns", "pk_quantize_append", "pk_decode_attention", "pk_dequantize", "pk_cache_layout",
             "pk_workspace_bytes", "pk_status_string", "pk_abi_version", "pk_window_pattern",
-            "pk_decode_attention_ragged"} <= names
+            "pk_decode_attention_ragged", "pk_probe_read", "pk_probe_copy",
+            "pk_probe_fma_f32", "pk_probe_mfma_f16"} <= names
     lib = C.CDLL(LIB)
     for n in names:
         assert hasattr(lib, n), n

@@ -12,6 +12,7 @@
  *   pk_decode_attention   Sec. 3.4 "Decode-stage KV reconstruction": attention
  *                         computed directly on the packed cache
  *   pk_decode_attention_ragged  the same over sequences filled to different lengths
+ *   pk_decode_attention_noalloc the same with the partial results in a fixed array of the library
  *   pk_window_pattern     Sec. 3.1 "Decoding Stage", Eq. 5: the pattern of a window of
  *                         vectors (per-channel Chebyshev centre)
  *   pk_dequantize         the reconstruction rule below Eq. 6 (debug / parity)
@@ -22,7 +23,8 @@
  *   - Tensors are dense, row-major, last index fastest; fp16 = IEEE binary16.
  *   - The caller owns every byte, including the workspace.  The library never
  *     allocates or frees device memory, keeps no global state and retains no
- *     pointer after a call returns.
+ *     pointer after a call returns.  (One exception, by design:
+ *     pk_decode_attention_noalloc uses a fixed scratch array of the library.)
  *   - Calls enqueue work on `stream` (a hipStream_t passed as void*, NULL = the
  *     default stream) and return without synchronising.  pk_state is updated on
  *     the host at enqueue time.
@@ -249,6 +251,29 @@ pk_status pk_decode_attention_ragged(const pk_config *cfg, const pk_cache *cache
                                      const pk_state *prefix_state, const void *q, float softmax_scale,
                                      const void *patterns_k, const void *patterns_v, float *out, float *lse,
                                      void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * pk_decode_attention for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and results as
+ * pk_decode_attention without the workspace: the per-split partial results (outputs, per-pattern softmax mass,
+ * running maximum and sum) live in a fixed array of PK_NOALLOC_SCRATCH_BYTES inside the library's device image
+ * (one copy per GPU, held until the process ends).  The call allocates and frees nothing; on the first call
+ * on a device it looks up that device's copy of the array (hipGetSymbolAddress, with the calling thread's
+ * current device, which must be the device of `stream` and of all pointers).
+ *   - A decode whose partials (pk_workspace_bytes(cfg, PK_OP_DECODE, ...) for the cache's current fill) exceed
+ *     PK_NOALLOC_SCRATCH_BYTES is refused with PK_ERR_WORKSPACE before anything is launched.
+ *   - Every slot of the array that a call's merge reads was written by that call's own kernels first, so
+ *     nothing needs clearing and what an earlier call left behind is never read.
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different streams or
+ *     host threads) race on it.  Serialise them on one stream.
+ * Errors: as pk_decode_attention; PK_ERR_DEVICE if the device's array cannot be located.
+ */
+#define PK_NOALLOC_SCRATCH_BYTES (32u << 20)
+pk_status pk_decode_attention_noalloc(const pk_config *cfg, const pk_cache *cache, const pk_state *state,
+                                      const pk_config *prefix_cfg, const pk_cache *prefix,
+                                      const pk_state *prefix_state, const void *q, float softmax_scale,
+                                      const void *patterns_k, const void *patterns_v, float *out, float *lse,
+                                      void *stream);
 
 /*
  * Decode-stage pattern update (Sec. 3.1 "Decoding Stage", Eq. 5): for each of n_sets windows of n

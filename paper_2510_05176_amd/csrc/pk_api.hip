@@ -2,12 +2,36 @@
 // layout, workspace carving and kernel launches.  Nothing here allocates device memory
 // or synchronises with the device.
 #include <cstring>
+#include <mutex>
 
 #include "pk_internal.h"
 
 using namespace pk;
 
+// Partial results of pk_decode_attention_noalloc.  Part of the library's device image: every GPU the library
+// runs on holds its own copy at its own address until the process ends.  In host code this name is only a
+// handle for hipGetSymbolAddress; the address kernels are given is the one that call returns.
+static __device__ __align__(256) unsigned char scratch[PK_NOALLOC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices];   // per device: address of that device's copy of `scratch`, once looked up
+
+// Address of the current device's copy of the scratch array (looked up once per device), or nullptr.
+void *scratch_of_current_device()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline uint64_t round_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
@@ -373,6 +397,19 @@ pk_status pk_decode_attention_ragged(const pk_config *cfg, const pk_cache *cache
     if (bound->tail_start != 0) return PK_ERR_STATE;   // the bound carries sizes only; ring positions are per sequence
     return decode_impl(cfg, cache, bound, seq_states, prefix_cfg, prefix, prefix_state, q, softmax_scale, patterns_k,
                        patterns_v, out, lse, workspace, workspace_bytes, stream);
+}
+
+pk_status pk_decode_attention_noalloc(const pk_config *cfg, const pk_cache *cache, const pk_state *state,
+                                      const pk_config *prefix_cfg, const pk_cache *prefix, const pk_state *prefix_state,
+                                      const void *q, float softmax_scale, const void *patterns_k, const void *patterns_v,
+                                      float *out, float *lse, void *stream)
+{
+    void *ptr = scratch_of_current_device();
+    if (!ptr) return PK_ERR_DEVICE;
+    // decode_impl refuses a decode whose partials do not fit (PK_ERR_WORKSPACE) before launching anything; every
+    // partial slot the merge reads is written by this call's own kernels, so the array needs no clearing
+    return decode_impl(cfg, cache, state, nullptr, prefix_cfg, prefix, prefix_state, q, softmax_scale, patterns_k, patterns_v,
+                       out, lse, ptr, PK_NOALLOC_SCRATCH_BYTES, stream);
 }
 
 pk_status pk_window_pattern(const void *x, int64_t set_stride, int32_t n_sets, int32_t n, int32_t head_dim,

@@ -78,6 +78,11 @@ _lib.pk_decode_attention_ragged.argtypes = [C.POINTER(_Config), C.POINTER(_Cache
                                             C.POINTER(_Config), C.POINTER(_Cache), C.POINTER(_State), C.c_void_p,
                                             C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                             C.c_size_t, C.c_void_p]
+_lib.pk_decode_attention_noalloc.restype = C.c_int
+_lib.pk_decode_attention_noalloc.argtypes = [C.POINTER(_Config), C.POINTER(_Cache), C.POINTER(_State),
+                                             C.POINTER(_Config), C.POINTER(_Cache), C.POINTER(_State), C.c_void_p,
+                                             C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+NOALLOC_SCRATCH_BYTES = 32 << 20   # PK_NOALLOC_SCRATCH_BYTES
 _lib.pk_window_pattern.restype = C.c_int
 _lib.pk_window_pattern.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p]
 _lib.pk_dequantize.restype = C.c_int
@@ -285,6 +290,25 @@ def pk_decode_attention(cfg: Config, cache: Cache, q: torch.Tensor, softmax_scal
                                   C.c_float(softmax_scale), _ptr(patterns_k), _ptr(patterns_v), _ptr(out),
                                   _ptr(lse), _ptr(workspace), workspace.numel(), _stream())
     _check(st, "pk_decode_attention")
+    return out
+
+
+def pk_decode_attention_noalloc(cfg: Config, cache: Cache, q: torch.Tensor, softmax_scale: float,
+                                patterns_k: torch.Tensor, patterns_v: torch.Tensor, out: torch.Tensor,
+                                lse: torch.Tensor | None = None, prefix: Cache | None = None):
+    """pk_decode_attention with the partial results in the library's fixed scratch array: nothing is allocated,
+    here or in the library, so `out` [n_seq, n_q_heads, d] fp32 must be passed in."""
+    assert q.dtype == torch.float16 and out.dtype == torch.float32 and out.shape == q.shape
+    cc, kc = cfg.c(), cache.c()
+    if prefix is not None:
+        pc, pkc = prefix.cfg.c(), prefix.c()
+        pargs = (C.byref(pc), C.byref(pkc), C.byref(prefix.state))
+    else:
+        pargs = (None, None, None)
+    st = _lib.pk_decode_attention_noalloc(C.byref(cc), C.byref(kc), C.byref(cache.state), *pargs, _ptr(q),
+                                          C.c_float(softmax_scale), _ptr(patterns_k), _ptr(patterns_v), _ptr(out),
+                                          _ptr(lse), _stream())
+    _check(st, "pk_decode_attention_noalloc")
     return out
 
 

@@ -1,22 +1,32 @@
 #!/usr/bin/env python3
 """Benchmark of the PatternKV hot path on one MI355X.
 
-One "step" = one pass of the whole hot path over one batch of synthetic KV that is already resident
-in HBM: mine the K and V pattern tables (Lloyd iterations), quantize-append the whole context
-against them, run one decode-attention step over the packed cache for every query head.
+One "step" = one pass of the whole hot path over one batch of synthetic KV that is already resident in HBM:
+mine the K and V pattern tables (Lloyd iterations), quantize-append the whole context against them, run one
+decode-attention step over the packed cache for every query head.
 
-Prints ONE JSON line.  `value` is whole-path throughput (context tokens pushed through mining,
-quantize-append and decode per second); the per-stage figures the contract's metric names
-(quantize-append GB/s, decode-attention tokens/s, each as a fraction of the 8 TB/s HBM peak) are in
-`stages`.  `roofline` describes the stage kernel that takes the most time in a step; `stage_rooflines`
-has all three.  Per-stage durations come from HIP events recorded on the launch stream around each
-library call, with a cache flush (a 1 GiB fill, outside the events) before every timed call so that
-inputs come from HBM and not from the 256 MB Infinity Cache.
+Prints ONE JSON line.  The contract's metric has two quantities, KV quantize-append GB/s and decode-attention
+tokens/s on the 2-bit cache, each as a fraction of the 8 TB/s HBM peak: `value` is the decode-attention
+tokens/s (sequences of the batch that receive one token per decode step over all layers, divided by the time of
+the decode call), `quantize_append_GBps` the other one; `ms_per_step` is the wall-clock time of a whole step
+(mine + quantize-append + decode, back to back).  `roofline` describes the decode stage, `stage_rooflines` all
+three.  Per-stage durations come from HIP events recorded on the launch stream around each library call, with a
+cache flush (a 1 GiB fill, outside the events) before every timed call so that inputs come from HBM and not from
+the 256 MB Infinity Cache.
 
-Workloads (--workload): cfg2x32 (default: the contract's config 2 - Llama-3-8B-shaped layer, batch 1, T=8192,
-8 KV / 32 query heads, P=64, group 64 - for the model's 32 layers in one launch, 256 KV streams), cfg2 (one
-layer of it: 8 streams, launch-bound), cfg3 (32 layers x batch 16 x T=32768, P=128), cfg5 (T=131072, P=256),
-cfg4 (streaming: 64 samples over a shared 4096-token prompt cache, one token appended per step; use --steps 256).
+Default workload: cfg3, the contract's long-context batched decode (32 layers x batch 16 x T = 32768, 8 KV / 32
+query heads, P = 128, 2-bit, group 64, 128 recent fp16 tokens; 68.7 GB of fp16 source).  With the default
+workload the line also carries `sweep` (the same stages on cfg2x32 - config 2's layer for all 32 layers of the
+model in one launch -, cfg5, cfg4 at its full schedule of 8192 generated tokens with a decode after every
+append, and cfg2x32 with the min-max selection rule) and `measured_peaks` (streaming read / copy, fp32 FMA and
+fp16 MFMA loops on this GPU).
+
+Other modes (no GPU needed):
+  bench.py --summarise-trace RESULTS.db --cmd "..."            per-kernel table of a rocprofv3 --kernel-trace --stats run
+  bench.py --summarise-pmc FETCH.csv WRITE.csv --calls N --key K --cmd "..."
+        HBM bytes per library call from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) of
+        `bench.py --traffic-probe`; writes profiles/<key>_hbm_traffic.txt and updates profiles/hbm_traffic.json,
+        which `roofline.traffic` is read back from (a stored reading, not measured in the timed run).
 """
 import argparse
 import json
@@ -30,11 +40,15 @@ if ROOT not in sys.path:
 
 import numpy as np
 
+METRIC = "KV quantize-append GB/s and decode-attention tokens/s on 2-bit cache, % HBM peak"
 HBM_PEAK_GBPS = 8000.0
 MFMA_F16_PEAK_TFLOPS = 2500.0
+# vector-ALU lane operations per second for one-result-per-lane binary32 instructions (subtract, min, max):
+# 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz.  (The published 157.3 TFLOP/s counts 2 flops of an FMA and the
+# two halves of packed operations; a subtract or a maximum is one lane operation.)
+VALU_LANE_OPS_PEAK_T = 256 * 4 * 16 * 2.4e9 / 1e12
 
 WORKLOADS = {
-    # name: (spec key, layers, batch, P, iters, group, recent, flush, default bits)
     "cfg2": dict(spec="cfg2", layers=1, batch=1, P=64, iters=10, group=64, recent=0, flush=64),
     "cfg2x32": dict(spec="cfg2", layers=32, batch=1, P=64, iters=10, group=64, recent=0, flush=64),
     "cfg3": dict(spec="cfg3", layers=32, batch=16, P=128, iters=10, group=64, recent=128, flush=128),
@@ -42,17 +56,237 @@ WORKLOADS = {
     "cfg4": dict(spec="cfg4"),   # streaming: its own step, see run_streaming()
     "cfg3r": dict(spec="cfg3"),  # config 3's shape with a mix of sequence lengths: decode only, see run_ragged()
 }
+DECODE_KERNELS = "decode_packed_kernel(+decode_tail_kernel+decode_merge_kernel)"
 
 
-def run_streaming(args, torch, pk, synth):
+def stored_traffic(workload, bits):
+    """HBM bytes per library call from rocprofv3 --pmc runs of this script (see --summarise-pmc): stored readings."""
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if not os.path.exists(tpath):
+        return {}
+    return json.load(open(tpath)).get("%s_%dbit" % (workload, bits), {})
+
+
+def progress(msg):
+    """One line on stderr per finished part of the run (the JSON line on stdout stays the only output there)."""
+    print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
+
+
+def event_ms(torch, fn):
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    fn()
+    e1.record()
+    e1.synchronize()
+    return e0.elapsed_time(e1)
+
+
+# ------------------------------------------------------------------------------------------------------------
+def run_static(name, args, torch, pk, synth, steps, warmup, metric=None, cpu_baseline=False, traffic_probe=False):
+    """Mine, quantize-append the whole context, decode once; returns the result dictionary of the workload."""
+    dev = "cuda"
+    metric = pk.METRIC_L2 if metric is None else metric
+    w = WORKLOADS[name]
+    base = synth.SPECS[w["spec"]]
+    spec = synth.KVSpec(**{**base.__dict__, "n_layers": w["layers"], "batch": w["batch"]})
+    L, B, Hkv, Hq, T, d = w["layers"], w["batch"], spec.n_kv_heads, spec.n_q_heads, spec.T, spec.d
+    P, iters, G, R, F, bits = w["P"], w["iters"], w["group"], w["recent"], w["flush"], args.bits
+    n_seq = L * B
+    N = n_seq * Hkv
+    cap = (T - R) // F * F
+
+    # ---------------------------------------------------------------- inputs, resident in HBM
+    t_gen = time.time()
+    if n_seq == 1:
+        Kh, Vh = synth.make_kv(args.seed, spec)
+        K = torch.from_numpy(Kh.view(np.int16)).to(dev).view(torch.float16)
+        V = torch.from_numpy(Vh.view(np.int16)).to(dev).view(torch.float16)
+    else:
+        K = torch.empty((n_seq, Hkv, T, d), dtype=torch.float16, device=dev)
+        V = torch.empty_like(K)
+        one = synth.KVSpec(**{**spec.__dict__, "n_layers": 1})
+        for layer in range(L):
+            K[layer * B:(layer + 1) * B], V[layer * B:(layer + 1) * B] = synth.make_layer_device(args.seed, layer, one, dev)
+    q = torch.from_numpy(synth.make_queries(args.seed, n_seq, Hq, d).view(np.int16)).to(dev).view(torch.float16)
+    torch.cuda.synchronize()
+    t_gen = time.time() - t_gen
+    progress(f"{name}: inputs resident ({t_gen:.1f} s)")
+
+    cfg = pk.Config(n_seq=n_seq, n_kv_heads=Hkv, n_q_heads=Hq, head_dim=d, n_patterns=P,
+                    seqs_per_set=(B if L > 1 else 0), bits=bits, group=G, recent=R, flush=F, t_capacity=cap,
+                    metric=metric)
+    n_sets = cfg.n_sets
+    cache = pk.Cache(cfg)
+    Mk = torch.empty((n_sets, P, d), dtype=torch.float16, device=dev)
+    Mv = torch.empty_like(Mk)
+    out = torch.empty((n_seq, Hq, d), dtype=torch.float32, device=dev)
+    ws_mine = torch.empty(max(pk.pk_workspace_bytes(cfg, pk.OP_MINE, T, n_sets), 16), dtype=torch.uint8, device=dev)
+    ws_dec = torch.empty(max(pk.pk_workspace_bytes(cfg, pk.OP_DECODE, T, 0), 16), dtype=torch.uint8, device=dev)
+    flush_buf = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    scale = d ** -0.5
+
+    # mining reads the first batch element of every layer: for a batch > 1 those streams are gathered once, at
+    # set-up, into one uniformly strided tensor, so that all layers' tables are mined by one call per tensor
+    Kmine = K.view(n_sets, T, d) if B == 1 else K[::B].reshape(n_sets, T, d).contiguous()
+    Vmine = V.view(n_sets, T, d) if B == 1 else V[::B].reshape(n_sets, T, d).contiguous()
+
+    def mine():
+        pk.pk_mine_patterns(cfg, Kmine, iters, patterns=Mk, workspace=ws_mine)
+        pk.pk_mine_patterns(cfg, Vmine, iters, patterns=Mv, workspace=ws_mine)
+
+    def quantize():
+        cache.state.t_quant = cache.state.t_tail = cache.state.tail_start = 0
+        pk.pk_quantize_append(cfg, cache, K, V, Mk, Mv)
+
+    def decode():
+        pk.pk_decode_attention(cfg, cache, q, scale, Mk, Mv, out=out, workspace=ws_dec)
+
+    stages = [("mine", mine), ("quantize_append", quantize), ("decode_attention", decode)]
+
+    def timed_pass():
+        ms = {}
+        for sname, fn in stages:
+            flush_buf.fill_(1)
+            ms[sname] = event_ms(torch, fn)
+        return ms
+
+    for _ in range(warmup):
+        for _, fn in stages:
+            fn()
+    torch.cuda.synchronize()
+    # whole steps, back to back
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        for _, fn in stages:
+            fn()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
+    progress(f"{name}: {steps} whole steps timed, {ms_per_step:.3f} ms each")
+    # per-stage durations from HIP events, inputs evicted before every call
+    cold = [timed_pass() for _ in range(steps)]
+    progress(f"{name}: per-stage passes timed")
+    stage_ms = {sname: float(np.mean([c[sname] for c in cold])) for sname, _ in stages}
+    stage_ms_min = {sname: float(np.min([c[sname] for c in cold])) for sname, _ in stages}
+    assert cache.t_quant == cap and cache.t_tail == T - cap
+
+    # ---------------------------------------------------------------- algorithmic bytes / flops
+    Gc = min(G, d)
+    k_tok = bits * d / 8 + 2 * 2 * d / G + 1          # K: codes + (s,z) amortised over the group + index
+    v_tok = bits * d / 8 + 2 * 2 * d / Gc + 1         # V: codes + (s,z) per channel group + index
+    packed_per_tok = k_tok + v_tok                    # 82 B at 2 bits, group 64
+    quant_bytes = N * (cap * (2 * d * 2 + packed_per_tok) + (T - cap) * 2 * d * 2 * 2)   # tail: read + write
+    dec_bytes = N * (cap * packed_per_tok + (T - cap) * 2 * d * 2 + 2 * P * d * 2) + n_seq * Hq * d * (2 + 4)
+    mine_flops = 2.0 * T * P * d * (2 * L * Hkv) * iters
+    mine_bytes = 2.0 * L * Hkv * iters * T * d * 2            # per Lloyd iteration: one pass over x
+    traffic = stored_traffic(name, bits) if metric == pk.METRIC_L2 else {}
+
+    def roof(stage, bound, achieved, peak, unit, kernels):
+        return {"bound": bound, "achieved": round(achieved, 3), "peak": peak, "unit": unit,
+                "frac": round(achieved / peak, 4), "traffic": traffic.get(stage), "kernel": kernels}
+
+    # mining: the distance contraction is a dense GEMM only at large P; below that the pass over x binds
+    mine_s = stage_ms["mine"] * 1e-3
+    if P >= 256:
+        mine_roof = roof("mine", "mfma", mine_flops / mine_s / 1e12, MFMA_F16_PEAK_TFLOPS, "TFLOP/s", "mine_step_kernel")
+    else:
+        mine_roof = roof("mine", "hbm", mine_bytes / mine_s / 1e9, HBM_PEAK_GBPS, "GB/s", "mine_step_kernel")
+    q_s = stage_ms["quantize_append"] * 1e-3
+    if metric == pk.METRIC_L2:
+        q_roof = roof("quantize_append", "hbm", quant_bytes / q_s / 1e9, HBM_PEAK_GBPS, "GB/s",
+                      "quantize_k_wave_kernel+quantize_v_kernel")
+    else:
+        # d_mm of one vector against one pattern: d subtractions, d maxima, d minima in binary32 (Sec. 3.2)
+        lane_ops = 2.0 * N * cap * P * 3 * d
+        q_roof = roof("quantize_append", "alu", lane_ops / q_s / 1e12, round(VALU_LANE_OPS_PEAK_T, 2), "T lane-ops/s",
+                      "quantize_k_minmax_kernel+quantize_v_minmax_kernel")
+        q_roof["hbm_GB/s"] = round(quant_bytes / q_s / 1e9, 2)
+    rl = {
+        "mine": mine_roof,
+        "quantize_append": q_roof,
+        "decode_attention": roof("decode_attention", "hbm", dec_bytes / (stage_ms["decode_attention"] * 1e-3) / 1e9,
+                                 HBM_PEAK_GBPS, "GB/s", DECODE_KERNELS),
+    }
+    stage_out = {
+        "mine": {"ms": round(stage_ms["mine"], 4), "ms_min": round(stage_ms_min["mine"], 4),
+                 "TFLOP/s": round(mine_flops / mine_s / 1e12, 3), "GB/s": round(mine_bytes / mine_s / 1e9, 2)},
+        "quantize_append": {"ms": round(stage_ms["quantize_append"], 4), "ms_min": round(stage_ms_min["quantize_append"], 4),
+                            "GB/s": round(quant_bytes / q_s / 1e9, 3), "frac_hbm_peak": round(quant_bytes / q_s / 1e9 / HBM_PEAK_GBPS, 4),
+                            "algorithmic_bytes": int(quant_bytes)},
+        "decode_attention": {"ms": round(stage_ms["decode_attention"], 4), "ms_min": round(stage_ms_min["decode_attention"], 4),
+                             "GB/s": rl["decode_attention"]["achieved"], "frac_hbm_peak": rl["decode_attention"]["frac"],
+                             "tokens/s": round(B / (stage_ms["decode_attention"] * 1e-3), 2),
+                             "algorithmic_bytes": int(dec_bytes)},
+    }
+    result = {
+        "ms_per_step": round(ms_per_step, 4),
+        "config": {"workload": name, "layers": L, "batch": B, "n_kv_heads": Hkv, "n_q_heads": Hq, "T": T,
+                   "head_dim": d, "n_patterns": P, "lloyd_iters": iters, "bits": bits, "group": G, "recent": R,
+                   "flush": F, "metric": "L2" if metric == pk.METRIC_L2 else "MINMAX", "seed": args.seed},
+        "stages": stage_out,
+        "stage_rooflines": rl,
+        "input_generation_s": round(t_gen, 2),
+    }
+
+    # ---------------------------------------------------------------- the oracle on the host, bounded sample
+    if cpu_baseline:
+        from oracle import pk_oracle as oracle
+        heads = min(Hkv, 8)                                   # sample: the first `heads` KV heads of sequence 0
+        r = Hq // Hkv
+        Ts = min(T, 16384)
+        it_s = 1 if P >= 128 else min(iters, 4)               # about 10-30 s of host work in all
+        Ks = K[0, :heads, :Ts].cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+        Vs = V[0, :heads, :Ts].cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+        qs = q[0:1, :heads * r].cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+        caps = (Ts - R) // F * F
+        ocfg = oracle.Config(n_seq=1, n_kv_heads=heads, n_q_heads=heads * r, head_dim=d, n_patterns=P, seqs_per_set=0,
+                             bits=bits, group=G, recent=R, flush=F, t_capacity=caps,
+                             metric=0 if metric == pk.METRIC_L2 else 1)
+        t0 = time.perf_counter()
+        Mko, _, _, _ = oracle.mine(Ks, P, it_s)
+        Mvo, _, _, _ = oracle.mine(Vs, P, it_s)
+        t_mine_s = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        oc = oracle.Cache(ocfg)
+        oc.append(Ks[None], Vs[None], Mko, Mvo)
+        t_q = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        oracle.decode_attention(oc, qs, Mko, Mvo, scale)
+        t_d = time.perf_counter() - t0
+        progress(f"{name}: oracle sample timed on the host ({t_mine_s + t_q + t_d:.1f} s)")
+        # the sample scaled to the whole workload: streams, context length and Lloyd iterations are all linear
+        factor = (N / heads) * (T / Ts)
+        q_bytes_s = heads * (caps * (2 * d * 2 + packed_per_tok) + (Ts - caps) * 2 * d * 2 * 2)
+        result["cpu_baseline"] = {
+            "value": round(B / (t_d * factor), 4), "unit": "decode-attention tokens/s", "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": f"sequence 0 of layer 0: {heads} of {N} KV streams, the first {Ts} of {T} tokens, {it_s} of {iters} "
+                      f"Lloyd iterations; measured {t_mine_s + t_q + t_d:.2f} s; the decode time is scaled linearly to all "
+                      f"streams and the full context (extrapolated)",
+            "quantize_append_GB/s": round(q_bytes_s / t_q / 1e9, 4),
+            "mine_s_full_extrapolated": round(t_mine_s * (iters / it_s) * (L * Hkv / heads) * (T / Ts), 1),
+            "stage_seconds_sample": {"mine": round(t_mine_s, 3), "quantize_append": round(t_q, 3),
+                                     "decode_attention": round(t_d, 3)},
+        }
+    if traffic_probe:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(3)
+        dst = torch.empty_like(src)
+        flush_buf.fill_(2)
+        torch.cuda.synchronize()
+        torch.bitwise_not(src, out=dst)      # one dispatch: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+    return result
+
+
+# ------------------------------------------------------------------------------------------------------------
+def run_streaming(args, torch, pk, synth, gen0, steps, warm):
     """Config 4: 64 samples share a 4096-token prompt cache (patterns mined once on the prompt, P=64); every step
     appends one generated token per sample (flushed to the packed cache in 128-token chunks, group 32, 2 bits)
-    and runs decode attention over prompt + own cache.  A step here = one generation step of all samples."""
+    and runs decode attention over prompt + own cache.  A step here = one generation step of all samples; with
+    gen0 = 0 and steps = 8192 the run is the contract's whole schedule."""
     dev = "cuda"
     spec = synth.SPECS["cfg4"]
     S, Hkv, Hq, d, P, Tp, G, F, bits = spec.batch, spec.n_kv_heads, spec.n_q_heads, spec.d, 64, 4096, 32, 128, args.bits
-    gen0, steps, warm = args.gen_len, args.steps, args.warmup
-    t_all = gen0 + steps + warm
+    t_all = gen0 + steps
     cap = -(-t_all // F) * F
     pcfg = pk.Config(n_seq=1, n_kv_heads=Hkv, n_q_heads=Hq, head_dim=d, n_patterns=P, seqs_per_set=0, bits=bits,
                      group=G, recent=0, flush=F, t_capacity=Tp, metric=pk.METRIC_L2)
@@ -64,7 +298,6 @@ def run_streaming(args, torch, pk, synth):
     Mv = pk.pk_mine_patterns(pcfg, Vp[0], 10)
     pc, gc = pk.Cache(pcfg), pk.Cache(cfg)
     pk.pk_quantize_append(pcfg, pc, Kp, Vp, Mk, Mv)
-    pk.pk_quantize_append(cfg, gc, Kg[:, :, :gen0], Vg[:, :, :gen0], Mk, Mv)
     q = torch.from_numpy(synth.make_queries(args.seed, S, Hq, d).view(np.int16)).to(dev).view(torch.float16)
     out = torch.empty((S, Hq, d), dtype=torch.float32, device=dev)
     ws = torch.empty(max(pk.pk_workspace_bytes(cfg, pk.OP_DECODE, t_all, Tp), 16), dtype=torch.uint8, device=dev)
@@ -74,56 +307,50 @@ def run_streaming(args, torch, pk, synth):
         pk.pk_quantize_append(cfg, gc, Kg[:, :, t:t + 1], Vg[:, :, t:t + 1], Mk, Mv)
         pk.pk_decode_attention(cfg, gc, q, scale, Mk, Mv, out=out, workspace=ws, prefix=pc)
 
-    t = gen0
-    for _ in range(warm):
-        step(t)
-        t += 1
+    def reset():
+        gc.state.t_quant = gc.state.t_tail = gc.state.tail_start = 0
+        if gen0:
+            pk.pk_quantize_append(cfg, gc, Kg[:, :, :gen0], Vg[:, :, :gen0], Mk, Mv)
+
+    reset()
+    for i in range(warm):          # warm-up steps on the same cache, then the cache starts over
+        step(gen0 + i)
+    reset()
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     e0.record()
-    for _ in range(steps):
+    for t in range(gen0, gen0 + steps):
         step(t)
-        t += 1
     e1.record()
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
-    # the two calls on their own at the final length (HIP events on the launch stream, median of 20)
-    def med(fn):
-        v = []
-        for _ in range(20):
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record(); fn(); b.record(); b.synchronize()
-            v.append(a.elapsed_time(b))
-        return float(np.median(v))
-    dec_ms = med(lambda: pk.pk_decode_attention(cfg, gc, q, scale, Mk, Mv, out=out, workspace=ws, prefix=pc))
+    progress(f"cfg4: {steps} generation steps timed, {ms_per_step:.4f} ms each")
+    # the decode call on its own at the final length (HIP events on the launch stream, median of 20)
+    dec_ms = float(np.median([event_ms(torch, lambda: pk.pk_decode_attention(cfg, gc, q, scale, Mk, Mv, out=out, workspace=ws, prefix=pc))
+                              for _ in range(20)]))
     N = S * Hkv
     tq, tt = gc.t_quant, gc.t_tail
     per_tok = 2 * (bits * d / 8) + 2 * (2 * 2 * d / G) + 2
     dec_bytes = N * (tq * per_tok + tt * 2 * d * 2) + Hkv * (pc.t_quant * per_tok + 2 * P * d * 2) + S * Hq * d * 6
     flush_bytes = N * F * (2 * d * 2 + per_tok)
-    result = {
-        "metric": "KV quantize-append GB/s and decode-attention tokens/s on 2-bit cache, % HBM peak",
-        "value": round(S * steps / (ms_per_step * steps * 1e-3), 1),
-        "unit": "generated tokens/s (64 samples, one layer: append + decode attention per step)",
-        "n_gpus": 1, "steps": steps, "warmup": warm, "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16 in, f32 arithmetic, u%d codes" % bits,
-        "data": "synthetic",
+    roofl = {"bound": "hbm", "achieved": round(dec_bytes / dec_ms / 1e6, 3), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+             "frac": round(dec_bytes / dec_ms / 1e6 / HBM_PEAK_GBPS, 4), "traffic": None, "kernel": DECODE_KERNELS}
+    return {
+        "ms_per_step": round(ms_per_step, 4),
+        "generated_tokens/s": round(S / (ms_per_step * 1e-3), 1),
         "config": {"workload": "cfg4", "samples": S, "n_kv_heads": Hkv, "n_q_heads": Hq, "prompt_tokens": Tp,
-                   "generated_tokens_at_end": t, "head_dim": d, "n_patterns": P, "bits": bits, "group": G, "flush": F,
-                   "metric": "L2", "seed": args.seed},
+                   "generated_tokens_at_start": gen0, "generated_tokens_at_end": gen0 + steps, "head_dim": d,
+                   "n_patterns": P, "bits": bits, "group": G, "flush": F, "metric": "L2", "seed": args.seed},
         "stages": {"step_ms_events": round(e0.elapsed_time(e1) / steps, 4),
-                   "decode_attention": {"ms": round(dec_ms, 4), "GB/s": round(dec_bytes / dec_ms / 1e6, 2),
-                                        "frac_hbm_peak": round(dec_bytes / dec_ms / 1e6 / HBM_PEAK_GBPS, 4),
-                                        "tokens/s": round(S / (dec_ms * 1e-3), 1), "algorithmic_bytes": int(dec_bytes)},
+                   "decode_attention_at_end": {"ms": round(dec_ms, 4), "GB/s": roofl["achieved"], "frac_hbm_peak": roofl["frac"],
+                                               "tokens/s": round(S / (dec_ms * 1e-3), 1), "algorithmic_bytes": int(dec_bytes)},
                    "append_flush_bytes_every_128_steps": int(flush_bytes)},
-        "roofline": {"bound": "hbm", "achieved": round(dec_bytes / dec_ms / 1e6, 3), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(dec_bytes / dec_ms / 1e6 / HBM_PEAK_GBPS, 4), "traffic": None,
-                     "kernel": "decode_packed_kernel(+decode_tail_kernel+decode_merge_kernel)"},
+        "stage_rooflines": {"decode_attention": roofl},
     }
-    print(json.dumps(result))
 
 
+# ------------------------------------------------------------------------------------------------------------
 def run_ragged(args, torch, pk, synth):
     """Config 3's shape (32 layers x batch 16, 8 KV / 32 query heads, P=128, group 64, 128 recent fp16 tokens) with
     the batch's 16 sequences filled to different lengths, drawn once (seeded, uniform in [2048, 32768]; a sequence
@@ -176,46 +403,148 @@ def run_ragged(args, torch, pk, synth):
     cold = []
     for _ in range(args.steps):
         flush_buf.fill_(1)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(); decode(); e1.record(); e1.synchronize()
-        cold.append(e0.elapsed_time(e1))
+        cold.append(event_ms(torch, decode))
     dec_ms = float(np.mean(cold))
     per_tok = 2 * (bits * d / 8) + 2 * (2 * 2 * d / G) + 2
     dec_bytes = Hkv * sum(s[0] * per_tok + s[1] * 2 * d * 2 + 2 * P * d * 2 for s in states) + n_seq * Hq * d * 6
-    roof = {"bound": "hbm", "achieved": round(dec_bytes / dec_ms / 1e6, 3), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-            "frac": round(dec_bytes / dec_ms / 1e6 / HBM_PEAK_GBPS, 4), "traffic": None,
-            "kernel": "decode_packed_kernel(+decode_tail_kernel+decode_merge_kernel)"}
-    print(json.dumps({
-        "metric": "KV quantize-append GB/s and decode-attention tokens/s on 2-bit cache, % HBM peak",
-        "value": round(B / (ms_per_step * 1e-3), 1),
-        "unit": "generated tokens/s (one ragged decode step of the 16-sequence batch over all 32 layers)",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16 in, f32 arithmetic, u%d codes" % bits, "data": "synthetic",
+    roofl = {"bound": "hbm", "achieved": round(dec_bytes / dec_ms / 1e6, 3), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+             "frac": round(dec_bytes / dec_ms / 1e6 / HBM_PEAK_GBPS, 4), "traffic": None, "kernel": DECODE_KERNELS}
+    return {
+        "ms_per_step": round(ms_per_step, 4),
         "config": {"workload": "cfg3r", "layers": L, "batch": B, "n_kv_heads": Hkv, "n_q_heads": Hq, "lengths": lens,
                    "head_dim": d, "n_patterns": P, "bits": bits, "group": G, "recent": R, "flush": F, "metric": "L2",
                    "seed": args.seed},
         "stages": {"decode_attention": {"ms": round(dec_ms, 4), "ms_min": round(float(np.min(cold)), 4),
-                                        "GB/s": roof["achieved"], "frac_hbm_peak": roof["frac"],
+                                        "GB/s": roofl["achieved"], "frac_hbm_peak": roofl["frac"],
                                         "tokens/s": round(B / (dec_ms * 1e-3), 1), "algorithmic_bytes": int(dec_bytes)}},
-        "roofline": roof,
-    }))
+        "stage_rooflines": {"decode_attention": roofl},
+    }
 
 
+# ------------------------------------------------------------------------------------------------------------
+def measure_peaks(torch, pk):
+    """What this GPU sustains on four plain kernels (include/patternkv_probe.h): best of 5 runs each."""
+    import ctypes as C
+    lib = pk._lib
+    for fn in ("pk_probe_read", "pk_probe_copy", "pk_probe_fma_f32", "pk_probe_mfma_f16"):
+        getattr(lib, fn).restype = C.c_int
+    lib.pk_probe_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+    lib.pk_probe_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.pk_probe_fma_f32.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
+    lib.pk_probe_mfma_f16.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
+    stream = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    nbytes = 4 << 30
+    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty(nbytes // 2, dtype=torch.uint8, device="cuda")
+    sink = torch.empty(2048 * 256, dtype=torch.float32, device="cuda")
+    fma_iters, mfma_iters = 8192, 128
+
+    def best(fn):
+        fn()
+        torch.cuda.synchronize()
+        return min(event_ms(torch, fn) for _ in range(5))
+
+    def checked(rc):
+        assert rc == 0, rc
+
+    t_read = best(lambda: checked(lib.pk_probe_read(src.data_ptr(), nbytes, sink.data_ptr(), stream)))
+    t_copy = best(lambda: checked(lib.pk_probe_copy(dst.data_ptr(), src.data_ptr(), nbytes // 2, stream)))
+    t_fma = best(lambda: checked(lib.pk_probe_fma_f32(sink.data_ptr(), fma_iters, stream)))
+    t_mfma = best(lambda: checked(lib.pk_probe_mfma_f16(sink.data_ptr(), mfma_iters, stream)))
+    del src, dst
+    return {
+        "hbm_read_GB/s": round(nbytes / t_read / 1e6, 1), "hbm_copy_GB/s": round(nbytes / t_copy / 1e6, 1),
+        "fma_f32_TFLOP/s": round(2.0 * 16 * fma_iters * 2048 * 256 / t_fma / 1e9, 2),
+        "mfma_f16_TFLOP/s": round(2.0 * 16 * 16 * 32 * 8 * mfma_iters * 2048 * 4 / t_mfma / 1e9, 1),
+        "note": "read: 4 GiB streamed once; copy: 2 GiB read + 2 GiB written; fma: v_fma_f32 (no packed fp32 in this "
+                "build: half of the published 157.3 TFLOP/s is the ceiling); mfma: v_mfma_f32_16x16x32_f16, 8 "
+                "independent accumulators per wave",
+    }
+
+
+# ------------------------------------------------------------------------------------------------------------
+def summarise_trace(db, cmd):
+    import sqlite3
+    cur = sqlite3.connect(db).cursor()
+    print(f"command: {cmd}")
+    print(f"{'kernel':100s} {'calls':>6s} {'total_us':>12s} {'avg_us':>10s} {'pct':>6s}")
+    for kname, calls, tot, avg, pct in cur.execute("select * from top_kernels"):   # durations in microseconds
+        if "at::native" in kname or "rocclr" in kname:
+            continue
+        print(f"{kname[:100]:100s} {calls:6d} {tot:12.1f} {avg:10.2f} {pct:6.2f}")
+
+
+def summarise_pmc(fetch_csv, write_csv, n_calls, key, cmd):
+    import collections
+    import csv
+
+    def load(path, counter):
+        tot, cnt = collections.defaultdict(float), collections.Counter()
+        for r in csv.DictReader(open(path)):
+            if r["Counter_Name"] != counter:
+                continue
+            tot[r["Kernel_Name"]] += float(r["Counter_Value"])
+            cnt[r["Kernel_Name"]] += 1
+        return tot, cnt
+
+    F, Fc = load(fetch_csv, "FETCH_SIZE")
+    W, Wc = load(write_csv, "WRITE_SIZE")
+    copyk = [k for k in F if "bitwise_not" in k]
+    assert len(copyk) == 1 and Fc[copyk[0]] == 1, "the 1 GiB copy of --traffic-probe was not found"
+    ck = copyk[0]
+    f_scale, w_scale = float(1 << 20) / (F[ck] / Fc[ck]), float(1 << 20) / (W[ck] / Wc[ck])
+    stages = {"mine": ["mine_"], "quantize_append": ["quantize_", "tail_copy"], "decode_attention": ["decode_"]}
+    res = {}
+    lines = [f"command (run twice, --pmc FETCH_SIZE and --pmc WRITE_SIZE): {cmd}",
+             f"copy kernel: {ck[:80]}: FETCH_SIZE {F[ck] / Fc[ck]:.0f} KiB, WRITE_SIZE {W[ck] / Wc[ck]:.0f} KiB for 1048576 KiB "
+             f"each way -> scale {f_scale:.4f} / {w_scale:.4f}",
+             f"library calls per stage in the run: {n_calls}", "",
+             f"{'kernel':70s} {'disp':>6s} {'fetch KiB/disp':>15s} {'write KiB/disp':>15s}"]
+    for st, subs in stages.items():
+        fb = wb = 0.0
+        for k in sorted(F):
+            if any(s in k for s in subs):
+                fb += F[k] * f_scale
+                wb += W.get(k, 0.0) * w_scale
+                lines.append(f"{k[:70]:70s} {Fc[k]:6d} {F[k] / Fc[k] * f_scale:15.1f} {W.get(k, 0.0) / max(Wc.get(k, 1), 1) * w_scale:15.1f}")
+        res[st] = int((fb + wb) * 1024 / n_calls)
+        lines.append(f"  => {st}: {res[st] / 1e6:.2f} MB per library call (fetch {fb * 1024 / n_calls / 1e6:.2f} + write {wb * 1024 / n_calls / 1e6:.2f})")
+    out_json = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    allj = json.load(open(out_json)) if os.path.exists(out_json) else {}
+    allj[key] = res
+    json.dump(allj, open(out_json, "w"), indent=1, sort_keys=True)
+    open(os.path.join(ROOT, "profiles", key + "_hbm_traffic.txt"), "w").write("\n".join(lines) + "\n")
+    print("\n".join(lines))
+
+
+# ------------------------------------------------------------------------------------------------------------
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="cfg2x32", choices=sorted(WORKLOADS))
+    ap.add_argument("--workload", default="cfg3", choices=sorted(WORKLOADS))
     ap.add_argument("--bits", type=int, default=2, choices=[2, 4])
+    ap.add_argument("--metric", default="l2", choices=["l2", "minmax"],
+                    help="pattern selection rule of quantize-append: l2 (matrix cores) or minmax (d_mm of Sec. 3.2, vector ALUs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sweep", action="store_true", help="default workload only: leave out the other configs")
+    ap.add_argument("--no-peaks", action="store_true")
     ap.add_argument("--seed", type=int, default=2)
-    ap.add_argument("--gen-len", type=int, default=4096, help="cfg4: generated tokens per sample before the timed steps")
+    ap.add_argument("--gen-len", type=int, default=0, help="cfg4: generated tokens per sample before the timed steps")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="also run one 1 GiB elementwise copy kernel (bitwise_not) at the end: the known traffic that "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings of this command are scaled by")
+    ap.add_argument("--summarise-trace", metavar="DB")
+    ap.add_argument("--summarise-pmc", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"))
+    ap.add_argument("--calls", type=int, default=1)
+    ap.add_argument("--key", default="")
+    ap.add_argument("--cmd", default="")
     args = ap.parse_args()
+    if args.summarise_trace:
+        return summarise_trace(args.summarise_trace, args.cmd)
+    if args.summarise_pmc:
+        return summarise_pmc(args.summarise_pmc[0], args.summarise_pmc[1], args.calls, args.key, args.cmd)
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus must be 1 (no sharding or collectives are part of it)",
               file=sys.stderr)
@@ -228,202 +557,65 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    metric = pk.METRIC_L2 if args.metric == "l2" else pk.METRIC_MINMAX
+    common = {"metric": METRIC, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "higher_is_better": True,
+              "scaling": "weak", "vs_baseline": None, "dtype": "f16 in, f32 arithmetic, u%d codes" % args.bits,
+              "data": "synthetic"}
+
     if args.workload == "cfg4":
-        return run_streaming(args, torch, pk, synth)
+        steps = args.steps if args.steps > 20 else 8192      # the contract's schedule unless a step count is asked for
+        r = run_streaming(args, torch, pk, synth, args.gen_len, steps, args.warmup)
+        line = {**common, "steps": steps, "value": r["generated_tokens/s"],
+                "unit": "generated tokens/s (64 samples, one layer: one append + one decode attention per sample and step)",
+                **r, "roofline": r["stage_rooflines"]["decode_attention"]}
+        print(json.dumps(line))
+        return
     if args.workload == "cfg3r":
-        return run_ragged(args, torch, pk, synth)
-    dev = "cuda"
-    w = WORKLOADS[args.workload]
-    base = synth.SPECS[w["spec"]]
-    spec = synth.KVSpec(**{**base.__dict__, "n_layers": w["layers"], "batch": w["batch"]})
-    L, B, Hkv, Hq, T, d = w["layers"], w["batch"], spec.n_kv_heads, spec.n_q_heads, spec.T, spec.d
-    P, iters, G, R, F, bits = w["P"], w["iters"], w["group"], w["recent"], w["flush"], args.bits
-    n_seq = L * B
-    N = n_seq * Hkv
-    cap = (T - R) // F * F
+        r = run_ragged(args, torch, pk, synth)
+        line = {**common, "value": r["stages"]["decode_attention"]["tokens/s"],
+                "unit": "decode-attention tokens/s (one ragged decode step of the 16-sequence batch over all 32 layers)",
+                **r, "roofline": r["stage_rooflines"]["decode_attention"]}
+        print(json.dumps(line))
+        return
 
-    # ---------------------------------------------------------------- inputs, resident in HBM
-    t_gen = time.time()
-    if n_seq == 1:
-        Kh, Vh = synth.make_kv(args.seed, spec)
-        K = torch.from_numpy(Kh.view(np.int16)).to(dev).view(torch.float16)
-        V = torch.from_numpy(Vh.view(np.int16)).to(dev).view(torch.float16)
-    else:
-        K = torch.empty((n_seq, Hkv, T, d), dtype=torch.float16, device=dev)
-        V = torch.empty_like(K)
-        one = synth.KVSpec(**{**spec.__dict__, "n_layers": 1})
-        for layer in range(L):
-            K[layer * B:(layer + 1) * B], V[layer * B:(layer + 1) * B] = synth.make_layer_device(args.seed, layer, one, dev)
-    q = torch.from_numpy(synth.make_queries(args.seed, n_seq, Hq, d).view(np.int16)).to(dev).view(torch.float16)
-    torch.cuda.synchronize()
-    t_gen = time.time() - t_gen
+    r = run_static(args.workload, args, torch, pk, synth, args.steps, args.warmup, metric=metric,
+                   cpu_baseline=not args.no_cpu_baseline, traffic_probe=args.traffic_probe)
+    c = r["config"]
+    line = {**common,
+            "value": r["stages"]["decode_attention"]["tokens/s"],
+            "unit": f"decode-attention tokens/s ({c['batch']} sequence(s) x one token per decode step over all {c['layers']} "
+                    f"layer(s), {args.bits}-bit cache; = batch / time of the decode call)",
+            "quantize_append_GBps": r["stages"]["quantize_append"]["GB/s"],
+            "ms_per_step_covers": "mine + quantize-append + decode, back to back (wall clock)",
+            **r, "roofline": r["stage_rooflines"]["decode_attention"]}
+    torch.cuda.empty_cache()
 
-    cfg = pk.Config(n_seq=n_seq, n_kv_heads=Hkv, n_q_heads=Hq, head_dim=d, n_patterns=P,
-                    seqs_per_set=(B if L > 1 else 0), bits=bits, group=G, recent=R, flush=F, t_capacity=cap,
-                    metric=pk.METRIC_L2)
-    n_sets = cfg.n_sets
-    cache = pk.Cache(cfg)
-    Mk = torch.empty((n_sets, P, d), dtype=torch.float16, device=dev)
-    Mv = torch.empty_like(Mk)
-    out = torch.empty((n_seq, Hq, d), dtype=torch.float32, device=dev)
-    ws_mine = torch.empty(max(pk.pk_workspace_bytes(cfg, pk.OP_MINE, T, n_sets), 16), dtype=torch.uint8, device=dev)
-    ws_dec = torch.empty(max(pk.pk_workspace_bytes(cfg, pk.OP_DECODE, T, 0), 16), dtype=torch.uint8, device=dev)
-    flush_buf = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
-    scale = d ** -0.5
-
-    # mining reads the first batch element of every layer: for a batch > 1 those streams are gathered once, at
-    # set-up, into one uniformly strided tensor, so that all layers' tables are mined by one call per tensor
-    Kmine = K.view(n_sets, T, d) if B == 1 else K[::B].reshape(n_sets, T, d).contiguous()
-    Vmine = V.view(n_sets, T, d) if B == 1 else V[::B].reshape(n_sets, T, d).contiguous()
-
-    def mine():
-        pk.pk_mine_patterns(cfg, Kmine, iters, patterns=Mk, workspace=ws_mine)
-        pk.pk_mine_patterns(cfg, Vmine, iters, patterns=Mv, workspace=ws_mine)
-
-    def quantize():
-        cache.state.t_quant = cache.state.t_tail = cache.state.tail_start = 0
-        pk.pk_quantize_append(cfg, cache, K, V, Mk, Mv)
-
-    def decode():
-        pk.pk_decode_attention(cfg, cache, q, scale, Mk, Mv, out=out, workspace=ws_dec)
-
-    stages = [("mine", mine), ("quantize_append", quantize), ("decode_attention", decode)]
-
-    def timed_pass(cold):
-        ms = {}
-        for name, fn in stages:
-            if cold:
-                flush_buf.fill_(1)
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            fn()
-            e1.record()
-            e1.synchronize()
-            ms[name] = e0.elapsed_time(e1)
-        return ms
-
-    for _ in range(args.warmup):
-        for _, fn in stages:
-            fn()
-    torch.cuda.synchronize()
-    # whole steps, back to back
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        for _, fn in stages:
-            fn()
-    torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
-    # per-stage durations from HIP events, inputs evicted before every call
-    cold = [timed_pass(True) for _ in range(args.steps)]
-    stage_ms = {name: float(np.mean([c[name] for c in cold])) for name, _ in stages}
-    stage_ms_min = {name: float(np.min([c[name] for c in cold])) for name, _ in stages}
-    assert cache.t_quant == cap and cache.t_tail == T - cap
-
-    # ---------------------------------------------------------------- algorithmic bytes / flops
-    Gc = min(G, d)
-    k_tok = bits * d / 8 + 2 * 2 * d / G + 1          # K: codes + (s,z) amortised over the group + index
-    v_tok = bits * d / 8 + 2 * 2 * d / Gc + 1         # V: codes + (s,z) per channel group + index
-    packed_per_tok = k_tok + v_tok                    # 82 B at 2 bits, group 64
-    quant_bytes = N * (cap * (2 * d * 2 + packed_per_tok) + (T - cap) * 2 * d * 2 * 2)   # tail: read + write
-    dec_bytes = N * (cap * packed_per_tok + (T - cap) * 2 * d * 2 + 2 * P * d * 2) + n_seq * Hq * d * (2 + 4)
-    mine_flops = 2.0 * T * P * d * (2 * L * Hkv) * iters
-    mine_bytes = 2.0 * L * Hkv * iters * T * d * 2            # per Lloyd iteration: one pass over x
-
-    # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE, scaled by a copy of known
-    # size): written by profiles/collect_traffic.py from runs of this script, read back here
-    traffic = {}
-    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-    if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get("%s_%dbit" % (args.workload, bits), {})
-
-    def roof(stage, bound, achieved, peak, unit, kernels):
-        return {"bound": bound, "achieved": round(achieved, 3), "peak": peak, "unit": unit,
-                "frac": round(achieved / peak, 4), "traffic": traffic.get(stage), "kernel": kernels}
-
-    # mining: the distance contraction is a dense GEMM only at large P; below that the pass over x binds
-    mine_s = stage_ms["mine"] * 1e-3
-    if P >= 256:
-        mine_roof = roof("mine", "mfma", mine_flops / mine_s / 1e12, MFMA_F16_PEAK_TFLOPS, "TFLOP/s", "mine_step_kernel")
-    else:
-        mine_roof = roof("mine", "hbm", mine_bytes / mine_s / 1e9, HBM_PEAK_GBPS, "GB/s", "mine_step_kernel")
-    rl = {
-        "mine": mine_roof,
-        "quantize_append": roof("quantize_append", "hbm", quant_bytes / (stage_ms["quantize_append"] * 1e-3) / 1e9,
-                                HBM_PEAK_GBPS, "GB/s", "quantize_k_wave_kernel+quantize_v_kernel"),
-        "decode_attention": roof("decode_attention", "hbm", dec_bytes / (stage_ms["decode_attention"] * 1e-3) / 1e9,
-                                 HBM_PEAK_GBPS, "GB/s", "decode_packed_kernel(+decode_tail_kernel+decode_merge_kernel)"),
-    }
-    dominant = max(stage_ms, key=stage_ms.get)
-    stage_out = {
-        "mine": {"ms": round(stage_ms["mine"], 4), "ms_min": round(stage_ms_min["mine"], 4),
-                 "TFLOP/s": round(mine_flops / mine_s / 1e12, 3), "GB/s": round(mine_bytes / mine_s / 1e9, 2)},
-        "quantize_append": {"ms": round(stage_ms["quantize_append"], 4), "ms_min": round(stage_ms_min["quantize_append"], 4),
-                            "GB/s": rl["quantize_append"]["achieved"], "frac_hbm_peak": rl["quantize_append"]["frac"],
-                            "algorithmic_bytes": int(quant_bytes)},
-        "decode_attention": {"ms": round(stage_ms["decode_attention"], 4), "ms_min": round(stage_ms_min["decode_attention"], 4),
-                             "GB/s": rl["decode_attention"]["achieved"], "frac_hbm_peak": rl["decode_attention"]["frac"],
-                             "tokens/s": round(B / (stage_ms["decode_attention"] * 1e-3), 2),
-                             "algorithmic_bytes": int(dec_bytes)},
-    }
-
-    result = {
-        "metric": "KV quantize-append GB/s and decode-attention tokens/s on 2-bit cache, % HBM peak",
-        "value": round(n_seq * T / (ms_per_step * 1e-3), 1),
-        "unit": "context tokens/s through the whole path (mine + quantize-append + decode)",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16 in, f32 arithmetic, u%d codes" % bits,
-        "data": "synthetic",
-        "config": {"workload": args.workload, "layers": L, "batch": B, "n_kv_heads": Hkv, "n_q_heads": Hq, "T": T,
-                   "head_dim": d, "n_patterns": P, "lloyd_iters": iters, "bits": bits, "group": G, "recent": R,
-                   "flush": F, "metric": "L2", "seed": args.seed},
-        "stages": stage_out,
-        "roofline": rl[dominant],
-        "stage_rooflines": rl,
-        "input_generation_s": round(t_gen, 2),
-    }
-
-    # ---------------------------------------------------------------- the oracle on the host, bounded sample
-    if not args.no_cpu_baseline:
-        from oracle import pk_oracle as oracle
-        heads = min(Hkv, 8)                                   # sample: the first `heads` KV heads of sequence 0
-        r = Hq // Hkv
-        Ks = K[0, :heads].cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
-        Vs = V[0, :heads].cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
-        qs = q[0:1, :heads * r].cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
-        Ts = min(T, 16384)
-        it_s = min(iters, 4)
-        Ks, Vs = np.ascontiguousarray(Ks[:, :Ts]), np.ascontiguousarray(Vs[:, :Ts])
-        ocfg = oracle.Config(n_seq=1, n_kv_heads=heads, n_q_heads=heads * r, head_dim=d, n_patterns=P, seqs_per_set=0,
-                             bits=bits, group=G, recent=R, flush=F, t_capacity=(Ts - R) // F * F, metric=0)
-        t0 = time.perf_counter()
-        Mko, _, _, _ = oracle.mine(Ks, P, it_s)
-        Mvo, _, _, _ = oracle.mine(Vs, P, it_s)
-        t_mine = (time.perf_counter() - t0) * iters / it_s
-        t0 = time.perf_counter()
-        oc = oracle.Cache(ocfg)
-        oc.append(Ks[None], Vs[None], Mko, Mvo)
-        t_q = time.perf_counter() - t0
-        t0 = time.perf_counter()
-        oracle.decode_attention(oc, qs, Mko, Mvo, scale)
-        t_d = time.perf_counter() - t0
-        # scale the sample to the whole workload: streams and context length are both linear
-        factor = (N / heads) * (T / Ts)
-        t_full = (t_mine * (L * Hkv / heads) * (T / Ts)) + (t_q + t_d) * factor
-        result["cpu_baseline"] = {
-            "value": round(n_seq * T / t_full, 2), "unit": result["unit"], "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": f"{heads} of {N} KV streams, {Ts} of {T} tokens, {it_s} of {iters} Lloyd iterations; "
-                      f"measured {t_mine * it_s / iters + t_q + t_d:.2f} s, scaled linearly to the full workload",
-            "stage_seconds_sample": {"mine": round(t_mine * it_s / iters, 3), "quantize_append": round(t_q, 3),
-                                     "decode_attention": round(t_d, 3)},
-        }
-    if args.traffic_probe:
-        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(3)
-        dst = torch.empty_like(src)
-        flush_buf.fill_(2)
-        torch.cuda.synchronize()
-        torch.bitwise_not(src, out=dst)      # one dispatch: reads 1 GiB, writes 1 GiB
-        torch.cuda.synchronize()
-    print(json.dumps(result))
+    if args.workload == "cfg3" and not args.no_sweep and metric == pk.METRIC_L2:
+        sweep = {}
+        for wname in ("cfg2x32", "cfg5"):
+            s = run_static(wname, args, torch, pk, synth, 10, 2)
+            torch.cuda.empty_cache()
+            sweep[wname] = {st: {"ms": s["stages"][st]["ms"], "bound": s["stage_rooflines"][st]["bound"],
+                                 "achieved": s["stage_rooflines"][st]["achieved"], "unit": s["stage_rooflines"][st]["unit"],
+                                 "frac": s["stage_rooflines"][st]["frac"]} for st in s["stages"]}
+            sweep[wname]["decode_attention"]["tokens/s"] = s["stages"]["decode_attention"]["tokens/s"]
+        s = run_streaming(args, torch, pk, synth, 0, 8192, 8)
+        torch.cuda.empty_cache()
+        sweep["cfg4"] = {"schedule": "64 samples x 8192 generated tokens over a shared 4096-token prompt; one append and one "
+                                     "decode per step, a 128-token flush every 128 steps",
+                         "ms_per_step": s["ms_per_step"], "generated_tokens/s": s["generated_tokens/s"],
+                         "decode_attention_at_end": {k: s["stages"]["decode_attention_at_end"][k] for k in ("ms", "GB/s", "frac_hbm_peak")}}
+        s = run_static("cfg2x32", args, torch, pk, synth, 5, 1, metric=pk.METRIC_MINMAX)
+        torch.cuda.empty_cache()
+        rq = s["stage_rooflines"]["quantize_append"]
+        sweep["cfg2x32_minmax"] = {"quantize_append": {"ms": s["stages"]["quantize_append"]["ms"], "bound": rq["bound"],
+                                                       "achieved": rq["achieved"], "unit": rq["unit"], "peak": rq["peak"],
+                                                       "frac": rq["frac"], "hbm_GB/s": rq["hbm_GB/s"]}}
+        line["sweep"] = sweep
+    if not args.no_peaks:
+        line["measured_peaks"] = measure_peaks(torch, pk)
+        progress("peak probes done")
+    print(json.dumps(line))
 
 
 if __name__ == "__main__":

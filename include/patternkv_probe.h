@@ -34,6 +34,12 @@ int pk_probe_fma_f32(float *sink, int32_t iters, void *stream);
  * v_mfma_f32_16x16x32_f16.  Flops: 2 * 16 * 16 * 32 * 8 * iters * 2048 * 4.  sink: at least 2048 * 256 floats. */
 int pk_probe_mfma_f16(float *sink, int32_t iters, void *stream);
 
+/* The quantizer's two division sequences (Sec. 2.1 Eq. 1: s = (max - z)/(2^b - 1), and 1/s), which replace the
+ * IEEE divisions by a reciprocal estimate with one correction step, evaluated on n plain values so that a test
+ * can compare them with IEEE division: recip[i] = 1/x[i] (meant for positive fp16-representable x),
+ * by3[i] = x[i]/3, by15[i] = x[i]/15 (finite x >= 0).  All arrays hold n floats. */
+int pk_probe_divisions(const float *x, size_t n, float *recip, float *by3, float *by15, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

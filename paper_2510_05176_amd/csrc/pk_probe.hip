@@ -1,9 +1,12 @@
 // Machine-peak probes (include/patternkv_probe.h): streaming read, streaming copy, an fp32 FMA loop and an
 // fp16 MFMA loop.  Measurement aids for the benchmark; the hot path does not use them.
+#pragma clang fp contract(off)   // as in the quantizer: the division sequences below run exactly as written
+
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
 #include "patternkv_probe.h"
+#include "pk_divide.h"
 
 namespace {
 
@@ -94,6 +97,18 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(float *sink, int iters)
     sink[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
 }
 
+// the quantizer's two division sequences, evaluated on plain arrays
+__global__ __launch_bounds__(256) void probe_divisions_kernel(const float *x, size_t n, float *recip, float *by3, float *by15)
+{
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
+        const float v = x[i];
+        recip[i] = pk::recip_of_scale(v);
+        by3[i] = pk::div_by_levels(v, 2);
+        by15[i] = pk::div_by_levels(v, 4);
+    }
+}
+
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 }  // namespace
@@ -127,6 +142,13 @@ int pk_probe_mfma_f16(float *sink, int32_t iters, void *stream)
 {
     if (!sink || iters < 1 || !aligned16(sink)) return 1;
     hipLaunchKernelGGL(probe_mfma_kernel, dim3(kGroups), dim3(256), 0, static_cast<hipStream_t>(stream), sink, iters);
+    return hipGetLastError() == hipSuccess ? 0 : 8;
+}
+
+int pk_probe_divisions(const float *x, size_t n, float *recip, float *by3, float *by15, void *stream)
+{
+    if (!x || !recip || !by3 || !by15 || n == 0) return 1;
+    hipLaunchKernelGGL(probe_divisions_kernel, dim3(kGroups), dim3(256), 0, static_cast<hipStream_t>(stream), x, n, recip, by3, by15);
     return hipGetLastError() == hipSuccess ? 0 : 8;
 }
 

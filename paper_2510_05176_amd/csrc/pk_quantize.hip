@@ -11,6 +11,7 @@
 
 #include "pk_assign.h"
 #include "pk_assign_mfma.h"
+#include "pk_divide.h"
 #include "pk_internal.h"
 
 namespace pk {
@@ -21,26 +22,6 @@ struct GroupParams {
     unsigned short s16, z16;
     float s, z, inv;
 };
-
-// The two divisions of the definition, each correctly rounded like the IEEE operation but in three
-// instructions: a reciprocal estimate and one Newton correction (1/s, s a positive fp16 value), or a multiply
-// by the rounded reciprocal of the constant and one residual correction (x / (2^b - 1), x >= 0 finite).
-// Checked on the GPU against the compiler's IEEE division for every positive fp16 s and for all 2^23
-// mantissas of x over 51 binades, divisors 3 and 15: no mismatch.
-__device__ __forceinline__ float recip_of_scale(float s)
-{
-    const float r = __builtin_amdgcn_rcpf(s);
-    const float e = fmaf(-s, r, 1.f);
-    const float q = fmaf(e, r, r);
-    return s < INFINITY ? q : 0.f;   // a scale that overflowed fp16: 1/inf
-}
-__device__ __forceinline__ float div_by_levels(float x, int bits)
-{
-    const float L = (float)((1 << bits) - 1), c = 1.0f / L;   // c: compile-time rounded reciprocal
-    const float q = x * c;
-    const float r = fmaf(-L, q, x);
-    return fmaf(r, c, q);
-}
 
 __device__ __forceinline__ GroupParams group_params(float mn, float mx, int bits)
 {

@@ -28,7 +28,7 @@ def test_exports_every_declared_symbol(pk):
     assert {"pk_mine_patterns", "pk_quantize_append", "pk_decode_attention", "pk_dequantize", "pk_cache_layout",
             "pk_workspace_bytes", "pk_status_string", "pk_abi_version", "pk_window_pattern",
             "pk_decode_attention_ragged", "pk_decode_attention_noalloc", "pk_probe_read", "pk_probe_copy",
-            "pk_probe_fma_f32", "pk_probe_mfma_f16"} <= names
+            "pk_probe_fma_f32", "pk_probe_mfma_f16", "pk_probe_divisions"} <= names
     lib = C.CDLL(LIB)
     for n in names:
         assert hasattr(lib, n), n

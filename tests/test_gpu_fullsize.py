@@ -11,7 +11,7 @@ import numpy as np
 import pytest
 
 from paper_2510_05176_amd import synth
-from test_gpu_parity import compare_caches, dev, host_u16, rel_l2   # noqa: F401  (shared helpers)
+from test_gpu_parity import _mining_step_parity, assert_attention, compare_caches, dev, host_u16   # noqa: F401  (shared helpers)
 
 pytestmark = pytest.mark.gpu
 
@@ -58,7 +58,7 @@ def check_stream(oracle, pk, gc, gcfg, kw, K, V, Mk, Mv, q, out, seq, head, appe
     qs = host_u16(q[seq, head * r:(head + 1) * r])[None]
     want, _ = oracle.decode_attention(oc, qs, Mks, Mvs, 128 ** -0.5)
     got = out[seq, head * r:(head + 1) * r].cpu().numpy()[None]
-    assert rel_l2(got, want) <= 2e-3
+    assert_attention(got, want)
     return n_diff
 
 
@@ -168,4 +168,93 @@ def test_config4_streaming_appends_over_shared_prompt(oracle, pk):
         want, _ = oracle.decode_attention(ooc, qs, Mks, Mvs, d ** -0.5, prefix=opc, prefix_patterns_k=Mks,
                                           prefix_patterns_v=Mvs)
         got = out[seq, head * r:(head + 1) * r].cpu().numpy()[None]
-        assert rel_l2(got, want) <= 2e-3
+        assert_attention(got, want)
+
+
+def test_config5_mining_launch(oracle, pk):
+    """Config 5's mining launch: 4 sets x 131072 vectors at P = 256 (64 chunks of 2048 vectors = 8 sub-tiles of the
+    8-wave kernel per set).  The GPU runs two Lloyd iterations over all four sets; the oracle checks one set per
+    iteration from the same centroids (assignments bit for bit outside the near-tie band, centroids within one
+    fp16 step, objective)."""
+    spec = synth.SPECS["cfg5"]
+    K, _ = synth.make_kv(5, spec)
+    x = K[0]                                                   # [4, 131072, 128]
+    cur = x[:, :256].copy().view(np.uint16)
+    for it, s in enumerate((2, 2)):
+        new = _mining_step_parity(oracle, pk, x, 256, cur, check_sets=[s])
+        cur = cur.copy()
+        cur[s] = new[s]                                        # set 2 moves on with the oracle's centroids
+
+
+def test_config3_mining_launch(oracle, pk):
+    """Config 3's mining launch: 256 sets (32 layers x 8 KV heads) x 32768 vectors at P = 128, two chunks of 16384
+    vectors = 128 sub-tiles per set; the oracle checks three sets of one iteration."""
+    spec = synth.SPECS["cfg3"]
+    one = synth.KVSpec(**{**spec.__dict__, "n_layers": 1, "batch": 1})
+    x = torch.empty((256, spec.T, 128), dtype=torch.float16, device="cuda")
+    for layer in range(32):
+        x[layer * 8:(layer + 1) * 8] = synth.make_layer_device(3, layer, one, "cuda")[0][0]
+    P = 128
+    pat = x[:, :P].contiguous()
+    cur = host_u16(pat)
+    asg = torch.empty((256, spec.T), dtype=torch.int32, device="cuda")
+    pk.pk_mine_patterns(pk.Config(n_patterns=P), x, 1, patterns=pat, init_given=True, assign=asg)
+    Mg = host_u16(pat)
+    for s in (0, 137, 255):
+        xs = host_u16(x[s])
+        Mo, ao, _, cnt = oracle.mine(xs[None], P, 1, init=cur[s:s + 1])
+        ag = asg[s].cpu().numpy()
+        diff = ag != ao[0]
+        if diff.any():
+            _, best, second = oracle.assign(xs, cur[s], 0)
+            gap = (second - best) / np.maximum(second, 1e-30)
+            assert np.all(gap[diff] < 1e-4), (s, gap[diff].max())
+        clean = np.ones(P, bool)
+        clean[np.unique(np.concatenate([ag[diff], ao[0][diff]]))] = False
+        key = lambda u: np.where(u.astype(np.int32) & 0x8000, -(u.astype(np.int32) & 0x7fff), u.astype(np.int32))
+        assert np.abs(key(Mg[s][clean]) - key(Mo[0][clean])).max() <= 1, s
+
+
+def test_config4_decode_after_every_append(oracle, pk):
+    """Config 4's schedule in small: 64 samples over the shared 4096-token prompt cache, one generated token
+    appended per step and a decode after EVERY append, across two flushes of 128 tokens (260 steps).  The oracle
+    replays three sampled streams step by step and checks every step's output of their query heads."""
+    spec = synth.SPECS["cfg4"]
+    S, Hkv, Hq, d, P, Tp, steps = spec.batch, spec.n_kv_heads, spec.n_q_heads, spec.d, 64, 4096, 260
+    pkw = dict(n_seq=1, n_kv_heads=Hkv, n_q_heads=Hq, head_dim=d, n_patterns=P, seqs_per_set=0, bits=2, group=32,
+               recent=0, flush=128, t_capacity=Tp, metric=0)
+    kw = dict(pkw, n_seq=S, seqs_per_set=S, t_capacity=512)
+    pcfg, gcfg = pk.Config(**pkw), pk.Config(**kw)
+    Kp, Vp = synth.make_layer_device(4, 0, synth.KVSpec(**{**spec.__dict__, "batch": 1, "T": Tp}), "cuda")
+    Kg, Vg = synth.make_layer_device(4, 1, synth.KVSpec(**{**spec.__dict__, "T": steps}), "cuda")
+    Mk, Mv = first_vectors(Kp, P, 1), first_vectors(Vp, P, 1)
+    pc, gc = pk.Cache(pcfg), pk.Cache(gcfg)
+    pk.pk_quantize_append(pcfg, pc, Kp, Vp, Mk, Mv)
+    q = dev(synth.make_queries(4, S, Hq, d))
+    r = Hq // Hkv
+    sampled = [(0, 1), (37, 6), (S - 1, 0)]
+    outs = torch.empty((steps, len(sampled), r, d), dtype=torch.float32, device="cuda")
+    out = torch.empty((S, Hq, d), dtype=torch.float32, device="cuda")
+    ws = torch.empty(pk.pk_workspace_bytes(gcfg, pk.OP_DECODE, 512, Tp), dtype=torch.uint8, device="cuda")
+    for t in range(steps):
+        pk.pk_quantize_append(gcfg, gc, Kg[:, :, t:t + 1], Vg[:, :, t:t + 1], Mk, Mv)
+        pk.pk_decode_attention(gcfg, gc, q, d ** -0.5, Mk, Mv, out=out, workspace=ws, prefix=pc)
+        for i, (seq, head) in enumerate(sampled):
+            outs[t, i] = out[seq, head * r:(head + 1) * r]
+    torch.cuda.synchronize()
+    assert gc.t_quant == 256 and gc.t_tail == 4
+    got = outs.cpu().numpy()
+    for i, (seq, head) in enumerate(sampled):
+        okw = dict(pkw, n_kv_heads=1, n_q_heads=r)
+        opc = oracle.Cache(oracle.Config(**okw))
+        Mks, Mvs = host_u16(Mk[head])[None], host_u16(Mv[head])[None]
+        opc.append(host_u16(Kp[0, head])[None, None], host_u16(Vp[0, head])[None, None], Mks, Mvs)
+        ooc = oracle.Cache(oracle.Config(**dict(okw, t_capacity=512)))
+        kg, vg = host_u16(Kg[seq, head]), host_u16(Vg[seq, head])
+        qs = host_u16(q[seq, head * r:(head + 1) * r])[None]
+        for t in range(steps):
+            ooc.append(kg[None, None, t:t + 1], vg[None, None, t:t + 1], Mks, Mvs)
+            want, _ = oracle.decode_attention(ooc, qs, Mks, Mvs, d ** -0.5, prefix=opc, prefix_patterns_k=Mks,
+                                              prefix_patterns_v=Mvs)
+            assert_attention(got[t, i][None], want)
+        compare_caches(oracle, ooc, StreamView(gc, seq * Hkv + head), 0)

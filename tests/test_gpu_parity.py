@@ -128,6 +128,20 @@ def rel_l2(a, b):
     return float(np.linalg.norm(a.astype(np.float64) - b.astype(np.float64)) / max(np.linalg.norm(b.astype(np.float64)), 1e-30))
 
 
+def assert_attention(got, want, elementwise=True):
+    """The attention bar, applied to every (sequence, query head) row on its own: relative L2 error <= 2e-3, and
+    (for runs on shared pattern tables) every element within 2e-3 of the row's largest magnitude."""
+    got, want = np.asarray(got, np.float64), np.asarray(want, np.float64)
+    assert got.shape == want.shape and np.isfinite(got).all()
+    g2, w2 = got.reshape(-1, got.shape[-1]), want.reshape(-1, want.shape[-1])
+    err = np.linalg.norm(g2 - w2, axis=1) / np.maximum(np.linalg.norm(w2, axis=1), 1e-30)
+    assert err.max() <= 2e-3, f"row {int(err.argmax())}: relative L2 error {err.max():.3e}"
+    if elementwise:
+        bound = 2e-3 * np.abs(w2).max(axis=1, keepdims=True)
+        worst = (np.abs(g2 - w2) / np.maximum(bound, 1e-30)).max()
+        assert worst <= 1.0, f"element error {worst:.3f} x the bound"
+
+
 # ------------------------------------------------------------------------------ quantize-append
 
 @pytest.mark.parametrize("bits,G,P,metric", [
@@ -177,7 +191,7 @@ def test_v_adaptive_threshold_parity(oracle, pk, bits, G, P, metric, hq):
     q = synth.make_queries(9, 2, hq, 128)
     want, _ = oracle.decode_attention(oc, q.view(np.uint16), Mk, Mv, 128 ** -0.5)
     got = pk.pk_decode_attention(gcfg, gc, dev(q), 128 ** -0.5, Mkd, Mvd).cpu().numpy()
-    assert rel_l2(got, want) <= 2e-3
+    assert_attention(got, want)
 
 
 def test_streaming_appends_with_recent_window(oracle, pk):
@@ -222,6 +236,33 @@ def test_append_is_reproducible_bit_for_bit(oracle, pk):
         assert torch.equal(g1.array(n), g2.array(n)), n
 
 
+def test_division_sequences_match_ieee_division(pk):
+    """The quantizer forms s = (max - z)/(2^b - 1) and 1/s with a reciprocal estimate plus one correction step
+    instead of the division instruction sequence; the codes are bit-exact only if both are correctly rounded.
+    Checked here against IEEE binary32 division (numpy float32, the same operation the oracle's C code performs):
+    1/s for every positive finite fp16 value, x/3 and x/15 for all 2^23 mantissas in each of seven binades that
+    span fp16-sized ranges (2^-24 .. 2^17), and for every positive finite fp16 value."""
+    import ctypes as C
+    lib = pk._lib
+    lib.pk_probe_divisions.restype = C.c_int
+    lib.pk_probe_divisions.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    halves = np.arange(1, 0x7c00, dtype=np.uint16).view(np.float16).astype(np.float32)      # subnormals included
+    mant = np.arange(1 << 23, dtype=np.uint32)
+    sweeps = [((np.uint32(e + 127) << np.uint32(23)) | mant).view(np.float32) for e in (-24, -14, -7, -1, 0, 5, 17)]
+    for x in [halves] + sweeps:
+        xd = torch.from_numpy(x.copy()).cuda()
+        outs = [torch.empty_like(xd) for _ in range(3)]
+        rc = lib.pk_probe_divisions(xd.data_ptr(), xd.numel(), outs[0].data_ptr(), outs[1].data_ptr(), outs[2].data_ptr(),
+                                    C.c_void_p(torch.cuda.current_stream().cuda_stream))
+        assert rc == 0
+        torch.cuda.synchronize()
+        recip, by3, by15 = (o.cpu().numpy() for o in outs)
+        assert np.array_equal(by3.view(np.uint32), (x / np.float32(3)).view(np.uint32))
+        assert np.array_equal(by15.view(np.uint32), (x / np.float32(15)).view(np.uint32))
+        if x is halves:
+            assert np.array_equal(recip.view(np.uint32), (np.float32(1) / x).view(np.uint32))
+
+
 # ------------------------------------------------------------------------------ decode attention
 
 @pytest.mark.parametrize("hkv,hq,bits,G,P,R,T", [
@@ -243,13 +284,13 @@ def test_decode_attention_parity(oracle, pk, hkv, hq, bits, G, P, R, T):
     lse = torch.empty((2, hq), dtype=torch.float32, device="cuda")
     # (a) end to end: GPU-built cache
     got = pk.pk_decode_attention(gcfg, gc, dev(q), scale, Mkd, Mvd, lse=lse).cpu().numpy()
-    assert rel_l2(got, want) <= 2e-3
+    assert_attention(got, want)
     assert np.abs(lse.cpu().numpy() - want_lse).max() <= 2e-3
     # (b) decode alone: the oracle's cache uploaded, so both sides read identical bytes
     gc2 = pk.Cache(gcfg)
     upload(gc2, oc)
     got2 = pk.pk_decode_attention(gcfg, gc2, dev(q), scale, Mkd, Mvd).cpu().numpy()
-    assert rel_l2(got2, want) <= 2e-3
+    assert_attention(got2, want)
     # reproducible
     got3 = pk.pk_decode_attention(gcfg, gc2, dev(q), scale, Mkd, Mvd).cpu().numpy()
     assert np.allclose(got2, got3, rtol=1e-5, atol=1e-6)
@@ -274,7 +315,7 @@ def test_decode_tail_only_and_empty_context(oracle, pk):
     q = synth.make_queries(4, 2, 8, 128)
     want, _ = oracle.decode_attention(oc, q.view(np.uint16), Mk, Mv, 128 ** -0.5)
     got = pk.pk_decode_attention(gcfg, gc, dev(q), 128 ** -0.5, Mkd, Mvd).cpu().numpy()
-    assert rel_l2(got, want) <= 2e-3
+    assert_attention(got, want)
     # plain fp16 attention over the window
     Kd, Vd, Qd = K.astype(np.float64), V.astype(np.float64), q.astype(np.float64)
     for s in range(2):
@@ -307,7 +348,7 @@ def test_decode_with_shared_prefix(oracle, pk):
                                              prefix_patterns_k=Mk, prefix_patterns_v=Mv)
     lse = torch.empty((3, hq), dtype=torch.float32, device="cuda")
     got = pk.pk_decode_attention(pk.Config(**own_kw), go, dev(q), 128 ** -0.5, Mkd, Mvd, lse=lse, prefix=gp).cpu().numpy()
-    assert rel_l2(got, want) <= 2e-3
+    assert_attention(got, want)
     assert np.abs(lse.cpu().numpy() - want_lse).max() <= 2e-3
 
 
@@ -354,7 +395,7 @@ def test_decode_ragged_batch_parity(oracle, pk, hkv, hq, bits, G, P, R, lens):
         if n == 0:
             assert np.all(got[i] == 0) and np.all(np.isneginf(glse[i]))
         else:
-            assert rel_l2(got[i], want[i]) <= 2e-3, (i, n)
+            assert_attention(got[i], want[i])
             assert np.abs(glse[i] - want_lse[i]).max() <= 2e-3
     # entries beyond the bound are clamped to it: the longest sequence reads the same with an oversized entry
     big = int(np.argmax([s[0] for s in states]))
@@ -391,7 +432,7 @@ def test_decode_ragged_batch_with_shared_prefix(oracle, pk):
     got = pk.pk_decode_attention_ragged(gcfg, gc, st, max(s[0] for s in states), max(s[1] for s in states), dev(q),
                                         128 ** -0.5, Mkd, Mvd, prefix=gp).cpu().numpy()
     for i in range(3):
-        assert rel_l2(got[i], want[i]) <= 2e-3, i
+        assert_attention(got[i], want[i])
 
 
 # ------------------------------------------------------------------------------ decode-stage pattern update
@@ -430,7 +471,7 @@ def test_window_pattern_and_growing_tables(oracle, pk):
     q = synth.make_queries(12, n_seq, hq, 128)
     want, _ = oracle.decode_attention(oc, q.view(np.uint16), Mk, Mv, 128 ** -0.5)
     got = pk.pk_decode_attention(gc.cfg, gc, dev(q), 128 ** -0.5, Mkd, Mvd).cpu().numpy()
-    assert rel_l2(got, want) <= 2e-3
+    assert_attention(got, want)
     # strided output: straight into a row of a table
     tab = torch.zeros((N, 4, 128), dtype=torch.float16, device="cuda")
     pk.pk_window_pattern(Kd.view(N, -1, 128)[:, 64:128], out=tab[:, 2])
@@ -475,6 +516,57 @@ def test_mining_parity_per_iteration(oracle, pk, T, P, n_c):
             assert np.array_equal(Mg[s][empty & clean], cur[s][empty & clean])      # empty clusters keep their centroid
         assert np.allclose(J.cpu().numpy()[:, 0], Jo[:, 0], rtol=1e-4)
         cur = Mo                                                                    # both continue from the oracle's centroids
+
+
+def _mining_step_parity(oracle, pk, x, P, cur, check_sets):
+    """One Lloyd iteration on the GPU over all sets of x [S, T, d] from the centroids `cur` (uint16 [S, P, d]);
+    the sets in check_sets are compared with the oracle's iteration from the same centroids.  Returns the
+    oracle's new centroids of the checked sets ({set: uint16 [P, d]}): what a following iteration starts from."""
+    S, T, _ = x.shape
+    pat = dev(cur.view(np.float16)).clone()
+    asg = torch.empty((S, T), dtype=torch.int32, device="cuda")
+    J = torch.empty((S, 1), dtype=torch.float32, device="cuda")
+    pk.pk_mine_patterns(pk.Config(n_patterns=P), dev(x), 1, patterns=pat, init_given=True, assign=asg, inertia=J)
+    ag, Mg, Jg = asg.cpu().numpy(), host_u16(pat), J.cpu().numpy()
+    new = {}
+    for s in check_sets:
+        Mo, ao, Jo, cnt = oracle.mine(x[s:s + 1].view(np.uint16), P, 1, init=cur[s:s + 1])
+        diff = ag[s] != ao[0]
+        if diff.any():
+            _, best, second = oracle.assign(x[s].view(np.uint16), cur[s], 0)
+            gap = (second - best) / np.maximum(second, 1e-30)
+            assert np.all(gap[diff] < 1e-4), (s, gap[diff].max())
+        clean = np.ones(P, bool)
+        clean[np.unique(np.concatenate([ag[s][diff], ao[0][diff]]))] = False   # clusters with equal member sets
+        assert clean.sum() >= P - 2 * int(diff.sum())
+        assert _ulp_diff(Mg[s][clean], Mo[0][clean]).max() <= 1, s
+        empty = cnt[0] == 0
+        assert np.array_equal(Mg[s][empty & clean], cur[s][empty & clean])      # empty clusters keep their centroid
+        assert np.allclose(Jg[s, 0], Jo[0, 0], rtol=1e-4)
+        new[s] = Mo[0]
+    return new
+
+
+def test_mining_parity_many_sets_several_subtiles(oracle, pk):
+    """64 sets x 4133 vectors at P = 128: the launch cuts every set into 7 chunks of 640 vectors = five 128-vector
+    sub-tiles each (prefetch of the next sub-tile, accumulators carried across barriers, a ragged last chunk)."""
+    spec = synth.KVSpec(1, 8, 8, 8, 4096 + 37, 128, 48)
+    K, _ = synth.make_kv(91, spec)
+    x = K.reshape(64, 4096 + 37, 128)
+    cur = x[:, :128].copy().view(np.uint16)
+    for it in range(2):
+        new = _mining_step_parity(oracle, pk, x, 128, cur, check_sets=range(64))
+        cur = np.stack([new[s] for s in range(64)])            # both sides continue from the oracle's centroids
+
+
+def test_mining_parity_256_patterns_long_chunks(oracle, pk):
+    """One set of 65636 vectors at P = 256 (the 8-wave kernel): 57 chunks of 1152 vectors = 4.5 sub-tiles of 256."""
+    spec = synth.KVSpec(1, 1, 1, 1, 65536 + 100, 128, 200)
+    K, _ = synth.make_kv(92, spec)
+    x = K.reshape(1, -1, 128)
+    cur = x[:, :256].copy().view(np.uint16)
+    for it in range(2):
+        cur = _mining_step_parity(oracle, pk, x, 256, cur, check_sets=[0])[0][None]
 
 
 def test_mining_end_to_end_and_reproducible(oracle, pk):
@@ -524,7 +616,7 @@ def test_config1_smoke_full_path(oracle, pk):
     oc = oracle.Cache(ocfg)
     oc.append(K.view(np.uint16), V.view(np.uint16), Mk_o, Mv_o)
     want, _ = oracle.decode_attention(oc, q.view(np.uint16), Mk_o, Mv_o, 128 ** -0.5)
-    assert rel_l2(got, want) <= 2e-3
+    assert_attention(got, want, elementwise=False)   # each side on its own mined tables
     # and stage by stage on shared patterns
     oc2, gc2, Mkd, Mvd = run_appends(oracle, pk, ocfg, gcfg, K, V, Mk_o, Mv_o, [1024])
     compare_caches(oracle, oc2, gc2, 0)
@@ -556,7 +648,7 @@ def test_config2_llama_shaped_layer(oracle, pk, bits):
     q = synth.make_queries(2, 1, 32, 128)
     want, _ = oracle.decode_attention(oc, q.view(np.uint16), Mk, Mv, 128 ** -0.5)
     got = pk.pk_decode_attention(gcfg, gc, dev(q), 128 ** -0.5, Mkd, Mvd).cpu().numpy()
-    assert rel_l2(got, want) <= 2e-3
+    assert_attention(got, want)
     if bits == 2:
         # mining at full size: objective after 10 iterations against the oracle's run from the same start
         J = torch.empty((8, 10), dtype=torch.float32, device="cuda")
@@ -568,4 +660,4 @@ def test_config2_llama_shaped_layer(oracle, pk, bits):
         gc2 = pk.Cache(gcfg)
         pk.pk_quantize_append(gcfg, gc2, dev(K), dev(V), Mg, Mvg)
         got2 = pk.pk_decode_attention(gcfg, gc2, dev(q), 128 ** -0.5, Mg, Mvg).cpu().numpy()
-        assert rel_l2(got2, want) <= 2e-3
+        assert_attention(got2, want, elementwise=False)   # each side on its own mined tables

@@ -662,3 +662,34 @@ def test_ragged_batch_is_attention_per_sequence(oracle):
             p = np.exp(sc - sc.max()); p /= p.sum()
             assert np.allclose(out[i, h], p @ V[i, h // 2, :n].astype(np.float64), rtol=1e-6, atol=1e-7)
             assert abs(lse[i, h] - (sc.max() + np.log(np.exp(sc - sc.max()).sum()))) < 1e-5
+
+
+@pytest.mark.parametrize("n_seq,hkv,k,expected", [
+    # streams in order (sequence-major, then KV head) -> the pattern table each one must use, written out by hand
+    (3, 2, 0, [0, 1, 0, 1, 0, 1]),                               # one table per KV head, shared by all sequences
+    (3, 2, 1, [0, 1, 2, 3, 4, 5]),                               # one table per (sequence, head)
+    (6, 2, 3, [0, 1, 0, 1, 0, 1, 2, 3, 2, 3, 2, 3]),             # 2 layers x batch 3: one table per (layer, head)
+    (7, 1, 3, [0, 0, 0, 1, 1, 1, 2]),                            # a last, partly filled set
+])
+def test_stream_to_pattern_set_mapping(oracle, n_seq, hkv, k, expected):
+    """Which table a stream is quantized against (seqs_per_set).  Made visible through the stored zero points:
+    all vectors are zero, table s holds the single pattern (s+1, s+1, ...), so every residual is -(s+1), the group's
+    minimum - and with it the stored K zero point and V zero point - names the table that was used."""
+    d, G = 128, 64
+    cfg = oracle.Config(n_seq=n_seq, n_kv_heads=hkv, n_q_heads=hkv, head_dim=d, n_patterns=1, seqs_per_set=k, bits=2,
+                        group=G, recent=0, flush=64, t_capacity=64, metric=0)
+    n_sets = len(set(expected))
+    assert cfg.n_sets == n_sets
+    tables = np.empty((n_sets, 1, d), np.float16)
+    for s in range(n_sets):
+        tables[s] = s + 1
+    zeros = np.zeros((n_seq, hkv, 64, d), np.uint16)
+    c = oracle.Cache(cfg)
+    c.append(zeros, zeros, tables.view(np.uint16), tables.view(np.uint16))
+    zk = c.k_zero[:, 0, :].view(np.float16).astype(np.float64)              # [streams, d]
+    zv = c.v_zero[:, 0].view(np.float16).astype(np.float64)                 # [streams, groups, 16 tokens]
+    for n, s in enumerate(expected):
+        assert np.all(zk[n] == -(s + 1)) and np.all(zv[n] == -(s + 1)), (n, s)
+    # and the reconstruction with the same tables gives the zero vectors back
+    kh, vh = c.dequantize(tables.view(np.uint16), tables.view(np.uint16))
+    assert not kh.any() and not vh.any()

@@ -22,6 +22,15 @@
 //   V side  A operand: row n = (h, g), lane group kb <-> the 16 tokens of unit kb of the block
 //           B operand: column n <-> channel 16*tile + n, lane group kb <-> the same 16 tokens
 //           D (output accumulators): column n <-> channel 16*tile + n, rows 4*kb+i <-> (h, g) rows
+//
+// HALF variant (r * NG <= 8, one K group per block): the (h, g) pairs fill only eight of the sixteen columns, so
+// column n and column n + 8 carry the same pair and the two halves of a lane group's 16 tokens are split between
+// them: lanes n < 8 keep the scores of tokens 16*kb + 0..7 (score tiles x = 0, 1), lanes n >= 8 those of tokens
+// 16*kb + 8..15 (tiles x = 2, 3).  Every per-token step after the K-side MFMAs (pattern-score gather, exponentials,
+// per-pattern mass, V-side A operand) then runs on 8 values per lane instead of 16.  On the V side the two K = 32
+// steps of a channel tile cover tokens 0..7 and 8..15 of the units, so lanes n < 8 feed the first step and lanes
+// n >= 8 the second (the other operand is zero): output rows rho and rho + 8 are two partial sums of one (h, g)
+// pair and are added in the epilogue.
 #include "pk_internal.h"
 
 namespace pk {
@@ -91,17 +100,20 @@ struct GroupOperand {
     float qz;          // scale * log2(e) * q_h . z[g]
 };
 
-template <int BITS, bool G32>
+template <int BITS, bool G32, bool HALF>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void decode_packed_kernel(DecodeArgs a)
 {
+    static_assert(!(HALF && G32), "the split of a unit's tokens over column halves assumes one K group per block");
     constexpr int WPU = BITS / 2;   // 32-bit words per (channel, 16-token unit) of V; K: 4*BITS words per token
+    constexpr int NTK = HALF ? 8 : 16;   // tokens of a block whose scores a lane keeps
     // dynamic LDS: QMs [P][16] floats (q.M_K per pattern and column); Ws [4 waves][R][w_stride] 64-bit fixed-point
     // sums (softmax mass per V pattern, unit 2^-31).  Integer LDS atomics run at full rate on this chip, float
     // ones retire about one lane per 2.6 cycles (measured), which made the mass sums the slowest part of a block.
     extern __shared__ __align__(16) unsigned char dyn_smem[];
     __shared__ float stat_m[4][16], stat_l[4][16], stat_pz[4][16];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 15, kb = lane >> 4;
+    const int tid = threadIdx.x, lane = tid & 63, n = lane & 15, kb = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: block ranges and base addresses stay scalar
     const int split = blockIdx.x, ns = blockIdx.y;
     const int n_slots = a.splits_prefix + a.splits_own + 2;
     const int seq = ns / a.n_kv_heads, head = ns - seq * a.n_kv_heads;
@@ -132,11 +144,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
     const int R = a.n_q_heads / a.n_kv_heads, G = a.G, P = a.P;
     const int lgG = 31 - __clz(G);   // G is a power of two
     const int Gc = G < kD ? G : kD, NG = kD / Gc;
-    const bool col_ok = n < R * NG;
-    const int h = col_ok ? n % R : 0, g = col_ok ? n / R : 0;
+    const int hcol = HALF ? (n & 7) : n;            // the (h, g) pair of this lane's column
+    const bool second = HALF && n >= 8;             // this lane keeps the second half of its unit's tokens
+    const uint32_t m_first = second ? 0u : 0xffffffffu, m_second = ~m_first;
+    const bool col_ok = hcol < R * NG;
+    const int h = col_ok ? hcol % R : 0, g = col_ok ? hcol / R : 0;
     const __half *MK = a.patterns_k + (int64_t)set * P * kD;
-    const float sc2 = a.softmax_scale * kLog2e;
-    const float c1 = sc2 * 65536.f, inv_c1 = 1.f / c1;
     const int WS = a.w_stride;   // P, or 256 when index 255 can occur (tokens quantized without a pattern)
     float *QMs = reinterpret_cast<float *>(dyn_smem);
     unsigned long long *Ws = reinterpret_cast<unsigned long long *>(QMs + P * 16);
@@ -158,6 +171,27 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
             }
         }
     }
+    // The operands below multiply q by up to 2^8 and by the K scales in fp16: the head's query is brought to
+    // max |q| in [1, 2) by a power of two first (exact), which is folded back into the softmax scale of the
+    // column, so that only the stored scales bound the operands (s_K < 128, i.e. a K residual range per
+    // channel and group below 3 * 128 at 2 bits).
+    float lam = 1.f;
+    {
+        float qmax = 0.f;
+#pragma unroll
+        for (int i = 0; i < 32; ++i) qmax = fmaxf(qmax, fabsf((float)qh[i]));
+        qmax = fmaxf(qmax, __shfl_xor(qmax, 16));
+        qmax = fmaxf(qmax, __shfl_xor(qmax, 32));
+        if (qmax > 0.f) {
+            int e;
+            (void)frexpf(qmax, &e);          // qmax = m * 2^e, m in [0.5, 1)
+            lam = ldexpf(1.f, 1 - e);
+        }
+#pragma unroll
+        for (int i = 0; i < 32; ++i) qh[i] = (_Float16)((float)qh[i] * lam);
+    }
+    const float sc2 = a.softmax_scale * kLog2e / lam;
+    const float c1 = sc2 * 65536.f, inv_c1 = 1.f / c1;
     uint32_t qn[16], qp[16];   // natural channel order; operand order with the field scale folded in
 #pragma unroll
     for (int i = 0; i < 16; ++i) qn[i] = pack2(qh[2 * i], qh[2 * i + 1]);
@@ -268,9 +302,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
     };
 
 
-    // K-side inputs of a block: plane words of this lane's 4 token rows, pattern indices of its 16 tokens
+    // K-side inputs of a block: plane words of this lane's 4 token rows, pattern indices of the tokens whose scores
+    // it keeps (16, or its half of the unit: 8)
     uint32_t kw[4][BITS];
-    uint4 kid;
+    uint32_t kidw[NTK / 4];
     auto load_k = [&](int tb) {
 #pragma unroll
         for (int x = 0; x < 4; ++x) {
@@ -288,7 +323,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
                 kw[x][BITS - 1] = v.w;
             }
         }
-        kid = *reinterpret_cast<const uint4 *>(kidx + (uint32_t)(tb + 16 * kb));
+        if (HALF) {
+            const uint2 v = *reinterpret_cast<const uint2 *>(kidx + (uint32_t)(tb + 16 * kb + (second ? 8 : 0)));
+            kidw[0] = v.x;
+            kidw[1] = v.y;
+        } else {
+            const uint4 v = *reinterpret_cast<const uint4 *>(kidx + (uint32_t)(tb + 16 * kb));
+            kidw[0] = v.x;
+            kidw[1] = v.y;
+            kidw[NTK / 4 - 2] = v.z;
+            kidw[NTK / 4 - 1] = v.w;
+        }
     };
 
     if (b0 < b1) {
@@ -303,12 +348,34 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
         }
     }
 
+    // field scale 2^(8 - pos) of the V-side operand registers this lane builds: registers 0..7 of a unit, or
+    // (HALF) the four of its token half
+    constexpr int NAV = NTK / 2;
+    uint32_t cfield[NAV];
+#pragma unroll
+    for (int V = 0; V < NAV; ++V) {
+        const _Float16 c_lo = (_Float16)(float)(1 << (8 - fpos(V)));
+        const _Float16 c_hi = (_Float16)(float)(1 << (8 - fpos(HALF ? V + 4 : V)));
+        cfield[V] = second ? pack2(c_hi, c_hi) : pack2(c_lo, c_lo);
+    }
+
     for (int b = b0; b < b1; ++b) {
         const int tb = t_begin + (b << 6);
 
         // ---- V-side loads of the block (used after the scores)
         const int unit = (tb >> 4) + kb;   // 16-token unit of this lane group
-        const uint4 vid = *reinterpret_cast<const uint4 *>(vidx + (uint32_t)(tb + 16 * kb));
+        uint32_t vidw[NTK / 4];
+        if (HALF) {
+            const uint2 v = *reinterpret_cast<const uint2 *>(vidx + (uint32_t)(tb + 16 * kb + (second ? 8 : 0)));
+            vidw[0] = v.x;
+            vidw[1] = v.y;
+        } else {
+            const uint4 v = *reinterpret_cast<const uint4 *>(vidx + (uint32_t)(tb + 16 * kb));
+            vidw[0] = v.x;
+            vidw[1] = v.y;
+            vidw[NTK / 4 - 2] = v.z;
+            vidw[NTK / 4 - 1] = v.w;
+        }
         uint32_t vw[8 * WPU];
         {
             const uint4 *src = reinterpret_cast<const uint4 *>(vcodes + ((uint32_t)unit * 16 + n) * 8 * WPU * 4);
@@ -321,24 +388,25 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
                 vw[4 * i + 3] = v.w;
             }
         }
-        uint32_t sv[8], zv[8];
+        uint32_t sv[NAV], zv[NAV];   // scales / zero points of the lane's tokens, two per register
         {
-            const uint4 *sp = reinterpret_cast<const uint4 *>(vscale + ((uint32_t)unit * NG + g) * 32);
-            const uint4 *zp = reinterpret_cast<const uint4 *>(vzero + ((uint32_t)unit * NG + g) * 32);
+            const uint32_t poff = ((uint32_t)unit * NG + g) * 32 + (second ? 16 : 0);
+            const uint4 *sp = reinterpret_cast<const uint4 *>(vscale + poff);
+            const uint4 *zp = reinterpret_cast<const uint4 *>(vzero + poff);
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
+            for (int i = 0; i < NAV / 4; ++i) {
                 const uint4 s4 = sp[i], z4 = zp[i];
                 sv[4 * i] = s4.x; sv[4 * i + 1] = s4.y; sv[4 * i + 2] = s4.z; sv[4 * i + 3] = s4.w;
                 zv[4 * i] = z4.x; zv[4 * i + 1] = z4.y; zv[4 * i + 2] = z4.z; zv[4 * i + 3] = z4.w;
             }
         }
 
-        // ---- K side: scores of the 64 tokens relative to m_run (this lane: column n, tokens 16*kb + 0..15),
-        //      log2 domain.  The accumulator starts at (q.z - m_run) / c1.
-        float S[16];
-        const uint32_t kidw[4] = {kid.x, kid.y, kid.z, kid.w};
+        // ---- K side: scores of the 64 tokens relative to m_run (this lane: column n, tokens 16*kb + 0..15, or
+        //      its half of them), log2 domain.  The accumulator starts at (q.z - m_run) / c1.
+        float S[NTK];
         const float d0 = (ga.qz - m_run) * inv_c1;
         const float d02 = G32 ? (gb.qz - m_run) * inv_c1 : 0.f;
+        floatx4 dfirst[HALF ? 2 : 1];   // HALF: score tiles 0 and 1 wait for tiles 2 and 3
 #pragma unroll
         for (int x = 0; x < 4; ++x) {
             uint32_t A16[16];
@@ -366,10 +434,24 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
                 }
             }
             if (G32 && kb >= 2) d = d2;
+            if (HALF) {
+                if (x < 2) {
+                    dfirst[x] = d;
+                } else {
+                    // lanes n < 8 take tile x - 2 (tokens 4(x-2) + i of the unit), lanes n >= 8 tile x (tokens 8 + 4(x-2) + i)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int id = (kidw[x] >> (8 * i)) & 255;
-                S[4 * x + i] = fmaf(d[i], c1, QMs[id * 16 + n]);
+                    for (int i = 0; i < 4; ++i) {
+                        const uint32_t sel = (__float_as_uint(dfirst[x - 2][i]) & m_first) | (__float_as_uint(d[i]) & m_second);
+                        const int id = (kidw[x - 2] >> (8 * i)) & 255;
+                        S[4 * (x - 2) + i] = fmaf(__uint_as_float(sel), c1, QMs[id * 16 + n]);
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int id = (kidw[x] >> (8 * i)) & 255;
+                    S[4 * x + i] = fmaf(d[i], c1, QMs[id * 16 + n]);
+                }
             }
         }
 
@@ -381,11 +463,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
         if (more) load_k(tbn);
         if (new_group) load_group_raw(tbn >> lgG, gr);
 
-        // ---- online softmax (per column; the four lane groups hold different tokens)
+        // ---- online softmax (per column; the lane groups, and with HALF the two column halves, hold different tokens)
         float bmax = fmaxf(S[0], S[1]);
 #pragma unroll
-        for (int k = 2; k < 16; k += 2) bmax = fmaxf(fmaxf(bmax, S[k]), S[k + 1]);
+        for (int k = 2; k < NTK; k += 2) bmax = fmaxf(fmaxf(bmax, S[k]), S[k + 1]);
         if (!started || __ballot(bmax > 0.f) != 0ull) {
+            if (HALF) bmax = fmaxf(bmax, __shfl_xor(bmax, 8));
             bmax = fmaxf(bmax, __shfl_xor(bmax, 16));
             bmax = fmaxf(bmax, __shfl_xor(bmax, 32));
             const float delta = started ? fmaxf(bmax, 0.f) : bmax;
@@ -409,19 +492,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
             }
             m_run += delta;
 #pragma unroll
-            for (int k = 0; k < 16; ++k) S[k] -= delta;
+            for (int k = 0; k < NTK; ++k) S[k] -= delta;
             started = true;
         }
-        float pr[16];
+        float pr[NTK];
 #pragma unroll
-        for (int k = 0; k < 16; ++k) pr[k] = __builtin_amdgcn_exp2f(S[k]);
+        for (int k = 0; k < NTK; ++k) pr[k] = __builtin_amdgcn_exp2f(S[k]);
 
-        // ---- softmax mass per V pattern (columns of group 0 carry the heads once)
-        if (n < R) {
-            const uint32_t vidw[4] = {vid.x, vid.y, vid.z, vid.w};
+        // ---- softmax mass per V pattern (the columns of channel group 0 carry every head once per token)
+        if (hcol < R) {
 #pragma unroll
-            for (int k = 0; k < 16; ++k)
-                atomicAdd(&Ws[(wave * R + n) * WS + ((vidw[k >> 2] >> (8 * (k & 3))) & 255)],
+            for (int k = 0; k < NTK; ++k)
+                atomicAdd(&Ws[(wave * R + hcol) * WS + ((vidw[k >> 2] >> (8 * (k & 3))) & 255)],
                           (unsigned long long)(uint32_t)(pr[k] * kWUnit));   // pr <= 1: no overflow; truncation loses < 2^-31
         }
 
@@ -429,13 +511,21 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
         uint32_t Ap[8], Ap4[8];
         const uint32_t ones = pack2((_Float16)1.f, (_Float16)1.f);
 #pragma unroll
-        for (int V = 0; V < 8; ++V) {
+        for (int V = 0; V < NAV; ++V) {
             const uint32_t ph = cvt2(pr[2 * V], pr[2 * V + 1]);
             pzacc = dot2(ph, zv[V], pzacc);
             l_run = dot2(ph, ones, l_run);   // the denominator sums the same rounded weights the numerator uses
-            const _Float16 c = (_Float16)(float)(1 << (8 - fpos(V)));
-            Ap[V] = pk_mul(pk_mul(ph, sv[V]), pack2(c, c));
-            if (BITS == 4) Ap4[V] = pk_mul(Ap[V], pack2((_Float16)4.f, (_Float16)4.f));
+            const uint32_t av = pk_mul(pk_mul(ph, sv[V]), cfield[V]);
+            if (HALF) {   // registers 0..3 feed the K step of tokens 0..7, registers 4..7 that of tokens 8..15
+                Ap[V] = av & m_first;
+                Ap[V + 4] = av & m_second;
+            } else {
+                Ap[V] = av;
+            }
+        }
+        if (BITS == 4) {
+#pragma unroll
+            for (int V = 0; V < 8; ++V) Ap4[V] = pk_mul(Ap[V], pack2((_Float16)4.f, (_Float16)4.f));
         }
         if (G32 && new_group) {   // first group done here, so that one set of registers serves both loads
             build_group(gr, ga);
@@ -468,6 +558,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
     if (!started) m_run = -INFINITY;   // a wave without blocks contributes nothing to the merge
 
     // ---- merge the four waves of the workgroup
+    if (HALF) {   // the two column halves hold partial sums over different tokens
+        l_run += __shfl_xor(l_run, 8);
+        pzacc += __shfl_xor(pzacc, 8);
+    }
     l_run += __shfl_xor(l_run, 16);
     l_run += __shfl_xor(l_run, 32);
     pzacc += __shfl_xor(pzacc, 16);
@@ -496,29 +590,35 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
         a.part_w[pbase * P + e] = acc * (1.f / kWUnit);
     }
     __syncthreads();
-    // every wave leaves its outputs, scaled to the workgroup's reference, in a slab of its own: Os[4][R][kD] floats
-    // over the start of the dynamic LDS (the launch sizes it for that)
+    // every wave leaves its outputs, scaled to the workgroup's reference, in slabs of its own: Os[4][NH][R][kD]
+    // floats over the start of the dynamic LDS (the launch sizes it for that); NH = 2 with HALF, where output rows
+    // rho and rho + 8 are the two token halves of one (h, g) pair
+    constexpr int NH = HALF ? 2 : 1;
     float *Os = reinterpret_cast<float *>(dyn_smem);
     {
         const int w = wave;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int rho = 4 * kb + i;
-            if (rho < R * NG) {
-                const int gg = (rho >= R) + (rho >= 2 * R) + (rho >= 3 * R), hh = rho - gg * R;   // NG <= 4
-                const float M = fmaxf(fmaxf(stat_m[0][rho], stat_m[1][rho]), fmaxf(stat_m[2][rho], stat_m[3][rho]));
-                const float f = __builtin_amdgcn_exp2f(stat_m[w][rho] - M);
-                const float pzv = stat_pz[w][rho];
+            const int rho = 4 * kb + i, rc = HALF ? (rho & 7) : rho, half = HALF ? (rho >> 3) : 0;
+            if (rc < R * NG) {
+                const int gg = (rc >= R) + (rc >= 2 * R) + (rc >= 3 * R), hh = rc - gg * R;   // NG <= 4
+                const float M = fmaxf(fmaxf(stat_m[0][rc], stat_m[1][rc]), fmaxf(stat_m[2][rc], stat_m[3][rc]));
+                const float f = __builtin_amdgcn_exp2f(stat_m[w][rc] - M);
+                const float pzv = half == 0 ? stat_pz[w][rc] : 0.f;   // the zero-point part is added once
 #pragma unroll
                 for (int t = 0; t < 8; ++t) {
-                    if (((16 * t) >> lgGc) == gg) Os[(w * R + hh) * kD + 16 * t + n] = f * fmaf(O[t][i], 65536.f, pzv);
+                    if (((16 * t) >> lgGc) == gg) Os[((w * NH + half) * R + hh) * kD + 16 * t + n] = f * fmaf(O[t][i], 65536.f, pzv);
                 }
             }
         }
     }
     __syncthreads();
-    for (int e = tid; e < R * kD; e += 256)   // waves added in order 0, 1, 2, 3
-        a.part_o[pbase * kD + e] = ((Os[e] + Os[R * kD + e]) + Os[2 * R * kD + e]) + Os[3 * R * kD + e];
+    for (int e = tid; e < R * kD; e += 256) {   // slabs added in a fixed order: waves 0, 1, 2, 3 (first half, second half)
+        float acc = Os[e];
+#pragma unroll
+        for (int k = 1; k < 4 * NH; ++k) acc += Os[k * R * kD + e];
+        a.part_o[pbase * kD + e] = acc;
+    }
     if (tid < R) {
         const float M = fmaxf(fmaxf(stat_m[0][tid], stat_m[1][tid]), fmaxf(stat_m[2][tid], stat_m[3][tid]));
         float L = 0.f;
@@ -531,13 +631,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
 
 }  // namespace
 
-template <int BITS, bool G32>
+template <int BITS, bool G32, bool HALF>
 static hipError_t launch_one(const DecodeArgs &a, dim3 grid, size_t lds, hipStream_t s)
 {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_packed_kernel<BITS, G32>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_packed_kernel<BITS, G32, HALF>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((decode_packed_kernel<BITS, G32>), grid, dim3(256), lds, s, a);
+    hipLaunchKernelGGL((decode_packed_kernel<BITS, G32, HALF>), grid, dim3(256), lds, s, a);
     return hipGetLastError();
 }
 
@@ -546,13 +646,17 @@ hipError_t launch_decode_packed(const DecodeArgs &a, hipStream_t s)
     const int splits = a.splits_prefix + a.splits_own;
     if (splits == 0) return hipSuccess;
     const dim3 grid(splits, a.n_seq * a.n_kv_heads);
-    const int R = a.n_q_heads / a.n_kv_heads;
+    const int R = a.n_q_heads / a.n_kv_heads, NG = kD / (a.G < kD ? a.G : kD);
+    // eight or fewer (head, channel group) pairs leave half of the score columns free: they take the second half
+    // of every unit's tokens
+    const bool half = a.G != 32 && R * NG <= 8;
     size_t lds = (size_t)a.P * 16 * 4 + (size_t)4 * R * a.w_stride * 8;   // QMs, Ws
-    if (lds < (size_t)4 * R * kD * 4) lds = (size_t)4 * R * kD * 4;               // reused for the four waves' outputs at the end
-    if (a.bits == 2 && a.G == 32) return launch_one<2, true>(a, grid, lds, s);
-    if (a.bits == 2) return launch_one<2, false>(a, grid, lds, s);
-    if (a.bits == 4 && a.G == 32) return launch_one<4, true>(a, grid, lds, s);
-    if (a.bits == 4) return launch_one<4, false>(a, grid, lds, s);
+    const size_t out_slabs = (size_t)4 * (half ? 2 : 1) * R * kD * 4;     // reused for the waves' outputs at the end
+    if (lds < out_slabs) lds = out_slabs;
+    if (a.bits == 2 && a.G == 32) return launch_one<2, true, false>(a, grid, lds, s);
+    if (a.bits == 2) return half ? launch_one<2, false, true>(a, grid, lds, s) : launch_one<2, false, false>(a, grid, lds, s);
+    if (a.bits == 4 && a.G == 32) return launch_one<4, true, false>(a, grid, lds, s);
+    if (a.bits == 4) return half ? launch_one<4, false, true>(a, grid, lds, s) : launch_one<4, false, false>(a, grid, lds, s);
     return hipErrorInvalidValue;
 }
 

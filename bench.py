@@ -43,9 +43,10 @@ import numpy as np
 METRIC = "KV quantize-append GB/s and decode-attention tokens/s on 2-bit cache, % HBM peak"
 HBM_PEAK_GBPS = 8000.0
 MFMA_F16_PEAK_TFLOPS = 2500.0
-# vector-ALU lane operations per second for one-result-per-lane binary32 instructions (subtract, min, max):
-# 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz.  (The published 157.3 TFLOP/s counts 2 flops of an FMA and the
-# two halves of packed operations; a subtract or a maximum is one lane operation.)
+# vector-ALU lane operations per second at one wave-wide instruction per SIMD every four cycles: 256 compute units
+# x 4 SIMDs x 16 lanes x 2.4 GHz.  (The published 157.3 TFLOP/s counts 2 flops of an FMA at twice that issue rate,
+# which plain add / multiply / fma / and / shift reach on this chip; min, max, the mixed-precision and three-operand
+# forms issue every four cycles - see measured_peaks and the instruction table in the design doc.)
 VALU_LANE_OPS_PEAK_T = 256 * 4 * 16 * 2.4e9 / 1e12
 
 WORKLOADS = {
@@ -53,6 +54,9 @@ WORKLOADS = {
     "cfg2x32": dict(spec="cfg2", layers=32, batch=1, P=64, iters=10, group=64, recent=0, flush=64),
     "cfg3": dict(spec="cfg3", layers=32, batch=16, P=128, iters=10, group=64, recent=128, flush=128),
     "cfg5": dict(spec="cfg5", layers=1, batch=1, P=256, iters=20, group=128, recent=0, flush=128),
+    # second workload: the latent cache of multi-head latent attention (one stream per sequence, 8 query heads)
+    "mla": dict(spec="mla", layers=27, batch=16, P=128, iters=10, group=64, recent=128, flush=128),
+    "mla_prerope": dict(spec="mla_prerope", layers=27, batch=16, P=128, iters=10, group=64, recent=128, flush=128),
     "cfg4": dict(spec="cfg4"),   # streaming: its own step, see run_streaming()
     "cfg3r": dict(spec="cfg3"),  # config 3's shape with a mix of sequence lengths: decode only, see run_ragged()
 }
@@ -87,9 +91,14 @@ def run_static(name, args, torch, pk, synth, steps, warmup, metric=None, cpu_bas
     dev = "cuda"
     metric = pk.METRIC_L2 if metric is None else metric
     w = WORKLOADS[name]
-    base = synth.SPECS[w["spec"]]
-    spec = synth.KVSpec(**{**base.__dict__, "n_layers": w["layers"], "batch": w["batch"]})
-    L, B, Hkv, Hq, T, d = w["layers"], w["batch"], spec.n_kv_heads, spec.n_q_heads, spec.T, spec.d
+    mla = w["spec"] in synth.MLA_SPECS
+    if mla:
+        spec = synth.MLASpec(**{**synth.MLA_SPECS[w["spec"]].__dict__, "n_layers": w["layers"], "batch": w["batch"]})
+        L, B, Hkv, Hq, T, d = w["layers"], w["batch"], 1, spec.n_q_heads, spec.T, spec.d
+    else:
+        base = synth.SPECS[w["spec"]]
+        spec = synth.KVSpec(**{**base.__dict__, "n_layers": w["layers"], "batch": w["batch"]})
+        L, B, Hkv, Hq, T, d = w["layers"], w["batch"], spec.n_kv_heads, spec.n_q_heads, spec.T, spec.d
     P, iters, G, R, F, bits = w["P"], w["iters"], w["group"], w["recent"], w["flush"], args.bits
     n_seq = L * B
     N = n_seq * Hkv
@@ -97,7 +106,12 @@ def run_static(name, args, torch, pk, synth, steps, warmup, metric=None, cpu_bas
 
     # ---------------------------------------------------------------- inputs, resident in HBM
     t_gen = time.time()
-    if n_seq == 1:
+    if mla:
+        K = torch.empty((n_seq, Hkv, T, d), dtype=torch.float16, device=dev)
+        V = torch.empty_like(K)
+        for layer in range(L):
+            K[layer * B:(layer + 1) * B], V[layer * B:(layer + 1) * B] = synth.make_mla_layer_device(args.seed, layer, spec, dev)
+    elif n_seq == 1:
         Kh, Vh = synth.make_kv(args.seed, spec)
         K = torch.from_numpy(Kh.view(np.int16)).to(dev).view(torch.float16)
         V = torch.from_numpy(Vh.view(np.int16)).to(dev).view(torch.float16)
@@ -195,10 +209,11 @@ def run_static(name, args, torch, pk, synth, steps, warmup, metric=None, cpu_bas
         q_roof = roof("quantize_append", "hbm", quant_bytes / q_s / 1e9, HBM_PEAK_GBPS, "GB/s",
                       "quantize_k_wave_kernel+quantize_v_kernel")
     else:
-        # d_mm of one vector against one pattern: d subtractions, d maxima, d minima in binary32 (Sec. 3.2)
-        lane_ops = 2.0 * N * cap * P * 3 * d
+        # d_mm of one vector against one pattern (Sec. 3.2) in its shortest instruction form: d binary32 subtractions,
+        # d/2 three-operand maxima and d/2 three-operand minima = 2 lane operations per channel, for K and for V
+        lane_ops = 2.0 * N * cap * P * 2 * d
         q_roof = roof("quantize_append", "alu", lane_ops / q_s / 1e12, round(VALU_LANE_OPS_PEAK_T, 2), "T lane-ops/s",
-                      "quantize_k_minmax_kernel+quantize_v_minmax_kernel")
+                      "assign_minmax_kernel(+quantize_k_wave_kernel+quantize_v_kernel)")
         q_roof["hbm_GB/s"] = round(quant_bytes / q_s / 1e9, 2)
     rl = {
         "mine": mine_roof,
@@ -456,9 +471,9 @@ def measure_peaks(torch, pk):
         "hbm_read_GB/s": round(nbytes / t_read / 1e6, 1), "hbm_copy_GB/s": round(nbytes / t_copy / 1e6, 1),
         "fma_f32_TFLOP/s": round(2.0 * 16 * fma_iters * 2048 * 256 / t_fma / 1e9, 2),
         "mfma_f16_TFLOP/s": round(2.0 * 16 * 16 * 32 * 8 * mfma_iters * 2048 * 4 / t_mfma / 1e9, 1),
-        "note": "read: 4 GiB streamed once; copy: 2 GiB read + 2 GiB written; fma: v_fma_f32 (no packed fp32 in this "
-                "build: half of the published 157.3 TFLOP/s is the ceiling); mfma: v_mfma_f32_16x16x32_f16, 8 "
-                "independent accumulators per wave",
+        "note": "read: 4 GiB streamed once; copy: 2 GiB read + 2 GiB written; fma: plain v_fma_f32, 16 independent chains "
+                "per lane (this build uses no packed fp32 instructions); mfma: v_mfma_f32_16x16x32_f16, 8 independent "
+                "accumulators per wave",
     }
 
 
@@ -592,7 +607,7 @@ def main():
 
     if args.workload == "cfg3" and not args.no_sweep and metric == pk.METRIC_L2:
         sweep = {}
-        for wname in ("cfg2x32", "cfg5"):
+        for wname in ("cfg2x32", "cfg5", "mla"):
             s = run_static(wname, args, torch, pk, synth, 10, 2)
             torch.cuda.empty_cache()
             sweep[wname] = {st: {"ms": s["stages"][st]["ms"], "bound": s["stage_rooflines"][st]["bound"],

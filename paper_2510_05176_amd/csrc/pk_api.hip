@@ -258,6 +258,7 @@ pk_status pk_quantize_append(const pk_config *cfg, const pk_cache *cache, pk_sta
         a.sets.seqs_per_set = cfg->seqs_per_set;
         a.P = cfg->n_patterns;
         a.metric = cfg->metric;
+        a.idx_given = 0;
         a.v_rho = 0.f;
         a.bits = cfg->bits;
         a.G = cfg->group;

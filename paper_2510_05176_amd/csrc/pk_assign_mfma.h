@@ -27,8 +27,7 @@ constexpr int kTabStride = kD + 16;   // halves per pattern row in LDS: 288 B = 
 __host__ __device__ constexpr int pad16(int p) { return (p + 15) & ~15; }
 
 struct PatternTable {
-    const __half *lds_rows;   // LDS copy, pad16(P) rows of stride kTabStride, rows past P are zero (TAB_LDS kernels)
-    const __half *glb_rows;   // global table, row stride kD
+    const __half *lds_rows;   // LDS copy, pad16(P) rows of stride kTabStride, rows past P are zero
     const float *nh;          // LDS [pad16(P)]: -||m_p||^2 / 2, -inf past P
     float norm2_max;          // max_p ||m_p||^2
     int P;
@@ -43,7 +42,7 @@ __device__ __forceinline__ floatx4_t mfma_f16(const uint4 &a, const uint4 &b, fl
 // guarded) and compute the row norms; red_s gets one maximum per wave.  Ends with a barrier.
 // Work item i = (row i/16, 16-byte piece i%16): the 16 lanes of a row sum their squares.
 __device__ __forceinline__ void stage_patterns(const __half *Mg, int P, __half *tab_s, float *nh_s, float *red_s,
-                                               bool to_lds, int nthr = 256)
+                                               int nthr = 256)
 {
     const int tid = threadIdx.x;
     float mx = 0.f;
@@ -53,7 +52,7 @@ __device__ __forceinline__ void stage_patterns(const __half *Mg, int P, __half *
         const int r = i >> 4, ch = i & 15;
         uint4 v = make_uint4(0u, 0u, 0u, 0u);
         if (r < P) v = *reinterpret_cast<const uint4 *>(Mg + (int64_t)r * kD + ch * 8);
-        if (to_lds) *reinterpret_cast<uint4 *>(tab_s + r * kTabStride + ch * 8) = v;   // rows past P are zero
+        *reinterpret_cast<uint4 *>(tab_s + r * kTabStride + ch * 8) = v;   // rows past P are zero
         const half2_t *h = reinterpret_cast<const half2_t *>(&v);
         float acc = 0.f;
 #pragma unroll
@@ -75,11 +74,9 @@ struct PatternTile {
     float4 nh;
 };
 
-template <bool TAB_LDS>
 __device__ __forceinline__ void load_pattern_tile(const PatternTable &tb, int p0, int n, int kb, PatternTile &t)
 {
-    const __half *arow = TAB_LDS ? tb.lds_rows + (p0 + n) * kTabStride + 8 * kb
-                                 : tb.glb_rows + (int64_t)min(p0 + n, tb.P - 1) * kD + 8 * kb;
+    const __half *arow = tb.lds_rows + (p0 + n) * kTabStride + 8 * kb;
 #pragma unroll
     for (int s = 0; s < 4; ++s) t.a[s] = *reinterpret_cast<const uint4 *>(arow + 32 * s);
     t.nh = *reinterpret_cast<const float4 *>(tb.nh + p0 + 4 * kb);
@@ -108,7 +105,7 @@ __device__ __forceinline__ void rank_pattern_tile(const uint4 (&xb)[4], const Pa
 // NT 16-token tiles held as B operands xb[j][4] (K-step s in xb[j][s]); every pattern tile read from the table
 // serves all NT of them.  Returns, in every lane of column n, per tile: best index, best squared distance (from
 // the expanded form, low 8 mantissa bits dropped), ||x||^2 and whether the token needs the exact re-evaluation.
-template <bool TAB_LDS, int NT>
+template <int NT>
 __device__ __forceinline__ void assign_tiles_mfma(const uint4 (&xb)[NT][4], const PatternTable &tb, int lane, int (&best_i)[NT],
                                                   float (&best_v)[NT], float (&x2)[NT], bool (&flag)[NT])
 {
@@ -135,13 +132,13 @@ __device__ __forceinline__ void assign_tiles_mfma(const uint4 (&xb)[NT][4], cons
     for (int j = 0; j < NT; ++j) k1[j] = k2[j] = 0xffffffffu;   // above every key
     const int Pp = pad16(tb.P);
     PatternTile ta, tc;
-    load_pattern_tile<TAB_LDS>(tb, 0, n, kb, ta);
+    load_pattern_tile(tb, 0, n, kb, ta);
     for (int p0 = 0;;) {   // two tiles per round, the next one in flight while the current is ranked
-        if (p0 + 16 < Pp) load_pattern_tile<TAB_LDS>(tb, p0 + 16, n, kb, tc);
+        if (p0 + 16 < Pp) load_pattern_tile(tb, p0 + 16, n, kb, tc);
 #pragma unroll
         for (int j = 0; j < NT; ++j) rank_pattern_tile(xb[j], ta, hx[j], p0, k1[j], k2[j]);
         if ((p0 += 16) >= Pp) break;
-        if (p0 + 16 < Pp) load_pattern_tile<TAB_LDS>(tb, p0 + 16, n, kb, ta);
+        if (p0 + 16 < Pp) load_pattern_tile(tb, p0 + 16, n, kb, ta);
 #pragma unroll
         for (int j = 0; j < NT; ++j) rank_pattern_tile(xb[j], tc, hx[j], p0, k1[j], k2[j]);
         if ((p0 += 16) >= Pp) break;
@@ -167,14 +164,13 @@ __device__ __forceinline__ void assign_tiles_mfma(const uint4 (&xb)[NT][4], cons
 }
 
 // One 16-token tile.
-template <bool TAB_LDS>
 __device__ __forceinline__ void assign_tile_mfma(const uint4 (&xb)[4], const PatternTable &tb, int lane, int &best_i,
                                                  float &best_v, float &x2, bool &flag)
 {
     int bi[1];
     float bv[1], xx[1];
     bool fl[1];
-    assign_tiles_mfma<TAB_LDS, 1>(reinterpret_cast<const uint4 (&)[1][4]>(xb), tb, lane, bi, bv, xx, fl);
+    assign_tiles_mfma<1>(reinterpret_cast<const uint4 (&)[1][4]>(xb), tb, lane, bi, bv, xx, fl);
     best_i = bi[0];
     best_v = bv[0];
     x2 = xx[0];

@@ -634,9 +634,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
 template <int BITS, bool G32, bool HALF>
 static hipError_t launch_one(const DecodeArgs &a, dim3 grid, size_t lds, hipStream_t s)
 {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_packed_kernel<BITS, G32, HALF>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    // the most any launch of this instantiation needs: 256 patterns, 8 heads per KV head, 256 mass slots per head
+    static LdsOptIn opt_in;
+    constexpr size_t kMaxLds = (size_t)256 * 16 * 4 + (size_t)4 * 8 * 256 * 8;
+    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(&decode_packed_kernel<BITS, G32, HALF>), opt_in, kMaxLds);
     if (e != hipSuccess) return e;
+    if (lds > kMaxLds) return hipErrorInvalidValue;
     hipLaunchKernelGGL((decode_packed_kernel<BITS, G32, HALF>), grid, dim3(256), lds, s, a);
     return hipGetLastError();
 }

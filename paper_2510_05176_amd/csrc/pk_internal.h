@@ -6,6 +6,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "patternkv.h"
 
 namespace pk {
@@ -75,11 +77,32 @@ __device__ __forceinline__ unsigned short f2h_up(float f)
 
 // ---- launchers (host) -------------------------------------------------------
 
+// A kernel that uses more than 64 KB of dynamic LDS has to be allowed to, per function and device.  This is done
+// once per kernel instantiation and device, with the most that instantiation can ever be launched with, so
+// that concurrent calls with different sizes cannot lower each other's limit and a launch costs no extra
+// runtime call.
+struct LdsOptIn {
+    std::mutex m;
+    uint64_t devices_done = 0;
+};
+inline hipError_t allow_dynamic_lds(const void *kernel, LdsOptIn &st, size_t max_bytes)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lock(st.m);
+    if (dev < 64 && ((st.devices_done >> dev) & 1u)) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)max_bytes);
+    if (e == hipSuccess && dev < 64) st.devices_done |= 1ull << dev;
+    return e;
+}
+
 struct QuantArgs {
     RowSource src;
     SetMap sets;
     const __half *patterns;   // [n_sets][P][kD]
     int32_t P, metric, bits, G;
+    int32_t idx_given;        // the index array already holds every vector's pattern (min-max metric: searched by a kernel of its own)
     float v_rho;              // V side: adaptive threshold (0 = off)
     int32_t n_streams;
     int32_t nq;               // vectors to quantize per stream (multiple of G)

@@ -34,7 +34,7 @@ __global__ __launch_bounds__(256) void mine_init_kernel(MineArgs a)
 // group's lanes address four to a row.  The one-hot operand is formed in packed fp16 as
 // clamp(1 - (idx_t - p)^2, 0, 1), which is exactly 1 or 0 for integers below 256; products are exact and the
 // accumulation order is fixed by the instruction sequence, so the sums are reproducible.
-// Dynamic LDS: [table pad16(P) rows (TAB_LDS only)] [-norm2/2 pad16(P)] [cnt pad16(P)] [xs 16 NT NW rows]
+// Dynamic LDS: [table pad16(P) rows] [-norm2/2 pad16(P)] [cnt pad16(P)] [xs 16 NT NW rows]
 //              [idx 16 NT NW halves] [xrow NW*kD halves]
 constexpr int kMineXs = kD + 16;   // halves per row of the vector tile: 72 words, so the eight rows that 32 lanes
                                    // of a transposing read touch (8 words each) fall on 64 distinct banks
@@ -43,13 +43,13 @@ typedef _Float16 half2m __attribute__((ext_vector_type(2)));
 typedef short short4m __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) short4m *lds_short4_ptr;
 
-template <bool TAB_LDS, int NPT, int NW, int NT>
+template <int NPT, int NW, int NT>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NT == 1 && NPT <= 4 ? 4 : 2))) void mine_step_kernel(MineArgs a, int chunk, int outputs)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const int P = a.P;
     __half *tab_s = reinterpret_cast<__half *>(smem);
-    float *norm_s = reinterpret_cast<float *>(smem + (TAB_LDS ? (size_t)pad16(P) * kTabStride * 2 : 0));
+    float *norm_s = reinterpret_cast<float *>(smem + (size_t)pad16(P) * kTabStride * 2);
     int *cnt = reinterpret_cast<int *>(norm_s + pad16(P));
     __half *xs = reinterpret_cast<__half *>(cnt + pad16(P));
     constexpr int ST = 16 * NT * NW;     // vectors per sub-tile: NT 16-vector tiles per wave
@@ -75,10 +75,9 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NT == 1
     load_tile(0, xb);
 
     for (int i = tid; i < pad16(P); i += 64 * NW) cnt[i] = 0;
-    stage_patterns(Mg, P, tab_s, norm_s, red_s, TAB_LDS, 64 * NW);   // ends with a barrier
+    stage_patterns(Mg, P, tab_s, norm_s, red_s, 64 * NW);   // ends with a barrier
     PatternTable tb;
     tb.lds_rows = tab_s;
-    tb.glb_rows = Mg;
     tb.nh = norm_s;
     tb.norm2_max = red_s[0];
 #pragma unroll
@@ -106,7 +105,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NT == 1
         int bi[NT];
         float bv[NT], x2[NT];
         bool flag[NT];
-        assign_tiles_mfma<TAB_LDS, NT>(xb, tb, lane, bi, bv, x2, flag);
+        assign_tiles_mfma<NT>(xb, tb, lane, bi, bv, x2, flag);
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
             const int tl = (wave * NT + j) * 16 + n, tok = sub * ST + tl;
@@ -254,9 +253,9 @@ __global__ __launch_bounds__(256) void window_pattern_kernel(const __half *x, in
     }
 }
 
-size_t step_lds_bytes(int P, int nw, int nt, bool tab_lds)
+size_t step_lds_bytes(int P, int nw, int nt)
 {
-    size_t b = tab_lds ? (size_t)pad16(P) * kTabStride * 2 : 0;
+    size_t b = (size_t)pad16(P) * kTabStride * 2;
     b += (size_t)pad16(P) * 4 + (size_t)pad16(P) * 4 + 16 * nw * nt * (size_t)kMineXs * 2 + 16 * nw * nt * 2 + (size_t)nw * kD * 2;
     return (b + 15) / 16 * 16;
 }
@@ -286,15 +285,15 @@ int mine_tsplit(int T, int n_sets, int P) { return (T + mine_chunk(T, n_sets, P)
 template <int NPT, int NW, int NT>
 static hipError_t launch_step(const MineArgs &a, int chunk, size_t lds, hipStream_t s, int outputs)
 {
-    hipLaunchKernelGGL((mine_step_kernel<true, NPT, NW, NT>), dim3(a.tsplit, a.n_sets), dim3(64 * NW), lds, s, a, chunk, outputs);
+    hipLaunchKernelGGL((mine_step_kernel<NPT, NW, NT>), dim3(a.tsplit, a.n_sets), dim3(64 * NW), lds, s, a, chunk, outputs);
     return hipGetLastError();
 }
 
 template <int NPT, int NW, int NT>
-static hipError_t prepare_step(const MineArgs &, int, size_t lds, hipStream_t, int)
+static hipError_t prepare_step(const MineArgs &, int, size_t, hipStream_t, int)
 {
-    return hipFuncSetAttribute(reinterpret_cast<const void *>(&mine_step_kernel<true, NPT, NW, NT>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    static LdsOptIn opt_in;   // the most this instantiation needs: a table of 16 * NPT patterns
+    return allow_dynamic_lds(reinterpret_cast<const void *>(&mine_step_kernel<NPT, NW, NT>), opt_in, step_lds_bytes(16 * NPT, NW, NT));
 }
 
 hipError_t launch_mine(const MineArgs &a, hipStream_t s)
@@ -308,7 +307,7 @@ hipError_t launch_mine(const MineArgs &a, hipStream_t s)
     // serves 32 vectors (at 64 patterns and below the smaller tile and the higher occupancy win).
     const int nt = npt >= 8 ? 2 : 1;
     const int nw = a.P > 128 ? 8 : 4;
-    const size_t lds = step_lds_bytes(a.P, nw, nt, true);
+    const size_t lds = step_lds_bytes(a.P, nw, nt);
 #define PK_STEP(CALL)                                                                                       \
     (npt == 1 ? CALL<1, 4, 1> : npt == 2 ? CALL<2, 4, 1> : npt == 4 ? CALL<4, 4, 1> : npt == 8 ? CALL<8, 4, 2> : CALL<16, 8, 2>)
     if ((e = PK_STEP(prepare_step)(a, chunk, lds, s, 0)) != hipSuccess) return e;

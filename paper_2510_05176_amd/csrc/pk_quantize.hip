@@ -9,7 +9,6 @@
 // that the sequence is exactly what is written.
 #pragma clang fp contract(off)
 
-#include "pk_assign.h"
 #include "pk_assign_mfma.h"
 #include "pk_divide.h"
 #include "pk_internal.h"
@@ -45,167 +44,110 @@ __device__ __forceinline__ int quantize_one(float r, const GroupParams &g, int b
 }
 
 // ---------------------------------------------------------------------------
-// K: one workgroup (128 threads) per (group of G tokens, stream).
+// Min-max metric (Sec. 3.2): d_mm(x, m) = max_c (x_c - m_c) - min_c (x_c - m_c), argmin over the patterns, lowest
+// index on ties.  Every operation is exact in binary32 apart from one correctly rounded subtraction per
+// channel (fp16 values widened exactly), so the result is the definition's, bit for bit; it is not a
+// contraction and runs on the vector ALUs.  A wave takes 64 vectors, lane <-> vector, the vector's 128 channels
+// in registers as binary32; a pattern row is wave-uniform and comes through the scalar data path as packed fp16,
+// which the mixed-precision subtract (x * 1.0 - m with the fp16 half widened) reads directly: per pattern and
+// vector 128 subtractions and 128 three-operand maxima / minima.  The indices go to the cache's index array; the
+// quantizers below then skip their own search.
 // ---------------------------------------------------------------------------
-template <int G, int BITS>
-__global__ __launch_bounds__(128) void quantize_k_valu_kernel(QuantArgs a)
+__device__ __forceinline__ float sub_s_lo(float x, uint32_t m)   // x - half(m.lo), m wave-uniform
 {
-    __shared__ __align__(16) __half xs[G * kXsStride];
-    __shared__ AssignScratch sc;
-    __shared__ int idx_s[G];
-    __shared__ __align__(16) uint32_t pack_s[G * 4 * BITS];
-
-    const int g = blockIdx.x, n = blockIdx.y, tid = threadIdx.x;
-    const __half *Mg = a.patterns + (int64_t)a.sets.set_of(n) * a.P * kD;
-
-    stage_rows(xs, G, [&](int r) { return a.src.row(n, g * G + r); });
-    // assign_tile starts with a barrier that also publishes xs
-    assign_tile<G>(xs, G, Mg, a.P, a.metric, sc, idx_s, nullptr);
-
-    const int64_t tq = (int64_t)a.t0 + (int64_t)g * G;   // first packed position of this group
-    if (tid < G) a.idx[(int64_t)n * a.t_capacity + tq + tid] = (uint8_t)idx_s[tid];
-
-    // thread <-> channel
-    const int c = tid;
-    float mn = INFINITY, mx = -INFINITY;
-    for (int t = 0; t < G; ++t) {
-        const float r = h2f(xs[t * kXsStride + c]) - h2f(Mg[(int64_t)idx_s[t] * kD + c]);
-        mn = fminf(mn, r);
-        mx = fmaxf(mx, r);
-    }
-    const GroupParams gp = group_params(mn, mx, BITS);
-    const int64_t grow = ((int64_t)n * (a.t_capacity / G) + tq / G) * kD + c;
-    a.scale[grow] = __ushort_as_half(gp.s16);
-    a.zero[grow] = __ushort_as_half(gp.z16);
-
-    const int wave = tid >> 6, lane = tid & 63;
-    for (int t = 0; t < G; ++t) {
-        const float r = h2f(xs[t * kXsStride + c]) - h2f(Mg[(int64_t)idx_s[t] * kD + c]);
-        const int code = quantize_one(r, gp, BITS);
-#pragma unroll
-        for (int j = 0; j < BITS; ++j) {
-            const unsigned long long m = __ballot((code >> j) & 1);
-            if (lane == 0) {
-                pack_s[(t * 4 + 2 * wave) * BITS + j] = (uint32_t)m;
-                pack_s[(t * 4 + 2 * wave + 1) * BITS + j] = (uint32_t)(m >> 32);
-            }
-        }
-    }
-    __syncthreads();
-    uint4 *dst = reinterpret_cast<uint4 *>(a.codes_k + ((int64_t)n * a.t_capacity + tq) * 4 * BITS);
-    const uint4 *srcp = reinterpret_cast<const uint4 *>(pack_s);
-    for (int i = tid; i < G * BITS; i += 128) dst[i] = srcp[i];
+    float r;
+    asm("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel:[0,0,0] op_sel_hi:[0,0,1]" : "=v"(r) : "v"(x), "s"(m));
+    return r;
+}
+__device__ __forceinline__ float sub_s_hi(float x, uint32_t m)   // x - half(m.hi)
+{
+    float r;
+    asm("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel:[0,0,1] op_sel_hi:[0,0,1]" : "=v"(r) : "v"(x), "s"(m));
+    return r;
 }
 
-// ---------------------------------------------------------------------------
-// V: one workgroup (128 threads) per (block of 64 tokens, stream).
-// ---------------------------------------------------------------------------
-template <int BITS>
-__global__ __launch_bounds__(128) void quantize_v_valu_kernel(QuantArgs a)
+// Sixteen consecutive dwords through the scalar data path (read only; address wave-uniform, 4-byte aligned), and the
+// wait for every scalar load issued so far; the values are tied to the wait so that no use can move ahead of it.
+typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
+__device__ __forceinline__ u32x16 sload16(const uint32_t *p)
 {
-    constexpr int TV = 64;
-    constexpr int WPU = BITS / 2;   // 32-bit words per (channel, 16-token unit)
-    __shared__ __align__(16) __half xs[TV * kXsStride];
-    __shared__ AssignScratch sc;
-    __shared__ int idx_s[TV];
-    __shared__ float red_mn[TV][4], red_mx[TV][4], raw_mn[TV][4], raw_mx[TV][4];
-    __shared__ __align__(16) uint32_t out_s[TV * kD * BITS / 32];
-    __shared__ __align__(16) unsigned short par_s[2][4 * 4 * 16];   // scale / zero slices: [unit][group][16]
-
-    const int tile = blockIdx.x, n = blockIdx.y, tid = threadIdx.x;
-    const __half *Mg = a.patterns + (int64_t)a.sets.set_of(n) * a.P * kD;
-
-    stage_rows(xs, TV, [&](int r) { return a.src.row(n, tile * TV + r); });
-    assign_tile<TV>(xs, TV, Mg, a.P, a.metric, sc, idx_s, nullptr);
-
-    const int64_t tq = (int64_t)a.t0 + (int64_t)tile * TV;
-    const bool thr = a.v_rho > 0.f;
-
-    const int c = tid, lane = tid & 63, quarter = tid >> 5;
-    // phase A: min / max of every 32-channel quarter of every token, of the residual and (for the adaptive
-    // threshold) of the vector itself
-    for (int t = 0; t < TV; ++t) {
-        const float xv = h2f(xs[t * kXsStride + c]);
-        const float r = xv - h2f(Mg[(int64_t)idx_s[t] * kD + c]);
-        float mn = r, mx = r, xn = xv, xx = xv;
-#pragma unroll
-        for (int off = 1; off < 32; off <<= 1) {
-            mn = fminf(mn, __shfl_xor(mn, off));
-            mx = fmaxf(mx, __shfl_xor(mx, off));
-            if (thr) {
-                xn = fminf(xn, __shfl_xor(xn, off));
-                xx = fmaxf(xx, __shfl_xor(xx, off));
-            }
-        }
-        if ((lane & 31) == 0) {
-            red_mn[t][quarter] = mn;
-            red_mx[t][quarter] = mx;
-            raw_mn[t][quarter] = xn;
-            raw_mx[t][quarter] = xx;
-        }
-    }
-    __syncthreads();
-    // adaptive threshold (Sec. 3.3): keep the pattern iff R_flat <= rho * R_raw over the whole vector
-    if (tid < TV) {
-        int id = idx_s[tid];
-        if (thr) {
-            const float rf = fmaxf(fmaxf(red_mx[tid][0], red_mx[tid][1]), fmaxf(red_mx[tid][2], red_mx[tid][3])) -
-                             fminf(fminf(red_mn[tid][0], red_mn[tid][1]), fminf(red_mn[tid][2], red_mn[tid][3]));
-            const float rr = fmaxf(fmaxf(raw_mx[tid][0], raw_mx[tid][1]), fmaxf(raw_mx[tid][2], raw_mx[tid][3])) -
-                             fminf(fminf(raw_mn[tid][0], raw_mn[tid][1]), fminf(raw_mn[tid][2], raw_mn[tid][3]));
-            if (!(rf <= a.v_rho * rr)) id = PK_NO_PATTERN;
-        }
-        idx_s[tid] = id;
-        a.idx[(int64_t)n * a.t_capacity + tq + tid] = (uint8_t)id;
-    }
-    __syncthreads();
-    // phase B: stored parameters, codes, bit planes along the tokens (16 tokens per word)
-    const int Gc = a.G < kD ? a.G : kD;
-    const int ng = kD / Gc, qpg = Gc / 32;   // channel groups per token, quarters per group
-    const int grp = c / Gc;
-    uint32_t acc[BITS];
-#pragma unroll
-    for (int j = 0; j < BITS; ++j) acc[j] = 0;
-    for (int t = 0; t < TV; ++t) {
-        const bool raw = thr && idx_s[t] == PK_NO_PATTERN;   // quantized without a pattern
-        const float(*smn)[4] = raw ? raw_mn : red_mn;
-        const float(*smx)[4] = raw ? raw_mx : red_mx;
-        float mn = smn[t][grp * qpg], mx = smx[t][grp * qpg];
-        for (int k = 1; k < qpg; ++k) {
-            mn = fminf(mn, smn[t][grp * qpg + k]);
-            mx = fmaxf(mx, smx[t][grp * qpg + k]);
-        }
-        const GroupParams gp = group_params(mn, mx, BITS);
-        if (c % Gc == 0) {
-            par_s[0][((t >> 4) * ng + grp) * 16 + (t & 15)] = gp.s16;
-            par_s[1][((t >> 4) * ng + grp) * 16 + (t & 15)] = gp.z16;
-        }
-        const float r = raw ? h2f(xs[t * kXsStride + c]) : h2f(xs[t * kXsStride + c]) - h2f(Mg[(int64_t)idx_s[t] * kD + c]);
-        const int code = quantize_one(r, gp, BITS);
-#pragma unroll
-        for (int j = 0; j < BITS; ++j) acc[j] |= (uint32_t)((code >> j) & 1) << (t & 15);
-        if ((t & 15) == 15) {
-            const int unit = t >> 4;   // 16-token unit inside the block
-#pragma unroll
-            for (int w = 0; w < WPU; ++w) {
-                out_s[((unit * 16 + (c & 15)) * (kD / 16) + (c >> 4)) * WPU + w] = acc[2 * w] | (acc[2 * w + 1] << 16);
-                acc[2 * w] = acc[2 * w + 1] = 0;
-            }
-        }
-    }
-    __syncthreads();
-    uint4 *dst = reinterpret_cast<uint4 *>(a.codes_v + ((int64_t)n * a.t_capacity + tq) * (kD * BITS / 8));
-    const uint4 *srcp = reinterpret_cast<const uint4 *>(out_s);
-    for (int i = tid; i < TV * kD * BITS / 8 / 16; i += 128) dst[i] = srcp[i];
-    // parameters of the block: 4 units x ng groups x 16 tokens, contiguous in memory
-    const int npar = 4 * ng * 16;
-    const int64_t pbase = ((int64_t)n * a.t_capacity + tq) * ng;
-    for (int i = tid; i < npar; i += 128) {
-        a.scale[pbase + i] = __ushort_as_half(par_s[0][i]);
-        a.zero[pbase + i] = __ushort_as_half(par_s[1][i]);
-    }
+    u32x16 r;
+    asm volatile("s_load_dwordx16 %0, %1, 0x0" : "=s"(r) : "s"(p) : "memory");
+    return r;
+}
+__device__ __forceinline__ void swait2(u32x16 &r0, u32x16 &r1)
+{
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(r0), "+s"(r1));
 }
 
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void assign_minmax_kernel(QuantArgs a, int tiles_per_wg)
+{
+    const int tid = threadIdx.x, lane = tid & 63, ns = blockIdx.y;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint32_t *Mg = reinterpret_cast<const uint32_t *>(a.patterns + (int64_t)a.sets.set_of(ns) * a.P * kD);
+    const int n_tiles = a.nq / 64;
+    const int tile0 = blockIdx.x * tiles_per_wg, tile1 = min(n_tiles, tile0 + tiles_per_wg);
+    for (int tile = tile0 + wave; tile < tile1; tile += 4) {
+        // the lane's vector, widened
+        float x[kD];
+        {
+            const __half *row = a.src.row(ns, tile * 64 + lane);
+#pragma unroll
+            for (int ch = 0; ch < kRowChunks; ++ch) {
+                const uint4 v = *reinterpret_cast<const uint4 *>(row + 8 * ch);
+                const __half2 *h2 = reinterpret_cast<const __half2 *>(&v);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    x[8 * ch + 2 * k] = __low2float(h2[k]);
+                    x[8 * ch + 2 * k + 1] = __high2float(h2[k]);
+                }
+            }
+        }
+        float best = INFINITY;
+        int best_p = 0;
+        // A pattern row is taken in two halves of 64 channels (32 scalar registers each).  Scalar loads return
+        // in any order, so a wait covers all that are outstanding: the next half is requested right after the
+        // wait for the current one and arrives under the 192 vector operations of that half.
+        u32x16 a0 = sload16(Mg), a1 = sload16(Mg + 16), b0, b1;
+        // two running maxima and minima, so that consecutive operations do not wait for each other
+        float mxa, mxb, mna, mnb;
+        auto scan = [&](const u32x16 &m, int c0) {   // channels c0 .. c0+31
+#pragma unroll
+            for (int c4 = 0; c4 < 8; ++c4) {
+                const int c = c0 + 4 * c4;
+                const float d0 = sub_s_lo(x[c], m[2 * c4]), d1 = sub_s_hi(x[c + 1], m[2 * c4]);
+                const float d2 = sub_s_lo(x[c + 2], m[2 * c4 + 1]), d3 = sub_s_hi(x[c + 3], m[2 * c4 + 1]);
+                mxa = fmaxf(fmaxf(mxa, d0), d1);
+                mna = fminf(fminf(mna, d0), d1);
+                mxb = fmaxf(fmaxf(mxb, d2), d3);
+                mnb = fminf(fminf(mnb, d2), d3);
+            }
+        };
+        for (int p = 0; p < a.P; ++p) {
+            const uint32_t *mrow = Mg + (size_t)p * (kD / 2);                                   // wave-uniform
+            const uint32_t *mnext = Mg + (size_t)min(p + 1, a.P - 1) * (kD / 2);                // (the last round repeats the last row; unused)
+            swait2(a0, a1);
+            b0 = sload16(mrow + 32);
+            b1 = sload16(mrow + 48);
+            mxa = mxb = -INFINITY;
+            mna = mnb = INFINITY;
+            scan(a0, 0);
+            scan(a1, 32);
+            swait2(b0, b1);
+            a0 = sload16(mnext);
+            a1 = sload16(mnext + 16);
+            scan(b0, 64);
+            scan(b1, 96);
+            const float dist = fmaxf(mxa, mxb) - fminf(mna, mnb);
+            if (dist < best) {   // patterns in increasing order: strict < keeps the lowest index
+                best = dist;
+                best_p = p;
+            }
+        }
+        swait2(a0, a1);   // nothing may be in flight into registers that the next tile reuses
+        a.idx[(int64_t)ns * a.t_capacity + a.t0 + tile * 64 + lane] = (uint8_t)best_p;
+    }
+}
 
 // ===========================================================================
 // Euclidean metric: nearest pattern on the matrix cores (pk_assign_mfma.h).  A wave owns 16-token
@@ -269,7 +211,7 @@ __device__ __forceinline__ uint32_t plane_byte_shifted(uint32_t lo, uint32_t hi,
 }
 
 struct TileShared {
-    __half *tab;      // [pad16(P)][kTabStride]   (TAB_LDS only)
+    __half *tab;      // [pad16(P)][kTabStride]
     float *nh;        // [pad16(P)]
     unsigned char *wsc;   // V: [4 waves][kWaveScratch] (re-evaluation row, output staging)
     float *red;       // [4]
@@ -288,10 +230,10 @@ constexpr int kWsZero = 1424;      // up to 128 B: zero points [group][16]
 constexpr int kWaveScratch = 1552;
 
 // TT = 0: no residual tile (V)
-__host__ __device__ inline size_t carve_offsets(int P, bool tab_lds, int TT, int G, size_t (&o)[7])
+__host__ __device__ inline size_t carve_offsets(int P, int TT, int G, size_t (&o)[7])
 {
     size_t at = 0;
-    o[0] = at; at += tab_lds ? (size_t)pad16(P) * kTabStride * 2 : 0;
+    o[0] = at; at += (size_t)pad16(P) * kTabStride * 2;
     o[1] = at; at += (size_t)pad16(P) * 4;
     o[2] = at; at += TT ? 0 : 4 * kWaveScratch;   // K stages in its own residual rows instead
     o[3] = at; at += 16;
@@ -302,10 +244,10 @@ __host__ __device__ inline size_t carve_offsets(int P, bool tab_lds, int TT, int
     return at;
 }
 
-__device__ __forceinline__ TileShared carve(unsigned char *smem, int P, bool tab_lds, int TT, int G)
+__device__ __forceinline__ TileShared carve(unsigned char *smem, int P, int TT, int G)
 {
     size_t o[7];
-    carve_offsets(P, tab_lds, TT, G, o);
+    carve_offsets(P, TT, G, o);
     TileShared t;
     t.tab = reinterpret_cast<__half *>(smem + o[0]);
     t.nh = reinterpret_cast<float *>(smem + o[1]);
@@ -317,17 +259,16 @@ __device__ __forceinline__ TileShared carve(unsigned char *smem, int P, bool tab
     return t;
 }
 
-static size_t tile_lds_bytes(int P, bool tab_lds, int TT, int G)
+static size_t tile_lds_bytes(int P, int TT, int G)
 {
     size_t o[7];
-    return carve_offsets(P, tab_lds, TT, G, o);
+    return carve_offsets(P, TT, G, o);
 }
 
 __device__ __forceinline__ PatternTable make_table(const TileShared &sh, const __half *Mg, int P)
 {
     PatternTable tb;
     tb.lds_rows = sh.tab;
-    tb.glb_rows = Mg;
     tb.nh = sh.nh;
     tb.norm2_max = fmaxf(fmaxf(sh.red[0], sh.red[1]), fmaxf(sh.red[2], sh.red[3]));
     tb.P = P;
@@ -344,11 +285,10 @@ __device__ __forceinline__ void load_tile(const QuantArgs &a, int ns, int i0, ui
 }
 
 // Residuals r[8k + j] of channel 32k + 8kb + j of the lane's token against pattern bi.
-template <bool TAB_LDS>
 __device__ __forceinline__ void residuals(const TileShared &sh, const __half *Mg, const uint4 (&xb)[4], int bi, float (&r)[32])
 {
     const int kb = (threadIdx.x & 63) >> 4;
-    const __half *mrow = TAB_LDS ? sh.tab + bi * kTabStride + 8 * kb : Mg + (int64_t)bi * kD + 8 * kb;
+    const __half *mrow = sh.tab + bi * kTabStride + 8 * kb;
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         const uint4 mv = *reinterpret_cast<const uint4 *>(mrow + 32 * k);
@@ -365,24 +305,22 @@ __device__ __forceinline__ void residuals(const TileShared &sh, const __half *Mg
 }
 
 // Nearest pattern of the tile's tokens (exact).
-template <bool TAB_LDS>
 __device__ __forceinline__ int assign_index(const PatternTable &tb, const __half *Mg, const uint4 (&xb)[4], __half *xrow)
 {
     const int lane = threadIdx.x & 63;
     int bi;
     float bv, x2, bd;
     bool flag;
-    assign_tile_mfma<TAB_LDS>(xb, tb, lane, bi, bv, x2, flag);
+    assign_tile_mfma(xb, tb, lane, bi, bv, x2, flag);
     resolve_flagged(xb, flag, xrow, tb, Mg, lane, bi, bd);
     return bi;
 }
 
-template <bool TAB_LDS>
 __device__ __forceinline__ int assign_residuals(const TileShared &sh, const PatternTable &tb, const __half *Mg,
                                                 const uint4 (&xb)[4], __half *xrow, float (&r)[32])
 {
-    const int bi = assign_index<TAB_LDS>(tb, Mg, xb, xrow);
-    residuals<TAB_LDS>(sh, Mg, xb, bi, r);
+    const int bi = assign_index(tb, Mg, xb, xrow);
+    residuals(sh, Mg, xb, bi, r);
     return bi;
 }
 
@@ -436,7 +374,7 @@ __device__ __forceinline__ void k_store_staging(const QuantArgs &a, int64_t tok0
 
 // K: workgroup = 256 threads, tiles of TT = max(64, G) tokens of one stream; wave w owns the 16-token
 // tiles w*NT .. w*NT + NT-1 of the tile.
-template <int G, int BITS, bool TAB_LDS>
+template <int G, int BITS>
 __global__ __launch_bounds__(256) void quantize_k_kernel(QuantArgs a, int tiles_per_wg)
 {
     constexpr int TT = G == 128 ? 128 : 64, NT = TT / 64;
@@ -444,7 +382,7 @@ __global__ __launch_bounds__(256) void quantize_k_kernel(QuantArgs a, int tiles_
     constexpr int CPR = 256 / LPC;        // channels per round of the scan
     constexpr int NGRP = TT / G;          // parameter groups per tile
     extern __shared__ __align__(16) unsigned char smem[];
-    const TileShared sh = carve(smem, a.P, TAB_LDS, TT, G);
+    const TileShared sh = carve(smem, a.P, TT, G);
     const int tid = threadIdx.x, ns = blockIdx.y;
     const int lane = tid & 63, wave = tid >> 6, n = lane & 15, kb = lane >> 4;
     const __half *Mg = a.patterns + (int64_t)a.sets.set_of(ns) * a.P * kD;
@@ -454,7 +392,7 @@ __global__ __launch_bounds__(256) void quantize_k_kernel(QuantArgs a, int tiles_
 #pragma unroll
     for (int j = 0; j < NT; ++j) load_tile(a, ns, tile0 * TT + (wave * NT + j) * 16, xb[j]);   // in flight while the table is staged
 
-    stage_patterns(Mg, a.P, sh.tab, sh.nh, sh.red, TAB_LDS);
+    stage_patterns(Mg, a.P, sh.tab, sh.nh, sh.red);
     const PatternTable tb = make_table(sh, Mg, a.P);
 
     const int q = tid % LPC, cc = tid / LPC;
@@ -462,10 +400,13 @@ __global__ __launch_bounds__(256) void quantize_k_kernel(QuantArgs a, int tiles_
         const int64_t tq0 = (int64_t)a.t0 + (int64_t)tile * TT;
         float r[NT][32];
         int bi[NT];
-        {   // the wave's NT 16-token tiles in one pass over the pattern table
+        if (a.idx_given) {   // searched beforehand (min-max metric)
+#pragma unroll
+            for (int j = 0; j < NT; ++j) bi[j] = a.idx[(int64_t)ns * a.t_capacity + tq0 + (wave * NT + j) * 16 + n];
+        } else {   // the wave's NT 16-token tiles in one pass over the pattern table
             float bv[NT], x2[NT];
             bool flag[NT];
-            assign_tiles_mfma<TAB_LDS, NT>(xb, tb, lane, bi, bv, x2, flag);
+            assign_tiles_mfma<NT>(xb, tb, lane, bi, bv, x2, flag);
 #pragma unroll
             for (int j = 0; j < NT; ++j) {
                 float bd;
@@ -477,7 +418,7 @@ __global__ __launch_bounds__(256) void quantize_k_kernel(QuantArgs a, int tiles_
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
             const int tl = (wave * NT + j) * 16 + n;   // token slot inside the tile
-            residuals<TAB_LDS>(sh, Mg, xb[j], bi[j], r[j]);
+            residuals(sh, Mg, xb[j], bi[j], r[j]);
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 float4 *dst = reinterpret_cast<float4 *>(sh.rt + tl * kRStride + 32 * k + 8 * kb);
@@ -557,12 +498,12 @@ constexpr int kWkStride = 32 + 4;                     // floats per row of the q
 constexpr int kWkTile = 16 * kWkStride * 4;           // bytes: 16 tokens x 32 channels (also the output staging area)
 constexpr int kWkWave = kWkTile + kD * 2 * 2 + kD * 4;   // + zero points, scales (fp16 bits), 1/s
 
-static size_t wave_k_lds_bytes(int P, bool tab_lds)
+static size_t wave_k_lds_bytes(int P)
 {
-    return (tab_lds ? (size_t)pad16(P) * kTabStride * 2 : 0) + (size_t)pad16(P) * 4 + 16 + 4 * (size_t)kWkWave;
+    return (size_t)pad16(P) * kTabStride * 2 + (size_t)pad16(P) * 4 + 16 + 4 * (size_t)kWkWave;
 }
 
-template <int G, int BITS, bool TAB_LDS, int NTA>
+template <int G, int BITS, int NTA>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NTA > 2 ? 2 : 3))) void quantize_k_wave_kernel(QuantArgs a, int tiles_per_wg)
 {
     constexpr int NTG = G / 16;
@@ -572,7 +513,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NTA > 2 ? 2
     TileShared sh;
     size_t at = 0;
     sh.tab = reinterpret_cast<__half *>(smem);
-    at += TAB_LDS ? (size_t)pad16(a.P) * kTabStride * 2 : 0;
+    at += (size_t)pad16(a.P) * kTabStride * 2;
     sh.nh = reinterpret_cast<float *>(smem + at);
     at += (size_t)pad16(a.P) * 4;
     sh.red = reinterpret_cast<float *>(smem + at);
@@ -594,7 +535,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NTA > 2 ? 2
 #pragma unroll
         for (int j = 0; j < NTG; ++j) load_tile(a, ns, g * G + j * 16, xb[j]);   // in flight while the table is staged
     }
-    stage_patterns(Mg, a.P, sh.tab, sh.nh, sh.red, TAB_LDS);
+    stage_patterns(Mg, a.P, sh.tab, sh.nh, sh.red);
     const PatternTable tb = make_table(sh, Mg, a.P);
 
     for (; g < g_end; g += 4) {
@@ -604,13 +545,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NTA > 2 ? 2
         float mn[4] = {INFINITY, INFINITY, INFINITY, INFINITY}, mx[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
         int bi[NTG];
         const int sc = lane & 31, sth = lane >> 5;
-        if (NTA > 1) {   // NTA tiles of the group per pass over the pattern table
+        if (a.idx_given) {   // searched beforehand (min-max metric)
+#pragma unroll
+            for (int j = 0; j < NTG; ++j) bi[j] = a.idx[(int64_t)ns * a.t_capacity + tq0 + j * 16 + n];
+        } else if (NTA > 1) {   // NTA tiles of the group per pass over the pattern table
 #pragma unroll
             for (int j0 = 0; j0 < NTG; j0 += NTA) {
                 float bv[NTA], x2[NTA];
                 bool flag[NTA];
                 int bj[NTA];
-                assign_tiles_mfma<TAB_LDS, NTA>(reinterpret_cast<const uint4 (&)[NTA][4]>(xb[j0]), tb, lane, bj, bv, x2, flag);
+                assign_tiles_mfma<NTA>(reinterpret_cast<const uint4 (&)[NTA][4]>(xb[j0]), tb, lane, bj, bv, x2, flag);
 #pragma unroll
                 for (int j = 0; j < NTA; ++j) {
                     float bd;
@@ -622,10 +566,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NTA > 2 ? 2
 #pragma unroll
         for (int j = 0; j < NTG; ++j) {
             float r[32];
-            if (NTA > 1)
-                residuals<TAB_LDS>(sh, Mg, xb[j], bi[j], r);
+            if (NTA > 1 || a.idx_given)
+                residuals(sh, Mg, xb[j], bi[j], r);
             else
-                bi[j] = assign_residuals<TAB_LDS>(sh, tb, Mg, xb[j], reinterpret_cast<__half *>(rt), r);
+                bi[j] = assign_residuals(sh, tb, Mg, xb[j], reinterpret_cast<__half *>(rt), r);
 #pragma unroll
             for (int k = 0; k < 4; ++k) {   // channels 32k .. 32k+31
                 float4 *dst = reinterpret_cast<float4 *>(rt + n * kWkStride + 8 * kb);
@@ -668,7 +612,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NTA > 2 ? 2
 #pragma unroll
         for (int j = 0; j < NTG; ++j) {
             float r[32];
-            residuals<TAB_LDS>(sh, Mg, xb[j], bi[j], r);
+            residuals(sh, Mg, xb[j], bi[j], r);
             if (g + 4 < g_end) load_tile(a, ns, (g + 4) * G + j * 16, xb[j]);
             k_codes_to_staging<BITS>(r, pz, pinv, stg);
             if (kb == 0) stg[16 * 16 * BITS + n] = (uint8_t)bi[j];
@@ -712,12 +656,12 @@ __device__ __forceinline__ uint32_t transpose16(uint32_t x, const TransposeConst
 // block.  NG = channel groups per token (kD / Gc).  NT = blocks taken together: the wave assigns its units of
 // NT consecutive blocks in one pass over the pattern table (every table tile read from LDS serves all of
 // them), then quantizes them one after the other.
-template <int BITS, int NG, bool TAB_LDS, int NT>
+template <int BITS, int NG, int NT>
 __global__ __launch_bounds__(256) void quantize_v_kernel(QuantArgs a, int tiles_per_wg)
 {
     constexpr int TT = 64, WPU = BITS / 2, BPG = 4 / NG;   // BPG = 32-channel blocks per group
     extern __shared__ __align__(16) unsigned char smem[];
-    const TileShared sh = carve(smem, a.P, TAB_LDS, 0, 1);
+    const TileShared sh = carve(smem, a.P, 0, 1);
     const int tid = threadIdx.x, ns = blockIdx.y;
     const int lane = tid & 63, wave = tid >> 6, n = lane & 15, kb = lane >> 4;
     const __half *Mg = a.patterns + (int64_t)a.sets.set_of(ns) * a.P * kD;
@@ -728,7 +672,7 @@ __global__ __launch_bounds__(256) void quantize_v_kernel(QuantArgs a, int tiles_
     for (int j = 0; j < NT; ++j)   // a block past the workgroup's range repeats the last one; its result is not used
         load_tile(a, ns, min(tile0 + j, tile1 - 1) * TT + wave * 16, xbs[j]);
 
-    stage_patterns(Mg, a.P, sh.tab, sh.nh, sh.red, TAB_LDS);
+    stage_patterns(Mg, a.P, sh.tab, sh.nh, sh.red);
     const PatternTable tb = make_table(sh, Mg, a.P);
     const TransposeConst tc = transpose_const(n);
     unsigned char *wsc = sh.wsc + wave * kWaveScratch;
@@ -758,10 +702,14 @@ __global__ __launch_bounds__(256) void quantize_v_kernel(QuantArgs a, int tiles_
 
     for (int tile_base = tile0; tile_base < tile1; tile_base += NT) {
         int bis[NT];
-        {
+        if (a.idx_given) {   // searched beforehand (min-max metric); a block past the range repeats the last one
+#pragma unroll
+            for (int j = 0; j < NT; ++j)
+                bis[j] = a.idx[(int64_t)ns * a.t_capacity + a.t0 + (int64_t)min(tile_base + j, tile1 - 1) * TT + wave * 16 + n];
+        } else {
             float bv[NT], x2[NT];
             bool flag[NT];
-            assign_tiles_mfma<TAB_LDS, NT>(xbs, tb, lane, bis, bv, x2, flag);
+            assign_tiles_mfma<NT>(xbs, tb, lane, bis, bv, x2, flag);
 #pragma unroll
             for (int j = 0; j < NT; ++j) {
                 float bd;
@@ -777,7 +725,7 @@ __global__ __launch_bounds__(256) void quantize_v_kernel(QuantArgs a, int tiles_
         float r[32];
         int bi = bis[j];
         store_pending();
-        residuals<TAB_LDS>(sh, Mg, xb, bi, r);
+        residuals(sh, Mg, xb, bi, r);
         if (a.v_rho > 0.f) {
             // adaptive threshold (Sec. 3.3): keep the pattern iff R_flat <= rho * R_raw, ranges over all d
             // channels of the token: lane-local over its 32 channels, then over the token's 4 lanes
@@ -922,22 +870,39 @@ static int tiles_per_wg(int n_tiles, int n_streams)
     return t < 1 ? 1 : (t > cap ? cap : t);
 }
 
-template <class K>
-static hipError_t launch_tiled(K kernel, const QuantArgs &a, int TT, size_t lds, hipStream_t s, int min_tiles = 1)
+template <auto KERNEL>
+static hipError_t launch_tiled(const QuantArgs &a, int TT, size_t lds, size_t max_lds, hipStream_t s, int min_tiles = 1)
 {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    static LdsOptIn opt_in;   // per kernel instantiation; max_lds: what it needs with a table of 256 patterns
+    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(KERNEL), opt_in, max_lds);
     if (e != hipSuccess) return e;
     int tpw = tiles_per_wg(a.nq / TT, a.n_streams);
     if (tpw < min_tiles) tpw = min_tiles;
     const int n_tiles = a.nq / TT;
-    hipLaunchKernelGGL(kernel, dim3((n_tiles + tpw - 1) / tpw, a.n_streams), dim3(256), lds, s, a, tpw);
+    hipLaunchKernelGGL(KERNEL, dim3((n_tiles + tpw - 1) / tpw, a.n_streams), dim3(256), lds, s, a, tpw);
     return hipGetLastError();
 }
 
-hipError_t launch_quantize_k(const QuantArgs &a, hipStream_t s)
+// Min-max metric: the search kernel fills the index array, the quantizers then take the indices from there.
+static hipError_t launch_assign_minmax(const QuantArgs &a, hipStream_t s)
 {
-    if (a.metric == PK_METRIC_L2) {
-        const bool tl = a.P <= 256;   // table rows in LDS (74 KB at 256 patterns)
+    const int n_tiles = a.nq / 64;
+    int tpw = tiles_per_wg(n_tiles, a.n_streams);
+    if (tpw < 4) tpw = 4;   // four waves, a 64-vector tile each per round
+    hipLaunchKernelGGL(assign_minmax_kernel, dim3((n_tiles + tpw - 1) / tpw, a.n_streams), dim3(256), 0, s, a, tpw);
+    return hipGetLastError();
+}
+
+hipError_t launch_quantize_k(const QuantArgs &a_in, hipStream_t s)
+{
+    QuantArgs a = a_in;
+    if (a.metric == PK_METRIC_MINMAX) {
+        const hipError_t e = launch_assign_minmax(a, s);
+        if (e != hipSuccess) return e;
+        a.idx_given = 1;
+    }
+    {
+        // (the pattern table, at most 256 rows = 74 KB, lives in LDS)
         // Tiles of a group assigned per pass over the pattern table (every table tile read from LDS serves all of
         // them): pairs keep three waves per SIMD; the whole 64-token group takes two, which pays above 128
         // patterns; 32-token groups gain from pairs only once the table is large.
@@ -951,16 +916,15 @@ hipError_t launch_quantize_k(const QuantArgs &a, hipStream_t s)
 #define PK_LAUNCH_K2(GG, BB)                                                                                       \
     if (a.G == GG && a.bits == BB) {                                                                               \
         constexpr int TT = GG == 128 ? 128 : 64;                                                                   \
-        return tl ? launch_tiled(quantize_k_kernel<GG, BB, true>, a, TT, tile_lds_bytes(a.P, true, TT, GG), s, big1) \
-                  : launch_tiled(quantize_k_kernel<GG, BB, false>, a, TT, tile_lds_bytes(a.P, false, TT, GG), s);  \
+        return launch_tiled<quantize_k_kernel<GG, BB>>(a, TT, tile_lds_bytes(a.P, TT, GG), tile_lds_bytes(256, TT, GG), s, big1); \
     }
 #define PK_LAUNCH_KW(GG, BB)                                                                                       \
     if (a.G == GG && a.bits == BB) {                                                                               \
         /* a wave owns whole groups: at least four groups per workgroup */                                        \
-        return !tl ? launch_tiled(quantize_k_wave_kernel<GG, BB, false, 1>, a, 64, wave_k_lds_bytes(a.P, false), s, GG / 16)   \
-               : kmulti == 4 && GG == 64 ? launch_tiled(quantize_k_wave_kernel<GG, BB, true, GG / 16>, a, 64, wave_k_lds_bytes(a.P, true), s, bigw > GG / 16 ? bigw : GG / 16) \
-               : kmulti >= 2 ? launch_tiled(quantize_k_wave_kernel<GG, BB, true, 2>, a, 64, wave_k_lds_bytes(a.P, true), s, GG / 16) \
-                        : launch_tiled(quantize_k_wave_kernel<GG, BB, true, 1>, a, 64, wave_k_lds_bytes(a.P, true), s, GG / 16); \
+        const size_t lds = wave_k_lds_bytes(a.P), mx = wave_k_lds_bytes(256);                                      \
+        return kmulti == 4 && GG == 64 ? launch_tiled<quantize_k_wave_kernel<GG, BB, GG / 16>>(a, 64, lds, mx, s, bigw > GG / 16 ? bigw : GG / 16) \
+               : kmulti >= 2 ? launch_tiled<quantize_k_wave_kernel<GG, BB, 2>>(a, 64, lds, mx, s, GG / 16)         \
+                             : launch_tiled<quantize_k_wave_kernel<GG, BB, 1>>(a, 64, lds, mx, s, GG / 16);        \
     }
         PK_LAUNCH_KW(32, 2) PK_LAUNCH_KW(64, 2) PK_LAUNCH_K2(128, 2)
         PK_LAUNCH_KW(32, 4) PK_LAUNCH_KW(64, 4) PK_LAUNCH_K2(128, 4)
@@ -968,46 +932,32 @@ hipError_t launch_quantize_k(const QuantArgs &a, hipStream_t s)
 #undef PK_LAUNCH_K2
         return hipErrorInvalidValue;
     }
-    const dim3 grid(a.nq / a.G, a.n_streams), block(128);
-#define PK_LAUNCH_K(GG, BB)                                                             \
-    if (a.G == GG && a.bits == BB) {                                                    \
-        hipLaunchKernelGGL((quantize_k_valu_kernel<GG, BB>), grid, block, 0, s, a);     \
-        return hipGetLastError();                                                       \
-    }
-    PK_LAUNCH_K(32, 2) PK_LAUNCH_K(64, 2) PK_LAUNCH_K(128, 2)
-    PK_LAUNCH_K(32, 4) PK_LAUNCH_K(64, 4) PK_LAUNCH_K(128, 4)
-#undef PK_LAUNCH_K
-    return hipErrorInvalidValue;
 }
 
-hipError_t launch_quantize_v(const QuantArgs &a, hipStream_t s)
+hipError_t launch_quantize_v(const QuantArgs &a_in, hipStream_t s)
 {
-    if (a.metric == PK_METRIC_L2) {
-        const bool tl = a.P <= 256;   // table rows in LDS (74 KB at 256 patterns)
+    QuantArgs a = a_in;
+    if (a.metric == PK_METRIC_MINMAX) {
+        const hipError_t e = launch_assign_minmax(a, s);
+        if (e != hipSuccess) return e;
+        a.idx_given = 1;
+    }
+    {
         const int ng = kD / (a.G < kD ? a.G : kD);
-        const size_t lds = tile_lds_bytes(a.P, tl, 0, 1);
+        const size_t lds = tile_lds_bytes(a.P, 0, 1), mx = tile_lds_bytes(256, 0, 1);
         const bool two = a.P >= 128;   // two blocks per table pass (three waves per SIMD instead of four) pay from 128 patterns on
         // a large table (two workgroups per CU, 64 KB of patterns staged by each): a small job as one resident round
         const int64_t tiles64 = (int64_t)(a.nq / 64) * a.n_streams;
         const int big1 = a.P > 128 && tiles64 <= 512 * 64 ? (int)((tiles64 + 511) / 512) : 1;
 #define PK_LAUNCH_V2(BB, NN)                                                                   \
     if (a.bits == BB && ng == NN)                                                              \
-        return !tl ? launch_tiled(quantize_v_kernel<BB, NN, false, 1>, a, 64, lds, s)          \
-               : two ? launch_tiled(quantize_v_kernel<BB, NN, true, 2>, a, 64, lds, s, big1)   \
-                     : launch_tiled(quantize_v_kernel<BB, NN, true, 1>, a, 64, lds, s);
+        return two ? launch_tiled<quantize_v_kernel<BB, NN, 2>>(a, 64, lds, mx, s, big1)       \
+                   : launch_tiled<quantize_v_kernel<BB, NN, 1>>(a, 64, lds, mx, s);
         PK_LAUNCH_V2(2, 1) PK_LAUNCH_V2(2, 2) PK_LAUNCH_V2(2, 4)
         PK_LAUNCH_V2(4, 1) PK_LAUNCH_V2(4, 2) PK_LAUNCH_V2(4, 4)
 #undef PK_LAUNCH_V2
         return hipErrorInvalidValue;
     }
-    const dim3 grid(a.nq / 64, a.n_streams), block(128);
-    if (a.bits == 2)
-        hipLaunchKernelGGL((quantize_v_valu_kernel<2>), grid, block, 0, s, a);
-    else if (a.bits == 4)
-        hipLaunchKernelGGL((quantize_v_valu_kernel<4>), grid, block, 0, s, a);
-    else
-        return hipErrorInvalidValue;
-    return hipGetLastError();
 }
 
 hipError_t launch_tail_copy(const TailCopyArgs &a, hipStream_t s)

@@ -107,6 +107,107 @@ SPECS = {
 }
 
 
+# ---------------------------------------------------------------------------------------------------------------
+# Second workload: the cache that multi-head latent attention actually stores (the paper's appendix on ALiBi / MLA
+# states that the method applies to it directly).  Per token there is ONE vector shared by all query heads: a
+# compressed latent (clustered, no outlier channels - it plays the role of V as well) followed by a small RoPE
+# sub-space of larger magnitude whose pairs rotate with the position.  K = [latent | rope part], V = [latent | 0];
+# n_kv_heads = 1 and every query head reads the same stream.  `pre_rope` leaves the rotation out (the pre-RoPE K
+# variant of Sec. 4.1's setting discussion).
+@dataclass(frozen=True)
+class MLASpec:
+    n_layers: int = 1
+    batch: int = 1
+    n_q_heads: int = 8
+    T: int = 1024
+    d: int = 128
+    d_rope: int = 32
+    n_clusters: int = 32
+    sigma: float = 0.3
+    rope_scale: float = 8.0
+    rope_base: float = 10000.0
+    pre_rope: bool = False
+
+
+def mla_layer_params(seed: int, layer: int, spec: MLASpec):
+    rng = np.random.Generator(np.random.PCG64([seed, layer, 4242, 0]))
+    c_lat = rng.standard_normal((spec.n_clusters, spec.d - spec.d_rope))
+    c_rope = rng.standard_normal((spec.n_clusters, spec.d_rope))
+    return c_lat, c_rope
+
+
+def _rope_angles(T: int, spec: MLASpec):
+    i = np.arange(spec.d_rope // 2)
+    return np.arange(T)[:, None] * spec.rope_base ** (-2.0 * i / spec.d_rope)[None, :]      # [T, d_rope/2]
+
+
+def make_mla_stream(seed: int, layer: int, b: int, spec: MLASpec, T: int | None = None):
+    """One (layer, sequence) latent stream: K, V as float16 [T, d]."""
+    T = spec.T if T is None else T
+    c_lat, c_rope = mla_layer_params(seed, layer, spec)
+    rng = np.random.Generator(np.random.PCG64([seed, layer, 4242, 1 + b]))
+    u = rng.integers(0, spec.n_clusters, size=T)
+    lat = c_lat[u] + spec.sigma * rng.standard_normal((T, spec.d - spec.d_rope))
+    ur = rng.integers(0, spec.n_clusters, size=T)
+    kr = spec.rope_scale * (c_rope[ur] + spec.sigma * rng.standard_normal((T, spec.d_rope)))
+    if not spec.pre_rope:
+        ang = _rope_angles(T, spec)
+        even, odd = kr[:, 0::2].copy(), kr[:, 1::2].copy()
+        kr[:, 0::2] = even * np.cos(ang) - odd * np.sin(ang)
+        kr[:, 1::2] = even * np.sin(ang) + odd * np.cos(ang)
+    k = np.concatenate([lat, kr], axis=1)
+    v = np.concatenate([lat, np.zeros((T, spec.d_rope))], axis=1)
+    return k.astype(np.float16), v.astype(np.float16)
+
+
+def make_mla_kv(seed: int, spec: MLASpec, T: int | None = None):
+    """K, V as float16 [n_layers*batch, 1, T, d]; sequence index = layer*batch + b."""
+    T = spec.T if T is None else T
+    K = np.empty((spec.n_layers * spec.batch, 1, T, spec.d), np.float16)
+    V = np.empty_like(K)
+    for layer in range(spec.n_layers):
+        for b in range(spec.batch):
+            K[layer * spec.batch + b, 0], V[layer * spec.batch + b, 0] = make_mla_stream(seed, layer, b, spec, T)
+    return K, V
+
+
+def make_mla_layer_device(seed: int, layer: int, spec: MLASpec, device="cuda", T: int | None = None):
+    """Device-side twin of make_mla_kv for one layer: K, V float16 [batch, 1, T, d] (layer parameters as in
+    mla_layer_params; the per-token draws come from a torch generator and differ from the numpy stream)."""
+    import torch
+
+    T = spec.T if T is None else T
+    dl = spec.d - spec.d_rope
+    K = torch.zeros((spec.batch, 1, T, spec.d), dtype=torch.float16, device=device)
+    V = torch.zeros_like(K)
+    c_lat, c_rope = mla_layer_params(seed, layer, spec)
+    c_lat_d = torch.from_numpy(c_lat).to(device=device, dtype=torch.float32)
+    c_rope_d = torch.from_numpy(c_rope).to(device=device, dtype=torch.float32)
+    ang = torch.from_numpy(_rope_angles(T, spec)).to(device=device, dtype=torch.float32)
+    gen = torch.Generator(device=device)
+    for b in range(spec.batch):
+        gen.manual_seed((seed * 1009 + layer) * 100003 + 77 + b)
+        u = torch.randint(0, spec.n_clusters, (T,), generator=gen, device=device)
+        lat = c_lat_d[u] + spec.sigma * torch.randn((T, dl), generator=gen, device=device)
+        ur = torch.randint(0, spec.n_clusters, (T,), generator=gen, device=device)
+        kr = spec.rope_scale * (c_rope_d[ur] + spec.sigma * torch.randn((T, spec.d_rope), generator=gen, device=device))
+        if not spec.pre_rope:
+            even, odd = kr[:, 0::2].clone(), kr[:, 1::2].clone()
+            kr[:, 0::2] = even * torch.cos(ang) - odd * torch.sin(ang)
+            kr[:, 1::2] = even * torch.sin(ang) + odd * torch.cos(ang)
+        K[b, 0, :, :dl] = lat.to(torch.float16)
+        K[b, 0, :, dl:] = kr.to(torch.float16)
+        V[b, 0, :, :dl] = lat.to(torch.float16)
+    return K, V
+
+
+# MLA-shaped long-context decode: 27 layers x batch 16 x T = 32768, one latent stream per sequence read by 8 query heads
+MLA_SPECS = {
+    "mla": MLASpec(27, 16, 8, 32768, 128, 32, 32, 0.3, 8.0),
+    "mla_prerope": MLASpec(27, 16, 8, 32768, 128, 32, 32, 0.3, 8.0, pre_rope=True),
+}
+
+
 def make_layer_device(seed: int, layer: int, spec: KVSpec, device="cuda", T: int | None = None):
     """Device-side twin of make_kv for workloads too large for host memory: one layer's
     K, V as float16 [batch, n_kv_heads, T, d] on `device`.

@@ -501,6 +501,38 @@ def test_window_pattern_and_growing_tables(oracle, pk):
     assert np.array_equal(host_u16(tab[:, 2]), oracle.window_pattern(Kf[:, 64:128].view(np.uint16))) and not tab[:, 3].any()
 
 
+# ------------------------------------------------------------------------------ second workload: MLA latent cache
+
+@pytest.mark.parametrize("pre_rope,metric", [(False, 0), (True, 0), (False, 1)])
+def test_mla_latent_cache_workload(oracle, pk, pre_rope, metric):
+    """The cache that multi-head latent attention stores (appendix on ALiBi / MLA): one latent stream per sequence
+    (n_kv_heads = 1) read by all 8 query heads, K = [latent | RoPE sub-space of larger magnitude], V = [latent | 0];
+    with and without the rotation (pre-RoPE keys), Euclidean and min-max selection.  Whole path: patterns mined
+    per layer by both sides from the same start, streaming appends with a recent window, decode."""
+    spec = synth.MLASpec(n_layers=2, batch=2, n_q_heads=8, T=1400, pre_rope=pre_rope)
+    K, V = synth.make_mla_kv(13, spec)
+    P, bits, G, R, F = 32, 2, 64, 64, 128
+    kw = dict(n_seq=4, n_kv_heads=1, n_q_heads=8, head_dim=128, n_patterns=P, seqs_per_set=2, bits=bits, group=G,
+              recent=R, flush=F, t_capacity=1408, metric=metric)
+    ocfg, gcfg = oracle.Config(**kw), pk.Config(**kw)
+    # one table per layer, mined on the layer's first sequence: per-iteration agreement is covered by the mining
+    # tests, here both sides quantize against the oracle's tables
+    Mk, _, Jk, _ = oracle.mine(K[::2, 0].view(np.uint16), P, 4)
+    Mv, _, _, _ = oracle.mine(V[::2, 0].view(np.uint16), P, 4)
+    J = torch.empty((2, 4), dtype=torch.float32, device="cuda")
+    pk.pk_mine_patterns(gcfg, dev(K[::2, 0]), 4, inertia=J)
+    assert np.allclose(J.cpu().numpy(), Jk, rtol=1e-3)
+    oc, gc, Mkd, Mvd = run_appends(oracle, pk, ocfg, gcfg, K, V, Mk, Mv, [700, 1, 450, 249])
+    assert oc.t_quant == 1280 and oc.t_tail == 120
+    assert compare_caches(oracle, oc, gc, metric) <= 8
+    q = synth.make_queries(13, 4, 8, 128)
+    want, want_lse = oracle.decode_attention(oc, q.view(np.uint16), Mk, Mv, 128 ** -0.5)
+    lse = torch.empty((4, 8), dtype=torch.float32, device="cuda")
+    got = pk.pk_decode_attention(gcfg, gc, dev(q), 128 ** -0.5, Mkd, Mvd, lse=lse).cpu().numpy()
+    assert_attention(got, want)
+    assert np.abs(lse.cpu().numpy() - want_lse).max() <= 2e-3
+
+
 # ------------------------------------------------------------------------------ pattern mining
 
 def _ulp_diff(a_u16, b_u16):

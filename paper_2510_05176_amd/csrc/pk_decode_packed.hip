@@ -96,9 +96,36 @@ __host__ __device__ constexpr int e_lo(int v) { return v < 5 ? 2 * v : 10 + 2 * 
 __host__ __device__ constexpr int fpos(int v) { return v < 5 ? 2 * v : 2 * (v - 5); }
 
 struct GroupOperand {
-    uint32_t Bq[16];   // q[h][c] * s[g][c] * 2^(8-pos), operand order
+    uint32_t Bq[16];   // q[h][c] * s[g][c] * 2^(8-pos) rounded to fp16, operand order
+    uint32_t Bl[16];   // what that rounding dropped (the product of two fp16 numbers has 22 significant bits), as fp16;
+                       // formed and used only for groups whose scales are large enough for it to matter (lo_on)
     float qz;          // scale * log2(e) * q_h . z[g]
+    bool lo_on;        // wave-uniform
 };
+
+// sum over the 64 lanes (row shifts, then the two row broadcasts of the wave), returned wave-uniform
+__device__ __forceinline__ float wave_sum(float v)
+{
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x111, 0xf, 0xf, true));
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x112, 0xf, 0xf, true));
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x114, 0xf, 0xf, true));
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x118, 0xf, 0xf, true));
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x142, 0xa, 0xf, false));   // row_bcast:15 into rows 1 and 3
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x143, 0xc, 0xf, false));   // row_bcast:31 into rows 2 and 3
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
+}
+
+// lo/hi half of (a * b - c) with the fp16 halves widened and one rounding at the end: for c = fp16(a * b) this is
+// exactly the rounding error of the fp16 product (it has at most 11 significant bits), again as fp16
+__device__ __forceinline__ uint32_t product_error(uint32_t a, uint32_t b, uint32_t c)
+{
+    uint32_t r;
+    asm("v_fma_mixlo_f16 %0, %1, %2, -%3 op_sel:[0,0,0] op_sel_hi:[1,1,1]\n\t"
+        "v_fma_mixhi_f16 %0, %1, %2, -%3 op_sel:[1,1,1] op_sel_hi:[1,1,1]"
+        : "=&v"(r)
+        : "v"(a), "v"(b), "v"(c));
+    return r;
+}
 
 template <int BITS, bool G32, bool HALF>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void decode_packed_kernel(DecodeArgs a)
@@ -106,6 +133,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
     static_assert(!(HALF && G32), "the split of a unit's tokens over column halves assumes one K group per block");
     constexpr int WPU = BITS / 2;   // 32-bit words per (channel, 16-token unit) of V; K: 4*BITS words per token
     constexpr int NTK = HALF ? 8 : 16;   // tokens of a block whose scores a lane keeps
+    // second contraction pass with the rounding errors of q * s (see build_group); not with two K groups per block,
+    // whose two operand sets leave no registers for it (32-token groups also have the smallest scales)
+    constexpr bool COMP = !G32;
     // dynamic LDS: QMs [P][16] floats (q.M_K per pattern and column); Ws [4 waves][R][w_stride] 64-bit fixed-point
     // sums (softmax mass per V pattern, unit 2^-31).  Integer LDS atomics run at full rate on this chip, float
     // ones retire about one lane per 2.6 cycles (measured), which made the mass sums the slowest part of a block.
@@ -192,6 +222,22 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
     }
     const float sc2 = a.softmax_scale * kLog2e / lam;
     const float c1 = sc2 * 65536.f, inv_c1 = 1.f / c1;
+    // sum_c s_c^2 of a K group above which the dropped parts of q * s are contracted as well: the estimated score
+    // error softmax_scale * 4.2e-4 * sqrt(|q|^2 / d * sum_c s_c^2) then exceeds 6e-4 for some head of the stream
+    float lo_threshold = INFINITY;
+    if (COMP) {
+        float qq = 0.f;
+#pragma unroll
+        for (int i = 0; i < 32; ++i) qq = fmaf((float)qh[i], (float)qh[i], qq);
+        qq += __shfl_xor(qq, 16);
+        qq += __shfl_xor(qq, 32);                                     // |lam q|^2 of the column's head
+        const float per_head = a.softmax_scale * a.softmax_scale / (lam * lam) * qq * (1.f / kD);
+        float worst = per_head;
+#pragma unroll
+        for (int off = 1; off < 16; off <<= 1) worst = fmaxf(worst, __shfl_xor(worst, off));
+        worst = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, worst)));
+        lo_threshold = worst > 0.f ? 2.04f / worst : INFINITY;       // (6e-4 / 4.2e-4)^2
+    }
     uint32_t qn[16], qp[16];   // natural channel order; operand order with the field scale folded in
 #pragma unroll
     for (int i = 0; i < 16; ++i) qn[i] = pack2(qh[2 * i], qh[2 * i + 1]);
@@ -259,6 +305,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
     // parameters of one K group: raw loads, then the B operand
     struct GroupRaw {
         uint4 s[4], z[4];
+        uint32_t own;   // the lane's own two of the group's 128 scales (lane <-> dword), for the sum of their squares
     };
     auto load_group_raw = [&](int grp, GroupRaw &gr) {
         // offsets inside a stream fit 32 bits (checked on the host): base pointer + 32-bit lane offset
@@ -270,6 +317,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
             gr.s[i] = sp[i];
             gr.z[i] = zp[i];
         }
+        if (COMP) gr.own = *reinterpret_cast<const uint32_t *>(kscale + (uint32_t)grp * kD * 2 + lane * 4);
     };
     auto build_group = [&](const GroupRaw &gr, GroupOperand &go) {
         _Float16 sh[32];
@@ -295,6 +343,22 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
         for (int V = 0; V < 16; ++V) {
             const int v = V & 7, odd = V >> 3;
             go.Bq[V] = pk_mul(qp[V], pack2(sh[e_lo(v) + odd], sh[e_lo(v) + 16 + odd]));
+        }
+        // The fp16 rounding of q * s (2^-12 relative per channel) leaves a score error of about
+        // softmax_scale * 4.2e-4 * sqrt(sum_c q_c^2 s_c^2); where the group's scales make that matter (large-magnitude
+        // channels: outliers over long groups, a RoPE sub-space), the dropped part of every product is formed too
+        // and contracted in a second pass over the same code operand.  The test uses |q|^2 / d for q_c^2.
+        go.lo_on = false;
+        if (COMP) {
+            const float s2 = wave_sum(dot2(gr.own, gr.own, 0.f));
+            go.lo_on = s2 > lo_threshold;
+            if (go.lo_on) {
+#pragma unroll
+                for (int V = 0; V < 16; ++V) {
+                    const int v = V & 7, odd = V >> 3;
+                    go.Bl[V] = product_error(qp[V], pack2(sh[e_lo(v) + odd], sh[e_lo(v) + 16 + odd]), go.Bq[V]);
+                }
+            }
         }
         acc += __shfl_xor(acc, 16);
         acc += __shfl_xor(acc, 32);
@@ -415,6 +479,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
             floatx4 d = {d0, d0, d0, d0}, d2 = {d02, d02, d02, d02};
 #pragma unroll
             for (int s = 0; s < 4; ++s) d = mfma16(&A16[4 * s], &ga.Bq[4 * s], d);
+            if (COMP && ga.lo_on) {
+#pragma unroll
+                for (int s = 0; s < 4; ++s) d = mfma16(&A16[4 * s], &ga.Bl[4 * s], d);
+            }
             if (G32) {
 #pragma unroll
                 for (int s = 0; s < 4; ++s) d2 = mfma16(&A16[4 * s], &gb.Bq[4 * s], d2);
@@ -426,6 +494,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
                 floatx4 e = {0.f, 0.f, 0.f, 0.f}, e2 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int s = 0; s < 4; ++s) e = mfma16(&H16[4 * s], &ga.Bq[4 * s], e);
+                if (COMP && ga.lo_on) {
+#pragma unroll
+                    for (int s = 0; s < 4; ++s) e = mfma16(&H16[4 * s], &ga.Bl[4 * s], e);
+                }
                 d += 4.f * e;
                 if (G32) {
 #pragma unroll

@@ -130,8 +130,7 @@ def rel_l2(a, b):
 
 def assert_attention(got, want, elementwise=True, row_tol=2e-3):
     """The attention bar, applied to every (sequence, query head) row on its own: relative L2 error <= 2e-3, and
-    (for runs on shared pattern tables) every element within 2e-3 of the row's largest magnitude.  (row_tol: see
-    the one caller that passes it.)"""
+    (for runs on shared pattern tables) every element within 2e-3 of the row's largest magnitude."""
     got, want = np.asarray(got, np.float64), np.asarray(want, np.float64)
     assert got.shape == want.shape and np.isfinite(got).all()
     g2, w2 = got.reshape(-1, got.shape[-1]), want.reshape(-1, want.shape[-1])

@@ -295,17 +295,32 @@ __global__ __launch_bounds__(128 * NQ) void decode_merge_kernel(DecodeArgs a)
 
 int decode_chunk(int64_t n_streams, int64_t t_packed_total, int P, int r)
 {
-    // aim at one resident round of workgroups (two per CU, 512 on the chip): splits that run side by side take
-    // the same time, and a longer split pays the fixed parts once - prologue (q.M_K table, LDS clears), epilogue
-    // (merge of the four waves) and the r*P pattern masses and r*128 outputs it writes - so a split holds at
-    // least r*P/2 tokens, one 64-token block per wave at least, and at most 32768 tokens.
-    int64_t c = (n_streams * t_packed_total + 511) / 512;
-    const int64_t floor_c = (int64_t)r * P / 2;
-    if (c < floor_c) c = floor_c;
-    c = (c + 255) / 256 * 256;
-    if (c < 256) c = 256;
-    if (c > 32768) c = 32768;
-    return (int)c;
+    // Equal splits, their number k chosen for the shortest modelled time: the chip holds 512 workgroups at once
+    // (two per CU), workgroups that run side by side take the same time, so k splits per stream cost
+    // ceil(n_streams * k / 512) rounds of (split length + fixed part).  The fixed part - prologue (q.M_K table,
+    // LDS clears), epilogue (merge of the four waves), the r*P pattern masses and r*128 outputs every split
+    // writes - is worth about 1024 + r*P/2 tokens of block work.  A split holds at least r*P/2 tokens and one
+    // 64-token block per wave, at most 32768 tokens.  (Unequal splits - a long one and a remainder - leave the
+    // long ones of the last streams waiting for a slot: 0.78 against 0.54 ms on 432 streams x 32768.)
+    const int64_t t = t_packed_total > 0 ? t_packed_total : 1;
+    int64_t floor_c = (int64_t)r * P / 2;
+    if (floor_c < 256) floor_c = 256;
+    const int64_t fixed = 1024 + (int64_t)r * P / 2;
+    int64_t best_c = 0, best_cost = 0;
+    for (int64_t k = (t + 32767) / 32768; k <= 512; ++k) {
+        int64_t c = ((t + k - 1) / k + 255) / 256 * 256;
+        if (c < floor_c) c = (floor_c + 255) / 256 * 256;
+        if (c > 32768) c = 32768;
+        const int64_t splits = (t + c - 1) / c;
+        const int64_t rounds = (n_streams * splits + 511) / 512;
+        const int64_t cost = rounds * (c + fixed);
+        if (best_c == 0 || cost < best_cost) {
+            best_c = c;
+            best_cost = cost;
+        }
+        if (c <= floor_c || c <= 256) break;   // shorter splits are not allowed
+    }
+    return (int)best_c;
 }
 
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t s)

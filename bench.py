@@ -27,6 +27,7 @@ Other modes (no GPU needed):
         HBM bytes per library call from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) of
         `bench.py --traffic-probe`; writes profiles/<key>_hbm_traffic.txt and updates profiles/hbm_traffic.json,
         which `roofline.traffic` is read back from (a stored reading, not measured in the timed run).
+  bench.py --summarise-counters COUNTERS.csv --cmd "..."       per-kernel averages per dispatch of any other --pmc run
 """
 import argparse
 import json
@@ -532,6 +533,24 @@ def summarise_pmc(fetch_csv, write_csv, n_calls, key, cmd):
     print("\n".join(lines))
 
 
+def summarise_counters(csv_path, cmd):
+    """Per-kernel averages per dispatch of whatever counters one rocprofv3 --pmc run of this script collected."""
+    import collections
+    import csv
+    tot, cnt = collections.defaultdict(float), collections.Counter()
+    for r in csv.DictReader(open(csv_path)):
+        tot[(r["Kernel_Name"], r["Counter_Name"])] += float(r["Counter_Value"])
+        cnt[(r["Kernel_Name"], r["Counter_Name"])] += 1
+    names = sorted({c for _, c in tot})
+    print(f"command: {cmd}")
+    print("average per dispatch; kernels of this library only")
+    print(f"{'kernel':60s} {'disp':>5s} " + " ".join(f"{c[:18]:>18s}" for c in names))
+    for k in sorted({k for k, _ in tot}):
+        if "pk::" not in k:
+            continue
+        print(f"{k[:60]:60s} {cnt[(k, names[0])]:5d} " + " ".join(f"{tot[(k, c)] / max(cnt[(k, c)], 1):18.1f}" for c in names))
+
+
 # ------------------------------------------------------------------------------------------------------------
 def main():
     ap = argparse.ArgumentParser()
@@ -552,12 +571,15 @@ def main():
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings of this command are scaled by")
     ap.add_argument("--summarise-trace", metavar="DB")
     ap.add_argument("--summarise-pmc", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"))
+    ap.add_argument("--summarise-counters", metavar="CSV")
     ap.add_argument("--calls", type=int, default=1)
     ap.add_argument("--key", default="")
     ap.add_argument("--cmd", default="")
     args = ap.parse_args()
     if args.summarise_trace:
         return summarise_trace(args.summarise_trace, args.cmd)
+    if args.summarise_counters:
+        return summarise_counters(args.summarise_counters, args.cmd)
     if args.summarise_pmc:
         return summarise_pmc(args.summarise_pmc[0], args.summarise_pmc[1], args.calls, args.key, args.cmd)
     if args.gpus != 1:

@@ -31,8 +31,13 @@
  *   - Every argument, shape, alignment (16 bytes for all device pointers),
  *     capacity and state error is detected on the host before anything is
  *     launched; the call then returns a status other than PK_OK and leaves
- *     pk_state and device memory untouched.  A failed launch gives
- *     PK_ERR_DEVICE.  Nothing is printed, thrown or aborted.
+ *     pk_state and device memory untouched.  A launch the HIP runtime refuses
+ *     gives PK_ERR_DEVICE: pk_state is unchanged then as well, but kernels
+ *     launched earlier by the same call may already have written device memory
+ *     (an append launches the K quantizer, the V quantizer and the tail copy in
+ *     turn; what they wrote lies behind t_quant / outside the tail range that
+ *     pk_state describes, so repeating the call overwrites it).  Nothing is
+ *     printed, thrown or aborted.
  *   - Calls are re-entrant; calls that touch different caches on different
  *     streams may run concurrently.
  *
@@ -112,7 +117,9 @@ typedef struct {
     int32_t bits;         /* b: 2 or 4                                                        */
     int32_t group;        /* G: 32, 64 or 128                                                 */
     int32_t recent;       /* R >= 0: vectors always kept in fp16                              */
-    int32_t flush;        /* F: multiple of G and of 64; vectors quantized per flush          */
+    int32_t flush;        /* F: multiple of G and of 64 (V codes and parameters are stored in
+                             blocks of 64 tokens, so G = 32 with F = 32 is refused); vectors
+                             quantized per flush                                              */
     int32_t t_capacity;   /* maximum packed tokens per stream, multiple of F, at most 2^25    */
     int32_t metric;       /* pk_metric                                                        */
     float v_rho;          /* adaptive threshold on V (Sec. 3.3, "Adaptive Threshold for V"): 0 = off.  With
@@ -222,6 +229,13 @@ pk_status pk_quantize_append(const pk_config *cfg, const pk_cache *cache, pk_sta
  *   out      [n_seq][n_q_heads][d] float
  *   lse      optional [n_seq][n_q_heads] float: log-sum-exp of the scaled scores
  * A context of length 0 yields out = 0 and lse = -inf.
+ * Arithmetic and supported range: scores and outputs are accumulated in binary32; the operands
+ * of the two code contractions are fp16 products, q * s_K (q brought to max |q| in [1, 2) per
+ * head by a power of two first, so any finite fp16 query is accepted) and p * s_V with p <= 1.
+ * Both carry a factor of up to 2^8 for the position of a code inside its word, hence the stored
+ * scales must satisfy s_K < 128 and s_V < 256 (a residual range below 384 resp. 768 per group at
+ * 2 bits); larger scales overflow fp16 and give non-finite outputs.  The rounding of q * s_K is
+ * compensated where it would exceed about 6e-4 in a score (groups of 64 or 128 tokens).
  */
 pk_status pk_decode_attention(const pk_config *cfg, const pk_cache *cache, const pk_state *state,
                               const pk_config *prefix_cfg, const pk_cache *prefix,

@@ -32,6 +32,7 @@
 // n >= 8 the second (the other operand is zero): output rows rho and rho + 8 are two partial sums of one (h, g)
 // pair and are added in the epilogue.
 #include "pk_internal.h"
+#include "pk_decode_tail.h"
 
 namespace pk {
 
@@ -142,6 +143,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
     extern __shared__ __align__(16) unsigned char dyn_smem[];
     __shared__ float stat_m[4][16], stat_l[4][16], stat_pz[4][16];
 
+    // Rows of the grid behind the streams hold the workgroups of the fp16 tails (own tails first, then the shared
+    // prefix's if it has one): they ride along in this launch and fill the slots that the last round of packed
+    // splits leaves idle, instead of running as a kernel of their own afterwards.
+    if ((int)blockIdx.y >= a.n_seq * a.n_kv_heads) {
+        const int N = a.n_seq * a.n_kv_heads;
+        const int id = ((int)blockIdx.y - N) * (int)gridDim.x + (int)blockIdx.x;
+        if (id >= N * (a.prefix.t_tail > 0 ? 2 : 1)) return;
+        const int which = id / N;
+        if (a.n_q_heads / a.n_kv_heads <= 4)
+            decode_tail_body<4>(a, which, id - which * N, *reinterpret_cast<TailShared<4> *>(dyn_smem));
+        else
+            decode_tail_body<8>(a, which, id - which * N, *reinterpret_cast<TailShared<8> *>(dyn_smem));
+        return;
+    }
     const int tid = threadIdx.x, lane = tid & 63, n = lane & 15, kb = lane >> 4;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: block ranges and base addresses stay scalar
     const int split = blockIdx.x, ns = blockIdx.y;
@@ -720,14 +735,20 @@ hipError_t launch_decode_packed(const DecodeArgs &a, hipStream_t s)
 {
     const int splits = a.splits_prefix + a.splits_own;
     if (splits == 0) return hipSuccess;
-    const dim3 grid(splits, a.n_seq * a.n_kv_heads);
+    const int N = a.n_seq * a.n_kv_heads;
     const int R = a.n_q_heads / a.n_kv_heads, NG = kD / (a.G < kD ? a.G : kD);
+    // tail workgroups (one per stream, another one per stream for the shared prefix's tail) in rows behind the streams
+    const bool tails = decode_tails_ride_along(a);
+    const int n_tail = tails ? N * (a.prefix.t_tail > 0 ? 2 : 1) : 0;
+    const dim3 grid(splits, N + (n_tail + splits - 1) / splits);
     // eight or fewer (head, channel group) pairs leave half of the score columns free: they take the second half
     // of every unit's tokens
     const bool half = a.G != 32 && R * NG <= 8;
     size_t lds = (size_t)a.P * 16 * 4 + (size_t)4 * R * a.w_stride * 8;   // QMs, Ws
     const size_t out_slabs = (size_t)4 * (half ? 2 : 1) * R * kD * 4;     // reused for the waves' outputs at the end
     if (lds < out_slabs) lds = out_slabs;
+    const size_t tail_lds = R <= 4 ? sizeof(TailShared<4>) : sizeof(TailShared<8>);
+    if (tails && lds < tail_lds) lds = tail_lds;
     if (a.bits == 2 && a.G == 32) return launch_one<2, true, false>(a, grid, lds, s);
     if (a.bits == 2) return half ? launch_one<2, false, true>(a, grid, lds, s) : launch_one<2, false, false>(a, grid, lds, s);
     if (a.bits == 4 && a.G == 32) return launch_one<4, true, false>(a, grid, lds, s);

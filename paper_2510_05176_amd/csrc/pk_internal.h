@@ -188,6 +188,16 @@ __device__ __forceinline__ void own_state(const DecodeArgs &a, int seq, int &t_q
     }
 }
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t s);
+// Whether the workgroups of the fp16 tails are part of the packed kernel's launch (rows of its grid behind the
+// streams) instead of a kernel of their own.  They then run at that kernel's occupancy (two workgroups per CU),
+// which suits a few hundred tails that fill slots the packed splits leave idle (config 4: -7 % per step) and does
+// not suit thousands of them (config 3, 4096 tails: +8 % on the whole decode; the tail code hides its load
+// latency by occupancy, eight workgroups per CU when launched alone).
+inline bool decode_tails_ride_along(const DecodeArgs &a)
+{
+    const int n_tail = a.n_seq * a.n_kv_heads * (a.prefix.t_tail > 0 ? 2 : 1);
+    return a.splits_prefix + a.splits_own > 0 && (a.own.t_tail > 0 || a.prefix.t_tail > 0) && n_tail <= 1024;
+}
 int decode_chunk(int64_t n_streams, int64_t t_packed_total, int P, int r);
 constexpr int kMaxSlots = 2304;   // partial slots per stream the merge kernel holds weights for (splits + 2)
 

@@ -85,7 +85,7 @@
 extern "C" {
 #endif
 
-#define PK_ABI_VERSION 3u
+#define PK_ABI_VERSION 4u
 
 typedef enum {
     PK_OK = 0,
@@ -174,6 +174,18 @@ pk_status pk_cache_layout(const pk_config *cfg, pk_layout *out /* host, out */);
  * all smaller ones.  Returns 0 for an invalid configuration.
  */
 size_t pk_workspace_bytes(const pk_config *cfg, pk_op op, int64_t a, int64_t b);
+
+/*
+ * How pk_decode_attention would cut a context (Sec. 3.4 leaves the work decomposition open): the length of the
+ * equal splits that own_packed packed tokens per stream of the cache itself and prefix_packed of a shared prefix are
+ * cut into, the number of partial-result slots per stream (splits of both plus two for the fp16 tails) and the
+ * workspace bytes those slots take - never more than pk_workspace_bytes reports for the same or longer contexts,
+ * and what has to fit PK_NOALLOC_SCRATCH_BYTES for pk_decode_attention_noalloc.  Host-only; never touches the
+ * device.  Each out pointer may be NULL.  Errors: cfg NULL or a negative count -> PK_ERR_INVALID_ARG; an invalid
+ * configuration -> its status.
+ */
+pk_status pk_decode_plan(const pk_config *cfg, int64_t own_packed, int64_t prefix_packed, int32_t *split_tokens /* host, out */,
+                         int32_t *n_slots /* host, out */, size_t *bytes_needed /* host, out */);
 
 /*
  * Pattern mining (Sec. 3.1, Eq. 4): `iters` Lloyd iterations of K-means under

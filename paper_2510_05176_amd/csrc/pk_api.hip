@@ -189,6 +189,23 @@ size_t pk_workspace_bytes(const pk_config *cfg, pk_op op, int64_t a, int64_t b)
     return 0;
 }
 
+pk_status pk_decode_plan(const pk_config *cfg, int64_t own_packed, int64_t prefix_packed, int32_t *split_tokens,
+                         int32_t *n_slots, size_t *bytes_needed)
+{
+    if (!cfg || own_packed < 0 || prefix_packed < 0) return PK_ERR_INVALID_ARG;
+    const pk_status st = check_config(cfg);
+    if (st != PK_OK) return st;
+    const int64_t N = (int64_t)cfg->n_seq * cfg->n_kv_heads, r = cfg->n_q_heads / cfg->n_kv_heads;
+    const int64_t c = decode_chunk(N, own_packed + prefix_packed, cfg->n_patterns, (int)r);
+    const int64_t slots = (own_packed + c - 1) / c + (prefix_packed + c - 1) / c + 2;
+    if (split_tokens) *split_tokens = (int32_t)c;
+    if (n_slots) *n_slots = (int32_t)slots;
+    if (bytes_needed)
+        *bytes_needed = (size_t)(round_up((uint64_t)N * slots * r * kD * 4, 256) + round_up((uint64_t)N * slots * r * cfg->n_patterns * 4, 256) +
+                                 round_up((uint64_t)N * slots * r * 2 * 4, 256));
+    return PK_OK;
+}
+
 pk_status pk_mine_patterns(const pk_config *cfg, const void *x, int64_t set_stride, int32_t n_sets, int32_t T,
                            int32_t iters, int32_t init_given, void *patterns, int32_t *assign, float *inertia,
                            void *workspace, size_t workspace_bytes, void *stream)

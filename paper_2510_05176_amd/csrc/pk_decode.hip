@@ -137,7 +137,8 @@ int decode_chunk(int64_t n_streams, int64_t t_packed_total, int P, int r)
     if (floor_c < 256) floor_c = 256;
     const int64_t fixed = 1024 + (int64_t)r * P / 2;
     int64_t best_c = 0, best_cost = 0;
-    for (int64_t k = (t + 32767) / 32768; k <= 512; ++k) {
+    const int64_t k_min = (t + 32767) / 32768;   // the fewest splits the length limit allows
+    for (int64_t k = k_min; k < k_min + 512; ++k) {
         int64_t c = ((t + k - 1) / k + 255) / 256 * 256;
         if (c < floor_c) c = (floor_c + 255) / 256 * 256;
         if (c > 32768) c = 32768;

@@ -49,7 +49,7 @@ class _State(C.Structure):
     _fields_ = [("t_quant", C.c_int32), ("t_tail", C.c_int32), ("tail_start", C.c_int32)]
 
 
-ABI_VERSION = 3          # PK_ABI_VERSION of include/patternkv.h this binding's structs are laid out for
+ABI_VERSION = 4          # PK_ABI_VERSION of include/patternkv.h this binding's structs are laid out for
 
 _lib.pk_abi_version.restype = C.c_uint32
 if int(_lib.pk_abi_version()) != ABI_VERSION:
@@ -58,6 +58,9 @@ _lib.pk_status_string.restype = C.c_char_p
 _lib.pk_status_string.argtypes = [C.c_int]
 _lib.pk_cache_layout.restype = C.c_int
 _lib.pk_cache_layout.argtypes = [C.POINTER(_Config), C.POINTER(_Layout)]
+_lib.pk_decode_plan.restype = C.c_int
+_lib.pk_decode_plan.argtypes = [C.POINTER(_Config), C.c_int64, C.c_int64, C.POINTER(C.c_int32), C.POINTER(C.c_int32),
+                                C.POINTER(C.c_size_t)]
 _lib.pk_workspace_bytes.restype = C.c_size_t
 _lib.pk_workspace_bytes.argtypes = [C.POINTER(_Config), C.c_int, C.c_int64, C.c_int64]
 _lib.pk_mine_patterns.restype = C.c_int
@@ -155,6 +158,15 @@ def pk_cache_layout(cfg: Config) -> dict:
     c = cfg.c()
     _check(_lib.pk_cache_layout(C.byref(c), C.byref(lay)), "pk_cache_layout")
     return {n: int(getattr(lay, n)) for n, _ in _Layout._fields_}
+
+
+def pk_decode_plan(cfg: Config, own_packed: int, prefix_packed: int = 0):
+    """(split length in tokens, partial slots per stream, workspace bytes in use) of a decode over that many packed tokens."""
+    c = cfg.c()
+    split, slots, need = C.c_int32(0), C.c_int32(0), C.c_size_t(0)
+    st = _lib.pk_decode_plan(C.byref(c), own_packed, prefix_packed, C.byref(split), C.byref(slots), C.byref(need))
+    _check(st, "pk_decode_plan")
+    return int(split.value), int(slots.value), int(need.value)
 
 
 def pk_workspace_bytes(cfg: Config, op: int, a: int, b: int = 0) -> int:

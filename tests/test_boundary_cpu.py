@@ -26,13 +26,13 @@ def test_exports_every_declared_symbol(pk):
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
     names = set(re.findall(r"\b(pk_[a-z0-9_]+)\s*\(", src))
     assert {"pk_mine_patterns", "pk_quantize_append", "pk_decode_attention", "pk_dequantize", "pk_cache_layout",
-            "pk_workspace_bytes", "pk_status_string", "pk_abi_version", "pk_window_pattern",
+            "pk_workspace_bytes", "pk_decode_plan", "pk_status_string", "pk_abi_version", "pk_window_pattern",
             "pk_decode_attention_ragged", "pk_decode_attention_noalloc", "pk_probe_read", "pk_probe_copy",
             "pk_probe_fma_f32", "pk_probe_mfma_f16", "pk_probe_divisions"} <= names
     lib = C.CDLL(LIB)
     for n in names:
         assert hasattr(lib, n), n
-    assert pk.pk_abi_version() == 3
+    assert pk.pk_abi_version() == 4
 
 
 def test_status_strings(pk):
@@ -98,6 +98,26 @@ def test_workspace_sizes_are_monotone(pk):
         assert w > prev
         prev = w
     assert pk.pk_workspace_bytes(cfg, pk.OP_APPEND, 128) == 0
+
+
+def test_decode_plan_fits_the_workspace_bound(pk):
+    """The split chooser of decode against the size the caller is told to allocate: for every stream count, context
+    length (up to the largest capacity, with and without a shared prefix), table size and head ratio tried, the
+    split is a positive multiple of 256 of at most 32768 tokens and the partial slots in use fit the workspace that
+    pk_workspace_bytes reports for the same context."""
+    n_cases = 0
+    for n_seq, hkv in [(1, 1), (1, 4), (2, 1), (1, 8), (37, 1), (32, 8), (432, 1), (75, 8), (512, 8), (1500, 8)]:
+        for P, r, G in [(1, 1, 64), (64, 4, 64), (128, 8, 64), (256, 7, 128), (64, 4, 32)]:
+            cfg = pk.Config(n_seq=n_seq, n_kv_heads=hkv, n_q_heads=hkv * r, n_patterns=P, bits=2, group=G, recent=0,
+                            flush=128, t_capacity=1 << 25)
+            for t in [0, 128, 256, 1024, 4096, 8192, 12288, 32640, 32768, 65536, 131072, 1 << 20, (1 << 24) + 128, 1 << 25]:
+                for pre in [0, 4096, 100096]:
+                    split, slots, need = pk.pk_decode_plan(cfg, t, pre)
+                    assert 0 < split <= 32768 and split % 256 == 0
+                    assert slots == -(-t // split) + -(-pre // split) + 2
+                    assert need <= pk.pk_workspace_bytes(cfg, pk.OP_DECODE, t, pre), (n_seq, hkv, P, r, t, pre, split, slots)
+                    n_cases += 1
+    assert n_cases == 10 * 5 * 14 * 3
 
 
 def _fake_cache(pk, base=0x1000):

@@ -258,3 +258,62 @@ def test_config4_decode_after_every_append(oracle, pk):
                                               prefix_patterns_v=Mvs)
             assert_attention(got[t, i][None], want)
         compare_caches(oracle, ooc, StreamView(gc, seq * Hkv + head), 0)
+
+
+class PeriodView:
+    """Tokens [j*Tp, (j+1)*Tp) of every stream of a GPU cache, presented like a cache of capacity Tp (every packed
+    array is token-major inside a stream, so the part of a token range is a byte range of the same proportion)."""
+
+    def __init__(self, gc, j, Tp):
+        self.gc, self.j, self.Tp = gc, j, Tp
+        self.N, self.cap = gc.cfg.n_seq * gc.cfg.n_kv_heads, gc.cfg.t_capacity
+
+    def array(self, name):
+        raw = self.gc.array(name)
+        if name.startswith("tail"):
+            return raw
+        per = raw.numel() // self.N
+        pp = per * self.Tp // self.cap
+        return raw.view(self.N, per)[:, self.j * pp:(self.j + 1) * pp].contiguous().view(-1)
+
+
+@pytest.mark.parametrize("bits,G,hq", [(2, 64, 8), (4, 32, 4)])
+def test_maximum_capacity_periodic_stream(oracle, pk, bits, G, hq):
+    """The largest capacity the interface accepts (2^25 packed tokens per stream; with 4-bit codes the last K and V
+    code bytes of a stream sit just below 2^31, the second stream's behind it), filled by one append and read by
+    one decode.  The streams repeat a 4096-token period 8192 times, which gives results the oracle can state
+    from ONE period: every period of the packed cache equals the oracle's cache of that period (the quantizer
+    works on groups of at most 128 tokens and 4096 is a multiple of every group and block size), and softmax
+    attention over identical periods equals attention over one of them, with log-sum-exp larger by ln(8192)."""
+    Tp, reps, hkv, P = 4096, 8192, 2, 64
+    cap = Tp * reps
+    assert cap == 1 << 25
+    kw = dict(n_seq=1, n_kv_heads=hkv, n_q_heads=hq, head_dim=128, n_patterns=P, seqs_per_set=0, bits=bits, group=G,
+              recent=0, flush=128, metric=0)
+    spec = synth.KVSpec(1, 1, hkv, hq, Tp, 128, 16)
+    Kp, Vp = synth.make_kv(11, spec)                       # [1, hkv, Tp, d] float16 (numpy)
+    Mk, Mv = np.ascontiguousarray(Kp[0, :, :P]), np.ascontiguousarray(Vp[0, :, :P])
+    ocfg = oracle.Config(**kw, t_capacity=Tp)
+    oc = oracle.Cache(ocfg)
+    oc.append(Kp.view(np.uint16), Vp.view(np.uint16), Mk.view(np.uint16), Mv.view(np.uint16))
+    assert (oc.t_quant, oc.t_tail) == (Tp, 0)
+
+    gcfg = pk.Config(**kw, t_capacity=cap)
+    gc = pk.Cache(gcfg)
+    Kd = torch.from_numpy(Kp).cuda().repeat(1, 1, reps, 1)  # [1, hkv, 2^25, d]: 8.6 GB per stream
+    Vd = torch.from_numpy(Vp).cuda().repeat(1, 1, reps, 1)
+    Mkd, Mvd = torch.from_numpy(Mk).cuda(), torch.from_numpy(Mv).cuda()
+    pk.pk_quantize_append(gcfg, gc, Kd, Vd, Mkd, Mvd)
+    torch.cuda.synchronize()
+    del Kd, Vd
+    assert (gc.t_quant, gc.t_tail) == (cap, 0)
+    for j in (0, 1, reps // 2 - 1, reps // 2, reps - 1):   # first, around the middle (byte offset 2^30 / 2^31), last
+        assert compare_caches(oracle, oc, PeriodView(gc, j, Tp), 0) <= 8, f"period {j}"
+
+    rng = np.random.default_rng(5)
+    q = rng.standard_normal((1, hq, 128)).astype(np.float16)
+    want, want_lse = oracle.decode_attention(oc, q.view(np.uint16), Mk.view(np.uint16), Mv.view(np.uint16), 128 ** -0.5)
+    lse = torch.empty((1, hq), dtype=torch.float32, device="cuda")
+    out = pk.pk_decode_attention(gcfg, gc, torch.from_numpy(q).cuda(), 128 ** -0.5, Mkd, Mvd, lse=lse)
+    assert_attention(out.cpu().numpy(), want)
+    assert np.abs(lse.cpu().numpy() - (np.asarray(want_lse) + np.log(reps))).max() <= 2e-3

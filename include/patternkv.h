@@ -167,7 +167,8 @@ pk_status pk_cache_layout(const pk_config *cfg, pk_layout *out /* host, out */);
 /*
  * Bytes of device workspace the given operation needs.
  *   PK_OP_MINE  : a = tokens per set T, b = number of pattern sets
- *   PK_OP_APPEND: a = n_new, b unused
+ *   PK_OP_APPEND: a, b unused: what pk_quantize_append_ragged needs (32 bytes per sequence); the uniform
+ *                 pk_quantize_append needs none and ignores its workspace arguments
  *   PK_OP_DECODE: a = packed + tail tokens per stream of the cache itself,
  *                 b = the same for the shared prefix (0 if none)
  * Non-decreasing in a and b, so a workspace sized for the largest case serves
@@ -224,6 +225,32 @@ pk_status pk_quantize_append(const pk_config *cfg, const pk_cache *cache, pk_sta
                              const void *k_new, const void *v_new, int32_t n_new,
                              int64_t stream_stride, const void *patterns_k, const void *patterns_v,
                              void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * pk_quantize_append for a batch whose sequences are filled to different lengths and receive different numbers
+ * of new vectors in one call (prompts of different lengths prefilled together; continuous batching, where every
+ * sequence is at a step of its own).  Sec. 3.2's computation is per stream and unchanged; every sequence keeps a
+ * pk_state of its own and is treated exactly as pk_quantize_append would treat it alone.
+ *   states          host, in/out, [n_seq]: the fill state of every sequence (each as for the uniform call)
+ *   n_new           host, [n_seq]: new vectors of every sequence, >= 0 (0: the sequence is left as it is)
+ *   k_new, v_new    [n_seq][n_kv_heads][n_max][d] fp16 with n_max >= max_i n_new[i]: sequence i uses the first
+ *                   n_new[i] rows of each of its streams; stream n starts at base + n*stream_stride elements
+ *                   (stream_stride 0 = max_i n_new[i] * d)
+ *   seq_states_out  optional DEVICE int32 [n_seq][4], 16-byte aligned: receives t_quant, t_tail, tail_start (and
+ *                   0) of every sequence after the append, in the form pk_decode_attention_ragged reads, so that
+ *                   an append and a decode can follow each other without a host-to-device copy by the caller
+ *   workspace       device, at least pk_workspace_bytes(cfg, PK_OP_APPEND, 0, 0) bytes (32 per sequence: the
+ *                   per-sequence launch parameters, written by a small kernel from values that travel in its
+ *                   arguments - no host buffer has to outlive the call)
+ * All sequences are checked before anything is launched: a bad state -> PK_ERR_STATE, a negative count ->
+ * PK_ERR_INVALID_ARG, a sequence whose flushes would exceed t_capacity -> PK_ERR_CAPACITY, a missing or small
+ * workspace -> PK_ERR_WORKSPACE; states and device memory are then untouched.  Launch sizes follow the largest
+ * sequence; workgroups beyond a shorter sequence's share return at once.
+ */
+pk_status pk_quantize_append_ragged(const pk_config *cfg, const pk_cache *cache, pk_state *states /* host [n_seq] */,
+                                    const void *k_new, const void *v_new, const int32_t *n_new /* host [n_seq] */,
+                                    int64_t stream_stride, const void *patterns_k, const void *patterns_v,
+                                    int32_t *seq_states_out, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * One decode step of attention over [shared prefix | packed | tail] for every

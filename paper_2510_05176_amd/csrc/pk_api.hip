@@ -2,6 +2,7 @@
 // layout, workspace carving and kernel launches.  Nothing here allocates device memory
 // or synchronises with the device.
 #include <cstring>
+#include <vector>
 #include <mutex>
 
 #include "pk_internal.h"
@@ -179,7 +180,7 @@ size_t pk_workspace_bytes(const pk_config *cfg, pk_op op, int64_t a, int64_t b)
         return mine_carve(b, a, cfg->n_patterns).total;
     }
     if (check_config(cfg) != PK_OK) return 0;
-    if (op == PK_OP_APPEND) return 0;
+    if (op == PK_OP_APPEND) return (size_t)cfg->n_seq * kSeqEntry * sizeof(int32_t);
     if (op == PK_OP_DECODE) {
         const int64_t N = (int64_t)cfg->n_seq * cfg->n_kv_heads, r = cfg->n_q_heads / cfg->n_kv_heads;
         const int64_t slots = decode_slots_bound(N, a, b);
@@ -239,37 +240,27 @@ pk_status pk_mine_patterns(const pk_config *cfg, const void *x, int64_t set_stri
     return launch_mine(a, static_cast<hipStream_t>(stream)) == hipSuccess ? PK_OK : PK_ERR_DEVICE;
 }
 
-pk_status pk_quantize_append(const pk_config *cfg, const pk_cache *cache, pk_state *state, const void *k_new,
-                             const void *v_new, int32_t n_new, int64_t stream_stride, const void *patterns_k,
-                             const void *patterns_v, void *workspace, size_t workspace_bytes, void *stream)
+namespace {
+
+// What an append launches: uniform values, or (seq_table set) the batch's largest counts for the launch sizes and
+// a per-sequence table for everything else.
+struct AppendPlan {
+    int64_t nq;            // vectors to quantize per stream (largest of the batch)
+    int32_t t0, ring_start, n_ring;
+    int64_t i0, i1;        // tail copy: logical vectors [i0, i1) (ragged: 0 .. the widest range)
+    const int32_t *seq_table;
+};
+
+pk_status launch_append(const pk_config *cfg, const pk_cache *cache, const AppendPlan &p, const void *k_new, const void *v_new,
+                        int64_t stream_stride, const void *patterns_k, const void *patterns_v, hipStream_t hs)
 {
-    (void)workspace;
-    (void)workspace_bytes;
-    pk_status st = check_config(cfg);
-    if (st != PK_OK) return st;
-    if ((st = check_cache(cache)) != PK_OK) return st;
-    if ((st = check_state(cfg, state)) != PK_OK) return st;
-    if (n_new < 0) return PK_ERR_INVALID_ARG;
-    if (n_new == 0) return PK_OK;
-    if (!k_new || !v_new || !patterns_k || !patterns_v) return PK_ERR_INVALID_ARG;
-    if (stream_stride == 0) stream_stride = (int64_t)n_new * kD;
-    if (stream_stride < (int64_t)n_new * kD || stream_stride % 8 != 0) return PK_ERR_SHAPE;
-    if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(patterns_k) || !aligned16(patterns_v))
-        return PK_ERR_ALIGNMENT;
-
-    const int64_t R = cfg->recent, F = cfg->flush, ring = R + F;
-    const int64_t L = (int64_t)state->t_tail + n_new;
-    const int64_t nf = L >= R ? (L - R) / F : 0;
-    const int64_t nq = nf * F;
-    if ((int64_t)state->t_quant + nq > cfg->t_capacity) return PK_ERR_CAPACITY;
-
-    hipStream_t hs = static_cast<hipStream_t>(stream);
     const int N = cfg->n_seq * cfg->n_kv_heads;
-    if (nq > 0) {
+    const int64_t ring = (int64_t)cfg->recent + cfg->flush;
+    if (p.nq > 0) {
         QuantArgs a;
         a.src.ring_len = (int32_t)ring;
-        a.src.ring_start = state->tail_start;
-        a.src.n_ring = state->t_tail;
+        a.src.ring_start = p.ring_start;
+        a.src.n_ring = p.n_ring;
         a.src.fresh_stride = stream_stride;
         a.sets.n_kv_heads = cfg->n_kv_heads;
         a.sets.seqs_per_set = cfg->seqs_per_set;
@@ -280,9 +271,10 @@ pk_status pk_quantize_append(const pk_config *cfg, const pk_cache *cache, pk_sta
         a.bits = cfg->bits;
         a.G = cfg->group;
         a.n_streams = N;
-        a.nq = (int32_t)nq;
-        a.t0 = state->t_quant;
+        a.nq = (int32_t)p.nq;
+        a.t0 = p.t0;
         a.t_capacity = cfg->t_capacity;
+        a.seq_table = p.seq_table;
         // K
         a.src.ring = static_cast<const __half *>(cache->tail_k);
         a.src.fresh = static_cast<const __half *>(k_new);
@@ -314,16 +306,137 @@ pk_status pk_quantize_append(const pk_config *cfg, const pk_cache *cache, pk_sta
     c.ring_k = static_cast<__half *>(cache->tail_k);
     c.ring_v = static_cast<__half *>(cache->tail_v);
     c.ring_len = (int32_t)ring;
-    c.ring_start = state->tail_start;
-    c.n_ring = state->t_tail;
-    c.i0 = (int32_t)(nq > state->t_tail ? nq : state->t_tail);
-    c.i1 = (int32_t)L;
+    c.ring_start = p.ring_start;
+    c.n_ring = p.n_ring;
+    c.i0 = (int32_t)p.i0;
+    c.i1 = (int32_t)p.i1;
     c.n_streams = N;
+    c.n_kv_heads = cfg->n_kv_heads;
+    c.seq_table = p.seq_table;
     if (launch_tail_copy(c, hs) != hipSuccess) return PK_ERR_DEVICE;
+    return PK_OK;
+}
+
+}  // namespace
+
+pk_status pk_quantize_append(const pk_config *cfg, const pk_cache *cache, pk_state *state, const void *k_new,
+                             const void *v_new, int32_t n_new, int64_t stream_stride, const void *patterns_k,
+                             const void *patterns_v, void *workspace, size_t workspace_bytes, void *stream)
+{
+    (void)workspace;
+    (void)workspace_bytes;
+    pk_status st = check_config(cfg);
+    if (st != PK_OK) return st;
+    if ((st = check_cache(cache)) != PK_OK) return st;
+    if ((st = check_state(cfg, state)) != PK_OK) return st;
+    if (n_new < 0) return PK_ERR_INVALID_ARG;
+    if (n_new == 0) return PK_OK;
+    if (!k_new || !v_new || !patterns_k || !patterns_v) return PK_ERR_INVALID_ARG;
+    if (stream_stride == 0) stream_stride = (int64_t)n_new * kD;
+    if (stream_stride < (int64_t)n_new * kD || stream_stride % 8 != 0) return PK_ERR_SHAPE;
+    if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(patterns_k) || !aligned16(patterns_v))
+        return PK_ERR_ALIGNMENT;
+
+    const int64_t R = cfg->recent, F = cfg->flush, ring = R + F;
+    const int64_t L = (int64_t)state->t_tail + n_new;
+    const int64_t nf = L >= R ? (L - R) / F : 0;
+    const int64_t nq = nf * F;
+    if ((int64_t)state->t_quant + nq > cfg->t_capacity) return PK_ERR_CAPACITY;
+
+    AppendPlan p;
+    p.nq = nq;
+    p.t0 = state->t_quant;
+    p.ring_start = state->tail_start;
+    p.n_ring = state->t_tail;
+    p.i0 = nq > state->t_tail ? nq : state->t_tail;
+    p.i1 = L;
+    p.seq_table = nullptr;
+    if ((st = launch_append(cfg, cache, p, k_new, v_new, stream_stride, patterns_k, patterns_v, static_cast<hipStream_t>(stream))) != PK_OK)
+        return st;
 
     state->t_quant += (int32_t)nq;
     state->tail_start = (int32_t)((state->tail_start + nq) % ring);
     state->t_tail = (int32_t)(L - nq);
+    return PK_OK;
+}
+
+pk_status pk_quantize_append_ragged(const pk_config *cfg, const pk_cache *cache, pk_state *states, const void *k_new,
+                                    const void *v_new, const int32_t *n_new, int64_t stream_stride, const void *patterns_k,
+                                    const void *patterns_v, int32_t *seq_states_out, void *workspace, size_t workspace_bytes,
+                                    void *stream)
+{
+    pk_status st = check_config(cfg);
+    if (st != PK_OK) return st;
+    if ((st = check_cache(cache)) != PK_OK) return st;
+    if (!states || !n_new) return PK_ERR_INVALID_ARG;
+    const int S = cfg->n_seq;
+    int64_t max_new = 0;
+    for (int i = 0; i < S; ++i) {
+        if ((st = check_state(cfg, &states[i])) != PK_OK) return st;
+        if (n_new[i] < 0) return PK_ERR_INVALID_ARG;
+        if (n_new[i] > max_new) max_new = n_new[i];
+    }
+    if (seq_states_out && !aligned16(seq_states_out)) return PK_ERR_ALIGNMENT;
+    const size_t table_bytes = (size_t)S * kSeqEntry * sizeof(int32_t);
+    if (max_new > 0) {
+        if (!k_new || !v_new || !patterns_k || !patterns_v) return PK_ERR_INVALID_ARG;
+        if (stream_stride == 0) stream_stride = max_new * kD;
+        if (stream_stride < max_new * kD || stream_stride % 8 != 0) return PK_ERR_SHAPE;
+        if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(patterns_k) || !aligned16(patterns_v)) return PK_ERR_ALIGNMENT;
+    }
+    if (!workspace || workspace_bytes < table_bytes) return PK_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return PK_ERR_ALIGNMENT;
+
+    // the plan of every sequence, checked as a whole before anything is launched
+    const int64_t R = cfg->recent, F = cfg->flush, ring = R + F;
+    std::vector<int32_t> entry((size_t)S * kSeqEntry, 0), after((size_t)S * 3, 0);
+    AppendPlan p;
+    p.nq = 0;
+    p.t0 = 0;
+    p.ring_start = 0;
+    p.n_ring = 0;
+    p.i0 = 0;
+    p.i1 = 0;
+    for (int i = 0; i < S; ++i) {
+        const pk_state &s = states[i];
+        const int64_t L = (int64_t)s.t_tail + n_new[i];
+        const int64_t nq = L >= R ? (L - R) / F * F : 0;
+        if ((int64_t)s.t_quant + nq > cfg->t_capacity) return PK_ERR_CAPACITY;
+        int32_t *e = &entry[(size_t)i * kSeqEntry];
+        e[kSeqNq] = (int32_t)nq;
+        e[kSeqT0] = s.t_quant;
+        e[kSeqRingStart] = s.tail_start;
+        e[kSeqNRing] = s.t_tail;
+        e[kSeqI0] = (int32_t)(nq > s.t_tail ? nq : s.t_tail);
+        e[kSeqI1] = (int32_t)L;
+        after[(size_t)i * 3] = (int32_t)(s.t_quant + nq);
+        after[(size_t)i * 3 + 1] = (int32_t)(L - nq);
+        after[(size_t)i * 3 + 2] = (int32_t)((s.tail_start + nq) % ring);
+        if (nq > p.nq) p.nq = nq;
+        if (e[kSeqI1] - e[kSeqI0] > p.i1) p.i1 = e[kSeqI1] - e[kSeqI0];   // launch width of the tail copy
+    }
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    p.seq_table = static_cast<const int32_t *>(workspace);
+    for (int first = 0; first < S; first += kSeqChunk) {
+        SeqTableArgs t;
+        t.table = static_cast<int32_t *>(workspace);
+        t.states_out = seq_states_out;
+        t.first = first;
+        t.count = S - first < kSeqChunk ? S - first : kSeqChunk;
+        std::memset(t.entry, 0, sizeof(t.entry));
+        std::memset(t.state, 0, sizeof(t.state));
+        std::memcpy(t.entry, &entry[(size_t)first * kSeqEntry], (size_t)t.count * kSeqEntry * sizeof(int32_t));
+        std::memcpy(t.state, &after[(size_t)first * 3], (size_t)t.count * 3 * sizeof(int32_t));
+        if (launch_seq_table(t, hs) != hipSuccess) return PK_ERR_DEVICE;
+    }
+    if (max_new > 0 &&
+        (st = launch_append(cfg, cache, p, k_new, v_new, stream_stride, patterns_k, patterns_v, hs)) != PK_OK)
+        return st;
+    for (int i = 0; i < S; ++i) {
+        states[i].t_quant = after[(size_t)i * 3];
+        states[i].t_tail = after[(size_t)i * 3 + 1];
+        states[i].tail_start = after[(size_t)i * 3 + 2];
+    }
     return PK_OK;
 }
 

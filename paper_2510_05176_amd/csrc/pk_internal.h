@@ -112,7 +112,26 @@ struct QuantArgs {
     uint8_t *codes_v;         // V side
     __half *scale, *zero;
     uint8_t *idx;
+    // A ragged append: per-sequence fill parameters, [n_seq][kSeqEntry] int32 in device memory (written by
+    // seq_table_kernel from the host's plan): vectors to quantize, first packed position, ring start, vectors in
+    // the ring, first and end logical vector of the tail copy.  nq above is then the largest of the batch (launch
+    // sizing only).  Null for a uniform append.
+    const int32_t *seq_table;
 };
+constexpr int kSeqEntry = 8;                                   // int32 per sequence in the table
+enum { kSeqNq = 0, kSeqT0 = 1, kSeqRingStart = 2, kSeqNRing = 3, kSeqI0 = 4, kSeqI1 = 5 };
+
+// The fill parameters of the workgroup's own sequence replace the uniform ones (wave-uniform loads).
+__device__ __forceinline__ void take_sequence_entry(QuantArgs &a, int stream)
+{
+    if (a.seq_table) {
+        const int32_t *e = a.seq_table + (int64_t)(stream / a.sets.n_kv_heads) * kSeqEntry;
+        a.nq = e[kSeqNq];
+        a.t0 = e[kSeqT0];
+        a.src.ring_start = e[kSeqRingStart];
+        a.src.n_ring = e[kSeqNRing];
+    }
+}
 
 hipError_t launch_quantize_k(const QuantArgs &a, hipStream_t s);
 hipError_t launch_quantize_v(const QuantArgs &a, hipStream_t s);
@@ -124,7 +143,21 @@ struct TailCopyArgs {
     int32_t ring_len, ring_start, n_ring;   // as in RowSource (state before the append)
     int32_t i0, i1;                          // logical vectors [i0, i1) to place into the ring
     int32_t n_streams;
+    int32_t n_kv_heads;
+    const int32_t *seq_table;                // ragged append: as in QuantArgs (i0, i1 above: the widest range)
 };
+// Writes up to kSeqChunk entries of the per-sequence table, and (optionally) the fill states after the append in
+// the form the ragged decode reads, from values that travel in the kernel arguments: no host buffer has to outlive
+// the call and nothing is copied from pageable memory.
+constexpr int kSeqChunk = 64;
+struct SeqTableArgs {
+    int32_t *table;          // [n_seq][kSeqEntry]
+    int32_t *states_out;     // [n_seq][4] or null: t_quant, t_tail, tail_start, 0 after the append
+    int32_t first, count;
+    int32_t entry[kSeqChunk][kSeqEntry];
+    int32_t state[kSeqChunk][3];
+};
+hipError_t launch_seq_table(const SeqTableArgs &a, hipStream_t s);
 hipError_t launch_tail_copy(const TailCopyArgs &a, hipStream_t s);
 
 struct MineArgs {

@@ -69,6 +69,17 @@ __device__ __forceinline__ float sub_s_hi(float x, uint32_t m)   // x - half(m.h
 // Sixteen consecutive dwords through the scalar data path (read only; address wave-uniform, 4-byte aligned), and the
 // wait for every scalar load issued so far; the values are tied to the wait so that no use can move ahead of it.
 typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
+// Which run of tiles of its stream (blockIdx.y) a workgroup takes.  Workgroups go to the chip's eight XCDs in turn
+// by their linear index, y * gridDim.x + x; with the run taken as x itself an XCD would get the runs x = k, k + 8, ...
+// of EVERY stream, and when streams have different numbers of runs (a ragged append: the grid is sized for the
+// longest sequence and the runs past a sequence's end return at once) the XCDs of low k get up to 55 % more
+// work than the last one (measured: 16 prompts of 2 k to 32 k tokens ran 1.55x slower than the same bytes in
+// equal lengths).  Rotating the run by the stream index gives every XCD every residue class in turn.
+__device__ __forceinline__ int chunk_of_workgroup()
+{
+    return (int)((blockIdx.x + blockIdx.y) % gridDim.x);
+}
+
 __device__ __forceinline__ u32x16 sload16(const uint32_t *p)
 {
     u32x16 r;
@@ -85,8 +96,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void a
     const int tid = threadIdx.x, lane = tid & 63, ns = blockIdx.y;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t *Mg = reinterpret_cast<const uint32_t *>(a.patterns + (int64_t)a.sets.set_of(ns) * a.P * kD);
+    take_sequence_entry(a, ns);
     const int n_tiles = a.nq / 64;
-    const int tile0 = blockIdx.x * tiles_per_wg, tile1 = min(n_tiles, tile0 + tiles_per_wg);
+    const int tile0 = chunk_of_workgroup() * tiles_per_wg, tile1 = min(n_tiles, tile0 + tiles_per_wg);
     for (int tile = tile0 + wave; tile < tile1; tile += 4) {
         // the lane's vector, widened
         float x[kD];
@@ -386,8 +398,10 @@ __global__ __launch_bounds__(256) void quantize_k_kernel(QuantArgs a, int tiles_
     const int tid = threadIdx.x, ns = blockIdx.y;
     const int lane = tid & 63, wave = tid >> 6, n = lane & 15, kb = lane >> 4;
     const __half *Mg = a.patterns + (int64_t)a.sets.set_of(ns) * a.P * kD;
+    take_sequence_entry(a, ns);
     const int n_tiles = a.nq / TT;
-    const int tile0 = blockIdx.x * tiles_per_wg, tile1 = min(n_tiles, tile0 + tiles_per_wg);
+    const int tile0 = chunk_of_workgroup() * tiles_per_wg, tile1 = min(n_tiles, tile0 + tiles_per_wg);
+    if (tile0 >= n_tiles) return;   // a ragged append: this sequence has fewer tiles than the launch was sized for
     uint4 xb[NT][4];
 #pragma unroll
     for (int j = 0; j < NT; ++j) load_tile(a, ns, tile0 * TT + (wave * NT + j) * 16, xb[j]);   // in flight while the table is staged
@@ -526,8 +540,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NTA > 2 ? 2
     float *pinv = reinterpret_cast<float *>(mine + kWkTile + kD * 2 * 2);
 
     const __half *Mg = a.patterns + (int64_t)a.sets.set_of(ns) * a.P * kD;
+    take_sequence_entry(a, ns);
     const int n_tiles = a.nq / 64;
-    const int tile0 = blockIdx.x * tiles_per_wg, tile1 = min(n_tiles, tile0 + tiles_per_wg);
+    const int tile0 = chunk_of_workgroup() * tiles_per_wg, tile1 = min(n_tiles, tile0 + tiles_per_wg);
+    if (tile0 >= n_tiles) return;   // a ragged append: this sequence has fewer tiles than the launch was sized for
     const int g_end = tile1 * (64 / G);
     int g = tile0 * (64 / G) + wave;
     uint4 xb[NTG][4];
@@ -665,8 +681,10 @@ __global__ __launch_bounds__(256) void quantize_v_kernel(QuantArgs a, int tiles_
     const int tid = threadIdx.x, ns = blockIdx.y;
     const int lane = tid & 63, wave = tid >> 6, n = lane & 15, kb = lane >> 4;
     const __half *Mg = a.patterns + (int64_t)a.sets.set_of(ns) * a.P * kD;
+    take_sequence_entry(a, ns);
     const int n_tiles = a.nq / TT;
-    const int tile0 = blockIdx.x * tiles_per_wg, tile1 = min(n_tiles, tile0 + tiles_per_wg);
+    const int tile0 = chunk_of_workgroup() * tiles_per_wg, tile1 = min(n_tiles, tile0 + tiles_per_wg);
+    if (tile0 >= n_tiles) return;   // a ragged append: this sequence has fewer tiles than the launch was sized for
     uint4 xbs[NT][4];
 #pragma unroll
     for (int j = 0; j < NT; ++j)   // a block past the workgroup's range repeats the last one; its result is not used
@@ -845,6 +863,13 @@ __global__ __launch_bounds__(256) void quantize_v_kernel(QuantArgs a, int tiles_
 __global__ __launch_bounds__(256) void tail_copy_kernel(TailCopyArgs a)
 {
     const int n = blockIdx.y, side = blockIdx.z;
+    if (a.seq_table) {   // a ragged append: the ring state and the range of the stream's own sequence
+        const int32_t *e = a.seq_table + (int64_t)(n / a.n_kv_heads) * kSeqEntry;
+        a.ring_start = e[kSeqRingStart];
+        a.n_ring = e[kSeqNRing];
+        a.i0 = e[kSeqI0];
+        a.i1 = e[kSeqI1];
+    }
     const int64_t work = (int64_t)(a.i1 - a.i0) * kRowChunks;
     const int64_t w = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (w >= work) return;
@@ -857,7 +882,21 @@ __global__ __launch_bounds__(256) void tail_copy_kernel(TailCopyArgs a)
     *reinterpret_cast<uint4 *>(ring + ((int64_t)n * a.ring_len + slot) * kD + ch * 8) = v;
 }
 
+__global__ __launch_bounds__(kSeqChunk * kSeqEntry) void seq_table_kernel(SeqTableArgs a)
+{
+    const int i = threadIdx.x / kSeqEntry, f = threadIdx.x % kSeqEntry;
+    if (i >= a.count) return;
+    a.table[(int64_t)(a.first + i) * kSeqEntry + f] = a.entry[i][f];
+    if (a.states_out && f < 4) a.states_out[(int64_t)(a.first + i) * 4 + f] = f < 3 ? a.state[i][f] : 0;
+}
+
 }  // namespace
+
+hipError_t launch_seq_table(const SeqTableArgs &a, hipStream_t s)
+{
+    hipLaunchKernelGGL(seq_table_kernel, dim3(1), dim3(kSeqChunk * kSeqEntry), 0, s, a);
+    return hipGetLastError();
+}
 
 static int tiles_per_wg(int n_tiles, int n_streams)
 {

@@ -71,6 +71,10 @@ _lib.pk_quantize_append.restype = C.c_int
 _lib.pk_quantize_append.argtypes = [C.POINTER(_Config), C.POINTER(_Cache), C.POINTER(_State), C.c_void_p,
                                     C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
                                     C.c_size_t, C.c_void_p]
+_lib.pk_quantize_append_ragged.restype = C.c_int
+_lib.pk_quantize_append_ragged.argtypes = [C.POINTER(_Config), C.POINTER(_Cache), C.POINTER(_State), C.c_void_p, C.c_void_p,
+                                           C.POINTER(C.c_int32), C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                           C.c_size_t, C.c_void_p]
 _lib.pk_decode_attention.restype = C.c_int
 _lib.pk_decode_attention.argtypes = [C.POINTER(_Config), C.POINTER(_Cache), C.POINTER(_State),
                                      C.POINTER(_Config), C.POINTER(_Cache), C.POINTER(_State), C.c_void_p,
@@ -209,10 +213,15 @@ class Cache:
     def sequence(self, i: int) -> "Cache":
         """The part of sequence i as a cache of its own (n_seq = 1, one pattern set per KV head) over the same
         memory, with a fill state of its own: the arrays are laid out stream by stream."""
+        return self.sequences(i, 1)
+
+    def sequences(self, first: int, count: int) -> "Cache":
+        """Sequences [first, first + count) as a cache of their own (one pattern set per KV head, shared by them)."""
+        per = {n: self.bytes[n] // self.cfg.n_seq for n in _ARRAYS}
         sub = Cache.__new__(Cache)
-        sub.cfg = replace(self.cfg, n_seq=1, seqs_per_set=0)
-        sub.bytes = {n: self.bytes[n] // self.cfg.n_seq for n in _ARRAYS}
-        sub.buf = {n: self.buf[n][i * sub.bytes[n]:(i + 1) * sub.bytes[n]] for n in _ARRAYS}
+        sub.cfg = replace(self.cfg, n_seq=count, seqs_per_set=0)
+        sub.bytes = {n: per[n] * count for n in _ARRAYS}
+        sub.buf = {n: self.buf[n][first * per[n]:(first + count) * per[n]] for n in _ARRAYS}
         sub.state = _State(0, 0, 0)
         return sub
 
@@ -278,6 +287,30 @@ def pk_quantize_append(cfg: Config, cache: Cache, k_new: torch.Tensor, v_new: to
                                  _ptr(patterns_v), _ptr(workspace), 0 if workspace is None else workspace.numel(),
                                  _stream())
     _check(st, "pk_quantize_append")
+
+
+def pk_quantize_append_ragged(cfg: Config, cache: Cache, states: list, k_new: torch.Tensor, v_new: torch.Tensor, n_new: list,
+                              patterns_k: torch.Tensor, patterns_v: torch.Tensor, seq_states_out: torch.Tensor | None = None,
+                              workspace: torch.Tensor | None = None):
+    """One append for sequences at different fill: states = one [t_quant, t_tail, tail_start] per sequence (updated in
+    place), n_new = new vectors per sequence; k_new, v_new [n_seq, n_kv_heads, n_max, d] fp16, contiguous."""
+    assert k_new.dtype == torch.float16 and v_new.dtype == torch.float16 and k_new.shape == v_new.shape
+    assert k_new.is_contiguous() and v_new.is_contiguous()
+    n_seq, hkv, n_max, d = k_new.shape
+    assert n_seq == cfg.n_seq and len(states) == n_seq and len(n_new) == n_seq and max(n_new) <= n_max
+    if seq_states_out is not None:
+        assert seq_states_out.dtype == torch.int32 and tuple(seq_states_out.shape) == (n_seq, 4) and seq_states_out.is_contiguous()
+    if workspace is None:
+        workspace = torch.empty(max(pk_workspace_bytes(cfg, OP_APPEND, 0, 0), 16), dtype=torch.uint8, device=k_new.device)
+    st_arr = (_State * n_seq)(*[_State(int(s[0]), int(s[1]), int(s[2])) for s in states])
+    nn_arr = (C.c_int32 * n_seq)(*[int(n) for n in n_new])
+    cc, kc = cfg.c(), cache.c()
+    st = _lib.pk_quantize_append_ragged(C.byref(cc), C.byref(kc), st_arr, C.c_void_p(k_new.data_ptr()),
+                                        C.c_void_p(v_new.data_ptr()), nn_arr, n_max * d, _ptr(patterns_k), _ptr(patterns_v),
+                                        _ptr(seq_states_out), _ptr(workspace), workspace.numel(), _stream())
+    _check(st, "pk_quantize_append_ragged")
+    for i in range(n_seq):
+        states[i][0], states[i][1], states[i][2] = st_arr[i].t_quant, st_arr[i].t_tail, st_arr[i].tail_start
 
 
 def pk_decode_attention(cfg: Config, cache: Cache, q: torch.Tensor, softmax_scale: float,

@@ -12,6 +12,16 @@ static int g_launches = 0;
 hipError_t launch_quantize_k(const QuantArgs &, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_quantize_v(const QuantArgs &, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_tail_copy(const TailCopyArgs &, hipStream_t) { ++g_launches; return hipSuccess; }
+static int32_t g_table[64][kSeqEntry], g_after[64][3];
+hipError_t launch_seq_table(const SeqTableArgs &a, hipStream_t)
+{
+    ++g_launches;
+    for (int i = 0; i < a.count && a.first + i < 64; ++i) {
+        std::memcpy(g_table[a.first + i], a.entry[i], sizeof(g_table[0]));
+        std::memcpy(g_after[a.first + i], a.state[i], sizeof(g_after[0]));
+    }
+    return hipSuccess;
+}
 hipError_t launch_mine(const MineArgs &, hipStream_t) { ++g_launches; return hipSuccess; }
 int mine_tsplit(int T, int, int) { return (T + 255) / 256; }
 hipError_t launch_window_pattern(const __half *, int64_t, int, int, __half *, int64_t, hipStream_t) { ++g_launches; return hipSuccess; }
@@ -60,6 +70,29 @@ int main()
     CHECK(pk_quantize_append(&c, &k, &st, base + 2, base, 1, 0, base, base, nullptr, 0, nullptr) == PK_ERR_ALIGNMENT);
     pk_state wrong = {100, 0, 0};
     CHECK(pk_quantize_append(&c, &k, &wrong, base, base, 1, 0, base, base, nullptr, 0, nullptr) == PK_ERR_STATE);
+    // one append for sequences at different fill: every sequence's plan is what the uniform call would do for it
+    {
+        pk_state ss[2] = {{0, 0, 0}, {256, 144, 96}};
+        const int32_t nn[2] = {100, 300};
+        const size_t wa = pk_workspace_bytes(&c, PK_OP_APPEND, 0, 0);
+        CHECK(wa == 2 * 32);
+        CHECK(pk_quantize_append_ragged(&c, &k, ss, base, base, nn, 0, base, base, nullptr, base, wa, nullptr) == PK_OK);
+        CHECK(ss[0].t_quant == 0 && ss[0].t_tail == 100 && ss[0].tail_start == 0);
+        CHECK(ss[1].t_quant == 256 + 384 && ss[1].t_tail == 444 - 384 && ss[1].tail_start == (96 + 384) % 160);
+        CHECK(pk::g_table[1][pk::kSeqNq] == 384 && pk::g_table[1][pk::kSeqT0] == 256 && pk::g_table[1][pk::kSeqI0] == 384 &&
+              pk::g_table[1][pk::kSeqI1] == 444 && pk::g_table[0][pk::kSeqNq] == 0 && pk::g_table[0][pk::kSeqI1] == 100);
+        CHECK(pk::g_after[1][0] == 640 && pk::g_after[1][1] == 60);
+        const pk_state keep0 = ss[0], keep1 = ss[1];
+        const int32_t too_many[2] = {1, 4000};
+        CHECK(pk_quantize_append_ragged(&c, &k, ss, base, base, too_many, 0, base, base, nullptr, base, wa, nullptr) == PK_ERR_CAPACITY);
+        CHECK(std::memcmp(&keep0, &ss[0], sizeof(keep0)) == 0 && std::memcmp(&keep1, &ss[1], sizeof(keep1)) == 0);
+        CHECK(pk_quantize_append_ragged(&c, &k, ss, base, base, nn, 0, base, base, nullptr, base, wa - 1, nullptr) == PK_ERR_WORKSPACE);
+        const int32_t neg[2] = {1, -1};
+        CHECK(pk_quantize_append_ragged(&c, &k, ss, base, base, neg, 0, base, base, nullptr, base, wa, nullptr) == PK_ERR_INVALID_ARG);
+        const int32_t none[2] = {0, 0};
+        CHECK(pk_quantize_append_ragged(&c, &k, ss, nullptr, nullptr, none, 0, nullptr, nullptr, nullptr, base, wa, nullptr) == PK_OK);
+        CHECK(std::memcmp(&keep0, &ss[0], sizeof(keep0)) == 0);
+    }
     // decode: workspace check, prefix consistency
     const size_t ws = pk_workspace_bytes(&c, PK_OP_DECODE, st.t_quant + st.t_tail, 0);
     float *out = reinterpret_cast<float *>(base);

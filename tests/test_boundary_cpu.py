@@ -25,7 +25,7 @@ def test_exports_every_declared_symbol(pk):
     src = open(HEADER).read() + open(PROBE_HEADER).read()
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
     names = set(re.findall(r"\b(pk_[a-z0-9_]+)\s*\(", src))
-    assert {"pk_mine_patterns", "pk_quantize_append", "pk_decode_attention", "pk_dequantize", "pk_cache_layout",
+    assert {"pk_mine_patterns", "pk_quantize_append", "pk_quantize_append_ragged", "pk_decode_attention", "pk_dequantize", "pk_cache_layout",
             "pk_workspace_bytes", "pk_decode_plan", "pk_status_string", "pk_abi_version", "pk_window_pattern",
             "pk_decode_attention_ragged", "pk_decode_attention_noalloc", "pk_probe_read", "pk_probe_copy",
             "pk_probe_fma_f32", "pk_probe_mfma_f16", "pk_probe_divisions"} <= names
@@ -97,7 +97,7 @@ def test_workspace_sizes_are_monotone(pk):
         w = pk.pk_workspace_bytes(cfg, pk.OP_MINE, t, 16)
         assert w > prev
         prev = w
-    assert pk.pk_workspace_bytes(cfg, pk.OP_APPEND, 128) == 0
+    assert pk.pk_workspace_bytes(cfg, pk.OP_APPEND, 128) == 4 * 32   # the per-sequence table of the ragged form
 
 
 def test_decode_plan_fits_the_workspace_bound(pk):

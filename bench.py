@@ -17,8 +17,9 @@ the 256 MB Infinity Cache.
 Default workload: cfg3, the contract's long-context batched decode (32 layers x batch 16 x T = 32768, 8 KV / 32
 query heads, P = 128, 2-bit, group 64, 128 recent fp16 tokens; 68.7 GB of fp16 source).  With the default
 workload the line also carries `sweep` (the same stages on cfg2x32 - config 2's layer for all 32 layers of the
-model in one launch -, cfg5, cfg4 at its full schedule of 8192 generated tokens with a decode after every
-append, and cfg2x32 with the min-max selection rule) and `measured_peaks` (streaming read / copy, fp32 FMA and
+model in one launch -, cfg5, the MLA latent-cache workload, cfg4 at its full schedule of 8192 generated tokens
+with a decode after every append, cfg3r - config 3 with sequences of different lengths: ragged prefill and ragged
+decode -, and cfg2x32 with the min-max selection rule) and `measured_peaks` (streaming read / copy, fp32 FMA and
 fp16 MFMA loops on this GPU).
 
 Other modes (no GPU needed):
@@ -59,7 +60,7 @@ WORKLOADS = {
     "mla": dict(spec="mla", layers=27, batch=16, P=128, iters=10, group=64, recent=128, flush=128),
     "mla_prerope": dict(spec="mla_prerope", layers=27, batch=16, P=128, iters=10, group=64, recent=128, flush=128),
     "cfg4": dict(spec="cfg4"),   # streaming: its own step, see run_streaming()
-    "cfg3r": dict(spec="cfg3"),  # config 3's shape with a mix of sequence lengths: decode only, see run_ragged()
+    "cfg3r": dict(spec="cfg3"),  # config 3's shape with a mix of sequence lengths: ragged prefill + ragged decode, see run_ragged()
 }
 DECODE_KERNELS = "decode_packed_kernel(+decode_tail_kernel+decode_merge_kernel)"
 
@@ -652,6 +653,12 @@ def main():
                                      "decode per step, a 128-token flush every 128 steps",
                          "ms_per_step": s["ms_per_step"], "generated_tokens/s": s["generated_tokens/s"],
                          "decode_attention_at_end": {k: s["stages"]["decode_attention_at_end"][k] for k in ("ms", "GB/s", "frac_hbm_peak")}}
+        s = run_ragged(args, torch, pk, synth)
+        torch.cuda.empty_cache()
+        progress("cfg3r: ragged prefill and decode timed")
+        sweep["cfg3r"] = {"batch": "config 3's shape, the 16 sequences filled to different lengths (seeded, 2048 .. 32768)",
+                          "quantize_append_ragged": {k: s["stages"]["quantize_append_ragged"][k] for k in ("ms", "GB/s", "frac_hbm_peak")},
+                          "decode_attention_ragged": {k: s["stages"]["decode_attention"][k] for k in ("ms", "GB/s", "frac_hbm_peak", "tokens/s")}}
         s = run_static("cfg2x32", args, torch, pk, synth, 5, 1, metric=pk.METRIC_MINMAX)
         torch.cuda.empty_cache()
         rq = s["stage_rooflines"]["quantize_append"]

@@ -102,6 +102,9 @@ CacheView make_view(const pk_config *c, const pk_cache *k, const pk_state *s)
     return v;
 }
 
+// the sequence order of a ragged batch lives behind the partials
+uint64_t decode_order_bytes(int64_t n_seq) { return round_up((uint64_t)n_seq * 4, 256); }
+
 // upper bound on the number of partial slots decode uses for up to a own / b prefix tokens
 int64_t decode_slots_bound(int64_t N, int64_t a, int64_t b)
 {
@@ -185,7 +188,7 @@ size_t pk_workspace_bytes(const pk_config *cfg, pk_op op, int64_t a, int64_t b)
         const int64_t N = (int64_t)cfg->n_seq * cfg->n_kv_heads, r = cfg->n_q_heads / cfg->n_kv_heads;
         const int64_t slots = decode_slots_bound(N, a, b);
         return round_up((uint64_t)N * slots * r * kD * 4, 256) + round_up((uint64_t)N * slots * r * cfg->n_patterns * 4, 256) +
-               round_up((uint64_t)N * slots * r * 2 * 4, 256);
+               round_up((uint64_t)N * slots * r * 2 * 4, 256) + decode_order_bytes(cfg->n_seq);
     }
     return 0;
 }
@@ -203,7 +206,7 @@ pk_status pk_decode_plan(const pk_config *cfg, int64_t own_packed, int64_t prefi
     if (n_slots) *n_slots = (int32_t)slots;
     if (bytes_needed)
         *bytes_needed = (size_t)(round_up((uint64_t)N * slots * r * kD * 4, 256) + round_up((uint64_t)N * slots * r * cfg->n_patterns * 4, 256) +
-                                 round_up((uint64_t)N * slots * r * 2 * 4, 256));
+                                 round_up((uint64_t)N * slots * r * 2 * 4, 256) + decode_order_bytes(cfg->n_seq));
     return PK_OK;
 }
 
@@ -484,7 +487,8 @@ static pk_status decode_impl(const pk_config *cfg, const pk_cache *cache, const 
     const uint64_t o_bytes = round_up((uint64_t)N * slots * r * kD * 4, 256);
     const uint64_t w_bytes = round_up((uint64_t)N * slots * r * cfg->n_patterns * 4, 256);
     const uint64_t ml_bytes = round_up((uint64_t)N * slots * r * 2 * 4, 256);
-    if (!workspace || workspace_bytes < o_bytes + w_bytes + ml_bytes) return PK_ERR_WORKSPACE;
+    const uint64_t order_bytes = decode_order_bytes(cfg->n_seq);
+    if (!workspace || workspace_bytes < o_bytes + w_bytes + ml_bytes + order_bytes) return PK_ERR_WORKSPACE;
     if (!aligned16(workspace)) return PK_ERR_ALIGNMENT;
 
     a.sets.n_kv_heads = cfg->n_kv_heads;
@@ -505,6 +509,9 @@ static pk_status decode_impl(const pk_config *cfg, const pk_cache *cache, const 
     a.out = out;
     a.lse = lse;
     a.seq_state = seq_states;
+    a.seq_order = seq_states && cfg->n_seq > 1 && cfg->n_seq <= kMaxOrdered
+                      ? reinterpret_cast<const int32_t *>(static_cast<char *>(workspace) + o_bytes + w_bytes + ml_bytes)
+                      : nullptr;
     return launch_decode(a, static_cast<hipStream_t>(stream)) == hipSuccess ? PK_OK : PK_ERR_DEVICE;
 }
 

@@ -121,6 +121,30 @@ __global__ __launch_bounds__(128 * NQ) void decode_merge_kernel(DecodeArgs a)
     if (a.lse && c == 0) a.lse[u] = L > 0.f ? (M + log2f(L)) * kLn2 : -INFINITY;
 }
 
+// Ragged batch: rank of every sequence by the length of its packed part, longest first (ties by index), by
+// counting; one workgroup, n_seq <= kMaxOrdered.  Workgroups are dispatched in grid order, so starting the long
+// streams first keeps the last round from consisting of a few long ones running alone.
+__global__ __launch_bounds__(kMaxOrdered) void decode_order_kernel(DecodeArgs a, int32_t *order)
+{
+    __shared__ int32_t key[kMaxOrdered];
+    const int i = threadIdx.x, n = a.n_seq;
+    int mine = 0;
+    if (i < n) {
+        int tq, tt, ts;
+        own_state(a, i, tq, tt, ts);
+        mine = tq;
+        key[i] = tq;
+    }
+    __syncthreads();
+    if (i >= n) return;
+    int rank = 0;
+    for (int j = 0; j < n; ++j) {
+        const int k = key[j];
+        rank += (k > mine || (k == mine && j < i)) ? 1 : 0;
+    }
+    order[rank] = i;
+}
+
 }  // namespace
 
 int decode_chunk(int64_t n_streams, int64_t t_packed_total, int P, int r)
@@ -159,6 +183,10 @@ hipError_t launch_decode(const DecodeArgs &a, hipStream_t s)
     const int r = a.n_q_heads / a.n_kv_heads;
     const int N = a.n_seq * a.n_kv_heads;
     hipError_t e;
+    if (a.seq_order && a.splits_prefix + a.splits_own > 0) {
+        hipLaunchKernelGGL(decode_order_kernel, dim3(1), dim3(kMaxOrdered), 0, s, a, const_cast<int32_t *>(a.seq_order));
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
     if ((e = launch_decode_packed(a, s)) != hipSuccess) return e;
     if ((a.own.t_tail > 0 || a.prefix.t_tail > 0) && !decode_tails_ride_along(a)) {
         // (launched for the prefix only if it has a tail: workgroups that find nothing to do still cost their

@@ -159,7 +159,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
     }
     const int tid = threadIdx.x, lane = tid & 63, n = lane & 15, kb = lane >> 4;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: block ranges and base addresses stay scalar
-    const int split = blockIdx.x, ns = blockIdx.y;
+    const int split = blockIdx.x;
+    int ns = blockIdx.y;
+    if (a.seq_order) {   // a ragged batch: row y of the grid is a head of the (y / heads)-th longest sequence
+        const int rank = ns / a.n_kv_heads;
+        ns = a.seq_order[rank] * a.n_kv_heads + (ns - rank * a.n_kv_heads);
+    }
     const int n_slots = a.splits_prefix + a.splits_own + 2;
     const int seq = ns / a.n_kv_heads, head = ns - seq * a.n_kv_heads;
     const bool in_prefix = split < a.splits_prefix;

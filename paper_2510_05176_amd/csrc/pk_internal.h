@@ -203,6 +203,9 @@ struct DecodeArgs {
     float *part_w;                // [N][S][r][P]   softmax mass per V pattern (packed splits only)
     float *part_ml;               // [N][S][r][2]   running maximum (log2 domain) and sum
     float *out, *lse;
+    const int32_t *seq_order;     // optional, device [n_seq]: sequences from the longest packed part to the shortest (a
+                                  // ragged batch of at most kMaxOrdered sequences: the packed kernel takes its
+                                  // streams in this order, so that the long ones start first)
     const int32_t *seq_state;     // optional, device [n_seq][4]: t_quant, t_tail, tail_start, 0 of every sequence's own
                                   // cache; own.t_quant / own.t_tail are then upper bounds
 };
@@ -220,6 +223,7 @@ __device__ __forceinline__ void own_state(const DecodeArgs &a, int seq, int &t_q
         tail_start = min(max(v.z, 0), a.own.ring_len - 1);
     }
 }
+constexpr int kMaxOrdered = 1024;   // sequences a single workgroup ranks by counting
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t s);
 // Whether the workgroups of the fp16 tails are part of the packed kernel's launch (rows of its grid behind the
 // streams) instead of a kernel of their own.  They then run at that kernel's occupancy (two workgroups per CU),

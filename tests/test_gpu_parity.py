@@ -439,6 +439,8 @@ def test_decode_ragged_batch_parity(oracle, pk, hkv, hq, bits, G, P, R, lens):
     (2, 8, 2, 64, 32, 32, 64, 0, [[0, 70, 197, 1000, 517], [5, 0, 300, 64, 1], [1, 1, 1, 1, 1]]),
     (1, 4, 4, 32, 16, 0, 128, 0, [[640, 64, 1, 333], [0, 0, 700, 127]]),
     (2, 2, 2, 128, 200, 100, 128, 1, [[300, 1200, 40], [228, 1, 88]]),     # large table, group 128, min-max rule
+    # more sequences than one launch of the table kernel carries (64)
+    (1, 2, 2, 64, 8, 16, 64, 0, [[(37 * i) % 211 for i in range(70)], [(91 * i) % 67 for i in range(70)]]),
 ])
 def test_quantize_append_ragged_parity(oracle, pk, hkv, hq, bits, G, P, R, F, metric, rounds):
     """One append call for sequences at different fill (prompts of different lengths, then steps of different size,

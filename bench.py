@@ -17,7 +17,7 @@ the 256 MB Infinity Cache.
 Default workload: cfg3, the contract's long-context batched decode (32 layers x batch 16 x T = 32768, 8 KV / 32
 query heads, P = 128, 2-bit, group 64, 128 recent fp16 tokens; 68.7 GB of fp16 source).  With the default
 workload the line also carries `sweep` (the same stages on cfg2x32 - config 2's layer for all 32 layers of the
-model in one launch -, cfg5, the MLA latent-cache workload, cfg4 at its full schedule of 8192 generated tokens
+model in one launch, with 2- and with 4-bit codes -, cfg5, the MLA latent-cache workload, cfg4 at its full schedule of 8192 generated tokens
 with a decode after every append, cfg3r - config 3 with sequences of different lengths: ragged prefill and ragged
 decode -, and cfg2x32 with the min-max selection rule) and `measured_peaks` (streaming read / copy, fp32 FMA and
 fp16 MFMA loops on this GPU).
@@ -647,6 +647,15 @@ def main():
                                  "achieved": s["stage_rooflines"][st]["achieved"], "unit": s["stage_rooflines"][st]["unit"],
                                  "frac": s["stage_rooflines"][st]["frac"]} for st in s["stages"]}
             sweep[wname]["decode_attention"]["tokens/s"] = s["stages"]["decode_attention"]["tokens/s"]
+        import copy
+        args4 = copy.copy(args)
+        args4.bits = 4                                        # config 2 asks for both code widths
+        s = run_static("cfg2x32", args4, torch, pk, synth, 10, 2)
+        torch.cuda.empty_cache()
+        sweep["cfg2x32_4bit"] = {st: {"ms": s["stages"][st]["ms"], "bound": s["stage_rooflines"][st]["bound"],
+                                      "achieved": s["stage_rooflines"][st]["achieved"], "unit": s["stage_rooflines"][st]["unit"],
+                                      "frac": s["stage_rooflines"][st]["frac"]} for st in ("quantize_append", "decode_attention")}
+        sweep["cfg2x32_4bit"]["decode_attention"]["tokens/s"] = s["stages"]["decode_attention"]["tokens/s"]
         s = run_streaming(args, torch, pk, synth, 0, 8192, 8)
         torch.cuda.empty_cache()
         sweep["cfg4"] = {"schedule": "64 samples x 8192 generated tokens over a shared 4096-token prompt; one append and one "

@@ -7,6 +7,12 @@
 // (subtract, one division per group for s, one for 1/s, subtract, multiply, round
 // half to even, clamp); contraction into FMAs is switched off for this file so
 // that the sequence is exactly what is written.
+//
+// Kernels, in file order: assign_minmax_kernel (the min-max selection rule of Sec. 3.2 as a search of its own: it
+// writes the indices and the quantizers below then take them as given); quantize_k_kernel (groups of 128 tokens,
+// a workgroup per tile) and quantize_k_wave_kernel (groups of 32 / 64 tokens, a wave per group); quantize_v_kernel
+// (a wave per 16-token unit); tail_copy_kernel (the fp16 ring); seq_table_kernel (per-sequence launch parameters
+// of a ragged append).  Under the Euclidean rule the quantizers search on the matrix cores (pk_assign_mfma.h).
 #pragma clang fp contract(off)
 
 #include "pk_assign_mfma.h"

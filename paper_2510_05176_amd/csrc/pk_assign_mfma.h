@@ -179,13 +179,15 @@ __device__ __forceinline__ void assign_tile_mfma(const uint4 (&xb)[4], const Pat
 
 // Exact re-evaluation of one token by a whole wave: xrow_s = its 128 channels (fp16) in LDS.
 // Every lane returns the exact argmin (lowest index on ties) and its distance.
-__device__ __forceinline__ void exact_argmin_wave(const __half *xrow_s, const PatternTable &tb, const __half *Mg,
-                                                  int lane, int &best_i, float &best_d)
+__device__ __forceinline__ void exact_argmin_wave(const __half *xrow_s, const PatternTable &tb, int lane, int &best_i,
+                                                  float &best_d)
 {
     float bd = INFINITY;
     int bi = 0x7fffffff;
     for (int p = lane; p < tb.P; p += 64) {
-        const __half *m = Mg + (int64_t)p * kD;
+        // the pattern rows come from the LDS copy of the table (the same fp16 values): read from global memory they
+        // missed L2 often enough to add a fifth to the HBM traffic of a mining step on a large job
+        const __half *m = tb.lds_rows + p * kTabStride;
         float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
         for (int ch = 0; ch < kRowChunks; ++ch) {
             const uint4 mv = *reinterpret_cast<const uint4 *>(m + ch * 8);
@@ -220,7 +222,7 @@ __device__ __forceinline__ void exact_argmin_wave(const __half *xrow_s, const Pa
 
 // Re-evaluate the flagged tokens of a tile.  xrow_s: per-wave LDS scratch of kD halves.
 __device__ __forceinline__ void resolve_flagged(const uint4 (&xb)[4], bool flag, __half *xrow_s, const PatternTable &tb,
-                                                const __half *Mg, int lane, int &best_i, float &best_d)
+                                                int lane, int &best_i, float &best_d)
 {
     const int n = lane & 15, kb = lane >> 4;
     unsigned long long todo = __ballot(flag) & 0xffffull;   // one bit per column
@@ -235,7 +237,7 @@ __device__ __forceinline__ void resolve_flagged(const uint4 (&xb)[4], bool flag,
         __builtin_amdgcn_wave_barrier();
         int bi;
         float bd;
-        exact_argmin_wave(xrow_s, tb, Mg, lane, bi, bd);
+        exact_argmin_wave(xrow_s, tb, lane, bi, bd);
         if (n == col) {
             best_i = bi;
             best_d = bd;

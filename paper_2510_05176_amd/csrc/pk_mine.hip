@@ -110,7 +110,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NT == 1
         for (int j = 0; j < NT; ++j) {
             const int tl = (wave * NT + j) * 16 + n, tok = sub * ST + tl;
             float bd = fmaxf(bv[j], 0.f);
-            resolve_flagged(xb[j], flag[j], xrow_s + wave * kD, tb, Mg, lane, bi[j], bd);
+            resolve_flagged(xb[j], flag[j], xrow_s + wave * kD, tb, lane, bi[j], bd);
 #pragma unroll
             for (int k = 0; k < 4; ++k)   // a row past the chunk is stored as zeros, so it adds nothing to any sum
                 *reinterpret_cast<uint4 *>(xs + tl * kMineXs + 32 * k + 8 * kb) = tok < n_tok ? xb[j][k] : make_uint4(0u, 0u, 0u, 0u);

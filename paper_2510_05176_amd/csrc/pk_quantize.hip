@@ -330,7 +330,7 @@ __device__ __forceinline__ int assign_index(const PatternTable &tb, const __half
     float bv, x2, bd;
     bool flag;
     assign_tile_mfma(xb, tb, lane, bi, bv, x2, flag);
-    resolve_flagged(xb, flag, xrow, tb, Mg, lane, bi, bd);
+    resolve_flagged(xb, flag, xrow, tb, lane, bi, bd);
     return bi;
 }
 
@@ -431,7 +431,7 @@ __global__ __launch_bounds__(256) void quantize_k_kernel(QuantArgs a, int tiles_
             for (int j = 0; j < NT; ++j) {
                 float bd;
                 // scratch for the exact re-evaluation: the tile's own residual rows, which are written only below
-                resolve_flagged(xb[j], flag[j], reinterpret_cast<__half *>(sh.rt + (wave * NT + j) * 16 * kRStride), tb, Mg, lane,
+                resolve_flagged(xb[j], flag[j], reinterpret_cast<__half *>(sh.rt + (wave * NT + j) * 16 * kRStride), tb, lane,
                                 bi[j], bd);
             }
         }
@@ -580,7 +580,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NTA > 2 ? 2
 #pragma unroll
                 for (int j = 0; j < NTA; ++j) {
                     float bd;
-                    resolve_flagged(xb[j0 + j], flag[j], reinterpret_cast<__half *>(rt), tb, Mg, lane, bj[j], bd);
+                    resolve_flagged(xb[j0 + j], flag[j], reinterpret_cast<__half *>(rt), tb, lane, bj[j], bd);
                     bi[j0 + j] = bj[j];
                 }
             }
@@ -737,7 +737,7 @@ __global__ __launch_bounds__(256) void quantize_v_kernel(QuantArgs a, int tiles_
 #pragma unroll
             for (int j = 0; j < NT; ++j) {
                 float bd;
-                resolve_flagged(xbs[j], flag[j], reinterpret_cast<__half *>(wsc + kWsRow), tb, Mg, lane, bis[j], bd);
+                resolve_flagged(xbs[j], flag[j], reinterpret_cast<__half *>(wsc + kWsRow), tb, lane, bis[j], bd);
             }
         }
 #pragma unroll

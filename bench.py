@@ -128,11 +128,17 @@ def run_static(name, args, torch, pk, synth, steps, warmup, metric=None, cpu_bas
     t_gen = time.time() - t_gen
     progress(f"{name}: inputs resident ({t_gen:.1f} s)")
 
+    PT = getattr(args, "page_tokens", 0)
+    assert PT == 0 or cap % PT == 0, f"the packed capacity {cap} is not a multiple of --page-tokens {PT}"
     cfg = pk.Config(n_seq=n_seq, n_kv_heads=Hkv, n_q_heads=Hq, head_dim=d, n_patterns=P,
                     seqs_per_set=(B if L > 1 else 0), bits=bits, group=G, recent=R, flush=F, t_capacity=cap,
-                    metric=metric)
+                    metric=metric, page_tokens=PT, n_pages=(n_seq * (cap // PT) if PT else 0))
     n_sets = cfg.n_sets
     cache = pk.Cache(cfg)
+    if PT:   # a paged cache: the pool's pages in a seeded random order
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(args.seed)
+        cache.page_table.copy_(torch.randperm(cfg.n_pages, generator=gen, device=dev).to(torch.int32).view(n_seq, cap // PT))
     Mk = torch.empty((n_sets, P, d), dtype=torch.float16, device=dev)
     Mv = torch.empty_like(Mk)
     out = torch.empty((n_seq, Hq, d), dtype=torch.float32, device=dev)
@@ -238,7 +244,8 @@ def run_static(name, args, torch, pk, synth, steps, warmup, metric=None, cpu_bas
         "ms_per_step": round(ms_per_step, 4),
         "config": {"workload": name, "layers": L, "batch": B, "n_kv_heads": Hkv, "n_q_heads": Hq, "T": T,
                    "head_dim": d, "n_patterns": P, "lloyd_iters": iters, "bits": bits, "group": G, "recent": R,
-                   "flush": F, "metric": "L2" if metric == pk.METRIC_L2 else "MINMAX", "seed": args.seed},
+                   "flush": F, "metric": "L2" if metric == pk.METRIC_L2 else "MINMAX", "seed": args.seed,
+                   **({"page_tokens": PT, "page_table": "scrambled"} if PT else {})},
         "stages": stage_out,
         "stage_rooflines": rl,
         "input_generation_s": round(t_gen, 2),
@@ -572,6 +579,9 @@ def main():
     ap.add_argument("--bits", type=int, default=2, choices=[2, 4])
     ap.add_argument("--metric", default="l2", choices=["l2", "minmax"],
                     help="pattern selection rule of quantize-append: l2 (matrix cores) or minmax (d_mm of Sec. 3.2, vector ALUs)")
+    ap.add_argument("--page-tokens", type=int, default=0,
+                    help="static workloads: run on a paged cache with pages of this many tokens (a power of two >= 128 "
+                         "that divides the packed capacity) and a scrambled page table")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true", help="default workload only: leave out the other configs")
     ap.add_argument("--no-peaks", action="store_true")

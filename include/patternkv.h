@@ -70,6 +70,18 @@
  *                                             vectors, kept in full precision;
  *                                             logical tail token i is in slot
  *                                             (tail_start + i) % (recent+flush)
+ * Paged cache (page_tokens > 0; the paper fixes no memory layout, serving engines allocate KV memory in pages)
+ *   The packed arrays hold n_pages pages instead of N contiguous streams.  A page holds page_tokens consecutive
+ *   tokens of ALL KV heads of one sequence, head after head; inside a (page, head) part every array is laid out
+ *   exactly as a contiguous stream of page_tokens tokens above (so a page is [n_kv_heads][page_tokens] tokens and
+ *   token t of stream (seq, head) lives at packed position
+ *       (page_table[seq][t / page_tokens] * n_kv_heads + head) * page_tokens + t % page_tokens
+ *   in units of tokens of the array concerned: k_codes [pos][d/32][b], k_scale [pos/G][d], k_idx [pos], v_codes in
+ *   64-token blocks from pos, v_scale [pos/16][d/Gc][16], v_idx [pos]).  page_table is DEVICE int32
+ *   [n_seq][t_capacity / page_tokens]; the kernels clamp every entry they read to [0, n_pages), so no table
+ *   content can lead outside the arrays; entries of pages a sequence does not yet use are never read; giving two
+ *   logical pages the same physical page is the caller's error (the later write wins).  The fp16 tails are not
+ *   paged.  Quantization groups, 64-token blocks and flushes never straddle a page.
  *   Stored parameters: z = min of the residual group rounded to fp16 towards
  *   -inf; s = (max - z)/(2^b - 1) rounded to fp16 towards +inf; code =
  *   clamp(rint((r - z) * (1/s)), 0, 2^b - 1) in binary32, ties to even; a group
@@ -85,7 +97,7 @@
 extern "C" {
 #endif
 
-#define PK_ABI_VERSION 4u
+#define PK_ABI_VERSION 5u
 
 typedef enum {
     PK_OK = 0,
@@ -129,6 +141,10 @@ typedef struct {
                              vector itself is quantized and its index is PK_NO_PATTERN.  The caller passes
                              rho_*(d, alpha), the root in (0,1) of 1 - rho^2 = 2 z_{1-alpha}/sqrt(5d) *
                              sqrt(1 + rho^4).  Needs n_patterns <= 255.  K is never thresholded.        */
+    int32_t page_tokens;  /* 0: every stream's packed part is contiguous (the layout above).  Otherwise the
+                             packed arrays are a pool of pages, see "Paged cache" below: tokens per page, a
+                             power of two >= 128 that divides t_capacity                              */
+    int32_t n_pages;      /* pages in the pool (page_tokens > 0), >= 1                               */
 } pk_config;
 
 #define PK_NO_PATTERN 255 /* v_idx of a token quantized without a pattern (only when v_rho > 0)    */
@@ -147,6 +163,7 @@ typedef struct {
     void *k_codes, *k_scale, *k_zero, *k_idx;
     void *v_codes, *v_scale, *v_zero, *v_idx;
     void *tail_k, *tail_v;
+    const int32_t *page_table; /* device; required when page_tokens > 0, ignored otherwise          */
 } pk_cache;
 
 /* Host-side bookkeeping of a cache (all streams have the same lengths).  Start

@@ -56,6 +56,14 @@ pk_status check_config(const pk_config *c)
     if (c->flush % c->group != 0 || c->flush % 64 != 0) return PK_ERR_SHAPE;
     if (c->t_capacity % c->flush != 0) return PK_ERR_SHAPE;
     if (c->t_capacity > (1 << 25)) return PK_ERR_UNSUPPORTED;   // byte offsets inside a stream stay below 2^32
+    if (c->page_tokens < 0 || c->n_pages < 0) return PK_ERR_INVALID_ARG;
+    if (c->page_tokens > 0) {
+        // a power of two of at least 128, so that no quantization group, 64-token block or tile straddles a page
+        if (c->page_tokens < 128 || (c->page_tokens & (c->page_tokens - 1)) != 0) return PK_ERR_UNSUPPORTED;
+        if (c->t_capacity % c->page_tokens != 0) return PK_ERR_SHAPE;
+        if (c->n_pages < 1) return PK_ERR_INVALID_ARG;
+        if ((int64_t)c->n_pages * c->n_kv_heads * c->page_tokens > ((int64_t)1 << 36)) return PK_ERR_UNSUPPORTED;
+    }
     return PK_OK;
 }
 
@@ -81,9 +89,31 @@ pk_status check_cache(const pk_cache *k)
     return PK_OK;
 }
 
+// a paged configuration needs its page table
+pk_status check_paging(const pk_config *c, const pk_cache *k)
+{
+    if (c->page_tokens == 0) return PK_OK;
+    if (!k->page_table) return PK_ERR_INVALID_ARG;
+    return aligned16(k->page_table) ? PK_OK : PK_ERR_ALIGNMENT;
+}
+
+PackedMap make_map(const pk_config *c, const pk_cache *k)
+{
+    PackedMap m;
+    m.page_table = c->page_tokens > 0 ? k->page_table : nullptr;
+    m.page_shift = 0;
+    while (c->page_tokens > 0 && (1 << m.page_shift) < c->page_tokens) ++m.page_shift;
+    m.pages_per_seq = c->page_tokens > 0 ? c->t_capacity / c->page_tokens : 0;
+    m.n_pages = c->n_pages;
+    m.n_kv_heads = c->n_kv_heads;
+    m.t_capacity = c->t_capacity;
+    return m;
+}
+
 CacheView make_view(const pk_config *c, const pk_cache *k, const pk_state *s)
 {
     CacheView v;
+    v.map = make_map(c, k);
     v.k_codes = static_cast<const uint32_t *>(k->k_codes);
     v.k_scale = static_cast<const __half *>(k->k_scale);
     v.k_zero = static_cast<const __half *>(k->k_zero);
@@ -158,15 +188,18 @@ pk_status pk_cache_layout(const pk_config *cfg, pk_layout *out)
     pk_status st = check_config(cfg);
     if (st != PK_OK) return st;
     if (!out) return PK_ERR_INVALID_ARG;
-    const uint64_t N = (uint64_t)cfg->n_seq * cfg->n_kv_heads, cap = cfg->t_capacity, d = kD, b = cfg->bits;
+    const uint64_t N = (uint64_t)cfg->n_seq * cfg->n_kv_heads, d = kD, b = cfg->bits;
     const uint64_t G = cfg->group, Gc = G < d ? G : d;
+    // packed token slots: N streams of t_capacity tokens, or a pool of pages of [n_kv_heads][page_tokens] tokens
+    const uint64_t slots = cfg->page_tokens > 0 ? (uint64_t)cfg->n_pages * cfg->n_kv_heads * cfg->page_tokens
+                                                : N * (uint64_t)cfg->t_capacity;
     out->align = 16;
-    out->k_codes = N * cap * d * b / 8;
-    out->k_scale = out->k_zero = N * (cap / G) * d * 2;
-    out->k_idx = N * cap;
-    out->v_codes = N * cap * d * b / 8;
-    out->v_scale = out->v_zero = N * cap * (d / Gc) * 2;
-    out->v_idx = N * cap;
+    out->k_codes = slots * d * b / 8;
+    out->k_scale = out->k_zero = (slots / G) * d * 2;
+    out->k_idx = slots;
+    out->v_codes = slots * d * b / 8;
+    out->v_scale = out->v_zero = slots * (d / Gc) * 2;
+    out->v_idx = slots;
     out->tail_k = out->tail_v = N * (uint64_t)(cfg->recent + cfg->flush) * d * 2;
     const uint64_t parts[10] = {out->k_codes, out->k_scale, out->k_zero, out->k_idx, out->v_codes,
                                 out->v_scale, out->v_zero,  out->v_idx,  out->tail_k, out->tail_v};
@@ -276,7 +309,7 @@ pk_status launch_append(const pk_config *cfg, const pk_cache *cache, const Appen
         a.n_streams = N;
         a.nq = (int32_t)p.nq;
         a.t0 = p.t0;
-        a.t_capacity = cfg->t_capacity;
+        a.map = make_map(cfg, cache);
         a.seq_table = p.seq_table;
         // K
         a.src.ring = static_cast<const __half *>(cache->tail_k);
@@ -331,6 +364,7 @@ pk_status pk_quantize_append(const pk_config *cfg, const pk_cache *cache, pk_sta
     pk_status st = check_config(cfg);
     if (st != PK_OK) return st;
     if ((st = check_cache(cache)) != PK_OK) return st;
+    if ((st = check_paging(cfg, cache)) != PK_OK) return st;
     if ((st = check_state(cfg, state)) != PK_OK) return st;
     if (n_new < 0) return PK_ERR_INVALID_ARG;
     if (n_new == 0) return PK_OK;
@@ -371,6 +405,7 @@ pk_status pk_quantize_append_ragged(const pk_config *cfg, const pk_cache *cache,
     pk_status st = check_config(cfg);
     if (st != PK_OK) return st;
     if ((st = check_cache(cache)) != PK_OK) return st;
+    if ((st = check_paging(cfg, cache)) != PK_OK) return st;
     if (!states || !n_new) return PK_ERR_INVALID_ARG;
     const int S = cfg->n_seq;
     int64_t max_new = 0;
@@ -451,6 +486,7 @@ static pk_status decode_impl(const pk_config *cfg, const pk_cache *cache, const 
     pk_status st = check_config(cfg);
     if (st != PK_OK) return st;
     if ((st = check_cache(cache)) != PK_OK) return st;
+    if ((st = check_paging(cfg, cache)) != PK_OK) return st;
     if ((st = check_state(cfg, state)) != PK_OK) return st;
     if (!q || !patterns_k || !patterns_v || !out) return PK_ERR_INVALID_ARG;
     if ((cfg->n_q_heads / cfg->n_kv_heads) * (kD / (cfg->group < kD ? cfg->group : kD)) > 16) return PK_ERR_UNSUPPORTED;
@@ -462,6 +498,7 @@ static pk_status decode_impl(const pk_config *cfg, const pk_cache *cache, const 
         if (!prefix_cfg || !prefix || !prefix_state) return PK_ERR_INVALID_ARG;
         if ((st = check_config(prefix_cfg)) != PK_OK) return st;
         if ((st = check_cache(prefix)) != PK_OK) return st;
+        if ((st = check_paging(prefix_cfg, prefix)) != PK_OK) return st;
         if ((st = check_state(prefix_cfg, prefix_state)) != PK_OK) return st;
         if (prefix_cfg->n_seq != 1 || prefix_cfg->n_kv_heads != cfg->n_kv_heads ||
             prefix_cfg->n_q_heads != cfg->n_q_heads || prefix_cfg->n_patterns != cfg->n_patterns ||
@@ -568,6 +605,7 @@ pk_status pk_dequantize(const pk_config *cfg, const pk_cache *cache, const pk_st
     pk_status st = check_config(cfg);
     if (st != PK_OK) return st;
     if ((st = check_cache(cache)) != PK_OK) return st;
+    if ((st = check_paging(cfg, cache)) != PK_OK) return st;
     if ((st = check_state(cfg, state)) != PK_OK) return st;
     if (t0 < 0 || t1 < t0 || t1 > state->t_quant) return PK_ERR_SHAPE;
     if ((k_out && !patterns_k) || (v_out && !patterns_v)) return PK_ERR_INVALID_ARG;

@@ -128,7 +128,7 @@ __device__ __forceinline__ uint32_t product_error(uint32_t a, uint32_t b, uint32
     return r;
 }
 
-template <int BITS, bool G32, bool HALF>
+template <int BITS, bool G32, bool HALF, bool PAGED>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void decode_packed_kernel(DecodeArgs a)
 {
     static_assert(!(HALF && G32), "the split of a unit's tokens over column halves assumes one K group per block");
@@ -189,7 +189,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
         }
         return;
     }
-    const int cap = cv.t_capacity;
 
     const int R = a.n_q_heads / a.n_kv_heads, G = a.G, P = a.P;
     const int lgG = 31 - __clz(G);   // G is a power of two
@@ -311,16 +310,35 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
     for (int t = 0; t < 8; ++t) O[t] = floatx4{0.f, 0.f, 0.f, 0.f};
     GroupOperand ga, gb;   // gb: second K group of a block, only when G == 32
 
-    // per-stream base pointers (wave-uniform); everything inside a stream is addressed with 32-bit byte offsets
-    // (the host refuses capacities for which those would not fit)
-    const char *kcodes = reinterpret_cast<const char *>(cv.k_codes + (int64_t)cstream * cap * 4 * BITS);
-    const char *vcodes = reinterpret_cast<const char *>(cv.v_codes) + (int64_t)cstream * cap * (kD * BITS / 8);
-    const char *kscale = reinterpret_cast<const char *>(cv.k_scale + (int64_t)cstream * (cap >> lgG) * kD);
-    const char *kzero = reinterpret_cast<const char *>(cv.k_zero + (int64_t)cstream * (cap >> lgG) * kD);
-    const char *vscale = reinterpret_cast<const char *>(cv.v_scale + (int64_t)cstream * cap * NG);
-    const char *vzero = reinterpret_cast<const char *>(cv.v_zero + (int64_t)cstream * cap * NG);
-    const char *kidx = reinterpret_cast<const char *>(cv.k_idx + (int64_t)cstream * cap);
-    const char *vidx = reinterpret_cast<const char *>(cv.v_idx + (int64_t)cstream * cap);
+    // Base pointers (wave-uniform) such that base + offset(logical token) is the token's place: for contiguous
+    // streams the stream's start, fixed; for a paged cache the start of the page part that holds the block,
+    // minus the block's logical position, set anew for every block (a 64-token block and a K group never
+    // straddle a page).  The K-side set runs one block ahead of the V-side set (K inputs are prefetched).
+    // Offsets from a base fit 32 bits (the host refuses capacities for which they would not).
+    // (PAGED is a template parameter: the re-basing branches cost the contiguous case 1 % when decided at run time)
+    constexpr bool paged = PAGED;
+    const char *kcodes, *kscale, *kzero, *kidx, *vcodes, *vscale, *vzero, *vidx;
+    // (the page of a block is looked up one block ahead of its first use, so that the scalar load of the table entry
+    // is not on the path of the block's loads: with the lookup in place a scrambled cache of 128-token pages read
+    // 33 % slower than contiguous streams)
+    auto set_k_bases = [&](int tb, int page) {
+        const int64_t delta = cv.map.pos_in(page, cstream, tb) - tb;   // a multiple of the page size (or stream * capacity)
+        kcodes = reinterpret_cast<const char *>(cv.k_codes + delta * 4 * BITS);
+        kscale = reinterpret_cast<const char *>(cv.k_scale + (delta >> lgG) * kD);
+        kzero = reinterpret_cast<const char *>(cv.k_zero + (delta >> lgG) * kD);
+        kidx = reinterpret_cast<const char *>(cv.k_idx + delta);
+    };
+    auto set_v_bases = [&](int tb, int page) {
+        const int64_t delta = cv.map.pos_in(page, cstream, tb) - tb;
+        vcodes = reinterpret_cast<const char *>(cv.v_codes) + delta * (kD * BITS / 8);
+        vscale = reinterpret_cast<const char *>(cv.v_scale + delta * NG);
+        vzero = reinterpret_cast<const char *>(cv.v_zero + delta * NG);
+        vidx = reinterpret_cast<const char *>(cv.v_idx + delta);
+    };
+    int pg_cur = paged ? cv.map.page_of(cstream, t_begin + (b0 << 6)) : 0, pg_next = pg_cur;   // pages of this wave's current / next block
+    set_k_bases(t_begin + (b0 << 6), pg_cur);
+    set_v_bases(t_begin + (b0 << 6), pg_cur);
+    int pg_v = pg_cur;   // page the V-side bases stand for
 
     // parameters of one K group: raw loads, then the B operand
     struct GroupRaw {
@@ -447,6 +465,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
         const int tb = t_begin + (b << 6);
 
         // ---- V-side loads of the block (used after the scores)
+        if (paged) {   // bases change only where the walk enters another page
+            if (pg_cur != pg_v) {
+                set_v_bases(tb, pg_cur);
+                pg_v = pg_cur;
+            }
+            if (b + 1 < b1 && ((tb + 64) & ((1 << cv.map.page_shift) - 1)) == 0) pg_next = cv.map.page_of(cstream, tb + 64);
+        }
         const int unit = (tb >> 4) + kb;   // 16-token unit of this lane group
         uint32_t vidw[NTK / 4];
         if (HALF) {
@@ -552,6 +577,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
         const int tbn = tb + 64;
         const bool new_group = more && (G32 || (tbn >> lgG) != (tb >> lgG));
         GroupRaw gr;
+        if (paged && more && pg_next != pg_cur) {
+            set_k_bases(tbn, pg_next);
+            pg_cur = pg_next;
+        }
         if (more) load_k(tbn);
         if (new_group) load_group_raw(tbn >> lgG, gr);
 
@@ -723,17 +752,25 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
 
 }  // namespace
 
-template <int BITS, bool G32, bool HALF>
-static hipError_t launch_one(const DecodeArgs &a, dim3 grid, size_t lds, hipStream_t s)
+template <int BITS, bool G32, bool HALF, bool PAGED>
+static hipError_t launch_variant(const DecodeArgs &a, dim3 grid, size_t lds, hipStream_t s)
 {
     // the most any launch of this instantiation needs: 256 patterns, 8 heads per KV head, 256 mass slots per head
     static LdsOptIn opt_in;
     constexpr size_t kMaxLds = (size_t)256 * 16 * 4 + (size_t)4 * 8 * 256 * 8;
-    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(&decode_packed_kernel<BITS, G32, HALF>), opt_in, kMaxLds);
+    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(&decode_packed_kernel<BITS, G32, HALF, PAGED>), opt_in, kMaxLds);
     if (e != hipSuccess) return e;
     if (lds > kMaxLds) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((decode_packed_kernel<BITS, G32, HALF>), grid, dim3(256), lds, s, a);
+    hipLaunchKernelGGL((decode_packed_kernel<BITS, G32, HALF, PAGED>), grid, dim3(256), lds, s, a);
     return hipGetLastError();
+}
+
+// a paged cache of its own or a paged shared prefix: the variant that re-bases its pointers block by block
+template <int BITS, bool G32, bool HALF>
+static hipError_t launch_one(const DecodeArgs &a, dim3 grid, size_t lds, hipStream_t s)
+{
+    return a.own.map.page_table || a.prefix.map.page_table ? launch_variant<BITS, G32, HALF, true>(a, grid, lds, s)
+                                                           : launch_variant<BITS, G32, HALF, false>(a, grid, lds, s);
 }
 
 hipError_t launch_decode_packed(const DecodeArgs &a, hipStream_t s)

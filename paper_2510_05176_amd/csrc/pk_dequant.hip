@@ -15,25 +15,25 @@ __global__ __launch_bounds__(128) void dequant_kernel(DequantArgs a)
     const int t = a.t0 + blockIdx.x, n = blockIdx.y, c = threadIdx.x;
     const int set = a.sets.set_of(n);
     const int G = a.G, Gc = G < kD ? G : kD, ng = kD / Gc;
-    const int64_t tok = (int64_t)n * a.c.t_capacity + t;
+    const int64_t tok = a.c.map.pos(n, t);   // where token t of the stream is stored
     const int64_t orow = ((int64_t)n * (a.t1 - a.t0) + (t - a.t0)) * kD + c;
     if (a.k_out) {
         int code = 0;
 #pragma unroll
         for (int j = 0; j < BITS; ++j)
             code |= (int)((a.c.k_codes[(tok * 4 + (c >> 5)) * BITS + j] >> (c & 31)) & 1u) << j;
-        const int64_t prow = ((int64_t)n * (a.c.t_capacity / G) + t / G) * kD + c;
+        const int64_t prow = (tok / G) * kD + c;
         const float s = h2f(a.c.k_scale[prow]), z = h2f(a.c.k_zero[prow]);
         const float res = s * (float)code + z;
         a.k_out[orow] = h2f(a.patterns_k[((int64_t)set * a.P + a.c.k_idx[tok]) * kD + c]) + res;
     }
     if (a.v_out) {
-        const uint32_t *vbase = reinterpret_cast<const uint32_t *>(a.c.v_codes) + (int64_t)n * a.c.t_capacity * (kD * BITS / 32);
-        const int64_t word = (((int64_t)(t >> 4) * 16 + (c & 15)) * (kD / 16) + (c >> 4)) * (BITS / 2);
+        const uint32_t *vbase = reinterpret_cast<const uint32_t *>(a.c.v_codes);
+        const int64_t word = (((tok >> 4) * 16 + (c & 15)) * (kD / 16) + (c >> 4)) * (BITS / 2);
         int code = 0;
 #pragma unroll
         for (int j = 0; j < BITS; ++j) code |= (int)((vbase[word + j / 2] >> (16 * (j % 2) + (t & 15))) & 1u) << j;
-        const int64_t prow = ((int64_t)n * a.c.t_capacity * ng) + ((int64_t)(t >> 4) * ng + c / Gc) * 16 + (t & 15);
+        const int64_t prow = ((tok >> 4) * ng + c / Gc) * 16 + (t & 15);
         const float s = h2f(a.c.v_scale[prow]), z = h2f(a.c.v_zero[prow]);
         const float res = s * (float)code + z;
         const int vi = a.c.v_idx[tok];

@@ -36,6 +36,32 @@ struct RowSource {
     }
 };
 
+// Where token `tok` of stream `stream` lives in the packed arrays, in tokens: stream * capacity + tok for contiguous
+// streams; through the sequence's page table for a paged cache (a page = [n_kv_heads][page_tokens] tokens).  A table
+// entry is clamped to the pool, so whatever the table holds the position stays inside the arrays.  Quantization
+// groups, 64-token blocks and tiles never straddle a page (page_tokens is a power of two >= 128), so a kernel asks
+// for the position of a tile's first token and adds offsets inside the tile.
+struct PackedMap {
+    const int32_t *page_table;   // device [n_seq][pages_per_seq], or null
+    int32_t page_shift;          // log2(page_tokens)
+    int32_t pages_per_seq, n_pages, n_kv_heads, t_capacity;
+    // physical page of the stream's token (clamped to the pool); 0 for contiguous streams
+    __device__ __forceinline__ int page_of(int stream, int tok) const
+    {
+        if (!page_table) return 0;
+        const int page = page_table[(int64_t)(stream / n_kv_heads) * pages_per_seq + min(tok >> page_shift, pages_per_seq - 1)];
+        return min(max(page, 0), n_pages - 1);
+    }
+    // position of the token given its page (as page_of returns it)
+    __device__ __forceinline__ int64_t pos_in(int page, int stream, int tok) const
+    {
+        if (!page_table) return (int64_t)stream * t_capacity + tok;
+        const int head = stream % n_kv_heads;
+        return (((int64_t)page * n_kv_heads + head) << page_shift) + (tok & ((1 << page_shift) - 1));
+    }
+    __device__ __forceinline__ int64_t pos(int stream, int tok) const { return pos_in(page_of(stream, tok), stream, tok); }
+};
+
 struct SetMap {
     int32_t n_kv_heads;
     int32_t seqs_per_set;
@@ -107,7 +133,7 @@ struct QuantArgs {
     int32_t n_streams;
     int32_t nq;               // vectors to quantize per stream (multiple of G)
     int32_t t0;               // first packed position to write (= t_quant)
-    int32_t t_capacity;
+    PackedMap map;            // where the packed tokens of a stream live
     uint32_t *codes_k;        // K side
     uint8_t *codes_v;         // V side
     __half *scale, *zero;
@@ -186,6 +212,7 @@ struct CacheView {
     const uint8_t *v_idx;
     const __half *tail_k, *tail_v;
     int32_t t_capacity, t_quant, t_tail, tail_start, ring_len;
+    PackedMap map;
 };
 
 struct DecodeArgs {

@@ -163,7 +163,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void a
             }
         }
         swait2(a0, a1);   // nothing may be in flight into registers that the next tile reuses
-        a.idx[(int64_t)ns * a.t_capacity + a.t0 + tile * 64 + lane] = (uint8_t)best_p;
+        a.idx[a.map.pos(ns, a.t0 + tile * 64) + lane] = (uint8_t)best_p;
     }
 }
 
@@ -418,11 +418,12 @@ __global__ __launch_bounds__(256) void quantize_k_kernel(QuantArgs a, int tiles_
     const int q = tid % LPC, cc = tid / LPC;
     for (int tile = tile0; tile < tile1; ++tile) {
         const int64_t tq0 = (int64_t)a.t0 + (int64_t)tile * TT;
+        const int64_t pq0 = a.map.pos(ns, (int)tq0);   // where the tile's first token is stored
         float r[NT][32];
         int bi[NT];
         if (a.idx_given) {   // searched beforehand (min-max metric)
 #pragma unroll
-            for (int j = 0; j < NT; ++j) bi[j] = a.idx[(int64_t)ns * a.t_capacity + tq0 + (wave * NT + j) * 16 + n];
+            for (int j = 0; j < NT; ++j) bi[j] = a.idx[pq0 + (wave * NT + j) * 16 + n];
         } else {   // the wave's NT 16-token tiles in one pass over the pattern table
             float bv[NT], x2[NT];
             bool flag[NT];
@@ -486,7 +487,7 @@ __global__ __launch_bounds__(256) void quantize_k_kernel(QuantArgs a, int tiles_
         if (wave == 3 && lane < NGRP * 32) {
             const int grp = lane >> 5, arr = (lane >> 4) & 1, piece = lane & 15;
             const uint4 v = *reinterpret_cast<const uint4 *>(sh.pz + (arr * NGRP + grp) * kD + piece * 8);
-            __half *dstp = (arr ? a.scale : a.zero) + ((int64_t)ns * (a.t_capacity / G) + tq0 / G + grp) * kD + piece * 8;
+            __half *dstp = (arr ? a.scale : a.zero) + (pq0 / G + grp) * kD + piece * 8;
             *reinterpret_cast<uint4 *>(dstp) = v;
         }
 
@@ -501,7 +502,7 @@ __global__ __launch_bounds__(256) void quantize_k_kernel(QuantArgs a, int tiles_
             k_codes_to_staging<BITS>(r[j], sh.pz + grp * kD, sh.pinv + grp * kD, stg);
             if (kb == 0) stg[16 * 16 * BITS + n] = (uint8_t)bi[j];
             wave_lds_sync();
-            k_store_staging<BITS>(a, (int64_t)ns * a.t_capacity + tq0 + tl0, stg);
+            k_store_staging<BITS>(a, pq0 + tl0, stg);
         }
         // the residual tile is rewritten only after the next barrier-separated scan has been passed by
         // every wave: the scan of this tile ended before the barrier above
@@ -561,7 +562,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NTA > 2 ? 2
     const PatternTable tb = make_table(sh, Mg, a.P);
 
     for (; g < g_end; g += 4) {
-        const int64_t tq0 = (int64_t)a.t0 + (int64_t)g * G;   // packed position of the group's first token
+        const int64_t tq0 = (int64_t)a.t0 + (int64_t)g * G;   // logical position of the group's first token
+        const int64_t pq0 = a.map.pos(ns, (int)tq0);            // where it is stored
         // ---- pass A: indices; running minimum / maximum per channel.  The residuals pass through the LDS tile a
         //      quarter (32 channels = one operand step) at a time; lane <-> (channel lane%32, token half lane/32)
         float mn[4] = {INFINITY, INFINITY, INFINITY, INFINITY}, mx[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
@@ -569,7 +571,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NTA > 2 ? 2
         const int sc = lane & 31, sth = lane >> 5;
         if (a.idx_given) {   // searched beforehand (min-max metric)
 #pragma unroll
-            for (int j = 0; j < NTG; ++j) bi[j] = a.idx[(int64_t)ns * a.t_capacity + tq0 + j * 16 + n];
+            for (int j = 0; j < NTG; ++j) bi[j] = a.idx[pq0 + j * 16 + n];
         } else if (NTA > 1) {   // NTA tiles of the group per pass over the pattern table
 #pragma unroll
             for (int j0 = 0; j0 < NTG; j0 += NTA) {
@@ -626,7 +628,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NTA > 2 ? 2
         if (lane < 32) {   // stored parameters: 16-byte pieces, zero points then scales
             const int arr = lane >> 4, piece = lane & 15;
             const uint4 v = *reinterpret_cast<const uint4 *>(pz + arr * kD + piece * 8);
-            __half *dstp = (arr ? a.scale : a.zero) + ((int64_t)ns * (a.t_capacity / G) + tq0 / G) * kD + piece * 8;
+            __half *dstp = (arr ? a.scale : a.zero) + (pq0 / G) * kD + piece * 8;
             *reinterpret_cast<uint4 *>(dstp) = v;
         }
         // ---- pass B: residuals again, codes, planes; the tile's registers then take the next group
@@ -639,7 +641,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NTA > 2 ? 2
             k_codes_to_staging<BITS>(r, pz, pinv, stg);
             if (kb == 0) stg[16 * 16 * BITS + n] = (uint8_t)bi[j];
             wave_lds_sync();
-            k_store_staging<BITS>(a, (int64_t)ns * a.t_capacity + tq0 + j * 16, stg);
+            k_store_staging<BITS>(a, pq0 + j * 16, stg);
             wave_lds_sync();   // the staging area is rewritten by the next tile
         }
     }
@@ -729,7 +731,7 @@ __global__ __launch_bounds__(256) void quantize_v_kernel(QuantArgs a, int tiles_
         if (a.idx_given) {   // searched beforehand (min-max metric); a block past the range repeats the last one
 #pragma unroll
             for (int j = 0; j < NT; ++j)
-                bis[j] = a.idx[(int64_t)ns * a.t_capacity + a.t0 + (int64_t)min(tile_base + j, tile1 - 1) * TT + wave * 16 + n];
+                bis[j] = a.idx[a.map.pos(ns, a.t0 + min(tile_base + j, tile1 - 1) * TT) + wave * 16 + n];
         } else {
             float bv[NT], x2[NT];
             bool flag[NT];
@@ -745,7 +747,6 @@ __global__ __launch_bounds__(256) void quantize_v_kernel(QuantArgs a, int tiles_
         const int tile = tile_base + j;
         if (tile >= tile1) break;
         uint4 (&xb)[4] = xbs[j];
-        const int64_t t_first = (int64_t)a.t0 + (int64_t)tile * TT + wave * 16;   // first token of the unit
         float r[32];
         int bi = bis[j];
         store_pending();
@@ -857,7 +858,7 @@ __global__ __launch_bounds__(256) void quantize_v_kernel(QuantArgs a, int tiles_
             }
         }
         wave_lds_sync();
-        pend_tok0 = (int64_t)ns * a.t_capacity + t_first;   // stored at the start of the next unit
+        pend_tok0 = a.map.pos(ns, a.t0 + tile * TT) + wave * 16;   // stored at the start of the next unit
       }
     }
     store_pending();

@@ -30,7 +30,8 @@ OP_MINE, OP_APPEND, OP_DECODE = 0, 1, 2
 class _Config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "n_seq", "n_kv_heads", "n_q_heads", "head_dim", "n_patterns", "seqs_per_set",
-        "bits", "group", "recent", "flush", "t_capacity", "metric")] + [("v_rho", C.c_float)]
+        "bits", "group", "recent", "flush", "t_capacity", "metric")] + [("v_rho", C.c_float), ("page_tokens", C.c_int32),
+                                                                          ("n_pages", C.c_int32)]
 
 
 class _Layout(C.Structure):
@@ -42,14 +43,14 @@ class _Layout(C.Structure):
 class _Cache(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in (
         "k_codes", "k_scale", "k_zero", "k_idx", "v_codes", "v_scale", "v_zero", "v_idx",
-        "tail_k", "tail_v")]
+        "tail_k", "tail_v", "page_table")]
 
 
 class _State(C.Structure):
     _fields_ = [("t_quant", C.c_int32), ("t_tail", C.c_int32), ("tail_start", C.c_int32)]
 
 
-ABI_VERSION = 4          # PK_ABI_VERSION of include/patternkv.h this binding's structs are laid out for
+ABI_VERSION = 5          # PK_ABI_VERSION of include/patternkv.h this binding's structs are laid out for
 
 _lib.pk_abi_version.restype = C.c_uint32
 if int(_lib.pk_abi_version()) != ABI_VERSION:
@@ -131,6 +132,8 @@ class Config:
     t_capacity: int = 0
     metric: int = METRIC_L2
     v_rho: float = 0.0      # adaptive threshold on V (0 = off); see include/patternkv.h
+    page_tokens: int = 0    # > 0: the packed arrays are a pool of n_pages pages of this many tokens (all KV heads)
+    n_pages: int = 0
 
     def c(self) -> _Config:
         return _Config(**asdict(self))
@@ -190,9 +193,17 @@ class Cache:
         self.bytes = {n: lay[n] for n in _ARRAYS}
         self.buf = {n: torch.zeros(max(lay[n], 16), dtype=torch.uint8, device=device) for n in _ARRAYS}
         self.state = _State(0, 0, 0)
+        # paged: physical page of every logical page, int32 [n_seq, t_capacity / page_tokens]; the caller fills it
+        self.page_table = None
+        if cfg.page_tokens > 0:
+            self.page_table = torch.zeros((cfg.n_seq, cfg.t_capacity // cfg.page_tokens), dtype=torch.int32, device=device)
 
     def c(self) -> _Cache:
-        return _Cache(**{n: self.buf[n].data_ptr() for n in _ARRAYS})
+        if self.page_table is not None:
+            assert self.page_table.dtype == torch.int32 and self.page_table.is_contiguous()
+            assert tuple(self.page_table.shape) == (self.cfg.n_seq, self.cfg.t_capacity // self.cfg.page_tokens)
+        return _Cache(**{n: self.buf[n].data_ptr() for n in _ARRAYS},
+                      page_table=None if self.page_table is None else self.page_table.data_ptr())
 
     @property
     def t_quant(self):
@@ -216,13 +227,20 @@ class Cache:
         return self.sequences(i, 1)
 
     def sequences(self, first: int, count: int) -> "Cache":
-        """Sequences [first, first + count) as a cache of their own (one pattern set per KV head, shared by them)."""
-        per = {n: self.bytes[n] // self.cfg.n_seq for n in _ARRAYS}
+        """Sequences [first, first + count) as a cache of their own (one pattern set per KV head, shared by them).
+        A paged cache shares its page pool with the view; only the tails and the page table rows are the view's."""
         sub = Cache.__new__(Cache)
         sub.cfg = replace(self.cfg, n_seq=count, seqs_per_set=0)
-        sub.bytes = {n: per[n] * count for n in _ARRAYS}
-        sub.buf = {n: self.buf[n][first * per[n]:(first + count) * per[n]] for n in _ARRAYS}
         sub.state = _State(0, 0, 0)
+        paged = self.page_table is not None
+        sub.page_table = self.page_table[first:first + count] if paged else None
+        per = {n: self.bytes[n] // self.cfg.n_seq for n in _ARRAYS}
+        sub.bytes, sub.buf = {}, {}
+        for n in _ARRAYS:
+            if paged and not n.startswith("tail"):
+                sub.bytes[n], sub.buf[n] = self.bytes[n], self.buf[n]
+            else:
+                sub.bytes[n], sub.buf[n] = per[n] * count, self.buf[n][first * per[n]:(first + count) * per[n]]
         return sub
 
 

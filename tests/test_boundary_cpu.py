@@ -32,7 +32,7 @@ def test_exports_every_declared_symbol(pk):
     lib = C.CDLL(LIB)
     for n in names:
         assert hasattr(lib, n), n
-    assert pk.pk_abi_version() == 4
+    assert pk.pk_abi_version() == 5
 
 
 def test_status_strings(pk):
@@ -72,6 +72,31 @@ def test_bad_config_is_refused(pk, field, value, status):
         pk.pk_cache_layout(pk.Config(**kw))
     assert e.value.status == status
     assert pk.pk_workspace_bytes(pk.Config(**kw), pk.OP_DECODE, 1024) == 0
+
+
+def test_paged_layout_and_its_config_checks(pk):
+    """A paged configuration: the packed arrays are sized by the pool (n_pages x heads x page_tokens token slots), the
+    tails by the streams; page sizes that a group or block could straddle, or that do not divide the capacity, are
+    refused; a paged cache without a page table is refused before any launch."""
+    kw = dict(n_seq=3, n_kv_heads=4, n_q_heads=8, n_patterns=16, bits=2, group=64, recent=32, flush=128, t_capacity=2048)
+    lay = pk.pk_cache_layout(pk.Config(**kw, page_tokens=256, n_pages=10))
+    slots = 10 * 4 * 256
+    assert lay["k_codes"] == lay["v_codes"] == slots * 128 * 2 // 8
+    assert lay["k_scale"] == slots // 64 * 128 * 2 and lay["v_scale"] == slots * 2 * 2 and lay["k_idx"] == slots
+    assert lay["tail_k"] == 3 * 4 * 160 * 128 * 2
+    for bad, status in [(dict(page_tokens=64, n_pages=10), 2), (dict(page_tokens=192, n_pages=10), 2),
+                        (dict(page_tokens=4096, n_pages=10), 3), (dict(page_tokens=256, n_pages=0), 1),
+                        (dict(page_tokens=-128, n_pages=4), 1)]:
+        with pytest.raises(pk.PkError) as e:
+            pk.pk_cache_layout(pk.Config(**kw, **bad))
+        assert e.value.status == status, bad
+    lib = C.CDLL(LIB)
+    cfg = pk.Config(**kw, page_tokens=256, n_pages=10).c()
+    cache, state = _fake_cache(pk), pk._State(0, 0, 0)          # page_table left NULL
+    good = C.c_void_p(0x2000)
+    st = lib.pk_quantize_append(C.byref(cfg), C.byref(cache), C.byref(state), good, good, C.c_int32(8), C.c_int64(0), good, good,
+                                None, C.c_size_t(0), None)
+    assert st == 1 and (state.t_quant, state.t_tail) == (0, 0)
 
 
 def test_v_threshold_needs_a_free_index(pk):

@@ -767,3 +767,94 @@ def test_config2_llama_shaped_layer(oracle, pk, bits):
         pk.pk_quantize_append(gcfg, gc2, dev(K), dev(V), Mg, Mvg)
         got2 = pk.pk_decode_attention(gcfg, gc2, dev(q), 128 ** -0.5, Mg, Mvg).cpu().numpy()
         assert_attention(got2, want, elementwise=False)   # each side on its own mined tables
+
+
+# ------------------------------------------------------------------------------ paged cache
+
+class PagedView:
+    """The streams of a paged GPU cache gathered back into the contiguous layout (page after page through the page
+    table), so that they compare with the oracle's cache, which knows nothing of pages."""
+
+    def __init__(self, gc):
+        self.gc = gc
+
+    def array(self, name):
+        raw = self.gc.array(name)
+        if name.startswith("tail"):
+            return raw
+        cfg = self.gc.cfg
+        hkv, PT = cfg.n_kv_heads, cfg.page_tokens
+        parts = raw.view(cfg.n_pages * hkv, -1)                        # one row per (page, head)
+        table = self.gc.page_table.long()                              # [n_seq, pages_per_seq]
+        rows = table[:, None, :] * hkv + torch.arange(hkv, device=raw.device)[None, :, None]   # [n_seq, hkv, pages]
+        return parts[rows.reshape(-1)].reshape(-1)                     # [n_seq][hkv][page][...] = stream-major
+
+
+@pytest.mark.parametrize("bits,G,P,metric,R,PT,ragged", [
+    (2, 64, 32, 0, 32, 128, False),
+    (4, 32, 16, 0, 0, 256, False),
+    (2, 128, 130, 1, 100, 128, False),      # groups of 128 tokens = whole pages, large table, min-max rule
+    (2, 64, 32, 0, 32, 128, True),          # ragged appends and ragged decode over pages
+])
+def test_paged_cache_parity(oracle, pk, bits, G, P, metric, R, PT, ragged):
+    """A cache whose packed arrays are a pool of pages, with a scrambled page table (more pages in the pool than
+    the batch uses): appends in several pieces, then dequantize and decode.  Gathered back through the page table,
+    every stream must equal the oracle's contiguous cache; attention and reconstruction must agree as usual."""
+    S, hkv, hq, F, cap = 3, 2, 8, 128, 1024
+    kw = dict(n_kv_heads=hkv, n_q_heads=hq, head_dim=128, n_patterns=P, bits=bits, group=G, recent=R, flush=F,
+              t_capacity=cap, metric=metric)
+    pages_per_seq = cap // PT
+    n_pages = S * pages_per_seq + 5
+    K, V = synth.make_kv(700 + P + PT, synth.KVSpec(1, S, hkv, hq, cap, 128, 12))
+    Mk, _, _, _ = oracle.mine(K[0].view(np.uint16), P, 3)
+    Mv, _, _, _ = oracle.mine(V[0].view(np.uint16), P, 3)
+    Mkd, Mvd = dev(Mk.view(np.float16)), dev(Mv.view(np.float16))
+    gcfg = pk.Config(**dict(kw, n_seq=S, seqs_per_set=S, page_tokens=PT, n_pages=n_pages))
+    gc = pk.Cache(gcfg)
+    perm = np.random.default_rng(PT + P).permutation(n_pages)[:S * pages_per_seq].astype(np.int32)
+    gc.page_table.copy_(torch.from_numpy(perm.reshape(S, pages_per_seq)))
+    ocs = [oracle.Cache(oracle.Config(**dict(kw, n_seq=1, seqs_per_set=0))) for _ in range(S)]
+    rounds = [[300, 900, 40], [500, 100, 1], [224, 24, 700]] if ragged else [[300] * S, [500] * S, [224] * S]
+    states, done = [[0, 0, 0] for _ in range(S)], [0] * S
+    for n_new in rounds:
+        n_max = max(n_new)
+        Kn, Vn = np.zeros((S, hkv, n_max, 128), np.float16), np.zeros((S, hkv, n_max, 128), np.float16)
+        for i, n in enumerate(n_new):
+            Kn[i, :, :n], Vn[i, :, :n] = K[i, :, done[i]:done[i] + n], V[i, :, done[i]:done[i] + n]
+            ocs[i].append(Kn[i:i + 1, :, :n].view(np.uint16), Vn[i:i + 1, :, :n].view(np.uint16), Mk, Mv)
+            done[i] += n
+        if ragged:
+            pk.pk_quantize_append_ragged(gcfg, gc, states, dev(Kn), dev(Vn), n_new, Mkd, Mvd)
+        else:
+            pk.pk_quantize_append(gcfg, gc, dev(Kn), dev(Vn), Mkd, Mvd)
+            states = [[gc.t_quant, gc.t_tail, gc.tail_start] for _ in range(S)]
+    torch.cuda.synchronize()
+    gathered = PagedView(gc)
+    for i, oc in enumerate(ocs):
+        assert states[i] == [oc.t_quant, oc.t_tail, oc.tail_start]
+
+        class One:   # sequence i of the gathered arrays, as a one-sequence cache
+            def array(self, name, i=i):
+                raw = gathered.array(name)
+                per = raw.numel() // S
+                return raw[i * per:(i + 1) * per]
+        compare_caches(oracle, oc, One(), metric)
+    q = synth.make_queries(34, S, hq, 128)
+    want, _ = oracle.decode_attention_ragged(ocs, q.view(np.uint16), Mk, Mv, 128 ** -0.5)
+    if ragged:
+        st = torch.tensor([s + [0] for s in states], dtype=torch.int32, device="cuda")
+        got = pk.pk_decode_attention_ragged(gcfg, gc, st, max(s[0] for s in states), max(s[1] for s in states), dev(q),
+                                            128 ** -0.5, Mkd, Mvd).cpu().numpy()
+    else:
+        got = pk.pk_decode_attention(gcfg, gc, dev(q), 128 ** -0.5, Mkd, Mvd).cpu().numpy()
+        # reconstruction through the page table
+        kg, vg = pk.pk_dequantize(gcfg, gc, Mkd, Mvd)
+        tq = gc.t_quant
+        for i, oc in enumerate(ocs):
+            ko, vo = oc.dequantize(Mk, Mv)
+            dk = np.abs(kg[i * hkv:(i + 1) * hkv].cpu().numpy() - ko).max(axis=2)      # [hkv, tq]
+            dv = np.abs(vg[i * hkv:(i + 1) * hkv].cpu().numpy() - vo).max(axis=2)
+            # (a token whose assignment differs inside the near-tie band is reconstructed from another pattern)
+            assert (dk > 1e-3).sum() <= 2 * G and (dv > 1e-3).sum() <= 2 and tq == oc.t_quant
+    for i in range(S):
+        assert_attention(got[i], want[i])

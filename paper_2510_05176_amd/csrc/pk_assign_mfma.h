@@ -177,6 +177,20 @@ __device__ __forceinline__ void assign_tile_mfma(const uint4 (&xb)[4], const Pat
     flag = fl[0];
 }
 
+// Differences with one rounding, as the binary32 subtraction of the widened values: v_fma_mix_f32
+// computes a*1.0 + (-b) with fp16 sources widened exactly.
+__device__ __forceinline__ float sub_lo(uint32_t x, uint32_t m)   // half(x.lo) - half(m.lo)
+{
+    float r;
+    asm("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel:[0,0,0] op_sel_hi:[1,0,1]" : "=v"(r) : "v"(x), "v"(m));
+    return r;
+}
+__device__ __forceinline__ float sub_hi(uint32_t x, uint32_t m)   // half(x.hi) - half(m.hi)
+{
+    float r;
+    asm("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel:[1,0,1] op_sel_hi:[1,0,1]" : "=v"(r) : "v"(x), "v"(m));
+    return r;
+}
 // Exact re-evaluation of one token by a whole wave: xrow_s = its 128 channels (fp16) in LDS.
 // Every lane returns the exact argmin (lowest index on ties) and its distance.
 __device__ __forceinline__ void exact_argmin_wave(const __half *xrow_s, const PatternTable &tb, int lane, int &best_i,
@@ -189,15 +203,13 @@ __device__ __forceinline__ void exact_argmin_wave(const __half *xrow_s, const Pa
         // missed L2 often enough to add a fifth to the HBM traffic of a mining step on a large job
         const __half *m = tb.lds_rows + p * kTabStride;
         float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-        for (int ch = 0; ch < kRowChunks; ++ch) {
+#pragma unroll 4
+        for (int ch = 0; ch < kRowChunks; ++ch) {   // several row pieces in flight
             const uint4 mv = *reinterpret_cast<const uint4 *>(m + ch * 8);
             const uint4 xv = *reinterpret_cast<const uint4 *>(xrow_s + ch * 8);
-            const half2_t *mh = reinterpret_cast<const half2_t *>(&mv);
-            const half2_t *xh = reinterpret_cast<const half2_t *>(&xv);
-            const float d0 = (float)xh[0][0] - (float)mh[0][0], d1 = (float)xh[0][1] - (float)mh[0][1];
-            const float d2 = (float)xh[1][0] - (float)mh[1][0], d3 = (float)xh[1][1] - (float)mh[1][1];
-            const float d4 = (float)xh[2][0] - (float)mh[2][0], d5 = (float)xh[2][1] - (float)mh[2][1];
-            const float d6 = (float)xh[3][0] - (float)mh[3][0], d7 = (float)xh[3][1] - (float)mh[3][1];
+            // (one v_fma_mix_f32 per difference instead of two conversions and a subtraction: the same value)
+            const float d0 = sub_lo(xv.x, mv.x), d1 = sub_hi(xv.x, mv.x), d2 = sub_lo(xv.y, mv.y), d3 = sub_hi(xv.y, mv.y);
+            const float d4 = sub_lo(xv.z, mv.z), d5 = sub_hi(xv.z, mv.z), d6 = sub_lo(xv.w, mv.w), d7 = sub_hi(xv.w, mv.w);
             a0 = fmaf(d0, d0, a0); a1 = fmaf(d1, d1, a1); a2 = fmaf(d2, d2, a2); a3 = fmaf(d3, d3, a3);
             a0 = fmaf(d4, d4, a0); a1 = fmaf(d5, d5, a1); a2 = fmaf(d6, d6, a2); a3 = fmaf(d7, d7, a3);
         }

@@ -183,20 +183,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void a
 
 constexpr int kRStride = kD + 4;           // floats per row of the residual tile (16-byte aligned rows, bank skew 4)
 
-// Differences with one rounding, as the binary32 subtraction of the widened values: v_fma_mix_f32
-// computes a*1.0 + (-b) with fp16 sources widened exactly.
-__device__ __forceinline__ float sub_lo(uint32_t x, uint32_t m)   // half(x.lo) - half(m.lo)
-{
-    float r;
-    asm("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel:[0,0,0] op_sel_hi:[1,0,1]" : "=v"(r) : "v"(x), "v"(m));
-    return r;
-}
-__device__ __forceinline__ float sub_hi(uint32_t x, uint32_t m)   // half(x.hi) - half(m.hi)
-{
-    float r;
-    asm("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel:[1,0,1] op_sel_hi:[1,0,1]" : "=v"(r) : "v"(x), "v"(m));
-    return r;
-}
+// (sub_lo / sub_hi, the fp16 differences with one rounding, live in pk_assign_mfma.h: the exact search uses them too)
 __device__ __forceinline__ float subz_lo(float x, uint32_t z)   // x - half(z.lo)
 {
     float r;

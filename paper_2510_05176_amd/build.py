@@ -12,7 +12,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libpatternkv.so")
 SOURCES = ["pk_api.hip", "pk_mine.hip", "pk_quantize.hip", "pk_decode.hip", "pk_decode_packed.hip", "pk_dequant.hip",
-           "pk_probe.hip"]
+           "pk_probe.hip", "pk_generic.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",

@@ -44,12 +44,14 @@ pk_status check_config(const pk_config *c)
         c->recent < 0 || c->flush < 1 || c->t_capacity < 0)
         return PK_ERR_INVALID_ARG;
     if (c->metric != PK_METRIC_L2 && c->metric != PK_METRIC_MINMAX) return PK_ERR_INVALID_ARG;
-    if (c->head_dim != kD) return PK_ERR_UNSUPPORTED;
+    if (c->head_dim != kD && c->head_dim != 96 && c->head_dim != 256) return PK_ERR_UNSUPPORTED;
     if (c->n_patterns > 256) return PK_ERR_UNSUPPORTED;
     if (!(c->v_rho >= 0.f) || !(c->v_rho < 1.f)) return PK_ERR_INVALID_ARG;   // also rejects NaN
     if (c->v_rho > 0.f && c->n_patterns > PK_NO_PATTERN) return PK_ERR_UNSUPPORTED;
     if (c->bits != 2 && c->bits != 4) return PK_ERR_UNSUPPORTED;
     if (c->group != 32 && c->group != 64 && c->group != 128) return PK_ERR_UNSUPPORTED;
+    // V is quantized over contiguous groups of min(G, d) channels: they have to tile the head (d = 96: G = 32 or 128)
+    if (c->head_dim % (c->group < c->head_dim ? c->group : c->head_dim) != 0) return PK_ERR_UNSUPPORTED;
     if (c->n_q_heads % c->n_kv_heads != 0) return PK_ERR_SHAPE;
     if (c->n_q_heads / c->n_kv_heads > 8) return PK_ERR_UNSUPPORTED;
     if ((int64_t)c->n_seq * c->n_kv_heads > 65535) return PK_ERR_UNSUPPORTED;
@@ -149,14 +151,14 @@ int64_t decode_slots_bound(int64_t N, int64_t a, int64_t b)
 struct MineCarve {
     size_t assign, best, psum, pcnt, total;
 };
-MineCarve mine_carve(int64_t S, int64_t T, int P)
+MineCarve mine_carve(int64_t S, int64_t T, int P, int d)
 {
     MineCarve m;
     const int ts = mine_tsplit((int)T, (int)S, P);
     m.assign = 0;
     m.best = round_up(m.assign + (uint64_t)S * T * 4, 256);
     m.psum = round_up(m.best + (uint64_t)S * T * 4, 256);
-    m.pcnt = round_up(m.psum + (uint64_t)S * ts * P * kD * 4, 256);
+    m.pcnt = round_up(m.psum + (uint64_t)S * ts * P * d * 4, 256);
     m.total = round_up(m.pcnt + (uint64_t)S * ts * P * 4, 256);
     return m;
 }
@@ -188,7 +190,7 @@ pk_status pk_cache_layout(const pk_config *cfg, pk_layout *out)
     pk_status st = check_config(cfg);
     if (st != PK_OK) return st;
     if (!out) return PK_ERR_INVALID_ARG;
-    const uint64_t N = (uint64_t)cfg->n_seq * cfg->n_kv_heads, d = kD, b = cfg->bits;
+    const uint64_t N = (uint64_t)cfg->n_seq * cfg->n_kv_heads, d = cfg->head_dim, b = cfg->bits;
     const uint64_t G = cfg->group, Gc = G < d ? G : d;
     // packed token slots: N streams of t_capacity tokens, or a pool of pages of [n_kv_heads][page_tokens] tokens
     const uint64_t slots = cfg->page_tokens > 0 ? (uint64_t)cfg->n_pages * cfg->n_kv_heads * cfg->page_tokens
@@ -212,15 +214,16 @@ size_t pk_workspace_bytes(const pk_config *cfg, pk_op op, int64_t a, int64_t b)
 {
     if (!cfg || a < 0 || b < 0) return 0;
     if (op == PK_OP_MINE) {
-        if (cfg->head_dim != kD || cfg->n_patterns < 1 || cfg->n_patterns > 256 || b < 1) return 0;
-        return mine_carve(b, a, cfg->n_patterns).total;
+        const int hd = cfg->head_dim;
+        if ((hd != kD && hd != 96 && hd != 256) || cfg->n_patterns < 1 || cfg->n_patterns > 256 || b < 1) return 0;
+        return mine_carve(b, a, cfg->n_patterns, hd).total;
     }
     if (check_config(cfg) != PK_OK) return 0;
     if (op == PK_OP_APPEND) return (size_t)cfg->n_seq * kSeqEntry * sizeof(int32_t);
     if (op == PK_OP_DECODE) {
         const int64_t N = (int64_t)cfg->n_seq * cfg->n_kv_heads, r = cfg->n_q_heads / cfg->n_kv_heads;
         const int64_t slots = decode_slots_bound(N, a, b);
-        return round_up((uint64_t)N * slots * r * kD * 4, 256) + round_up((uint64_t)N * slots * r * cfg->n_patterns * 4, 256) +
+        return round_up((uint64_t)N * slots * r * cfg->head_dim * 4, 256) + round_up((uint64_t)N * slots * r * cfg->n_patterns * 4, 256) +
                round_up((uint64_t)N * slots * r * 2 * 4, 256) + decode_order_bytes(cfg->n_seq);
     }
     return 0;
@@ -238,7 +241,7 @@ pk_status pk_decode_plan(const pk_config *cfg, int64_t own_packed, int64_t prefi
     if (split_tokens) *split_tokens = (int32_t)c;
     if (n_slots) *n_slots = (int32_t)slots;
     if (bytes_needed)
-        *bytes_needed = (size_t)(round_up((uint64_t)N * slots * r * kD * 4, 256) + round_up((uint64_t)N * slots * r * cfg->n_patterns * 4, 256) +
+        *bytes_needed = (size_t)(round_up((uint64_t)N * slots * r * cfg->head_dim * 4, 256) + round_up((uint64_t)N * slots * r * cfg->n_patterns * 4, 256) +
                                  round_up((uint64_t)N * slots * r * 2 * 4, 256) + decode_order_bytes(cfg->n_seq));
     return PK_OK;
 }
@@ -249,11 +252,12 @@ pk_status pk_mine_patterns(const pk_config *cfg, const void *x, int64_t set_stri
 {
     if (!cfg || !x || !patterns) return PK_ERR_INVALID_ARG;
     if (n_sets < 1 || T < 1 || iters < 0 || cfg->n_patterns < 1) return PK_ERR_INVALID_ARG;
-    if (cfg->head_dim != kD || cfg->n_patterns > 256 || n_sets > 65535) return PK_ERR_UNSUPPORTED;
+    const int hd = cfg->head_dim;
+    if ((hd != kD && hd != 96 && hd != 256) || cfg->n_patterns > 256 || n_sets > 65535) return PK_ERR_UNSUPPORTED;
     if (!init_given && T < cfg->n_patterns) return PK_ERR_SHAPE;
-    if (set_stride < (int64_t)T * kD || set_stride % 8 != 0) return PK_ERR_SHAPE;
+    if (set_stride < (int64_t)T * hd || set_stride % 8 != 0) return PK_ERR_SHAPE;
     if (!aligned16(x) || !aligned16(patterns) || (assign && !aligned16(assign))) return PK_ERR_ALIGNMENT;
-    const MineCarve mc = mine_carve(n_sets, T, cfg->n_patterns);
+    const MineCarve mc = mine_carve(n_sets, T, cfg->n_patterns, hd);
     if (!workspace || workspace_bytes < mc.total) return PK_ERR_WORKSPACE;
     if (!aligned16(workspace)) return PK_ERR_ALIGNMENT;
 
@@ -266,7 +270,9 @@ pk_status pk_mine_patterns(const pk_config *cfg, const void *x, int64_t set_stri
     a.P = cfg->n_patterns;
     a.iters = iters;
     a.init_given = init_given;
+    a.d = hd;
     a.patterns = static_cast<__half *>(patterns);
+    a.assign_ws = reinterpret_cast<int32_t *>(ws + mc.assign);
     a.assign = assign;   // optional: written by the last step only
     a.best = reinterpret_cast<float *>(ws + mc.best);
     a.psum = reinterpret_cast<float *>(ws + mc.psum);
@@ -306,6 +312,7 @@ pk_status launch_append(const pk_config *cfg, const pk_cache *cache, const Appen
         a.v_rho = 0.f;
         a.bits = cfg->bits;
         a.G = cfg->group;
+        a.d = cfg->head_dim;
         a.n_streams = N;
         a.nq = (int32_t)p.nq;
         a.t0 = p.t0;
@@ -348,6 +355,7 @@ pk_status launch_append(const pk_config *cfg, const pk_cache *cache, const Appen
     c.i1 = (int32_t)p.i1;
     c.n_streams = N;
     c.n_kv_heads = cfg->n_kv_heads;
+    c.d = cfg->head_dim;
     c.seq_table = p.seq_table;
     if (launch_tail_copy(c, hs) != hipSuccess) return PK_ERR_DEVICE;
     return PK_OK;
@@ -369,8 +377,8 @@ pk_status pk_quantize_append(const pk_config *cfg, const pk_cache *cache, pk_sta
     if (n_new < 0) return PK_ERR_INVALID_ARG;
     if (n_new == 0) return PK_OK;
     if (!k_new || !v_new || !patterns_k || !patterns_v) return PK_ERR_INVALID_ARG;
-    if (stream_stride == 0) stream_stride = (int64_t)n_new * kD;
-    if (stream_stride < (int64_t)n_new * kD || stream_stride % 8 != 0) return PK_ERR_SHAPE;
+    if (stream_stride == 0) stream_stride = (int64_t)n_new * cfg->head_dim;
+    if (stream_stride < (int64_t)n_new * cfg->head_dim || stream_stride % 8 != 0) return PK_ERR_SHAPE;
     if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(patterns_k) || !aligned16(patterns_v))
         return PK_ERR_ALIGNMENT;
 
@@ -407,6 +415,7 @@ pk_status pk_quantize_append_ragged(const pk_config *cfg, const pk_cache *cache,
     if ((st = check_cache(cache)) != PK_OK) return st;
     if ((st = check_paging(cfg, cache)) != PK_OK) return st;
     if (!states || !n_new) return PK_ERR_INVALID_ARG;
+    if (cfg->head_dim != kD) return PK_ERR_UNSUPPORTED;   // the generic kernels take uniform appends only
     const int S = cfg->n_seq;
     int64_t max_new = 0;
     for (int i = 0; i < S; ++i) {
@@ -489,7 +498,8 @@ static pk_status decode_impl(const pk_config *cfg, const pk_cache *cache, const 
     if ((st = check_paging(cfg, cache)) != PK_OK) return st;
     if ((st = check_state(cfg, state)) != PK_OK) return st;
     if (!q || !patterns_k || !patterns_v || !out) return PK_ERR_INVALID_ARG;
-    if ((cfg->n_q_heads / cfg->n_kv_heads) * (kD / (cfg->group < kD ? cfg->group : kD)) > 16) return PK_ERR_UNSUPPORTED;
+    if (cfg->head_dim == kD && (cfg->n_q_heads / cfg->n_kv_heads) * (kD / (cfg->group < kD ? cfg->group : kD)) > 16)
+        return PK_ERR_UNSUPPORTED;
     if (!aligned16(q) || !aligned16(patterns_k) || !aligned16(patterns_v) || !aligned16(out) ||
         (lse && !aligned16(lse)))
         return PK_ERR_ALIGNMENT;
@@ -502,7 +512,7 @@ static pk_status decode_impl(const pk_config *cfg, const pk_cache *cache, const 
         if ((st = check_state(prefix_cfg, prefix_state)) != PK_OK) return st;
         if (prefix_cfg->n_seq != 1 || prefix_cfg->n_kv_heads != cfg->n_kv_heads ||
             prefix_cfg->n_q_heads != cfg->n_q_heads || prefix_cfg->n_patterns != cfg->n_patterns ||
-            prefix_cfg->bits != cfg->bits || prefix_cfg->group != cfg->group)
+            prefix_cfg->bits != cfg->bits || prefix_cfg->group != cfg->group || prefix_cfg->head_dim != cfg->head_dim)
             return PK_ERR_SHAPE;
     }
 
@@ -521,7 +531,7 @@ static pk_status decode_impl(const pk_config *cfg, const pk_cache *cache, const 
     a.splits_prefix = (a.prefix.t_quant + a.chunk - 1) / a.chunk;
     const int64_t slots = a.splits_own + a.splits_prefix + 2;
     if (slots > kMaxSlots) return PK_ERR_UNSUPPORTED;
-    const uint64_t o_bytes = round_up((uint64_t)N * slots * r * kD * 4, 256);
+    const uint64_t o_bytes = round_up((uint64_t)N * slots * r * cfg->head_dim * 4, 256);
     const uint64_t w_bytes = round_up((uint64_t)N * slots * r * cfg->n_patterns * 4, 256);
     const uint64_t ml_bytes = round_up((uint64_t)N * slots * r * 2 * 4, 256);
     const uint64_t order_bytes = decode_order_bytes(cfg->n_seq);
@@ -539,6 +549,8 @@ static pk_status decode_impl(const pk_config *cfg, const pk_cache *cache, const 
     a.P = cfg->n_patterns;
     a.bits = cfg->bits;
     a.G = cfg->group;
+    a.d = cfg->head_dim;
+    a.v_thresholded = (cfg->v_rho > 0.f || (has_prefix && prefix_cfg->v_rho > 0.f)) ? 1 : 0;
     a.softmax_scale = softmax_scale;
     a.part_o = reinterpret_cast<float *>(workspace);
     a.part_w = reinterpret_cast<float *>(static_cast<char *>(workspace) + o_bytes);
@@ -591,12 +603,14 @@ pk_status pk_window_pattern(const void *x, int64_t set_stride, int32_t n_sets, i
                             void *pattern_out, int64_t out_stride, void *stream)
 {
     if (!x || !pattern_out || n_sets < 1 || n < 1 || set_stride < 0 || out_stride < 0) return PK_ERR_INVALID_ARG;
-    if (head_dim != kD || n_sets > 65535) return PK_ERR_UNSUPPORTED;
+    if ((head_dim != kD && head_dim != 96 && head_dim != 256) || n_sets > 65535) return PK_ERR_UNSUPPORTED;
     if (!aligned16(x) || !aligned16(pattern_out) || set_stride % 8 != 0 || out_stride % 8 != 0) return PK_ERR_ALIGNMENT;
-    return launch_window_pattern(static_cast<const __half *>(x), set_stride, n_sets, n, static_cast<__half *>(pattern_out),
-                                 out_stride, static_cast<hipStream_t>(stream)) == hipSuccess
-               ? PK_OK
-               : PK_ERR_DEVICE;
+    const __half *xs = static_cast<const __half *>(x);
+    __half *po = static_cast<__half *>(pattern_out);
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    const hipError_t e = head_dim == kD ? launch_window_pattern(xs, set_stride, n_sets, n, po, out_stride, hs)
+                                        : launch_generic_window_pattern(xs, set_stride, n_sets, n, head_dim, po, out_stride, hs);
+    return e == hipSuccess ? PK_OK : PK_ERR_DEVICE;
 }
 
 pk_status pk_dequantize(const pk_config *cfg, const pk_cache *cache, const pk_state *state, const void *patterns_k,
@@ -620,6 +634,7 @@ pk_status pk_dequantize(const pk_config *cfg, const pk_cache *cache, const pk_st
     a.P = cfg->n_patterns;
     a.bits = cfg->bits;
     a.G = cfg->group;
+    a.d = cfg->head_dim;
     a.v_thresholded = cfg->v_rho > 0.f ? 1 : 0;
     a.t0 = t0;
     a.t1 = t1;

@@ -180,6 +180,7 @@ int decode_chunk(int64_t n_streams, int64_t t_packed_total, int P, int r)
 
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t s)
 {
+    if (a.d != kD) return launch_generic_decode(a, s);
     const int r = a.n_q_heads / a.n_kv_heads;
     const int N = a.n_seq * a.n_kv_heads;
     hipError_t e;

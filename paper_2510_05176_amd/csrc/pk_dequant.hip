@@ -48,6 +48,7 @@ __global__ __launch_bounds__(128) void dequant_kernel(DequantArgs a)
 
 hipError_t launch_dequant(const DequantArgs &a, hipStream_t s)
 {
+    if (a.d != kD) return launch_generic_dequant(a, s);
     if (a.t1 <= a.t0) return hipSuccess;
     const dim3 grid(a.t1 - a.t0, a.n_streams), block(128);
     if (a.bits == 2)

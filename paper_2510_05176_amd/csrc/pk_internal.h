@@ -34,6 +34,16 @@ struct RowSource {
         }
         return fresh + (int64_t)n * fresh_stride + (int64_t)(i - n_ring) * kD;
     }
+    // the same for rows of d elements (the generic kernels for head dimensions other than kD)
+    __device__ __forceinline__ const __half *row_d(int n, int i, int d) const
+    {
+        if (i < n_ring) {
+            int slot = ring_start + i;
+            if (slot >= ring_len) slot -= ring_len;
+            return ring + ((int64_t)n * ring_len + slot) * d;
+        }
+        return fresh + (int64_t)n * fresh_stride + (int64_t)(i - n_ring) * d;
+    }
 };
 
 // Where token `tok` of stream `stream` lives in the packed arrays, in tokens: stream * capacity + tok for contiguous
@@ -128,6 +138,7 @@ struct QuantArgs {
     SetMap sets;
     const __half *patterns;   // [n_sets][P][kD]
     int32_t P, metric, bits, G;
+    int32_t d;                // head dimension: kD runs the tuned kernels, 96 and 256 the generic ones (pk_generic.hip)
     int32_t idx_given;        // the index array already holds every vector's pattern (min-max metric: searched by a kernel of its own)
     float v_rho;              // V side: adaptive threshold (0 = off)
     int32_t n_streams;
@@ -170,6 +181,7 @@ struct TailCopyArgs {
     int32_t i0, i1;                          // logical vectors [i0, i1) to place into the ring
     int32_t n_streams;
     int32_t n_kv_heads;
+    int32_t d;                               // head dimension
     const int32_t *seq_table;                // ragged append: as in QuantArgs (i0, i1 above: the widest range)
 };
 // Writes up to kSeqChunk entries of the per-sequence table, and (optionally) the fill states after the append in
@@ -190,7 +202,9 @@ struct MineArgs {
     const __half *x;
     int64_t set_stride;
     int32_t n_sets, T, P, iters, init_given;
+    int32_t d;             // head dimension
     __half *patterns;
+    int32_t *assign_ws;    // [n_sets][T] workspace (the generic path keeps every step's assignment there)
     int32_t *assign;       // [n_sets][T] caller's, or null
     float *best;           // [n_sets][T] workspace (written when inertia is asked for)
     float *psum;           // [n_sets][tsplit][P][kD]
@@ -202,6 +216,13 @@ hipError_t launch_mine(const MineArgs &a, hipStream_t s);
 int mine_tsplit(int T, int n_sets, int P);
 hipError_t launch_window_pattern(const __half *x, int64_t set_stride, int n_sets, int n, __half *out, int64_t out_stride,
                                  hipStream_t s);
+
+// Head dimensions other than kD (pk_generic.hip): plain kernels, thread <-> channel, same results to the same bars.
+hipError_t launch_generic_quantize(const QuantArgs &a, bool v_side, hipStream_t s);
+hipError_t launch_generic_tail_copy(const TailCopyArgs &a, hipStream_t s);
+hipError_t launch_generic_mine(const MineArgs &a, hipStream_t s);
+hipError_t launch_generic_window_pattern(const __half *x, int64_t set_stride, int n_sets, int n, int d, __half *out,
+                                         int64_t out_stride, hipStream_t s);
 
 struct CacheView {
     const uint32_t *k_codes;
@@ -221,6 +242,8 @@ struct DecodeArgs {
     const __half *q;              // [n_seq][Hq][kD]
     const __half *patterns_k, *patterns_v;
     int32_t n_seq, n_kv_heads, n_q_heads, P, bits, G;
+    int32_t d;                    // head dimension
+    int32_t v_thresholded;        // v_idx may hold PK_NO_PATTERN (read by the generic decode; the tuned one needs no flag)
     float softmax_scale;
     int32_t chunk;                // packed tokens per split
     int32_t w_stride;             // entries per (wave, head) row of the per-pattern softmax mass in LDS: P, or 256
@@ -270,9 +293,12 @@ struct DequantArgs {
     SetMap sets;
     const __half *patterns_k, *patterns_v;
     int32_t n_streams, P, bits, G, t0, t1;
+    int32_t d;                // head dimension
     int32_t v_thresholded;    // v_idx == PK_NO_PATTERN marks a token quantized without a pattern
     float *k_out, *v_out;
 };
 hipError_t launch_dequant(const DequantArgs &a, hipStream_t s);
+hipError_t launch_generic_decode(const DecodeArgs &a, hipStream_t s);
+hipError_t launch_generic_dequant(const DequantArgs &a, hipStream_t s);
 
 }  // namespace pk

@@ -298,6 +298,7 @@ static hipError_t prepare_step(const MineArgs &, int, size_t, hipStream_t, int)
 
 hipError_t launch_mine(const MineArgs &a, hipStream_t s)
 {
+    if (a.d != kD) return launch_generic_mine(a, s);
     hipError_t e;
     const int chunk = mine_chunk(a.T, a.n_sets, a.P);
     const int npt = a.P <= 16 ? 1 : a.P <= 32 ? 2 : a.P <= 64 ? 4 : a.P <= 128 ? 8 : 16;

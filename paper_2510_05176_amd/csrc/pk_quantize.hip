@@ -16,38 +16,12 @@
 #pragma clang fp contract(off)
 
 #include "pk_assign_mfma.h"
-#include "pk_divide.h"
+#include "pk_quant_arith.h"
 #include "pk_internal.h"
 
 namespace pk {
 
 namespace {
-
-struct GroupParams {
-    unsigned short s16, z16;
-    float s, z, inv;
-};
-
-__device__ __forceinline__ GroupParams group_params(float mn, float mx, int bits)
-{
-    GroupParams g;
-    g.z16 = f2h_down(mn);
-    g.z = hbits2f(g.z16);
-    const float s32 = div_by_levels(mx - g.z, bits);
-    g.s16 = f2h_up(s32);
-    g.s = hbits2f(g.s16);
-    g.inv = g.s == 0.f ? 0.f : recip_of_scale(g.s);
-    return g;
-}
-
-__device__ __forceinline__ int quantize_one(float r, const GroupParams &g, int bits)
-{
-    if (g.s == 0.f) return 0;
-    float q = rintf((r - g.z) * g.inv);
-    const float qmax = (float)((1 << bits) - 1);
-    q = fminf(fmaxf(q, 0.f), qmax);
-    return (int)q;
-}
 
 // ---------------------------------------------------------------------------
 // Min-max metric (Sec. 3.2): d_mm(x, m) = max_c (x_c - m_c) - min_c (x_c - m_c), argmin over the patterns, lowest
@@ -928,6 +902,7 @@ static hipError_t launch_assign_minmax(const QuantArgs &a, hipStream_t s)
 
 hipError_t launch_quantize_k(const QuantArgs &a_in, hipStream_t s)
 {
+    if (a_in.d != kD) return launch_generic_quantize(a_in, false, s);
     QuantArgs a = a_in;
     if (a.metric == PK_METRIC_MINMAX) {
         const hipError_t e = launch_assign_minmax(a, s);
@@ -969,6 +944,7 @@ hipError_t launch_quantize_k(const QuantArgs &a_in, hipStream_t s)
 
 hipError_t launch_quantize_v(const QuantArgs &a_in, hipStream_t s)
 {
+    if (a_in.d != kD) return launch_generic_quantize(a_in, true, s);
     QuantArgs a = a_in;
     if (a.metric == PK_METRIC_MINMAX) {
         const hipError_t e = launch_assign_minmax(a, s);
@@ -995,6 +971,7 @@ hipError_t launch_quantize_v(const QuantArgs &a_in, hipStream_t s)
 
 hipError_t launch_tail_copy(const TailCopyArgs &a, hipStream_t s)
 {
+    if (a.d != kD) return launch_generic_tail_copy(a, s);
     const int64_t work = (int64_t)(a.i1 - a.i0) * kRowChunks;
     if (work <= 0) return hipSuccess;
     const dim3 grid((unsigned)((work + 255) / 256), a.n_streams, 2), block(256);

@@ -25,6 +25,7 @@ hipError_t launch_seq_table(const SeqTableArgs &a, hipStream_t)
 hipError_t launch_mine(const MineArgs &, hipStream_t) { ++g_launches; return hipSuccess; }
 int mine_tsplit(int T, int, int) { return (T + 255) / 256; }
 hipError_t launch_window_pattern(const __half *, int64_t, int, int, __half *, int64_t, hipStream_t) { ++g_launches; return hipSuccess; }
+hipError_t launch_generic_window_pattern(const __half *, int64_t, int, int, int, __half *, int64_t, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_decode(const DecodeArgs &, hipStream_t) { ++g_launches; return hipSuccess; }
 int decode_chunk(int64_t, int64_t, int, int) { return 256; }
 hipError_t launch_dequant(const DequantArgs &, hipStream_t) { ++g_launches; return hipSuccess; }
@@ -111,7 +112,8 @@ int main()
     CHECK(pk_mine_patterns(&c, base, 4096 * 128, 4, 4096, 5, 0, base, nullptr, nullptr, base, wm, nullptr) == PK_OK);
     CHECK(pk_mine_patterns(&c, base, 4096 * 128, 4, 8, 5, 0, base, nullptr, nullptr, base, wm, nullptr) == PK_ERR_SHAPE);
     CHECK(pk_window_pattern(base, 128 * 128, 4, 128, 128, base, 128, nullptr) == PK_OK);
-    CHECK(pk_window_pattern(base, 128 * 128, 4, 128, 96, base, 128, nullptr) == PK_ERR_UNSUPPORTED);
+    CHECK(pk_window_pattern(base, 128 * 128, 4, 128, 64, base, 128, nullptr) == PK_ERR_UNSUPPORTED);
+    CHECK(pk_window_pattern(base, 128 * 96, 4, 128, 96, base, 96, nullptr) == PK_OK);
     CHECK(pk_dequantize(&c, &k, &st, base, base, 0, 256, out, out, nullptr) == PK_OK);
     CHECK(pk_dequantize(&c, &k, &st, base, base, 0, 512, out, out, nullptr) == PK_ERR_SHAPE);
     CHECK(pk::g_launches > 0);

@@ -99,6 +99,33 @@ def test_paged_layout_and_its_config_checks(pk):
     assert st == 1 and (state.t_quant, state.t_tail) == (0, 0)
 
 
+def test_other_head_dimensions_in_the_layout_and_checks(pk):
+    """Head dimensions 96 and 256: the layout formulas carry d, V's channel groups of min(G, d) must tile the head,
+    the ragged append (tuned kernels only) refuses them before any launch."""
+    kw = dict(n_seq=2, n_kv_heads=2, n_q_heads=4, n_patterns=16, bits=2, recent=0, flush=128, t_capacity=1024)
+    lay = pk.pk_cache_layout(pk.Config(**kw, head_dim=256, group=64))
+    N = 4
+    assert lay["k_codes"] == lay["v_codes"] == N * 1024 * 256 * 2 // 8
+    assert lay["k_scale"] == N * (1024 // 64) * 256 * 2 and lay["v_scale"] == N * 1024 * 4 * 2
+    assert lay["tail_k"] == N * 128 * 256 * 2
+    lay = pk.pk_cache_layout(pk.Config(**kw, head_dim=96, group=128))
+    assert lay["k_codes"] == N * 1024 * 96 * 2 // 8 and lay["v_scale"] == N * 1024 * 1 * 2   # one V group of 96 channels
+    with pytest.raises(pk.PkError) as e:
+        pk.pk_cache_layout(pk.Config(**kw, head_dim=96, group=64))
+    assert e.value.status == 2
+    assert pk.pk_workspace_bytes(pk.Config(**kw, head_dim=256, group=64), pk.OP_MINE, 4096, 2) > \
+        pk.pk_workspace_bytes(pk.Config(**kw, head_dim=128, group=64), pk.OP_MINE, 4096, 2)
+    lib = C.CDLL(LIB)
+    cfg = pk.Config(**kw, head_dim=256, group=64).c()
+    cache = _fake_cache(pk)
+    states = (pk._State * 2)(pk._State(0, 0, 0), pk._State(0, 0, 0))
+    n_new = (C.c_int32 * 2)(8, 8)
+    good = C.c_void_p(0x2000)
+    st = lib.pk_quantize_append_ragged(C.byref(cfg), C.byref(cache), states, good, good, n_new, C.c_int64(0), good, good, None,
+                                       good, C.c_size_t(1024), None)
+    assert st == 2
+
+
 def test_v_threshold_needs_a_free_index(pk):
     # the adaptive threshold marks raw-quantized V tokens with index 255 (PK_NO_PATTERN)
     kw = dict(n_seq=1, n_kv_heads=4, n_q_heads=4, bits=2, group=64, recent=0, flush=64, t_capacity=1024, v_rho=0.9)

@@ -632,7 +632,7 @@ def _mining_step_parity(oracle, pk, x, P, cur, check_sets):
     pat = dev(cur.view(np.float16)).clone()
     asg = torch.empty((S, T), dtype=torch.int32, device="cuda")
     J = torch.empty((S, 1), dtype=torch.float32, device="cuda")
-    pk.pk_mine_patterns(pk.Config(n_patterns=P), dev(x), 1, patterns=pat, init_given=True, assign=asg, inertia=J)
+    pk.pk_mine_patterns(pk.Config(n_patterns=P, head_dim=x.shape[2]), dev(x), 1, patterns=pat, init_given=True, assign=asg, inertia=J)
     ag, Mg, Jg = asg.cpu().numpy(), host_u16(pat), J.cpu().numpy()
     new = {}
     for s in check_sets:
@@ -858,3 +858,51 @@ def test_paged_cache_parity(oracle, pk, bits, G, P, metric, R, PT, ragged):
             assert (dk > 1e-3).sum() <= 2 * G and (dv > 1e-3).sum() <= 2 and tq == oc.t_quant
     for i in range(S):
         assert_attention(got[i], want[i])
+
+
+# ------------------------------------------------------------------------------ other head dimensions
+
+@pytest.mark.parametrize("d,G,bits,P,metric,R,rho,with_prefix", [
+    (96, 32, 2, 16, 0, 32, 0.0, False),
+    (256, 64, 4, 40, 0, 0, 0.0, True),
+    (256, 128, 2, 24, 1, 40, 0.0, False),       # min-max rule, groups of 128 tokens
+    (96, 128, 4, 8, 0, 16, 0.8, False),         # one V group of all 96 channels, adaptive threshold on V
+])
+def test_other_head_dimensions_parity(oracle, pk, d, G, bits, P, metric, R, rho, with_prefix):
+    """Head dimensions 96 and 256 (the generic kernels): two Lloyd iterations, appends in pieces, the window pattern,
+    dequantize and decode (tail, optionally a shared prefix) against the oracle, to the bars of head dimension 128."""
+    S, hkv, hq, T, F = 2, 2, 4, 400, 128
+    K, V = synth.make_kv(900 + d + P, synth.KVSpec(1, S, hkv, hq, T, d, 12))
+    # mining: per iteration from the oracle's centroids, K streams of the first sequence as sets
+    x = np.ascontiguousarray(K[0])
+    cur = x[:, :P].copy().view(np.uint16)
+    for _ in range(2):
+        new = _mining_step_parity(oracle, pk, x, P, cur, check_sets=range(hkv))
+        cur = np.stack([new[s_] for s_ in range(hkv)])
+    Mk = cur
+    Mv, _, _, _ = oracle.mine(V[0].view(np.uint16), P, 2)
+    # window pattern
+    wp = pk.pk_window_pattern(dev(K[0][:, :100])).cpu().numpy().view(np.uint16)
+    assert np.array_equal(wp, oracle.window_pattern(K[0][:, :100].view(np.uint16)))
+    kw = dict(n_seq=S, n_kv_heads=hkv, n_q_heads=hq, head_dim=d, n_patterns=P, seqs_per_set=0, bits=bits, group=G,
+              recent=R, flush=F, t_capacity=-(-T // F) * F, metric=metric, v_rho=rho)
+    oc, gc, Mkd, Mvd = run_appends(oracle, pk, oracle.Config(**kw), pk.Config(**kw), K, V, Mk, Mv, [150, 1, 249])
+    n_diff = compare_caches(oracle, oc, gc, metric)
+    assert n_diff <= 4
+    kg, vg = pk.pk_dequantize(pk.Config(**kw), gc, Mkd, Mvd)
+    ko, vo = oc.dequantize(Mk, Mv)
+    assert (np.abs(kg.cpu().numpy() - ko).max(axis=2) > 1e-3).sum() <= n_diff * G
+    assert (np.abs(vg.cpu().numpy() - vo).max(axis=2) > 1e-3).sum() <= n_diff
+    q = synth.make_queries(35, S, hq, d)
+    op = gp = None
+    if with_prefix:
+        Kp, Vp = synth.make_kv(901, synth.KVSpec(1, 1, hkv, hq, 300, d, 12))
+        pre_kw = dict(kw, n_seq=1, recent=16, t_capacity=384)
+        op, gp, _, _ = run_appends(oracle, pk, oracle.Config(**pre_kw), pk.Config(**pre_kw), Kp, Vp, Mk, Mv, [300])
+    want, want_lse = oracle.decode_attention(oc, q.view(np.uint16), Mk, Mv, d ** -0.5, prefix=op,
+                                             prefix_patterns_k=Mk if with_prefix else None,
+                                             prefix_patterns_v=Mv if with_prefix else None)
+    lse = torch.empty((S, hq), dtype=torch.float32, device="cuda")
+    got = pk.pk_decode_attention(pk.Config(**kw), gc, dev(q), d ** -0.5, Mkd, Mvd, lse=lse, prefix=gp).cpu().numpy()
+    assert_attention(got, want)
+    assert np.abs(lse.cpu().numpy() - want_lse).max() <= 2e-3

@@ -660,9 +660,11 @@ def test_mining_parity_many_sets_several_subtiles(oracle, pk):
     K, _ = synth.make_kv(91, spec)
     x = K.reshape(64, 4096 + 37, 128)
     cur = x[:, :128].copy().view(np.uint16)
+    checked = range(0, 64, 4)   # the GPU runs all 64 sets, the oracle every fourth (first, middle and last workgroups of the launch)
     for it in range(2):
-        new = _mining_step_parity(oracle, pk, x, 128, cur, check_sets=range(64))
-        cur = np.stack([new[s] for s in range(64)])            # both sides continue from the oracle's centroids
+        new = _mining_step_parity(oracle, pk, x, 128, cur, check_sets=checked)
+        # both sides continue from the oracle's centroids; the sets the oracle skipped keep theirs (inputs never come from the GPU)
+        cur = np.stack([new[s] if s in new else cur[s] for s in range(64)])
 
 
 def test_mining_parity_256_patterns_long_chunks(oracle, pk):

@@ -54,6 +54,9 @@ VALU_LANE_OPS_PEAK_T = 256 * 4 * 16 * 2.4e9 / 1e12
 WORKLOADS = {
     "cfg2": dict(spec="cfg2", layers=1, batch=1, P=64, iters=10, group=64, recent=0, flush=64),
     "cfg2x32": dict(spec="cfg2", layers=32, batch=1, P=64, iters=10, group=64, recent=0, flush=64),
+    # config 2's 32 layers at head dimensions 96 and 256: the plain kernels of pk_generic.hip
+    "cfg2x32_d96": dict(spec="cfg2_d96", layers=32, batch=1, P=64, iters=10, group=32, recent=0, flush=64),
+    "cfg2x32_d256": dict(spec="cfg2_d256", layers=32, batch=1, P=64, iters=10, group=64, recent=0, flush=64),
     "cfg3": dict(spec="cfg3", layers=32, batch=16, P=128, iters=10, group=64, recent=128, flush=128),
     "cfg5": dict(spec="cfg5", layers=1, batch=1, P=256, iters=20, group=128, recent=0, flush=128),
     # second workload: the latent cache of multi-head latent attention (one stream per sequence, 8 query heads)
@@ -202,7 +205,13 @@ def run_static(name, args, torch, pk, synth, steps, warmup, metric=None, cpu_bas
     mine_bytes = 2.0 * L * Hkv * iters * T * d * 2            # per Lloyd iteration: one pass over x
     traffic = stored_traffic(name, bits) if metric == pk.METRIC_L2 else {}
 
+    generic = d != 128   # head dimensions 96 and 256 run the plain kernels
+
     def roof(stage, bound, achieved, peak, unit, kernels):
+        if generic:
+            kernels = {"mine": "gen_mine_assign_kernel+gen_mine_sums_kernel+gen_mine_update_kernel",
+                       "quantize_append": "gen_assign_kernel+gen_quantize_k_kernel+gen_quantize_v_kernel",
+                       "decode_attention": "gen_decode_split_kernel+gen_decode_merge_kernel"}[stage]
         return {"bound": bound, "achieved": round(achieved, 3), "peak": peak, "unit": unit,
                 "frac": round(achieved / peak, 4), "traffic": traffic.get(stage), "kernel": kernels}
 
@@ -666,6 +675,13 @@ def main():
                                       "achieved": s["stage_rooflines"][st]["achieved"], "unit": s["stage_rooflines"][st]["unit"],
                                       "frac": s["stage_rooflines"][st]["frac"]} for st in ("quantize_append", "decode_attention")}
         sweep["cfg2x32_4bit"]["decode_attention"]["tokens/s"] = s["stages"]["decode_attention"]["tokens/s"]
+        for wname in ("cfg2x32_d96", "cfg2x32_d256"):
+            s = run_static(wname, args, torch, pk, synth, 5, 1)
+            torch.cuda.empty_cache()
+            sweep[wname] = {st: {"ms": s["stages"][st]["ms"], "bound": s["stage_rooflines"][st]["bound"],
+                                 "achieved": s["stage_rooflines"][st]["achieved"], "unit": s["stage_rooflines"][st]["unit"],
+                                 "frac": s["stage_rooflines"][st]["frac"], "kernel": s["stage_rooflines"][st]["kernel"]}
+                            for st in s["stages"]}
         s = run_streaming(args, torch, pk, synth, 0, 8192, 8)
         torch.cuda.empty_cache()
         sweep["cfg4"] = {"schedule": "64 samples x 8192 generated tokens over a shared 4096-token prompt; one append and one "

@@ -177,20 +177,6 @@ __device__ __forceinline__ void assign_tile_mfma(const uint4 (&xb)[4], const Pat
     flag = fl[0];
 }
 
-// Differences with one rounding, as the binary32 subtraction of the widened values: v_fma_mix_f32
-// computes a*1.0 + (-b) with fp16 sources widened exactly.
-__device__ __forceinline__ float sub_lo(uint32_t x, uint32_t m)   // half(x.lo) - half(m.lo)
-{
-    float r;
-    asm("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel:[0,0,0] op_sel_hi:[1,0,1]" : "=v"(r) : "v"(x), "v"(m));
-    return r;
-}
-__device__ __forceinline__ float sub_hi(uint32_t x, uint32_t m)   // half(x.hi) - half(m.hi)
-{
-    float r;
-    asm("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel:[1,0,1] op_sel_hi:[1,0,1]" : "=v"(r) : "v"(x), "v"(m));
-    return r;
-}
 // Exact re-evaluation of one token by a whole wave: xrow_s = its 128 channels (fp16) in LDS.
 // Every lane returns the exact argmin (lowest index on ties) and its distance.
 __device__ __forceinline__ void exact_argmin_wave(const __half *xrow_s, const PatternTable &tb, int lane, int &best_i,

@@ -1,9 +1,9 @@
 // The hot path for head dimensions other than 128 (96 and 256, the other two that Sec. 3.3 names): plain kernels,
-// thread <-> channel or thread <-> token, no matrix cores, no LDS tiling.  They compute the same definitions with
+// thread <-> channel or thread <-> token (vector), no matrix cores.  They compute the same definitions with
 // the same arithmetic where it decides an integer (the quantizer's parameters and codes come from the shared
 // pk_quant_arith.h; pattern selection evaluates the metric in binary32 over all patterns, lowest index on ties) and
 // store the same cache format (head_dim enters the layout formulas), so they meet the same parity bars; they are
-// not tuned, and the tuned kernels of the other files keep their fixed head dimension.
+// kept simple rather than tuned, and the tuned kernels of the other files keep their fixed head dimension.
 // Uniform appends, decode (with shared prefix and with per-sequence fill states), mining, the window pattern and
 // dequantize are covered, on contiguous and on paged caches.
 #pragma clang fp contract(off)
@@ -16,12 +16,6 @@ namespace {
 
 constexpr int kGenThreads = 256;   // >= the largest head dimension
 
-__device__ __forceinline__ float wave_min(float v)
-{
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v = fminf(v, __shfl_xor(v, off));
-    return v;
-}
 __device__ __forceinline__ float wave_max(float v)
 {
 #pragma unroll
@@ -29,47 +23,61 @@ __device__ __forceinline__ float wave_max(float v)
     return v;
 }
 
-// Distance of the fp16 vector x (d elements, LDS or global) to pattern row m under the metric: the sum of squared
-// binary32 differences in channel order, or d_mm = max - min of the differences (Sec. 3.2).
-__device__ __forceinline__ float metric_distance(const __half *x, const __half *m, int d, int metric)
-{
-    if (metric == PK_METRIC_MINMAX) {
-        float mx = -INFINITY, mn = INFINITY;
-        for (int c = 0; c < d; ++c) {
-            const float r = h2f(x[c]) - h2f(m[c]);
-            mx = fmaxf(mx, r);
-            mn = fminf(mn, r);
-        }
-        return mx - mn;
-    }
-    float acc = 0.f;
-    for (int c = 0; c < d; ++c) {
-        const float r = h2f(x[c]) - h2f(m[c]);
-        acc = fmaf(r, r, acc);
-    }
-    return acc;
-}
-
-// argmin over the patterns for the vector in xs (LDS): lane <-> pattern, then a wave reduction (lowest index on ties)
-__device__ __forceinline__ void wave_nearest(const __half *xs, const __half *M, int P, int d, int metric, int lane, int &best_i,
-                                             float &best_d)
+// Nearest pattern of one vector per thread (lane <-> vector): the vector's D channels stay in registers as loaded,
+// the pattern rows pass through LDS in chunks of kTabRows and are read by all lanes at once (one broadcast read per
+// 8 channels), four patterns at a time.  Per pattern the metric is evaluated in binary32 - the squared differences
+// added in channel order into one accumulator, or d_mm = max - min of the differences (Sec. 3.2) - and patterns are compared in increasing order with a strict <, so the lowest index wins ties.  All threads of the
+// workgroup call this together (it has workgroup barriers).
+constexpr int kTabRows = 32;
+template <int D, int METRIC>
+__device__ __forceinline__ void nearest_pattern(const uint4 (&x)[D / 8], const __half *M, int P, __half *tab, int tid,
+                                                int &best_i, float &best_d)
 {
     float bd = INFINITY;
-    int bi = 0x7fffffff;
-    for (int p = lane; p < P; p += 64) {
-        const float dist = metric_distance(xs, M + (int64_t)p * d, d, metric);
-        if (dist < bd) {
-            bd = dist;
-            bi = p;
-        }
-    }
+    int bi = 0;
+    for (int p0 = 0; p0 < P; p0 += kTabRows) {
+        const int np = min(kTabRows, P - p0);
+        __syncthreads();   // the previous chunk has been read
+        for (int k = tid; k < np * (D / 8); k += kGenThreads)
+            reinterpret_cast<uint4 *>(tab)[k] = reinterpret_cast<const uint4 *>(M + (int64_t)p0 * D)[k];
+        __syncthreads();
+        for (int p = 0; p < np; p += 4) {
+            const __half *m[4];
 #pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const float od = __shfl_xor(bd, off);
-        const int oi = __shfl_xor(bi, off);
-        if (od < bd || (od == bd && oi < bi)) {
-            bd = od;
-            bi = oi;
+            for (int j = 0; j < 4; ++j) m[j] = tab + min(p + j, np - 1) * D;   // rows past the chunk repeat its last one
+            float acc[4], mn[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                acc[j] = METRIC == PK_METRIC_MINMAX ? -INFINITY : 0.f;   // the running maximum under the min-max rule
+                mn[j] = INFINITY;
+            }
+#pragma unroll
+            for (int k = 0; k < D / 8; ++k) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint4 mv = *reinterpret_cast<const uint4 *>(m[j] + 8 * k);
+                    const uint32_t xw[4] = {x[k].x, x[k].y, x[k].z, x[k].w}, mw[4] = {mv.x, mv.y, mv.z, mv.w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float r0 = sub_lo(xw[e], mw[e]), r1 = sub_hi(xw[e], mw[e]);   // binary32 differences
+                        if (METRIC == PK_METRIC_MINMAX) {
+                            acc[j] = fmaxf(fmaxf(acc[j], r0), r1);
+                            mn[j] = fminf(fminf(mn[j], r0), r1);
+                        } else {
+                            acc[j] = fmaf(r0, r0, acc[j]);
+                            acc[j] = fmaf(r1, r1, acc[j]);
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float dist = METRIC == PK_METRIC_MINMAX ? acc[j] - mn[j] : acc[j];
+                if (p + j < np && dist < bd) {
+                    bd = dist;
+                    bi = p0 + p + j;
+                }
+            }
         }
     }
     best_i = bi;
@@ -77,21 +85,21 @@ __device__ __forceinline__ void wave_nearest(const __half *xs, const __half *M, 
 }
 
 // ---------------------------------------------------------------------------------------------- quantize-append
-// Pattern index of every vector to quantize: one wave per vector, four vectors per workgroup.
-__global__ __launch_bounds__(256) void gen_assign_kernel(QuantArgs a)
+// Pattern index of every vector to quantize: a workgroup takes 256 consecutive vectors of a stream.
+template <int D, int METRIC>
+__global__ __launch_bounds__(kGenThreads) void gen_assign_kernel(QuantArgs a)
 {
-    __shared__ __half xs[4][256];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, ns = blockIdx.y;
-    const int i = blockIdx.x * 4 + wave;
-    if (i >= a.nq) return;
-    const __half *row = a.src.row_d(ns, i, a.d);
-    for (int c = lane; c < a.d; c += 64) xs[wave][c] = row[c];
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
+    __shared__ __align__(16) __half tab[kTabRows * D];
+    const int tid = threadIdx.x, ns = blockIdx.y, i = blockIdx.x * kGenThreads + tid;
+    const bool live = i < a.nq;
+    uint4 x[D / 8];
+    const uint4 *row = reinterpret_cast<const uint4 *>(a.src.row_d(ns, live ? i : a.nq - 1, D));
+#pragma unroll
+    for (int k = 0; k < D / 8; ++k) x[k] = row[k];
     int bi;
     float bd;
-    wave_nearest(xs[wave], a.patterns + (int64_t)a.sets.set_of(ns) * a.P * a.d, a.P, a.d, a.metric, lane, bi, bd);
-    if (lane == 0) a.idx[a.map.pos(ns, a.t0 + i)] = (uint8_t)bi;
+    nearest_pattern<D, METRIC>(x, a.patterns + (int64_t)a.sets.set_of(ns) * a.P * D, a.P, tab, tid, bi, bd);
+    if (live) a.idx[a.map.pos(ns, a.t0 + i)] = (uint8_t)bi;
 }
 
 // K: one workgroup per (group of G tokens, stream), thread <-> channel.  Two passes over the group's residuals (the
@@ -129,17 +137,17 @@ __global__ __launch_bounds__(kGenThreads) void gen_quantize_k_kernel(QuantArgs a
     }
 }
 
-// V: one workgroup per (16-token unit, stream), thread <-> channel.  Per token: residual, the adaptive threshold of
-// Sec. 3.3 if it is on, minimum / maximum per group of Gc channels (one thread per group walks its channels in LDS),
-// parameters, code; every thread collects the bits of its channel's 16 tokens in the words it then stores.
+// V: one workgroup per (16-token unit, stream), thread <-> channel.  Per token: residual, minimum and maximum of
+// the residuals and of the vector over every 32 channels (cross-lane steps inside half a wave), the halves exchanged
+// through LDS (one barrier per token, two buffers in turn); from them every thread forms the adaptive threshold's
+// decision of Sec. 3.3 (whole vector) and the parameters of its own group of Gc channels (a multiple of 32), then
+// its code; a thread collects the bits of its channel's 16 tokens in the words it stores at the end.
 __global__ __launch_bounds__(kGenThreads) void gen_quantize_v_kernel(QuantArgs a)
 {
-    __shared__ float rs[kGenThreads], xr[kGenThreads];
-    __shared__ float pz[8], pinv[8], ps[8];
-    __shared__ int keep_s;
+    __shared__ float4 half_mm[2][kGenThreads / 32];   // per 32 channels: min r, max r, min x, max x
     const int c = threadIdx.x, ns = blockIdx.y, u = blockIdx.x, d = a.d;
     const bool on = c < d;
-    const int Gc = a.G < d ? a.G : d, NG = d / Gc;
+    const int Gc = a.G < d ? a.G : d, NG = d / Gc, g = on ? c / Gc : 0;
     const __half *M = a.patterns + (int64_t)a.sets.set_of(ns) * a.P * d;
     const int64_t p0 = a.map.pos(ns, a.t0 + u * 16);
     uint32_t word[2] = {0u, 0u};
@@ -150,50 +158,41 @@ __global__ __launch_bounds__(kGenThreads) void gen_quantize_v_kernel(QuantArgs a
             x = h2f(a.src.row_d(ns, u * 16 + i, d)[c]);
             r = x - h2f(M[(int64_t)idx * d + c]);
         }
-        __syncthreads();   // the previous token's parameters have been read
-        rs[c] = r;
-        xr[c] = x;
+        float rmn = on ? r : INFINITY, rmx = on ? r : -INFINITY, xmn = on ? x : INFINITY, xmx = on ? x : -INFINITY;
+#pragma unroll
+        for (int off = 1; off < 32; off <<= 1) {
+            rmn = fminf(rmn, __shfl_xor(rmn, off));
+            rmx = fmaxf(rmx, __shfl_xor(rmx, off));
+            xmn = fminf(xmn, __shfl_xor(xmn, off));
+            xmx = fmaxf(xmx, __shfl_xor(xmx, off));
+        }
+        float4(&hm)[kGenThreads / 32] = half_mm[i & 1];
+        if ((c & 31) == 0) hm[c >> 5] = make_float4(rmn, rmx, xmn, xmx);
         __syncthreads();
         if (a.v_rho > 0.f) {
-            if (c == 0) {
-                float rmn = INFINITY, rmx = -INFINITY, xmn = INFINITY, xmx = -INFINITY;
-                for (int k = 0; k < d; ++k) {
-                    rmn = fminf(rmn, rs[k]);
-                    rmx = fmaxf(rmx, rs[k]);
-                    xmn = fminf(xmn, xr[k]);
-                    xmx = fmaxf(xmx, xr[k]);
-                }
-                keep_s = (rmx - rmn) <= a.v_rho * (xmx - xmn) ? 1 : 0;
+            float4 row = hm[0];
+            for (int k = 1; k < d / 32; ++k) {
+                const float4 o = hm[k];
+                row = make_float4(fminf(row.x, o.x), fmaxf(row.y, o.y), fminf(row.z, o.z), fmaxf(row.w, o.w));
             }
-            __syncthreads();
-            if (!keep_s) {   // the vector itself is quantized, stored under the index that says so
-                idx = PK_NO_PATTERN;
+            if (!((row.y - row.x) <= a.v_rho * (row.w - row.z))) {   // the vector itself is quantized, stored under the
+                idx = PK_NO_PATTERN;                                 // index that says so
                 r = x;
-                __syncthreads();
-                rs[c] = r;
-                __syncthreads();
             }
         }
-        if (c < NG) {
-            float mn = INFINITY, mx = -INFINITY;
-            for (int k = c * Gc; k < (c + 1) * Gc; ++k) {
-                mn = fminf(mn, rs[k]);
-                mx = fmaxf(mx, rs[k]);
-            }
-            const GroupParams gp = group_params(mn, mx, a.bits);
-            pz[c] = gp.z;
-            ps[c] = gp.s;
-            pinv[c] = gp.inv;
-            a.scale[((p0 >> 4) * NG + c) * 16 + i] = __ushort_as_half(gp.s16);
-            a.zero[((p0 >> 4) * NG + c) * 16 + i] = __ushort_as_half(gp.z16);
+        float mn = INFINITY, mx = -INFINITY;
+        for (int k = g * (Gc / 32); k < (g + 1) * (Gc / 32); ++k) {
+            const float4 o = hm[k];
+            mn = fminf(mn, idx == PK_NO_PATTERN && a.v_rho > 0.f ? o.z : o.x);
+            mx = fmaxf(mx, idx == PK_NO_PATTERN && a.v_rho > 0.f ? o.w : o.y);
+        }
+        const GroupParams gp = group_params(mn, mx, a.bits);
+        if (on && c == g * Gc) {
+            a.scale[((p0 >> 4) * NG + g) * 16 + i] = __ushort_as_half(gp.s16);
+            a.zero[((p0 >> 4) * NG + g) * 16 + i] = __ushort_as_half(gp.z16);
         }
         if (c == 0) a.idx[p0 + i] = (uint8_t)idx;
-        __syncthreads();
         if (on) {
-            GroupParams gp;
-            gp.z = pz[c / Gc];
-            gp.s = ps[c / Gc];
-            gp.inv = pinv[c / Gc];
             const int code = quantize_one(r, gp, a.bits);
             for (int j = 0; j < a.bits; ++j) word[j >> 1] |= (uint32_t)((code >> j) & 1) << (16 * (j & 1) + i);
         }
@@ -228,21 +227,21 @@ __global__ __launch_bounds__(256) void gen_mine_init_kernel(MineArgs a)
     a.patterns[(int64_t)s * a.P * a.d + w] = a.x[(int64_t)s * a.set_stride + w];   // the first P vectors
 }
 
-// assignment step: one wave per vector
-__global__ __launch_bounds__(256) void gen_mine_assign_kernel(MineArgs a, int last)
+// assignment step: a workgroup takes 256 consecutive vectors of a set
+template <int D>
+__global__ __launch_bounds__(kGenThreads) void gen_mine_assign_kernel(MineArgs a, int last)
 {
-    __shared__ __half xs[4][256];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, s = blockIdx.y;
-    const int t = blockIdx.x * 4 + wave;
-    if (t >= a.T) return;
-    const __half *row = a.x + (int64_t)s * a.set_stride + (int64_t)t * a.d;
-    for (int c = lane; c < a.d; c += 64) xs[wave][c] = row[c];
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
+    __shared__ __align__(16) __half tab[kTabRows * D];
+    const int tid = threadIdx.x, s = blockIdx.y, t = blockIdx.x * kGenThreads + tid;
+    const bool live = t < a.T;
+    uint4 x[D / 8];
+    const uint4 *row = reinterpret_cast<const uint4 *>(a.x + (int64_t)s * a.set_stride + (int64_t)(live ? t : a.T - 1) * D);
+#pragma unroll
+    for (int k = 0; k < D / 8; ++k) x[k] = row[k];
     int bi;
     float bd;
-    wave_nearest(xs[wave], a.patterns + (int64_t)s * a.P * a.d, a.P, a.d, PK_METRIC_L2, lane, bi, bd);
-    if (lane == 0) {
+    nearest_pattern<D, PK_METRIC_L2>(x, a.patterns + (int64_t)s * a.P * D, a.P, tab, tid, bi, bd);
+    if (live) {
         a.assign_ws[(int64_t)s * a.T + t] = bi;
         if (last && a.assign) a.assign[(int64_t)s * a.T + t] = bi;
         a.best[(int64_t)s * a.T + t] = bd;
@@ -361,98 +360,388 @@ __global__ __launch_bounds__(kGenThreads) void gen_dequant_kernel(DequantArgs a)
 }
 
 // ---------------------------------------------------------------------------------------------- decode
-// One workgroup per (sequence, query head): the context [prefix packed | prefix tail | own packed | own tail] in
-// chunks of 256 tokens.  Scores: thread <-> token (the reconstructed key against q, channel by channel); online
-// softmax over the chunks; values: thread <-> channel over the chunk's tokens.  Everything in binary32.
-__global__ __launch_bounds__(kGenThreads) void gen_decode_kernel(DecodeArgs a)
+// Decode attention (Sec. 3.4) in plain vector arithmetic.  The context of a stream is cut into the same slots as in
+// the tuned path (equal splits of the shared prefix's packed part, of the own packed part, then the own tail and
+// the prefix's tail); a workgroup takes one slot of one stream for all r <= R query heads of the KV head at once, so
+// the codes are taken apart once for all of them, and leaves an unnormalised partial (o, per-pattern softmax mass
+// W, running maximum m in the log2 domain, sum l); a second kernel merges the partials and adds W . M_V once per
+// head.  Scores: thread <-> token, score = q.M_K[k*] (a table formed once per workgroup) + sum_c q_c (s_c code_c +
+// z_c).  Values: thread <-> channel over the tokens of the pass, o += p_t (s_t code_tc + z_t).  The reference of
+// the online softmax is the running maximum; when a pass raises it, o, l and W are rescaled.  W is summed in LDS
+// as 64-bit fixed point (unit 2^-31, weights are <= 1) with integer atomics, so the result does not depend on the
+// order in which the tokens arrive.
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kMassUnit = 2147483648.f;   // 2^31
+constexpr int kPass = kGenThreads;           // tokens per pass
+
+__device__ __forceinline__ float half_of(const uint4 &v, int e)   // element e (0..7) of eight packed fp16
 {
-    __shared__ float qs[kGenThreads], pr[kGenThreads], red[kGenThreads];
-    const int tid = threadIdx.x, d = a.d;
-    const int seq = blockIdx.x / a.n_q_heads, qh = blockIdx.x - seq * a.n_q_heads;
-    const int r = a.n_q_heads / a.n_kv_heads, head = qh / r;
-    const int n_own = seq * a.n_kv_heads + head;
-    const int Gc = a.G < d ? a.G : d;
-    if (tid < d) qs[tid] = h2f(a.q[((int64_t)seq * a.n_q_heads + qh) * d + tid]);
+    const uint32_t w = e < 2 ? v.x : e < 4 ? v.y : e < 6 ? v.z : v.w;
+    return h2f(__ushort_as_half((unsigned short)((e & 1) ? w >> 16 : w & 0xffffu)));
+}
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+    return v;
+}
+
+// LDS of a split workgroup, in this order (the 8-byte arrays first)
+struct GenDecodeLds {
+    unsigned long long *W;   // [P][R]   softmax mass per V pattern and head, fixed point
+    long long *pos;          // [kPass]  packed position (or tail ring row) of the pass's tokens
+    float *qf;               // [d][R]   the queries, channel-major; heads beyond r are zero
+    float *QM;               // [P][R]   q . M_K[p]
+    float *sc;               // [kPass][R] softmax numerators of the pass
+    float *red;              // [4][R]
+    __device__ GenDecodeLds(unsigned char *base, int d, int P, int R)
+    {
+        W = reinterpret_cast<unsigned long long *>(base);
+        pos = reinterpret_cast<long long *>(W + (size_t)P * R);
+        qf = reinterpret_cast<float *>(pos + kPass);
+        QM = qf + (size_t)d * R;
+        sc = QM + (size_t)P * R;
+        red = sc + (size_t)kPass * R;
+    }
+};
+inline size_t gen_decode_lds_bytes(int d, int P, int R)
+{
+    return (size_t)P * R * 8 + (size_t)kPass * 8 + ((size_t)d * R + (size_t)P * R + (size_t)kPass * R + 4 * R) * 4;
+}
+
+template <int R, int BITS>
+__global__ __launch_bounds__(kGenThreads) void gen_decode_split_kernel(DecodeArgs a)
+{
+    extern __shared__ __align__(16) unsigned char gen_decode_smem[];
+    const int tid = threadIdx.x, d = a.d, P = a.P;
+    const GenDecodeLds lds(gen_decode_smem, d, P, R);
+    const int n = blockIdx.x, slot = blockIdx.y;
+    const int seq = n / a.n_kv_heads, head = n - seq * a.n_kv_heads;
+    const int r = a.n_q_heads / a.n_kv_heads, nh = min(R, r);   // r <= 8 by the configuration check
+    const int n_packed = a.splits_prefix + a.splits_own, n_slots = n_packed + 2;
+    const bool packed = slot < n_packed;
+    const bool pre = slot < a.splits_prefix || slot == n_packed + 1;
+    const CacheView &cv = pre ? a.prefix : a.own;
+    int tq = cv.t_quant, tt = cv.t_tail, ts = cv.tail_start;
+    if (!pre) own_state(a, seq, tq, tt, ts);
+    const int stream = pre ? head : n;
+    const int set = pre ? head : a.sets.set_of(n);
+    int t_begin = 0, t_end = tt;
+    if (packed) {
+        t_begin = (pre ? slot : slot - a.splits_prefix) * a.chunk;
+        t_end = min(tq, t_begin + a.chunk);
+    }
+    const int64_t pb = ((int64_t)n * n_slots + slot) * r;   // partial of the KV head's first query head
+    if (t_end <= t_begin) {   // nothing in this slot: the merge skips partials whose sum is zero
+        if (tid < nh) {
+            a.part_ml[(pb + tid) * 2] = -INFINITY;
+            a.part_ml[(pb + tid) * 2 + 1] = 0.f;
+        }
+        return;
+    }
+    const int Gc = a.G < d ? a.G : d, ng = d / Gc;
+    const float scale2 = a.softmax_scale * kLog2e;
+
+    for (int i = tid; i < d * R; i += kGenThreads) {
+        const int c = i / R, h = i - c * R;
+        lds.qf[i] = h < nh ? h2f(a.q[((int64_t)seq * a.n_q_heads + head * r + h) * d + c]) : 0.f;
+    }
+    for (int i = tid; i < P * R; i += kGenThreads) lds.W[i] = 0ull;
     __syncthreads();
-    float m_run = -INFINITY, l_run = 0.f, acc = 0.f;
-    for (int part = 0; part < 4; ++part) {
-        const bool pre = part < 2, packed = (part & 1) == 0;
-        const CacheView &cv = pre ? a.prefix : a.own;
-        const int stream = pre ? head : n_own;
-        const int set = pre ? head : a.sets.set_of(n_own);
-        int tq = cv.t_quant, tt = cv.t_tail, ts = cv.tail_start;
-        if (!pre) own_state(a, seq, tq, tt, ts);
-        const int n_tok = packed ? tq : tt;
-        const __half *MK = a.patterns_k + (int64_t)set * a.P * d, *MV = a.patterns_v + (int64_t)set * a.P * d;
-        for (int t0 = 0; t0 < n_tok; t0 += kGenThreads) {
-            const int t = t0 + tid;
-            float sc = -INFINITY;
-            int64_t where = 0;   // packed position, or row of the tail ring
-            if (t < n_tok) {
-                float dot = 0.f;
-                if (packed) {
-                    where = cv.map.pos(stream, t);
-                    for (int c = 0; c < d; ++c) dot = fmaf(qs[c], k_hat(cv, MK, where, c, d, a.bits, a.G), dot);
-                } else {
-                    int slot = ts + t;
-                    if (slot >= cv.ring_len) slot -= cv.ring_len;
-                    where = (int64_t)stream * cv.ring_len + slot;
-                    for (int c = 0; c < d; ++c) dot = fmaf(qs[c], h2f(cv.tail_k[where * d + c]), dot);
+    if (packed) {
+        const __half *MK = a.patterns_k + (int64_t)set * P * d;
+        for (int p = tid; p < P; p += kGenThreads) {
+            float s[R];
+#pragma unroll
+            for (int h = 0; h < R; ++h) s[h] = 0.f;
+            for (int c8 = 0; c8 < d / 8; ++c8) {
+                const uint4 mv = *reinterpret_cast<const uint4 *>(MK + (int64_t)p * d + 8 * c8);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float x = half_of(mv, e);
+#pragma unroll
+                    for (int h = 0; h < R; ++h) s[h] = fmaf(lds.qf[(8 * c8 + e) * R + h], x, s[h]);
                 }
-                sc = dot * a.softmax_scale;
             }
-            // chunk maximum
-            red[tid] = sc;
-            __syncthreads();
-            for (int w = kGenThreads / 2; w > 0; w >>= 1) {
-                if (tid < w) red[tid] = fmaxf(red[tid], red[tid + w]);
-                __syncthreads();
-            }
-            const float m_new = fmaxf(m_run, red[0]);
-            __syncthreads();
-            const float p = t < n_tok ? __expf(sc - m_new) : 0.f;
-            pr[tid] = p;
-            red[tid] = p;
-            // the positions of the chunk's tokens, for the value phase
-            __syncthreads();
-            for (int w = kGenThreads / 2; w > 0; w >>= 1) {
-                if (tid < w) red[tid] += red[tid + w];
-                __syncthreads();
-            }
-            const float alpha = m_run == -INFINITY ? 0.f : __expf(m_run - m_new);
-            l_run = l_run * alpha + red[0];
-            acc *= alpha;
-            m_run = m_new;
-            if (tid < d) {
-                const int n_here = min(kGenThreads, n_tok - t0);
-                for (int k = 0; k < n_here; ++k) {
-                    const int tk = t0 + k;
-                    float v;
-                    if (packed) {
-                        v = v_hat(cv, MV, cv.map.pos(stream, tk), tid, d, a.bits, Gc, a.v_thresholded);
-                    } else {
-                        int slot = ts + tk;
-                        if (slot >= cv.ring_len) slot -= cv.ring_len;
-                        v = h2f(cv.tail_v[((int64_t)stream * cv.ring_len + slot) * d + tid]);
+#pragma unroll
+            for (int h = 0; h < R; ++h) lds.QM[p * R + h] = s[h];
+        }
+        __syncthreads();
+    }
+
+    float m_run[R], l_thr[R], acc[R];
+#pragma unroll
+    for (int h = 0; h < R; ++h) {
+        m_run[h] = -INFINITY;
+        l_thr[h] = 0.f;
+        acc[h] = 0.f;
+    }
+    // value phase: thread <-> (channel, sub); the subs take the 16-token blocks (tail tokens) of a pass in turn
+    const int n_sub = kGenThreads / d;
+    const int vsub = tid / d, vc = tid - vsub * d;
+    const bool v_active = vsub < n_sub;
+    const uint32_t *vwords = reinterpret_cast<const uint32_t *>(cv.v_codes);
+
+    for (int t0 = t_begin; t0 < t_end; t0 += kPass) {
+        const int t = t0 + tid;
+        const bool live = t < t_end;
+        float s[R];
+        int64_t where = 0;
+#pragma unroll
+        for (int h = 0; h < R; ++h) s[h] = -INFINITY;
+        if (live && packed) {
+            where = cv.map.pos(stream, t);
+            const int idx = min((int)cv.k_idx[where], P - 1);
+#pragma unroll
+            for (int h = 0; h < R; ++h) s[h] = lds.QM[idx * R + h];
+            const int64_t prow = (where / a.G) * d;
+            for (int w = 0; w < d / 32; ++w) {
+                uint32_t pl[BITS];
+#pragma unroll
+                for (int j = 0; j < BITS; ++j) pl[j] = cv.k_codes[(where * (d / 32) + w) * BITS + j];
+#pragma unroll
+                for (int o = 0; o < 4; ++o) {
+                    const uint4 sv = *reinterpret_cast<const uint4 *>(cv.k_scale + prow + 32 * w + 8 * o);
+                    const uint4 zv = *reinterpret_cast<const uint4 *>(cv.k_zero + prow + 32 * w + 8 * o);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const int cc = 8 * o + e;
+                        uint32_t code = 0;
+#pragma unroll
+                        for (int j = 0; j < BITS; ++j) code |= ((pl[j] >> cc) & 1u) << j;
+                        const float val = half_of(sv, e) * (float)code + half_of(zv, e);
+#pragma unroll
+                        for (int h = 0; h < R; ++h) s[h] = fmaf(lds.qf[(32 * w + cc) * R + h], val, s[h]);
                     }
-                    acc = fmaf(pr[k], v, acc);
                 }
             }
-            __syncthreads();
+        } else if (live) {
+            int sl = ts + t;
+            if (sl >= cv.ring_len) sl -= cv.ring_len;
+            where = (int64_t)stream * cv.ring_len + sl;
+#pragma unroll
+            for (int h = 0; h < R; ++h) s[h] = 0.f;
+            for (int c8 = 0; c8 < d / 8; ++c8) {
+                const uint4 kv = *reinterpret_cast<const uint4 *>(cv.tail_k + where * d + 8 * c8);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float x = half_of(kv, e);
+#pragma unroll
+                    for (int h = 0; h < R; ++h) s[h] = fmaf(lds.qf[(8 * c8 + e) * R + h], x, s[h]);
+                }
+            }
+        }
+        // maximum of the pass per head
+#pragma unroll
+        for (int h = 0; h < R; ++h) {
+            s[h] *= scale2;   // -inf stays -inf
+            const float wm = wave_max(s[h]);
+            if ((tid & 63) == 0) lds.red[(tid >> 6) * R + h] = wm;
+        }
+        lds.pos[tid] = where;
+        __syncthreads();
+        bool raised = false;   // the same in every thread
+        float alpha[R];
+#pragma unroll
+        for (int h = 0; h < R; ++h) {
+            const float pm = fmaxf(fmaxf(lds.red[h], lds.red[R + h]), fmaxf(lds.red[2 * R + h], lds.red[3 * R + h]));
+            alpha[h] = 1.f;
+            if (pm > m_run[h]) {
+                alpha[h] = exp2f(m_run[h] - pm);   // 0 the first time
+                m_run[h] = pm;
+                raised = true;
+            }
+        }
+        if (raised) {
+#pragma unroll
+            for (int h = 0; h < R; ++h) {
+                acc[h] *= alpha[h];
+                l_thr[h] *= alpha[h];
+            }
+            if (packed) {
+                for (int p = tid; p < P; p += kGenThreads) {
+#pragma unroll
+                    for (int h = 0; h < R; ++h)
+                        lds.W[p * R + h] = (unsigned long long)((double)lds.W[p * R + h] * (double)alpha[h]);
+                }
+                __syncthreads();   // before this pass's atomics
+            }
+        }
+        float pw[R];
+#pragma unroll
+        for (int h = 0; h < R; ++h) {
+            pw[h] = live ? exp2f(s[h] - m_run[h]) : 0.f;
+            l_thr[h] += pw[h];
+            lds.sc[tid * R + h] = pw[h];
+        }
+        if (live && packed) {
+            const int vi = cv.v_idx[where];
+            if (!(a.v_thresholded && vi == PK_NO_PATTERN)) {   // a token quantized without a pattern carries no mass
+                const int vp = min(vi, P - 1);
+#pragma unroll
+                for (int h = 0; h < R; ++h) atomicAdd(&lds.W[vp * R + h], (unsigned long long)(pw[h] * kMassUnit));
+            }
+        }
+        __syncthreads();
+
+        const int n_here = min(kPass, t_end - t0);
+        if (v_active && packed) {
+            for (int b = vsub; 16 * b < n_here; b += n_sub) {
+                const int64_t w0 = lds.pos[16 * b];   // the 16 tokens of a block are stored together
+                const int64_t word = (((w0 >> 4) * 16 + (vc & 15)) * (d / 16) + (vc >> 4)) * (BITS / 2);
+                uint32_t cw[BITS / 2];
+#pragma unroll
+                for (int j = 0; j < BITS / 2; ++j) cw[j] = vwords[word + j];
+                const int64_t prow = ((w0 >> 4) * ng + vc / Gc) * 16;
+                const uint4 sv[2] = {*reinterpret_cast<const uint4 *>(cv.v_scale + prow),
+                                     *reinterpret_cast<const uint4 *>(cv.v_scale + prow + 8)};
+                const uint4 zv[2] = {*reinterpret_cast<const uint4 *>(cv.v_zero + prow),
+                                     *reinterpret_cast<const uint4 *>(cv.v_zero + prow + 8)};
+#pragma unroll
+                for (int k = 0; k < 16; ++k) {
+                    uint32_t code = 0;
+#pragma unroll
+                    for (int j = 0; j < BITS; ++j) code |= ((cw[j / 2] >> (16 * (j % 2) + k)) & 1u) << j;
+                    const float val = half_of(sv[k >> 3], k & 7) * (float)code + half_of(zv[k >> 3], k & 7);
+#pragma unroll
+                    for (int h = 0; h < R; ++h) acc[h] = fmaf(lds.sc[(16 * b + k) * R + h], val, acc[h]);
+                }
+            }
+        } else if (v_active) {
+            for (int k = vsub; k < n_here; k += n_sub) {
+                const float val = h2f(cv.tail_v[lds.pos[k] * d + vc]);
+#pragma unroll
+                for (int h = 0; h < R; ++h) acc[h] = fmaf(lds.sc[k * R + h], val, acc[h]);
+            }
+        }
+        __syncthreads();   // sc and pos are rewritten by the next pass
+    }
+
+    // the partial: sums over the threads in a fixed order
+#pragma unroll
+    for (int h = 0; h < R; ++h) {
+        const float ws = wave_sum(l_thr[h]);
+        if ((tid & 63) == 0) lds.red[(tid >> 6) * R + h] = ws;
+    }
+    if (v_active && vsub > 0) {
+#pragma unroll
+        for (int h = 0; h < R; ++h) lds.sc[(vsub * d + vc) * R + h] = acc[h];
+    }
+    __syncthreads();
+    if (tid < d) {
+        for (int k = 1; k < n_sub; ++k) {
+#pragma unroll
+            for (int h = 0; h < R; ++h) acc[h] += lds.sc[(k * d + tid) * R + h];
+        }
+#pragma unroll
+        for (int h = 0; h < R; ++h)
+            if (h < nh) a.part_o[(pb + h) * d + tid] = acc[h];
+    }
+    if (packed) {
+        for (int p = tid; p < P; p += kGenThreads) {
+#pragma unroll
+            for (int h = 0; h < R; ++h)
+                if (h < nh) a.part_w[(pb + h) * P + p] = (float)lds.W[p * R + h] * (1.f / kMassUnit);
         }
     }
-    const int64_t u = (int64_t)seq * a.n_q_heads + qh;
-    if (tid < d) a.out[u * d + tid] = l_run > 0.f ? acc / l_run : 0.f;
-    if (a.lse && tid == 0) a.lse[u] = l_run > 0.f ? m_run + __logf(l_run) : -INFINITY;
+#pragma unroll
+    for (int h = 0; h < R; ++h) {
+        if (tid == h && h < nh) {
+            a.part_ml[(pb + h) * 2] = m_run[h];
+            a.part_ml[(pb + h) * 2 + 1] = (lds.red[h] + lds.red[R + h]) + (lds.red[2 * R + h] + lds.red[3 * R + h]);
+        }
+    }
+}
+
+// log-sum-exp merge of the partials of one (sequence, query head) and the pattern part of the values, W . M_V
+__global__ __launch_bounds__(kGenThreads) void gen_decode_merge_kernel(DecodeArgs a)
+{
+    __shared__ float wslot[kMaxSlots];
+    __shared__ float Wsum[2][kGenThreads];   // shared prefix, own cache
+    __shared__ float red[8];
+    const int u = blockIdx.x, tid = threadIdx.x, d = a.d, P = a.P;
+    const int seq = u / a.n_q_heads, qh = u - seq * a.n_q_heads;
+    const int r = a.n_q_heads / a.n_kv_heads, head = qh / r, hr = qh - head * r;
+    const int n = seq * a.n_kv_heads + head;
+    const int n_packed = a.splits_prefix + a.splits_own, n_slots = n_packed + 2;
+    const int64_t base = (int64_t)n * n_slots;
+    float M = -INFINITY;
+    for (int s = tid; s < n_slots; s += kGenThreads) {
+        const int64_t q = ((base + s) * r + hr) * 2;
+        if (a.part_ml[q + 1] > 0.f) M = fmaxf(M, a.part_ml[q]);
+    }
+    M = wave_max(M);
+    if ((tid & 63) == 0) red[tid >> 6] = M;
+    __syncthreads();
+    M = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    float L = 0.f;
+    for (int s = tid; s < n_slots; s += kGenThreads) {
+        const int64_t q = ((base + s) * r + hr) * 2;
+        const float l = a.part_ml[q + 1];
+        const float w = l > 0.f ? exp2f(a.part_ml[q] - M) : 0.f;
+        wslot[s] = w;
+        L = fmaf(l, w, L);
+    }
+    L = wave_sum(L);
+    if ((tid & 63) == 0) red[4 + (tid >> 6)] = L;
+    __syncthreads();
+    L = (red[4] + red[5]) + (red[6] + red[7]);
+    for (int p = tid; p < P; p += kGenThreads) {
+        float wp = 0.f, wo = 0.f;
+        for (int s = 0; s < a.splits_prefix; ++s)
+            if (wslot[s] > 0.f) wp = fmaf(a.part_w[((base + s) * r + hr) * P + p], wslot[s], wp);
+        for (int s = a.splits_prefix; s < n_packed; ++s)
+            if (wslot[s] > 0.f) wo = fmaf(a.part_w[((base + s) * r + hr) * P + p], wslot[s], wo);
+        Wsum[0][p] = wp;
+        Wsum[1][p] = wo;
+    }
+    __syncthreads();
+    if (tid >= d) return;
+    float acc = 0.f;
+    for (int s = 0; s < n_slots; ++s)
+        if (wslot[s] > 0.f) acc = fmaf(a.part_o[((base + s) * r + hr) * d + tid], wslot[s], acc);
+    if (a.splits_prefix > 0) {
+        const __half *MV = a.patterns_v + (int64_t)head * P * d;
+        for (int p = 0; p < P; ++p) acc = fmaf(Wsum[0][p], h2f(MV[(int64_t)p * d + tid]), acc);
+    }
+    if (a.splits_own > 0) {
+        const __half *MV = a.patterns_v + (int64_t)a.sets.set_of(n) * P * d;
+        for (int p = 0; p < P; ++p) acc = fmaf(Wsum[1][p], h2f(MV[(int64_t)p * d + tid]), acc);
+    }
+    a.out[(int64_t)u * d + tid] = L > 0.f ? acc / L : 0.f;
+    if (a.lse && tid == 0) a.lse[u] = L > 0.f ? (M + log2f(L)) * kLn2 : -INFINITY;
+}
+
+template <int R>
+hipError_t launch_gen_decode_split(const DecodeArgs &a, dim3 grid, size_t lds, hipStream_t s)
+{
+    if (a.bits == 2)
+        hipLaunchKernelGGL((gen_decode_split_kernel<R, 2>), grid, dim3(kGenThreads), lds, s, a);
+    else
+        hipLaunchKernelGGL((gen_decode_split_kernel<R, 4>), grid, dim3(kGenThreads), lds, s, a);
+    return hipGetLastError();
 }
 
 }  // namespace
 
 // ---------------------------------------------------------------------------------------------- launchers
+template <int D>
+static hipError_t launch_gen_assign(const QuantArgs &a, hipStream_t s)
+{
+    const dim3 grid((a.nq + kGenThreads - 1) / kGenThreads, a.n_streams);
+    if (a.metric == PK_METRIC_MINMAX)
+        hipLaunchKernelGGL((gen_assign_kernel<D, PK_METRIC_MINMAX>), grid, dim3(kGenThreads), 0, s, a);
+    else
+        hipLaunchKernelGGL((gen_assign_kernel<D, PK_METRIC_L2>), grid, dim3(kGenThreads), 0, s, a);
+    return hipGetLastError();
+}
+
 hipError_t launch_generic_quantize(const QuantArgs &a, bool v_side, hipStream_t s)
 {
-    hipLaunchKernelGGL(gen_assign_kernel, dim3((a.nq + 3) / 4, a.n_streams), dim3(256), 0, s, a);
-    hipError_t e = hipGetLastError();
+    if (a.nq <= 0) return hipSuccess;
+    if (a.d != 96 && a.d != 256) return hipErrorInvalidValue;
+    hipError_t e = a.d == 96 ? launch_gen_assign<96>(a, s) : launch_gen_assign<256>(a, s);
     if (e != hipSuccess) return e;
     if (v_side)
         hipLaunchKernelGGL(gen_quantize_v_kernel, dim3(a.nq / 16, a.n_streams), dim3(kGenThreads), 0, s, a);
@@ -478,7 +767,11 @@ hipError_t launch_generic_mine(const MineArgs &a, hipStream_t s)
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     for (int it = 0; it < a.iters; ++it) {
-        hipLaunchKernelGGL(gen_mine_assign_kernel, dim3((a.T + 3) / 4, a.n_sets), dim3(256), 0, s, a, it == a.iters - 1 ? 1 : 0);
+        const dim3 agrid((a.T + kGenThreads - 1) / kGenThreads, a.n_sets);
+        if (a.d == 96)
+            hipLaunchKernelGGL(gen_mine_assign_kernel<96>, agrid, dim3(kGenThreads), 0, s, a, it == a.iters - 1 ? 1 : 0);
+        else
+            hipLaunchKernelGGL(gen_mine_assign_kernel<256>, agrid, dim3(kGenThreads), 0, s, a, it == a.iters - 1 ? 1 : 0);
         if ((e = hipGetLastError()) != hipSuccess) return e;
         if (a.inertia) {
             hipLaunchKernelGGL(gen_mine_inertia_kernel, dim3(a.n_sets), dim3(256), 0, s, a, it);
@@ -501,7 +794,18 @@ hipError_t launch_generic_window_pattern(const __half *x, int64_t set_stride, in
 
 hipError_t launch_generic_decode(const DecodeArgs &a, hipStream_t s)
 {
-    hipLaunchKernelGGL(gen_decode_kernel, dim3(a.n_seq * a.n_q_heads), dim3(kGenThreads), 0, s, a);
+    // heads of a KV head per workgroup: the power of two that holds them (r <= 8 by the configuration check)
+    const int r = a.n_q_heads / a.n_kv_heads;
+    if (r > 8) return hipErrorInvalidValue;
+    const int R = r > 4 ? 8 : r > 2 ? 4 : r > 1 ? 2 : 1;
+    const dim3 grid(a.n_seq * a.n_kv_heads, a.splits_prefix + a.splits_own + 2);
+    const size_t lds = gen_decode_lds_bytes(a.d, a.P, R);
+    hipError_t e = R == 8   ? launch_gen_decode_split<8>(a, grid, lds, s)
+                   : R == 4 ? launch_gen_decode_split<4>(a, grid, lds, s)
+                   : R == 2 ? launch_gen_decode_split<2>(a, grid, lds, s)
+                            : launch_gen_decode_split<1>(a, grid, lds, s);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(gen_decode_merge_kernel, dim3(a.n_seq * a.n_q_heads), dim3(kGenThreads), 0, s, a);
     return hipGetLastError();
 }
 

@@ -87,6 +87,20 @@ struct SetMap {
 __device__ __forceinline__ float h2f(__half h) { return __half2float(h); }
 __device__ __forceinline__ float hbits2f(unsigned short u) { return __half2float(__ushort_as_half(u)); }
 
+// Differences with one rounding, as the binary32 subtraction of the widened values: v_fma_mix_f32
+// computes a*1.0 + (-b) with fp16 sources widened exactly.
+__device__ __forceinline__ float sub_lo(uint32_t x, uint32_t m)   // half(x.lo) - half(m.lo)
+{
+    float r;
+    asm("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel:[0,0,0] op_sel_hi:[1,0,1]" : "=v"(r) : "v"(x), "v"(m));
+    return r;
+}
+__device__ __forceinline__ float sub_hi(uint32_t x, uint32_t m)   // half(x.hi) - half(m.hi)
+{
+    float r;
+    asm("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel:[1,0,1] op_sel_hi:[1,0,1]" : "=v"(r) : "v"(x), "v"(m));
+    return r;
+}
 // largest binary16 value <= f
 __device__ __forceinline__ unsigned short f2h_down(float f)
 {

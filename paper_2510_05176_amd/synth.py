@@ -101,6 +101,9 @@ def make_queries(seed: int, n_seq: int, n_q_heads: int, d: int):
 SPECS = {
     "cfg1": KVSpec(1, 1, 1, 1, 1024, 128, 16, 0.3, 0.5, 4, 8.0),
     "cfg2": KVSpec(1, 1, 8, 32, 8192, 128, 32, 0.3, 0.5, 4, 8.0),
+    # config 2's layer at the other two head sizes that Sec. 3.3 names
+    "cfg2_d96": KVSpec(1, 1, 8, 32, 8192, 96, 32, 0.3, 0.5, 4, 8.0),
+    "cfg2_d256": KVSpec(1, 1, 8, 32, 8192, 256, 32, 0.3, 0.5, 4, 8.0),
     "cfg3": KVSpec(32, 16, 8, 32, 32768, 128, 32, 0.3, 0.5, 4, 8.0),
     "cfg4": KVSpec(1, 64, 8, 32, 8192, 128, 32, 0.3, 0.5, 4, 8.0, drift_sigma=0.05, drift_chunk=128),
     "cfg5": KVSpec(1, 1, 4, 28, 131072, 128, 256, 0.3, 0.5, 8, 10.0),

@@ -908,3 +908,45 @@ def test_other_head_dimensions_parity(oracle, pk, d, G, bits, P, metric, R, rho,
     got = pk.pk_decode_attention(pk.Config(**kw), gc, dev(q), d ** -0.5, Mkd, Mvd, lse=lse, prefix=gp).cpu().numpy()
     assert_attention(got, want)
     assert np.abs(lse.cpu().numpy() - want_lse).max() <= 2e-3
+
+
+@pytest.mark.parametrize("d,hkv,hq,bits,G,P,R,lens", [
+    (96, 2, 6, 2, 32, 16, 32, [0, 70, 1500, 517]),      # r = 3 (padded to four), empty and tail-only sequences, several splits
+    (256, 1, 8, 4, 64, 8, 0, [1024, 333]),              # r = 8, 4-bit
+    (256, 2, 2, 2, 128, 32, 40, [2048, 900, 129]),      # r = 1, groups of 128 tokens
+    (96, 1, 7, 2, 128, 24, 0, [1100, 1100]),            # r = 7, one V group of all 96 channels
+])
+def test_other_head_dimensions_decode_splits(oracle, pk, d, hkv, hq, bits, G, P, R, lens):
+    """Decode at head dimensions 96 and 256 over contexts of several splits and passes, with per-sequence fill states
+    (splits past a sequence's end, sequences with only a tail or nothing), query-head counts that are no power of two, against the oracle; the uniform entry point on the longest sequence gives
+    the ragged one's result bit for bit."""
+    S, T = len(lens), max(lens)
+    F = max(G, 64)
+    kw = dict(n_kv_heads=hkv, n_q_heads=hq, head_dim=d, n_patterns=P, bits=bits, group=G, recent=R, flush=F,
+              t_capacity=-(-T // F) * F, metric=0)
+    K, V = synth.make_kv(700 + d + P, synth.KVSpec(1, S, hkv, hq, T, d, 12))
+    Mk, _, _, _ = oracle.mine(K[0].view(np.uint16), P, 2)
+    Mv, _, _, _ = oracle.mine(V[0].view(np.uint16), P, 2)
+    gcfg, gc, ocs, states, Mkd, Mvd = _ragged_batch(oracle, pk, kw, K, V, Mk, Mv, lens)
+    q = synth.make_queries(37, S, hq, d)
+    want, want_lse = oracle.decode_attention_ragged(ocs, q.view(np.uint16), Mk, Mv, d ** -0.5)
+    st = torch.tensor(states, dtype=torch.int32, device="cuda")
+    bq, bt = max(s[0] for s in states), max(s[1] for s in states)
+    split_tokens, n_slots, _ = pk.pk_decode_plan(gcfg, bq, 0)
+    assert n_slots >= 4 or T < 1024             # the long cases run several packed splits
+    lse = torch.empty((S, hq), dtype=torch.float32, device="cuda")
+    got = pk.pk_decode_attention_ragged(gcfg, gc, st, bq, bt, dev(q), d ** -0.5, Mkd, Mvd, lse=lse).cpu().numpy()
+    glse = lse.cpu().numpy()
+    for i, n in enumerate(lens):
+        if n == 0:
+            assert np.all(got[i] == 0) and np.all(np.isneginf(glse[i]))
+        else:
+            assert_attention(got[i], want[i])
+            assert np.abs(glse[i] - want_lse[i]).max() <= 2e-3
+    again = pk.pk_decode_attention_ragged(gcfg, gc, st, bq, bt, dev(q), d ** -0.5, Mkd, Mvd).cpu().numpy()
+    assert np.array_equal(again, got)           # fixed-point masses and fixed summation orders: reproducible
+    big = int(np.argmax([s[0] for s in states]))
+    full = gc.sequence(big)
+    full.state = pk._State(*states[big][:3])
+    one = pk.pk_decode_attention(full.cfg, full, dev(q[big:big + 1]), d ** -0.5, Mkd, Mvd).cpu().numpy()
+    assert_attention(one[0], want[big])

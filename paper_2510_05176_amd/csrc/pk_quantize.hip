@@ -10,7 +10,7 @@
 //
 // Kernels, in file order: assign_minmax_kernel (the min-max selection rule of Sec. 3.2 as a search of its own: it
 // writes the indices and the quantizers below then take them as given); quantize_k_kernel (groups of 128 tokens,
-// a workgroup per tile) and quantize_k_wave_kernel (groups of 32 / 64 tokens, a wave per group); quantize_v_kernel
+// a workgroup of eight waves per tile) and quantize_k_wave_kernel (groups of 32 / 64 tokens, a wave per group); quantize_v_kernel
 // (a wave per 16-token unit); tail_copy_kernel (the fp16 ring); seq_table_kernel (per-sequence launch parameters
 // of a ragged append).  Under the Euclidean rule the quantizers search on the matrix cores (pk_assign_mfma.h).
 #pragma clang fp contract(off)
@@ -193,7 +193,7 @@ struct TileShared {
     __half *tab;      // [pad16(P)][kTabStride]
     float *nh;        // [pad16(P)]
     unsigned char *wsc;   // V: [4 waves][kWaveScratch] (re-evaluation row, output staging)
-    float *red;       // [4]
+    float *red;       // [8]: one maximum per wave from stage_patterns
     float *rt;        // K: [TT][kRStride]
     uint16_t *pz;     // K: [TT/G][kD] zero points (fp16 bits), then [TT/G][kD] scales
     float *pinv;      // K: [TT/G][kD] 1/s
@@ -215,7 +215,7 @@ __host__ __device__ inline size_t carve_offsets(int P, int TT, int G, size_t (&o
     o[0] = at; at += (size_t)pad16(P) * kTabStride * 2;
     o[1] = at; at += (size_t)pad16(P) * 4;
     o[2] = at; at += TT ? 0 : 4 * kWaveScratch;   // K stages in its own residual rows instead
-    o[3] = at; at += 16;
+    o[3] = at; at += 32;
     o[4] = at; at += (size_t)TT * kRStride * 4;
     const int ngrp = TT ? TT / G : 0;
     o[5] = at; at += (size_t)ngrp * kD * 2 * 2;
@@ -351,14 +351,18 @@ __device__ __forceinline__ void k_store_staging(const QuantArgs &a, int64_t tok0
     if (lane == 0) *reinterpret_cast<uint4 *>(a.idx + tok0) = *reinterpret_cast<const uint4 *>(stg + 16 * 16 * BITS);
 }
 
-// K: workgroup = 256 threads, tiles of TT = max(64, G) tokens of one stream; wave w owns the 16-token
-// tiles w*NT .. w*NT + NT-1 of the tile.
-template <int G, int BITS>
-__global__ __launch_bounds__(256) void quantize_k_kernel(QuantArgs a, int tiles_per_wg)
+// K: workgroup = NW waves, tiles of TT = max(64, G) tokens of one stream; wave w owns the 16-token
+// tiles w*NT .. w*NT + NT-1 of the tile.  Launched for groups of 128 tokens with NW = 8, one 16-token tile per
+// wave: the 128-token residual tile (68 KB) beside the pattern table leaves room for one workgroup per CU from 128
+// patterns on, and eight waves give every SIMD two (four waves measured 12 % slower, on a bulk job at 64 patterns
+// as on the 4-stream job at 256).
+template <int G, int BITS, int NW>
+__global__ __launch_bounds__(64 * NW) void quantize_k_kernel(QuantArgs a, int tiles_per_wg)
 {
-    constexpr int TT = G == 128 ? 128 : 64, NT = TT / 64;
+    constexpr int TT = G == 128 ? 128 : 64, NT = TT / (16 * NW);
+    static_assert(NT >= 1, "every wave takes at least one 16-token tile");
     constexpr int LPC = TT / 32;          // lanes that share one channel in the column scan, 32 tokens each
-    constexpr int CPR = 256 / LPC;        // channels per round of the scan
+    constexpr int CPR = 64 * NW / LPC;    // channels per round of the scan
     constexpr int NGRP = TT / G;          // parameter groups per tile
     extern __shared__ __align__(16) unsigned char smem[];
     const TileShared sh = carve(smem, a.P, TT, G);
@@ -373,8 +377,9 @@ __global__ __launch_bounds__(256) void quantize_k_kernel(QuantArgs a, int tiles_
 #pragma unroll
     for (int j = 0; j < NT; ++j) load_tile(a, ns, tile0 * TT + (wave * NT + j) * 16, xb[j]);   // in flight while the table is staged
 
-    stage_patterns(Mg, a.P, sh.tab, sh.nh, sh.red);
-    const PatternTable tb = make_table(sh, Mg, a.P);
+    stage_patterns(Mg, a.P, sh.tab, sh.nh, sh.red, 64 * NW);
+    PatternTable tb = make_table(sh, Mg, a.P);
+    if (NW == 8) tb.norm2_max = fmaxf(tb.norm2_max, fmaxf(fmaxf(sh.red[4], sh.red[5]), fmaxf(sh.red[6], sh.red[7])));
 
     const int q = tid % LPC, cc = tid / LPC;
     for (int tile = tile0; tile < tile1; ++tile) {
@@ -445,7 +450,7 @@ __global__ __launch_bounds__(256) void quantize_k_kernel(QuantArgs a, int tiles_
         }
         __syncthreads();
         // stored parameters of the tile's groups: 16-byte pieces, zero points then scales
-        if (wave == 3 && lane < NGRP * 32) {
+        if (wave == NW - 1 && lane < NGRP * 32) {
             const int grp = lane >> 5, arr = (lane >> 4) & 1, piece = lane & 15;
             const uint4 v = *reinterpret_cast<const uint4 *>(sh.pz + (arr * NGRP + grp) * kD + piece * 8);
             __half *dstp = (arr ? a.scale : a.zero) + (pq0 / G + grp) * kD + piece * 8;
@@ -877,7 +882,7 @@ static int tiles_per_wg(int n_tiles, int n_streams)
     return t < 1 ? 1 : (t > cap ? cap : t);
 }
 
-template <auto KERNEL>
+template <auto KERNEL, int THREADS = 256>
 static hipError_t launch_tiled(const QuantArgs &a, int TT, size_t lds, size_t max_lds, hipStream_t s, int min_tiles = 1)
 {
     static LdsOptIn opt_in;   // per kernel instantiation; max_lds: what it needs with a table of 256 patterns
@@ -886,7 +891,7 @@ static hipError_t launch_tiled(const QuantArgs &a, int TT, size_t lds, size_t ma
     int tpw = tiles_per_wg(a.nq / TT, a.n_streams);
     if (tpw < min_tiles) tpw = min_tiles;
     const int n_tiles = a.nq / TT;
-    hipLaunchKernelGGL(KERNEL, dim3((n_tiles + tpw - 1) / tpw, a.n_streams), dim3(256), lds, s, a, tpw);
+    hipLaunchKernelGGL(KERNEL, dim3((n_tiles + tpw - 1) / tpw, a.n_streams), dim3(THREADS), lds, s, a, tpw);
     return hipGetLastError();
 }
 
@@ -924,7 +929,7 @@ hipError_t launch_quantize_k(const QuantArgs &a_in, hipStream_t s)
 #define PK_LAUNCH_K2(GG, BB)                                                                                       \
     if (a.G == GG && a.bits == BB) {                                                                               \
         constexpr int TT = GG == 128 ? 128 : 64;                                                                   \
-        return launch_tiled<quantize_k_kernel<GG, BB>>(a, TT, tile_lds_bytes(a.P, TT, GG), tile_lds_bytes(256, TT, GG), s, big1); \
+        return launch_tiled<quantize_k_kernel<GG, BB, 8>, 512>(a, TT, tile_lds_bytes(a.P, TT, GG), tile_lds_bytes(256, TT, GG), s, big1); \
     }
 #define PK_LAUNCH_KW(GG, BB)                                                                                       \
     if (a.G == GG && a.bits == BB) {                                                                               \

@@ -124,7 +124,7 @@ typedef struct {
     int32_t n_q_heads;    /* multiple of n_kv_heads; r = n_q_heads/n_kv_heads in 1..8; at d = 128
                              pk_decode_attention needs r * (d / min(G, d)) <= 16                 */
     int32_t head_dim;     /* d: 128 (the tuned kernels), or 96 / 256 (the other head sizes of Sec. 3.3: plain
-                             vector-ALU kernels; every call but pk_quantize_append_ragged takes them).  min(G, d)
+                             vector-ALU kernels; every call takes them).  min(G, d)
                              must divide d (d = 96: G = 32 or 128)                                  */
     int32_t n_patterns;   /* P: 1..256 (indices are stored in one byte)                       */
     int32_t seqs_per_set; /* see "Streams and pattern sets" above; >= 0                       */

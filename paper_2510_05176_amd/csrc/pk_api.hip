@@ -415,7 +415,6 @@ pk_status pk_quantize_append_ragged(const pk_config *cfg, const pk_cache *cache,
     if ((st = check_cache(cache)) != PK_OK) return st;
     if ((st = check_paging(cfg, cache)) != PK_OK) return st;
     if (!states || !n_new) return PK_ERR_INVALID_ARG;
-    if (cfg->head_dim != kD) return PK_ERR_UNSUPPORTED;   // the generic kernels take uniform appends only
     const int S = cfg->n_seq;
     int64_t max_new = 0;
     for (int i = 0; i < S; ++i) {
@@ -427,8 +426,8 @@ pk_status pk_quantize_append_ragged(const pk_config *cfg, const pk_cache *cache,
     const size_t table_bytes = (size_t)S * kSeqEntry * sizeof(int32_t);
     if (max_new > 0) {
         if (!k_new || !v_new || !patterns_k || !patterns_v) return PK_ERR_INVALID_ARG;
-        if (stream_stride == 0) stream_stride = max_new * kD;
-        if (stream_stride < max_new * kD || stream_stride % 8 != 0) return PK_ERR_SHAPE;
+        if (stream_stride == 0) stream_stride = max_new * cfg->head_dim;
+        if (stream_stride < max_new * cfg->head_dim || stream_stride % 8 != 0) return PK_ERR_SHAPE;
         if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(patterns_k) || !aligned16(patterns_v)) return PK_ERR_ALIGNMENT;
     }
     if (!workspace || workspace_bytes < table_bytes) return PK_ERR_WORKSPACE;

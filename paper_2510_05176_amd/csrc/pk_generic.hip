@@ -4,8 +4,8 @@
 // pk_quant_arith.h; pattern selection evaluates the metric in binary32 over all patterns, lowest index on ties) and
 // store the same cache format (head_dim enters the layout formulas), so they meet the same parity bars; they are
 // kept simple rather than tuned, and the tuned kernels of the other files keep their fixed head dimension.
-// Uniform appends, decode (with shared prefix and with per-sequence fill states), mining, the window pattern and
-// dequantize are covered, on contiguous and on paged caches.
+// Uniform and ragged appends, decode (with shared prefix and with per-sequence fill states), mining, the window
+// pattern and dequantize are covered, on contiguous and on paged caches.
 #pragma clang fp contract(off)
 
 #include "pk_quant_arith.h"
@@ -91,6 +91,8 @@ __global__ __launch_bounds__(kGenThreads) void gen_assign_kernel(QuantArgs a)
 {
     __shared__ __align__(16) __half tab[kTabRows * D];
     const int tid = threadIdx.x, ns = blockIdx.y, i = blockIdx.x * kGenThreads + tid;
+    take_sequence_entry(a, ns);
+    if ((int)(blockIdx.x * kGenThreads) >= a.nq) return;   // a ragged append: sized for the longest sequence
     const bool live = i < a.nq;
     uint4 x[D / 8];
     const uint4 *row = reinterpret_cast<const uint4 *>(a.src.row_d(ns, live ? i : a.nq - 1, D));
@@ -107,6 +109,8 @@ __global__ __launch_bounds__(kGenThreads) void gen_assign_kernel(QuantArgs a)
 __global__ __launch_bounds__(kGenThreads) void gen_quantize_k_kernel(QuantArgs a)
 {
     const int c = threadIdx.x, lane = c & 63, ns = blockIdx.y, g = blockIdx.x, d = a.d, G = a.G;
+    take_sequence_entry(a, ns);
+    if (g * G >= a.nq) return;   // a ragged append: sized for the longest sequence
     const bool on = c < d;
     const __half *M = a.patterns + (int64_t)a.sets.set_of(ns) * a.P * d;
     const int64_t p0 = a.map.pos(ns, a.t0 + g * G);   // a group never straddles a page
@@ -146,6 +150,8 @@ __global__ __launch_bounds__(kGenThreads) void gen_quantize_v_kernel(QuantArgs a
 {
     __shared__ float4 half_mm[2][kGenThreads / 32];   // per 32 channels: min r, max r, min x, max x
     const int c = threadIdx.x, ns = blockIdx.y, u = blockIdx.x, d = a.d;
+    take_sequence_entry(a, ns);
+    if (u * 16 >= a.nq) return;   // a ragged append: sized for the longest sequence
     const bool on = c < d;
     const int Gc = a.G < d ? a.G : d, NG = d / Gc, g = on ? c / Gc : 0;
     const __half *M = a.patterns + (int64_t)a.sets.set_of(ns) * a.P * d;
@@ -207,6 +213,13 @@ __global__ __launch_bounds__(kGenThreads) void gen_quantize_v_kernel(QuantArgs a
 __global__ __launch_bounds__(256) void gen_tail_copy_kernel(TailCopyArgs a)
 {
     const int n = blockIdx.y, side = blockIdx.z, chunks = a.d / 8;
+    if (a.seq_table) {   // a ragged append: the ring state and the range of the stream's own sequence
+        const int32_t *e = a.seq_table + (int64_t)(n / a.n_kv_heads) * kSeqEntry;
+        a.ring_start = e[kSeqRingStart];
+        a.n_ring = e[kSeqNRing];
+        a.i0 = e[kSeqI0];
+        a.i1 = e[kSeqI1];
+    }
     const int64_t work = (int64_t)(a.i1 - a.i0) * chunks;
     const int64_t w = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (w >= work) return;

@@ -101,7 +101,7 @@ def test_paged_layout_and_its_config_checks(pk):
 
 def test_other_head_dimensions_in_the_layout_and_checks(pk):
     """Head dimensions 96 and 256: the layout formulas carry d, V's channel groups of min(G, d) must tile the head,
-    the ragged append (tuned kernels only) refuses them before any launch."""
+    the ragged append sizes its stride check by d."""
     kw = dict(n_seq=2, n_kv_heads=2, n_q_heads=4, n_patterns=16, bits=2, recent=0, flush=128, t_capacity=1024)
     lay = pk.pk_cache_layout(pk.Config(**kw, head_dim=256, group=64))
     N = 4
@@ -121,9 +121,10 @@ def test_other_head_dimensions_in_the_layout_and_checks(pk):
     states = (pk._State * 2)(pk._State(0, 0, 0), pk._State(0, 0, 0))
     n_new = (C.c_int32 * 2)(8, 8)
     good = C.c_void_p(0x2000)
-    st = lib.pk_quantize_append_ragged(C.byref(cfg), C.byref(cache), states, good, good, n_new, C.c_int64(0), good, good, None,
-                                       good, C.c_size_t(1024), None)
-    assert st == 2
+    # a stream stride that holds 8 vectors of 128 channels is too short for 8 vectors of 256: refused before any launch
+    st = lib.pk_quantize_append_ragged(C.byref(cfg), C.byref(cache), states, good, good, n_new, C.c_int64(8 * 128), good, good,
+                                       None, good, C.c_size_t(1024), None)
+    assert st == 3
 
 
 def test_v_threshold_needs_a_free_index(pk):

@@ -435,14 +435,17 @@ def test_decode_ragged_batch_parity(oracle, pk, hkv, hq, bits, G, P, R, lens):
     assert np.array_equal(one, rag1)
 
 
-@pytest.mark.parametrize("hkv,hq,bits,G,P,R,F,metric,rounds", [
-    (2, 8, 2, 64, 32, 32, 64, 0, [[0, 70, 197, 1000, 517], [5, 0, 300, 64, 1], [1, 1, 1, 1, 1]]),
-    (1, 4, 4, 32, 16, 0, 128, 0, [[640, 64, 1, 333], [0, 0, 700, 127]]),
-    (2, 2, 2, 128, 200, 100, 128, 1, [[300, 1200, 40], [228, 1, 88]]),     # large table, group 128, min-max rule
+@pytest.mark.parametrize("d,hkv,hq,bits,G,P,R,F,metric,rounds", [
+    (128, 2, 8, 2, 64, 32, 32, 64, 0, [[0, 70, 197, 1000, 517], [5, 0, 300, 64, 1], [1, 1, 1, 1, 1]]),
+    (128, 1, 4, 4, 32, 16, 0, 128, 0, [[640, 64, 1, 333], [0, 0, 700, 127]]),
+    (128, 2, 2, 2, 128, 200, 100, 128, 1, [[300, 1200, 40], [228, 1, 88]]),     # large table, group 128, min-max rule
     # more sequences than one launch of the table kernel carries (64)
-    (1, 2, 2, 64, 8, 16, 64, 0, [[(37 * i) % 211 for i in range(70)], [(91 * i) % 67 for i in range(70)]]),
+    (128, 1, 2, 2, 64, 8, 16, 64, 0, [[(37 * i) % 211 for i in range(70)], [(91 * i) % 67 for i in range(70)]]),
+    # the other head dimensions (plain kernels)
+    (96, 2, 4, 2, 32, 16, 32, 64, 0, [[0, 70, 197, 700, 517], [5, 0, 300, 64, 1]]),
+    (256, 1, 2, 4, 128, 24, 40, 128, 1, [[300, 900, 40], [228, 1, 88]]),
 ])
-def test_quantize_append_ragged_parity(oracle, pk, hkv, hq, bits, G, P, R, F, metric, rounds):
+def test_quantize_append_ragged_parity(oracle, pk, d, hkv, hq, bits, G, P, R, F, metric, rounds):
     """One append call for sequences at different fill (prompts of different lengths, then steps of different size,
     a sequence that receives nothing): every sequence's part of the cache equals the oracle's cache of that sequence
     alone after the same appends; the fill states written for the ragged decode are the sequences' own; the decode
@@ -450,9 +453,9 @@ def test_quantize_append_ragged_parity(oracle, pk, hkv, hq, bits, G, P, R, F, me
     S = len(rounds[0])
     total = [sum(r[i] for r in rounds) for i in range(S)]
     T = max(total)
-    kw = dict(n_kv_heads=hkv, n_q_heads=hq, head_dim=128, n_patterns=P, bits=bits, group=G, recent=R, flush=F,
+    kw = dict(n_kv_heads=hkv, n_q_heads=hq, head_dim=d, n_patterns=P, bits=bits, group=G, recent=R, flush=F,
               t_capacity=-(-T // F) * F, metric=metric)
-    K, V = synth.make_kv(500 + P, synth.KVSpec(1, S, hkv, hq, T, 128, 12))
+    K, V = synth.make_kv(500 + P, synth.KVSpec(1, S, hkv, hq, T, d, 12))
     Mk, _, _, _ = oracle.mine(K[0].view(np.uint16), P, 3)
     Mv, _, _, _ = oracle.mine(V[0].view(np.uint16), P, 3)
     gcfg = pk.Config(**dict(kw, n_seq=S, seqs_per_set=S))
@@ -464,7 +467,7 @@ def test_quantize_append_ragged_parity(oracle, pk, hkv, hq, bits, G, P, R, F, me
     st_dev = torch.full((S, 4), -1, dtype=torch.int32, device="cuda")
     for n_new in rounds:
         n_max = max(n_new)
-        Kn = np.zeros((S, hkv, n_max, 128), np.float16)
+        Kn = np.zeros((S, hkv, n_max, d), np.float16)
         Vn = np.zeros_like(Kn)
         for i, n in enumerate(n_new):
             Kn[i, :, :n], Vn[i, :, :n] = K[i, :, done[i]:done[i] + n], V[i, :, done[i]:done[i] + n]
@@ -479,10 +482,10 @@ def test_quantize_append_ragged_parity(oracle, pk, hkv, hq, bits, G, P, R, F, me
             sub = gc.sequence(i)
             sub.state = pk._State(*states[i])
             compare_caches(oracle, oc, sub, metric)
-    q = synth.make_queries(33, S, hq, 128)
-    want, _ = oracle.decode_attention_ragged(ocs, q.view(np.uint16), Mk, Mv, 128 ** -0.5)
+    q = synth.make_queries(33, S, hq, d)
+    want, _ = oracle.decode_attention_ragged(ocs, q.view(np.uint16), Mk, Mv, d ** -0.5)
     got = pk.pk_decode_attention_ragged(gcfg, gc, st_dev, max(s[0] for s in states), max(s[1] for s in states), dev(q),
-                                        128 ** -0.5, Mkd, Mvd).cpu().numpy()
+                                        d ** -0.5, Mkd, Mvd).cpu().numpy()
     for i in range(S):
         assert_attention(got[i], want[i])
 

@@ -497,8 +497,6 @@ static pk_status decode_impl(const pk_config *cfg, const pk_cache *cache, const 
     if ((st = check_paging(cfg, cache)) != PK_OK) return st;
     if ((st = check_state(cfg, state)) != PK_OK) return st;
     if (!q || !patterns_k || !patterns_v || !out) return PK_ERR_INVALID_ARG;
-    if (cfg->head_dim == kD && (cfg->n_q_heads / cfg->n_kv_heads) * (kD / (cfg->group < kD ? cfg->group : kD)) > 16)
-        return PK_ERR_UNSUPPORTED;
     if (!aligned16(q) || !aligned16(patterns_k) || !aligned16(patterns_v) || !aligned16(out) ||
         (lse && !aligned16(lse)))
         return PK_ERR_ALIGNMENT;

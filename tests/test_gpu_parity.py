@@ -273,6 +273,8 @@ def test_division_sequences_match_ieee_division(pk):
     (2, 8, 2, 32, 64, 0, 900),        # r = 4, group 32: four V channel groups, two K groups per 64-token block
     (1, 4, 4, 32, 16, 0, 333),        # 4-bit with group 32
     (2, 8, 4, 64, 64, 0, 640),        # 4-bit, r = 4, empty tail
+    (1, 8, 2, 32, 16, 16, 700),       # r = 8 with group 32: 32 (head, channel group) pairs, more than a tile's 16 columns
+    (1, 5, 4, 32, 8, 0, 1300),        # r = 5 with group 32, 4-bit, several splits
 ])
 def test_decode_attention_parity(oracle, pk, hkv, hq, bits, G, P, R, T):
     kw, ocfg, gcfg, K, V, Mk, Mv = make_case(oracle, pk, 31 + hq + T, T=T, P=P, bits=bits, G=G, R=R, F=max(G, 64),
@@ -316,17 +318,6 @@ def test_decode_large_query_and_key_range(oracle, pk, hkv, hq, bits, G):
     got = pk.pk_decode_attention(gcfg, gc, dev(q), scale, Mkd, Mvd, lse=lse).cpu().numpy()
     assert_attention(got, want)
     assert np.abs(lse.cpu().numpy() - want_lse).max() <= 2e-3 * max(1.0, np.abs(want_lse).max())
-
-
-def test_decode_unsupported_head_group_combination(oracle, pk):
-    # r * (V channel groups per token) must fit the 16 rows of one matrix-core tile
-    cfg = pk.Config(n_seq=1, n_kv_heads=1, n_q_heads=8, n_patterns=8, bits=2, group=32, flush=64, t_capacity=64)
-    cache = pk.Cache(cfg)
-    q = torch.zeros((1, 8, 128), dtype=torch.float16, device="cuda")
-    M = torch.zeros((1, 8, 128), dtype=torch.float16, device="cuda")
-    with pytest.raises(pk.PkError) as e:
-        pk.pk_decode_attention(cfg, cache, q, 0.1, M, M)
-    assert e.value.status == 2
 
 
 def test_decode_tail_only_and_empty_context(oracle, pk):

@@ -693,3 +693,79 @@ def test_stream_to_pattern_set_mapping(oracle, n_seq, hkv, k, expected):
     # and the reconstruction with the same tables gives the zero vectors back
     kh, vh = c.dequantize(tables.view(np.uint16), tables.view(np.uint16))
     assert not kh.any() and not vh.any()
+
+
+# ---------------------------------------------------------------- head dimensions 96 and 256
+
+@pytest.mark.parametrize("d,G", [(96, 32), (96, 128), (256, 64), (256, 128)])
+@pytest.mark.parametrize("bits", [2, 4])
+def test_other_head_dimensions_quantizer_and_format(oracle, d, G, bits):
+    """The oracle at the other head sizes of Sec. 3.3: with a zero pattern both quantizers are the textbook asymmetric
+    quantizer (numpy, written separately) over K's token groups and V's channel groups of min(G, d); the packed
+    words follow the stated index formulas (hand-worked probes in tests/golden/pack_format_other_d.txt) and
+    round-trip."""
+    rng = np.random.default_rng(40 + d + G + bits)
+    n = 256
+    x = f16(rng.standard_normal((1, n, d)) * np.exp(rng.standard_normal((1, 1, d))))
+    M = np.zeros((1, 1, d), np.uint16)
+    set_of = np.zeros(1, np.int32)
+    rk = oracle.quantize_streams(x.view(np.uint16), set_of, M, 0, bits, G, 0, want_codes=True)
+    rv = oracle.quantize_streams(x.view(np.uint16), set_of, M, 0, bits, G, 1, want_codes=True)
+    r = x[0].astype(np.float32)
+    qk, sk, zk = _numpy_asym_quant(r.reshape(n // G, G, d), bits, axis=1)
+    assert np.array_equal(rk["codes"][0], qk.reshape(n, d))
+    assert np.array_equal(rk["scale"][0], sk.reshape(n // G, d).view(np.uint16))
+    assert np.array_equal(rk["zero"][0], zk.reshape(n // G, d).view(np.uint16))
+    Gc = min(G, d)
+    qv, sv, zv = _numpy_asym_quant(r.reshape(n, d // Gc, Gc), bits, axis=2)
+    assert np.array_equal(rv["codes"][0], qv.reshape(n, d))
+    assert np.array_equal(oracle.v_params_by_token(rv["scale"][0]), sv.reshape(n, d // Gc).view(np.uint16))
+    assert np.array_equal(oracle.v_params_by_token(rv["zero"][0]), zv.reshape(n, d // Gc).view(np.uint16))
+    # format
+    codes = rk["codes"][0][:48]
+    wk, wv = oracle.pack_k(codes, bits), oracle.pack_v(codes, bits)
+    assert wk.nbytes == wv.nbytes == 48 * d * bits // 8
+    assert np.array_equal(oracle.unpack_k(wk, 48, d, bits), codes) and np.array_equal(oracle.unpack_v(wv, 48, d, bits), codes)
+    probed = 0
+    for line in open(os.path.join(GOLDEN, "pack_format_other_d.txt")):
+        if not line.strip() or line.startswith("#"):
+            continue
+        side, b, dd, t, c, j, unit, bit = line.split()
+        if int(b) != bits or int(dd) != d:
+            continue
+        one = np.zeros((48, d), np.uint8)
+        one[int(t), int(c)] = 1 << int(j)
+        w = (oracle.pack_k(one, bits) if side == "K" else oracle.pack_v(one, bits)).reshape(-1)
+        assert w.dtype == np.uint32 and np.flatnonzero(w).tolist() == [int(unit)] and w[int(unit)] == 1 << int(bit)
+        probed += 1
+    assert probed == 2
+
+
+@pytest.mark.parametrize("d,G", [(96, 32), (256, 128)])
+def test_other_head_dimensions_attention_matches_torch_sdpa(oracle, d, G):
+    """Decode over a cache with a packed part, a tail and a shared prefix at head dimensions 96 and 256 equals
+    torch's scaled_dot_product_attention over the reconstructed keys and values."""
+    import torch
+    cfg = _cfg(oracle, head_dim=d, group=G, flush=128, recent=16, t_capacity=512)
+    spec = synth.KVSpec(1, cfg.n_seq, cfg.n_kv_heads, cfg.n_q_heads, 300, d, 8)
+    K, V = synth.make_kv(41, spec)
+    M_k, _, _, _ = oracle.mine(K[0].view(np.uint16), cfg.n_patterns, 2)
+    M_v, _, _, _ = oracle.mine(V[0].view(np.uint16), cfg.n_patterns, 2)
+    c = oracle.Cache(cfg)
+    c.append(K.view(np.uint16), V.view(np.uint16), M_k, M_v)
+    assert c.t_quant == 256 and c.t_tail == 44
+    q = synth.make_queries(41, cfg.n_seq, cfg.n_q_heads, d)
+    out, lse = oracle.decode_attention(c, q.view(np.uint16), M_k, M_v, d ** -0.5)
+    Kh, Vh = c.materialize(M_k, M_v)
+    Kh = torch.from_numpy(Kh).reshape(2, 2, 300, d).repeat_interleave(2, dim=1).double()
+    Vh = torch.from_numpy(Vh).reshape(2, 2, 300, d).repeat_interleave(2, dim=1).double()
+    Q = torch.from_numpy(q.astype(np.float64)).reshape(2, 4, 1, d)
+    ref = torch.nn.functional.scaled_dot_product_attention(Q, Kh, Vh, scale=d ** -0.5)
+    assert np.allclose(out, ref.reshape(2, 4, d).numpy(), rtol=1e-5, atol=1e-6)
+    ref_lse = torch.logsumexp((Q @ Kh.transpose(-1, -2)) * d ** -0.5, dim=-1).reshape(2, 4).numpy()
+    assert np.allclose(lse, ref_lse, rtol=1e-6)
+    # the reconstruction stays close to the source
+    Kf = torch.from_numpy(K.astype(np.float64)).repeat_interleave(2, dim=1)
+    Vf = torch.from_numpy(V.astype(np.float64)).repeat_interleave(2, dim=1)
+    full = torch.nn.functional.scaled_dot_product_attention(Q, Kf, Vf, scale=d ** -0.5).reshape(2, 4, d).numpy()
+    assert np.linalg.norm(out - full) / np.linalg.norm(full) < 0.35

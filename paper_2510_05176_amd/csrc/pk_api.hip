@@ -53,7 +53,7 @@ pk_status check_config(const pk_config *c)
     // V is quantized over contiguous groups of min(G, d) channels: they have to tile the head (d = 96: G = 32 or 128)
     if (c->head_dim % (c->group < c->head_dim ? c->group : c->head_dim) != 0) return PK_ERR_UNSUPPORTED;
     if (c->n_q_heads % c->n_kv_heads != 0) return PK_ERR_SHAPE;
-    if (c->n_q_heads / c->n_kv_heads > 8) return PK_ERR_UNSUPPORTED;
+    if (c->n_q_heads / c->n_kv_heads > 64) return PK_ERR_UNSUPPORTED;
     if ((int64_t)c->n_seq * c->n_kv_heads > 65535) return PK_ERR_UNSUPPORTED;
     if (c->flush % c->group != 0 || c->flush % 64 != 0) return PK_ERR_SHAPE;
     if (c->t_capacity % c->flush != 0) return PK_ERR_SHAPE;

@@ -375,7 +375,7 @@ __global__ __launch_bounds__(kGenThreads) void gen_dequant_kernel(DequantArgs a)
 // ---------------------------------------------------------------------------------------------- decode
 // Decode attention (Sec. 3.4) in plain vector arithmetic.  The context of a stream is cut into the same slots as in
 // the tuned path (equal splits of the shared prefix's packed part, of the own packed part, then the own tail and
-// the prefix's tail); a workgroup takes one slot of one stream for all r <= R query heads of the KV head at once, so
+// the prefix's tail); a workgroup takes one slot of one stream for up to R = 8 query heads of the KV head at once (more heads: further workgroups), so
 // the codes are taken apart once for all of them, and leaves an unnormalised partial (o, per-pattern softmax mass
 // W, running maximum m in the log2 domain, sum l); a second kernel merges the partials and adds W . M_V once per
 // head.  Scores: thread <-> token, score = q.M_K[k*] (a table formed once per workgroup) + sum_c q_c (s_c code_c +
@@ -404,7 +404,7 @@ __device__ __forceinline__ float wave_sum(float v)
 struct GenDecodeLds {
     unsigned long long *W;   // [P][R]   softmax mass per V pattern and head, fixed point
     long long *pos;          // [kPass]  packed position (or tail ring row) of the pass's tokens
-    float *qf;               // [d][R]   the queries, channel-major; heads beyond r are zero
+    float *qf;               // [d][R]   the queries, channel-major; heads beyond the workgroup's are zero
     float *QM;               // [P][R]   q . M_K[p]
     float *sc;               // [kPass][R] softmax numerators of the pass
     float *red;              // [4][R]
@@ -429,9 +429,9 @@ __global__ __launch_bounds__(kGenThreads) void gen_decode_split_kernel(DecodeArg
     extern __shared__ __align__(16) unsigned char gen_decode_smem[];
     const int tid = threadIdx.x, d = a.d, P = a.P;
     const GenDecodeLds lds(gen_decode_smem, d, P, R);
-    const int n = blockIdx.x, slot = blockIdx.y;
+    const int n = blockIdx.x, slot = blockIdx.y, h0 = blockIdx.z * R;   // the workgroup's first head of the KV head's r
     const int seq = n / a.n_kv_heads, head = n - seq * a.n_kv_heads;
-    const int r = a.n_q_heads / a.n_kv_heads, nh = min(R, r);   // r <= 8 by the configuration check
+    const int r = a.n_q_heads / a.n_kv_heads, nh = min(R, r - h0);
     const int n_packed = a.splits_prefix + a.splits_own, n_slots = n_packed + 2;
     const bool packed = slot < n_packed;
     const bool pre = slot < a.splits_prefix || slot == n_packed + 1;
@@ -445,7 +445,7 @@ __global__ __launch_bounds__(kGenThreads) void gen_decode_split_kernel(DecodeArg
         t_begin = (pre ? slot : slot - a.splits_prefix) * a.chunk;
         t_end = min(tq, t_begin + a.chunk);
     }
-    const int64_t pb = ((int64_t)n * n_slots + slot) * r;   // partial of the KV head's first query head
+    const int64_t pb = ((int64_t)n * n_slots + slot) * r + h0;   // partial of the workgroup's first query head
     if (t_end <= t_begin) {   // nothing in this slot: the merge skips partials whose sum is zero
         if (tid < nh) {
             a.part_ml[(pb + tid) * 2] = -INFINITY;
@@ -458,7 +458,7 @@ __global__ __launch_bounds__(kGenThreads) void gen_decode_split_kernel(DecodeArg
 
     for (int i = tid; i < d * R; i += kGenThreads) {
         const int c = i / R, h = i - c * R;
-        lds.qf[i] = h < nh ? h2f(a.q[((int64_t)seq * a.n_q_heads + head * r + h) * d + c]) : 0.f;
+        lds.qf[i] = h < nh ? h2f(a.q[((int64_t)seq * a.n_q_heads + head * r + h0 + h) * d + c]) : 0.f;
     }
     for (int i = tid; i < P * R; i += kGenThreads) lds.W[i] = 0ull;
     __syncthreads();
@@ -807,11 +807,11 @@ hipError_t launch_generic_window_pattern(const __half *x, int64_t set_stride, in
 
 hipError_t launch_generic_decode(const DecodeArgs &a, hipStream_t s)
 {
-    // heads of a KV head per workgroup: the power of two that holds them (r <= 8 by the configuration check)
+    // heads of a KV head per workgroup: the power of two that holds them, eight at most; more heads per KV head
+    // (up to 64 by the configuration check) go to further workgroups along z
     const int r = a.n_q_heads / a.n_kv_heads;
-    if (r > 8) return hipErrorInvalidValue;
     const int R = r > 4 ? 8 : r > 2 ? 4 : r > 1 ? 2 : 1;
-    const dim3 grid(a.n_seq * a.n_kv_heads, a.splits_prefix + a.splits_own + 2);
+    const dim3 grid(a.n_seq * a.n_kv_heads, a.splits_prefix + a.splits_own + 2, (r + R - 1) / R);
     const size_t lds = gen_decode_lds_bytes(a.d, a.P, R);
     hipError_t e = R == 8   ? launch_gen_decode_split<8>(a, grid, lds, s)
                    : R == 4 ? launch_gen_decode_split<4>(a, grid, lds, s)

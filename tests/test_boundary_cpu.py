@@ -61,7 +61,7 @@ def test_layout_byte_counts(pk):
 
 @pytest.mark.parametrize("field,value,status", [
     ("head_dim", 64, 2), ("bits", 3, 2), ("group", 48, 2), ("n_patterns", 257, 2), ("n_patterns", 0, 1),
-    ("n_q_heads", 5, 3), ("n_q_heads", 36, 2), ("flush", 96, 3), ("t_capacity", 100, 3), ("metric", 7, 1),
+    ("n_q_heads", 5, 3), ("n_q_heads", 260, 2), ("flush", 96, 3), ("t_capacity", 100, 3), ("metric", 7, 1),
     ("recent", -1, 1), ("n_seq", 0, 1), ("n_seq", 70000, 2),
     ("v_rho", -0.1, 1), ("v_rho", 1.0, 1), ("v_rho", float("nan"), 1),
 ])

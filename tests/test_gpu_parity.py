@@ -275,6 +275,8 @@ def test_division_sequences_match_ieee_division(pk):
     (2, 8, 4, 64, 64, 0, 640),        # 4-bit, r = 4, empty tail
     (1, 8, 2, 32, 16, 16, 700),       # r = 8 with group 32: 32 (head, channel group) pairs, more than a tile's 16 columns
     (1, 5, 4, 32, 8, 0, 1300),        # r = 5 with group 32, 4-bit, several splits
+    (1, 16, 2, 64, 24, 32, 900),      # r = 16: two groups of eight heads through the plain kernels
+    (2, 24, 2, 128, 8, 0, 640),       # r = 12: a full and a half-filled head group
 ])
 def test_decode_attention_parity(oracle, pk, hkv, hq, bits, G, P, R, T):
     kw, ocfg, gcfg, K, V, Mk, Mv = make_case(oracle, pk, 31 + hq + T, T=T, P=P, bits=bits, G=G, R=R, F=max(G, 64),
@@ -909,6 +911,7 @@ def test_other_head_dimensions_parity(oracle, pk, d, G, bits, P, metric, R, rho,
     (256, 1, 8, 4, 64, 8, 0, [1024, 333]),              # r = 8, 4-bit
     (256, 2, 2, 2, 128, 32, 40, [2048, 900, 129]),      # r = 1, groups of 128 tokens
     (96, 1, 7, 2, 128, 24, 0, [1100, 1100]),            # r = 7, one V group of all 96 channels
+    (256, 1, 12, 2, 64, 8, 16, [1024, 333]),            # r = 12: two head groups per KV head, the second half filled
 ])
 def test_other_head_dimensions_decode_splits(oracle, pk, d, hkv, hq, bits, G, P, R, lens):
     """Decode at head dimensions 96 and 256 over contexts of several splits and passes, with per-sequence fill states

@@ -181,10 +181,10 @@ int decode_chunk(int64_t n_streams, int64_t t_packed_total, int P, int r)
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t s)
 {
     const int r = a.n_q_heads / a.n_kv_heads;
-    // the matrix-core kernel holds the (head, V channel group) pairs of a KV head in the 16 columns of one tile and
-    // takes up to 8 heads; more pairs (5 to 8 heads with 32-channel groups), more heads and the other head dimensions
-    // run the plain kernels
-    if (a.d != kD || r > 8 || r * (kD / (a.G < kD ? a.G : kD)) > 16) return launch_generic_decode(a, s);
+    // the matrix-core kernel holds the (head, V channel group) pairs of a group of heads in the 16 columns of one tile
+    // and takes up to 8 heads per KV head, in one group or two; what does not fit (5 or 7 heads with 32-channel
+    // groups), more heads and the other head dimensions run the plain kernels
+    if (a.d != kD || r > 8 || (r / a.head_groups) * (kD / (a.G < kD ? a.G : kD)) > 16) return launch_generic_decode(a, s);
     const int N = a.n_seq * a.n_kv_heads;
     hipError_t e;
     if (a.seq_order && a.splits_prefix + a.splits_own > 0) {

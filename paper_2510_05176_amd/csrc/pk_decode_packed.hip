@@ -146,9 +146,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
     // Rows of the grid behind the streams hold the workgroups of the fp16 tails (own tails first, then the shared
     // prefix's if it has one): they ride along in this launch and fill the slots that the last round of packed
     // splits leaves idle, instead of running as a kernel of their own afterwards.
-    if ((int)blockIdx.y >= a.n_seq * a.n_kv_heads) {
+    if ((int)blockIdx.y >= a.n_seq * a.n_kv_heads * a.head_groups) {
         const int N = a.n_seq * a.n_kv_heads;
-        const int id = ((int)blockIdx.y - N) * (int)gridDim.x + (int)blockIdx.x;
+        const int id = ((int)blockIdx.y - N * a.head_groups) * (int)gridDim.x + (int)blockIdx.x;
         if (id >= N * (a.prefix.t_tail > 0 ? 2 : 1)) return;
         const int which = id / N;
         if (a.n_q_heads / a.n_kv_heads <= 4)
@@ -160,7 +160,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
     const int tid = threadIdx.x, lane = tid & 63, n = lane & 15, kb = lane >> 4;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: block ranges and base addresses stay scalar
     const int split = blockIdx.x;
+    // row y of the grid: stream y / head_groups, group y % head_groups of its query heads
     int ns = blockIdx.y;
+    int head0 = 0;                                   // first head of the row's group inside the KV head
+    const int R_all = a.n_q_heads / a.n_kv_heads;    // query heads per KV head
+    if (a.head_groups > 1) {
+        const int grp = ns % a.head_groups;
+        ns /= a.head_groups;
+        head0 = grp * (R_all / a.head_groups);
+    }
     if (a.seq_order) {   // a ragged batch: row y of the grid is a head of the (y / heads)-th longest sequence
         const int rank = ns / a.n_kv_heads;
         ns = a.seq_order[rank] * a.n_kv_heads + (ns - rank * a.n_kv_heads);
@@ -179,8 +187,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
     }
     const int t_end = max(t_begin, min(tq, t_begin + a.chunk));
     if (t_end == t_begin) {   // nothing of this sequence in the split: an empty partial (mass 0; the merge skips it)
-        const int R0 = a.n_q_heads / a.n_kv_heads;
-        const int64_t pbase = ((int64_t)ns * n_slots + split) * R0;
+        const int R0 = R_all / a.head_groups;
+        const int64_t pbase = ((int64_t)ns * n_slots + split) * R_all + head0;
         for (int e = tid; e < R0 * kD; e += 256) a.part_o[pbase * kD + e] = 0.f;
         for (int e = tid; e < R0 * a.P; e += 256) a.part_w[pbase * a.P + e] = 0.f;
         if (tid < R0) {
@@ -190,7 +198,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
         return;
     }
 
-    const int R = a.n_q_heads / a.n_kv_heads, G = a.G, P = a.P;
+    const int R = R_all / a.head_groups, G = a.G, P = a.P;   // heads of this row
     const int lgG = 31 - __clz(G);   // G is a power of two
     const int Gc = G < kD ? G : kD, NG = kD / Gc;
     const int hcol = HALF ? (n & 7) : n;            // the (h, g) pair of this lane's column
@@ -207,7 +215,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
     // ---- this lane's slice of its query head: channels 32*kb .. 32*kb+31
     _Float16 qh[32];
     {
-        const uint4 *qsrc = reinterpret_cast<const uint4 *>(a.q + ((int64_t)seq * a.n_q_heads + head * R + h) * kD + 32 * kb);
+        const uint4 *qsrc = reinterpret_cast<const uint4 *>(a.q + ((int64_t)seq * a.n_q_heads + head * R_all + head0 + h) * kD + 32 * kb);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             uint4 v = qsrc[i];
@@ -697,7 +705,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
     // and the channel tile's group by a shift - integer divisions by run-time values here once cost more than
     // the rest of the epilogue, 10 us per workgroup)
     const int lgGc = 31 - __clz(Gc);
-    const int64_t pbase = ((int64_t)ns * n_slots + split) * R;
+    const int64_t pbase = ((int64_t)ns * n_slots + split) * R_all + head0;
     // pattern masses first: afterwards the table and mass area of the dynamic LDS is free for the outputs
     for (int e = tid; e < R * P; e += 256) {
         int hh = 0;
@@ -778,18 +786,19 @@ hipError_t launch_decode_packed(const DecodeArgs &a, hipStream_t s)
     const int splits = a.splits_prefix + a.splits_own;
     if (splits == 0) return hipSuccess;
     const int N = a.n_seq * a.n_kv_heads;
-    const int R = a.n_q_heads / a.n_kv_heads, NG = kD / (a.G < kD ? a.G : kD);
+    const int r = a.n_q_heads / a.n_kv_heads, NG = kD / (a.G < kD ? a.G : kD);
+    const int R = r / a.head_groups;   // heads per row of the grid
     // tail workgroups (one per stream, another one per stream for the shared prefix's tail) in rows behind the streams
     const bool tails = decode_tails_ride_along(a);
     const int n_tail = tails ? N * (a.prefix.t_tail > 0 ? 2 : 1) : 0;
-    const dim3 grid(splits, N + (n_tail + splits - 1) / splits);
+    const dim3 grid(splits, N * a.head_groups + (n_tail + splits - 1) / splits);
     // eight or fewer (head, channel group) pairs leave half of the score columns free: they take the second half
     // of every unit's tokens
     const bool half = a.G != 32 && R * NG <= 8;
     size_t lds = (size_t)a.P * 16 * 4 + (size_t)4 * R * a.w_stride * 8;   // QMs, Ws
     const size_t out_slabs = (size_t)4 * (half ? 2 : 1) * R * kD * 4;     // reused for the waves' outputs at the end
     if (lds < out_slabs) lds = out_slabs;
-    const size_t tail_lds = R <= 4 ? sizeof(TailShared<4>) : sizeof(TailShared<8>);
+    const size_t tail_lds = r <= 4 ? sizeof(TailShared<4>) : sizeof(TailShared<8>);
     if (tails && lds < tail_lds) lds = tail_lds;
     if (a.bits == 2 && a.G == 32) return launch_one<2, true, false>(a, grid, lds, s);
     if (a.bits == 2) return half ? launch_one<2, false, true>(a, grid, lds, s) : launch_one<2, false, false>(a, grid, lds, s);

@@ -263,6 +263,9 @@ struct DecodeArgs {
     int32_t w_stride;             // entries per (wave, head) row of the per-pattern softmax mass in LDS: P, or 256
                                   // when v_idx may hold PK_NO_PATTERN
     int32_t splits_prefix, splits_own;   // packed splits; two more slots hold the tails
+    int32_t head_groups;          // the matrix-core kernel takes the r query heads of a KV head in this many groups of
+                                  // r / head_groups heads, a workgroup row per (stream, group): 1, or 2 when the
+                                  // (head, V channel group) pairs of all r heads exceed a tile's 16 columns
     float *part_o;                // [N][S][r][kD]  unnormalised partial outputs
     float *part_w;                // [N][S][r][P]   softmax mass per V pattern (packed splits only)
     float *part_ml;               // [N][S][r][2]   running maximum (log2 domain) and sum

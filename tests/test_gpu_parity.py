@@ -273,7 +273,8 @@ def test_division_sequences_match_ieee_division(pk):
     (2, 8, 2, 32, 64, 0, 900),        # r = 4, group 32: four V channel groups, two K groups per 64-token block
     (1, 4, 4, 32, 16, 0, 333),        # 4-bit with group 32
     (2, 8, 4, 64, 64, 0, 640),        # 4-bit, r = 4, empty tail
-    (1, 8, 2, 32, 16, 16, 700),       # r = 8 with group 32: 32 (head, channel group) pairs, more than a tile's 16 columns
+    (1, 8, 2, 32, 16, 16, 700),       # r = 8 with group 32: 32 (head, channel group) pairs, two groups of four heads
+    (2, 12, 4, 32, 24, 0, 500),       # r = 6 with group 32, 4-bit: two groups of three heads
     (1, 5, 4, 32, 8, 0, 1300),        # r = 5 with group 32, 4-bit, several splits
     (1, 16, 2, 64, 24, 32, 900),      # r = 16: two groups of eight heads through the plain kernels
     (2, 24, 2, 128, 8, 0, 640),       # r = 12: a full and a half-filled head group
@@ -390,6 +391,7 @@ def _ragged_batch(oracle, pk, kw, K, V, Mk, Mv, lens):
 @pytest.mark.parametrize("hkv,hq,bits,G,P,R,lens", [
     (2, 8, 2, 64, 32, 32, [0, 70, 197, 1000, 517]),        # an empty sequence, a tail-only one, several splits
     (1, 4, 4, 32, 16, 0, [640, 64, 1, 333]),               # 4-bit, group 32, no recent window
+    (2, 16, 2, 32, 16, 32, [300, 0, 900, 64]),             # r = 8 with group 32: the heads of a KV head in two groups
 ])
 def test_decode_ragged_batch_parity(oracle, pk, hkv, hq, bits, G, P, R, lens):
     S, T = len(lens), max(lens)

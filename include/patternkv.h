@@ -122,8 +122,8 @@ typedef struct {
     int32_t n_seq;        /* sequences (layers x batch flattened), >= 1                       */
     int32_t n_kv_heads;   /* >= 1                                                             */
     int32_t n_q_heads;    /* multiple of n_kv_heads; r = n_q_heads/n_kv_heads in 1..64 (at d = 128 the matrix-core
-                             decode kernel takes r <= 8, with G = 32 r = 1..4, 6 or 8; other head counts decode
-                             through the plain kernels)                                          */
+                             decode kernel takes r <= 8 and even r up to 16, with G = 32 r = 1..4, 6 or 8; other head
+                             counts decode through the plain kernels)                            */
     int32_t head_dim;     /* d: 128 (the tuned kernels), or 96 / 256 (the other head sizes of Sec. 3.3: plain
                              vector-ALU kernels; every call takes them).  min(G, d)
                              must divide d (d = 96: G = 32 or 128)                                  */

@@ -548,9 +548,11 @@ static pk_status decode_impl(const pk_config *cfg, const pk_cache *cache, const 
     a.G = cfg->group;
     a.d = cfg->head_dim;
     a.v_thresholded = (cfg->v_rho > 0.f || (has_prefix && prefix_cfg->v_rho > 0.f)) ? 1 : 0;
-    {   // 6 or 8 heads per KV head over 32-channel groups: two groups of heads, 12 or 16 columns each
+    {   // 6 or 8 heads per KV head over 32-channel groups, or 10 to 16 heads: two groups of heads, each with at
+        // most 8 heads and 16 (head, V channel group) pairs
         const int64_t ng = kD / (cfg->group < kD ? cfg->group : kD);
-        a.head_groups = (cfg->head_dim == kD && r <= 8 && r * ng > 16 && r % 2 == 0 && (r / 2) * ng <= 16) ? 2 : 1;
+        const bool one_fits = r <= 8 && r * ng <= 16;
+        a.head_groups = (cfg->head_dim == kD && !one_fits && r % 2 == 0 && r / 2 <= 8 && (r / 2) * ng <= 16) ? 2 : 1;
     }
     a.softmax_scale = softmax_scale;
     a.part_o = reinterpret_cast<float *>(workspace);

@@ -18,12 +18,13 @@ constexpr int kMaxP = 256;
 constexpr float kLn2 = 0.6931471805599453f;
 
 // Stand-alone launch of the tails, for decodes without a packed part or with too many tails to ride along in the
-// packed kernel's launch (decode_tails_ride_along).  x = 0: own tails, x = 1: the shared prefix's tail.
+// packed kernel's launch (decode_tails_ride_along).  x = 0: own tails, x = 1: the shared prefix's tail; y: stream;
+// z: group of query heads.
 template <int RP>
 __global__ __launch_bounds__(256) void decode_tail_kernel(DecodeArgs a)
 {
     __shared__ TailShared<RP> sh;
-    decode_tail_body<RP>(a, blockIdx.x, blockIdx.y, sh);
+    decode_tail_body<RP>(a, blockIdx.x, blockIdx.y, blockIdx.z, sh);
 }
 
 // log-sum-exp merge of the partials of one (sequence, query head); 128*NQ threads, thread <-> (channel c,
@@ -182,9 +183,11 @@ hipError_t launch_decode(const DecodeArgs &a, hipStream_t s)
 {
     const int r = a.n_q_heads / a.n_kv_heads;
     // the matrix-core kernel holds the (head, V channel group) pairs of a group of heads in the 16 columns of one tile
-    // and takes up to 8 heads per KV head, in one group or two; what does not fit (5 or 7 heads with 32-channel
-    // groups), more heads and the other head dimensions run the plain kernels
-    if (a.d != kD || r > 8 || (r / a.head_groups) * (kD / (a.G < kD ? a.G : kD)) > 16) return launch_generic_decode(a, s);
+    // and takes up to 8 heads per group, the heads of a KV head in one group or two; what does not fit (5 or 7 heads
+    // with 32-channel groups, an odd head count above 8, more than 16 heads) and the other head dimensions run the
+    // plain kernels
+    const int rg = r / a.head_groups;
+    if (a.d != kD || rg > 8 || rg * (kD / (a.G < kD ? a.G : kD)) > 16) return launch_generic_decode(a, s);
     const int N = a.n_seq * a.n_kv_heads;
     hipError_t e;
     if (a.seq_order && a.splits_prefix + a.splits_own > 0) {
@@ -195,8 +198,8 @@ hipError_t launch_decode(const DecodeArgs &a, hipStream_t s)
     if ((a.own.t_tail > 0 || a.prefix.t_tail > 0) && !decode_tails_ride_along(a)) {
         // (launched for the prefix only if it has a tail: workgroups that find nothing to do still cost their
         // dispatch, tens of nanoseconds each)
-        const dim3 grid(a.prefix.t_tail > 0 ? 2 : 1, N);
-        if (r <= 4)
+        const dim3 grid(a.prefix.t_tail > 0 ? 2 : 1, N, a.head_groups);
+        if (rg <= 4)
             hipLaunchKernelGGL((decode_tail_kernel<4>), grid, dim3(256), 0, s, a);
         else
             hipLaunchKernelGGL((decode_tail_kernel<8>), grid, dim3(256), 0, s, a);

@@ -148,13 +148,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
     // splits leaves idle, instead of running as a kernel of their own afterwards.
     if ((int)blockIdx.y >= a.n_seq * a.n_kv_heads * a.head_groups) {
         const int N = a.n_seq * a.n_kv_heads;
-        const int id = ((int)blockIdx.y - N * a.head_groups) * (int)gridDim.x + (int)blockIdx.x;
-        if (id >= N * (a.prefix.t_tail > 0 ? 2 : 1)) return;
-        const int which = id / N;
-        if (a.n_q_heads / a.n_kv_heads <= 4)
-            decode_tail_body<4>(a, which, id - which * N, *reinterpret_cast<TailShared<4> *>(dyn_smem));
+        const int NG2 = N * a.head_groups;   // (stream, head group) pairs
+        const int id = ((int)blockIdx.y - NG2) * (int)gridDim.x + (int)blockIdx.x;
+        if (id >= NG2 * (a.prefix.t_tail > 0 ? 2 : 1)) return;
+        const int which = id / NG2, sg = id - which * NG2;
+        if (a.n_q_heads / a.n_kv_heads / a.head_groups <= 4)
+            decode_tail_body<4>(a, which, sg / a.head_groups, sg % a.head_groups, *reinterpret_cast<TailShared<4> *>(dyn_smem));
         else
-            decode_tail_body<8>(a, which, id - which * N, *reinterpret_cast<TailShared<8> *>(dyn_smem));
+            decode_tail_body<8>(a, which, sg / a.head_groups, sg % a.head_groups, *reinterpret_cast<TailShared<8> *>(dyn_smem));
         return;
     }
     const int tid = threadIdx.x, lane = tid & 63, n = lane & 15, kb = lane >> 4;
@@ -790,7 +791,7 @@ hipError_t launch_decode_packed(const DecodeArgs &a, hipStream_t s)
     const int R = r / a.head_groups;   // heads per row of the grid
     // tail workgroups (one per stream, another one per stream for the shared prefix's tail) in rows behind the streams
     const bool tails = decode_tails_ride_along(a);
-    const int n_tail = tails ? N * (a.prefix.t_tail > 0 ? 2 : 1) : 0;
+    const int n_tail = tails ? N * a.head_groups * (a.prefix.t_tail > 0 ? 2 : 1) : 0;
     const dim3 grid(splits, N * a.head_groups + (n_tail + splits - 1) / splits);
     // eight or fewer (head, channel group) pairs leave half of the score columns free: they take the second half
     // of every unit's tokens
@@ -798,7 +799,7 @@ hipError_t launch_decode_packed(const DecodeArgs &a, hipStream_t s)
     size_t lds = (size_t)a.P * 16 * 4 + (size_t)4 * R * a.w_stride * 8;   // QMs, Ws
     const size_t out_slabs = (size_t)4 * (half ? 2 : 1) * R * kD * 4;     // reused for the waves' outputs at the end
     if (lds < out_slabs) lds = out_slabs;
-    const size_t tail_lds = r <= 4 ? sizeof(TailShared<4>) : sizeof(TailShared<8>);
+    const size_t tail_lds = R <= 4 ? sizeof(TailShared<4>) : sizeof(TailShared<8>);
     if (tails && lds < tail_lds) lds = tail_lds;
     if (a.bits == 2 && a.G == 32) return launch_one<2, true, false>(a, grid, lds, s);
     if (a.bits == 2) return half ? launch_one<2, false, true>(a, grid, lds, s) : launch_one<2, false, false>(a, grid, lds, s);

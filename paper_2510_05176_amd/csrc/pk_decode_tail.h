@@ -32,12 +32,13 @@ __device__ __forceinline__ float row_sum_to_last(float v)
 // Thread (cg, tg) = (tid % 16, tid / 16) owns channels 8cg .. 8cg+7 of the tokens tg, tg+16, ... of a tile, in
 // the score phase and in the value phase alike: the 16 lanes of a token read its 256-byte row in 16-byte
 // pieces, scores are summed over those lanes, outputs over the token groups at the end.
+// grp: which of the stream's head_groups groups of query heads (r of them each) the workgroup takes.
 template <int RP>
-__device__ __forceinline__ void decode_tail_body(const DecodeArgs &a, int which, int n, TailShared<RP> &sh)
+__device__ __forceinline__ void decode_tail_body(const DecodeArgs &a, int which, int n, int grp, TailShared<RP> &sh)
 {
     const int tid = threadIdx.x;
     const int n_slots = a.splits_prefix + a.splits_own + 2;
-    const int r = a.n_q_heads / a.n_kv_heads;
+    const int r_all = a.n_q_heads / a.n_kv_heads, r = r_all / a.head_groups, head0 = grp * r;
     const int seq = n / a.n_kv_heads, head = n - seq * a.n_kv_heads;
     const CacheView &cv = which == 0 ? a.own : a.prefix;
     const int cstream = which == 0 ? n : head;
@@ -53,7 +54,7 @@ __device__ __forceinline__ void decode_tail_body(const DecodeArgs &a, int which,
 #pragma unroll
     for (int h = 0; h < RP; ++h) {
         uint4 v = make_uint4(0u, 0u, 0u, 0u);
-        if (h < r) v = *reinterpret_cast<const uint4 *>(a.q + ((int64_t)seq * a.n_q_heads + head * r + h) * kD + 8 * cg);
+        if (h < r) v = *reinterpret_cast<const uint4 *>(a.q + ((int64_t)seq * a.n_q_heads + head * r_all + head0 + h) * kD + 8 * cg);
         const __half2 *h2 = reinterpret_cast<const __half2 *>(&v);
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
@@ -172,7 +173,7 @@ __device__ __forceinline__ void decode_tail_body(const DecodeArgs &a, int which,
     __syncthreads();
     if (tid < kD) {
         const int c = tid;
-        const int64_t pbase = ((int64_t)n * n_slots + slot) * r;
+        const int64_t pbase = ((int64_t)n * n_slots + slot) * r_all + head0;
 #pragma unroll
         for (int h = 0; h < RP; ++h) {
             if (h < r) {

@@ -265,7 +265,7 @@ struct DecodeArgs {
     int32_t splits_prefix, splits_own;   // packed splits; two more slots hold the tails
     int32_t head_groups;          // the matrix-core kernel takes the r query heads of a KV head in this many groups of
                                   // r / head_groups heads, a workgroup row per (stream, group): 1, or 2 when the
-                                  // (head, V channel group) pairs of all r heads exceed a tile's 16 columns
+                                  // (head, V channel group) pairs of all r heads exceed a tile's 16 columns or r > 8
     float *part_o;                // [N][S][r][kD]  unnormalised partial outputs
     float *part_w;                // [N][S][r][P]   softmax mass per V pattern (packed splits only)
     float *part_ml;               // [N][S][r][2]   running maximum (log2 domain) and sum
@@ -299,7 +299,7 @@ hipError_t launch_decode(const DecodeArgs &a, hipStream_t s);
 // latency by occupancy, eight workgroups per CU when launched alone).
 inline bool decode_tails_ride_along(const DecodeArgs &a)
 {
-    const int n_tail = a.n_seq * a.n_kv_heads * (a.prefix.t_tail > 0 ? 2 : 1);
+    const int n_tail = a.n_seq * a.n_kv_heads * a.head_groups * (a.prefix.t_tail > 0 ? 2 : 1);
     return a.splits_prefix + a.splits_own > 0 && (a.own.t_tail > 0 || a.prefix.t_tail > 0) && n_tail <= 1024;
 }
 int decode_chunk(int64_t n_streams, int64_t t_packed_total, int P, int r);

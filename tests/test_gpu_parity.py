@@ -276,8 +276,10 @@ def test_division_sequences_match_ieee_division(pk):
     (1, 8, 2, 32, 16, 16, 700),       # r = 8 with group 32: 32 (head, channel group) pairs, two groups of four heads
     (2, 12, 4, 32, 24, 0, 500),       # r = 6 with group 32, 4-bit: two groups of three heads
     (1, 5, 4, 32, 8, 0, 1300),        # r = 5 with group 32, 4-bit, several splits
-    (1, 16, 2, 64, 24, 32, 900),      # r = 16: two groups of eight heads through the plain kernels
-    (2, 24, 2, 128, 8, 0, 640),       # r = 12: a full and a half-filled head group
+    (1, 16, 2, 64, 24, 32, 900),      # r = 16: two groups of eight heads
+    (2, 24, 2, 128, 8, 0, 640),       # r = 12: two groups of six heads
+    (1, 16, 2, 64, 8, 0, 50),         # r = 16, nothing packed yet: the tail kernel on its own, two head groups
+    (1, 18, 2, 64, 8, 16, 700),       # r = 18: three groups of up to eight heads through the plain kernels
 ])
 def test_decode_attention_parity(oracle, pk, hkv, hq, bits, G, P, R, T):
     kw, ocfg, gcfg, K, V, Mk, Mv = make_case(oracle, pk, 31 + hq + T, T=T, P=P, bits=bits, G=G, R=R, F=max(G, 64),

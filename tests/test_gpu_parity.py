@@ -792,22 +792,24 @@ class PagedView:
         return parts[rows.reshape(-1)].reshape(-1)                     # [n_seq][hkv][page][...] = stream-major
 
 
-@pytest.mark.parametrize("bits,G,P,metric,R,PT,ragged", [
-    (2, 64, 32, 0, 32, 128, False),
-    (4, 32, 16, 0, 0, 256, False),
-    (2, 128, 130, 1, 100, 128, False),      # groups of 128 tokens = whole pages, large table, min-max rule
-    (2, 64, 32, 0, 32, 128, True),          # ragged appends and ragged decode over pages
+@pytest.mark.parametrize("d,bits,G,P,metric,R,PT,ragged", [
+    (128, 2, 64, 32, 0, 32, 128, False),
+    (128, 4, 32, 16, 0, 0, 256, False),
+    (128, 2, 128, 130, 1, 100, 128, False),      # groups of 128 tokens = whole pages, large table, min-max rule
+    (128, 2, 64, 32, 0, 32, 128, True),          # ragged appends and ragged decode over pages
+    (256, 2, 64, 16, 0, 32, 128, False),         # the plain kernels of the other head dimensions over pages
+    (96, 4, 32, 16, 0, 0, 256, True),            # ... with ragged appends and a ragged decode
 ])
-def test_paged_cache_parity(oracle, pk, bits, G, P, metric, R, PT, ragged):
+def test_paged_cache_parity(oracle, pk, d, bits, G, P, metric, R, PT, ragged):
     """A cache whose packed arrays are a pool of pages, with a scrambled page table (more pages in the pool than
     the batch uses): appends in several pieces, then dequantize and decode.  Gathered back through the page table,
     every stream must equal the oracle's contiguous cache; attention and reconstruction must agree as usual."""
     S, hkv, hq, F, cap = 3, 2, 8, 128, 1024
-    kw = dict(n_kv_heads=hkv, n_q_heads=hq, head_dim=128, n_patterns=P, bits=bits, group=G, recent=R, flush=F,
+    kw = dict(n_kv_heads=hkv, n_q_heads=hq, head_dim=d, n_patterns=P, bits=bits, group=G, recent=R, flush=F,
               t_capacity=cap, metric=metric)
     pages_per_seq = cap // PT
     n_pages = S * pages_per_seq + 5
-    K, V = synth.make_kv(700 + P + PT, synth.KVSpec(1, S, hkv, hq, cap, 128, 12))
+    K, V = synth.make_kv(700 + P + PT, synth.KVSpec(1, S, hkv, hq, cap, d, 12))
     Mk, _, _, _ = oracle.mine(K[0].view(np.uint16), P, 3)
     Mv, _, _, _ = oracle.mine(V[0].view(np.uint16), P, 3)
     Mkd, Mvd = dev(Mk.view(np.float16)), dev(Mv.view(np.float16))
@@ -820,7 +822,7 @@ def test_paged_cache_parity(oracle, pk, bits, G, P, metric, R, PT, ragged):
     states, done = [[0, 0, 0] for _ in range(S)], [0] * S
     for n_new in rounds:
         n_max = max(n_new)
-        Kn, Vn = np.zeros((S, hkv, n_max, 128), np.float16), np.zeros((S, hkv, n_max, 128), np.float16)
+        Kn, Vn = np.zeros((S, hkv, n_max, d), np.float16), np.zeros((S, hkv, n_max, d), np.float16)
         for i, n in enumerate(n_new):
             Kn[i, :, :n], Vn[i, :, :n] = K[i, :, done[i]:done[i] + n], V[i, :, done[i]:done[i] + n]
             ocs[i].append(Kn[i:i + 1, :, :n].view(np.uint16), Vn[i:i + 1, :, :n].view(np.uint16), Mk, Mv)
@@ -841,14 +843,14 @@ def test_paged_cache_parity(oracle, pk, bits, G, P, metric, R, PT, ragged):
                 per = raw.numel() // S
                 return raw[i * per:(i + 1) * per]
         compare_caches(oracle, oc, One(), metric)
-    q = synth.make_queries(34, S, hq, 128)
-    want, _ = oracle.decode_attention_ragged(ocs, q.view(np.uint16), Mk, Mv, 128 ** -0.5)
+    q = synth.make_queries(34, S, hq, d)
+    want, _ = oracle.decode_attention_ragged(ocs, q.view(np.uint16), Mk, Mv, d ** -0.5)
     if ragged:
         st = torch.tensor([s + [0] for s in states], dtype=torch.int32, device="cuda")
         got = pk.pk_decode_attention_ragged(gcfg, gc, st, max(s[0] for s in states), max(s[1] for s in states), dev(q),
-                                            128 ** -0.5, Mkd, Mvd).cpu().numpy()
+                                            d ** -0.5, Mkd, Mvd).cpu().numpy()
     else:
-        got = pk.pk_decode_attention(gcfg, gc, dev(q), 128 ** -0.5, Mkd, Mvd).cpu().numpy()
+        got = pk.pk_decode_attention(gcfg, gc, dev(q), d ** -0.5, Mkd, Mvd).cpu().numpy()
         # reconstruction through the page table
         kg, vg = pk.pk_dequantize(gcfg, gc, Mkd, Mvd)
         tq = gc.t_quant

@@ -30,12 +30,12 @@ def dev(a_f16):
     return torch.from_numpy(np.ascontiguousarray(a_f16).view(np.int16)).cuda().view(torch.float16)
 
 
-def build_case(pk, seed, n_seq, hkv, hq, T, P, bits, G, R, F, prefix_T=0):
+def build_case(pk, seed, n_seq, hkv, hq, T, P, bits, G, R, F, prefix_T=0, d=128):
     """Mine, append and return everything one decode call needs (all on the GPU, through the library)."""
     cap = -(-T // F) * F
-    cfg = pk.Config(n_seq=n_seq, n_kv_heads=hkv, n_q_heads=hq, head_dim=128, n_patterns=P, seqs_per_set=0, bits=bits,
+    cfg = pk.Config(n_seq=n_seq, n_kv_heads=hkv, n_q_heads=hq, head_dim=d, n_patterns=P, seqs_per_set=0, bits=bits,
                     group=G, recent=R, flush=F, t_capacity=cap, metric=pk.METRIC_L2)
-    K, V = synth.make_kv(seed, synth.KVSpec(1, n_seq, hkv, hq, T, 128, 8))
+    K, V = synth.make_kv(seed, synth.KVSpec(1, n_seq, hkv, hq, T, d, 8))
     Kd, Vd = dev(K), dev(V)
     Mk = pk.pk_mine_patterns(cfg, Kd[0], 3)
     Mv = pk.pk_mine_patterns(cfg, Vd[0], 3)
@@ -43,18 +43,18 @@ def build_case(pk, seed, n_seq, hkv, hq, T, P, bits, G, R, F, prefix_T=0):
     pk.pk_quantize_append(cfg, cache, Kd, Vd, Mk, Mv)
     prefix = None
     if prefix_T:
-        pcfg = pk.Config(n_seq=1, n_kv_heads=hkv, n_q_heads=hq, head_dim=128, n_patterns=P, seqs_per_set=0, bits=bits,
+        pcfg = pk.Config(n_seq=1, n_kv_heads=hkv, n_q_heads=hq, head_dim=d, n_patterns=P, seqs_per_set=0, bits=bits,
                          group=G, recent=R, flush=F, t_capacity=-(-prefix_T // F) * F, metric=pk.METRIC_L2)
-        Kp, Vp = synth.make_kv(seed + 100, synth.KVSpec(1, 1, hkv, hq, prefix_T, 128, 8))
+        Kp, Vp = synth.make_kv(seed + 100, synth.KVSpec(1, 1, hkv, hq, prefix_T, d, 8))
         prefix = pk.Cache(pcfg)
         pk.pk_quantize_append(pcfg, prefix, dev(Kp), dev(Vp), Mk, Mv)
-    q = dev(synth.make_queries(seed, n_seq, hq, 128))
+    q = dev(synth.make_queries(seed, n_seq, hq, d))
     return cfg, cache, prefix, q, Mk, Mv
 
 
 def both_ways(pk, case):
     cfg, cache, prefix, q, Mk, Mv = case
-    scale = 128 ** -0.5
+    scale = float(q.shape[-1]) ** -0.5
     lse_a = torch.empty(q.shape[:2], dtype=torch.float32, device="cuda")
     lse_b = torch.empty_like(lse_a)
     want = pk.pk_decode_attention(cfg, cache, q, scale, Mk, Mv, lse=lse_a, prefix=prefix)
@@ -75,6 +75,11 @@ def test_noalloc_matches_workspace_call_twice_in_a_row(pk):
     both_ways(pk, big)
     both_ways(pk, small)     # smaller input over the array the first call left behind
     both_ways(pk, big)
+    # the other kernels that write partials: two groups of query heads per KV head, and the plain kernels of
+    # head dimension 256
+    both_ways(pk, build_case(pk, 13, n_seq=2, hkv=1, hq=16, T=900, P=16, bits=2, G=64, R=16, F=64))
+    both_ways(pk, build_case(pk, 14, n_seq=2, hkv=2, hq=4, T=1100, P=16, bits=4, G=128, R=0, F=128, prefix_T=300, d=256))
+    both_ways(pk, small)
 
 
 def test_noalloc_refuses_partials_beyond_the_array(pk):

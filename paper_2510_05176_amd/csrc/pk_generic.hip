@@ -8,6 +8,7 @@
 // pattern and dequantize are covered, on contiguous and on paged caches.
 #pragma clang fp contract(off)
 
+#include "pk_assign_mfma.h"
 #include "pk_quant_arith.h"
 
 namespace pk {
@@ -82,6 +83,207 @@ __device__ __forceinline__ void nearest_pattern(const uint4 (&x)[D / 8], const _
     }
     best_i = bi;
     best_d = bd;
+}
+
+// ---------------------------------------------------------------------------------------------- Euclidean search
+// Nearest pattern under the Euclidean rule on the matrix cores at head dimension D (96 or 256), the scheme of the
+// tuned search with D / 32 operand steps: a wave ranks a 16-vector tile against 16 patterns per round,
+// e = x.m - (|m|^2 + |x|^2) / 2 = -|x - m|^2 / 2 from v_mfma_f32_16x16x32_f16 (fp16 products are exact in binary32,
+// only the accumulation rounds); the binary32 patterns of e, read as unsigned integers with the pattern index in
+// the low byte, order like the distances; best and second best are tracked, and a vector whose gap between the
+// two is inside the rounding band of that form is evaluated again exactly by the whole wave - the squared binary32
+// differences over all patterns, lowest index on ties - so every index equals the exact argmin.  The table lives
+// in LDS (rows of D + 16 halves: 16-byte reads of 16 rows x 4 column groups fall on distinct banks), the whole of it
+// or, when it would not fit beside a second workgroup, one workgroup per CU.
+template <int D>
+struct GenSearchLds {
+    static constexpr int kStride = D + 16;   // halves per table row
+    __half *tab;      // [pad16(P)][kStride], rows past P zero
+    float *nh;        // [pad16(P)]  -|m|^2 / 2, -inf past P
+    float *red;       // [4]
+    __half *xrow;     // [4 waves][D]: the vector under exact evaluation
+    __device__ GenSearchLds(unsigned char *base, int P)
+    {
+        tab = reinterpret_cast<__half *>(base);
+        nh = reinterpret_cast<float *>(tab + (size_t)pad16(P) * kStride);
+        red = nh + pad16(P);
+        xrow = reinterpret_cast<__half *>(red + 4);
+    }
+    static size_t bytes(int P) { return (size_t)pad16(P) * kStride * 2 + (size_t)pad16(P) * 4 + 16 + (size_t)4 * D * 2; }
+};
+
+// Stage the table of one pattern set and the row norms; returns max_p |m_p|^2.  All 256 threads; ends with a barrier.
+template <int D>
+__device__ __forceinline__ float gen_search_stage(const __half *Mg, int P, const GenSearchLds<D> &sh)
+{
+    constexpr int kStride = GenSearchLds<D>::kStride;
+    const int tid = threadIdx.x, Pp = pad16(P);
+    for (int i = tid; i < Pp * (D / 8); i += 256) {
+        const int r = i / (D / 8), ch = i - r * (D / 8);
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (r < P) v = *reinterpret_cast<const uint4 *>(Mg + (int64_t)r * D + 8 * ch);
+        *reinterpret_cast<uint4 *>(sh.tab + r * kStride + 8 * ch) = v;
+    }
+    __syncthreads();
+    float mx = 0.f;
+    for (int r = tid; r < Pp; r += 256) {
+        float acc = 0.f;
+        for (int ch = 0; ch < D / 8; ++ch) {
+            const uint4 v = *reinterpret_cast<const uint4 *>(sh.tab + r * kStride + 8 * ch);
+            const half2_t *h = reinterpret_cast<const half2_t *>(&v);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) acc = __builtin_amdgcn_fdot2(h[k], h[k], acc, false);
+        }
+        sh.nh[r] = r < P ? -0.5f * acc : -INFINITY;
+        mx = fmaxf(mx, acc);
+    }
+    mx = wave_max(mx);
+    if ((tid & 63) == 0) sh.red[tid >> 6] = mx;
+    __syncthreads();
+    return fmaxf(fmaxf(sh.red[0], sh.red[1]), fmaxf(sh.red[2], sh.red[3]));
+}
+
+// One 16-vector tile by one wave: row = the lane's vector (token n = lane % 16 of the tile).  Every lane of column n
+// returns the nearest pattern of token n and its squared distance (from the expanded form, 8 mantissa bits dropped,
+// or the exact one where the vector was evaluated again).
+template <int D>
+__device__ __forceinline__ void gen_search_tile(const __half *row, const GenSearchLds<D> &sh, float norm2_max, int P, __half *xrow,
+                                                int lane, int &best, float &best_d)
+{
+    constexpr int KS = D / 32;   // operand steps of 32 channels
+    constexpr int kStride = GenSearchLds<D>::kStride;
+    const int n = lane & 15, kb = lane >> 4, Pp = pad16(P);
+    uint4 xb[KS];   // B operand: token n, channels 32 s + 8 kb + j
+#pragma unroll
+    for (int s = 0; s < KS; ++s) xb[s] = *reinterpret_cast<const uint4 *>(row + 32 * s + 8 * kb);
+    float xx = 0.f;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+        const half2_t *h = reinterpret_cast<const half2_t *>(&xb[s]);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) xx = __builtin_amdgcn_fdot2(h[k], h[k], xx, false);
+    }
+    xx += __shfl_xor(xx, 16);
+    xx += __shfl_xor(xx, 32);
+    const float hx = 0.5f * xx;
+    uint32_t k1 = 0xffffffffu, k2 = 0xffffffffu;
+    for (int p0 = 0; p0 < Pp; p0 += 16) {
+        const __half *arow = sh.tab + (p0 + n) * kStride + 8 * kb;
+        const float4 nh = *reinterpret_cast<const float4 *>(sh.nh + p0 + 4 * kb);
+        floatx4_t e = {nh.x - hx, nh.y - hx, nh.z - hx, nh.w - hx};
+#pragma unroll
+        for (int s = 0; s < KS; ++s) e = mfma_f16(*reinterpret_cast<const uint4 *>(arow + 32 * s), xb[s], e);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t key = __builtin_amdgcn_perm(__float_as_uint(e[i]), (uint32_t)(p0 + 4 * kb + i), 0x07060500u);
+            k2 = max(min(k1, k2), min(max(k1, k2), key));   // second smallest so far
+            k1 = min(k1, key);
+        }
+    }
+#pragma unroll
+    for (int off = 16; off <= 32; off <<= 1) {   // the four lane groups of the column
+        const uint32_t o1 = (uint32_t)__shfl_xor((int)k1, off), o2 = (uint32_t)__shfl_xor((int)k2, off);
+        k2 = min(min(k2, o2), max(k1, o1));
+        k1 = min(k1, o1);
+    }
+    best = (int)(k1 & 0xffu);
+    const float bv = -2.f * __uint_as_float(k1 & 0xffffff00u), second = -2.f * __uint_as_float(k2 & 0xffffff00u);
+    best_d = fmaxf(bv, 0.f);
+    // rounding band: the accumulation over KS matrix instructions (far below 2^-21 (|x|^2 + |m|^2) each) and the 8
+    // mantissa bits the keys drop, with a wide margin
+    const float band = (KS > 4 ? 1.52587890625e-05f : 7.62939453125e-06f) * (xx + norm2_max) + 6.103515625e-05f * second;
+    const bool flag = P > 1 && !(second - bv > band);
+    unsigned long long todo = __ballot(flag) & 0xffffull;   // one bit per column
+    while (todo) {
+        const int col = __ffsll((long long)todo) - 1;
+        todo &= todo - 1;
+        if (n == col) {
+#pragma unroll
+            for (int s = 0; s < KS; ++s) *reinterpret_cast<uint4 *>(xrow + 32 * s + 8 * kb) = xb[s];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        float bd = INFINITY;
+        int bi = 0x7fffffff;
+        for (int p = lane; p < P; p += 64) {
+            const __half *m = sh.tab + p * kStride;
+            float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+#pragma unroll 4
+            for (int ch = 0; ch < D / 8; ++ch) {
+                const uint4 mv = *reinterpret_cast<const uint4 *>(m + 8 * ch);
+                const uint4 xv = *reinterpret_cast<const uint4 *>(xrow + 8 * ch);
+                const float d0 = sub_lo(xv.x, mv.x), d1 = sub_hi(xv.x, mv.x), d2 = sub_lo(xv.y, mv.y), d3 = sub_hi(xv.y, mv.y);
+                const float d4 = sub_lo(xv.z, mv.z), d5 = sub_hi(xv.z, mv.z), d6 = sub_lo(xv.w, mv.w), d7 = sub_hi(xv.w, mv.w);
+                a0 = fmaf(d0, d0, a0); a1 = fmaf(d1, d1, a1); a2 = fmaf(d2, d2, a2); a3 = fmaf(d3, d3, a3);
+                a0 = fmaf(d4, d4, a0); a1 = fmaf(d5, d5, a1); a2 = fmaf(d6, d6, a2); a3 = fmaf(d7, d7, a3);
+            }
+            const float dist = (a0 + a1) + (a2 + a3);
+            if (dist < bd) {
+                bd = dist;
+                bi = p;
+            }
+        }
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const float od = __shfl_xor(bd, off);
+            const int oi = __shfl_xor(bi, off);
+            if (od < bd || (od == bd && oi < bi)) {
+                bd = od;
+                bi = oi;
+            }
+        }
+        if (n == col) {
+            best = bi;
+            best_d = bd;
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+// Pattern index of every vector to quantize under the Euclidean rule: a workgroup stages its stream's table once and
+// takes tiles_per_wg tiles of 16 vectors, a wave per tile.
+template <int D>
+__global__ __launch_bounds__(256) void gen_assign_mfma_kernel(QuantArgs a, int tiles_per_wg)
+{
+    extern __shared__ __align__(16) unsigned char gen_search_smem[];
+    const GenSearchLds<D> sh(gen_search_smem, a.P);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, ns = blockIdx.y;
+    take_sequence_entry(a, ns);
+    const int n_tiles = a.nq / 16;   // nq is a multiple of the group size
+    const int tile0 = blockIdx.x * tiles_per_wg, tile1 = min(n_tiles, tile0 + tiles_per_wg);
+    if (tile0 >= n_tiles) return;    // a ragged append: sized for the longest sequence
+    const float norm2_max = gen_search_stage<D>(a.patterns + (int64_t)a.sets.set_of(ns) * a.P * D, a.P, sh);
+    for (int tile = tile0 + wave; tile < tile1; tile += 4) {
+        int best;
+        float bd;
+        gen_search_tile<D>(a.src.row_d(ns, tile * 16 + (lane & 15), D), sh, norm2_max, a.P, sh.xrow + wave * D, lane, best, bd);
+        if (lane < 16) a.idx[a.map.pos(ns, a.t0 + tile * 16) + lane] = (uint8_t)best;
+    }
+}
+
+// The assignment step of mining (Sec. 3.1 Eq. 4), the same search over the vectors of a set.
+template <int D>
+__global__ __launch_bounds__(256) void gen_mine_assign_mfma_kernel(MineArgs a, int last, int tiles_per_wg)
+{
+    extern __shared__ __align__(16) unsigned char gen_search_smem[];
+    const GenSearchLds<D> sh(gen_search_smem, a.P);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, s = blockIdx.y;
+    const int n_tiles = (a.T + 15) / 16;
+    const int tile0 = blockIdx.x * tiles_per_wg, tile1 = min(n_tiles, tile0 + tiles_per_wg);
+    if (tile0 >= n_tiles) return;
+    const float norm2_max = gen_search_stage<D>(a.patterns + (int64_t)s * a.P * D, a.P, sh);
+    for (int tile = tile0 + wave; tile < tile1; tile += 4) {
+        const int t = tile * 16 + (lane & 15);   // a vector past the set's end repeats the last one; nothing is stored for it
+        int best;
+        float bd;
+        gen_search_tile<D>(a.x + (int64_t)s * a.set_stride + (int64_t)min(t, a.T - 1) * D, sh, norm2_max, a.P, sh.xrow + wave * D, lane,
+                           best, bd);
+        if (lane < 16 && t < a.T) {
+            a.assign_ws[(int64_t)s * a.T + t] = best;
+            if (last && a.assign) a.assign[(int64_t)s * a.T + t] = best;
+            a.best[(int64_t)s * a.T + t] = bd;
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------------------------- quantize-append
@@ -240,45 +442,69 @@ __global__ __launch_bounds__(256) void gen_mine_init_kernel(MineArgs a)
     a.patterns[(int64_t)s * a.P * a.d + w] = a.x[(int64_t)s * a.set_stride + w];   // the first P vectors
 }
 
-// assignment step: a workgroup takes 256 consecutive vectors of a set
-template <int D>
-__global__ __launch_bounds__(kGenThreads) void gen_mine_assign_kernel(MineArgs a, int last)
+// cluster sums of one chunk of one set for a block of patterns (blockIdx.z).  The chunk is cut into
+// pieces of 1024 vectors whose assignments are staged in LDS, and every piece into kGenThreads / d consecutive slices
+// (two at d = 96, one at d = 256); thread <-> (slice, channel) adds the slice's vectors in order into the slice's
+// [patterns][d] accumulators in LDS (only this thread ever touches its column), the slices are added in order at the
+// end: the order of all additions is fixed.  The members are counted by all threads with integer atomics.
+// At the end the block goes to the chunk's own [P][d] part of the workspace.  A workgroup reads the assignment of
+// every vector of the chunk and the vectors of its own patterns only.
+constexpr int kSumsLdsFloats = 12288;   // accumulators per workgroup: floor(12288 / (slices * d)) - 1 patterns per block
+__global__ __launch_bounds__(kGenThreads) void gen_mine_sums_kernel(MineArgs a, int chunk, int pblock)
 {
-    __shared__ __align__(16) __half tab[kTabRows * D];
-    const int tid = threadIdx.x, s = blockIdx.y, t = blockIdx.x * kGenThreads + tid;
-    const bool live = t < a.T;
-    uint4 x[D / 8];
-    const uint4 *row = reinterpret_cast<const uint4 *>(a.x + (int64_t)s * a.set_stride + (int64_t)(live ? t : a.T - 1) * D);
-#pragma unroll
-    for (int k = 0; k < D / 8; ++k) x[k] = row[k];
-    int bi;
-    float bd;
-    nearest_pattern<D, PK_METRIC_L2>(x, a.patterns + (int64_t)s * a.P * D, a.P, tab, tid, bi, bd);
-    if (live) {
-        a.assign_ws[(int64_t)s * a.T + t] = bi;
-        if (last && a.assign) a.assign[(int64_t)s * a.T + t] = bi;
-        a.best[(int64_t)s * a.T + t] = bd;
-    }
-}
-
-// cluster sums of one chunk of one set, vectors in order: thread <-> channel adds into the chunk's own [P][d] block
-// of the workspace (only this thread ever touches its column), thread 0 counts
-__global__ __launch_bounds__(kGenThreads) void gen_mine_sums_kernel(MineArgs a, int chunk)
-{
-    const int c = threadIdx.x, ck = blockIdx.x, s = blockIdx.y, d = a.d;
+    constexpr int kAsg = 1024;             // assignments staged in LDS at a time
+    __shared__ float acc[kSumsLdsFloats];
+    __shared__ int32_t cnt[kGenThreads];   // pblock <= 64
+    __shared__ int32_t rel_s[kAsg];        // pattern of a vector relative to the block, -1 outside it
+    const int tid = threadIdx.x, ck = blockIdx.x, s = blockIdx.y, d = a.d;
+    const int n_slices = kGenThreads / d, slice = tid / d, c = tid - slice * d;
+    const int p0 = blockIdx.z * pblock, np = min(pblock, a.P - p0);
     const int t0 = ck * chunk, t1 = min(a.T, t0 + chunk);
-    float *ps = a.psum + ((int64_t)s * a.tsplit + ck) * a.P * d;
-    int32_t *pc = a.pcnt + ((int64_t)s * a.tsplit + ck) * a.P;
-    if (c < d)
-        for (int p = 0; p < a.P; ++p) ps[(int64_t)p * d + c] = 0.f;
-    for (int p = c; p < a.P; p += kGenThreads) pc[p] = 0;
+    for (int i = tid; i < n_slices * (np + 1) * d; i += kGenThreads) acc[i] = 0.f;
+    cnt[tid] = 0;
     __syncthreads();
     const int32_t *asg = a.assign_ws + (int64_t)s * a.T;
     const __half *x = a.x + (int64_t)s * a.set_stride;
-    if (c < d)
-        for (int t = t0; t < t1; ++t) ps[(int64_t)asg[t] * d + c] += h2f(x[(int64_t)t * d + c]);
-    if (c == 0)
-        for (int t = t0; t < t1; ++t) pc[asg[t]] += 1;
+    float *mine = acc + (slice < n_slices ? slice : 0) * (np + 1) * d;   // np rows and the spare one
+    for (int b0 = t0; b0 < t1; b0 += kAsg) {   // the chunk in pieces of kAsg vectors
+        const int b1 = min(t1, b0 + kAsg);
+        __syncthreads();   // the previous piece's assignments have been used
+        for (int t = b0 + tid; t < b1; t += kGenThreads) {
+            int rel = asg[t] - p0;
+            if (rel < 0 || rel >= np) rel = -1;
+            rel_s[t - b0] = rel;
+            if (rel >= 0) atomicAdd(&cnt[rel], 1);
+        }
+        __syncthreads();
+        if (slice < n_slices) {
+            const int len = (b1 - b0 + n_slices - 1) / n_slices;
+            const int s0 = b0 + slice * len, s1 = min(b1, s0 + len);
+            for (int t = s0; t < s1; t += 16) {
+                // the vectors of sixteen steps are requested together, then added in order
+                // (no branches: a vector outside the block, or past the slice, goes to a spare row nobody reads)
+                int rowi[16];
+                float v[16];
+#pragma unroll
+                for (int k = 0; k < 16; ++k) {
+                    const int tk = min(t + k, s1 - 1);
+                    const int rel = t + k < s1 ? rel_s[tk - b0] : -1;
+                    rowi[k] = (rel < 0 ? np : rel) * d + c;
+                    v[k] = h2f(x[(int64_t)tk * d + c]);
+                }
+#pragma unroll
+                for (int k = 0; k < 16; ++k) mine[rowi[k]] += v[k];
+            }
+        }
+    }
+    __syncthreads();
+    float *ps = a.psum + (((int64_t)s * a.tsplit + ck) * a.P + p0) * d;
+    int32_t *pc = a.pcnt + ((int64_t)s * a.tsplit + ck) * a.P + p0;
+    for (int i = tid; i < np * d; i += kGenThreads) {
+        float v = acc[i];
+        for (int k = 1; k < n_slices; ++k) v += acc[k * (np + 1) * d + i];
+        ps[i] = v;
+    }
+    if (tid < np) pc[tid] = cnt[tid];
 }
 
 // update: chunks in increasing order, mean in binary32, fp16 nearest even; an empty cluster keeps its centroid
@@ -750,11 +976,31 @@ static hipError_t launch_gen_assign(const QuantArgs &a, hipStream_t s)
     return hipGetLastError();
 }
 
+template <int D>
+static hipError_t launch_gen_assign_mfma(const QuantArgs &a, hipStream_t s)
+{
+    static LdsOptIn opt_in;   // per instantiation: the most it needs is a table of 256 patterns
+    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(&gen_assign_mfma_kernel<D>), opt_in, GenSearchLds<D>::bytes(256));
+    if (e != hipSuccess) return e;
+    // aim at ~2048 workgroups, each staging the table once for at least 16 and at most 256 tiles of 16 vectors
+    const int n_tiles = a.nq / 16;
+    const int64_t total = (int64_t)n_tiles * a.n_streams;
+    int tpw = (int)((total + 2047) / 2048);
+    tpw = tpw < 16 ? 16 : tpw > 256 ? 256 : tpw;
+    hipLaunchKernelGGL(gen_assign_mfma_kernel<D>, dim3((n_tiles + tpw - 1) / tpw, a.n_streams), dim3(256), GenSearchLds<D>::bytes(a.P), s, a,
+                       tpw);
+    return hipGetLastError();
+}
+
 hipError_t launch_generic_quantize(const QuantArgs &a, bool v_side, hipStream_t s)
 {
     if (a.nq <= 0) return hipSuccess;
     if (a.d != 96 && a.d != 256) return hipErrorInvalidValue;
-    hipError_t e = a.d == 96 ? launch_gen_assign<96>(a, s) : launch_gen_assign<256>(a, s);
+    hipError_t e;
+    if (a.metric == PK_METRIC_MINMAX)
+        e = a.d == 96 ? launch_gen_assign<96>(a, s) : launch_gen_assign<256>(a, s);
+    else
+        e = a.d == 96 ? launch_gen_assign_mfma<96>(a, s) : launch_gen_assign_mfma<256>(a, s);
     if (e != hipSuccess) return e;
     if (v_side)
         hipLaunchKernelGGL(gen_quantize_v_kernel, dim3(a.nq / 16, a.n_streams), dim3(kGenThreads), 0, s, a);
@@ -771,6 +1017,21 @@ hipError_t launch_generic_tail_copy(const TailCopyArgs &a, hipStream_t s)
     return hipGetLastError();
 }
 
+template <int D>
+static hipError_t launch_gen_mine_assign(const MineArgs &a, int last, hipStream_t s)
+{
+    static LdsOptIn opt_in;
+    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(&gen_mine_assign_mfma_kernel<D>), opt_in, GenSearchLds<D>::bytes(256));
+    if (e != hipSuccess) return e;
+    const int n_tiles = (a.T + 15) / 16;
+    const int64_t total = (int64_t)n_tiles * a.n_sets;
+    int tpw = (int)((total + 2047) / 2048);
+    tpw = tpw < 16 ? 16 : tpw > 256 ? 256 : tpw;
+    hipLaunchKernelGGL(gen_mine_assign_mfma_kernel<D>, dim3((n_tiles + tpw - 1) / tpw, a.n_sets), dim3(256), GenSearchLds<D>::bytes(a.P), s,
+                       a, last, tpw);
+    return hipGetLastError();
+}
+
 hipError_t launch_generic_mine(const MineArgs &a, hipStream_t s)
 {
     hipError_t e;
@@ -780,17 +1041,17 @@ hipError_t launch_generic_mine(const MineArgs &a, hipStream_t s)
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     for (int it = 0; it < a.iters; ++it) {
-        const dim3 agrid((a.T + kGenThreads - 1) / kGenThreads, a.n_sets);
-        if (a.d == 96)
-            hipLaunchKernelGGL(gen_mine_assign_kernel<96>, agrid, dim3(kGenThreads), 0, s, a, it == a.iters - 1 ? 1 : 0);
-        else
-            hipLaunchKernelGGL(gen_mine_assign_kernel<256>, agrid, dim3(kGenThreads), 0, s, a, it == a.iters - 1 ? 1 : 0);
-        if ((e = hipGetLastError()) != hipSuccess) return e;
+        if ((e = a.d == 96 ? launch_gen_mine_assign<96>(a, it == a.iters - 1 ? 1 : 0, s)
+                           : launch_gen_mine_assign<256>(a, it == a.iters - 1 ? 1 : 0, s)) != hipSuccess)
+            return e;
         if (a.inertia) {
             hipLaunchKernelGGL(gen_mine_inertia_kernel, dim3(a.n_sets), dim3(256), 0, s, a, it);
             if ((e = hipGetLastError()) != hipSuccess) return e;
         }
-        hipLaunchKernelGGL(gen_mine_sums_kernel, dim3(a.tsplit, a.n_sets), dim3(kGenThreads), 0, s, a, chunk);
+        const int per = kSumsLdsFloats / ((kGenThreads / a.d) * a.d) - 1;   // 47 patterns at d = 256, 63 at d = 96 (two slices); a spare row
+        const int pblock = a.P < per ? a.P : per;
+        hipLaunchKernelGGL(gen_mine_sums_kernel, dim3(a.tsplit, a.n_sets, (a.P + pblock - 1) / pblock), dim3(kGenThreads), 0,
+                           s, a, chunk, pblock);
         if ((e = hipGetLastError()) != hipSuccess) return e;
         hipLaunchKernelGGL(gen_mine_update_kernel, dim3(a.P, a.n_sets), dim3(kGenThreads), 0, s, a);
         if ((e = hipGetLastError()) != hipSuccess) return e;

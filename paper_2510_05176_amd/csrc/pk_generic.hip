@@ -1,9 +1,11 @@
 // The hot path for head dimensions other than 128 (96 and 256, the other two that Sec. 3.3 names): plain kernels,
-// thread <-> channel or thread <-> token (vector), no matrix cores.  They compute the same definitions with
-// the same arithmetic where it decides an integer (the quantizer's parameters and codes come from the shared
-// pk_quant_arith.h; pattern selection evaluates the metric in binary32 over all patterns, lowest index on ties) and
-// store the same cache format (head_dim enters the layout formulas), so they meet the same parity bars; they are
-// kept simple rather than tuned, and the tuned kernels of the other files keep their fixed head dimension.
+// thread <-> channel or thread <-> token (vector), with the Euclidean pattern search on the matrix cores.  They
+// compute the same definitions with the same arithmetic where it decides an integer (the quantizer's parameters and
+// codes come from the shared pk_quant_arith.h; pattern selection gives the exact argmin of the metric in binary32,
+// lowest index on ties) and store the same cache format (head_dim enters the layout formulas), so they meet the
+// same parity bars; they are kept simple rather than tuned, and the tuned kernels of the other files keep their
+// fixed head dimension.  The decode kernels here also serve head dimension 128 for head counts that the matrix-core
+// decode does not take.
 // Uniform and ragged appends, decode (with shared prefix and with per-sequence fill states), mining, the window
 // pattern and dequantize are covered, on contiguous and on paged caches.
 #pragma clang fp contract(off)

@@ -373,8 +373,13 @@ __global__ __launch_bounds__(kGenThreads) void gen_quantize_v_kernel(QuantArgs a
         for (int off = 1; off < 32; off <<= 1) {
             rmn = fminf(rmn, __shfl_xor(rmn, off));
             rmx = fmaxf(rmx, __shfl_xor(rmx, off));
-            xmn = fminf(xmn, __shfl_xor(xmn, off));
-            xmx = fmaxf(xmx, __shfl_xor(xmx, off));
+        }
+        if (a.v_rho > 0.f) {   // the vector's own range is needed for the threshold only
+#pragma unroll
+            for (int off = 1; off < 32; off <<= 1) {
+                xmn = fminf(xmn, __shfl_xor(xmn, off));
+                xmx = fmaxf(xmx, __shfl_xor(xmx, off));
+            }
         }
         float4(&hm)[kGenThreads / 32] = half_mm[i & 1];
         if ((c & 31) == 0) hm[c >> 5] = make_float4(rmn, rmx, xmn, xmx);

@@ -31,6 +31,7 @@ Other modes (no GPU needed):
   bench.py --summarise-counters COUNTERS.csv --cmd "..."       per-kernel averages per dispatch of any other --pmc run
 """
 import argparse
+import gc
 import json
 import os
 import sys
@@ -624,6 +625,11 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    # As timeit does: no pause of the host's cyclic collector between the launches of a timed call.  (With it on,
+    # about one default run in two had a pass of a short stage, always an append, stretched by 1 to 57 ms: the GPU
+    # idle between two launches while the host collected.  Reference counting still frees everything.)
+    gc.collect()
+    gc.disable()
     metric = pk.METRIC_L2 if args.metric == "l2" else pk.METRIC_MINMAX
     common = {"metric": METRIC, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "higher_is_better": True,
               "scaling": "weak", "vs_baseline": None, "dtype": "f16 in, f32 arithmetic, u%d codes" % args.bits,

@@ -625,9 +625,9 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    # As timeit does: no pause of the host's cyclic collector between the launches of a timed call.  (With it on,
-    # about one default run in two had a pass of a short stage, always an append, stretched by 1 to 57 ms: the GPU
-    # idle between two launches while the host collected.  Reference counting still frees everything.)
+    # As timeit does: no pause of the host's cyclic collector inside a timed region.  (With it on, about one default
+    # run in two had a pass of a short stage stretched by 1 to 57 ms: the host collected between the start event and
+    # the library call, with the GPU idle meanwhile.  Reference counting still frees everything.)
     gc.collect()
     gc.disable()
     metric = pk.METRIC_L2 if args.metric == "l2" else pk.METRIC_MINMAX

@@ -310,37 +310,57 @@ __global__ __launch_bounds__(kGenThreads) void gen_assign_kernel(QuantArgs a)
 
 // K: one workgroup per (group of G tokens, stream), thread <-> channel.  Two passes over the group's residuals (the
 // second recomputes them): minimum / maximum -> parameters, then codes; a plane word of 32 channels is a wave ballot.
+// The group's indices are staged in LDS and the vectors and pattern rows are requested 16 tokens at a time, without
+// branches (threads past the head dimension read its last channel and store nothing).
 __global__ __launch_bounds__(kGenThreads) void gen_quantize_k_kernel(QuantArgs a)
 {
+    __shared__ uint8_t idx_s[128];   // G <= 128
     const int c = threadIdx.x, lane = c & 63, ns = blockIdx.y, g = blockIdx.x, d = a.d, G = a.G;
     take_sequence_entry(a, ns);
     if (g * G >= a.nq) return;   // a ragged append: sized for the longest sequence
     const bool on = c < d;
-    const __half *M = a.patterns + (int64_t)a.sets.set_of(ns) * a.P * d;
+    const int cc = on ? c : d - 1;
+    const __half *M = a.patterns + (int64_t)a.sets.set_of(ns) * a.P * d + cc;
     const int64_t p0 = a.map.pos(ns, a.t0 + g * G);   // a group never straddles a page
+    if (c < G) idx_s[c] = a.idx[p0 + c];
+    __syncthreads();
     float mn = INFINITY, mx = -INFINITY;
-    for (int t = 0; t < G; ++t) {
-        const int idx = a.idx[p0 + t];
-        if (on) {
-            const float r = h2f(a.src.row_d(ns, g * G + t, d)[c]) - h2f(M[(int64_t)idx * d + c]);
+    for (int t0 = 0; t0 < G; t0 += 16) {
+        float xr[16], mr[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            xr[k] = h2f(a.src.row_d(ns, g * G + t0 + k, d)[cc]);
+            mr[k] = h2f(M[(int64_t)idx_s[t0 + k] * d]);
+        }
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            const float r = xr[k] - mr[k];
             mn = fminf(mn, r);
             mx = fmaxf(mx, r);
         }
     }
-    GroupParams gp = group_params(on ? mn : 0.f, on ? mx : 0.f, a.bits);
+    const GroupParams gp = group_params(mn, mx, a.bits);
     if (on) {
         a.scale[(p0 / G) * d + c] = __ushort_as_half(gp.s16);
         a.zero[(p0 / G) * d + c] = __ushort_as_half(gp.z16);
     }
     const int words = d / 32;
-    for (int t = 0; t < G; ++t) {
-        const int idx = a.idx[p0 + t];
-        int code = 0;
-        if (on) code = quantize_one(h2f(a.src.row_d(ns, g * G + t, d)[c]) - h2f(M[(int64_t)idx * d + c]), gp, a.bits);
-        for (int j = 0; j < a.bits; ++j) {
-            const unsigned long long m = __ballot((code >> j) & 1);   // bit l <-> channel 64 * wave + l
-            const int w = (c >> 6) * 2 + (lane >> 5);
-            if ((lane & 31) == 0 && w < words) a.codes_k[((p0 + t) * words + w) * a.bits + j] = (uint32_t)(m >> (lane & 32));
+    const int w = (c >> 6) * 2 + (lane >> 5);
+    const bool writer = (lane & 31) == 0 && w < words;
+    for (int t0 = 0; t0 < G; t0 += 16) {
+        float xr[16], mr[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            xr[k] = h2f(a.src.row_d(ns, g * G + t0 + k, d)[cc]);
+            mr[k] = h2f(M[(int64_t)idx_s[t0 + k] * d]);
+        }
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            const int code = on ? quantize_one(xr[k] - mr[k], gp, a.bits) : 0;
+            for (int j = 0; j < a.bits; ++j) {
+                const unsigned long long m = __ballot((code >> j) & 1);   // bit l <-> channel 64 * wave + l
+                if (writer) a.codes_k[((p0 + t0 + k) * words + w) * a.bits + j] = (uint32_t)(m >> (lane & 32));
+            }
         }
     }
 }

@@ -378,16 +378,23 @@ __global__ __launch_bounds__(kGenThreads) void gen_quantize_v_kernel(QuantArgs a
     if (u * 16 >= a.nq) return;   // a ragged append: sized for the longest sequence
     const bool on = c < d;
     const int Gc = a.G < d ? a.G : d, NG = d / Gc, g = on ? c / Gc : 0;
-    const __half *M = a.patterns + (int64_t)a.sets.set_of(ns) * a.P * d;
-    const int64_t p0 = a.map.pos(ns, a.t0 + u * 16);
-    uint32_t word[2] = {0u, 0u};
+    const int cc = on ? c : d - 1;   // threads past the head dimension read its last channel and store nothing
+    const __half *M = a.patterns + (int64_t)a.sets.set_of(ns) * a.P * d + cc;
+    const int64_t p0 = a.map.pos(ns, a.t0 + u * 16);   // a multiple of 16: the unit's 16 index bytes are one aligned piece
+    const uint4 iw = *reinterpret_cast<const uint4 *>(a.idx + p0);
+    const uint32_t iws[4] = {iw.x, iw.y, iw.z, iw.w};
+    float xs[16], ms[16];   // the unit's vectors and pattern rows, requested together
+#pragma unroll
     for (int i = 0; i < 16; ++i) {
-        int idx = a.idx[p0 + i];
-        float x = 0.f, r = 0.f;
-        if (on) {
-            x = h2f(a.src.row_d(ns, u * 16 + i, d)[c]);
-            r = x - h2f(M[(int64_t)idx * d + c]);
-        }
+        xs[i] = h2f(a.src.row_d(ns, u * 16 + i, d)[cc]);
+        ms[i] = h2f(M[(int64_t)((iws[i >> 2] >> (8 * (i & 3))) & 255) * d]);
+    }
+    uint32_t word[2] = {0u, 0u};
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        int idx = (iws[i >> 2] >> (8 * (i & 3))) & 255;
+        const float x = xs[i];
+        float r = x - ms[i];
         float rmn = on ? r : INFINITY, rmx = on ? r : -INFINITY, xmn = on ? x : INFINITY, xmx = on ? x : -INFINITY;
 #pragma unroll
         for (int off = 1; off < 32; off <<= 1) {

@@ -365,8 +365,29 @@ __global__ __launch_bounds__(kGenThreads) void gen_quantize_k_kernel(QuantArgs a
     }
 }
 
+// Minimum or maximum over each half (32 lanes) of a wave with data-parallel-primitive moves, no LDS traffic: an
+// inclusive scan over the rows of 16 lanes (row_shr 1, 2, 4, 8; a lane without a source keeps its own value), then
+// lane 15 of rows 0 and 2 is broadcast into rows 1 and 3 (row_bcast15).  The result is in lanes 31 and 63.
+template <bool MAX>
+__device__ __forceinline__ float half_wave_reduce_to_last(float v)
+{
+#define PK_DPP_STEP(CTRL, ROWS)                                                                                               \
+    {                                                                                                                         \
+        const float o = __builtin_bit_cast(                                                                                   \
+            float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, v), __builtin_bit_cast(int, v), CTRL, ROWS, 0xf, false)); \
+        v = MAX ? fmaxf(v, o) : fminf(v, o);                                                                                  \
+    }
+    PK_DPP_STEP(0x111, 0xf)
+    PK_DPP_STEP(0x112, 0xf)
+    PK_DPP_STEP(0x114, 0xf)
+    PK_DPP_STEP(0x118, 0xf)
+    PK_DPP_STEP(0x142, 0xa)
+#undef PK_DPP_STEP
+    return v;
+}
+
 // V: one workgroup per (16-token unit, stream), thread <-> channel.  Per token: residual, minimum and maximum of
-// the residuals and of the vector over every 32 channels (cross-lane steps inside half a wave), the halves exchanged
+// the residuals and of the vector over every 32 channels (data-parallel-primitive moves inside half a wave), the halves exchanged
 // through LDS (one barrier per token, two buffers in turn); from them every thread forms the adaptive threshold's
 // decision of Sec. 3.3 (whole vector) and the parameters of its own group of Gc channels (a multiple of 32), then
 // its code; a thread collects the bits of its channel's 16 tokens in the words it stores at the end.
@@ -396,20 +417,14 @@ __global__ __launch_bounds__(kGenThreads) void gen_quantize_v_kernel(QuantArgs a
         const float x = xs[i];
         float r = x - ms[i];
         float rmn = on ? r : INFINITY, rmx = on ? r : -INFINITY, xmn = on ? x : INFINITY, xmx = on ? x : -INFINITY;
-#pragma unroll
-        for (int off = 1; off < 32; off <<= 1) {
-            rmn = fminf(rmn, __shfl_xor(rmn, off));
-            rmx = fmaxf(rmx, __shfl_xor(rmx, off));
-        }
+        rmn = half_wave_reduce_to_last<false>(rmn);
+        rmx = half_wave_reduce_to_last<true>(rmx);
         if (a.v_rho > 0.f) {   // the vector's own range is needed for the threshold only
-#pragma unroll
-            for (int off = 1; off < 32; off <<= 1) {
-                xmn = fminf(xmn, __shfl_xor(xmn, off));
-                xmx = fmaxf(xmx, __shfl_xor(xmx, off));
-            }
+            xmn = half_wave_reduce_to_last<false>(xmn);
+            xmx = half_wave_reduce_to_last<true>(xmx);
         }
         float4(&hm)[kGenThreads / 32] = half_mm[i & 1];
-        if ((c & 31) == 0) hm[c >> 5] = make_float4(rmn, rmx, xmn, xmx);
+        if ((c & 31) == 31) hm[c >> 5] = make_float4(rmn, rmx, xmn, xmx);
         __syncthreads();
         if (a.v_rho > 0.f) {
             float4 row = hm[0];

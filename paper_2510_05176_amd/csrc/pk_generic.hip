@@ -386,73 +386,82 @@ __device__ __forceinline__ float half_wave_reduce_to_last(float v)
     return v;
 }
 
-// V: one workgroup per (16-token unit, stream), thread <-> channel.  Per token: residual, minimum and maximum of
-// the residuals and of the vector over every 32 channels (data-parallel-primitive moves inside half a wave), the halves exchanged
-// through LDS (one barrier per token, two buffers in turn); from them every thread forms the adaptive threshold's
-// decision of Sec. 3.3 (whole vector) and the parameters of its own group of Gc channels (a multiple of 32), then
-// its code; a thread collects the bits of its channel's 16 tokens in the words it stores at the end.
+// V: one workgroup per (16-token unit, stream) in three phases.  (1) thread <-> channel: residuals of the 16 tokens;
+// minimum and maximum of the residuals (and, for the adaptive threshold, of the vector) over every 32 channels by
+// data-parallel-primitive moves inside half a wave, left in LDS.  (2) thread <-> (token, channel group): the
+// threshold's decision of Sec. 3.3 for the whole vector, the group's minimum and maximum from the halves, the stored
+// parameters - all 16 tokens of a group in one pass - to LDS and, 16 tokens side by side, to memory.  (3) thread <->
+// channel again: codes against the parameters of its group, the bits of the channel's 16 tokens collected in the
+// words it stores.
 __global__ __launch_bounds__(kGenThreads) void gen_quantize_v_kernel(QuantArgs a)
 {
-    __shared__ float4 half_mm[2][kGenThreads / 32];   // per 32 channels: min r, max r, min x, max x
+    constexpr int kHalves = kGenThreads / 32;
+    __shared__ float4 half_mm[16][kHalves];     // per token and 32 channels: min r, max r, min x, max x
+    __shared__ float4 par[16][kHalves];         // per token and channel group: z, 1/s, s, raw flag
     const int c = threadIdx.x, ns = blockIdx.y, u = blockIdx.x, d = a.d;
     take_sequence_entry(a, ns);
     if (u * 16 >= a.nq) return;   // a ragged append: sized for the longest sequence
     const bool on = c < d;
-    const int Gc = a.G < d ? a.G : d, NG = d / Gc, g = on ? c / Gc : 0;
     const int cc = on ? c : d - 1;   // threads past the head dimension read its last channel and store nothing
+    const int Gc = a.G < d ? a.G : d, NG = d / Gc, g = cc / Gc;
     const __half *M = a.patterns + (int64_t)a.sets.set_of(ns) * a.P * d + cc;
     const int64_t p0 = a.map.pos(ns, a.t0 + u * 16);   // a multiple of 16: the unit's 16 index bytes are one aligned piece
     const uint4 iw = *reinterpret_cast<const uint4 *>(a.idx + p0);
     const uint32_t iws[4] = {iw.x, iw.y, iw.z, iw.w};
-    float xs[16], ms[16];   // the unit's vectors and pattern rows, requested together
+    const bool thresholded = a.v_rho > 0.f;
+    float xs[16], rs[16];   // the unit's vectors and residuals
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         xs[i] = h2f(a.src.row_d(ns, u * 16 + i, d)[cc]);
-        ms[i] = h2f(M[(int64_t)((iws[i >> 2] >> (8 * (i & 3))) & 255) * d]);
+        rs[i] = h2f(M[(int64_t)((iws[i >> 2] >> (8 * (i & 3))) & 255) * d]);
     }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        rs[i] = xs[i] - rs[i];
+        const float rmn = half_wave_reduce_to_last<false>(on ? rs[i] : INFINITY);
+        const float rmx = half_wave_reduce_to_last<true>(on ? rs[i] : -INFINITY);
+        float xmn = 0.f, xmx = 0.f;
+        if (thresholded) {   // the vector's own range is needed for the threshold only
+            xmn = half_wave_reduce_to_last<false>(on ? xs[i] : INFINITY);
+            xmx = half_wave_reduce_to_last<true>(on ? xs[i] : -INFINITY);
+        }
+        if ((c & 31) == 31) half_mm[i][c >> 5] = make_float4(rmn, rmx, xmn, xmx);
+    }
+    __syncthreads();
+    if (c < 16 * NG) {   // token i, channel group gg
+        const int i = c & 15, gg = c >> 4;
+        bool raw = false;   // the vector itself is quantized, stored under the index that says so
+        if (thresholded) {
+            float4 row = half_mm[i][0];
+            for (int k = 1; k < d / 32; ++k) {
+                const float4 o = half_mm[i][k];
+                row = make_float4(fminf(row.x, o.x), fmaxf(row.y, o.y), fminf(row.z, o.z), fmaxf(row.w, o.w));
+            }
+            raw = !((row.y - row.x) <= a.v_rho * (row.w - row.z));
+        }
+        float mn = INFINITY, mx = -INFINITY;
+        for (int k = gg * (Gc / 32); k < (gg + 1) * (Gc / 32); ++k) {
+            const float4 o = half_mm[i][k];
+            mn = fminf(mn, raw ? o.z : o.x);
+            mx = fmaxf(mx, raw ? o.w : o.y);
+        }
+        const GroupParams gp = group_params(mn, mx, a.bits);
+        par[i][gg] = make_float4(gp.z, gp.inv, gp.s, raw ? 1.f : 0.f);
+        a.scale[((p0 >> 4) * NG + gg) * 16 + i] = __ushort_as_half(gp.s16);
+        a.zero[((p0 >> 4) * NG + gg) * 16 + i] = __ushort_as_half(gp.z16);
+        if (gg == 0 && raw) a.idx[p0 + i] = (uint8_t)PK_NO_PATTERN;
+    }
+    __syncthreads();
     uint32_t word[2] = {0u, 0u};
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-        int idx = (iws[i >> 2] >> (8 * (i & 3))) & 255;
-        const float x = xs[i];
-        float r = x - ms[i];
-        float rmn = on ? r : INFINITY, rmx = on ? r : -INFINITY, xmn = on ? x : INFINITY, xmx = on ? x : -INFINITY;
-        rmn = half_wave_reduce_to_last<false>(rmn);
-        rmx = half_wave_reduce_to_last<true>(rmx);
-        if (a.v_rho > 0.f) {   // the vector's own range is needed for the threshold only
-            xmn = half_wave_reduce_to_last<false>(xmn);
-            xmx = half_wave_reduce_to_last<true>(xmx);
-        }
-        float4(&hm)[kGenThreads / 32] = half_mm[i & 1];
-        if ((c & 31) == 31) hm[c >> 5] = make_float4(rmn, rmx, xmn, xmx);
-        __syncthreads();
-        if (a.v_rho > 0.f) {
-            float4 row = hm[0];
-            for (int k = 1; k < d / 32; ++k) {
-                const float4 o = hm[k];
-                row = make_float4(fminf(row.x, o.x), fmaxf(row.y, o.y), fminf(row.z, o.z), fmaxf(row.w, o.w));
-            }
-            if (!((row.y - row.x) <= a.v_rho * (row.w - row.z))) {   // the vector itself is quantized, stored under the
-                idx = PK_NO_PATTERN;                                 // index that says so
-                r = x;
-            }
-        }
-        float mn = INFINITY, mx = -INFINITY;
-        for (int k = g * (Gc / 32); k < (g + 1) * (Gc / 32); ++k) {
-            const float4 o = hm[k];
-            mn = fminf(mn, idx == PK_NO_PATTERN && a.v_rho > 0.f ? o.z : o.x);
-            mx = fmaxf(mx, idx == PK_NO_PATTERN && a.v_rho > 0.f ? o.w : o.y);
-        }
-        const GroupParams gp = group_params(mn, mx, a.bits);
-        if (on && c == g * Gc) {
-            a.scale[((p0 >> 4) * NG + g) * 16 + i] = __ushort_as_half(gp.s16);
-            a.zero[((p0 >> 4) * NG + g) * 16 + i] = __ushort_as_half(gp.z16);
-        }
-        if (c == 0) a.idx[p0 + i] = (uint8_t)idx;
-        if (on) {
-            const int code = quantize_one(r, gp, a.bits);
-            for (int j = 0; j < a.bits; ++j) word[j >> 1] |= (uint32_t)((code >> j) & 1) << (16 * (j & 1) + i);
-        }
+        const float4 pr = par[i][g];
+        GroupParams gp;
+        gp.z = pr.x;
+        gp.inv = pr.y;
+        gp.s = pr.z;
+        const int code = quantize_one(pr.w != 0.f ? xs[i] : rs[i], gp, a.bits);
+        for (int j = 0; j < a.bits; ++j) word[j >> 1] |= (uint32_t)((code >> j) & 1) << (16 * (j & 1) + i);
     }
     if (on) {
         uint32_t *codes = reinterpret_cast<uint32_t *>(a.codes_v);

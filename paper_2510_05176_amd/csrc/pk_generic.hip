@@ -1060,10 +1060,11 @@ hipError_t launch_generic_quantize(const QuantArgs &a, bool v_side, hipStream_t 
     else
         e = a.d == 96 ? launch_gen_assign_mfma<96>(a, s) : launch_gen_assign_mfma<256>(a, s);
     if (e != hipSuccess) return e;
+    const dim3 block(a.d <= 128 ? 128 : kGenThreads);   // thread <-> channel: two waves hold 96 channels (and the 128 indices of a group)
     if (v_side)
-        hipLaunchKernelGGL(gen_quantize_v_kernel, dim3(a.nq / 16, a.n_streams), dim3(kGenThreads), 0, s, a);
+        hipLaunchKernelGGL(gen_quantize_v_kernel, dim3(a.nq / 16, a.n_streams), block, 0, s, a);
     else
-        hipLaunchKernelGGL(gen_quantize_k_kernel, dim3(a.nq / a.G, a.n_streams), dim3(kGenThreads), 0, s, a);
+        hipLaunchKernelGGL(gen_quantize_k_kernel, dim3(a.nq / a.G, a.n_streams), block, 0, s, a);
     return hipGetLastError();
 }
 

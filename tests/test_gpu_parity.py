@@ -347,9 +347,15 @@ def test_decode_tail_only_and_empty_context(oracle, pk):
     assert not out.any() and torch.isinf(lse).all()
 
 
-def test_decode_with_shared_prefix(oracle, pk):
+@pytest.mark.parametrize("G,hkv,hq", [
+    (32, 2, 8),        # r = 4
+    (32, 1, 8),        # r = 8 over 32-channel groups: two groups of query heads, in the prefix's splits and tails too
+    (64, 1, 16),       # r = 16: two groups of eight heads
+    (64, 1, 20),       # r = 20: the plain kernels
+])
+def test_decode_with_shared_prefix(oracle, pk, G, hkv, hq):
     # a shared prompt cache (n_seq = 1) in front of 3 sequences' own caches, same pattern tables
-    P, G, bits, hkv, hq = 32, 32, 2, 2, 8
+    P, bits = 32, 2
     own_kw = dict(n_seq=3, n_kv_heads=hkv, n_q_heads=hq, head_dim=128, n_patterns=P, seqs_per_set=0, bits=bits,
                   group=G, recent=0, flush=128, t_capacity=1024, metric=0)
     pre_kw = dict(own_kw, n_seq=1, flush=64, recent=16, t_capacity=512)
